@@ -1,0 +1,317 @@
+"""Pins of the CPU oracle against what the paper prints and what mathematics fixes.
+
+None of these tests touches the GPU or the HIP library.  Every expected value is either read from
+tests/golden (transcribed from the paper), produced by numpy's own float64 matmul, or follows from
+an identity written out in the test.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1805_10692_amd import workloads as wl
+
+
+def ints(a):
+    return np.asarray(a).astype(np.int64)
+
+
+# ------------------------------------------------------------------ the paper's worked example
+
+def test_cer_arrays_of_worked_example(example):
+    M = example["M"].astype(np.float32)
+    A = oracle.encode(M, np.array([0, 2, 3, 4], np.float32), "cer")
+    assert A.omega.tolist() == example["cer_Omega"].tolist()
+    assert A.count.tolist() == example["value_counts"].tolist()
+    assert A.colI.tolist() == ints(example["cer_colI"]).tolist()
+    assert A.omegaPtr.tolist() == ints(example["cer_OmegaPtr"]).tolist()
+    assert A.rowPtr.tolist() == ints(example["cer_rowPtr"]).tolist()
+    assert oracle.entries(A) == int(example["cer_entries"][0]) == 49
+
+
+def test_cser_arrays_of_worked_example(example):
+    M = example["M"].astype(np.float32)
+    A = oracle.encode(M, np.array([0, 2, 3, 4], np.float32), "cser")
+    assert A.colI.tolist() == ints(example["cser_colI"]).tolist()
+    assert A.omegaPtr.tolist() == ints(example["cser_OmegaPtr"]).tolist()
+    assert A.rowPtr.tolist() == ints(example["cser_rowPtr"]).tolist()
+    # the paper lists Omega in another order for CSER; what is fixed is the value of each group
+    printed = example["cser_Omega"][ints(example["cser_OmegaI"])]
+    assert A.omega[A.omegaI].tolist() == printed.tolist() == [4, 3, 2, 4, 4, 3, 2, 4, 3, 4]
+    assert oracle.entries(A) == int(example["cser_entries"][0]) == 59
+
+
+def test_single_row_encodings(example):
+    row = example["row0"].astype(np.float32)[None, :]
+    # with one row only, counts are 0:5, 4:3, 3:2, 2:2 -> ties between 3 and 2 resolved by codebook order
+    cb = np.array([0, 4, 3, 2], np.float32)
+    cer = oracle.encode(row, cb, "cer")
+    cser = oracle.encode(row, cb, "cser")
+    assert cer.omega.tolist() == example["row0_cer_Omega"].tolist()
+    assert cer.colI.tolist() == ints(example["row0_cer_colI"]).tolist()
+    assert cer.omegaPtr.tolist() == ints(example["row0_cer_OmegaPtr"]).tolist()
+    assert cer.rowPtr.tolist() == ints(example["row0_cer_rowPtr"]).tolist()
+    assert cser.omega.tolist() == example["row0_cser_Omega"].tolist()
+    assert cser.colI.tolist() == ints(example["row0_cser_colI"]).tolist()
+    assert cser.omegaI.tolist() == ints(example["row0_cser_OmegaI"]).tolist()
+    assert cser.omegaPtr.tolist() == ints(example["row0_cser_OmegaPtr"]).tolist()
+    assert cser.rowPtr.tolist() == ints(example["row0_cser_rowPtr"]).tolist()
+
+
+def test_csr_arrays_and_entry_counts(example):
+    M = example["M"].astype(np.float32)
+    C = oracle.csr_encode(M)
+    assert C.val.tolist() == example["csr_W"].tolist()
+    assert C.colI.tolist() == ints(example["csr_colI"]).tolist()
+    assert C.rowPtr.tolist() == ints(example["csr_rowPtr"]).tolist()
+    assert len(C.val) + len(C.colI) + len(C.rowPtr) == int(example["csr_entries"][0]) == 62
+    assert M.size == int(example["dense_entries"][0]) == 60
+
+
+def test_product_on_printed_arrays(example):
+    """The product routines run on the arrays exactly as the paper prints them (not on the
+    oracle's own encoding) and must give M.a; with integer data every sum is exact."""
+    M = example["M"]
+    rng = np.random.default_rng(7)
+    X = rng.integers(-9, 10, size=(12, 3)).astype(np.float32)
+    want = M @ X.astype(np.float64)
+    cer = oracle.Encoded("cer", 5, 12, example["cer_Omega"].astype(np.float32), ints(example["value_counts"]),
+                         ints(example["cer_colI"]), ints(example["cer_OmegaPtr"]), ints(example["cer_rowPtr"]), None)
+    cser = oracle.Encoded("cser", 5, 12, example["cser_Omega"].astype(np.float32), ints(example["value_counts"]),
+                          ints(example["cser_colI"]), ints(example["cser_OmegaPtr"]), ints(example["cser_rowPtr"]),
+                          ints(example["cser_OmegaI"]))
+    assert np.array_equal(oracle.dot(cer, X), want)
+    assert np.array_equal(oracle.dot(cser, X), want)
+    assert np.array_equal(oracle.decode(cer), M.astype(np.float32))
+    assert np.array_equal(oracle.decode(cser), M.astype(np.float32))
+    csr = oracle.CSR(5, 12, example["csr_W"].astype(np.float32), ints(example["csr_colI"]), ints(example["csr_rowPtr"]))
+    assert np.array_equal(oracle.dot_csr(csr, X), want)
+    assert np.array_equal(oracle.dot_dense(M.astype(np.float32), X), want)
+
+
+def test_factorised_second_row(example):
+    """Section II-B: row 2 of M times a equals 4*(a_1+a_2+a_6+a_9+a_10+a_12)."""
+    M = example["M"].astype(np.float32)
+    a = np.arange(1, 13, dtype=np.float32)[:, None] * 0.5
+    cols = ints(example["row1_columns"])
+    want = float(example["row1_factor"][0]) * float(a[cols, 0].astype(np.float64).sum())
+    for fmt in ("cer", "cser"):
+        A = oracle.encode(M, np.array([0, 2, 3, 4], np.float32), fmt)
+        # that row holds a single group whose indices are the listed columns
+        g0, g1 = A.rowPtr[1], A.rowPtr[2]
+        assert g1 - g0 == 1
+        assert A.colI[A.omegaPtr[g0]:A.omegaPtr[g1]].tolist() == cols.tolist()
+        assert oracle.dot(A, a)[1, 0] == want
+
+
+# ------------------------------------------------------------------ hand-built cases
+
+def test_padding_groups_hand_built():
+    """A row holding only the rank-3 value needs two repeated pointers before its group (CER) and
+    none in CSER; ranks above the row's highest rank emit nothing."""
+    W = np.array([[0, 1, 1, 1, 2, 2, 3, 0],     # global counts: 0 x22, 1 x5, 2 x3, 3 x2
+                  [0, 0, 3, 0, 0, 0, 0, 0],     # only rank 3
+                  [0, 0, 0, 0, 0, 0, 0, 0],     # empty row
+                  [1, 0, 0, 2, 0, 0, 0, 1]], np.float32)
+    cb = np.array([3, 2, 1, 0], np.float32)     # codebook order must not matter: counts are distinct
+    cer = oracle.encode(W, cb, "cer")
+    assert cer.omega.tolist() == [0, 1, 2, 3]
+    assert cer.count.tolist() == [22, 5, 3, 2]
+    assert cer.colI.tolist() == [1, 2, 3, 4, 5, 6, 2, 0, 7, 3]
+    assert cer.omegaPtr.tolist() == [0, 3, 5, 6, 6, 6, 7, 9, 10]
+    assert cer.rowPtr.tolist() == [0, 3, 6, 6, 8]
+    cser = oracle.encode(W, cb, "cser")
+    assert cser.colI.tolist() == cer.colI.tolist()
+    assert cser.omegaPtr.tolist() == [0, 3, 5, 6, 7, 9, 10]
+    assert cser.omegaI.tolist() == [1, 2, 3, 3, 1, 2]
+    assert cser.rowPtr.tolist() == [0, 3, 4, 4, 6]
+    assert np.array_equal(oracle.decode(cer), W) and np.array_equal(oracle.decode(cser), W)
+
+
+def test_tie_break_and_unused_codebook_values():
+    W = np.array([[5, 7, 5, 7], [9, 9, 5, 7]], np.float32)   # 5:3, 7:3, 9:2 ; 11 never occurs
+    a = oracle.encode(W, np.array([7, 5, 11, 9], np.float32), "cer")
+    assert a.omega.tolist() == [7, 5, 9]                      # tie -> earlier codebook position first
+    b = oracle.encode(W, np.array([5, 11, 9, 7], np.float32), "cer")
+    assert b.omega.tolist() == [5, 7, 9]
+    assert np.array_equal(oracle.decode(a), W) and np.array_equal(oracle.decode(b), W)
+    with pytest.raises(oracle.OracleError):
+        oracle.encode(W, np.array([5, 7], np.float32), "cer")            # 9 missing
+    with pytest.raises(oracle.OracleError):
+        oracle.encode(W, np.array([5, 7, 9, 7], np.float32), "cer")      # duplicate
+    with pytest.raises(oracle.OracleError):
+        oracle.encode(W, np.array([5, 7, 9, np.nan], np.float32), "cer")
+
+
+def test_negative_zero_is_zero():
+    W = np.array([[0.0, -0.0, 1.0], [-0.0, 1.0, 1.0]], np.float32)
+    A = oracle.encode(W, np.array([-0.0, 1.0], np.float32), "cer")
+    assert A.count.tolist() == [3, 3] and A.omega.tolist() == [0.0, 1.0]
+    assert not np.signbit(oracle.decode(A)).any()
+
+
+def test_round_trip_brute_force_all_tiny_matrices():
+    """Every 2x3 matrix over a 3-value codebook: decode(encode(W)) == W for both formats."""
+    cb = np.array([-1.5, 0.0, 2.0], np.float32)
+    for combo in itertools.product(range(3), repeat=6):
+        W = cb[np.array(combo)].reshape(2, 3)
+        for fmt in ("cer", "cser"):
+            A = oracle.encode(W, cb, fmt)
+            assert np.array_equal(oracle.decode(A), W), (combo, fmt)
+            X = np.array([[1.0, -2.0], [3.0, 0.5], [-4.0, 8.0]], np.float32)
+            assert np.array_equal(oracle.dot(A, X), W.astype(np.float64) @ X.astype(np.float64)), (combo, fmt)
+
+
+# ------------------------------------------------------------------ invariants on random matrices
+
+CASES = [
+    dict(m=37, n=300, K=16, p_dom=0.9, L=3, seed=11),
+    dict(m=64, n=70, K=8, p_dom=0.5, L=1, seed=12),
+    dict(m=20, n=1000, K=64, p_dom=0.97, L=2, seed=13),
+    dict(m=9, n=257, K=3, p_dom=0.4, L=5, seed=14, dominant=0),      # most frequent value is not 0
+    dict(m=5, n=40, K=1, p_dom=1.0, L=2, seed=15),                   # constant matrix
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: f"{c['m']}x{c['n']}K{c['K']}")
+def test_invariants_round_trip_and_dense_equality(case):
+    w = wl.random_lowentropy(**case)
+    N = w.W.size
+    cer = oracle.encode(w.W, w.codebook, "cer")
+    cser = oracle.encode(w.W, w.codebook, "cser")
+    for A in (cer, cser):
+        assert np.array_equal(oracle.decode(A), w.W)
+        assert (np.diff(A.count) <= 0).all() and A.count.sum() == N          # frequency-major
+        assert A.nnz == N - A.count[0] == A.omegaPtr[-1]
+        assert A.omegaPtr[0] == 0 and (np.diff(A.omegaPtr) >= 0).all()
+        assert A.rowPtr[0] == 0 and (np.diff(A.rowPtr) >= 0).all() and A.rowPtr[-1] == A.G
+        for g in range(A.G):                                                  # ascending inside a group
+            seg = A.colI[A.omegaPtr[g]:A.omegaPtr[g + 1]]
+            assert (np.diff(seg) > 0).all()
+        for r in range(A.m):                                                  # last group of a row is non-empty
+            if A.rowPtr[r + 1] > A.rowPtr[r]:
+                g = A.rowPtr[r + 1] - 1
+                assert A.omegaPtr[g + 1] > A.omegaPtr[g]
+    # CSER = CER with the repeated pointers deleted, plus OmegaI
+    assert np.array_equal(cer.colI, cser.colI) and np.array_equal(cer.omega, cser.omega)
+    sizes = np.diff(cer.omegaPtr)
+    assert np.array_equal(cser.omegaPtr, np.concatenate([[0], cer.omegaPtr[1:][sizes > 0]]))
+    assert (np.diff(cser.omegaPtr) > 0).all() and len(cser.omegaI) == cser.G
+    ranks = np.concatenate([np.arange(1, cer.rowPtr[r + 1] - cer.rowPtr[r] + 1) for r in range(cer.m)] or [[]])
+    assert np.array_equal(cser.omegaI, ranks[sizes > 0].astype(np.int64))
+
+    # product against numpy's float64 matmul (a library routine, independent of the oracle)
+    want = w.W.astype(np.float64) @ w.X.astype(np.float64)
+    scale = np.abs(w.W).astype(np.float64) @ np.abs(w.X).astype(np.float64) + 1e-300
+    for A in (cer, cser):
+        assert (np.abs(oracle.dot(A, w.X) - want) <= 1e-12 * scale + 1e-15 * np.abs(w.W).max() * np.abs(w.X).sum(0)).all()
+    assert (np.abs(oracle.dot_dense(w.W, w.X) - want) <= 1e-12 * scale).all()
+    assert np.allclose(oracle.abs_dot_dense(w.W, w.X), scale, rtol=1e-12)
+    # threads only split rows: identical bits
+    assert np.array_equal(oracle.dot(cer, w.X, threads=3), oracle.dot(cer, w.X))
+
+
+def test_exact_with_integer_data_and_nonzero_dominant():
+    """Small integers make every partial sum exact, so the grouped product must equal the dense
+    one bit for bit, including the constant term for a non-zero most-frequent value."""
+    rng = np.random.default_rng(3)
+    cb = np.array([3, -2, 5, 0, 1], np.float32)
+    sym = rng.choice(5, size=(23, 91), p=[0.6, 0.1, 0.1, 0.1, 0.1])
+    W = cb[sym]
+    X = rng.integers(-7, 8, size=(91, 4)).astype(np.float32)
+    want = W.astype(np.float64) @ X.astype(np.float64)
+    for fmt in ("cer", "cser"):
+        A = oracle.encode(W, cb, fmt)
+        assert A.omega[0] == 3.0
+        assert np.array_equal(oracle.dot(A, X), want)
+
+
+def test_special_cases_reduce_to_textbook_forms():
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((50, 2)).astype(np.float32)
+    X64 = X.astype(np.float64)
+    # K = 2: one value besides 0 -> scalar times a 0/1 pattern matrix
+    P = (rng.random((12, 50)) < 0.3)
+    A = oracle.encode(np.where(P, np.float32(0.75), np.float32(0)), np.array([0, 0.75], np.float32), "cer")
+    assert np.allclose(oracle.dot(A, X), 0.75 * (P.astype(np.float64) @ X64), rtol=0, atol=1e-13)
+    # all groups of length 1 -> CSER is CSR with OmegaPtr = 0,1,2,...
+    W = np.zeros((3, 50), np.float32)
+    W[0, [4, 9]] = [1, 2]; W[1, 7] = 3; W[2, [1, 2, 3]] = [3, 1, 2]
+    W[:, 20:] = 0
+    A = oracle.encode(W, np.array([0, 1, 2, 3], np.float32), "cser")
+    assert A.omegaPtr.tolist() == list(range(7))
+    assert np.allclose(oracle.dot(A, X), W.astype(np.float64) @ X64, atol=1e-14)
+    # constant matrix -> no indices at all, Y = omega0 * column sums
+    A = oracle.encode(np.full((4, 50), 0.5, np.float32), np.array([0.5], np.float32), "cer")
+    assert A.nnz == 0 and A.G == 0
+    assert np.allclose(oracle.dot(A, X), 0.5 * X64.sum(0)[None, :].repeat(4, 0), atol=1e-13)
+
+
+def test_linearity():
+    w = wl.random_lowentropy(m=15, n=200, K=8, p_dom=0.8, L=2, seed=21)
+    A = oracle.encode(w.W, w.codebook, "cer")
+    X2 = wl.sample_X(np.random.default_rng(1), 200, 2)
+    lhs = oracle.dot(A, (2.0 * w.X + 0.5 * X2).astype(np.float32))
+    rhs = 2.0 * oracle.dot(A, w.X) + 0.5 * oracle.dot(A, X2)
+    # 2x and 0.5x are exact in fp32; the fp32 sum 2x+0.5x' is rounded once per element
+    bound = np.abs(w.W).astype(np.float64) @ (np.abs(2.0 * w.X + 0.5 * X2).astype(np.float64)) * 2.0 ** -23
+    assert (np.abs(lhs - rhs) <= bound + 1e-12).all()
+
+
+# ------------------------------------------------------------------ storage cost and limits
+
+def test_min_bits_rule():
+    assert [oracle.min_bits(v) for v in (0, 255, 256, 65535, 65536, 2 ** 32 - 1)] == [8, 8, 16, 16, 32, 32]
+
+
+@pytest.mark.parametrize("case", CASES[:4], ids=lambda c: f"{c['m']}x{c['n']}K{c['K']}")
+def test_storage_formulas(case):
+    """Array lengths of the proofs of Theorems 1 and 2, and the per-element storage of Eq. (9)
+    and Eq. (11) recovered from them."""
+    w = wl.random_lowentropy(**case)
+    m, n = w.W.shape
+    N = m * n
+    cer = oracle.encode(w.W, w.codebook, "cer")
+    cser = oracle.encode(w.W, w.codebook, "cser")
+    # independent recount of k_bar_r and k_tilde_r straight from the dense matrix
+    vals, counts = np.unique(w.W, return_counts=True)
+    dom = cer.omega[0]
+    order = {float(v): i for i, v in enumerate(cer.omega)}
+    kbar = ktil = 0
+    for r in range(m):
+        present = sorted(order[float(v)] for v in np.unique(w.W[r]) if v != dom)
+        kbar += len(present)
+        ktil += (present[-1] - len(present)) if present else 0
+    nnz = N - counts[vals == dom][0]
+    assert cer.nnz == cser.nnz == nnz
+    assert cer.G == kbar + ktil and cser.G == kbar
+    assert oracle.entries(cer) == len(vals) + nnz + (kbar + ktil + 1) + (m + 1)
+    assert oracle.entries(cser) == len(vals) + nnz + kbar + (kbar + 1) + (m + 1)
+    st = oracle.stats(cer)
+    assert st["k_bar"] == pytest.approx(kbar / m) and st["k_tilde"] == pytest.approx(ktil / m)
+    assert st["p0"] == pytest.approx(1 - nnz / N)
+    # Eq. (9) / Eq. (11) with one index width b_I: leading terms + O(1/n) + O(1/N) remainder
+    bI = 32
+    p0 = 1 - nnz / N
+    for A, lead in ((cer, (1 - p0) * bI + (kbar + ktil) / m / n * bI), (cser, (1 - p0) * bI + 2 * kbar / m / n * bI)):
+        per_elem = (oracle.entries(A) - A.K) * bI / N + A.K * 32 / N
+        rest = per_elem - lead
+        assert 0 <= rest <= bI / n + (A.K * 32 + 2 * bI) / N + 1e-12
+    # per-array minimal widths
+    b = oracle.array_bits(cser)
+    assert b["colI"] == (8 if n <= 256 else 16) and b["omegaI"] == 8
+    assert oracle.storage_bits(cer) == cer.K * 32 + nnz * b["colI"] + (cer.G + 1) * oracle.min_bits(nnz) + (m + 1) * oracle.min_bits(cer.G)
+
+
+def test_limits_of_kbar():
+    """Section III-C: k_bar -> K-1 for a uniform distribution with many columns; -> 0 as H -> 0;
+    CER and CSER storage approach each other as n grows (padding disappears)."""
+    rng = np.random.default_rng(9)
+    cb = np.arange(8, dtype=np.float32)
+    W = cb[rng.integers(0, 8, size=(30, 4000))]
+    st = oracle.stats(oracle.encode(W, cb, "cer"))
+    assert st["k_bar"] == 7 and st["k_tilde"] == 0 and st["H"] > 2.99
+    W = np.zeros((30, 400), np.float32)
+    st = oracle.stats(oracle.encode(W, cb, "cer"))
+    assert st["k_bar"] == 0 and st["H"] == 0
