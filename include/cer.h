@@ -1,0 +1,167 @@
+/*
+ * cer.h -- C ABI of the MI355X (gfx950) CER / CSER matrix-product library.
+ *
+ * The library stores a quantized, low-entropy weight matrix W (m rows, n columns, every element
+ * one of K codebook values) in the two formats of Wiedemann, Mueller, Samek, "Compact and
+ * Computationally Efficient Representation of Deep Neural Networks":
+ *
+ *   CER  (Compressed Entropy Row,          Section II-A): Omega, colI, OmegaPtr, rowPtr
+ *   CSER (Compressed Shared Elements Row,  Section II-A): the same plus OmegaI
+ *
+ * and computes Y = W.X on the GPU from those arrays (Appendix A-C, Algorithms 3 and 4): per row,
+ * the inputs selected by one group of column indices are summed and the sum is multiplied once
+ * by the group's value; the most frequent value Omega[0] owns no indices and is handled by a
+ * constant term (Appendix A-A1).
+ *
+ * Conventions
+ *   - Every function returns CER_OK (0) or a negative CER_E_* code; nothing aborts or throws
+ *     across this boundary.  cer_strerror() names a code; cer_last_hip_error() returns the HIP
+ *     error number behind the calling thread's most recent CER_E_HIP.
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device memory on the
+ *     device that was current when the handle was created.  Matrices are row-major fp32.
+ *   - A handle is immutable after creation: any number of threads / streams may use it
+ *     concurrently for matmul, decode and inspection.  Free it exactly once.
+ *   - A handle made by cer_encode is a CER handle, one made by cser_encode a CSER handle; the
+ *     cer_matmul / cer_decode calls accept only the former, cser_matmul / cser_decode only the
+ *     latter (CER_E_FORMAT otherwise).  Inspection calls and cer_free accept both.
+ */
+#ifndef CER_H_
+#define CER_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cer_matrix cer_handle_t; /* opaque */
+
+enum {
+    CER_OK = 0,
+    CER_E_INVALID = -1,         /* null pointer, non-positive size, unknown selector */
+    CER_E_NOT_IN_CODEBOOK = -2, /* a matrix element equals no codebook value */
+    CER_E_BAD_CODEBOOK = -3,    /* duplicate, NaN or infinite codebook value */
+    CER_E_TOO_LARGE = -4,       /* n, the number of indexed elements or of groups exceeds 32 bits */
+    CER_E_NOMEM = -5,           /* host allocation failed */
+    CER_E_HIP = -6,             /* a HIP call failed, or the handle has no device copy */
+    CER_E_FORMAT = -7           /* CER handle given to a cser_* call or the reverse */
+};
+
+/* selectors of cer_get_array */
+enum {
+    CER_ARRAY_OMEGA = 0,    /* fp32 [K]      distinct values, most frequent first */
+    CER_ARRAY_COLI = 1,     /* uint [nnz]    column indices, grouped by row then by value */
+    CER_ARRAY_OMEGAPTR = 2, /* uint [G+1]    group boundaries into colI, leading 0 */
+    CER_ARRAY_ROWPTR = 3,   /* uint [m+1]    row boundaries into OmegaPtr, leading 0 */
+    CER_ARRAY_OMEGAI = 4,   /* uint [G]      CSER only: index into Omega of each group */
+    CER_ARRAY_COUNT = 5     /* int64 [K]     occurrences of Omega[k] in W (not part of the format) */
+};
+
+/*
+ * cer_encode / cser_encode -- dense matrix + codebook -> CER / CSER handle (Section II-A, the
+ * four format steps; CSER paragraph).  Host-side, O(m.n); not part of the timed product, as in
+ * the paper's experiments (Section V).
+ *
+ *   W_host    [m][n] fp32, host, row-major, borrowed for the duration of the call
+ *   codebook  [K] fp32, host, distinct finite values; every element of W must equal one of them
+ *             bit for bit, except that -0.0 and +0.0 are the same value (stored as +0.0)
+ *   out       receives the handle; owned by the caller until cer_free
+ *
+ * The arrays are defined as follows (all indices 0-based):
+ *   Omega     codebook values that occur in W, by occurrence count, highest first; equal counts
+ *             keep codebook order.  Omega[0] (whatever its value) is never indexed.
+ *   colI      for each row, for rank k = 1, 2, ...: the ascending columns holding Omega[k].
+ *   OmegaPtr  OmegaPtr[0] = 0; one entry per group = number of indices emitted so far.
+ *             CER: a row emits groups for ranks 1..kmax (kmax = highest rank present in it); an
+ *             absent rank repeats the previous pointer.  CSER: present ranks only.
+ *   OmegaI    CSER: the rank of each group.
+ *   rowPtr    rowPtr[0] = 0; rowPtr[r+1] = number of groups emitted up to and including row r.
+ *   widths    Omega fp32; each index array is stored in the smallest of 8/16/32 bits that holds
+ *             its largest possible value: colI n-1, OmegaPtr nnz, rowPtr G, OmegaI K-1 (Section V).
+ *
+ * If a HIP device is present the arrays are also uploaded to the current device (one
+ * allocation; colI and OmegaI at their minimal width, the pointer arrays as uint32); with no
+ * device the handle is host-only and *_matmul returns CER_E_HIP.
+ * m = 0 or n = 0 is allowed (empty arrays).  Errors: CER_E_INVALID, CER_E_BAD_CODEBOOK,
+ * CER_E_NOT_IN_CODEBOOK, CER_E_TOO_LARGE, CER_E_NOMEM, CER_E_HIP (upload failed).
+ */
+int cer_encode(const float* W_host, int64_t m, int64_t n, const float* codebook, int32_t K,
+               cer_handle_t** out);
+int cser_encode(const float* W_host, int64_t m, int64_t n, const float* codebook, int32_t K,
+                cer_handle_t** out);
+
+/*
+ * cer_matmul / cser_matmul -- Y = W.X from the encoded arrays (Algorithm 3 / Algorithm 4; the
+ * constant Omega[0].sum_i X[i,l] of Appendix A-A1 is added when Omega[0] != 0).
+ *
+ *   X_dev   [n][batch] fp32, device, row-major, read only
+ *   Y_dev   [m][batch] fp32, device, row-major, fully overwritten (no accumulation into Y)
+ *   batch   number of columns of X (L in the paper), >= 1
+ *   stream  a hipStream_t passed as void*; NULL = the default stream
+ *
+ * Work is enqueued on `stream` and the call returns without synchronising.  The caller keeps
+ * ownership of X and Y and must keep them alive until the stream has run the work.  When
+ * Omega[0] != 0 a stream-ordered temporary of batch floats (plus partial sums) is allocated and
+ * released on `stream`.  fp32 arithmetic; the summation order differs from a sequential loop.
+ * Errors: CER_E_INVALID (null pointers, batch < 1), CER_E_FORMAT, CER_E_HIP.
+ */
+int cer_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t batch, void* stream);
+int cser_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t batch, void* stream);
+
+/*
+ * cer_decode / cser_decode -- arrays -> dense matrix (Section II-A: M can be reconstructed
+ * uniquely).  W_host_out: [m][n] fp32, host, written completely; equals the encoder's input bit
+ * for bit (with -0.0 returned as +0.0).  Host-side.  Errors: CER_E_INVALID, CER_E_FORMAT.
+ */
+int cer_decode(const cer_handle_t* h, float* W_host_out);
+int cser_decode(const cer_handle_t* h, float* W_host_out);
+
+/*
+ * Inspection (host copies of the arrays of Section II-A; lengths as in the proofs of Theorems 1
+ * and 2, with the pointer arrays' leading zeros included).
+ *
+ * cer_get_array: *host_ptr is borrowed and valid until cer_free; *len = number of elements,
+ * *elem_bits = 8, 16 or 32 (unsigned integers), 32 for OMEGA (fp32), 64 for COUNT (int64).
+ * CER_ARRAY_OMEGAI on a CER handle yields len 0.  cer_get_dims: any output pointer may be NULL;
+ * nnz = len(colI), groups = len(OmegaPtr) - 1.  cer_storage_bits = sum over the format's arrays
+ * of length x width (negative code on error).  cer_get_stats: entropy H = -sum p_k log2 p_k of
+ * the element distribution (Section II), p0 = share of Omega[0], k_bar = mean number of
+ * non-empty groups per row, k_tilde = mean number of empty (padding) groups per row (Theorem 1).
+ */
+int cer_get_array(const cer_handle_t* h, int which, const void** host_ptr, int64_t* len,
+                  int32_t* elem_bits);
+int cer_get_dims(const cer_handle_t* h, int64_t* m, int64_t* n, int32_t* K, int64_t* nnz,
+                 int64_t* groups, int32_t* is_cser);
+int64_t cer_storage_bits(const cer_handle_t* h);
+int cer_get_stats(const cer_handle_t* h, double* H, double* p0, double* k_bar, double* k_tilde);
+
+/*
+ * cer_clone_device -- a second handle with the same host arrays and its own, freshly allocated
+ * device copy on the current device.  Lets a benchmark rotate over more encoded bytes than the
+ * GPU's caches hold.  Errors: CER_E_INVALID, CER_E_NOMEM, CER_E_HIP.
+ */
+int cer_clone_device(const cer_handle_t* h, cer_handle_t** out);
+
+/* Bytes of device memory the product reads from the handle's arrays in one call (colI at its
+ * width + uint32 OmegaPtr and rowPtr + OmegaI + Omega); 0 for a host-only handle. */
+int64_t cer_device_bytes(const cer_handle_t* h);
+
+/* Frees host and device memory.  NULL is allowed. */
+void cer_free(cer_handle_t* h);
+
+/*
+ * dense_matmul -- the plain dense fp32 product Y = W.X (Algorithm 1) as a HIP kernel on the same
+ * device: the baseline the CER / CSER speed-up is quoted against.
+ *   W_dev [m][n], X_dev [n][batch], Y_dev [m][batch]: fp32, device, row-major; Y overwritten.
+ * Enqueued on `stream`, no synchronisation.  Errors: CER_E_INVALID, CER_E_HIP.
+ */
+int dense_matmul(const float* W_dev, const float* X_dev, float* Y_dev, int64_t m, int64_t n,
+                 int64_t batch, void* stream);
+
+const char* cer_strerror(int code);
+int cer_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CER_H_ */

@@ -1,0 +1,224 @@
+"""Python binding of the C ABI in include/cer.h -- argument marshalling only.
+
+Every function has the name of the C entry point it calls.  Device buffers are passed as torch
+tensors (their ``data_ptr()`` is handed to the library) or as raw integer addresses; streams as
+``torch.cuda.Stream`` objects, raw ``hipStream_t`` integers, or None for the current torch stream.
+No step of the product runs in Python or in torch, and there is no CPU fallback: if the built
+library is missing, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libcer_hip.so")
+
+CER_OK = 0
+CER_E_INVALID = -1
+CER_E_NOT_IN_CODEBOOK = -2
+CER_E_BAD_CODEBOOK = -3
+CER_E_TOO_LARGE = -4
+CER_E_NOMEM = -5
+CER_E_HIP = -6
+CER_E_FORMAT = -7
+
+CER_ARRAY_OMEGA, CER_ARRAY_COLI, CER_ARRAY_OMEGAPTR, CER_ARRAY_ROWPTR, CER_ARRAY_OMEGAI, CER_ARRAY_COUNT = range(6)
+
+EXPORTS = [
+    "cer_encode", "cser_encode", "cer_matmul", "cser_matmul", "cer_decode", "cser_decode",
+    "cer_get_array", "cer_get_dims", "cer_storage_bits", "cer_get_stats", "cer_clone_device",
+    "cer_device_bytes", "cer_free", "dense_matmul", "cer_strerror", "cer_last_hip_error",
+]
+
+_lib = None
+
+
+class CerError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        msg = lib().cer_strerror(code).decode()
+        if code == CER_E_HIP:
+            msg += f" (hipError {lib().cer_last_hip_error()})"
+        super().__init__(f"{what}: {msg} [{code}]")
+        self.code = code
+
+
+def lib() -> ctypes.CDLL:
+    """Loads paper_1805_10692_amd/libcer_hip.so (built by `python -m paper_1805_10692_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_1805_10692_amd.build` "
+                              "(there is no fallback implementation)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+        pvp = ctypes.POINTER(vp)
+        for name in ("cer_encode", "cser_encode"):
+            getattr(L, name).restype = ctypes.c_int
+            getattr(L, name).argtypes = [vp, i64, i64, vp, i32, pvp]
+        for name in ("cer_matmul", "cser_matmul"):
+            getattr(L, name).restype = ctypes.c_int
+            getattr(L, name).argtypes = [vp, vp, vp, i64, vp]
+        for name in ("cer_decode", "cser_decode"):
+            getattr(L, name).restype = ctypes.c_int
+            getattr(L, name).argtypes = [vp, vp]
+        L.cer_get_array.restype = ctypes.c_int
+        L.cer_get_array.argtypes = [vp, ctypes.c_int, pvp, ctypes.POINTER(i64), ctypes.POINTER(i32)]
+        L.cer_get_dims.restype = ctypes.c_int
+        L.cer_get_dims.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i32),
+                                   ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i32)]
+        L.cer_storage_bits.restype = i64
+        L.cer_storage_bits.argtypes = [vp]
+        L.cer_get_stats.restype = ctypes.c_int
+        L.cer_get_stats.argtypes = [vp] + [ctypes.POINTER(ctypes.c_double)] * 4
+        L.cer_clone_device.restype = ctypes.c_int
+        L.cer_clone_device.argtypes = [vp, pvp]
+        L.cer_device_bytes.restype = i64
+        L.cer_device_bytes.argtypes = [vp]
+        L.cer_free.restype = None
+        L.cer_free.argtypes = [vp]
+        L.dense_matmul.restype = ctypes.c_int
+        L.dense_matmul.argtypes = [vp, vp, vp, i64, i64, i64, vp]
+        L.cer_strerror.restype = ctypes.c_char_p
+        L.cer_strerror.argtypes = [ctypes.c_int]
+        L.cer_last_hip_error.restype = ctypes.c_int
+        L.cer_last_hip_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != CER_OK:
+        raise CerError(rc, what)
+
+
+def _dev_ptr(t) -> int:
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda or t.dtype.itemsize != 4 or not t.is_contiguous():
+        raise ValueError("expected a contiguous fp32 tensor in device memory")
+    return t.data_ptr()
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+class Handle:
+    """Owns one cer_handle_t*; freed by cer_free() or when garbage-collected."""
+
+    def __init__(self, ptr: int, fmt: str):
+        self.ptr = ptr
+        self.fmt = fmt
+
+    def __del__(self):
+        try:
+            cer_free(self)
+        except Exception:
+            pass
+
+
+def _encode(name: str, W: np.ndarray, codebook: np.ndarray) -> Handle:
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    cb = np.ascontiguousarray(codebook, dtype=np.float32)
+    if W.ndim != 2 or cb.ndim != 1:
+        raise ValueError("W must be 2-D and the codebook 1-D")
+    out = ctypes.c_void_p()
+    rc = getattr(lib(), name)(W.ctypes.data, W.shape[0], W.shape[1], cb.ctypes.data, len(cb), ctypes.byref(out))
+    _check(rc, name)
+    return Handle(out.value, "cser" if name.startswith("cser") else "cer")
+
+
+def cer_encode(W: np.ndarray, codebook: np.ndarray) -> Handle:
+    return _encode("cer_encode", W, codebook)
+
+
+def cser_encode(W: np.ndarray, codebook: np.ndarray) -> Handle:
+    return _encode("cser_encode", W, codebook)
+
+
+def cer_matmul(h: Handle, X, Y, batch: int, stream=None) -> None:
+    _check(lib().cer_matmul(h.ptr, _dev_ptr(X), _dev_ptr(Y), batch, _stream_ptr(stream)), "cer_matmul")
+
+
+def cser_matmul(h: Handle, X, Y, batch: int, stream=None) -> None:
+    _check(lib().cser_matmul(h.ptr, _dev_ptr(X), _dev_ptr(Y), batch, _stream_ptr(stream)), "cser_matmul")
+
+
+def _decode(name: str, h: Handle) -> np.ndarray:
+    m, n = cer_get_dims(h)["m"], cer_get_dims(h)["n"]
+    W = np.empty((m, n), np.float32)
+    _check(getattr(lib(), name)(h.ptr, W.ctypes.data), name)
+    return W
+
+
+def cer_decode(h: Handle) -> np.ndarray:
+    return _decode("cer_decode", h)
+
+
+def cser_decode(h: Handle) -> np.ndarray:
+    return _decode("cser_decode", h)
+
+
+def cer_get_array(h: Handle, which: int) -> np.ndarray:
+    """A copy of one host array at its stored width (uint8/16/32, float32 for Omega, int64 counts)."""
+    p, n, bits = ctypes.c_void_p(), ctypes.c_int64(), ctypes.c_int32()
+    _check(lib().cer_get_array(h.ptr, which, ctypes.byref(p), ctypes.byref(n), ctypes.byref(bits)), "cer_get_array")
+    if which == CER_ARRAY_OMEGA:
+        dt = np.float32
+    elif which == CER_ARRAY_COUNT:
+        dt = np.int64
+    else:
+        dt = {8: np.uint8, 16: np.uint16, 32: np.uint32}[bits.value]
+    if n.value == 0:
+        return np.empty(0, dt)
+    buf = (ctypes.c_char * (n.value * np.dtype(dt).itemsize)).from_address(p.value)
+    return np.frombuffer(buf, dtype=dt).copy()
+
+
+def cer_get_dims(h: Handle) -> dict:
+    m, n, nnz, g = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    K, cs = ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().cer_get_dims(h.ptr, ctypes.byref(m), ctypes.byref(n), ctypes.byref(K), ctypes.byref(nnz),
+                              ctypes.byref(g), ctypes.byref(cs)), "cer_get_dims")
+    return {"m": m.value, "n": n.value, "K": K.value, "nnz": nnz.value, "groups": g.value, "is_cser": cs.value}
+
+
+def cer_storage_bits(h: Handle) -> int:
+    v = lib().cer_storage_bits(h.ptr)
+    if v < 0:
+        raise CerError(int(v), "cer_storage_bits")
+    return int(v)
+
+
+def cer_get_stats(h: Handle) -> dict:
+    vals = [ctypes.c_double() for _ in range(4)]
+    _check(lib().cer_get_stats(h.ptr, *[ctypes.byref(v) for v in vals]), "cer_get_stats")
+    return dict(zip(("H", "p0", "k_bar", "k_tilde"), (v.value for v in vals)))
+
+
+def cer_clone_device(h: Handle) -> Handle:
+    out = ctypes.c_void_p()
+    _check(lib().cer_clone_device(h.ptr, ctypes.byref(out)), "cer_clone_device")
+    return Handle(out.value, h.fmt)
+
+
+def cer_device_bytes(h: Handle) -> int:
+    return int(lib().cer_device_bytes(h.ptr))
+
+
+def cer_free(h: Handle) -> None:
+    if h.ptr:
+        lib().cer_free(h.ptr)
+        h.ptr = None
+
+
+def dense_matmul(W, X, Y, m: int, n: int, batch: int, stream=None) -> None:
+    _check(lib().dense_matmul(_dev_ptr(W), _dev_ptr(X), _dev_ptr(Y), m, n, batch, _stream_ptr(stream)), "dense_matmul")

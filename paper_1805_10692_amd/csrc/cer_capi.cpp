@@ -1,0 +1,273 @@
+// extern "C" boundary of the library: argument checks, handle lifetime, device upload.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "../../include/cer.h"
+#include "cer_internal.hpp"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return CER_E_HIP;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+std::vector<uint32_t> widen(const cer::HostArray& a) {
+    std::vector<uint32_t> out((size_t)a.len);
+    for (int64_t i = 0; i < a.len; ++i) out[(size_t)i] = (uint32_t)a.at(i);
+    return out;
+}
+
+// One allocation: [colI | 64 B pad][OmegaPtr u32][rowPtr u32][OmegaI][Omega], each 256-byte aligned.
+int upload(cer_matrix* h) {
+    const cer::HostMatrix& A = *h->host;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) {
+        (void)hipGetLastError();
+        h->device = -1;
+        return CER_OK;  // host-only handle
+    }
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+
+    const size_t colI_bytes = A.colI.bytes.size();
+    const size_t off_colI = 0;
+    const size_t off_optr = align_up(off_colI + colI_bytes + 64, 256);
+    const size_t off_rptr = align_up(off_optr + (size_t)(A.G + 1) * 4 + 16, 256);
+    const size_t off_oi = align_up(off_rptr + (size_t)(A.m + 1) * 4 + 16, 256);
+    const size_t off_om = align_up(off_oi + A.omegaI.bytes.size() + 16, 256);
+    const size_t total = align_up(off_om + (size_t)std::max(A.K, 1) * 4, 256);
+
+    void* base = nullptr;
+    e = hipMalloc(&base, total);
+    if (e != hipSuccess) return hip_fail(e);
+    auto* b = static_cast<unsigned char*>(base);
+    e = hipMemset(base, 0, total);
+    auto put = [&](size_t off, const void* src, size_t bytes) {
+        if (e == hipSuccess && bytes) e = hipMemcpy(b + off, src, bytes, hipMemcpyHostToDevice);
+    };
+    put(off_colI, A.colI.bytes.data(), colI_bytes);
+    {
+        std::vector<uint32_t> w = widen(A.omegaPtr);
+        put(off_optr, w.data(), w.size() * 4);
+    }
+    {
+        std::vector<uint32_t> w = widen(A.rowPtr);
+        put(off_rptr, w.data(), w.size() * 4);
+    }
+    put(off_oi, A.omegaI.bytes.data(), A.omegaI.bytes.size());
+    put(off_om, A.omega.data(), A.omega.size() * 4);
+    if (e != hipSuccess) {
+        (void)hipFree(base);
+        return hip_fail(e);
+    }
+    h->device = dev;
+    h->d_base = base;
+    h->d_bytes = total;
+    h->stream_bytes = (int64_t)(colI_bytes + (size_t)(A.G + 1) * 4 + (size_t)(A.m + 1) * 4 + A.omegaI.bytes.size() +
+                                A.omega.size() * 4);
+    cer::DeviceView& v = h->view;
+    v.colI = b + off_colI;
+    v.omegaPtr = reinterpret_cast<const uint32_t*>(b + off_optr);
+    v.rowPtr = reinterpret_cast<const uint32_t*>(b + off_rptr);
+    v.omegaI = b + off_oi;
+    v.omega = reinterpret_cast<const float*>(b + off_om);
+    v.colI_bits = A.colI.bits;
+    v.omegaI_bits = A.omegaI.bits;
+    v.cser = A.cser ? 1 : 0;
+    v.K = A.K;
+    v.m = A.m;
+    v.n = A.n;
+    v.omega0 = A.K > 0 ? A.omega[0] : 0.f;
+    return CER_OK;
+}
+
+int encode_any(const float* W, int64_t m, int64_t n, const float* codebook, int32_t K, bool cser, cer_handle_t** out) {
+    if (!out) return CER_E_INVALID;
+    *out = nullptr;
+    if (m < 0 || n < 0 || K < 0) return CER_E_INVALID;
+    if ((m > 0 && n > 0 && !W) || (K > 0 && !codebook)) return CER_E_INVALID;
+    if (m > 0 && n > 0 && K == 0) return CER_E_NOT_IN_CODEBOOK;
+    if (m > 0x7FFFFFFFll) return CER_E_TOO_LARGE;
+    try {
+        std::shared_ptr<cer::HostMatrix> host;
+        int rc = cer::encode_host(W, m, n, codebook, K, cser, &host);
+        if (rc != CER_OK) return rc;
+        auto* h = new cer_matrix();
+        h->host = std::move(host);
+        rc = upload(h);
+        if (rc != CER_OK) {
+            delete h;
+            return rc;
+        }
+        *out = h;
+        return CER_OK;
+    } catch (const std::bad_alloc&) {
+        return CER_E_NOMEM;
+    } catch (...) {
+        return CER_E_INVALID;
+    }
+}
+
+int matmul_any(const cer_handle_t* h, bool want_cser, const float* X, float* Y, int64_t batch, void* stream) {
+    if (!h || !X || !Y || batch < 1) return CER_E_INVALID;
+    if (h->host->cser != want_cser) return CER_E_FORMAT;
+    if (h->device < 0 || !h->d_base) {
+        g_last_hip_error = (int)hipErrorNoDevice;
+        return CER_E_HIP;
+    }
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev != h->device) return hip_fail(hipErrorInvalidDevice);
+    const int rc = cer::launch_matmul(h->view, X, Y, batch, stream);
+    return rc == 0 ? CER_OK : hip_fail((hipError_t)rc);
+}
+
+int decode_any(const cer_handle_t* h, bool want_cser, float* W_out) {
+    if (!h) return CER_E_INVALID;
+    if (h->host->cser != want_cser) return CER_E_FORMAT;
+    if (!W_out && h->host->m * h->host->n > 0) return CER_E_INVALID;
+    try {
+        return cer::decode_host(*h->host, W_out);
+    } catch (...) {
+        return CER_E_NOMEM;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int cer_encode(const float* W, int64_t m, int64_t n, const float* codebook, int32_t K, cer_handle_t** out) {
+    return encode_any(W, m, n, codebook, K, false, out);
+}
+int cser_encode(const float* W, int64_t m, int64_t n, const float* codebook, int32_t K, cer_handle_t** out) {
+    return encode_any(W, m, n, codebook, K, true, out);
+}
+
+int cer_matmul(const cer_handle_t* h, const float* X, float* Y, int64_t batch, void* stream) {
+    return matmul_any(h, false, X, Y, batch, stream);
+}
+int cser_matmul(const cer_handle_t* h, const float* X, float* Y, int64_t batch, void* stream) {
+    return matmul_any(h, true, X, Y, batch, stream);
+}
+
+int cer_decode(const cer_handle_t* h, float* W_out) { return decode_any(h, false, W_out); }
+int cser_decode(const cer_handle_t* h, float* W_out) { return decode_any(h, true, W_out); }
+
+int cer_get_array(const cer_handle_t* h, int which, const void** host_ptr, int64_t* len, int32_t* elem_bits) {
+    if (!h || !host_ptr || !len || !elem_bits) return CER_E_INVALID;
+    const cer::HostMatrix& A = *h->host;
+    const cer::HostArray* a = nullptr;
+    switch (which) {
+        case CER_ARRAY_OMEGA: *host_ptr = A.omega.data(); *len = A.K; *elem_bits = 32; return CER_OK;
+        case CER_ARRAY_COUNT: *host_ptr = A.count.data(); *len = A.K; *elem_bits = 64; return CER_OK;
+        case CER_ARRAY_COLI: a = &A.colI; break;
+        case CER_ARRAY_OMEGAPTR: a = &A.omegaPtr; break;
+        case CER_ARRAY_ROWPTR: a = &A.rowPtr; break;
+        case CER_ARRAY_OMEGAI: a = &A.omegaI; break;
+        default: return CER_E_INVALID;
+    }
+    *host_ptr = a->bytes.data();
+    *len = a->len;
+    *elem_bits = a->bits;
+    return CER_OK;
+}
+
+int cer_get_dims(const cer_handle_t* h, int64_t* m, int64_t* n, int32_t* K, int64_t* nnz, int64_t* groups,
+                 int32_t* is_cser) {
+    if (!h) return CER_E_INVALID;
+    const cer::HostMatrix& A = *h->host;
+    if (m) *m = A.m;
+    if (n) *n = A.n;
+    if (K) *K = A.K;
+    if (nnz) *nnz = A.nnz;
+    if (groups) *groups = A.G;
+    if (is_cser) *is_cser = A.cser ? 1 : 0;
+    return CER_OK;
+}
+
+int64_t cer_storage_bits(const cer_handle_t* h) {
+    if (!h) return CER_E_INVALID;
+    const cer::HostMatrix& A = *h->host;
+    int64_t bits = (int64_t)A.K * 32 + A.colI.len * A.colI.bits + A.omegaPtr.len * A.omegaPtr.bits +
+                   A.rowPtr.len * A.rowPtr.bits;
+    if (A.cser) bits += A.omegaI.len * A.omegaI.bits;
+    return bits;
+}
+
+int cer_get_stats(const cer_handle_t* h, double* H, double* p0, double* k_bar, double* k_tilde) {
+    if (!h) return CER_E_INVALID;
+    const cer::HostMatrix& A = *h->host;
+    const double N = (double)A.m * (double)A.n;
+    double ent = 0.0;
+    for (int32_t k = 0; k < A.K; ++k) {
+        const double p = N > 0 ? (double)A.count[(size_t)k] / N : 0.0;
+        if (p > 0) ent -= p * std::log2(p);
+    }
+    if (H) *H = ent;
+    if (p0) *p0 = (A.K > 0 && N > 0) ? (double)A.count[0] / N : 0.0;
+    if (k_bar) *k_bar = A.m > 0 ? (double)A.nonempty_groups / (double)A.m : 0.0;
+    if (k_tilde) *k_tilde = A.m > 0 ? (double)(A.G - A.nonempty_groups) / (double)A.m : 0.0;
+    return CER_OK;
+}
+
+int cer_clone_device(const cer_handle_t* h, cer_handle_t** out) {
+    if (!h || !out) return CER_E_INVALID;
+    *out = nullptr;
+    try {
+        auto* c = new cer_matrix();
+        c->host = h->host;
+        const int rc = upload(c);
+        if (rc != CER_OK) {
+            delete c;
+            return rc;
+        }
+        *out = c;
+        return CER_OK;
+    } catch (const std::bad_alloc&) {
+        return CER_E_NOMEM;
+    }
+}
+
+int64_t cer_device_bytes(const cer_handle_t* h) { return (h && h->device >= 0) ? h->stream_bytes : 0; }
+
+void cer_free(cer_handle_t* h) {
+    if (!h) return;
+    if (h->d_base) (void)hipFree(h->d_base);
+    delete h;
+}
+
+int dense_matmul(const float* W, const float* X, float* Y, int64_t m, int64_t n, int64_t batch, void* stream) {
+    if (m < 0 || n < 0 || batch < 1) return CER_E_INVALID;
+    if (!Y || (n > 0 && m > 0 && !W) || (n > 0 && !X)) return CER_E_INVALID;
+    const int rc = cer::launch_dense(W, X, Y, m, n, batch, stream);
+    return rc == 0 ? CER_OK : hip_fail((hipError_t)rc);
+}
+
+const char* cer_strerror(int code) {
+    switch (code) {
+        case CER_OK: return "ok";
+        case CER_E_INVALID: return "invalid argument";
+        case CER_E_NOT_IN_CODEBOOK: return "matrix element not in codebook";
+        case CER_E_BAD_CODEBOOK: return "codebook has a duplicate, NaN or infinite value";
+        case CER_E_TOO_LARGE: return "matrix too large for 32-bit indices";
+        case CER_E_NOMEM: return "out of host memory";
+        case CER_E_HIP: return "HIP error or no device copy";
+        case CER_E_FORMAT: return "handle has the other format";
+        default: return "unknown error";
+    }
+}
+
+int cer_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

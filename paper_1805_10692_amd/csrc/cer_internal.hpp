@@ -1,0 +1,70 @@
+// Internal declarations shared by the host encoder, the C ABI and the HIP launchers.
+#pragma once
+
+#include <cstdint>
+#include <memory>
+#include <vector>
+
+namespace cer {
+
+// One index array of the format, kept on the host at its minimal width (Section V).
+struct HostArray {
+    std::vector<uint8_t> bytes;
+    int64_t len = 0;
+    int32_t bits = 8;
+    uint64_t at(int64_t i) const {
+        switch (bits) {
+            case 8: return bytes[(size_t)i];
+            case 16: return reinterpret_cast<const uint16_t*>(bytes.data())[i];
+            default: return reinterpret_cast<const uint32_t*>(bytes.data())[i];
+        }
+    }
+};
+
+// Host side of a handle; immutable after encode and shared between clones.
+struct HostMatrix {
+    bool cser = false;
+    int64_t m = 0, n = 0;
+    int32_t K = 0;
+    int64_t nnz = 0, G = 0;
+    int64_t nonempty_groups = 0;
+    std::vector<float> omega;
+    std::vector<int64_t> count;
+    HostArray colI, omegaPtr, rowPtr, omegaI;
+};
+
+// What the kernels see: device pointers into the handle's single allocation.
+struct DeviceView {
+    const void* colI = nullptr;        // minimal width, padded with 64 readable bytes
+    const uint32_t* omegaPtr = nullptr; // G + 1
+    const uint32_t* rowPtr = nullptr;   // m + 1
+    const void* omegaI = nullptr;       // minimal width (CSER)
+    const float* omega = nullptr;       // K
+    int32_t colI_bits = 16;
+    int32_t omegaI_bits = 8;
+    int32_t cser = 0;
+    int32_t K = 0;
+    int64_t m = 0, n = 0;
+    float omega0 = 0.f;
+};
+
+// Host encoder (cer_host.cpp).  Returns a CER_* code.
+int encode_host(const float* W, int64_t m, int64_t n, const float* codebook, int32_t K, bool cser,
+                std::shared_ptr<HostMatrix>* out);
+int decode_host(const HostMatrix& A, float* W_out);
+int min_index_bits(uint64_t max_value);
+
+// HIP launchers (cer_kernels.hip).  Return a hipError_t value as int (0 = success).
+int launch_matmul(const DeviceView& v, const float* X, float* Y, int64_t L, void* stream);
+int launch_dense(const float* W, const float* X, float* Y, int64_t m, int64_t n, int64_t L, void* stream);
+
+}  // namespace cer
+
+struct cer_matrix {
+    std::shared_ptr<const cer::HostMatrix> host;
+    int device = -1;          // -1: host-only handle
+    void* d_base = nullptr;   // the one device allocation
+    size_t d_bytes = 0;       // its size
+    int64_t stream_bytes = 0; // bytes of format arrays a product reads
+    cer::DeviceView view;
+};

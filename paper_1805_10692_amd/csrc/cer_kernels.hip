@@ -1,0 +1,717 @@
+// HIP kernels for gfx950 (MI355X, CDNA4, wave64): Y = W.X with W in CER / CSER form
+// (Appendix A-C, Algorithms 3 and 4 of the paper), the constant term for a non-zero most frequent
+// value (Appendix A-A1), and the dense fp32 product used as the baseline (Algorithm 1).
+//
+// Mapping of the method onto the machine
+//   * one wavefront owns one output row (times one tile of batch columns);
+//   * the wave first turns the row's group pointers into a compact list of its NON-EMPTY groups
+//     in LDS: (end offset into colI, value - Omega[0]).  CER derives the value from the group's
+//     position in the row, CSER from OmegaI; empty CER padding groups vanish here, so both formats
+//     share every later step;
+//   * colI is then streamed with 16-byte coalesced loads.  Every lane keeps a cursor into the
+//     group list, a running sum of the inputs gathered for its current group, and multiplies that
+//     sum by the group's value only when it crosses a group boundary -- one multiplication per
+//     (lane, group) instead of one per element, which is the paper's point;
+//   * batch = 1: X is staged into LDS once per workgroup and gathered from there; the 64 lane
+//     totals are combined with DPP cross-lane adds.
+//   * batch > 1: lanes run across the batch columns (P lanes x V floats per index), 64/P indices
+//     are in flight per wave instruction, X rows are gathered from L2; workgroups are numbered so
+//     that one XCD's L2 sees as few batch tiles as possible.
+// MFMA is not used on this path: it is a gather-accumulate, not a dense contraction.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdlib>
+#include <mutex>
+
+#include "cer_internal.hpp"
+
+namespace cer {
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kGroupTile = 256;  // raw groups turned into one LDS list at a time
+constexpr uint32_t kNoEnd = 0xFFFFFFFFu;
+
+struct KView {
+    const void* colI;
+    const uint32_t* omegaPtr;
+    const uint32_t* rowPtr;
+    const void* omegaI;
+    const float* omega;
+    int32_t omegaI_bits;
+    int32_t cser;
+    uint32_t m;
+    uint32_t n;
+    float omega0;
+};
+
+__device__ __forceinline__ uint32_t load_rank(const void* p, int bits, uint32_t g) {
+    if (bits == 8) return static_cast<const uint8_t*>(p)[g];
+    if (bits == 16) return static_cast<const uint16_t*>(p)[g];
+    return static_cast<const uint32_t*>(p)[g];
+}
+
+__device__ __forceinline__ void wave_lds_sync() {
+    // LDS operations of one wave are executed in order; only the compiler must not move them.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ uint32_t uniform(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Compact list of the non-empty groups among raw groups [tg, tg_end) of the row whose first
+// group is g0.  ends[j] = offset in colI one past group j, wts[j] = Omega[rank] - Omega[0]
+// (Algorithm 3: rank = position in the row + 1; Algorithm 4: rank = OmegaI[g]).
+// A sentinel (end = 2^32-1, weight 0) closes the list.  Returns the list length.
+__device__ __forceinline__ int build_group_list(const KView& v, uint32_t g0, uint32_t tg, uint32_t tg_end,
+                                                uint32_t* ends, float* wts, int lane) {
+    int count = 0;
+    for (uint32_t j0 = tg; j0 < tg_end; j0 += kWave) {
+        const uint32_t g = j0 + lane;
+        uint32_t s = 0, e = 0;
+        if (g < tg_end) {
+            s = v.omegaPtr[g];
+            e = v.omegaPtr[g + 1];
+        }
+        const bool nonempty = e > s;
+        const uint64_t mask = __ballot(nonempty);
+        if (nonempty) {
+            const int pos = count + __popcll(mask & ((1ull << lane) - 1ull));
+            const uint32_t rank = v.cser ? load_rank(v.omegaI, v.omegaI_bits, g) : g - g0 + 1u;
+            ends[pos] = e;
+            wts[pos] = v.omega[rank] - v.omega0;
+        }
+        count += __popcll(mask);
+    }
+    if (lane == 0) {
+        ends[count] = kNoEnd;
+        wts[count] = 0.f;
+    }
+    wave_lds_sync();
+    return count;
+}
+
+// Per-lane position in the group list.
+struct Cursor {
+    int j;
+    uint32_t end;
+    float w;
+};
+
+// Moves the cursor to the group that contains colI offset `pos` (pos >= c.end on entry).
+__device__ __forceinline__ void cursor_seek(Cursor& c, uint32_t pos, const uint32_t* ends, const float* wts,
+                                            int count) {
+    ++c.j;
+    c.end = ends[c.j];
+    if (pos >= c.end) {
+        int lo = c.j + 1, hi = count;  // ends[count] is the sentinel, larger than any offset
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (ends[mid] > pos) hi = mid; else lo = mid + 1;
+        }
+        c.j = lo;
+        c.end = ends[lo];
+    }
+    c.w = wts[c.j];
+}
+
+template <typename IdxT> struct Chunk;  // one 16-byte load of colI
+template <> struct Chunk<uint8_t> { static constexpr int E = 16; };
+template <> struct Chunk<uint16_t> { static constexpr int E = 8; };
+template <> struct Chunk<uint32_t> { static constexpr int E = 4; };
+
+template <typename IdxT, int k>
+__device__ __forceinline__ uint32_t chunk_get(const uint4& q) {
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+    if constexpr (sizeof(IdxT) == 4) return w[k];
+    else if constexpr (sizeof(IdxT) == 2) return (w[k >> 1] >> ((k & 1) * 16)) & 0xFFFFu;
+    else return (w[k >> 2] >> ((k & 3) * 8)) & 0xFFu;
+}
+
+// Sum over the 64 lanes with DPP adds inside each row of 16 lanes, then four lane reads.
+__device__ __forceinline__ float wave_sum(float x) {
+    auto dpp_add = [](float v, auto ctrl) {
+        int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(ctrl)::value, 0xF, 0xF, false);
+        return v + __int_as_float(t);
+    };
+    x = dpp_add(x, std::integral_constant<int, 0xB1>{});   // quad_perm [1,0,3,2]
+    x = dpp_add(x, std::integral_constant<int, 0x4E>{});   // quad_perm [2,3,0,1]
+    x = dpp_add(x, std::integral_constant<int, 0x141>{});  // row_half_mirror
+    x = dpp_add(x, std::integral_constant<int, 0x140>{});  // row_mirror
+    const int xi = __float_as_int(x);
+    return (__int_as_float(__builtin_amdgcn_readlane(xi, 0)) + __int_as_float(__builtin_amdgcn_readlane(xi, 16))) +
+           (__int_as_float(__builtin_amdgcn_readlane(xi, 32)) + __int_as_float(__builtin_amdgcn_readlane(xi, 48)));
+}
+
+// ------------------------------------------------------------------------------------------------
+// batch = 1
+// ------------------------------------------------------------------------------------------------
+
+template <typename IdxT, bool kXinLds, int E, int... Ks>
+__device__ __forceinline__ void gemv_chunk(const uint4& q, uint32_t c, uint32_t ts, uint32_t te, const float* xg,
+                                           const float* xs, Cursor& cur, float& run, float& acc,
+                                           const uint32_t* ends, const float* wts, int count,
+                                           std::integer_sequence<int, Ks...>) {
+    const uint32_t idx[E] = {chunk_get<IdxT, Ks>(q)...};
+    const uint32_t first = c > ts ? c : ts;
+    if (first >= cur.end) {
+        acc = fmaf(run, cur.w, acc);
+        run = 0.f;
+        cursor_seek(cur, first, ends, wts, count);
+    }
+    const uint32_t stop = cur.end < te ? cur.end : te;
+    if (c >= ts && c + E <= stop) {
+        // whole chunk inside one group
+        float x[E];
+#pragma unroll
+        for (int k = 0; k < E; ++k) x[k] = kXinLds ? xs[idx[k]] : xg[idx[k]];
+#pragma unroll
+        for (int w = 1; w < E; w <<= 1)
+#pragma unroll
+            for (int k = 0; k + w < E; k += 2 * w) x[k] += x[k + w];
+        run += x[0];
+    } else {
+#pragma unroll
+        for (int k = 0; k < E; ++k) {
+            const uint32_t pos = c + k;
+            if (pos >= ts && pos < te) {
+                if (pos >= cur.end) {
+                    acc = fmaf(run, cur.w, acc);
+                    run = 0.f;
+                    cursor_seek(cur, pos, ends, wts, count);
+                }
+                run += kXinLds ? xs[idx[k]] : xg[idx[k]];
+            }
+        }
+    }
+}
+
+template <typename IdxT, bool kXinLds>
+__global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
+                                                        const float* __restrict__ T, uint32_t rows_per_block,
+                                                        int x_vec4_ok) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int E = Chunk<IdxT>::E;
+    constexpr int U = 4;  // 16-byte loads in flight per lane
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int nwaves = blockDim.x >> 6;
+
+    float* xs = reinterpret_cast<float*>(smem);
+    const uint32_t x_floats = kXinLds ? ((v.n + 3u) & ~3u) : 0u;
+    uint32_t* ends = reinterpret_cast<uint32_t*>(xs + x_floats) + wave * (kGroupTile + 1);
+    float* wts = reinterpret_cast<float*>(reinterpret_cast<uint32_t*>(xs + x_floats) + nwaves * (kGroupTile + 1)) +
+                 wave * (kGroupTile + 1);
+
+    if (kXinLds) {
+        if (x_vec4_ok) {
+            const uint32_t n4 = v.n >> 2;
+            const float4* X4 = reinterpret_cast<const float4*>(X);
+            float4* xs4 = reinterpret_cast<float4*>(xs);
+            for (uint32_t i = threadIdx.x; i < n4; i += blockDim.x) xs4[i] = X4[i];
+            for (uint32_t i = (n4 << 2) + threadIdx.x; i < v.n; i += blockDim.x) xs[i] = X[i];
+        } else {
+            for (uint32_t i = threadIdx.x; i < v.n; i += blockDim.x) xs[i] = X[i];
+        }
+        __syncthreads();
+    }
+
+    const float t_off = (v.omega0 != 0.f) ? v.omega0 * T[0] : 0.f;
+    const uint32_t row_begin = blockIdx.x * rows_per_block;
+    const uint32_t row_end = min(v.m, row_begin + rows_per_block);
+    const uint4* colI16 = static_cast<const uint4*>(v.colI);
+
+    for (uint32_t r = row_begin + wave; r < row_end; r += nwaves) {
+        const uint32_t g0 = uniform(v.rowPtr[r]);
+        const uint32_t g1 = uniform(v.rowPtr[r + 1]);
+        float acc = 0.f;
+        for (uint32_t tg = g0; tg < g1; tg += kGroupTile) {
+            const uint32_t tg_end = min(g1, tg + kGroupTile);
+            const uint32_t ts = uniform(v.omegaPtr[tg]);
+            const uint32_t te = uniform(v.omegaPtr[tg_end]);
+            const int count = build_group_list(v, g0, tg, tg_end, ends, wts, lane);
+            if (te > ts) {
+                Cursor cur{0, ends[0], wts[0]};
+                float run = 0.f;
+                const uint32_t a0 = ts & ~(uint32_t)(E - 1);
+                for (uint32_t c0 = a0 + lane * E; c0 < te; c0 += kWave * E * U) {
+                    uint4 q[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const uint32_t c = c0 + u * kWave * E;
+                        if (c < te) q[u] = colI16[c / E];
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const uint32_t c = c0 + u * kWave * E;
+                        if (c < te)
+                            gemv_chunk<IdxT, kXinLds, E>(q[u], c, ts, te, X, xs, cur, run, acc, ends, wts, count,
+                                                         std::make_integer_sequence<int, E>{});
+                    }
+                }
+                acc = fmaf(run, cur.w, acc);
+            }
+            wave_lds_sync();  // the list is rebuilt by the next tile / row
+        }
+        const float y = wave_sum(acc);
+        if (lane == 0) Y[r] = y + t_off;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// batch > 1
+// ------------------------------------------------------------------------------------------------
+
+template <int V> struct Vec;
+template <> struct Vec<1> {
+    float a;
+    __device__ __forceinline__ void zero() { a = 0.f; }
+    __device__ __forceinline__ void add(const Vec& o) { a += o.a; }
+    __device__ __forceinline__ void fma(const Vec& r, float w) { a = fmaf(r.a, w, a); }
+    __device__ __forceinline__ void load(const float* p) { a = *p; }
+    __device__ __forceinline__ void store(float* p) const { *p = a; }
+    __device__ __forceinline__ void xor_add(int off) { a += __shfl_xor(a, off, kWave); }
+    __device__ __forceinline__ void add_scaled(const float* t, float s) { a = fmaf(s, t[0], a); }
+};
+template <> struct Vec<4> {
+    float4 a;
+    __device__ __forceinline__ void zero() { a = make_float4(0.f, 0.f, 0.f, 0.f); }
+    __device__ __forceinline__ void add(const Vec& o) { a.x += o.a.x; a.y += o.a.y; a.z += o.a.z; a.w += o.a.w; }
+    __device__ __forceinline__ void fma(const Vec& r, float w) {
+        a.x = fmaf(r.a.x, w, a.x); a.y = fmaf(r.a.y, w, a.y); a.z = fmaf(r.a.z, w, a.z); a.w = fmaf(r.a.w, w, a.w);
+    }
+    __device__ __forceinline__ void load(const float* p) { a = *reinterpret_cast<const float4*>(p); }
+    __device__ __forceinline__ void store(float* p) const { *reinterpret_cast<float4*>(p) = a; }
+    __device__ __forceinline__ void xor_add(int off) {
+        a.x += __shfl_xor(a.x, off, kWave); a.y += __shfl_xor(a.y, off, kWave);
+        a.z += __shfl_xor(a.z, off, kWave); a.w += __shfl_xor(a.w, off, kWave);
+    }
+    __device__ __forceinline__ void add_scaled(const float* t, float s) {
+        a.x = fmaf(s, t[0], a.x); a.y = fmaf(s, t[1], a.y); a.z = fmaf(s, t[2], a.z); a.w = fmaf(s, t[3], a.w);
+    }
+};
+
+// V floats per lane, P lanes per index: one wave instruction gathers 64/P rows of X, each
+// V.P floats wide.  Workgroup = 4 waves = 4 consecutive rows of one batch tile.
+template <typename IdxT, int V, int P>
+__global__ __launch_bounds__(256) void cer_gemm_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
+                                                       const float* __restrict__ T, uint32_t L, uint32_t ntiles,
+                                                       uint32_t rowblocks, uint32_t items_per_xcd) {
+    constexpr int S = kWave / P;  // indices in flight per wave instruction
+    constexpr int U = 8;          // unroll: gathers in flight per lane
+    constexpr int TW = V * P;     // batch columns per tile
+    __shared__ uint32_t s_ends[4][kGroupTile + 1];
+    __shared__ float s_wts[4][kGroupTile + 1];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Give XCD x the x-th
+    // eighth of the (tile-major) work list, so that an XCD walks through few batch tiles of X.
+    const uint32_t xcd = blockIdx.x & 7u, q = blockIdx.x >> 3;
+    const uint32_t nitems = ntiles * rowblocks;
+    const uint32_t item = xcd * items_per_xcd + q;
+    if (q >= items_per_xcd || item >= nitems) return;
+    const uint32_t tile = item / rowblocks;
+    const uint32_t r = (item - tile * rowblocks) * 4u + wave;
+    if (r >= v.m) return;
+
+    const int sub = lane / P;
+    const uint32_t col0 = tile * TW + (lane % P) * V;
+    const bool active = col0 < L;  // V = 4 requires L % 4 == 0, so a lane is all in or all out
+    const float* xcol = X + col0;
+    const IdxT* colI = static_cast<const IdxT*>(v.colI);
+    uint32_t* ends = s_ends[wave];
+    float* wts = s_wts[wave];
+
+    const uint32_t g0 = uniform(v.rowPtr[r]);
+    const uint32_t g1 = uniform(v.rowPtr[r + 1]);
+    Vec<V> acc;
+    acc.zero();
+    for (uint32_t tg = g0; tg < g1; tg += kGroupTile) {
+        const uint32_t tg_end = min(g1, tg + kGroupTile);
+        const uint32_t ts = uniform(v.omegaPtr[tg]);
+        const uint32_t te = uniform(v.omegaPtr[tg_end]);
+        const int count = build_group_list(v, g0, tg, tg_end, ends, wts, lane);
+        if (te > ts) {
+            Cursor cur{0, ends[0], wts[0]};
+            Vec<V> run;
+            run.zero();
+            for (uint32_t base = ts; base < te; base += S * U) {
+                uint32_t idx[U];
+                Vec<V> xv[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t pos = base + u * S + sub;
+                    idx[u] = pos < te ? (uint32_t)colI[pos] : 0u;
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t pos = base + u * S + sub;
+                    xv[u].zero();
+                    if (active && pos < te) xv[u].load(xcol + (size_t)idx[u] * L);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t pos = base + u * S + sub;
+                    if (pos < te) {
+                        if (pos >= cur.end) {
+                            acc.fma(run, cur.w);
+                            run.zero();
+                            cursor_seek(cur, pos, ends, wts, count);
+                        }
+                        run.add(xv[u]);
+                    }
+                }
+            }
+            acc.fma(run, cur.w);
+        }
+        wave_lds_sync();
+    }
+#pragma unroll
+    for (int off = P; off < kWave; off <<= 1) acc.xor_add(off);
+    if (sub == 0 && active) {
+        if (v.omega0 != 0.f) acc.add_scaled(T + col0, v.omega0);
+        acc.store(Y + (size_t)r * L + col0);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Column sums of X (Appendix A-A1): T[l] = sum_i X[i,l], in two stages of short partial sums.
+// ------------------------------------------------------------------------------------------------
+
+// block (bx, by): columns [bx*CB, +CB), rows [by*slab, +slab).  CB divides 256.
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const float* __restrict__ X, uint32_t n, uint32_t L,
+                                                             uint32_t CB, uint32_t slab, float* __restrict__ part) {
+    __shared__ float red[256];
+    const uint32_t cl = threadIdx.x % CB, rl = threadIdx.x / CB, RPB = 256u / CB;
+    const uint32_t col = blockIdx.x * CB + cl;
+    const uint32_t i0 = blockIdx.y * slab, i1 = min(n, i0 + slab);
+    float a0 = 0.f, a1 = 0.f;
+    if (col < L) {
+        uint32_t i = i0 + rl;
+        for (; i + RPB < i1; i += 2 * RPB) {
+            a0 += X[(size_t)i * L + col];
+            a1 += X[(size_t)(i + RPB) * L + col];
+        }
+        if (i < i1) a0 += X[(size_t)i * L + col];
+    }
+    red[threadIdx.x] = a0 + a1;
+    __syncthreads();
+    for (uint32_t s = RPB >> 1; s > 0; s >>= 1) {
+        if (rl < s) red[threadIdx.x] += red[threadIdx.x + s * CB];
+        __syncthreads();
+    }
+    if (rl == 0 && col < L) part[(size_t)blockIdx.y * L + col] = red[cl];
+}
+
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part, uint32_t nslabs, uint32_t L,
+                                                           float* __restrict__ T) {
+    const uint32_t col = blockIdx.x * 256u + threadIdx.x;
+    if (col >= L) return;
+    float a0 = 0.f, a1 = 0.f;
+    uint32_t s = 0;
+    for (; s + 1 < nslabs; s += 2) {
+        a0 += part[(size_t)s * L + col];
+        a1 += part[(size_t)(s + 1) * L + col];
+    }
+    if (s < nslabs) a0 += part[(size_t)s * L + col];
+    T[col] = a0 + a1;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Dense fp32 baseline (Algorithm 1)
+// ------------------------------------------------------------------------------------------------
+
+// batch = 1: one wave per R rows, 16-byte loads, X read through the caches.
+template <int R>
+__global__ __launch_bounds__(256) void dense_gemv_kernel(const float* __restrict__ W, const float* __restrict__ X,
+                                                         float* __restrict__ Y, uint32_t m, uint32_t n, int vec_ok) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const uint32_t r0 = wave * R;
+    if (r0 >= m) return;
+    float acc[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) acc[k] = 0.f;
+    const float* rows[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) rows[k] = W + (size_t)min(r0 + k, m - 1) * n;
+    uint32_t c = 0;
+    if (vec_ok) {
+        const uint32_t n4 = n >> 2;
+        const float4* X4 = reinterpret_cast<const float4*>(X);
+        for (uint32_t i = lane; i < n4; i += kWave) {
+            const float4 x = X4[i];
+#pragma unroll
+            for (int k = 0; k < R; ++k) {
+                const float4 w = reinterpret_cast<const float4*>(rows[k])[i];
+                acc[k] = fmaf(w.x, x.x, acc[k]); acc[k] = fmaf(w.y, x.y, acc[k]);
+                acc[k] = fmaf(w.z, x.z, acc[k]); acc[k] = fmaf(w.w, x.w, acc[k]);
+            }
+        }
+        c = n4 << 2;
+    }
+    for (uint32_t i = c + lane; i < n; i += kWave) {
+        const float x = X[i];
+#pragma unroll
+        for (int k = 0; k < R; ++k) acc[k] = fmaf(rows[k][i], x, acc[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const float y = wave_sum(acc[k]);
+        if (lane == 0 && r0 + k < m) Y[r0 + k] = y;
+    }
+}
+
+// batch > 1: 64 x 64 output tile per workgroup, 16-deep k-steps through LDS, 4 x 4 outputs per
+// thread with plain v_fma_f32.
+__global__ __launch_bounds__(256) void dense_gemm_kernel(const float* __restrict__ W, const float* __restrict__ X,
+                                                         float* __restrict__ Y, uint32_t m, uint32_t n, uint32_t L) {
+    constexpr int BM = 64, BN = 64, BK = 16;
+    __shared__ float As[BK][BM + 4];
+    __shared__ float Bs[BK][BN + 4];
+    const uint32_t row0 = blockIdx.y * BM, col0 = blockIdx.x * BN;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    float acc[4][4] = {};
+    for (uint32_t k0 = 0; k0 < n; k0 += BK) {
+        // A tile: 64 rows x 16 k; thread loads 4 elements
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int e = threadIdx.x + t * 256;
+            const int rr = e >> 4, kk = e & 15;
+            const uint32_t gr = row0 + rr, gk = k0 + kk;
+            As[kk][rr] = (gr < m && gk < n) ? W[(size_t)gr * n + gk] : 0.f;
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int e = threadIdx.x + t * 256;
+            const int kk = e >> 6, cc = e & 63;
+            const uint32_t gk = k0 + kk, gc = col0 + cc;
+            Bs[kk][cc] = (gk < n && gc < L) ? X[(size_t)gk * L + gc] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BK; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t gr = row0 + ty * 4 + i, gc = col0 + tx * 4 + j;
+            if (gr < m && gc < L) Y[(size_t)gr * L + gc] = acc[i][j];
+        }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Launch logic
+// ------------------------------------------------------------------------------------------------
+
+struct DeviceInfo {
+    int cus = 256;
+    size_t lds_per_block = 64 * 1024;
+};
+
+const DeviceInfo& device_info() {
+    static DeviceInfo info[16];
+    static std::once_flag once[16];
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    if (dev < 0 || dev >= 16) dev = 0;
+    std::call_once(once[dev], [dev] {
+        hipDeviceProp_t p;
+        if (hipGetDeviceProperties(&p, dev) == hipSuccess) {
+            info[dev].cus = p.multiProcessorCount > 0 ? p.multiProcessorCount : 256;
+            info[dev].lds_per_block = p.sharedMemPerBlock;
+            if (p.maxSharedMemoryPerMultiProcessor > info[dev].lds_per_block)
+                info[dev].lds_per_block = p.maxSharedMemoryPerMultiProcessor;
+        }
+    });
+    return info[dev];
+}
+
+KView make_kview(const DeviceView& d) {
+    KView k;
+    k.colI = d.colI; k.omegaPtr = d.omegaPtr; k.rowPtr = d.rowPtr; k.omegaI = d.omegaI; k.omega = d.omega;
+    k.omegaI_bits = d.omegaI_bits; k.cser = d.cser; k.m = (uint32_t)d.m; k.n = (uint32_t)d.n; k.omega0 = d.omega0;
+    return k;
+}
+
+int env_int(const char* name, int fallback) {
+    const char* s = std::getenv(name);
+    return (s && *s) ? std::atoi(s) : fallback;
+}
+
+template <typename IdxT>
+hipError_t launch_gemv(const KView& k, const float* X, float* Y, const float* T, hipStream_t stream) {
+    const DeviceInfo& di = device_info();
+    const size_t x_bytes = (((size_t)k.n + 3) & ~(size_t)3) * sizeof(float);
+    const size_t list_bytes_per_wave = (size_t)(kGroupTile + 1) * 8;
+    // X in LDS if it fits beside the group lists of at least 4 waves
+    const bool x_in_lds = x_bytes + 4 * list_bytes_per_wave <= di.lds_per_block && env_int("CER_GEMV_X_GLOBAL", 0) == 0;
+    int waves = 4;
+    if (x_in_lds && x_bytes > 40 * 1024) {
+        waves = 16;
+        while (waves > 4 && x_bytes + waves * list_bytes_per_wave > di.lds_per_block) waves >>= 1;
+    }
+    waves = env_int("CER_GEMV_WAVES", waves);
+    const size_t lds = (x_in_lds ? x_bytes : 0) + waves * list_bytes_per_wave;
+    // resident workgroups per CU, limited by LDS and by 32 waves per CU
+    size_t per_cu = std::min<size_t>(di.lds_per_block / lds, (size_t)(32 / waves));
+    per_cu = std::max<size_t>(1, std::min<size_t>(per_cu, 8));
+    const uint64_t slots = (uint64_t)di.cus * per_cu;
+    uint32_t iters = (uint32_t)((k.m + slots * waves - 1) / (slots * waves));
+    iters = (uint32_t)env_int("CER_GEMV_ROW_ITERS", (int)std::max<uint32_t>(iters, 1));
+    const uint32_t rows_per_block = iters * waves;
+    const uint32_t blocks = (k.m + rows_per_block - 1) / rows_per_block;
+    const int vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15u) == 0) ? 1 : 0;
+    auto kern = x_in_lds ? cer_gemv_kernel<IdxT, true> : cer_gemv_kernel<IdxT, false>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(waves * kWave), lds, stream, k, X, Y, T, rows_per_block, vec_ok);
+    return hipGetLastError();
+}
+
+template <typename IdxT, int V, int P>
+hipError_t launch_gemm_vp(const KView& k, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream) {
+    constexpr uint32_t TW = V * P;
+    const uint32_t ntiles = (L + TW - 1) / TW;
+    const uint32_t rowblocks = (k.m + 3) / 4;
+    const uint64_t nitems = (uint64_t)ntiles * rowblocks;
+    if (nitems > 0x7FFFFFFFull / 8) return hipErrorInvalidValue;
+    const uint32_t ipx = (uint32_t)((nitems + 7) / 8);
+    hipLaunchKernelGGL((cer_gemm_kernel<IdxT, V, P>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L, ntiles,
+                       rowblocks, ipx);
+    return hipGetLastError();
+}
+
+inline uint32_t pow2_ceil(uint32_t x) {
+    uint32_t p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+template <typename IdxT>
+hipError_t launch_gemm(const KView& k, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream) {
+    const bool vec4 = (L % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15u) == 0) &&
+                      ((reinterpret_cast<uintptr_t>(Y) & 15u) == 0) && ((reinterpret_cast<uintptr_t>(T) & 15u) == 0);
+    if (vec4) {
+        // tile width: all of L up to 64 columns (256 B of one X row), 64 beyond
+        uint32_t tw = std::min<uint32_t>(pow2_ceil(L), 64u);
+        tw = std::max<uint32_t>(tw, 4u);
+        tw = (uint32_t)env_int("CER_GEMM_TILE", (int)tw);
+        switch (tw) {
+            case 4: return launch_gemm_vp<IdxT, 4, 1>(k, X, Y, T, L, stream);
+            case 8: return launch_gemm_vp<IdxT, 4, 2>(k, X, Y, T, L, stream);
+            case 16: return launch_gemm_vp<IdxT, 4, 4>(k, X, Y, T, L, stream);
+            case 32: return launch_gemm_vp<IdxT, 4, 8>(k, X, Y, T, L, stream);
+            case 64: return launch_gemm_vp<IdxT, 4, 16>(k, X, Y, T, L, stream);
+            case 128: return launch_gemm_vp<IdxT, 4, 32>(k, X, Y, T, L, stream);
+            case 256: return launch_gemm_vp<IdxT, 4, 64>(k, X, Y, T, L, stream);
+            default: return hipErrorInvalidValue;
+        }
+    }
+    const uint32_t tw = std::min<uint32_t>(pow2_ceil(L), 64u);
+    switch (tw) {
+        case 1: case 2: return launch_gemm_vp<IdxT, 1, 2>(k, X, Y, T, L, stream);
+        case 4: return launch_gemm_vp<IdxT, 1, 4>(k, X, Y, T, L, stream);
+        case 8: return launch_gemm_vp<IdxT, 1, 8>(k, X, Y, T, L, stream);
+        case 16: return launch_gemm_vp<IdxT, 1, 16>(k, X, Y, T, L, stream);
+        case 32: return launch_gemm_vp<IdxT, 1, 32>(k, X, Y, T, L, stream);
+        default: return launch_gemm_vp<IdxT, 1, 64>(k, X, Y, T, L, stream);
+    }
+}
+
+hipError_t launch_colsum(const float* X, uint32_t n, uint32_t L, float* part, uint32_t nslabs, uint32_t slab,
+                         uint32_t CB, float* T, hipStream_t stream) {
+    const uint32_t coltiles = (L + CB - 1) / CB;
+    hipLaunchKernelGGL(colsum_partial_kernel, dim3(coltiles, nslabs), dim3(256), 0, stream, X, n, L, CB, slab, part);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((L + 255) / 256), dim3(256), 0, stream, part, nslabs, L, T);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, void* stream_v) {
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    if (d.m == 0) return (int)hipSuccess;
+    if (L64 > 0x7FFFFFFFll || d.m > 0x7FFFFFFFll) return (int)hipErrorInvalidValue;
+    const uint32_t L = (uint32_t)L64;
+    const KView k = make_kview(d);
+
+    float* T = nullptr;
+    float* scratch = nullptr;
+    hipError_t e = hipSuccess;
+    if (d.omega0 != 0.f) {
+        // T[l] = sum_i X[i,l] in a stream-ordered temporary: [T: L rounded to 64][partials: nslabs x L]
+        const uint32_t CB = std::min<uint32_t>(256u, pow2_ceil(L));
+        const uint32_t coltiles = (L + CB - 1) / CB;
+        uint32_t nslabs = std::max<uint32_t>(1u, std::min<uint32_t>(((uint32_t)d.n + 255u) / 256u, 1024u / coltiles));
+        nslabs = std::max<uint32_t>(nslabs, 1u);
+        const uint32_t slab = ((uint32_t)d.n + nslabs - 1) / nslabs;
+        const size_t t_floats = ((size_t)L + 63) & ~(size_t)63;
+        e = hipMallocAsync(reinterpret_cast<void**>(&scratch), (t_floats + (size_t)nslabs * L) * sizeof(float), stream);
+        if (e != hipSuccess) return (int)e;
+        T = scratch;
+        e = launch_colsum(X, (uint32_t)d.n, L, scratch + t_floats, nslabs, std::max<uint32_t>(slab, 1u), CB, T, stream);
+        if (e != hipSuccess) {
+            (void)hipFreeAsync(scratch, stream);
+            return (int)e;
+        }
+    }
+    if (L == 1) {
+        switch (d.colI_bits) {
+            case 8: e = launch_gemv<uint8_t>(k, X, Y, T, stream); break;
+            case 16: e = launch_gemv<uint16_t>(k, X, Y, T, stream); break;
+            default: e = launch_gemv<uint32_t>(k, X, Y, T, stream); break;
+        }
+    } else {
+        switch (d.colI_bits) {
+            case 8: e = launch_gemm<uint8_t>(k, X, Y, T, L, stream); break;
+            case 16: e = launch_gemm<uint16_t>(k, X, Y, T, L, stream); break;
+            default: e = launch_gemm<uint32_t>(k, X, Y, T, L, stream); break;
+        }
+    }
+    if (scratch) {
+        hipError_t f = hipFreeAsync(scratch, stream);
+        if (e == hipSuccess) e = f;
+    }
+    return (int)e;
+}
+
+int launch_dense(const float* W, const float* X, float* Y, int64_t m, int64_t n, int64_t L, void* stream_v) {
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    if (m == 0) return (int)hipSuccess;
+    if (m > 0x7FFFFFFFll || n > 0x7FFFFFFFll || L > 0x7FFFFFFFll) return (int)hipErrorInvalidValue;
+    if (L == 1) {
+        constexpr int R = 2;
+        const int vec_ok = (n % 4 == 0) && ((reinterpret_cast<uintptr_t>(W) & 15u) == 0) &&
+                           ((reinterpret_cast<uintptr_t>(X) & 15u) == 0);
+        const uint32_t waves = (uint32_t)((m + R - 1) / R);
+        hipLaunchKernelGGL(dense_gemv_kernel<R>, dim3((waves + 3) / 4), dim3(256), 0, stream, W, X, Y, (uint32_t)m,
+                           (uint32_t)n, vec_ok);
+    } else {
+        hipLaunchKernelGGL(dense_gemm_kernel, dim3((uint32_t)((L + 63) / 64), (uint32_t)((m + 63) / 64)), dim3(256), 0,
+                           stream, W, X, Y, (uint32_t)m, (uint32_t)n, (uint32_t)L);
+    }
+    return (int)hipGetLastError();
+}
+
+}  // namespace cer

@@ -1,0 +1,198 @@
+"""GPU parity: the HIP path, called through the C ABI binding, against the CPU oracle on the same
+seeded inputs.  Integer arrays were already compared bit for bit on the host; here Y is compared
+element by element under the bound  |Y - Y_oracle| <= 1e-5 * sum_c |W[r,c]| |X[c,l]|  (fp32 sums in
+another order than the oracle's fp64 loop)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1805_10692_amd import binding as B
+from paper_1805_10692_amd import workloads as wl
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+def _gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: GPU parity tests need a real MI355X")
+    return torch.device("cuda:0")
+
+
+def run_matmul(fmt, W, codebook, X, stream=None):
+    dev = _gpu()
+    h = (B.cer_encode if fmt == "cer" else B.cser_encode)(W, codebook)
+    Xd = torch.from_numpy(np.ascontiguousarray(X)).to(dev)
+    Yd = torch.full((W.shape[0], X.shape[1]), float("nan"), dtype=torch.float32, device=dev)
+    (B.cer_matmul if fmt == "cer" else B.cser_matmul)(h, Xd, Yd, X.shape[1], stream)
+    torch.cuda.synchronize()
+    Y = Yd.cpu().numpy()
+    B.cer_free(h)
+    return Y
+
+
+def check(Y, want, scale, what):
+    assert Y.shape == want.shape, what
+    assert np.isfinite(Y).all(), f"{what}: non-finite output (unwritten element?)"
+    err = np.abs(Y.astype(np.float64) - want)
+    bad = err > TOL * scale
+    assert not bad.any(), (f"{what}: {int(bad.sum())} elements beyond tolerance; worst ratio "
+                           f"{float((err / np.maximum(scale, 1e-300)).max()):.3e} at {np.argwhere(bad)[:4].tolist()}")
+
+
+def full_check(w, fmts=("cer", "cser")):
+    print(f"case {w.name} m={w.m} n={w.n} L={w.L}", flush=True)
+    scale = oracle.abs_dot_dense(w.W, w.X, threads=8)
+    for fmt in fmts:
+        A = oracle.encode(w.W, w.codebook, fmt)
+        want = oracle.dot(A, w.X, threads=8)
+        Y = run_matmul(fmt, w.W, w.codebook, w.X)
+        check(Y, want, scale, f"{w.name}/{fmt}")
+
+
+SMALL = {
+    "c1": lambda: wl.config1(),
+    "alexnet_s8_L32": lambda: wl.alexnet_fc6(L=32, scale=8),
+    "vgg_s8_L1": lambda: wl.vgg_fc6(L=1, scale=8),
+    "vgg_s8_L64": lambda: wl.vgg_fc6(L=64, scale=8),
+    "sweep_K256_p99": lambda: wl.sweep_cell(256, 0.99, L=16, scale=4),
+    "sweep_K256_p50": lambda: wl.sweep_cell(256, 0.5, L=16, scale=4),
+    "sweep_K2_p70": lambda: wl.sweep_cell(2, 0.7, L=16, scale=4),
+    "sweep_K64_p90_L1": lambda: wl.sweep_cell(64, 0.9, L=1, scale=4),
+    "conv_s4_L200": lambda: wl.conv3x3(L=200, scale=4),
+    "conv_s4_dom_L200": lambda: wl.conv3x3(L=200, nonzero_dominant=True, scale=4),
+    "conv_s4_dom_L1": lambda: wl.conv3x3(L=1, nonzero_dominant=True, scale=4),
+    "conv_s4_dom_L7": lambda: wl.conv3x3(L=7, nonzero_dominant=True, scale=4),
+    "u8_index": lambda: wl.random_lowentropy(m=70, n=250, K=6, p_dom=0.6, L=1, seed=31),
+    "u8_index_L12": lambda: wl.random_lowentropy(m=70, n=250, K=6, p_dom=0.6, L=12, seed=32),
+    "u32_index_L1": lambda: wl.random_lowentropy(m=9, n=70001, K=8, p_dom=0.9, L=1, seed=33),   # X too big for LDS
+    "u32_index_L5": lambda: wl.random_lowentropy(m=9, n=70001, K=8, p_dom=0.9, L=5, seed=34),
+    "lds_edge": lambda: wl.random_lowentropy(m=33, n=38000, K=8, p_dom=0.95, L=1, seed=35),
+    "one_row": lambda: wl.random_lowentropy(m=1, n=3000, K=16, p_dom=0.7, L=1, seed=36),
+    "one_col": lambda: wl.random_lowentropy(m=300, n=1, K=3, p_dom=0.5, L=4, seed=37),
+    "constant": lambda: wl.random_lowentropy(m=10, n=100, K=1, p_dom=1.0, L=3, seed=38),
+    "many_groups": lambda: wl.random_lowentropy(m=40, n=9000, K=700, p_dom=0.3, L=1, seed=39, ratio=0.995),
+    "many_groups_L8": lambda: wl.random_lowentropy(m=40, n=9000, K=700, p_dom=0.3, L=8, seed=40, ratio=0.995),
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_small_cases_all_elements(name):
+    full_check(SMALL[name]())
+
+
+@pytest.mark.parametrize("L", [2, 3, 4, 5, 16, 17, 33, 63, 64, 65, 100, 256, 260, 516])
+def test_ragged_batch_widths(L):
+    full_check(wl.random_lowentropy(m=67, n=1500, K=16, p_dom=0.8, L=L, seed=100 + L))
+
+
+def test_rows_without_entries_and_unaligned_pointers():
+    w = wl.random_lowentropy(m=50, n=777, K=8, p_dom=0.9, L=4, seed=41)
+    w.W[::3] = w.W[0, 0] * 0 + w.codebook[4]            # every third row holds only the dominant value
+    dev = _gpu()
+    scale = oracle.abs_dot_dense(w.W, w.X)
+    for fmt in ("cer", "cser"):
+        want = oracle.dot(oracle.encode(w.W, w.codebook, fmt), w.X)
+        check(run_matmul(fmt, w.W, w.codebook, w.X), want, scale, f"empty rows/{fmt}")
+    # X and Y at addresses that are only 4-byte aligned (vector paths must not be taken)
+    for L in (1, 4):
+        X = w.X[:, :L].copy()
+        h = B.cer_encode(w.W, w.codebook)
+        Xbuf = torch.zeros(X.size + 1, dtype=torch.float32, device=dev)
+        Ybuf = torch.full((w.m * L + 1,), float("nan"), dtype=torch.float32, device=dev)
+        Xbuf[1:] = torch.from_numpy(X.reshape(-1)).to(dev)
+        B.cer_matmul(h, Xbuf.data_ptr() + 4, Ybuf.data_ptr() + 4, L)
+        torch.cuda.synchronize()
+        want = oracle.dot(oracle.encode(w.W, w.codebook, "cer"), X)
+        check(Ybuf[1:].cpu().numpy().reshape(w.m, L), want, oracle.abs_dot_dense(w.W, X), f"unaligned L={L}")
+        assert torch.isnan(Ybuf[0])
+        B.cer_free(h)
+
+
+def test_worked_example_on_the_gpu(example):
+    M = example["M"].astype(np.float32)
+    X = np.arange(1, 25, dtype=np.float32).reshape(12, 2)
+    want = example["M"] @ X.astype(np.float64)
+    for fmt in ("cer", "cser"):
+        Y = run_matmul(fmt, M, np.array([0, 2, 3, 4], np.float32), X)
+        assert np.array_equal(Y.astype(np.float64), want)       # small integers: exact in fp32
+
+
+def test_side_stream_and_handle_reuse():
+    dev = _gpu()
+    w = wl.vgg_fc6(L=1, scale=16)
+    A = oracle.encode(w.W, w.codebook, "cer")
+    h = B.cer_encode(w.W, w.codebook)
+    h2 = B.cer_clone_device(h)
+    s = torch.cuda.Stream()
+    outs = []
+    for k in range(3):
+        X = wl.sample_X(np.random.default_rng(k), w.n, 1)
+        Xd = torch.from_numpy(X).to(dev)
+        Yd = torch.empty((w.m, 1), dtype=torch.float32, device=dev)
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            B.cer_matmul(h if k % 2 == 0 else h2, Xd, Yd, 1)        # picks up the current (side) stream
+        outs.append((X, Xd, Yd))
+    s.synchronize()
+    for X, _, Yd in outs:
+        check(Yd.cpu().numpy(), oracle.dot(A, X), oracle.abs_dot_dense(w.W, X), "side stream")
+    assert B.cer_device_bytes(h) == A.nnz * 2 + (A.G + 1) * 4 + (A.m + 1) * 4 + A.K * 4
+    B.cer_free(h)
+    B.cer_free(h2)
+
+
+@pytest.mark.parametrize("shape", [(64, 256, 1), (67, 1500, 1), (130, 999, 1), (67, 1500, 5), (200, 700, 64), (129, 515, 100)])
+def test_dense_baseline(shape):
+    dev = _gpu()
+    m, n, L = shape
+    w = wl.random_lowentropy(m=m, n=n, K=16, p_dom=0.3, L=L, seed=77)
+    Wd, Xd = torch.from_numpy(w.W).to(dev), torch.from_numpy(w.X).to(dev)
+    Yd = torch.full((m, L), float("nan"), dtype=torch.float32, device=dev)
+    B.dense_matmul(Wd, Xd, Yd, m, n, L)
+    torch.cuda.synchronize()
+    check(Yd.cpu().numpy(), oracle.dot_dense(w.W, w.X), oracle.abs_dot_dense(w.W, w.X), f"dense {shape}")
+
+
+# ------------------------------------------------------------------ full sizes of the named workloads
+
+def sampled_check(w, fmts, rows):
+    """Full-size run on the GPU; the oracle recomputes a sample of output rows (all batch columns)."""
+    print(f"case {w.name} m={w.m} n={w.n} L={w.L} sampled rows={len(rows)}", flush=True)
+    Wr = np.ascontiguousarray(w.W[rows])
+    want = oracle.dot_dense(Wr, w.X, threads=8)
+    scale = oracle.abs_dot_dense(Wr, w.X, threads=8)
+    for fmt in fmts:
+        Y = run_matmul(fmt, w.W, w.codebook, w.X)
+        assert np.isfinite(Y).all()
+        check(Y[rows], want, scale, f"{w.name}/{fmt}")
+
+
+def test_full_vgg_fc6_gemv_all_outputs():
+    full_check(wl.vgg_fc6(L=1))
+
+
+def test_full_vgg_fc6_batch64_sampled():
+    w = wl.vgg_fc6(L=64)
+    rows = np.random.default_rng(0).choice(w.m, 96, replace=False)
+    sampled_check(w, ("cer", "cser"), np.sort(rows))
+
+
+def test_full_alexnet_fc6_batch32_sampled():
+    w = wl.alexnet_fc6(L=32)
+    rows = np.random.default_rng(1).choice(w.m, 96, replace=False)
+    sampled_check(w, ("cer", "cser"), np.sort(rows))
+
+
+@pytest.mark.parametrize("K,p0", [(256, 0.99), (16, 0.9)])
+def test_full_sweep_cells_all_outputs(K, p0):
+    full_check(wl.sweep_cell(K, p0))
+
+
+@pytest.mark.parametrize("variant", [False, True])
+def test_full_conv_batch3136_sampled(variant):
+    w = wl.conv3x3(nonzero_dominant=variant)
+    rows = np.random.default_rng(2).choice(w.m, 6, replace=False)
+    sampled_check(w, ("cer", "cser"), np.sort(rows))

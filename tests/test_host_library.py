@@ -1,0 +1,126 @@
+"""Host logic of the HIP library, checked on the CPU (no GPU calls): the library's own encoder
+against the oracle array by array and bit by bit, decode round trips, storage bits, error codes,
+and that the built library exports every symbol the header declares."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1805_10692_amd import binding as B
+from paper_1805_10692_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "cer.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b((?:cer|cser|dense)_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert B.lib().cer_strerror(B.CER_E_FORMAT).decode().startswith("handle")
+
+
+def _compare(h, A):
+    d = B.cer_get_dims(h)
+    assert (d["m"], d["n"], d["K"], d["nnz"], d["groups"]) == (A.m, A.n, A.K, A.nnz, A.G)
+    assert d["is_cser"] == int(A.fmt == "cser")
+    omega = B.cer_get_array(h, B.CER_ARRAY_OMEGA)
+    assert omega.dtype == np.float32 and omega.tobytes() == A.omega.tobytes()
+    assert np.array_equal(B.cer_get_array(h, B.CER_ARRAY_COUNT), A.count)
+    bits = oracle.array_bits(A)
+    for which, name in ((B.CER_ARRAY_COLI, "colI"), (B.CER_ARRAY_OMEGAPTR, "omegaPtr"), (B.CER_ARRAY_ROWPTR, "rowPtr")):
+        got = B.cer_get_array(h, which)
+        assert got.dtype.itemsize * 8 == bits[name], name
+        assert np.array_equal(got.astype(np.int64), getattr(A, name)), name
+    oi = B.cer_get_array(h, B.CER_ARRAY_OMEGAI)
+    if A.fmt == "cser":
+        assert oi.dtype.itemsize * 8 == bits["omegaI"]
+        assert np.array_equal(oi.astype(np.int64), A.omegaI)
+    else:
+        assert len(oi) == 0
+    assert B.cer_storage_bits(h) == oracle.storage_bits(A)
+    st, so = B.cer_get_stats(h), oracle.stats(A)
+    for k in ("H", "p0", "k_bar", "k_tilde"):
+        assert st[k] == pytest.approx(so[k], rel=1e-12, abs=1e-15)
+
+
+WORKLOADS = [
+    lambda: wl.config1(),
+    lambda: wl.alexnet_fc6(L=2, scale=16),
+    lambda: wl.vgg_fc6(L=1, scale=16),
+    lambda: wl.sweep_cell(256, 0.99, scale=8),
+    lambda: wl.sweep_cell(256, 0.5, scale=8),
+    lambda: wl.sweep_cell(2, 0.7, scale=8),
+    lambda: wl.conv3x3(L=3, scale=4),
+    lambda: wl.conv3x3(L=3, nonzero_dominant=True, scale=4),
+    lambda: wl.random_lowentropy(m=7, n=200, K=5, p_dom=0.5, L=1, seed=5),      # n <= 256: 8-bit colI
+    lambda: wl.random_lowentropy(m=3, n=70000, K=4, p_dom=0.9, L=1, seed=6),    # n > 65536: 32-bit colI
+    lambda: wl.random_lowentropy(m=5, n=40, K=1, p_dom=1.0, L=1, seed=7),       # constant matrix
+]
+
+
+@pytest.mark.parametrize("make", WORKLOADS, ids=[str(i) for i in range(len(WORKLOADS))])
+def test_encoder_matches_oracle_bit_exact(make):
+    w = make()
+    for fmt, enc, dec in (("cer", B.cer_encode, B.cer_decode), ("cser", B.cser_encode, B.cser_decode)):
+        h = enc(w.W, w.codebook)
+        _compare(h, oracle.encode(w.W, w.codebook, fmt))
+        assert dec(h).tobytes() == w.W.tobytes()
+        B.cer_free(h)
+
+
+def test_worked_example_through_the_library(example):
+    M = example["M"].astype(np.float32)
+    h = B.cer_encode(M, np.array([0, 2, 3, 4], np.float32))
+    assert B.cer_get_array(h, B.CER_ARRAY_OMEGA).tolist() == example["cer_Omega"].tolist()
+    assert B.cer_get_array(h, B.CER_ARRAY_COLI).tolist() == example["cer_colI"].tolist()
+    assert B.cer_get_array(h, B.CER_ARRAY_OMEGAPTR).tolist() == example["cer_OmegaPtr"].tolist()
+    assert B.cer_get_array(h, B.CER_ARRAY_ROWPTR).tolist() == example["cer_rowPtr"].tolist()
+    entries = sum(len(B.cer_get_array(h, a)) for a in (B.CER_ARRAY_OMEGA, B.CER_ARRAY_COLI, B.CER_ARRAY_OMEGAPTR,
+                                                       B.CER_ARRAY_ROWPTR))
+    assert entries == 49
+    hs = B.cser_encode(M, np.array([0, 2, 3, 4], np.float32))
+    om = B.cer_get_array(hs, B.CER_ARRAY_OMEGA)
+    assert om[B.cer_get_array(hs, B.CER_ARRAY_OMEGAI)].tolist() == [4, 3, 2, 4, 4, 3, 2, 4, 3, 4]
+    assert entries + len(B.cer_get_array(hs, B.CER_ARRAY_OMEGAI)) == 59
+
+
+def test_edge_cases_and_errors():
+    cb = np.array([0.0, 1.0, 2.0], np.float32)
+    # empty matrices
+    for shape in ((0, 5), (4, 0), (0, 0)):
+        h = B.cer_encode(np.zeros(shape, np.float32), cb)
+        d = B.cer_get_dims(h)
+        assert d["nnz"] == 0 and d["groups"] == 0
+        assert B.cer_get_array(h, B.CER_ARRAY_ROWPTR).tolist() == [0] * (shape[0] + 1)
+        assert B.cer_decode(h).shape == shape
+    W = np.array([[0, 1, 2], [2, 2, 0]], np.float32)
+    with pytest.raises(B.CerError) as e:
+        B.cer_encode(W, np.array([0.0, 1.0], np.float32))
+    assert e.value.code == B.CER_E_NOT_IN_CODEBOOK
+    with pytest.raises(B.CerError) as e:
+        B.cer_encode(W, np.array([0.0, 1.0, 2.0, 1.0], np.float32))
+    assert e.value.code == B.CER_E_BAD_CODEBOOK
+    with pytest.raises(B.CerError) as e:
+        B.cser_encode(W, np.array([0.0, 1.0, 2.0, np.inf], np.float32))
+    assert e.value.code == B.CER_E_BAD_CODEBOOK
+    # -0.0 is +0.0
+    h = B.cer_encode(np.array([[-0.0, 1.0, 0.0]], np.float32), np.array([-0.0, 1.0], np.float32))
+    assert not np.signbit(B.cer_decode(h)).any()
+    # format mismatch and null checks never reach the GPU
+    with pytest.raises(B.CerError) as e:
+        B.cser_decode(h)
+    assert e.value.code == B.CER_E_FORMAT
+    assert B.lib().cser_matmul(h.ptr, 16, 16, 1, None) == B.CER_E_FORMAT
+    assert B.lib().cer_matmul(h.ptr, None, 16, 1, None) == B.CER_E_INVALID
+    assert B.lib().cer_matmul(h.ptr, 16, 16, 0, None) == B.CER_E_INVALID
+    assert B.lib().cer_matmul(None, 16, 16, 1, None) == B.CER_E_INVALID
+    assert B.lib().dense_matmul(16, 16, None, 2, 2, 1, None) == B.CER_E_INVALID
+    assert B.lib().cer_get_array(h.ptr, 99, None, None, None) == B.CER_E_INVALID
+    B.cer_free(h)
+    B.cer_free(h)  # second free of the wrapper is a no-op
