@@ -1,0 +1,283 @@
+#!/usr/bin/env python3
+"""Benchmark of the CER / CSER product Y = W.X on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--format cer|cser]
+                    [--warm] [--report PATH --all]
+
+A step is one call of cer_matmul / cser_matmul (the whole hot path: group lists, index stream,
+gather-add, one multiply per group, cross-lane reduction, output write) on inputs that already
+reside in device memory.  By default successive steps rotate over R independent device copies of
+the encoded matrix, R chosen so that the copies exceed twice the 256 MB last-level cache: every
+step then streams its arrays from HBM ("cold").  --warm reuses one copy (cache-resident numbers).
+
+Prints ONE JSON line on stdout; --report writes a table over several workloads to a file.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+LAST_LEVEL_CACHE_BYTES = 256 << 20
+
+METRIC = "CER/CSER W.X dense-equiv GFLOP/s and achieved HBM GB/s (% of peak) vs dense HIP"
+
+
+def make_workload(name: str):
+    from paper_1805_10692_amd import workloads as wl
+    if name == "vgg_fc6_L1":
+        return wl.vgg_fc6(L=1)
+    if name == "vgg_fc6_L64":
+        return wl.vgg_fc6(L=64)
+    if name == "alexnet_fc6_L32":
+        return wl.alexnet_fc6(L=32)
+    if name == "alexnet_fc6_L1":
+        return wl.alexnet_fc6(L=1)
+    if name == "conv3x3_L3136":
+        return wl.conv3x3()
+    if name == "conv3x3_dom_L3136":
+        return wl.conv3x3(nonzero_dominant=True)
+    if name == "c1":
+        return wl.config1()
+    m = re.fullmatch(r"sweep_K(\d+)_p([0-9.]+)(?:_L(\d+))?", name)
+    if m:
+        return wl.sweep_cell(int(m.group(1)), float(m.group(2)), L=int(m.group(3) or 16))
+    raise SystemExit(f"unknown workload {name}")
+
+
+def algorithmic_bytes(dims: dict, bits: dict, L: int) -> int:
+    """Bytes the method itself must move per product: every format array once at its stored width
+    (pointer arrays counted as 32-bit, the width the device copy uses), X once, Y once."""
+    b = dims["nnz"] * bits["colI"] // 8 + 4 * (dims["groups"] + 1) + 4 * (dims["m"] + 1) + 4 * dims["K"]
+    if dims["is_cser"]:
+        b += dims["groups"] * bits["omegaI"] // 8
+    return b + 4 * dims["n"] * L + 4 * dims["m"] * L
+
+
+def read_traffic(workload: str, fmt: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{fmt}_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    txt = open(path).read()
+    f = re.search(r"^fetch_bytes_per_launch:\s*([0-9.eE+]+)", txt, re.M)
+    w = re.search(r"^write_bytes_per_launch:\s*([0-9.eE+]+)", txt, re.M)
+    if not f or not w:
+        return None
+    return float(f.group(1)) + float(w.group(1))
+
+
+def time_steps(fn, steps: int, warmup: int):
+    """(wall ms per step, HIP-event ms per step) over exactly `steps` calls after `warmup` calls."""
+    import torch
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: bool, with_dense: bool) -> dict:
+    import torch
+
+    import oracle
+    from paper_1805_10692_amd import binding as B
+
+    dev = torch.device("cuda:0")
+    w = make_workload(name)
+    enc, mm = (B.cer_encode, B.cer_matmul) if fmt == "cer" else (B.cser_encode, B.cser_matmul)
+    h0 = enc(w.W, w.codebook)
+    dims, stats = B.cer_get_dims(h0), B.cer_get_stats(h0)
+    bits = {"colI": B.cer_get_array(h0, B.CER_ARRAY_COLI).dtype.itemsize * 8,
+            "omegaI": B.cer_get_array(h0, B.CER_ARRAY_OMEGAI).dtype.itemsize * 8}
+    L = w.L
+    alg_bytes = algorithmic_bytes(dims, bits, L)
+    fmt_bytes = B.cer_device_bytes(h0)
+
+    Xd = torch.from_numpy(w.X).to(dev)
+    Yd = torch.empty((w.m, L), dtype=torch.float32, device=dev)
+
+    # parity on the buffers that are timed (sampled rows at full size)
+    rows = np.sort(np.random.default_rng(0).choice(w.m, min(w.m, 32 if L > 256 else 128), replace=False))
+    Wr = np.ascontiguousarray(w.W[rows])
+    want, scale = oracle.dot_dense(Wr, w.X, threads=8), oracle.abs_dot_dense(Wr, w.X, threads=8)
+    mm(h0, Xd, Yd, L)
+    torch.cuda.synchronize()
+    err = np.abs(Yd.cpu().numpy()[rows].astype(np.float64) - want)
+    if not (err <= 1e-5 * scale).all():
+        raise SystemExit(f"parity check failed on {name}/{fmt}: max err {err.max():.3e}")
+
+    # cold rotation: enough device copies to exceed twice the last-level cache
+    R = 1 if warm else max(2, -(-2 * LAST_LEVEL_CACHE_BYTES // max(fmt_bytes, 1)))
+    R = min(R, 256)
+    handles = [h0] + [B.cer_clone_device(h0) for _ in range(R - 1)]
+    stream = torch.cuda.current_stream().cuda_stream
+    lib = B.lib()
+    cfn = lib.cer_matmul if fmt == "cer" else lib.cser_matmul
+    ptrs = [h.ptr for h in handles]
+    xp, yp = Xd.data_ptr(), Yd.data_ptr()
+
+    def step(i):
+        rc = cfn(ptrs[i % R], xp, yp, L, stream)
+        if rc != 0:
+            raise SystemExit(f"matmul failed: {rc}")
+
+    wall_ms, ev_ms = time_steps(step, steps, warmup)
+    flops = 2.0 * w.m * w.n * L
+    out = {
+        "workload": name, "format": fmt, "m": w.m, "n": w.n, "L": L, "K": dims["K"], "nnz": dims["nnz"],
+        "groups": dims["groups"], "H_bits": round(stats["H"], 4), "p0": round(stats["p0"], 5),
+        "k_bar": round(stats["k_bar"], 3), "k_tilde": round(stats["k_tilde"], 3),
+        "cache_state": "warm (one copy)" if warm else f"cold (rotation over {R} device copies)",
+        "ms_per_step": wall_ms, "event_ms_per_step": ev_ms,
+        "dense_equiv_gflops": flops / (wall_ms * 1e-3) / 1e9,
+        "algorithmic_bytes": alg_bytes, "format_bytes": fmt_bytes,
+        "algorithmic_GBps": alg_bytes / (ev_ms * 1e-3) / 1e9,
+        "gather_GBps_onchip": dims["nnz"] * 4.0 * L / (ev_ms * 1e-3) / 1e9,
+        "dense_bytes": 4 * (w.m * w.n + w.n * L + w.m * L),
+    }
+    for h in handles[1:]:
+        B.cer_free(h)
+
+    if with_dense:
+        Wd = torch.from_numpy(w.W).to(dev)
+        Yd2 = torch.empty_like(Yd)
+        B.dense_matmul(Wd, Xd, Yd2, w.m, w.n, L)
+        torch.cuda.synchronize()
+        derr = np.abs(Yd2.cpu().numpy()[rows].astype(np.float64) - want)
+        if not (derr <= 1e-5 * scale).all():
+            raise SystemExit(f"dense baseline parity failed on {name}: {derr.max():.3e}")
+        wp = Wd.data_ptr()
+        y2 = Yd2.data_ptr()
+
+        def dstep(i):
+            rc = lib.dense_matmul(wp, xp, y2, w.m, w.n, L, stream)
+            if rc != 0:
+                raise SystemExit(f"dense_matmul failed: {rc}")
+
+        dsteps = max(5, min(steps, int(0.5e3 / max(out["dense_bytes"] / 4e9, 1e-3))))  # about 0.5 s at 4 TB/s
+        d_wall, d_ev = time_steps(dstep, dsteps, max(2, min(warmup, dsteps // 5)))
+        out["dense_hip"] = {"ms_per_step": d_wall, "event_ms_per_step": d_ev, "steps": dsteps,
+                            "gflops": flops / (d_wall * 1e-3) / 1e9,
+                            "GBps": out["dense_bytes"] / (d_ev * 1e-3) / 1e9}
+        # rocBLAS through torch, as a cross-check that the in-house dense kernel is not a straw man
+        for _ in range(3):
+            torch.matmul(Wd, Xd, out=Yd2)
+        t_wall, t_ev = time_steps(lambda i: torch.matmul(Wd, Xd, out=Yd2), dsteps, 2)
+        out["dense_rocblas_ms_per_step"] = t_wall
+        out["speedup_vs_dense_hip"] = d_wall / wall_ms
+        out["speedup_vs_dense_rocblas"] = t_wall / wall_ms
+        del Wd
+
+    if with_cpu:
+        A = oracle.encode(w.W, w.codebook, fmt)
+        cores = min(len(os.sched_getaffinity(0)), 16)
+        cpu = {}
+        for label, th in (("1", 1), (str(cores), cores)):
+            reps, t_used = 0, 0.0
+            budget = 8.0
+            while t_used < budget and reps < 200:
+                t0 = time.perf_counter()
+                oracle.dot(A, w.X, threads=th)
+                t_used += time.perf_counter() - t0
+                reps += 1
+            cpu[label] = t_used / reps
+        t0 = time.perf_counter()
+        oracle.dot_dense(w.W, w.X, threads=cores)
+        t_dense = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": flops / cpu[str(cores)] / 1e9, "unit": "GFLOP/s (dense-equivalent)", "cores": cores,
+            "kind": "oracle",
+            "sample": f"whole {name} product ({fmt}), group-sum oracle with fp64 sums, mean over repeats within 8 s",
+            "ms_per_step": cpu[str(cores)] * 1e3, "single_thread_ms_per_step": cpu["1"] * 1e3,
+            "oracle_dense_ms_per_step": t_dense * 1e3,
+            "cpu_speedup_over_dense_oracle": t_dense / cpu[str(cores)],
+        }
+    B.cer_free(h0)
+    return out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="vgg_fc6_L1")
+    ap.add_argument("--format", default="cer", choices=("cer", "cser"))
+    ap.add_argument("--warm", action="store_true", help="reuse one device copy (cache-resident)")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--report", default=None, help="write a table over workloads/formats to this JSON file")
+    ap.add_argument("--all", action="store_true", help="with --report: all named workloads and the entropy sweep")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU; this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
+        return 2
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+
+    r = run_one(args.workload, args.format, args.steps, args.warmup, args.warm, not args.no_cpu, not args.no_dense)
+    traffic = read_traffic(args.workload, args.format)
+    line = {
+        "metric": METRIC, "value": r["dense_equiv_gflops"], "unit": "GFLOP/s (dense-equivalent, 2*m*n*L/t)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {k: r[k] for k in ("workload", "format", "m", "n", "L", "K", "nnz", "groups", "H_bits", "p0",
+                                     "k_bar", "k_tilde", "cache_state")},
+        "roofline": {"bound": "hbm", "achieved": r["algorithmic_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": r["algorithmic_GBps"] / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "cer_gemv_kernel" if r["L"] == 1 else "cer_gemm_kernel",
+                     "algorithmic_bytes_per_launch": r["algorithmic_bytes"],
+                     "event_us_per_launch": r["event_ms_per_step"] * 1e3},
+        "cpu_baseline": r.get("cpu_baseline"),
+        "dense_hip": r.get("dense_hip"),
+        "speedup_vs_dense_hip": r.get("speedup_vs_dense_hip"),
+        "speedup_vs_dense_rocblas": r.get("speedup_vs_dense_rocblas"),
+        "hbm_frac_of_peak": r["algorithmic_GBps"] / HBM_PEAK_GBS,
+    }
+    print(json.dumps(line), flush=True)
+
+    if args.report:
+        names = ["vgg_fc6_L1", "vgg_fc6_L64", "alexnet_fc6_L32", "c1"]
+        if args.all:
+            from paper_1805_10692_amd import workloads as wl
+            names += ["conv3x3_L3136", "conv3x3_dom_L3136"]
+            names += [f"sweep_K{K}_p{p0}" for K in wl.SWEEP_K for p0 in wl.SWEEP_P0]
+        table = []
+        for nm in names:
+            for fmt in ("cer", "cser"):
+                for warm in (False, True):
+                    big = nm.startswith("conv")
+                    rr = run_one(nm, fmt, 20 if big else 300, 3 if big else 30, warm, False, not warm)
+                    table.append(rr)
+                    print(f"[report] {nm} {fmt} {'warm' if warm else 'cold'}: {rr['ms_per_step'] * 1e3:.2f} us/step, "
+                          f"{rr['algorithmic_GBps']:.0f} GB/s alg, speedup vs dense "
+                          f"{rr.get('speedup_vs_dense_hip', float('nan')):.2f}", file=sys.stderr, flush=True)
+        os.makedirs(os.path.dirname(os.path.abspath(args.report)), exist_ok=True)
+        with open(args.report, "w") as f:
+            json.dump(table, f, indent=1)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
