@@ -14,7 +14,8 @@ import os
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libcer_hip.so")
+# CER_HIP_LIB selects another build of the same library (e.g. one compiled with other tuning constants)
+LIB_PATH = os.environ.get("CER_HIP_LIB") or os.path.join(_PKG, "libcer_hip.so")
 
 CER_OK = 0
 CER_E_INVALID = -1

@@ -25,7 +25,9 @@ std::vector<uint32_t> widen(const cer::HostArray& a) {
     return out;
 }
 
-// One allocation: [colI | 64 B pad][OmegaPtr u32][rowPtr u32][OmegaI][Omega], each 256-byte aligned.
+// One allocation: [colI | 8 KiB pad][OmegaPtr u32][rowPtr u32][OmegaI][Omega][row descriptors], each 256-byte
+// aligned.  The row descriptors {rowPtr[r], OmegaPtr[rowPtr[r]]} are derived from the format arrays: they let a
+// wave find its row's slice of colI with one load instead of two dependent ones.
 int upload(cer_matrix* h) {
     const cer::HostMatrix& A = *h->host;
     int ndev = 0;
@@ -40,11 +42,12 @@ int upload(cer_matrix* h) {
 
     const size_t colI_bytes = A.colI.bytes.size();
     const size_t off_colI = 0;
-    const size_t off_optr = align_up(off_colI + colI_bytes + 64, 256);
+    const size_t off_optr = align_up(off_colI + colI_bytes + 8192, 256);  // the product reads ahead of a row's end
     const size_t off_rptr = align_up(off_optr + (size_t)(A.G + 1) * 4 + 16, 256);
     const size_t off_oi = align_up(off_rptr + (size_t)(A.m + 1) * 4 + 16, 256);
     const size_t off_om = align_up(off_oi + A.omegaI.bytes.size() + 16, 256);
-    const size_t total = align_up(off_om + (size_t)std::max(A.K, 1) * 4, 256);
+    const size_t off_ri = align_up(off_om + (size_t)std::max(A.K, 1) * 4, 256);
+    const size_t total = align_up(off_ri + (size_t)(A.m + 1) * 8, 256);
 
     void* base = nullptr;
     e = hipMalloc(&base, total);
@@ -62,6 +65,12 @@ int upload(cer_matrix* h) {
     {
         std::vector<uint32_t> w = widen(A.rowPtr);
         put(off_rptr, w.data(), w.size() * 4);
+        std::vector<uint32_t> info((size_t)(A.m + 1) * 2);
+        for (int64_t r = 0; r <= A.m; ++r) {
+            info[(size_t)r * 2] = w[(size_t)r];
+            info[(size_t)r * 2 + 1] = (uint32_t)A.omegaPtr.at((int64_t)w[(size_t)r]);
+        }
+        put(off_ri, info.data(), info.size() * 4);
     }
     put(off_oi, A.omegaI.bytes.data(), A.omegaI.bytes.size());
     put(off_om, A.omega.data(), A.omega.size() * 4);
@@ -80,12 +89,14 @@ int upload(cer_matrix* h) {
     v.rowPtr = reinterpret_cast<const uint32_t*>(b + off_rptr);
     v.omegaI = b + off_oi;
     v.omega = reinterpret_cast<const float*>(b + off_om);
+    v.rowInfo = b + off_ri;
     v.colI_bits = A.colI.bits;
     v.omegaI_bits = A.omegaI.bits;
     v.cser = A.cser ? 1 : 0;
     v.K = A.K;
     v.m = A.m;
     v.n = A.n;
+    v.max_row_groups = A.max_row_groups;
     v.omega0 = A.K > 0 ? A.omega[0] : 0.f;
     return CER_OK;
 }

@@ -195,6 +195,8 @@ int encode_host(const float* W, int64_t m, int64_t n, const float* codebook, int
     A->nnz = (int64_t)acc_n;
     A->G = (int64_t)acc_g;
     A->nonempty_groups = std::accumulate(nonempty_part.begin(), nonempty_part.end(), (int64_t)0);
+    for (int64_t r = 0; r < m; ++r)
+        A->max_row_groups = std::max<int64_t>(A->max_row_groups, (int64_t)(row_groups[(size_t)r + 1] - row_groups[(size_t)r]));
 
     // pass 3: fill
     std::vector<uint32_t> colI((size_t)acc_n), omegaPtr((size_t)acc_g + 1), rowPtr((size_t)m + 1),

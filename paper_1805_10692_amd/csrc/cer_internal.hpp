@@ -28,6 +28,7 @@ struct HostMatrix {
     int32_t K = 0;
     int64_t nnz = 0, G = 0;
     int64_t nonempty_groups = 0;
+    int64_t max_row_groups = 0;  // largest number of (raw) groups in one row
     std::vector<float> omega;
     std::vector<int64_t> count;
     HostArray colI, omegaPtr, rowPtr, omegaI;
@@ -35,9 +36,10 @@ struct HostMatrix {
 
 // What the kernels see: device pointers into the handle's single allocation.
 struct DeviceView {
-    const void* colI = nullptr;        // minimal width, padded with 64 readable bytes
+    const void* colI = nullptr;        // minimal width, followed by 8 KiB of readable zero padding
     const uint32_t* omegaPtr = nullptr; // G + 1
     const uint32_t* rowPtr = nullptr;   // m + 1
+    const void* rowInfo = nullptr;      // derived, m + 1 pairs {rowPtr[r], omegaPtr[rowPtr[r]]} as 2 x uint32
     const void* omegaI = nullptr;       // minimal width (CSER)
     const float* omega = nullptr;       // K
     int32_t colI_bits = 16;
@@ -45,6 +47,7 @@ struct DeviceView {
     int32_t cser = 0;
     int32_t K = 0;
     int64_t m = 0, n = 0;
+    int64_t max_row_groups = 0;
     float omega0 = 0.f;
 };
 

@@ -37,8 +37,10 @@ struct KView {
     const void* colI;
     const uint32_t* omegaPtr;
     const uint32_t* rowPtr;
+    const uint2* rowInfo;  // derived: {rowPtr[r], OmegaPtr[rowPtr[r]]}, m + 1 entries
     const void* omegaI;
     const float* omega;
+    uint32_t K;
     int32_t omegaI_bits;
     int32_t cser;
     uint32_t m;
@@ -46,10 +48,13 @@ struct KView {
     float omega0;
 };
 
+// OmegaI[g] for an 8-, 16- or 32-bit array, without a branch on the width: the aligned 32-bit
+// word that holds the element is loaded and the element is shifted out (the array is padded).
 __device__ __forceinline__ uint32_t load_rank(const void* p, int bits, uint32_t g) {
-    if (bits == 8) return static_cast<const uint8_t*>(p)[g];
-    if (bits == 16) return static_cast<const uint16_t*>(p)[g];
-    return static_cast<const uint32_t*>(p)[g];
+    const uint32_t byte_off = g * ((uint32_t)bits >> 3);
+    const uint32_t word = static_cast<const uint32_t*>(p)[byte_off >> 2];
+    const uint32_t mask = bits >= 32 ? 0xFFFFFFFFu : ((1u << bits) - 1u);
+    return (word >> ((byte_off & 3u) * 8u)) & mask;
 }
 
 __device__ __forceinline__ void wave_lds_sync() {
@@ -145,111 +150,242 @@ __device__ __forceinline__ float wave_sum(float x) {
            (__int_as_float(__builtin_amdgcn_readlane(xi, 32)) + __int_as_float(__builtin_amdgcn_readlane(xi, 48)));
 }
 
+// One lane's share of 64 consecutive raw groups: start, end and rank (loaded, not yet used).
+struct PtrTile {
+    uint32_t s, e, rank;
+};
+
+__device__ __forceinline__ PtrTile load_ptr_tile(const KView& v, uint32_t g0, uint32_t j0, uint32_t tg_end, int lane) {
+    PtrTile p{0u, 0u, 0u};
+    const uint32_t g = j0 + lane;
+    if (g < tg_end) {
+        p.s = v.omegaPtr[g];
+        p.e = v.omegaPtr[g + 1];
+        p.rank = v.cser ? load_rank(v.omegaI, v.omegaI_bits, g) : g - g0 + 1u;
+    }
+    return p;
+}
+
 // ------------------------------------------------------------------------------------------------
 // batch = 1
 // ------------------------------------------------------------------------------------------------
+//
+// One wave per row.  Lane l of step s owns the row's (64 s + l)-th index: the index loads are plain
+// coalesced IdxT loads (one cache line per wave instruction), all issued before the first is used,
+// and so are the LDS gathers of X.  Because the 64 lanes of a step cover 64 CONSECUTIVE positions of
+// colI, the group structure is the same for the whole wave: one wave-uniform cursor (scalar
+// registers, fed from the wave's LDS list of non-empty groups one entry ahead) walks the row's
+// group boundaries, and only a step whose window contains a boundary does extra work:
+//     lanes before the boundary add their input to the running sum, every lane multiplies its
+//     running sum once by the value of the group that ends, lanes after it start the next sum.
+// A lane therefore multiplies once per group it has touched, never once per element, no lane
+// searches a boundary list, and a step without a boundary costs two vector instructions (address
+// shift, add) plus the LDS gather -- the wave's instruction count is what bounds this kernel once
+// the stream is in flight.
 
-template <typename IdxT, bool kXinLds, int E, int... Ks>
-__device__ __forceinline__ void gemv_chunk(const uint4& q, uint32_t c, uint32_t ts, uint32_t te, const float* xg,
-                                           const float* xs, Cursor& cur, float& run, float& acc,
-                                           const uint32_t* ends, const float* wts, int count,
-                                           std::integer_sequence<int, Ks...>) {
-    const uint32_t idx[E] = {chunk_get<IdxT, Ks>(q)...};
-    const uint32_t first = c > ts ? c : ts;
-    if (first >= cur.end) {
-        acc = fmaf(run, cur.w, acc);
-        run = 0.f;
-        cursor_seek(cur, first, ends, wts, count);
-    }
-    const uint32_t stop = cur.end < te ? cur.end : te;
-    if (c >= ts && c + E <= stop) {
-        // whole chunk inside one group
-        float x[E];
-#pragma unroll
-        for (int k = 0; k < E; ++k) x[k] = kXinLds ? xs[idx[k]] : xg[idx[k]];
-#pragma unroll
-        for (int w = 1; w < E; w <<= 1)
-#pragma unroll
-            for (int k = 0; k + w < E; k += 2 * w) x[k] += x[k + w];
-        run += x[0];
-    } else {
-#pragma unroll
-        for (int k = 0; k < E; ++k) {
-            const uint32_t pos = c + k;
-            if (pos >= ts && pos < te) {
-                if (pos >= cur.end) {
-                    acc = fmaf(run, cur.w, acc);
-                    run = 0.f;
-                    cursor_seek(cur, pos, ends, wts, count);
-                }
-                run += kXinLds ? xs[idx[k]] : xg[idx[k]];
-            }
-        }
-    }
+constexpr int kGemvSteps = 24;  // index loads in flight per lane: one batch covers 64 * 24 positions
+
+// Wave-uniform cursor: current group in scalar registers, the following list entry already
+// requested from LDS (same address in every lane) and converted when the cursor moves on.
+struct UCursor {
+    uint32_t end;      // colI offset one past the current group (kNoEnd after the last one)
+    float w;           // current group's value - Omega[0]
+    uint32_t v_end;    // next entry, as read from LDS (uniform across lanes)
+    float v_w;
+    int j;             // list index of the current group
+};
+
+__device__ __forceinline__ void ucursor_advance(UCursor& c, const uint32_t* ends, const float* wts) {
+    c.end = uniform(c.v_end);
+    c.w = __int_as_float(uniform(__float_as_int(c.v_w)));
+    ++c.j;
+    c.v_end = ends[c.j + 1];
+    c.v_w = wts[c.j + 1];
 }
 
-template <typename IdxT, bool kXinLds>
+// One step: window [w0, w0 + 64) of colI offsets (w0 wave-uniform); x = this lane's input.  The
+// current group's end is never below w0; the sentinel end (2^32 - 1) is beyond every window.
+__device__ __forceinline__ void gemv_step(float x, uint32_t lane, uint32_t w0, UCursor& c, float& run, float& acc,
+                                          const uint32_t* ends, const float* wts) {
+    if (__builtin_expect(c.end - w0 >= (uint32_t)kWave, 1)) {  // no boundary inside the window
+        run += x;
+        return;
+    }
+    uint32_t lo = c.end - w0;  // boundary as a lane number, 0 .. 63
+    run += (lane < lo) ? x : 0.f;
+    acc = fmaf(run, c.w, acc);  // the one multiplication of this lane for the group that ends here
+    ucursor_advance(c, ends, wts);
+    while (c.end - w0 < (uint32_t)kWave) {  // groups wholly inside the window: <= 1 element per lane
+        const uint32_t hi = c.end - w0;
+        acc = fmaf((lane >= lo && lane < hi) ? x : 0.f, c.w, acc);
+        lo = hi;
+        ucursor_advance(c, ends, wts);
+    }
+    run = (lane >= lo) ? x : 0.f;
+}
+
+// Loads of one lane for 64 consecutive raw groups starting at j0 (clamped to the tile, so that
+// every lane issues the same straight-line loads; lanes past the tile are marked invalid).
+template <bool kCser>
+__device__ __forceinline__ PtrTile load_ptr_tile_clamped(const KView& v, uint32_t g0, uint32_t j0, uint32_t tg_end,
+                                                         uint32_t lane) {
+    const uint32_t g = j0 + lane;
+    const uint32_t gc = g < tg_end ? g : (tg_end > j0 ? tg_end - 1u : j0);  // OmegaPtr / OmegaI are padded by 16 B
+    PtrTile p;
+    p.s = v.omegaPtr[gc];
+    p.e = v.omegaPtr[gc + 1];
+    p.rank = kCser ? load_rank(v.omegaI, v.omegaI_bits, gc) : gc - g0 + 1u;
+    if (g >= tg_end) p.e = p.s;  // reads as an empty group
+    return p;
+}
+
+template <typename IdxT, bool kXinLds, bool kVec4, bool kCser>
 __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
                                                         const float* __restrict__ T, uint32_t rows_per_block,
-                                                        int x_vec4_ok) {
+                                                        int omega_in_lds, uint32_t gcap) {
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int E = Chunk<IdxT>::E;
-    constexpr int U = 4;  // 16-byte loads in flight per lane
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
-    const int nwaves = blockDim.x >> 6;
+    constexpr int NP = kGemvSteps;
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = uniform(threadIdx.x >> 6);
+    const uint32_t nwaves = blockDim.x >> 6;
 
+    // LDS: [X: n floats, rounded to 4] [Omega: K floats, optional] [ends | wts: nwaves x (gcap + 2)]
     float* xs = reinterpret_cast<float*>(smem);
     const uint32_t x_floats = kXinLds ? ((v.n + 3u) & ~3u) : 0u;
-    uint32_t* ends = reinterpret_cast<uint32_t*>(xs + x_floats) + wave * (kGroupTile + 1);
-    float* wts = reinterpret_cast<float*>(reinterpret_cast<uint32_t*>(xs + x_floats) + nwaves * (kGroupTile + 1)) +
-                 wave * (kGroupTile + 1);
+    float* oms = xs + x_floats;
+    const uint32_t om_floats = omega_in_lds ? ((v.K + 3u) & ~3u) : 0u;
+    uint32_t* list0 = reinterpret_cast<uint32_t*>(oms + om_floats);
+    uint32_t* ends = list0 + wave * (gcap + 2);
+    float* wts = reinterpret_cast<float*>(list0 + nwaves * (gcap + 2)) + wave * (gcap + 2);
+    const float* omega = omega_in_lds ? oms : v.omega;
+    const float* xsrc = kXinLds ? xs : X;
 
-    if (kXinLds) {
-        if (x_vec4_ok) {
-            const uint32_t n4 = v.n >> 2;
-            const float4* X4 = reinterpret_cast<const float4*>(X);
-            float4* xs4 = reinterpret_cast<float4*>(xs);
-            for (uint32_t i = threadIdx.x; i < n4; i += blockDim.x) xs4[i] = X4[i];
-            for (uint32_t i = (n4 << 2) + threadIdx.x; i < v.n; i += blockDim.x) xs[i] = X[i];
-        } else {
-            for (uint32_t i = threadIdx.x; i < v.n; i += blockDim.x) xs[i] = X[i];
-        }
-        __syncthreads();
-    }
-
-    const float t_off = (v.omega0 != 0.f) ? v.omega0 * T[0] : 0.f;
     const uint32_t row_begin = blockIdx.x * rows_per_block;
     const uint32_t row_end = min(v.m, row_begin + rows_per_block);
-    const uint4* colI16 = static_cast<const uint4*>(v.colI);
+    const IdxT* colI = static_cast<const IdxT*>(v.colI);
+    uint32_t r = row_begin + wave;  // wave-uniform: the descriptor loads below are scalar loads
 
-    for (uint32_t r = row_begin + wave; r < row_end; r += nwaves) {
-        const uint32_t g0 = uniform(v.rowPtr[r]);
-        const uint32_t g1 = uniform(v.rowPtr[r + 1]);
+    // (1) descriptor of the wave's first row: {first group, first colI offset} of rows r and r+1
+    uint32_t g0 = 0, g1 = 0, rs = 0, re = 0;
+    if (r < row_end) {
+        const uint2 d0 = v.rowInfo[r], d1 = v.rowInfo[r + 1];
+        g0 = d0.x; rs = d0.y; g1 = d1.x; re = d1.y;
+    }
+
+    // (2) X and Omega on their way to LDS: SX 16-byte loads per thread are issued here and stay in
+    //     flight while the first row's pointers and indices are requested (named registers: an
+    //     indexed array would end up in scratch memory)
+    typedef float F4 __attribute__((ext_vector_type(4)));
+    F4 xr0, xr1, xr2, xr3, xr4, xr5, xr6, xr7;
+    const uint32_t n4 = kVec4 ? (v.n >> 2) : 0u;
+    const F4* X4 = reinterpret_cast<const F4*>(X);
+#define CER_STAGE_IDX(k) ((k) * blockDim.x + threadIdx.x)
+#define CER_STAGE_LOAD(k) xr##k = X4[CER_STAGE_IDX(k) < n4 ? CER_STAGE_IDX(k) : n4 - 1u]
+    if (kXinLds && kVec4) {  // clamped: every load is issued, none leaves X (the launcher guarantees n4 > 0)
+        CER_STAGE_LOAD(0); CER_STAGE_LOAD(1); CER_STAGE_LOAD(2); CER_STAGE_LOAD(3);
+        CER_STAGE_LOAD(4); CER_STAGE_LOAD(5); CER_STAGE_LOAD(6); CER_STAGE_LOAD(7);
+    }
+    const float om_r = v.omega[threadIdx.x < v.K ? threadIdx.x : 0u];
+    // loads return in issue order: keep the X loads ahead of the index loads, so that staging can finish
+    // while the (much longer) index stream is still arriving
+    __builtin_amdgcn_sched_barrier(0);
+
+    // (3) first row: its first 64 group pointers and its first 64 * NP indices, all unconditional
+    //     (colI is followed by 8 KiB of readable padding).  Positions past the row's end yield some
+    //     valid index whose input ends up in a running sum that is multiplied by the list sentinel's 0.
+    PtrTile pt0 = load_ptr_tile_clamped<kCser>(v, g0, g0, min(g1, g0 + min(gcap, (uint32_t)kWave)), lane);
+    uint32_t idx[NP];
+    {
+        const IdxT* p = colI + rs + lane;
+#pragma unroll
+        for (int s = 0; s < NP; ++s) idx[s] = (uint32_t)p[s * kWave];
+    }
+
+    __builtin_amdgcn_sched_barrier(0);
+
+    // (4) finish staging
+    if (kXinLds) {
+        if (kVec4) {
+            // all eight values are used here unconditionally, which keeps the compiler from sinking a load
+            // into its (conditional) store below the index loads
+            asm volatile("" ::"v"(xr0), "v"(xr1), "v"(xr2), "v"(xr3), "v"(xr4), "v"(xr5), "v"(xr6), "v"(xr7));
+            F4* xs4 = reinterpret_cast<F4*>(xs);
+#define CER_STAGE_STORE(k) if (CER_STAGE_IDX(k) < n4) xs4[CER_STAGE_IDX(k)] = xr##k
+            CER_STAGE_STORE(0); CER_STAGE_STORE(1); CER_STAGE_STORE(2); CER_STAGE_STORE(3);
+            CER_STAGE_STORE(4); CER_STAGE_STORE(5); CER_STAGE_STORE(6); CER_STAGE_STORE(7);
+            for (uint32_t i = 8u * blockDim.x + threadIdx.x; i < n4; i += blockDim.x) xs4[i] = X4[i];
+        }
+        for (uint32_t i = (n4 << 2) + threadIdx.x; i < v.n; i += blockDim.x) xs[i] = X[i];
+    }
+#undef CER_STAGE_STORE
+#undef CER_STAGE_LOAD
+#undef CER_STAGE_IDX
+    if (omega_in_lds) {
+        if (threadIdx.x < v.K) oms[threadIdx.x] = om_r;
+        for (uint32_t i = blockDim.x + threadIdx.x; i < v.K; i += blockDim.x) oms[i] = v.omega[i];
+    }
+    if (kXinLds || omega_in_lds) __syncthreads();
+
+    const float t_off = (v.omega0 != 0.f) ? v.omega0 * T[0] : 0.f;
+
+    bool first_row = true;
+    for (; r < row_end; r += nwaves) {
+        if (!first_row) {
+            const uint2 e0 = v.rowInfo[r], e1 = v.rowInfo[r + 1];
+            g0 = e0.x; rs = e0.y; g1 = e1.x; re = e1.y;
+        }
         float acc = 0.f;
-        for (uint32_t tg = g0; tg < g1; tg += kGroupTile) {
-            const uint32_t tg_end = min(g1, tg + kGroupTile);
-            const uint32_t ts = uniform(v.omegaPtr[tg]);
-            const uint32_t te = uniform(v.omegaPtr[tg_end]);
-            const int count = build_group_list(v, g0, tg, tg_end, ends, wts, lane);
-            if (te > ts) {
-                Cursor cur{0, ends[0], wts[0]};
+        // a row is one tile unless it has more raw groups than the wave's list holds
+        for (uint32_t tg = g0; tg < g1; tg += gcap) {
+            const uint32_t tg_end = min(g1, tg + gcap);
+            const uint32_t ts = (tg == g0) ? rs : uniform(v.omegaPtr[tg]);
+            const uint32_t te = (tg_end == g1) ? re : uniform(v.omegaPtr[tg_end]);
+            const bool pre = first_row && tg == g0;
+            // list of the tile's non-empty groups, closed by two sentinels
+            int count = 0;
+            for (uint32_t j0 = tg; j0 < tg_end; j0 += kWave) {
+                const PtrTile p = (pre && j0 == tg) ? pt0 : load_ptr_tile_clamped<kCser>(v, g0, j0, tg_end, lane);
+                const bool nonempty = p.e > p.s;
+                const uint64_t mask = __ballot(nonempty);
+                if (nonempty) {
+                    const int pos = count + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                                           __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                    ends[pos] = p.e;
+                    wts[pos] = omega[p.rank] - v.omega0;
+                }
+                count += __popcll(mask);
+            }
+            if (lane < 2) {
+                ends[count + lane] = kNoEnd;
+                wts[count + lane] = 0.f;
+            }
+            wave_lds_sync();
+            if (count > 0) {
+                UCursor cur;
+                cur.j = -1;
+                cur.v_end = ends[0];
+                cur.v_w = wts[0];
+                ucursor_advance(cur, ends, wts);
                 float run = 0.f;
-                const uint32_t a0 = ts & ~(uint32_t)(E - 1);
-                for (uint32_t c0 = a0 + lane * E; c0 < te; c0 += kWave * E * U) {
-                    uint4 q[U];
+                for (uint32_t b0 = ts; b0 < te; b0 += NP * kWave) {
+                    if (!(pre && b0 == ts)) {  // the prefetched indices are those of the first batch of the first row
+                        const IdxT* p = colI + b0 + lane;
 #pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        const uint32_t c = c0 + u * kWave * E;
-                        if (c < te) q[u] = colI16[c / E];
+                        for (int s = 0; s < NP; ++s) idx[s] = (uint32_t)p[s * kWave];
                     }
+                    float xv[NP];
 #pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        const uint32_t c = c0 + u * kWave * E;
-                        if (c < te)
-                            gemv_chunk<IdxT, kXinLds, E>(q[u], c, ts, te, X, xs, cur, run, acc, ends, wts, count,
-                                                         std::make_integer_sequence<int, E>{});
+                    for (int s = 0; s < NP; ++s) xv[s] = xsrc[idx[s]];
+#define CER_STEP(S) gemv_step(xv[S], lane, b0 + (S) * kWave, cur, run, acc, ends, wts)
+                    CER_STEP(0); CER_STEP(1); CER_STEP(2); CER_STEP(3); CER_STEP(4); CER_STEP(5);
+                    CER_STEP(6); CER_STEP(7); CER_STEP(8); CER_STEP(9); CER_STEP(10); CER_STEP(11);
+                    CER_STEP(12); CER_STEP(13); CER_STEP(14); CER_STEP(15);
+                    if (b0 + 16 * kWave < te) {
+                        CER_STEP(16); CER_STEP(17); CER_STEP(18); CER_STEP(19);
+                        if (b0 + 20 * kWave < te) { CER_STEP(20); CER_STEP(21); CER_STEP(22); CER_STEP(23); }
                     }
+#undef CER_STEP
+                    static_assert(NP == 24, "steps are spelled out");
                 }
                 acc = fmaf(run, cur.w, acc);
             }
@@ -257,6 +393,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
         }
         const float y = wave_sum(acc);
         if (lane == 0) Y[r] = y + t_off;
+        first_row = false;
     }
 }
 
@@ -325,14 +462,14 @@ __global__ __launch_bounds__(256) void cer_gemm_kernel(KView v, const float* __r
     uint32_t* ends = s_ends[wave];
     float* wts = s_wts[wave];
 
-    const uint32_t g0 = uniform(v.rowPtr[r]);
-    const uint32_t g1 = uniform(v.rowPtr[r + 1]);
+    const uint2 d0 = v.rowInfo[r], d1 = v.rowInfo[r + 1];
+    const uint32_t g0 = uniform(d0.x), g1 = uniform(d1.x), rs = uniform(d0.y), re = uniform(d1.y);
     Vec<V> acc;
     acc.zero();
     for (uint32_t tg = g0; tg < g1; tg += kGroupTile) {
         const uint32_t tg_end = min(g1, tg + kGroupTile);
-        const uint32_t ts = uniform(v.omegaPtr[tg]);
-        const uint32_t te = uniform(v.omegaPtr[tg_end]);
+        const uint32_t ts = (tg == g0) ? rs : uniform(v.omegaPtr[tg]);
+        const uint32_t te = (tg_end == g1) ? re : uniform(v.omegaPtr[tg_end]);
         const int count = build_group_list(v, g0, tg, tg_end, ends, wts, lane);
         if (te > ts) {
             Cursor cur{0, ends[0], wts[0]};
@@ -544,7 +681,7 @@ const DeviceInfo& device_info() {
 
 KView make_kview(const DeviceView& d) {
     KView k;
-    k.colI = d.colI; k.omegaPtr = d.omegaPtr; k.rowPtr = d.rowPtr; k.omegaI = d.omegaI; k.omega = d.omega;
+    k.colI = d.colI; k.omegaPtr = d.omegaPtr; k.rowPtr = d.rowPtr; k.rowInfo = static_cast<const uint2*>(d.rowInfo); k.K = (uint32_t)d.K; k.omegaI = d.omegaI; k.omega = d.omega;
     k.omegaI_bits = d.omegaI_bits; k.cser = d.cser; k.m = (uint32_t)d.m; k.n = (uint32_t)d.n; k.omega0 = d.omega0;
     return k;
 }
@@ -555,35 +692,62 @@ int env_int(const char* name, int fallback) {
 }
 
 template <typename IdxT>
-hipError_t launch_gemv(const KView& k, const float* X, float* Y, const float* T, hipStream_t stream) {
+hipError_t launch_gemv(const KView& k, uint32_t max_row_groups, const float* X, float* Y, const float* T,
+                       hipStream_t stream) {
     const DeviceInfo& di = device_info();
     const size_t x_bytes = (((size_t)k.n + 3) & ~(size_t)3) * sizeof(float);
-    const size_t list_bytes_per_wave = (size_t)(kGroupTile + 1) * 8;
-    // X in LDS if it fits beside the group lists of at least 4 waves
-    const bool x_in_lds = x_bytes + 4 * list_bytes_per_wave <= di.lds_per_block && env_int("CER_GEMV_X_GLOBAL", 0) == 0;
-    int waves = 4;
-    if (x_in_lds && x_bytes > 40 * 1024) {
-        waves = 16;
-        while (waves > 4 && x_bytes + waves * list_bytes_per_wave > di.lds_per_block) waves >>= 1;
-    }
+    const bool omega_in_lds = k.K <= 4096;
+    const size_t om_bytes = omega_in_lds ? (((size_t)k.K + 3) & ~(size_t)3) * sizeof(float) : 0;
+    // per-wave list of non-empty groups: as long as the longest row needs, at most 1022 entries
+    uint32_t gcap = std::max<uint32_t>(1u, std::min<uint32_t>(max_row_groups, 1022u));
+    auto list_bytes = [&](int waves) { return (size_t)waves * (gcap + 2) * 8; };
+    // X is staged in LDS whenever it fits beside Omega and the lists of 4 waves (with at least 64 entries)
+    bool x_in_lds = env_int("CER_GEMV_X_GLOBAL", 0) == 0 &&
+                    x_bytes + om_bytes + (size_t)4 * (std::min<uint32_t>(gcap, 64u) + 2) * 8 <= di.lds_per_block;
+    const size_t fixed = (x_in_lds ? x_bytes : 0) + om_bytes;
+    // a workgroup that stages a large X should own many rows: 16 waves; small X: 4 waves, more workgroups
+    int waves = (x_in_lds && x_bytes > 40 * 1024) ? 16 : 4;
     waves = env_int("CER_GEMV_WAVES", waves);
-    const size_t lds = (x_in_lds ? x_bytes : 0) + waves * list_bytes_per_wave;
+    if (waves < 1 || waves > 16) return hipErrorInvalidValue;
+    while (fixed + list_bytes(waves) > di.lds_per_block && waves > 4) waves >>= 1;
+    while (fixed + list_bytes(waves) > di.lds_per_block && gcap > 64) gcap = std::max<uint32_t>(64u, gcap / 2);
+    const size_t lds = fixed + list_bytes(waves);
+    if (lds > di.lds_per_block) return hipErrorInvalidValue;
     // resident workgroups per CU, limited by LDS and by 32 waves per CU
     size_t per_cu = std::min<size_t>(di.lds_per_block / lds, (size_t)(32 / waves));
     per_cu = std::max<size_t>(1, std::min<size_t>(per_cu, 8));
     const uint64_t slots = (uint64_t)di.cus * per_cu;
     uint32_t iters = (uint32_t)((k.m + slots * waves - 1) / (slots * waves));
     iters = (uint32_t)env_int("CER_GEMV_ROW_ITERS", (int)std::max<uint32_t>(iters, 1));
-    const uint32_t rows_per_block = iters * waves;
+    const uint32_t rows_per_block = std::max<uint32_t>(iters, 1) * waves;
     const uint32_t blocks = (k.m + rows_per_block - 1) / rows_per_block;
-    const int vec_ok = ((reinterpret_cast<uintptr_t>(X) & 15u) == 0) ? 1 : 0;
-    auto kern = x_in_lds ? cer_gemv_kernel<IdxT, true> : cer_gemv_kernel<IdxT, false>;
+    const bool vec4 = (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && k.n >= 4;
+    using Kern = void (*)(KView, const float*, float*, const float*, uint32_t, int, uint32_t);
+    Kern kern;
+    if (k.cser)
+        kern = x_in_lds ? (vec4 ? cer_gemv_kernel<IdxT, true, true, true> : cer_gemv_kernel<IdxT, true, false, true>)
+                        : cer_gemv_kernel<IdxT, false, false, true>;
+    else
+        kern = x_in_lds ? (vec4 ? cer_gemv_kernel<IdxT, true, true, false> : cer_gemv_kernel<IdxT, true, false, false>)
+                        : cer_gemv_kernel<IdxT, false, false, false>;
+    const int kslot = (x_in_lds ? (vec4 ? 2 : 1) : 0) + (k.cser ? 3 : 0);
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
+        // raise the kernel's dynamic-LDS limit once per (kernel, device)
+        static std::mutex mu;
+        static bool granted[6][16] = {};
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        dev = (dev >= 0 && dev < 16) ? dev : 0;
+        std::lock_guard<std::mutex> lock(mu);
+        if (!granted[kslot][dev]) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)di.lds_per_block);
+            if (e != hipSuccess) return e;
+            granted[kslot][dev] = true;
+        }
     }
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(waves * kWave), lds, stream, k, X, Y, T, rows_per_block, vec_ok);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(waves * kWave), lds, stream, k, X, Y, T, rows_per_block,
+                       omega_in_lds ? 1 : 0, gcap);
     return hipGetLastError();
 }
 
@@ -678,9 +842,9 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
     }
     if (L == 1) {
         switch (d.colI_bits) {
-            case 8: e = launch_gemv<uint8_t>(k, X, Y, T, stream); break;
-            case 16: e = launch_gemv<uint16_t>(k, X, Y, T, stream); break;
-            default: e = launch_gemv<uint32_t>(k, X, Y, T, stream); break;
+            case 8: e = launch_gemv<uint8_t>(k, (uint32_t)d.max_row_groups, X, Y, T, stream); break;
+            case 16: e = launch_gemv<uint16_t>(k, (uint32_t)d.max_row_groups, X, Y, T, stream); break;
+            default: e = launch_gemv<uint32_t>(k, (uint32_t)d.max_row_groups, X, Y, T, stream); break;
         }
     } else {
         switch (d.colI_bits) {
