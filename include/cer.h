@@ -158,6 +158,15 @@ void cer_free(cer_handle_t* h);
 int dense_matmul(const float* W_dev, const float* X_dev, float* Y_dev, int64_t m, int64_t n,
                  int64_t batch, void* stream);
 
+/*
+ * cer_stream_copy -- plain device-to-device copy of `bytes` bytes (rounded down to a multiple of
+ * 16; both pointers 16-byte aligned) by a simple HIP kernel.  A measurement aid: a kernel of
+ * exactly known memory traffic against which hardware byte counters (and the attainable copy
+ * bandwidth) are calibrated.  Enqueued on `stream`, no synchronisation.  Errors: CER_E_INVALID,
+ * CER_E_HIP.
+ */
+int cer_stream_copy(void* dst_dev, const void* src_dev, int64_t bytes, void* stream);
+
 const char* cer_strerror(int code);
 int cer_last_hip_error(void);
 

@@ -31,7 +31,7 @@ CER_ARRAY_OMEGA, CER_ARRAY_COLI, CER_ARRAY_OMEGAPTR, CER_ARRAY_ROWPTR, CER_ARRAY
 EXPORTS = [
     "cer_encode", "cser_encode", "cer_matmul", "cser_matmul", "cer_decode", "cser_decode",
     "cer_get_array", "cer_get_dims", "cer_storage_bits", "cer_get_stats", "cer_clone_device",
-    "cer_device_bytes", "cer_free", "dense_matmul", "cer_strerror", "cer_last_hip_error",
+    "cer_device_bytes", "cer_free", "dense_matmul", "cer_stream_copy", "cer_strerror", "cer_last_hip_error",
 ]
 
 _lib = None
@@ -82,6 +82,8 @@ def lib() -> ctypes.CDLL:
         L.cer_free.argtypes = [vp]
         L.dense_matmul.restype = ctypes.c_int
         L.dense_matmul.argtypes = [vp, vp, vp, i64, i64, i64, vp]
+        L.cer_stream_copy.restype = ctypes.c_int
+        L.cer_stream_copy.argtypes = [vp, vp, i64, vp]
         L.cer_strerror.restype = ctypes.c_char_p
         L.cer_strerror.argtypes = [ctypes.c_int]
         L.cer_last_hip_error.restype = ctypes.c_int
@@ -223,3 +225,9 @@ def cer_free(h: Handle) -> None:
 
 def dense_matmul(W, X, Y, m: int, n: int, batch: int, stream=None) -> None:
     _check(lib().dense_matmul(_dev_ptr(W), _dev_ptr(X), _dev_ptr(Y), m, n, batch, _stream_ptr(stream)), "dense_matmul")
+
+
+def cer_stream_copy(dst, src, nbytes: int, stream=None) -> None:
+    def raw(t):
+        return t if isinstance(t, int) else t.data_ptr()
+    _check(lib().cer_stream_copy(raw(dst), raw(src), nbytes, _stream_ptr(stream)), "cer_stream_copy")

@@ -265,6 +265,13 @@ int dense_matmul(const float* W, const float* X, float* Y, int64_t m, int64_t n,
     return rc == 0 ? CER_OK : hip_fail((hipError_t)rc);
 }
 
+int cer_stream_copy(void* dst, const void* src, int64_t bytes, void* stream) {
+    if (!dst || !src || bytes < 0) return CER_E_INVALID;
+    if ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15u) return CER_E_INVALID;
+    const int rc = cer::launch_stream_copy(dst, src, bytes, stream);
+    return rc == 0 ? CER_OK : hip_fail((hipError_t)rc);
+}
+
 const char* cer_strerror(int code) {
     switch (code) {
         case CER_OK: return "ok";

@@ -60,6 +60,7 @@ int min_index_bits(uint64_t max_value);
 // HIP launchers (cer_kernels.hip).  Return a hipError_t value as int (0 = success).
 int launch_matmul(const DeviceView& v, const float* X, float* Y, int64_t L, void* stream);
 int launch_dense(const float* W, const float* X, float* Y, int64_t m, int64_t n, int64_t L, void* stream);
+int launch_stream_copy(void* dst, const void* src, int64_t bytes, void* stream);
 
 }  // namespace cer
 

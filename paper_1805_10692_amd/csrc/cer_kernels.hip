@@ -1,6 +1,6 @@
 // HIP kernels for gfx950 (MI355X, CDNA4, wave64): Y = W.X with W in CER / CSER form
-// (Appendix A-C, Algorithms 3 and 4 of the paper), the constant term for a non-zero most frequent
-// value (Appendix A-A1), and the dense fp32 product used as the baseline (Algorithm 1).
+// (Appendix A-C, Algorithms 3 and 4 of the paper) and the constant term for a non-zero most frequent
+// value (Appendix A-A1).
 //
 // Mapping of the method onto the machine
 //   * one wavefront owns one output row (times one tile of batch columns);
@@ -558,101 +558,6 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restri
 }
 
 // ------------------------------------------------------------------------------------------------
-// Dense fp32 baseline (Algorithm 1)
-// ------------------------------------------------------------------------------------------------
-
-// batch = 1: one wave per R rows, 16-byte loads, X read through the caches.
-template <int R>
-__global__ __launch_bounds__(256) void dense_gemv_kernel(const float* __restrict__ W, const float* __restrict__ X,
-                                                         float* __restrict__ Y, uint32_t m, uint32_t n, int vec_ok) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const uint32_t wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const uint32_t r0 = wave * R;
-    if (r0 >= m) return;
-    float acc[R];
-#pragma unroll
-    for (int k = 0; k < R; ++k) acc[k] = 0.f;
-    const float* rows[R];
-#pragma unroll
-    for (int k = 0; k < R; ++k) rows[k] = W + (size_t)min(r0 + k, m - 1) * n;
-    uint32_t c = 0;
-    if (vec_ok) {
-        const uint32_t n4 = n >> 2;
-        const float4* X4 = reinterpret_cast<const float4*>(X);
-        for (uint32_t i = lane; i < n4; i += kWave) {
-            const float4 x = X4[i];
-#pragma unroll
-            for (int k = 0; k < R; ++k) {
-                const float4 w = reinterpret_cast<const float4*>(rows[k])[i];
-                acc[k] = fmaf(w.x, x.x, acc[k]); acc[k] = fmaf(w.y, x.y, acc[k]);
-                acc[k] = fmaf(w.z, x.z, acc[k]); acc[k] = fmaf(w.w, x.w, acc[k]);
-            }
-        }
-        c = n4 << 2;
-    }
-    for (uint32_t i = c + lane; i < n; i += kWave) {
-        const float x = X[i];
-#pragma unroll
-        for (int k = 0; k < R; ++k) acc[k] = fmaf(rows[k][i], x, acc[k]);
-    }
-#pragma unroll
-    for (int k = 0; k < R; ++k) {
-        const float y = wave_sum(acc[k]);
-        if (lane == 0 && r0 + k < m) Y[r0 + k] = y;
-    }
-}
-
-// batch > 1: 64 x 64 output tile per workgroup, 16-deep k-steps through LDS, 4 x 4 outputs per
-// thread with plain v_fma_f32.
-__global__ __launch_bounds__(256) void dense_gemm_kernel(const float* __restrict__ W, const float* __restrict__ X,
-                                                         float* __restrict__ Y, uint32_t m, uint32_t n, uint32_t L) {
-    constexpr int BM = 64, BN = 64, BK = 16;
-    __shared__ float As[BK][BM + 4];
-    __shared__ float Bs[BK][BN + 4];
-    const uint32_t row0 = blockIdx.y * BM, col0 = blockIdx.x * BN;
-    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-    float acc[4][4] = {};
-    for (uint32_t k0 = 0; k0 < n; k0 += BK) {
-        // A tile: 64 rows x 16 k; thread loads 4 elements
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int e = threadIdx.x + t * 256;
-            const int rr = e >> 4, kk = e & 15;
-            const uint32_t gr = row0 + rr, gk = k0 + kk;
-            As[kk][rr] = (gr < m && gk < n) ? W[(size_t)gr * n + gk] : 0.f;
-        }
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int e = threadIdx.x + t * 256;
-            const int kk = e >> 6, cc = e & 63;
-            const uint32_t gk = k0 + kk, gc = col0 + cc;
-            Bs[kk][cc] = (gk < n && gc < L) ? X[(size_t)gk * L + gc] : 0.f;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int kk = 0; kk < BK; ++kk) {
-            float a[4], b[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
-        }
-        __syncthreads();
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t gr = row0 + ty * 4 + i, gc = col0 + tx * 4 + j;
-            if (gr < m && gc < L) Y[(size_t)gr * L + gc] = acc[i][j];
-        }
-}
-
-// ------------------------------------------------------------------------------------------------
 // Launch logic
 // ------------------------------------------------------------------------------------------------
 
@@ -858,24 +763,6 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
         if (e == hipSuccess) e = f;
     }
     return (int)e;
-}
-
-int launch_dense(const float* W, const float* X, float* Y, int64_t m, int64_t n, int64_t L, void* stream_v) {
-    hipStream_t stream = static_cast<hipStream_t>(stream_v);
-    if (m == 0) return (int)hipSuccess;
-    if (m > 0x7FFFFFFFll || n > 0x7FFFFFFFll || L > 0x7FFFFFFFll) return (int)hipErrorInvalidValue;
-    if (L == 1) {
-        constexpr int R = 2;
-        const int vec_ok = (n % 4 == 0) && ((reinterpret_cast<uintptr_t>(W) & 15u) == 0) &&
-                           ((reinterpret_cast<uintptr_t>(X) & 15u) == 0);
-        const uint32_t waves = (uint32_t)((m + R - 1) / R);
-        hipLaunchKernelGGL(dense_gemv_kernel<R>, dim3((waves + 3) / 4), dim3(256), 0, stream, W, X, Y, (uint32_t)m,
-                           (uint32_t)n, vec_ok);
-    } else {
-        hipLaunchKernelGGL(dense_gemm_kernel, dim3((uint32_t)((L + 63) / 64), (uint32_t)((m + 63) / 64)), dim3(256), 0,
-                           stream, W, X, Y, (uint32_t)m, (uint32_t)n, (uint32_t)L);
-    }
-    return (int)hipGetLastError();
 }
 
 }  // namespace cer

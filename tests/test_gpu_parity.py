@@ -144,7 +144,8 @@ def test_side_stream_and_handle_reuse():
     B.cer_free(h2)
 
 
-@pytest.mark.parametrize("shape", [(64, 256, 1), (67, 1500, 1), (130, 999, 1), (67, 1500, 5), (200, 700, 64), (129, 515, 100)])
+@pytest.mark.parametrize("shape", [(64, 256, 1), (67, 1500, 1), (130, 999, 1), (67, 1500, 5), (200, 700, 64), (129, 515, 100),
+                                   (256, 4096, 64), (300, 1000, 33), (130, 516, 200), (512, 2048, 16), (40, 37, 3), (1, 5, 2)])
 def test_dense_baseline(shape):
     dev = _gpu()
     m, n, L = shape
@@ -154,6 +155,15 @@ def test_dense_baseline(shape):
     B.dense_matmul(Wd, Xd, Yd, m, n, L)
     torch.cuda.synchronize()
     check(Yd.cpu().numpy(), oracle.dot_dense(w.W, w.X), oracle.abs_dot_dense(w.W, w.X), f"dense {shape}")
+
+
+def test_stream_copy_probe():
+    dev = _gpu()
+    src = torch.arange(1 << 20, dtype=torch.float32, device=dev)
+    dst = torch.zeros_like(src)
+    B.cer_stream_copy(dst, src, src.numel() * 4)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
 
 
 # ------------------------------------------------------------------ full sizes of the named workloads
