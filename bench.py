@@ -94,6 +94,18 @@ def time_steps(fn, steps: int, warmup: int):
     return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
 
+def probe_copy(mib: int, reps: int = 20) -> dict:
+    """Runs the library's plain copy kernel on `mib` MiB: known traffic (mib read + mib written per launch)
+    against which the rocprofv3 byte counters of the same run are scaled."""
+    import torch
+    from paper_1805_10692_amd import binding as B
+    n = (mib << 20) // 4
+    src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    wall, ev = time_steps(lambda i: B.cer_stream_copy(dst, src, n * 4), reps, 3)
+    return {"MiB": mib, "us_per_launch": ev * 1e3, "GBps_read_plus_write": 2 * n * 4 / (ev * 1e-3) / 1e9}
+
+
 def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: bool, with_dense: bool) -> dict:
     import torch
 
@@ -224,6 +236,8 @@ def main() -> int:
     ap.add_argument("--warm", action="store_true", help="reuse one device copy (cache-resident)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--probe-copy", type=int, default=0, metavar="MiB",
+                    help="also launch the plain copy kernel on this many MiB (calibrates byte counters)")
     ap.add_argument("--report", default=None, help="write a table over workloads/formats to this JSON file")
     ap.add_argument("--all", action="store_true", help="with --report: all named workloads and the entropy sweep")
     args = ap.parse_args()
@@ -255,6 +269,8 @@ def main() -> int:
         "speedup_vs_dense_rocblas": r.get("speedup_vs_dense_rocblas"),
         "hbm_frac_of_peak": r["algorithmic_GBps"] / HBM_PEAK_GBS,
     }
+    if args.probe_copy:
+        line["copy_probe"] = probe_copy(args.probe_copy)
     print(json.dumps(line), flush=True)
 
     if args.report:

@@ -174,7 +174,7 @@ __device__ __forceinline__ PtrTile load_ptr_tile(const KView& v, uint32_t g0, ui
 // coalesced IdxT loads (one cache line per wave instruction), all issued before the first is used,
 // and so are the LDS gathers of X.  Because the 64 lanes of a step cover 64 CONSECUTIVE positions of
 // colI, the group structure is the same for the whole wave: one wave-uniform cursor (scalar
-// registers, fed from the wave's LDS list of non-empty groups one entry ahead) walks the row's
+// registers, fed by lane reads from the wave's list of non-empty groups) walks the row's
 // group boundaries, and only a step whose window contains a boundary does extra work:
 //     lanes before the boundary add their input to the running sum, every lane multiplies its
 //     running sum once by the value of the group that ends, lanes after it start the next sum.
@@ -185,22 +185,34 @@ __device__ __forceinline__ PtrTile load_ptr_tile(const KView& v, uint32_t g0, ui
 
 constexpr int kGemvSteps = 24;  // index loads in flight per lane: one batch covers 64 * 24 positions
 
-// Wave-uniform cursor: current group in scalar registers, the following list entry already
-// requested from LDS (same address in every lane) and converted when the cursor moves on.
+// Wave-uniform cursor: current group in scalar registers.  The wave holds 64 consecutive entries of
+// its list of non-empty groups in two vector registers (lane i = entry chunk + i), so moving on is
+// two lane reads; a row with more than 64 non-empty groups reloads the registers from LDS.
 struct UCursor {
-    uint32_t end;      // colI offset one past the current group (kNoEnd after the last one)
-    float w;           // current group's value - Omega[0]
-    uint32_t v_end;    // next entry, as read from LDS (uniform across lanes)
-    float v_w;
-    int j;             // list index of the current group
+    uint32_t end;    // colI offset one past the current group (kNoEnd after the last one)
+    float w;         // current group's value - Omega[0]
+    uint32_t l_end;  // per lane: end of list entry chunk + lane
+    float l_w;       // per lane: its value
+    int next;        // lane of the entry the cursor takes next, 0 .. 64
+    int chunk;       // list index held by lane 0
+    int last;        // index of the last list entry (the second sentinel)
 };
 
-__device__ __forceinline__ void ucursor_advance(UCursor& c, const uint32_t* ends, const float* wts) {
-    c.end = uniform(c.v_end);
-    c.w = __int_as_float(uniform(__float_as_int(c.v_w)));
-    ++c.j;
-    c.v_end = ends[c.j + 1];
-    c.v_w = wts[c.j + 1];
+__device__ __forceinline__ void ucursor_load(UCursor& c, const uint32_t* ends, const float* wts, uint32_t lane) {
+    const int i = min(c.chunk + (int)lane, c.last);
+    c.l_end = ends[i];
+    c.l_w = wts[i];
+    c.next = 0;
+}
+
+__device__ __forceinline__ void ucursor_advance(UCursor& c, const uint32_t* ends, const float* wts, uint32_t lane) {
+    if (__builtin_expect(c.next == kWave, 0)) {
+        c.chunk += kWave;
+        ucursor_load(c, ends, wts, lane);
+    }
+    c.end = __builtin_amdgcn_readlane(c.l_end, c.next);
+    c.w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c.l_w), c.next));
+    ++c.next;
 }
 
 // One step: window [w0, w0 + 64) of colI offsets (w0 wave-uniform); x = this lane's input.  The
@@ -214,12 +226,12 @@ __device__ __forceinline__ void gemv_step(float x, uint32_t lane, uint32_t w0, U
     uint32_t lo = c.end - w0;  // boundary as a lane number, 0 .. 63
     run += (lane < lo) ? x : 0.f;
     acc = fmaf(run, c.w, acc);  // the one multiplication of this lane for the group that ends here
-    ucursor_advance(c, ends, wts);
+    ucursor_advance(c, ends, wts, lane);
     while (c.end - w0 < (uint32_t)kWave) {  // groups wholly inside the window: <= 1 element per lane
         const uint32_t hi = c.end - w0;
         acc = fmaf((lane >= lo && lane < hi) ? x : 0.f, c.w, acc);
         lo = hi;
-        ucursor_advance(c, ends, wts);
+        ucursor_advance(c, ends, wts, lane);
     }
     run = (lane >= lo) ? x : 0.f;
 }
@@ -286,6 +298,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
         CER_STAGE_LOAD(4); CER_STAGE_LOAD(5); CER_STAGE_LOAD(6); CER_STAGE_LOAD(7);
     }
     const float om_r = v.omega[threadIdx.x < v.K ? threadIdx.x : 0u];
+    const float om_l = v.omega[lane < v.K ? lane : 0u];  // Omega[lane]: lets a wave look values up by lane shuffle
     // loads return in issue order: keep the X loads ahead of the index loads, so that staging can finish
     // while the (much longer) index stream is still arriving
     __builtin_amdgcn_sched_barrier(0);
@@ -324,6 +337,26 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
         if (threadIdx.x < v.K) oms[threadIdx.x] = om_r;
         for (uint32_t i = blockDim.x + threadIdx.x; i < v.K; i += blockDim.x) oms[i] = v.omega[i];
     }
+    // With at most 64 values and at most 64 raw groups in the first row, its group list is built
+    // here, before the workgroup barrier, from the pointer tile (which arrives ahead of the indices)
+    // and a lane shuffle of Omega: the wait for the other waves' share of X hides it.
+    int count0 = -1;
+    if (v.K <= (uint32_t)kWave && g1 - g0 <= min(gcap, (uint32_t)kWave)) {
+        const bool nonempty = pt0.e > pt0.s;
+        const uint64_t mask = __ballot(nonempty);
+        const float w = __shfl(om_l, (int)(pt0.rank & 63u), kWave) - v.omega0;
+        if (nonempty) {
+            const int pos = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                           __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+            ends[pos] = pt0.e;
+            wts[pos] = w;
+        }
+        count0 = __popcll(mask);
+        if (lane < 2) {
+            ends[count0 + lane] = kNoEnd;
+            wts[count0 + lane] = 0.f;
+        }
+    }
     if (kXinLds || omega_in_lds) __syncthreads();
 
     const float t_off = (v.omega0 != 0.f) ? v.omega0 * T[0] : 0.f;
@@ -343,29 +376,33 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
             const bool pre = first_row && tg == g0;
             // list of the tile's non-empty groups, closed by two sentinels
             int count = 0;
-            for (uint32_t j0 = tg; j0 < tg_end; j0 += kWave) {
-                const PtrTile p = (pre && j0 == tg) ? pt0 : load_ptr_tile_clamped<kCser>(v, g0, j0, tg_end, lane);
-                const bool nonempty = p.e > p.s;
-                const uint64_t mask = __ballot(nonempty);
-                if (nonempty) {
-                    const int pos = count + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                                                           __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-                    ends[pos] = p.e;
-                    wts[pos] = omega[p.rank] - v.omega0;
+            if (pre && count0 >= 0) {
+                count = count0;  // built before the barrier
+            } else {
+                for (uint32_t j0 = tg; j0 < tg_end; j0 += kWave) {
+                    const PtrTile p = (pre && j0 == tg) ? pt0 : load_ptr_tile_clamped<kCser>(v, g0, j0, tg_end, lane);
+                    const bool nonempty = p.e > p.s;
+                    const uint64_t mask = __ballot(nonempty);
+                    if (nonempty) {
+                        const int pos = count + (int)__builtin_amdgcn_mbcnt_hi(
+                                                    (uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+                        ends[pos] = p.e;
+                        wts[pos] = omega[p.rank] - v.omega0;
+                    }
+                    count += __popcll(mask);
                 }
-                count += __popcll(mask);
-            }
-            if (lane < 2) {
-                ends[count + lane] = kNoEnd;
-                wts[count + lane] = 0.f;
+                if (lane < 2) {
+                    ends[count + lane] = kNoEnd;
+                    wts[count + lane] = 0.f;
+                }
             }
             wave_lds_sync();
             if (count > 0) {
                 UCursor cur;
-                cur.j = -1;
-                cur.v_end = ends[0];
-                cur.v_w = wts[0];
-                ucursor_advance(cur, ends, wts);
+                cur.chunk = 0;
+                cur.last = count + 1;
+                ucursor_load(cur, ends, wts, lane);
+                ucursor_advance(cur, ends, wts, lane);
                 float run = 0.f;
                 for (uint32_t b0 = ts; b0 < te; b0 += NP * kWave) {
                     if (!(pre && b0 == ts)) {  // the prefetched indices are those of the first batch of the first row
@@ -377,13 +414,22 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
 #pragma unroll
                     for (int s = 0; s < NP; ++s) xv[s] = xsrc[idx[s]];
 #define CER_STEP(S) gemv_step(xv[S], lane, b0 + (S) * kWave, cur, run, acc, ends, wts)
-                    CER_STEP(0); CER_STEP(1); CER_STEP(2); CER_STEP(3); CER_STEP(4); CER_STEP(5);
-                    CER_STEP(6); CER_STEP(7); CER_STEP(8); CER_STEP(9); CER_STEP(10); CER_STEP(11);
-                    CER_STEP(12); CER_STEP(13); CER_STEP(14); CER_STEP(15);
-                    if (b0 + 16 * kWave < te) {
-                        CER_STEP(16); CER_STEP(17); CER_STEP(18); CER_STEP(19);
-                        if (b0 + 20 * kWave < te) { CER_STEP(20); CER_STEP(21); CER_STEP(22); CER_STEP(23); }
+                    // four steps at a time: one boundary test when the next 256 positions hold none
+#define CER_STEP4(S)                                                                     \
+    if (cur.end - (b0 + (S) * kWave) >= 4u * kWave) {                                    \
+        run += (xv[S] + xv[(S) + 1]) + (xv[(S) + 2] + xv[(S) + 3]);                      \
+    } else {                                                                             \
+        CER_STEP(S); CER_STEP((S) + 1); CER_STEP((S) + 2); CER_STEP((S) + 3);            \
+    }
+                    CER_STEP4(0) CER_STEP4(4) CER_STEP4(8)
+                    if (b0 + 12 * kWave < te) {
+                        CER_STEP4(12)
+                        if (b0 + 16 * kWave < te) {
+                            CER_STEP4(16)
+                            if (b0 + 20 * kWave < te) { CER_STEP4(20) }
+                        }
                     }
+#undef CER_STEP4
 #undef CER_STEP
                     static_assert(NP == 24, "steps are spelled out");
                 }
