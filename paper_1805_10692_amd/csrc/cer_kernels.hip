@@ -503,7 +503,7 @@ __global__ __launch_bounds__(256) void cer_gemm_kernel(KView v, const float* __r
     const int sub = lane / P;
     const uint32_t col0 = tile * TW + (lane % P) * V;
     const bool active = col0 < L;  // V = 4 requires L % 4 == 0, so a lane is all in or all out
-    const float* xcol = X + col0;
+    const float* xgather = X + (active ? col0 : 0u);  // lanes beyond the batch read column 0 and store nothing
     const IdxT* colI = static_cast<const IdxT*>(v.colI);
     uint32_t* ends = s_ends[wave];
     float* wts = s_wts[wave];
@@ -521,33 +521,44 @@ __global__ __launch_bounds__(256) void cer_gemm_kernel(KView v, const float* __r
             Cursor cur{0, ends[0], wts[0]};
             Vec<V> run;
             run.zero();
-            for (uint32_t base = ts; base < te; base += S * U) {
-                uint32_t idx[U];
-                Vec<V> xv[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const uint32_t pos = base + u * S + sub;
-                    idx[u] = pos < te ? (uint32_t)colI[pos] : 0u;
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const uint32_t pos = base + u * S + sub;
-                    xv[u].zero();
-                    if (active && pos < te) xv[u].load(xcol + (size_t)idx[u] * L);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const uint32_t pos = base + u * S + sub;
-                    if (pos < te) {
-                        if (pos >= cur.end) {
-                            acc.fma(run, cur.w);
-                            run.zero();
-                            cursor_seek(cur, pos, ends, wts, count);
-                        }
-                        run.add(xv[u]);
-                    }
-                }
+            // Two batches of U indices / gathers are kept in flight (ping-pong): while one batch is
+            // summed, the gathers of the next and the index loads of the one after are under way.
+            // Every load is unconditional: colI is followed by readable padding and any value found
+            // there or in a neighbouring row is a valid row of X; positions past `te` are dropped
+            // when the batch is summed.
+            constexpr uint32_t SU = S * U;
+            uint32_t ia[U], ib[U];
+            Vec<V> xa[U], xb[U];
+#define CER_LOAD_IDX(ix, b)                                                    \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) ix[u] = (uint32_t)colI[(b) + u * S + sub];
+#define CER_GATHER(xv, ix)                                                     \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) xv[u].load(xgather + (size_t)ix[u] * L);
+#define CER_CONSUME(xv, b)                                                     \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) {                            \
+        const uint32_t pos = (b) + u * S + sub;                                \
+        if (pos < te) {                                                        \
+            if (pos >= cur.end) {                                              \
+                acc.fma(run, cur.w);                                           \
+                run.zero();                                                    \
+                cursor_seek(cur, pos, ends, wts, count);                       \
+            }                                                                  \
+            run.add(xv[u]);                                                    \
+        }                                                                      \
+    }
+            CER_LOAD_IDX(ia, ts)
+            CER_GATHER(xa, ia)
+            CER_LOAD_IDX(ib, ts + SU)
+            for (uint32_t base = ts; base < te; base += 2 * SU) {
+                CER_GATHER(xb, ib)
+                CER_LOAD_IDX(ia, base + 2 * SU)
+                CER_CONSUME(xa, base)
+                CER_GATHER(xa, ia)
+                CER_LOAD_IDX(ib, base + 3 * SU)
+                CER_CONSUME(xb, base + SU)
             }
+#undef CER_LOAD_IDX
+#undef CER_GATHER
+#undef CER_CONSUME
             acc.fma(run, cur.w);
         }
         wave_lds_sync();
@@ -726,8 +737,9 @@ hipError_t launch_gemm(const KView& k, const float* X, float* Y, const float* T,
     const bool vec4 = (L % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15u) == 0) &&
                       ((reinterpret_cast<uintptr_t>(Y) & 15u) == 0) && ((reinterpret_cast<uintptr_t>(T) & 15u) == 0);
     if (vec4) {
-        // tile width: all of L up to 64 columns (256 B of one X row), 64 beyond
-        uint32_t tw = std::min<uint32_t>(pow2_ceil(L), 64u);
+        // tile width: all of L up to 32 columns, 32 beyond: one gather = one 128-byte line of an X row, and a
+        // wider batch gives more waves (measured on MI355X: 32 beats 16, 64, 128 and 256 at L = 32, 64, 3136)
+        uint32_t tw = std::min<uint32_t>(pow2_ceil(L), 32u);
         tw = std::max<uint32_t>(tw, 4u);
         tw = (uint32_t)env_int("CER_GEMM_TILE", (int)tw);
         switch (tw) {
