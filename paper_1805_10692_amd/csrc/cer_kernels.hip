@@ -6,20 +6,27 @@
 //   * one wavefront owns one output row (times one tile of batch columns);
 //   * the wave first turns the row's group pointers into a compact list of its NON-EMPTY groups
 //     in LDS: (end offset into colI, value - Omega[0]).  CER derives the value from the group's
-//     position in the row, CSER from OmegaI; empty CER padding groups vanish here, so both formats
-//     share every later step;
-//   * colI is then streamed with 16-byte coalesced loads.  Every lane keeps a cursor into the
-//     group list, a running sum of the inputs gathered for its current group, and multiplies that
-//     sum by the group's value only when it crosses a group boundary -- one multiplication per
-//     (lane, group) instead of one per element, which is the paper's point;
+//     position in the row, CSER from OmegaI; empty CER padding groups vanish here (ballot +
+//     prefix-popcount compaction), so both formats share every later step;
+//   * one wave instruction always covers CONSECUTIVE positions of colI (64 of them for batch 1,
+//     64/P for a batch tile handled by P lanes per index), so the group structure is wave-uniform:
+//     a single cursor in scalar registers walks the row's group boundaries, and only a step whose
+//     window contains a boundary does extra work.  Lanes before the boundary add their input to
+//     the running sum, every lane multiplies its running sum once by the value of the group that
+//     ends, lanes after it start the next sum: one multiplication per (lane, group), never one per
+//     element -- the paper's point -- and no lane ever searches a boundary list;
 //   * batch = 1: X is staged into LDS once per workgroup and gathered from there; the 64 lane
-//     totals are combined with DPP cross-lane adds.
-//   * batch > 1: lanes run across the batch columns (P lanes x V floats per index), 64/P indices
-//     are in flight per wave instruction, X rows are gathered from L2; workgroups are numbered so
-//     that one XCD's L2 sees as few batch tiles as possible.
+//     totals are combined with DPP cross-lane adds;
+//   * batch > 1: P lanes x V floats cover a tile of batch columns, 64/P indices are gathered per
+//     wave instruction from L2, two batches of gathers are kept in flight, workgroups are numbered
+//     so that one XCD's L2 sees as few batch tiles of X as possible.
+// Every load that feeds the streams is unconditional and issued in straight-line code (colI is
+// followed by readable padding); positions past a row's end pick up some valid input that lands in
+// a running sum multiplied by the list sentinel's weight 0.
 // MFMA is not used on this path: it is a gather-accumulate, not a dense contraction.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdint>
 #include <cstdlib>
 #include <mutex>
@@ -30,7 +37,6 @@ namespace cer {
 namespace {
 
 constexpr int kWave = 64;
-constexpr int kGroupTile = 256;  // raw groups turned into one LDS list at a time
 constexpr uint32_t kNoEnd = 0xFFFFFFFFu;
 
 struct KView {
@@ -66,75 +72,6 @@ __device__ __forceinline__ void wave_lds_sync() {
 
 __device__ __forceinline__ uint32_t uniform(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 
-// Compact list of the non-empty groups among raw groups [tg, tg_end) of the row whose first
-// group is g0.  ends[j] = offset in colI one past group j, wts[j] = Omega[rank] - Omega[0]
-// (Algorithm 3: rank = position in the row + 1; Algorithm 4: rank = OmegaI[g]).
-// A sentinel (end = 2^32-1, weight 0) closes the list.  Returns the list length.
-__device__ __forceinline__ int build_group_list(const KView& v, uint32_t g0, uint32_t tg, uint32_t tg_end,
-                                                uint32_t* ends, float* wts, int lane) {
-    int count = 0;
-    for (uint32_t j0 = tg; j0 < tg_end; j0 += kWave) {
-        const uint32_t g = j0 + lane;
-        uint32_t s = 0, e = 0;
-        if (g < tg_end) {
-            s = v.omegaPtr[g];
-            e = v.omegaPtr[g + 1];
-        }
-        const bool nonempty = e > s;
-        const uint64_t mask = __ballot(nonempty);
-        if (nonempty) {
-            const int pos = count + __popcll(mask & ((1ull << lane) - 1ull));
-            const uint32_t rank = v.cser ? load_rank(v.omegaI, v.omegaI_bits, g) : g - g0 + 1u;
-            ends[pos] = e;
-            wts[pos] = v.omega[rank] - v.omega0;
-        }
-        count += __popcll(mask);
-    }
-    if (lane == 0) {
-        ends[count] = kNoEnd;
-        wts[count] = 0.f;
-    }
-    wave_lds_sync();
-    return count;
-}
-
-// Per-lane position in the group list.
-struct Cursor {
-    int j;
-    uint32_t end;
-    float w;
-};
-
-// Moves the cursor to the group that contains colI offset `pos` (pos >= c.end on entry).
-__device__ __forceinline__ void cursor_seek(Cursor& c, uint32_t pos, const uint32_t* ends, const float* wts,
-                                            int count) {
-    ++c.j;
-    c.end = ends[c.j];
-    if (pos >= c.end) {
-        int lo = c.j + 1, hi = count;  // ends[count] is the sentinel, larger than any offset
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (ends[mid] > pos) hi = mid; else lo = mid + 1;
-        }
-        c.j = lo;
-        c.end = ends[lo];
-    }
-    c.w = wts[c.j];
-}
-
-template <typename IdxT> struct Chunk;  // one 16-byte load of colI
-template <> struct Chunk<uint8_t> { static constexpr int E = 16; };
-template <> struct Chunk<uint16_t> { static constexpr int E = 8; };
-template <> struct Chunk<uint32_t> { static constexpr int E = 4; };
-
-template <typename IdxT, int k>
-__device__ __forceinline__ uint32_t chunk_get(const uint4& q) {
-    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-    if constexpr (sizeof(IdxT) == 4) return w[k];
-    else if constexpr (sizeof(IdxT) == 2) return (w[k >> 1] >> ((k & 1) * 16)) & 0xFFFFu;
-    else return (w[k >> 2] >> ((k & 3) * 8)) & 0xFFu;
-}
-
 // Sum over the 64 lanes with DPP adds inside each row of 16 lanes, then four lane reads.
 __device__ __forceinline__ float wave_sum(float x) {
     auto dpp_add = [](float v, auto ctrl) {
@@ -150,44 +87,67 @@ __device__ __forceinline__ float wave_sum(float x) {
            (__int_as_float(__builtin_amdgcn_readlane(xi, 32)) + __int_as_float(__builtin_amdgcn_readlane(xi, 48)));
 }
 
-// One lane's share of 64 consecutive raw groups: start, end and rank (loaded, not yet used).
+// ------------------------------------------------------------------------------------------------
+// Group list and cursor (shared by both kernels)
+// ------------------------------------------------------------------------------------------------
+
+// One lane's share of 64 consecutive raw groups: start, end and rank (Algorithm 3: rank = position
+// in the row + 1; Algorithm 4: rank = OmegaI[g]).
 struct PtrTile {
     uint32_t s, e, rank;
 };
 
-__device__ __forceinline__ PtrTile load_ptr_tile(const KView& v, uint32_t g0, uint32_t j0, uint32_t tg_end, int lane) {
-    PtrTile p{0u, 0u, 0u};
+// Loads for raw groups j0 + lane, clamped to the tile so that every lane issues the same
+// straight-line loads; lanes past the tile read as an empty group.  OmegaPtr / OmegaI are padded.
+__device__ __forceinline__ PtrTile load_ptr_tile(const KView& v, bool cser, uint32_t g0, uint32_t j0, uint32_t tg_end,
+                                                 uint32_t lane) {
     const uint32_t g = j0 + lane;
-    if (g < tg_end) {
-        p.s = v.omegaPtr[g];
-        p.e = v.omegaPtr[g + 1];
-        p.rank = v.cser ? load_rank(v.omegaI, v.omegaI_bits, g) : g - g0 + 1u;
-    }
+    const uint32_t gc = g < tg_end ? g : (tg_end > j0 ? tg_end - 1u : j0);
+    PtrTile p;
+    p.s = v.omegaPtr[gc];
+    p.e = v.omegaPtr[gc + 1];
+    p.rank = cser ? load_rank(v.omegaI, v.omegaI_bits, gc) : gc - g0 + 1u;
+    if (g >= tg_end) p.e = p.s;
     return p;
 }
 
-// ------------------------------------------------------------------------------------------------
-// batch = 1
-// ------------------------------------------------------------------------------------------------
-//
-// One wave per row.  Lane l of step s owns the row's (64 s + l)-th index: the index loads are plain
-// coalesced IdxT loads (one cache line per wave instruction), all issued before the first is used,
-// and so are the LDS gathers of X.  Because the 64 lanes of a step cover 64 CONSECUTIVE positions of
-// colI, the group structure is the same for the whole wave: one wave-uniform cursor (scalar
-// registers, fed by lane reads from the wave's list of non-empty groups) walks the row's
-// group boundaries, and only a step whose window contains a boundary does extra work:
-//     lanes before the boundary add their input to the running sum, every lane multiplies its
-//     running sum once by the value of the group that ends, lanes after it start the next sum.
-// A lane therefore multiplies once per group it has touched, never once per element, no lane
-// searches a boundary list, and a step without a boundary costs two vector instructions (address
-// shift, add) plus the LDS gather -- the wave's instruction count is what bounds this kernel once
-// the stream is in flight.
+// Appends the non-empty groups of one pointer tile to the wave's LDS list (w = that lane's weight).
+__device__ __forceinline__ int list_append(const PtrTile& p, float w, uint32_t* ends, float* wts, int count) {
+    const bool nonempty = p.e > p.s;
+    const uint64_t mask = __ballot(nonempty);
+    if (nonempty) {
+        const int pos = count + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                               __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+        ends[pos] = p.e;
+        wts[pos] = w;
+    }
+    return count + __popcll(mask);
+}
 
-constexpr int kGemvSteps = 24;  // index loads in flight per lane: one batch covers 64 * 24 positions
+// Two sentinels (end = 2^32 - 1, weight 0) close the list: the cursor may sit on the first one.
+__device__ __forceinline__ void list_close(uint32_t* ends, float* wts, int count, uint32_t lane) {
+    if (lane < 2) {
+        ends[count + lane] = kNoEnd;
+        wts[count + lane] = 0.f;
+    }
+}
+
+// List of the non-empty groups among raw groups [tg, tg_end) of the row whose first group is g0.
+__device__ __forceinline__ int list_build(const KView& v, bool cser, const float* omega, uint32_t g0, uint32_t tg,
+                                          uint32_t tg_end, bool have_first, const PtrTile& first, uint32_t* ends,
+                                          float* wts, uint32_t lane) {
+    int count = 0;
+    for (uint32_t j0 = tg; j0 < tg_end; j0 += kWave) {
+        const PtrTile p = (have_first && j0 == tg) ? first : load_ptr_tile(v, cser, g0, j0, tg_end, lane);
+        count = list_append(p, omega[p.rank] - v.omega0, ends, wts, count);
+    }
+    list_close(ends, wts, count, lane);
+    return count;
+}
 
 // Wave-uniform cursor: current group in scalar registers.  The wave holds 64 consecutive entries of
-// its list of non-empty groups in two vector registers (lane i = entry chunk + i), so moving on is
-// two lane reads; a row with more than 64 non-empty groups reloads the registers from LDS.
+// its list in two vector registers (lane i = entry chunk + i), so moving on is two lane reads; a row
+// with more than 64 non-empty groups reloads the registers from LDS.
 struct UCursor {
     uint32_t end;    // colI offset one past the current group (kNoEnd after the last one)
     float w;         // current group's value - Omega[0]
@@ -215,41 +175,90 @@ __device__ __forceinline__ void ucursor_advance(UCursor& c, const uint32_t* ends
     ++c.next;
 }
 
-// One step: window [w0, w0 + 64) of colI offsets (w0 wave-uniform); x = this lane's input.  The
-// current group's end is never below w0; the sentinel end (2^32 - 1) is beyond every window.
-__device__ __forceinline__ void gemv_step(float x, uint32_t lane, uint32_t w0, UCursor& c, float& run, float& acc,
-                                          const uint32_t* ends, const float* wts) {
-    if (__builtin_expect(c.end - w0 >= (uint32_t)kWave, 1)) {  // no boundary inside the window
-        run += x;
+__device__ __forceinline__ void ucursor_start(UCursor& c, const uint32_t* ends, const float* wts, int count,
+                                              uint32_t lane) {
+    c.chunk = 0;
+    c.last = count + 1;
+    ucursor_load(c, ends, wts, lane);
+    ucursor_advance(c, ends, wts, lane);
+}
+
+// V batch columns per lane.
+template <int V> struct Vec;
+template <> struct Vec<1> {
+    float a;
+    __device__ __forceinline__ void zero() { a = 0.f; }
+    __device__ __forceinline__ void add(const Vec& o) { a += o.a; }
+    __device__ __forceinline__ void add_if(bool c, const Vec& o) { a += c ? o.a : 0.f; }
+    __device__ __forceinline__ void set_if(bool c, const Vec& o) { a = c ? o.a : 0.f; }
+    __device__ __forceinline__ void fma(const Vec& r, float w) { a = fmaf(r.a, w, a); }
+    __device__ __forceinline__ void fma_if(bool c, const Vec& r, float w) { a = fmaf(c ? r.a : 0.f, w, a); }
+    __device__ __forceinline__ void load(const float* p) { a = *p; }
+    __device__ __forceinline__ void store(float* p) const { *p = a; }
+    __device__ __forceinline__ void xor_add(int off) { a += __shfl_xor(a, off, kWave); }
+    __device__ __forceinline__ void add_scaled(const float* t, float s) { a = fmaf(s, t[0], a); }
+};
+template <> struct Vec<4> {
+    float4 a;
+    __device__ __forceinline__ void zero() { a = make_float4(0.f, 0.f, 0.f, 0.f); }
+    __device__ __forceinline__ void add(const Vec& o) { a.x += o.a.x; a.y += o.a.y; a.z += o.a.z; a.w += o.a.w; }
+    __device__ __forceinline__ void add_if(bool c, const Vec& o) {
+        a.x += c ? o.a.x : 0.f; a.y += c ? o.a.y : 0.f; a.z += c ? o.a.z : 0.f; a.w += c ? o.a.w : 0.f;
+    }
+    __device__ __forceinline__ void set_if(bool c, const Vec& o) {
+        a.x = c ? o.a.x : 0.f; a.y = c ? o.a.y : 0.f; a.z = c ? o.a.z : 0.f; a.w = c ? o.a.w : 0.f;
+    }
+    __device__ __forceinline__ void fma(const Vec& r, float w) {
+        a.x = fmaf(r.a.x, w, a.x); a.y = fmaf(r.a.y, w, a.y); a.z = fmaf(r.a.z, w, a.z); a.w = fmaf(r.a.w, w, a.w);
+    }
+    __device__ __forceinline__ void fma_if(bool c, const Vec& r, float w) {
+        a.x = fmaf(c ? r.a.x : 0.f, w, a.x); a.y = fmaf(c ? r.a.y : 0.f, w, a.y);
+        a.z = fmaf(c ? r.a.z : 0.f, w, a.z); a.w = fmaf(c ? r.a.w : 0.f, w, a.w);
+    }
+    __device__ __forceinline__ void load(const float* p) { a = *reinterpret_cast<const float4*>(p); }
+    __device__ __forceinline__ void store(float* p) const { *reinterpret_cast<float4*>(p) = a; }
+    __device__ __forceinline__ void xor_add(int off) {
+        a.x += __shfl_xor(a.x, off, kWave); a.y += __shfl_xor(a.y, off, kWave);
+        a.z += __shfl_xor(a.z, off, kWave); a.w += __shfl_xor(a.w, off, kWave);
+    }
+    __device__ __forceinline__ void add_scaled(const float* t, float s) {
+        a.x = fmaf(s, t[0], a.x); a.y = fmaf(s, t[1], a.y); a.z = fmaf(s, t[2], a.z); a.w = fmaf(s, t[3], a.w);
+    }
+};
+
+// One step: the wave instruction covered colI offsets [w0, w0 + WIN); this lane's input x belongs to
+// offset w0 + who (who = lane for batch 1, the lane's sub-group for a batch tile).  The current
+// group's end is never below w0; the sentinel end (2^32 - 1) is beyond every window.
+template <int WIN, int V>
+__device__ __forceinline__ void cer_step(const Vec<V>& x, uint32_t who, uint32_t w0, UCursor& c, Vec<V>& run,
+                                         Vec<V>& acc, const uint32_t* ends, const float* wts, uint32_t lane) {
+    if (__builtin_expect(c.end - w0 >= (uint32_t)WIN, 1)) {  // no boundary inside the window
+        run.add(x);
         return;
     }
-    uint32_t lo = c.end - w0;  // boundary as a lane number, 0 .. 63
-    run += (lane < lo) ? x : 0.f;
-    acc = fmaf(run, c.w, acc);  // the one multiplication of this lane for the group that ends here
+    uint32_t lo = c.end - w0;  // the boundary, as a value of `who`
+    run.add_if(who < lo, x);
+    acc.fma(run, c.w);  // the one multiplication of this lane for the group that ends here
     ucursor_advance(c, ends, wts, lane);
-    while (c.end - w0 < (uint32_t)kWave) {  // groups wholly inside the window: <= 1 element per lane
+    while (c.end - w0 < (uint32_t)WIN) {  // groups wholly inside the window: at most one element per lane
         const uint32_t hi = c.end - w0;
-        acc = fmaf((lane >= lo && lane < hi) ? x : 0.f, c.w, acc);
+        acc.fma_if(who >= lo && who < hi, x, c.w);
         lo = hi;
         ucursor_advance(c, ends, wts, lane);
     }
-    run = (lane >= lo) ? x : 0.f;
+    run.set_if(who >= lo, x);
 }
 
-// Loads of one lane for 64 consecutive raw groups starting at j0 (clamped to the tile, so that
-// every lane issues the same straight-line loads; lanes past the tile are marked invalid).
-template <bool kCser>
-__device__ __forceinline__ PtrTile load_ptr_tile_clamped(const KView& v, uint32_t g0, uint32_t j0, uint32_t tg_end,
-                                                         uint32_t lane) {
-    const uint32_t g = j0 + lane;
-    const uint32_t gc = g < tg_end ? g : (tg_end > j0 ? tg_end - 1u : j0);  // OmegaPtr / OmegaI are padded by 16 B
-    PtrTile p;
-    p.s = v.omegaPtr[gc];
-    p.e = v.omegaPtr[gc + 1];
-    p.rank = kCser ? load_rank(v.omegaI, v.omegaI_bits, gc) : gc - g0 + 1u;
-    if (g >= tg_end) p.e = p.s;  // reads as an empty group
-    return p;
-}
+// ------------------------------------------------------------------------------------------------
+// batch = 1
+// ------------------------------------------------------------------------------------------------
+//
+// Lane l of step s owns the row's (64 s + l)-th index: the index loads are plain coalesced IdxT
+// loads (one cache line per wave instruction), all issued before the first is used, and so are the
+// LDS gathers of X.  A step without a boundary costs two vector instructions (address shift, add)
+// plus the LDS gather; once the stream is in flight the wave's instruction count bounds the kernel.
+
+constexpr int kGemvSteps = 24;  // index loads in flight per lane: one batch covers 64 * 24 positions
 
 template <typename IdxT, bool kXinLds, bool kVec4, bool kCser>
 __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
@@ -284,7 +293,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
         g0 = d0.x; rs = d0.y; g1 = d1.x; re = d1.y;
     }
 
-    // (2) X and Omega on their way to LDS: SX 16-byte loads per thread are issued here and stay in
+    // (2) X and Omega on their way to LDS: eight 16-byte loads per thread are issued here and stay in
     //     flight while the first row's pointers and indices are requested (named registers: an
     //     indexed array would end up in scratch memory)
     typedef float F4 __attribute__((ext_vector_type(4)));
@@ -304,9 +313,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
     __builtin_amdgcn_sched_barrier(0);
 
     // (3) first row: its first 64 group pointers and its first 64 * NP indices, all unconditional
-    //     (colI is followed by 8 KiB of readable padding).  Positions past the row's end yield some
-    //     valid index whose input ends up in a running sum that is multiplied by the list sentinel's 0.
-    PtrTile pt0 = load_ptr_tile_clamped<kCser>(v, g0, g0, min(g1, g0 + min(gcap, (uint32_t)kWave)), lane);
+    const PtrTile pt0 = load_ptr_tile(v, kCser, g0, g0, min(g1, g0 + min(gcap, (uint32_t)kWave)), lane);
     uint32_t idx[NP];
     {
         const IdxT* p = colI + rs + lane;
@@ -342,20 +349,9 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
     // and a lane shuffle of Omega: the wait for the other waves' share of X hides it.
     int count0 = -1;
     if (v.K <= (uint32_t)kWave && g1 - g0 <= min(gcap, (uint32_t)kWave)) {
-        const bool nonempty = pt0.e > pt0.s;
-        const uint64_t mask = __ballot(nonempty);
         const float w = __shfl(om_l, (int)(pt0.rank & 63u), kWave) - v.omega0;
-        if (nonempty) {
-            const int pos = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                                           __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-            ends[pos] = pt0.e;
-            wts[pos] = w;
-        }
-        count0 = __popcll(mask);
-        if (lane < 2) {
-            ends[count0 + lane] = kNoEnd;
-            wts[count0 + lane] = 0.f;
-        }
+        count0 = list_append(pt0, w, ends, wts, 0);
+        list_close(ends, wts, count0, lane);
     }
     if (kXinLds || omega_in_lds) __syncthreads();
 
@@ -367,57 +363,37 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
             const uint2 e0 = v.rowInfo[r], e1 = v.rowInfo[r + 1];
             g0 = e0.x; rs = e0.y; g1 = e1.x; re = e1.y;
         }
-        float acc = 0.f;
+        Vec<1> acc;
+        acc.zero();
         // a row is one tile unless it has more raw groups than the wave's list holds
         for (uint32_t tg = g0; tg < g1; tg += gcap) {
             const uint32_t tg_end = min(g1, tg + gcap);
             const uint32_t ts = (tg == g0) ? rs : uniform(v.omegaPtr[tg]);
             const uint32_t te = (tg_end == g1) ? re : uniform(v.omegaPtr[tg_end]);
             const bool pre = first_row && tg == g0;
-            // list of the tile's non-empty groups, closed by two sentinels
-            int count = 0;
-            if (pre && count0 >= 0) {
-                count = count0;  // built before the barrier
-            } else {
-                for (uint32_t j0 = tg; j0 < tg_end; j0 += kWave) {
-                    const PtrTile p = (pre && j0 == tg) ? pt0 : load_ptr_tile_clamped<kCser>(v, g0, j0, tg_end, lane);
-                    const bool nonempty = p.e > p.s;
-                    const uint64_t mask = __ballot(nonempty);
-                    if (nonempty) {
-                        const int pos = count + (int)__builtin_amdgcn_mbcnt_hi(
-                                                    (uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-                        ends[pos] = p.e;
-                        wts[pos] = omega[p.rank] - v.omega0;
-                    }
-                    count += __popcll(mask);
-                }
-                if (lane < 2) {
-                    ends[count + lane] = kNoEnd;
-                    wts[count + lane] = 0.f;
-                }
-            }
+            const int count = (pre && count0 >= 0)
+                                  ? count0
+                                  : list_build(v, kCser, omega, g0, tg, tg_end, pre, pt0, ends, wts, lane);
             wave_lds_sync();
             if (count > 0) {
                 UCursor cur;
-                cur.chunk = 0;
-                cur.last = count + 1;
-                ucursor_load(cur, ends, wts, lane);
-                ucursor_advance(cur, ends, wts, lane);
-                float run = 0.f;
+                ucursor_start(cur, ends, wts, count, lane);
+                Vec<1> run;
+                run.zero();
                 for (uint32_t b0 = ts; b0 < te; b0 += NP * kWave) {
                     if (!(pre && b0 == ts)) {  // the prefetched indices are those of the first batch of the first row
                         const IdxT* p = colI + b0 + lane;
 #pragma unroll
                         for (int s = 0; s < NP; ++s) idx[s] = (uint32_t)p[s * kWave];
                     }
-                    float xv[NP];
+                    Vec<1> xv[NP];
 #pragma unroll
-                    for (int s = 0; s < NP; ++s) xv[s] = xsrc[idx[s]];
-#define CER_STEP(S) gemv_step(xv[S], lane, b0 + (S) * kWave, cur, run, acc, ends, wts)
+                    for (int s = 0; s < NP; ++s) xv[s].a = xsrc[idx[s]];
+#define CER_STEP(S) cer_step<kWave, 1>(xv[S], lane, b0 + (S) * kWave, cur, run, acc, ends, wts, lane)
                     // four steps at a time: one boundary test when the next 256 positions hold none
 #define CER_STEP4(S)                                                                     \
     if (cur.end - (b0 + (S) * kWave) >= 4u * kWave) {                                    \
-        run += (xv[S] + xv[(S) + 1]) + (xv[(S) + 2] + xv[(S) + 3]);                      \
+        run.a += (xv[S].a + xv[(S) + 1].a) + (xv[(S) + 2].a + xv[(S) + 3].a);            \
     } else {                                                                             \
         CER_STEP(S); CER_STEP((S) + 1); CER_STEP((S) + 2); CER_STEP((S) + 3);            \
     }
@@ -433,11 +409,11 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
 #undef CER_STEP
                     static_assert(NP == 24, "steps are spelled out");
                 }
-                acc = fmaf(run, cur.w, acc);
+                acc.fma(run, cur.w);
             }
             wave_lds_sync();  // the list is rebuilt by the next tile / row
         }
-        const float y = wave_sum(acc);
+        const float y = wave_sum(acc.a);
         if (lane == 0) Y[r] = y + t_off;
         first_row = false;
     }
@@ -447,34 +423,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
 // batch > 1
 // ------------------------------------------------------------------------------------------------
 
-template <int V> struct Vec;
-template <> struct Vec<1> {
-    float a;
-    __device__ __forceinline__ void zero() { a = 0.f; }
-    __device__ __forceinline__ void add(const Vec& o) { a += o.a; }
-    __device__ __forceinline__ void fma(const Vec& r, float w) { a = fmaf(r.a, w, a); }
-    __device__ __forceinline__ void load(const float* p) { a = *p; }
-    __device__ __forceinline__ void store(float* p) const { *p = a; }
-    __device__ __forceinline__ void xor_add(int off) { a += __shfl_xor(a, off, kWave); }
-    __device__ __forceinline__ void add_scaled(const float* t, float s) { a = fmaf(s, t[0], a); }
-};
-template <> struct Vec<4> {
-    float4 a;
-    __device__ __forceinline__ void zero() { a = make_float4(0.f, 0.f, 0.f, 0.f); }
-    __device__ __forceinline__ void add(const Vec& o) { a.x += o.a.x; a.y += o.a.y; a.z += o.a.z; a.w += o.a.w; }
-    __device__ __forceinline__ void fma(const Vec& r, float w) {
-        a.x = fmaf(r.a.x, w, a.x); a.y = fmaf(r.a.y, w, a.y); a.z = fmaf(r.a.z, w, a.z); a.w = fmaf(r.a.w, w, a.w);
-    }
-    __device__ __forceinline__ void load(const float* p) { a = *reinterpret_cast<const float4*>(p); }
-    __device__ __forceinline__ void store(float* p) const { *reinterpret_cast<float4*>(p) = a; }
-    __device__ __forceinline__ void xor_add(int off) {
-        a.x += __shfl_xor(a.x, off, kWave); a.y += __shfl_xor(a.y, off, kWave);
-        a.z += __shfl_xor(a.z, off, kWave); a.w += __shfl_xor(a.w, off, kWave);
-    }
-    __device__ __forceinline__ void add_scaled(const float* t, float s) {
-        a.x = fmaf(s, t[0], a.x); a.y = fmaf(s, t[1], a.y); a.z = fmaf(s, t[2], a.z); a.w = fmaf(s, t[3], a.w);
-    }
-};
+constexpr int kGemmGroupTile = 256;  // raw groups turned into one LDS list at a time
 
 // V floats per lane, P lanes per index: one wave instruction gathers 64/P rows of X, each
 // V.P floats wide.  Workgroup = 4 waves = 4 consecutive rows of one batch tile.
@@ -482,14 +431,14 @@ template <typename IdxT, int V, int P>
 __global__ __launch_bounds__(256) void cer_gemm_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
                                                        const float* __restrict__ T, uint32_t L, uint32_t ntiles,
                                                        uint32_t rowblocks, uint32_t items_per_xcd) {
-    constexpr int S = kWave / P;  // indices in flight per wave instruction
-    constexpr int U = 8;          // unroll: gathers in flight per lane
+    constexpr int S = kWave / P;  // consecutive colI positions per wave instruction
+    constexpr int U = 8;          // wave instructions per batch
     constexpr int TW = V * P;     // batch columns per tile
-    __shared__ uint32_t s_ends[4][kGroupTile + 1];
-    __shared__ float s_wts[4][kGroupTile + 1];
+    __shared__ uint32_t s_ends[4][kGemmGroupTile + 2];
+    __shared__ float s_wts[4][kGemmGroupTile + 2];
 
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = uniform(threadIdx.x >> 6);
     // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Give XCD x the x-th
     // eighth of the (tile-major) work list, so that an XCD walks through few batch tiles of X.
     const uint32_t xcd = blockIdx.x & 7u, q = blockIdx.x >> 3;
@@ -500,7 +449,7 @@ __global__ __launch_bounds__(256) void cer_gemm_kernel(KView v, const float* __r
     const uint32_t r = (item - tile * rowblocks) * 4u + wave;
     if (r >= v.m) return;
 
-    const int sub = lane / P;
+    const uint32_t sub = lane / P;
     const uint32_t col0 = tile * TW + (lane % P) * V;
     const bool active = col0 < L;  // V = 4 requires L % 4 == 0, so a lane is all in or all out
     const float* xgather = X + (active ? col0 : 0u);  // lanes beyond the batch read column 0 and store nothing
@@ -509,42 +458,32 @@ __global__ __launch_bounds__(256) void cer_gemm_kernel(KView v, const float* __r
     float* wts = s_wts[wave];
 
     const uint2 d0 = v.rowInfo[r], d1 = v.rowInfo[r + 1];
-    const uint32_t g0 = uniform(d0.x), g1 = uniform(d1.x), rs = uniform(d0.y), re = uniform(d1.y);
+    const uint32_t g0 = d0.x, rs = d0.y, g1 = d1.x, re = d1.y;
     Vec<V> acc;
     acc.zero();
-    for (uint32_t tg = g0; tg < g1; tg += kGroupTile) {
-        const uint32_t tg_end = min(g1, tg + kGroupTile);
+    const PtrTile none{0u, 0u, 0u};
+    for (uint32_t tg = g0; tg < g1; tg += kGemmGroupTile) {
+        const uint32_t tg_end = min(g1, tg + kGemmGroupTile);
         const uint32_t ts = (tg == g0) ? rs : uniform(v.omegaPtr[tg]);
         const uint32_t te = (tg_end == g1) ? re : uniform(v.omegaPtr[tg_end]);
-        const int count = build_group_list(v, g0, tg, tg_end, ends, wts, lane);
-        if (te > ts) {
-            Cursor cur{0, ends[0], wts[0]};
+        const int count = list_build(v, v.cser != 0, v.omega, g0, tg, tg_end, false, none, ends, wts, lane);
+        wave_lds_sync();
+        if (count > 0) {
+            UCursor cur;
+            ucursor_start(cur, ends, wts, count, lane);
             Vec<V> run;
             run.zero();
-            // Two batches of U indices / gathers are kept in flight (ping-pong): while one batch is
+            // Two batches of U wave instructions are kept in flight (ping-pong): while one batch is
             // summed, the gathers of the next and the index loads of the one after are under way.
-            // Every load is unconditional: colI is followed by readable padding and any value found
-            // there or in a neighbouring row is a valid row of X; positions past `te` are dropped
-            // when the batch is summed.
             constexpr uint32_t SU = S * U;
             uint32_t ia[U], ib[U];
             Vec<V> xa[U], xb[U];
-#define CER_LOAD_IDX(ix, b)                                                    \
+#define CER_LOAD_IDX(ix, b) \
     _Pragma("unroll") for (int u = 0; u < U; ++u) ix[u] = (uint32_t)colI[(b) + u * S + sub];
-#define CER_GATHER(xv, ix)                                                     \
+#define CER_GATHER(xv, ix) \
     _Pragma("unroll") for (int u = 0; u < U; ++u) xv[u].load(xgather + (size_t)ix[u] * L);
-#define CER_CONSUME(xv, b)                                                     \
-    _Pragma("unroll") for (int u = 0; u < U; ++u) {                            \
-        const uint32_t pos = (b) + u * S + sub;                                \
-        if (pos < te) {                                                        \
-            if (pos >= cur.end) {                                              \
-                acc.fma(run, cur.w);                                           \
-                run.zero();                                                    \
-                cursor_seek(cur, pos, ends, wts, count);                       \
-            }                                                                  \
-            run.add(xv[u]);                                                    \
-        }                                                                      \
-    }
+#define CER_CONSUME(xv, b) \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) cer_step<S, V>(xv[u], sub, (b) + u * S, cur, run, acc, ends, wts, lane);
             CER_LOAD_IDX(ia, ts)
             CER_GATHER(xa, ia)
             CER_LOAD_IDX(ib, ts + SU)
@@ -643,8 +582,18 @@ const DeviceInfo& device_info() {
 
 KView make_kview(const DeviceView& d) {
     KView k;
-    k.colI = d.colI; k.omegaPtr = d.omegaPtr; k.rowPtr = d.rowPtr; k.rowInfo = static_cast<const uint2*>(d.rowInfo); k.K = (uint32_t)d.K; k.omegaI = d.omegaI; k.omega = d.omega;
-    k.omegaI_bits = d.omegaI_bits; k.cser = d.cser; k.m = (uint32_t)d.m; k.n = (uint32_t)d.n; k.omega0 = d.omega0;
+    k.colI = d.colI;
+    k.omegaPtr = d.omegaPtr;
+    k.rowPtr = d.rowPtr;
+    k.rowInfo = static_cast<const uint2*>(d.rowInfo);
+    k.omegaI = d.omegaI;
+    k.omega = d.omega;
+    k.K = (uint32_t)d.K;
+    k.omegaI_bits = d.omegaI_bits;
+    k.cser = d.cser;
+    k.m = (uint32_t)d.m;
+    k.n = (uint32_t)d.n;
+    k.omega0 = d.omega0;
     return k;
 }
 
