@@ -260,6 +260,46 @@ __device__ __forceinline__ void cer_step(const Vec<V>& x, uint32_t who, uint32_t
 
 constexpr int kGemvSteps = 24;  // index loads in flight per lane: one batch covers 64 * 24 positions
 
+// One batch of 24 steps of a row: offsets [b0, b0 + 1536) of colI, whose indices ix[] were requested
+// earlier.  The index loads return in order, so step s is gathered and summed while the indices of
+// later steps are still on their way from HBM: gathers run eight steps ahead of the sums, and
+// scheduling barriers keep the compiler from hoisting every gather (and with it the wait for the
+// last index) above the first sum.
+__device__ __forceinline__ void gemv_batch(const uint32_t (&ix)[kGemvSteps], const float* xsrc, uint32_t b0, uint32_t te,
+                                           uint32_t lane, UCursor& cur, Vec<1>& run, Vec<1>& acc, const uint32_t* ends,
+                                           const float* wts) {
+    static_assert(kGemvSteps == 24, "steps are spelled out");
+    Vec<1> xv[kGemvSteps];
+#define CER_GATHER4(S)                                                             \
+    xv[S].a = xsrc[ix[S]]; xv[(S) + 1].a = xsrc[ix[(S) + 1]];                      \
+    xv[(S) + 2].a = xsrc[ix[(S) + 2]]; xv[(S) + 3].a = xsrc[ix[(S) + 3]];
+#define CER_STEP(S) cer_step<kWave, 1>(xv[S], lane, b0 + (S) * kWave, cur, run, acc, ends, wts, lane)
+    // four steps at a time: one boundary test when the next 256 positions hold none
+#define CER_STEP4(S)                                                               \
+    if (cur.end - (b0 + (S) * kWave) >= 4u * kWave) {                              \
+        run.a += (xv[S].a + xv[(S) + 1].a) + (xv[(S) + 2].a + xv[(S) + 3].a);      \
+    } else {                                                                       \
+        CER_STEP(S); CER_STEP((S) + 1); CER_STEP((S) + 2); CER_STEP((S) + 3);      \
+    }
+#define CER_PIN __builtin_amdgcn_sched_barrier(0);
+    CER_GATHER4(0) CER_GATHER4(4) CER_PIN
+    CER_GATHER4(8) CER_PIN CER_STEP4(0) CER_PIN
+    CER_GATHER4(12) CER_PIN CER_STEP4(4) CER_PIN
+    CER_GATHER4(16) CER_PIN CER_STEP4(8) CER_PIN
+    CER_GATHER4(20) CER_PIN
+    if (b0 + 12 * kWave < te) {
+        CER_STEP4(12)
+        if (b0 + 16 * kWave < te) {
+            CER_STEP4(16)
+            if (b0 + 20 * kWave < te) { CER_STEP4(20) }
+        }
+    }
+#undef CER_PIN
+#undef CER_GATHER4
+#undef CER_STEP4
+#undef CER_STEP
+}
+
 template <typename IdxT, bool kXinLds, bool kVec4, bool kCser>
 __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
                                                         const float* __restrict__ T, uint32_t rows_per_block,
@@ -309,16 +349,21 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
     const float om_r = v.omega[threadIdx.x < v.K ? threadIdx.x : 0u];
     const float om_l = v.omega[lane < v.K ? lane : 0u];  // Omega[lane]: lets a wave look values up by lane shuffle
     // loads return in issue order: keep the X loads ahead of the index loads, so that staging can finish
-    // while the (much longer) index stream is still arriving
+    // while the (much longer) index stream is still arriving -- within this wave (scheduling barrier) and
+    // within the compute unit, whose memory pipeline is shared by all waves (workgroup barrier: no wave
+    // requests indices from HBM before every wave has requested its share of X from L2)
+    __builtin_amdgcn_sched_barrier(0);
+    if (kXinLds) __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
 
     // (3) first row: its first 64 group pointers and its first 64 * NP indices, all unconditional
     const PtrTile pt0 = load_ptr_tile(v, kCser, g0, g0, min(g1, g0 + min(gcap, (uint32_t)kWave)), lane);
-    uint32_t idx[NP];
+    uint32_t idx0[NP];  // used by one piece of code only (no merge with re-loaded values, which would make the
+                        // compiler widen -- and so wait for -- all of them at the merge point)
     {
         const IdxT* p = colI + rs + lane;
 #pragma unroll
-        for (int s = 0; s < NP; ++s) idx[s] = (uint32_t)p[s * kWave];
+        for (int s = 0; s < NP; ++s) idx0[s] = (uint32_t)p[s * kWave];
     }
 
     __builtin_amdgcn_sched_barrier(0);
@@ -357,57 +402,54 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
 
     const float t_off = (v.omega0 != 0.f) ? v.omega0 * T[0] : 0.f;
 
+    // The first batch of the first row runs from the prefetched indices when its list is ready
+    // (the common case); everything else -- later batches, rows with many groups, later rows --
+    // goes through the general loop below, which picks up the cursor and sums where this left off.
+    UCursor cur;
+    Vec<1> run, acc;
+    run.zero();
+    acc.zero();
+    bool resume = false;
+    if (r < row_end && count0 > 0) {
+        wave_lds_sync();
+        ucursor_start(cur, ends, wts, count0, lane);
+        gemv_batch(idx0, xsrc, rs, re, lane, cur, run, acc, ends, wts);
+        resume = true;
+    }
+
     bool first_row = true;
     for (; r < row_end; r += nwaves) {
         if (!first_row) {
             const uint2 e0 = v.rowInfo[r], e1 = v.rowInfo[r + 1];
             g0 = e0.x; rs = e0.y; g1 = e1.x; re = e1.y;
+            acc.zero();
         }
-        Vec<1> acc;
-        acc.zero();
         // a row is one tile unless it has more raw groups than the wave's list holds
         for (uint32_t tg = g0; tg < g1; tg += gcap) {
             const uint32_t tg_end = min(g1, tg + gcap);
             const uint32_t ts = (tg == g0) ? rs : uniform(v.omegaPtr[tg]);
             const uint32_t te = (tg_end == g1) ? re : uniform(v.omegaPtr[tg_end]);
-            const bool pre = first_row && tg == g0;
-            const int count = (pre && count0 >= 0)
-                                  ? count0
-                                  : list_build(v, kCser, omega, g0, tg, tg_end, pre, pt0, ends, wts, lane);
-            wave_lds_sync();
-            if (count > 0) {
-                UCursor cur;
-                ucursor_start(cur, ends, wts, count, lane);
-                Vec<1> run;
+            const bool resumed = first_row && resume;  // single tile, first batch done, list and cursor live
+            uint32_t b0 = ts;
+            int count;
+            if (resumed) {
+                count = count0;
+                b0 = ts + NP * kWave;
+            } else {
+                const bool pre = first_row && tg == g0;
+                count = (pre && count0 >= 0) ? count0
+                                             : list_build(v, kCser, omega, g0, tg, tg_end, pre, pt0, ends, wts, lane);
+                wave_lds_sync();
+                if (count > 0) ucursor_start(cur, ends, wts, count, lane);
                 run.zero();
-                for (uint32_t b0 = ts; b0 < te; b0 += NP * kWave) {
-                    if (!(pre && b0 == ts)) {  // the prefetched indices are those of the first batch of the first row
-                        const IdxT* p = colI + b0 + lane;
+            }
+            if (count > 0) {
+                for (; b0 < te; b0 += NP * kWave) {
+                    uint32_t ix[NP];
+                    const IdxT* p = colI + b0 + lane;
 #pragma unroll
-                        for (int s = 0; s < NP; ++s) idx[s] = (uint32_t)p[s * kWave];
-                    }
-                    Vec<1> xv[NP];
-#pragma unroll
-                    for (int s = 0; s < NP; ++s) xv[s].a = xsrc[idx[s]];
-#define CER_STEP(S) cer_step<kWave, 1>(xv[S], lane, b0 + (S) * kWave, cur, run, acc, ends, wts, lane)
-                    // four steps at a time: one boundary test when the next 256 positions hold none
-#define CER_STEP4(S)                                                                     \
-    if (cur.end - (b0 + (S) * kWave) >= 4u * kWave) {                                    \
-        run.a += (xv[S].a + xv[(S) + 1].a) + (xv[(S) + 2].a + xv[(S) + 3].a);            \
-    } else {                                                                             \
-        CER_STEP(S); CER_STEP((S) + 1); CER_STEP((S) + 2); CER_STEP((S) + 3);            \
-    }
-                    CER_STEP4(0) CER_STEP4(4) CER_STEP4(8)
-                    if (b0 + 12 * kWave < te) {
-                        CER_STEP4(12)
-                        if (b0 + 16 * kWave < te) {
-                            CER_STEP4(16)
-                            if (b0 + 20 * kWave < te) { CER_STEP4(20) }
-                        }
-                    }
-#undef CER_STEP4
-#undef CER_STEP
-                    static_assert(NP == 24, "steps are spelled out");
+                    for (int s = 0; s < NP; ++s) ix[s] = (uint32_t)p[s * kWave];
+                    gemv_batch(ix, xsrc, b0, te, lane, cur, run, acc, ends, wts);
                 }
                 acc.fma(run, cur.w);
             }
