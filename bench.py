@@ -114,14 +114,27 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
 
     dev = torch.device("cuda:0")
     w = make_workload(name)
-    enc, mm = (B.cer_encode, B.cer_matmul) if fmt == "cer" else (B.cser_encode, B.cser_matmul)
-    h0 = enc(w.W, w.codebook)
-    dims, stats = B.cer_get_dims(h0), B.cer_get_stats(h0)
-    bits = {"colI": B.cer_get_array(h0, B.CER_ARRAY_COLI).dtype.itemsize * 8,
-            "omegaI": B.cer_get_array(h0, B.CER_ARRAY_OMEGAI).dtype.itemsize * 8}
     L = w.L
-    alg_bytes = algorithmic_bytes(dims, bits, L)
-    fmt_bytes = B.cer_device_bytes(h0)
+    if fmt == "csr":
+        # the paper's sparse comparator: every element != 0 stored with its own fp32 value
+        hs = B.cser_encode(w.W, w.codebook)
+        stats = B.cer_get_stats(hs)
+        B.cer_free(hs)
+        h0 = B.csr_encode(w.W)
+        mm, clone, free, dev_bytes = B.csr_matmul, B.csr_clone_device, B.csr_free, B.csr_device_bytes
+        nnz = len(B.csr_get_array(h0, 0))
+        dims = {"m": w.m, "n": w.n, "K": len(w.codebook), "nnz": nnz, "groups": 0, "is_cser": 0}
+        idx_bytes = B.csr_get_array(h0, 1).dtype.itemsize
+        alg_bytes = nnz * (4 + idx_bytes) + 4 * (w.m + 1) + 4 * w.n * L + 4 * w.m * L
+    else:
+        enc, mm = (B.cer_encode, B.cer_matmul) if fmt == "cer" else (B.cser_encode, B.cser_matmul)
+        clone, free, dev_bytes = B.cer_clone_device, B.cer_free, B.cer_device_bytes
+        h0 = enc(w.W, w.codebook)
+        dims, stats = B.cer_get_dims(h0), B.cer_get_stats(h0)
+        bits = {"colI": B.cer_get_array(h0, B.CER_ARRAY_COLI).dtype.itemsize * 8,
+                "omegaI": B.cer_get_array(h0, B.CER_ARRAY_OMEGAI).dtype.itemsize * 8}
+        alg_bytes = algorithmic_bytes(dims, bits, L)
+    fmt_bytes = dev_bytes(h0)
 
     Xd = torch.from_numpy(w.X).to(dev)
     Yd = torch.empty((w.m, L), dtype=torch.float32, device=dev)
@@ -139,10 +152,10 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
     # cold rotation: enough device copies to exceed twice the last-level cache
     R = 1 if warm else max(2, -(-2 * LAST_LEVEL_CACHE_BYTES // max(fmt_bytes, 1)))
     R = min(R, 256)
-    handles = [h0] + [B.cer_clone_device(h0) for _ in range(R - 1)]
+    handles = [h0] + [clone(h0) for _ in range(R - 1)]
     stream = torch.cuda.current_stream().cuda_stream
     lib = B.lib()
-    cfn = lib.cer_matmul if fmt == "cer" else lib.cser_matmul
+    cfn = {"cer": lib.cer_matmul, "cser": lib.cser_matmul, "csr": lib.csr_matmul}[fmt]
     ptrs = [h.ptr for h in handles]
     xp, yp = Xd.data_ptr(), Yd.data_ptr()
 
@@ -166,7 +179,7 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
         "dense_bytes": 4 * (w.m * w.n + w.n * L + w.m * L),
     }
     for h in handles[1:]:
-        B.cer_free(h)
+        free(h)
 
     if with_dense:
         Wd = torch.from_numpy(w.W).to(dev)
@@ -199,7 +212,8 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
         del Wd
 
     if with_cpu:
-        A = oracle.encode(w.W, w.codebook, fmt)
+        A = oracle.csr_encode(w.W) if fmt == "csr" else oracle.encode(w.W, w.codebook, fmt)
+        odot = (lambda th: oracle.dot_csr(A, w.X)) if fmt == "csr" else (lambda th: oracle.dot(A, w.X, threads=th))
         cores = min(len(os.sched_getaffinity(0)), 16)
         cpu = {}
         for label, th in (("1", 1), (str(cores), cores)):
@@ -207,7 +221,7 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
             budget = 8.0
             while t_used < budget and reps < 200:
                 t0 = time.perf_counter()
-                oracle.dot(A, w.X, threads=th)
+                odot(th)
                 t_used += time.perf_counter() - t0
                 reps += 1
             cpu[label] = t_used / reps
@@ -222,7 +236,7 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
             "oracle_dense_ms_per_step": t_dense * 1e3,
             "cpu_speedup_over_dense_oracle": t_dense / cpu[str(cores)],
         }
-    B.cer_free(h0)
+    free(h0)
     return out
 
 
@@ -232,7 +246,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="vgg_fc6_L1")
-    ap.add_argument("--format", default="cer", choices=("cer", "cser"))
+    ap.add_argument("--format", default="cer", choices=("cer", "cser", "csr"))
     ap.add_argument("--warm", action="store_true", help="reuse one device copy (cache-resident)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
@@ -260,7 +274,7 @@ def main() -> int:
                                      "k_bar", "k_tilde", "cache_state")},
         "roofline": {"bound": "hbm", "achieved": r["algorithmic_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": r["algorithmic_GBps"] / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "cer_gemv_kernel" if r["L"] == 1 else "cer_gemm_kernel",
+                     "kernel": ("csr" if args.format == "csr" else "cer") + ("_gemv_kernel" if r["L"] == 1 else "_gemm_kernel"),
                      "algorithmic_bytes_per_launch": r["algorithmic_bytes"],
                      "event_us_per_launch": r["event_ms_per_step"] * 1e3},
         "cpu_baseline": r.get("cpu_baseline"),
@@ -281,7 +295,7 @@ def main() -> int:
             names += [f"sweep_K{K}_p{p0}" for K in wl.SWEEP_K for p0 in wl.SWEEP_P0]
         table = []
         for nm in names:
-            for fmt in ("cer", "cser"):
+            for fmt in ("cer", "cser", "csr"):
                 for warm in (False, True):
                     big = nm.startswith("conv")
                     rr = run_one(nm, fmt, 20 if big else 300, 3 if big else 30, warm, False, not warm)

@@ -159,6 +159,25 @@ int dense_matmul(const float* W_dev, const float* X_dev, float* Y_dev, int64_t m
                  int64_t batch, void* stream);
 
 /*
+ * CSR comparator (Section II-A "Sparse format", Algorithm 2): the paper's main sparse baseline in
+ * the same harness.  csr_encode stores the elements different from 0.0 in row-major order (values
+ * fp32, column indices at the minimal 8/16/32-bit width, row pointers; on the device the row
+ * pointers are uint32); csr_matmul computes Y = W.X from them (one multiply-add per stored
+ * element); csr_decode rebuilds the dense matrix (-0.0 comes back as +0.0).  Pointer, layout,
+ * stream and error conventions are those of cer_encode / cer_matmul / cer_decode.
+ * csr_get_array selectors: 0 values (fp32 [nnz]), 1 colI (uint [nnz]), 2 rowPtr (uint [m+1]).
+ */
+typedef struct csr_matrix csr_handle_t; /* opaque */
+int csr_encode(const float* W_host, int64_t m, int64_t n, csr_handle_t** out);
+int csr_matmul(const csr_handle_t* h, const float* X_dev, float* Y_dev, int64_t batch, void* stream);
+int csr_decode(const csr_handle_t* h, float* W_host_out);
+int csr_get_array(const csr_handle_t* h, int which, const void** host_ptr, int64_t* len, int32_t* elem_bits);
+int64_t csr_storage_bits(const csr_handle_t* h);
+int64_t csr_device_bytes(const csr_handle_t* h);
+int csr_clone_device(const csr_handle_t* h, csr_handle_t** out);
+void csr_free(csr_handle_t* h);
+
+/*
  * cer_stream_copy -- plain device-to-device copy of `bytes` bytes (rounded down to a multiple of
  * 16; both pointers 16-byte aligned) by a simple HIP kernel.  A measurement aid: a kernel of
  * exactly known memory traffic against which hardware byte counters (and the attainable copy

@@ -32,6 +32,8 @@ EXPORTS = [
     "cer_encode", "cser_encode", "cer_matmul", "cser_matmul", "cer_decode", "cser_decode",
     "cer_get_array", "cer_get_dims", "cer_storage_bits", "cer_get_stats", "cer_clone_device",
     "cer_device_bytes", "cer_free", "dense_matmul", "cer_stream_copy", "cer_strerror", "cer_last_hip_error",
+    "csr_encode", "csr_matmul", "csr_decode", "csr_get_array", "csr_storage_bits", "csr_device_bytes",
+    "csr_clone_device", "csr_free",
 ]
 
 _lib = None
@@ -82,6 +84,22 @@ def lib() -> ctypes.CDLL:
         L.cer_free.argtypes = [vp]
         L.dense_matmul.restype = ctypes.c_int
         L.dense_matmul.argtypes = [vp, vp, vp, i64, i64, i64, vp]
+        L.csr_encode.restype = ctypes.c_int
+        L.csr_encode.argtypes = [vp, i64, i64, pvp]
+        L.csr_matmul.restype = ctypes.c_int
+        L.csr_matmul.argtypes = [vp, vp, vp, i64, vp]
+        L.csr_decode.restype = ctypes.c_int
+        L.csr_decode.argtypes = [vp, vp]
+        L.csr_get_array.restype = ctypes.c_int
+        L.csr_get_array.argtypes = [vp, ctypes.c_int, pvp, ctypes.POINTER(i64), ctypes.POINTER(i32)]
+        L.csr_storage_bits.restype = i64
+        L.csr_storage_bits.argtypes = [vp]
+        L.csr_device_bytes.restype = i64
+        L.csr_device_bytes.argtypes = [vp]
+        L.csr_clone_device.restype = ctypes.c_int
+        L.csr_clone_device.argtypes = [vp, pvp]
+        L.csr_free.restype = None
+        L.csr_free.argtypes = [vp]
         L.cer_stream_copy.restype = ctypes.c_int
         L.cer_stream_copy.argtypes = [vp, vp, i64, vp]
         L.cer_strerror.restype = ctypes.c_char_p
@@ -231,3 +249,63 @@ def cer_stream_copy(dst, src, nbytes: int, stream=None) -> None:
     def raw(t):
         return t if isinstance(t, int) else t.data_ptr()
     _check(lib().cer_stream_copy(raw(dst), raw(src), nbytes, _stream_ptr(stream)), "cer_stream_copy")
+
+
+class CsrHandle:
+    """Owns one csr_handle_t*."""
+
+    def __init__(self, ptr: int, m: int, n: int):
+        self.ptr, self.m, self.n = ptr, m, n
+
+    def __del__(self):
+        try:
+            csr_free(self)
+        except Exception:
+            pass
+
+
+def csr_encode(W: np.ndarray) -> CsrHandle:
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    out = ctypes.c_void_p()
+    _check(lib().csr_encode(W.ctypes.data, W.shape[0], W.shape[1], ctypes.byref(out)), "csr_encode")
+    return CsrHandle(out.value, W.shape[0], W.shape[1])
+
+
+def csr_matmul(h: CsrHandle, X, Y, batch: int, stream=None) -> None:
+    _check(lib().csr_matmul(h.ptr, _dev_ptr(X), _dev_ptr(Y), batch, _stream_ptr(stream)), "csr_matmul")
+
+
+def csr_decode(h: CsrHandle) -> np.ndarray:
+    W = np.empty((h.m, h.n), np.float32)
+    _check(lib().csr_decode(h.ptr, W.ctypes.data), "csr_decode")
+    return W
+
+
+def csr_get_array(h: CsrHandle, which: int) -> np.ndarray:
+    p, n, bits = ctypes.c_void_p(), ctypes.c_int64(), ctypes.c_int32()
+    _check(lib().csr_get_array(h.ptr, which, ctypes.byref(p), ctypes.byref(n), ctypes.byref(bits)), "csr_get_array")
+    dt = np.float32 if which == 0 else {8: np.uint8, 16: np.uint16, 32: np.uint32}[bits.value]
+    if n.value == 0:
+        return np.empty(0, dt)
+    buf = (ctypes.c_char * (n.value * np.dtype(dt).itemsize)).from_address(p.value)
+    return np.frombuffer(buf, dtype=dt).copy()
+
+
+def csr_storage_bits(h: CsrHandle) -> int:
+    return int(lib().csr_storage_bits(h.ptr))
+
+
+def csr_device_bytes(h: CsrHandle) -> int:
+    return int(lib().csr_device_bytes(h.ptr))
+
+
+def csr_clone_device(h: CsrHandle) -> CsrHandle:
+    out = ctypes.c_void_p()
+    _check(lib().csr_clone_device(h.ptr, ctypes.byref(out)), "csr_clone_device")
+    return CsrHandle(out.value, h.m, h.n)
+
+
+def csr_free(h: CsrHandle) -> None:
+    if h.ptr:
+        lib().csr_free(h.ptr)
+        h.ptr = None

@@ -19,6 +19,15 @@ int hip_fail(hipError_t e) {
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+}  // namespace
+
+int cer::record_hip_error(int hip_error) {
+    g_last_hip_error = hip_error;
+    return CER_E_HIP;
+}
+
+namespace {
+
 std::vector<uint32_t> widen(const cer::HostArray& a) {
     std::vector<uint32_t> out((size_t)a.len);
     for (int64_t i = 0; i < a.len; ++i) out[(size_t)i] = (uint32_t)a.at(i);

@@ -62,6 +62,9 @@ int launch_matmul(const DeviceView& v, const float* X, float* Y, int64_t L, void
 int launch_dense(const float* W, const float* X, float* Y, int64_t m, int64_t n, int64_t L, void* stream);
 int launch_stream_copy(void* dst, const void* src, int64_t bytes, void* stream);
 
+// Remembers a HIP error for cer_last_hip_error() and returns CER_E_HIP (cer_capi.cpp).
+int record_hip_error(int hip_error);
+
 }  // namespace cer
 
 struct cer_matrix {

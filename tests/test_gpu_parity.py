@@ -206,3 +206,35 @@ def test_full_conv_batch3136_sampled(variant):
     w = wl.conv3x3(nonzero_dominant=variant)
     rows = np.random.default_rng(2).choice(w.m, 6, replace=False)
     sampled_check(w, ("cer", "cser"), np.sort(rows))
+
+
+# ------------------------------------------------------------------ CSR comparator (Algorithm 2)
+
+CSR_CASES = {
+    "c1": lambda: wl.config1(),
+    "vgg_s8_L1": lambda: wl.vgg_fc6(L=1, scale=8),
+    "vgg_s8_L64": lambda: wl.vgg_fc6(L=64, scale=8),
+    "alexnet_s8_L32": lambda: wl.alexnet_fc6(L=32, scale=8),
+    "conv_s4_dom_L7": lambda: wl.conv3x3(L=7, nonzero_dominant=True, scale=4),
+    "sweep_K256_p50": lambda: wl.sweep_cell(256, 0.5, L=16, scale=4),
+    "u8_index_L12": lambda: wl.random_lowentropy(m=70, n=250, K=6, p_dom=0.6, L=12, seed=32),
+    "u32_index_L1": lambda: wl.random_lowentropy(m=9, n=70001, K=8, p_dom=0.9, L=1, seed=33),
+    "long_rows_L1": lambda: wl.random_lowentropy(m=20, n=9000, K=8, p_dom=0.3, L=1, seed=42),
+    "ragged_L100": lambda: wl.random_lowentropy(m=67, n=1500, K=16, p_dom=0.8, L=100, seed=43),
+    "all_zero": lambda: wl.random_lowentropy(m=10, n=100, K=1, p_dom=1.0, L=3, seed=38),
+}
+
+
+@pytest.mark.parametrize("name", list(CSR_CASES))
+def test_csr_matmul(name):
+    dev = _gpu()
+    w = CSR_CASES[name]()
+    print(f"csr case {w.name}", flush=True)
+    h = B.csr_encode(w.W)
+    Xd = torch.from_numpy(w.X).to(dev)
+    Yd = torch.full((w.m, w.L), float("nan"), dtype=torch.float32, device=dev)
+    B.csr_matmul(h, Xd, Yd, w.L)
+    torch.cuda.synchronize()
+    want = oracle.dot_csr(oracle.csr_encode(w.W), w.X)
+    check(Yd.cpu().numpy(), want, oracle.abs_dot_dense(w.W, w.X), f"csr {w.name}")
+    B.csr_free(h)

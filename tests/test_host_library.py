@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "cer.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b((?:cer|cser|dense)_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b((?:cer|cser|csr|dense)_[a-z_]+)\s*\(", header))
     assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
     L = B.lib()
     for name in declared:
@@ -124,3 +124,23 @@ def test_edge_cases_and_errors():
     assert B.lib().cer_get_array(h.ptr, 99, None, None, None) == B.CER_E_INVALID
     B.cer_free(h)
     B.cer_free(h)  # second free of the wrapper is a no-op
+
+
+def test_csr_comparator_host_side(example):
+    M = example["M"].astype(np.float32)
+    h = B.csr_encode(M)
+    assert B.csr_get_array(h, 0).tolist() == example["csr_W"].tolist()
+    assert B.csr_get_array(h, 1).tolist() == example["csr_colI"].tolist()
+    assert B.csr_get_array(h, 2).tolist() == example["csr_rowPtr"].tolist()
+    assert sum(len(B.csr_get_array(h, k)) for k in range(3)) == 62
+    assert B.csr_decode(h).tobytes() == M.tobytes()
+    w = wl.alexnet_fc6(L=1, scale=16)
+    h = B.csr_encode(w.W)
+    C = oracle.csr_encode(w.W)
+    assert B.csr_get_array(h, 0).tobytes() == C.val.tobytes()
+    assert np.array_equal(B.csr_get_array(h, 1).astype(np.int64), C.colI)
+    assert np.array_equal(B.csr_get_array(h, 2).astype(np.int64), C.rowPtr)
+    assert B.csr_decode(h).tobytes() == w.W.tobytes()
+    nnz = len(C.val)
+    assert B.csr_storage_bits(h) == nnz * 32 + nnz * oracle.min_bits(w.n - 1) + (w.m + 1) * oracle.min_bits(nnz)
+    B.csr_free(h)
