@@ -178,6 +178,31 @@ int csr_clone_device(const csr_handle_t* h, csr_handle_t** out);
 void csr_free(csr_handle_t* h);
 
 /*
+ * Cost model (host-side analytics; Sections II-B, III and V): elementary operations of ONE
+ * matrix-vector product (batch 1) per format, the storage of the format, and the energy that
+ * Table I (45 nm CMOS, pJ) assigns to those operations -- reads and writes priced by the width of
+ * the value and the size of the array that holds it, 32-bit float add 0.9 pJ, mul 3.7 pJ.
+ *   CER_COUNT_THEOREM  counts as Eq. (2), (4), (10), (12) price them (proofs of Theorems 1, 2)
+ *   CER_COUNT_EXAMPLE  the hand count of Section II-B: both ends of a row's pointer range are read
+ *                      and summing k terms costs k - 1 additions (dense 48, CSR 32, CER 24 for the
+ *                      example row)
+ * A non-zero most frequent value adds n input reads, n + m additions, one multiplication and one
+ * Omega read (Appendix A-A1).  Errors: CER_E_INVALID.
+ */
+enum { CER_COUNT_THEOREM = 0, CER_COUNT_EXAMPLE = 1 };
+typedef struct {
+    int64_t read_weight;   /* dense elements / CSR values */
+    int64_t read_omega, read_colI, read_omegaPtr, read_rowPtr, read_omegaI;
+    int64_t read_input;    /* elements of the input vector */
+    int64_t mul, add, write;
+    int64_t storage_bits;
+    double energy_pj;
+} cer_cost_t;
+int cer_cost_model(const cer_handle_t* h, int convention, cer_cost_t* out);
+int csr_cost_model(const csr_handle_t* h, int convention, cer_cost_t* out);
+int dense_cost_model(int64_t m, int64_t n, int convention, cer_cost_t* out);
+
+/*
  * cer_stream_copy -- plain device-to-device copy of `bytes` bytes (rounded down to a multiple of
  * 16; both pointers 16-byte aligned) by a simple HIP kernel.  A measurement aid: a kernel of
  * exactly known memory traffic against which hardware byte counters (and the attainable copy

@@ -33,10 +33,24 @@ EXPORTS = [
     "cer_get_array", "cer_get_dims", "cer_storage_bits", "cer_get_stats", "cer_clone_device",
     "cer_device_bytes", "cer_free", "dense_matmul", "cer_stream_copy", "cer_strerror", "cer_last_hip_error",
     "csr_encode", "csr_matmul", "csr_decode", "csr_get_array", "csr_storage_bits", "csr_device_bytes",
-    "csr_clone_device", "csr_free",
+    "csr_clone_device", "csr_free", "cer_cost_model", "csr_cost_model", "dense_cost_model",
 ]
 
 _lib = None
+
+CER_COUNT_THEOREM, CER_COUNT_EXAMPLE = 0, 1
+
+
+class CostT(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_int64) for k in ("read_weight", "read_omega", "read_colI", "read_omegaPtr", "read_rowPtr",
+                                              "read_omegaI", "read_input", "mul", "add", "write", "storage_bits")] + [
+        ("energy_pj", ctypes.c_double)]
+
+    def as_dict(self) -> dict:
+        d = {k: getattr(self, k) for k, _ in self._fields_}
+        d["reads"] = sum(v for k, v in d.items() if k.startswith("read_"))
+        d["ops"] = d["reads"] + d["mul"] + d["add"] + d["write"]
+        return d
 
 
 class CerError(RuntimeError):
@@ -100,6 +114,12 @@ def lib() -> ctypes.CDLL:
         L.csr_clone_device.argtypes = [vp, pvp]
         L.csr_free.restype = None
         L.csr_free.argtypes = [vp]
+        L.cer_cost_model.restype = ctypes.c_int
+        L.cer_cost_model.argtypes = [vp, ctypes.c_int, ctypes.POINTER(CostT)]
+        L.csr_cost_model.restype = ctypes.c_int
+        L.csr_cost_model.argtypes = [vp, ctypes.c_int, ctypes.POINTER(CostT)]
+        L.dense_cost_model.restype = ctypes.c_int
+        L.dense_cost_model.argtypes = [i64, i64, ctypes.c_int, ctypes.POINTER(CostT)]
         L.cer_stream_copy.restype = ctypes.c_int
         L.cer_stream_copy.argtypes = [vp, vp, i64, vp]
         L.cer_strerror.restype = ctypes.c_char_p
@@ -309,3 +329,21 @@ def csr_free(h: CsrHandle) -> None:
     if h.ptr:
         lib().csr_free(h.ptr)
         h.ptr = None
+
+
+def cer_cost_model(h: Handle, convention: int = CER_COUNT_THEOREM) -> dict:
+    c = CostT()
+    _check(lib().cer_cost_model(h.ptr, convention, ctypes.byref(c)), "cer_cost_model")
+    return c.as_dict()
+
+
+def csr_cost_model(h: CsrHandle, convention: int = CER_COUNT_THEOREM) -> dict:
+    c = CostT()
+    _check(lib().csr_cost_model(h.ptr, convention, ctypes.byref(c)), "csr_cost_model")
+    return c.as_dict()
+
+
+def dense_cost_model(m: int, n: int, convention: int = CER_COUNT_THEOREM) -> dict:
+    c = CostT()
+    _check(lib().dense_cost_model(m, n, convention, ctypes.byref(c)), "dense_cost_model")
+    return c.as_dict()

@@ -18,22 +18,6 @@
 #include "../../include/cer.h"
 #include "cer_internal.hpp"
 
-struct csr_host {
-    int64_t m = 0, n = 0, nnz = 0;
-    std::vector<float> val;
-    cer::HostArray colI, rowPtr;
-};
-
-struct csr_matrix {
-    std::shared_ptr<const csr_host> host;
-    int device = -1;
-    void* d_base = nullptr;
-    const float* d_val = nullptr;
-    const void* d_colI = nullptr;
-    const uint32_t* d_rowPtr = nullptr;
-    int64_t stream_bytes = 0;
-};
-
 namespace {
 
 constexpr int kWave = 64;
