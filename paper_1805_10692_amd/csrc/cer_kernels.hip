@@ -467,6 +467,39 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
 
 constexpr int kGemmGroupTile = 256;  // raw groups turned into one LDS list at a time
 
+// The stream of one tile of groups, colI offsets [ts, te): two batches of U wave instructions are
+// kept in flight (ping-pong) -- while one batch is summed, the gathers of the next and the index
+// loads of the one after are under way.  With kPre the indices of the first two batches (ia, ib)
+// were requested by the caller.
+template <typename IdxT, int V, int P, bool kPre>
+__device__ __forceinline__ void gemm_tile(const IdxT* colI, const float* xgather, uint32_t L, uint32_t ts, uint32_t te,
+                                          uint32_t sub, uint32_t lane, uint32_t (&ia)[8], uint32_t (&ib)[8], UCursor& cur,
+                                          Vec<V>& run, Vec<V>& acc, const uint32_t* ends, const float* wts) {
+    constexpr int S = kWave / P, U = 8;
+    constexpr uint32_t SU = S * U;
+    Vec<V> xa[U], xb[U];
+#define CER_LOAD_IDX(ix, b) \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) ix[u] = (uint32_t)colI[(b) + u * S + sub];
+#define CER_GATHER(xv, ix) \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) xv[u].load(xgather + (size_t)ix[u] * L);
+#define CER_CONSUME(xv, b) \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) cer_step<S, V>(xv[u], sub, (b) + u * S, cur, run, acc, ends, wts, lane);
+    if (!kPre) { CER_LOAD_IDX(ia, ts) }
+    CER_GATHER(xa, ia)
+    if (!kPre) { CER_LOAD_IDX(ib, ts + SU) }
+    for (uint32_t base = ts; base < te; base += 2 * SU) {
+        CER_GATHER(xb, ib)
+        CER_LOAD_IDX(ia, base + 2 * SU)
+        CER_CONSUME(xa, base)
+        CER_GATHER(xa, ia)
+        CER_LOAD_IDX(ib, base + 3 * SU)
+        CER_CONSUME(xb, base + SU)
+    }
+#undef CER_LOAD_IDX
+#undef CER_GATHER
+#undef CER_CONSUME
+}
+
 // V floats per lane, P lanes per index: one wave instruction gathers 64/P rows of X, each
 // V.P floats wide.  Workgroup = 4 waves = 4 consecutive rows of one batch tile.
 template <typename IdxT, int V, int P>
@@ -499,47 +532,53 @@ __global__ __launch_bounds__(256) void cer_gemm_kernel(KView v, const float* __r
     uint32_t* ends = s_ends[wave];
     float* wts = s_wts[wave];
 
-    const uint2 d0 = v.rowInfo[r], d1 = v.rowInfo[r + 1];
+    const uint2 d0 = v.rowInfo[r], d1 = v.rowInfo[r + 1];  // scalar loads: r is wave-uniform
     const uint32_t g0 = d0.x, rs = d0.y, g1 = d1.x, re = d1.y;
-    Vec<V> acc;
+    // Everything the first tile needs is requested at once -- 64 group pointers, Omega by lane, the
+    // indices of the first two batches -- so that their latencies overlap instead of adding up.
+    const bool cser = v.cser != 0;
+    const uint32_t tg_end0 = min(g1, g0 + (uint32_t)kGemmGroupTile);
+    const PtrTile pt0 = load_ptr_tile(v, cser, g0, g0, min(tg_end0, g0 + (uint32_t)kWave), lane);
+    const float om_l = v.omega[lane < v.K ? lane : 0u];
+    uint32_t ia[U], ib[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) ia[u] = (uint32_t)colI[rs + u * S + sub];
+#pragma unroll
+    for (int u = 0; u < U; ++u) ib[u] = (uint32_t)colI[rs + (U + u) * S + sub];
+
+    Vec<V> acc, run;
     acc.zero();
-    const PtrTile none{0u, 0u, 0u};
-    for (uint32_t tg = g0; tg < g1; tg += kGemmGroupTile) {
-        const uint32_t tg_end = min(g1, tg + kGemmGroupTile);
-        const uint32_t ts = (tg == g0) ? rs : uniform(v.omegaPtr[tg]);
-        const uint32_t te = (tg_end == g1) ? re : uniform(v.omegaPtr[tg_end]);
-        const int count = list_build(v, v.cser != 0, v.omega, g0, tg, tg_end, false, none, ends, wts, lane);
+    UCursor cur;
+    if (g1 > g0) {
+        const uint32_t te = (tg_end0 == g1) ? re : uniform(v.omegaPtr[tg_end0]);
+        int count;
+        if (v.K <= (uint32_t)kWave && tg_end0 - g0 <= (uint32_t)kWave) {  // values looked up by lane shuffle
+            count = list_append(pt0, __shfl(om_l, (int)(pt0.rank & 63u), kWave) - v.omega0, ends, wts, 0);
+            list_close(ends, wts, count, lane);
+        } else {
+            count = list_build(v, cser, v.omega, g0, g0, tg_end0, true, pt0, ends, wts, lane);
+        }
         wave_lds_sync();
         if (count > 0) {
-            UCursor cur;
             ucursor_start(cur, ends, wts, count, lane);
-            Vec<V> run;
             run.zero();
-            // Two batches of U wave instructions are kept in flight (ping-pong): while one batch is
-            // summed, the gathers of the next and the index loads of the one after are under way.
-            constexpr uint32_t SU = S * U;
-            uint32_t ia[U], ib[U];
-            Vec<V> xa[U], xb[U];
-#define CER_LOAD_IDX(ix, b) \
-    _Pragma("unroll") for (int u = 0; u < U; ++u) ix[u] = (uint32_t)colI[(b) + u * S + sub];
-#define CER_GATHER(xv, ix) \
-    _Pragma("unroll") for (int u = 0; u < U; ++u) xv[u].load(xgather + (size_t)ix[u] * L);
-#define CER_CONSUME(xv, b) \
-    _Pragma("unroll") for (int u = 0; u < U; ++u) cer_step<S, V>(xv[u], sub, (b) + u * S, cur, run, acc, ends, wts, lane);
-            CER_LOAD_IDX(ia, ts)
-            CER_GATHER(xa, ia)
-            CER_LOAD_IDX(ib, ts + SU)
-            for (uint32_t base = ts; base < te; base += 2 * SU) {
-                CER_GATHER(xb, ib)
-                CER_LOAD_IDX(ia, base + 2 * SU)
-                CER_CONSUME(xa, base)
-                CER_GATHER(xa, ia)
-                CER_LOAD_IDX(ib, base + 3 * SU)
-                CER_CONSUME(xb, base + SU)
-            }
-#undef CER_LOAD_IDX
-#undef CER_GATHER
-#undef CER_CONSUME
+            gemm_tile<IdxT, V, P, true>(colI, xgather, L, rs, te, sub, lane, ia, ib, cur, run, acc, ends, wts);
+            acc.fma(run, cur.w);
+        }
+        wave_lds_sync();
+    }
+    // rows with more raw groups than one list holds: further tiles
+    for (uint32_t tg = g0 + kGemmGroupTile; tg < g1; tg += kGemmGroupTile) {
+        const uint32_t tg_end = min(g1, tg + kGemmGroupTile);
+        const uint32_t ts = uniform(v.omegaPtr[tg]);
+        const uint32_t te = (tg_end == g1) ? re : uniform(v.omegaPtr[tg_end]);
+        const int count = list_build(v, cser, v.omega, g0, tg, tg_end, false, pt0, ends, wts, lane);
+        wave_lds_sync();
+        if (count > 0) {
+            ucursor_start(cur, ends, wts, count, lane);
+            run.zero();
+            uint32_t ja[U], jb[U];
+            gemm_tile<IdxT, V, P, false>(colI, xgather, L, ts, te, sub, lane, ja, jb, cur, run, acc, ends, wts);
             acc.fma(run, cur.w);
         }
         wave_lds_sync();
