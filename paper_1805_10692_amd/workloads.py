@@ -190,6 +190,20 @@ def random_lowentropy(m: int, n: int, K: int, p_dom: float, L: int, seed: int,
     return Workload(f"rand_{m}x{n}_K{K}_p{p_dom:.2f}_L{L}_s{seed}", W, cb, X, pmf, seed)
 
 
+def dense_weights(m: int, n: int, seed: int = 5, outliers: float = 1e-4, sigma: float = 0.01,
+                  tail: float = 5.0) -> np.ndarray:
+    """Unquantized fp32 weights for the quantizer front-end (Section V-B): a Laplace body of scale
+    `sigma` with a fraction `outliers` of elements drawn `tail` times wider, the heavy tail that makes
+    the range of a trained layer several times its bulk.  Stands in for a trained layer's weights."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    W = rng.laplace(0.0, sigma, size=(m, n)).astype(np.float32)
+    if outliers > 0 and W.size:
+        k = max(1, int(round(outliers * W.size)))
+        pos = rng.integers(0, W.size, size=k)
+        W.reshape(-1)[pos] = rng.laplace(0.0, tail * sigma, size=k).astype(np.float32)
+    return W
+
+
 def describe(pmf: np.ndarray) -> dict:
     return {"H_bits": entropy_bits(pmf), "p_max": float(pmf.max()), "K": int(len(pmf)),
             "min_entropy_bits": -math.log2(float(pmf.max()))}
