@@ -203,6 +203,41 @@ int csr_cost_model(const csr_handle_t* h, int convention, cer_cost_t* out);
 int dense_cost_model(int64_t m, int64_t n, int convention, cer_cost_t* out);
 
 /*
+ * Device front-end -- for a weight matrix that already lives in GPU memory (Section V-B: weights
+ * are quantized, then converted losslessly into the format).
+ *
+ * cer_encode_device: as cer_encode / cser_encode, but W_dev is a DEVICE pointer to the row-major
+ * m x n fp32 matrix (borrowed for the call, never written) and the whole conversion runs in HIP
+ * kernels on `stream`; only the encoded arrays travel to the host (the handle's host mirror).
+ * `codebook` is a HOST array of K <= 256 values (CER_E_TOO_LARGE above that); `format` is
+ * CER_FORMAT_CER or CER_FORMAT_CSER.  The handle is identical, array for array and bit for bit, to
+ * the one cer_encode / cser_encode builds from the same matrix.  The call returns after the stream
+ * has drained.  Errors: those of cer_encode, CER_E_HIP (also: no device).
+ *
+ * cer_quantize_uniform: the uniform quantizer.  Takes the range [w_min, w_max] of the `count`
+ * elements at W_dev, places K = 2^bits (1 <= bits <= 8) equidistant points on it, both ends
+ * included, and maps every element to its nearest point.  All arithmetic is IEEE binary32 with one
+ * rounding per operation: step = (w_max - w_min) / (K - 1); point_j = w_min + j.step (the last
+ * point is w_max itself); code = clamp(round_half_even((w - w_min) / step), 0, K - 1).  A constant
+ * array has the single point w_min (K = 1).  Outputs, each optional (NULL): codes_dev (device,
+ * one byte per element), Wq_dev (device, fp32, the quantized values; must not overlap W_dev),
+ * codebook_out (host, room for 2^bits floats), K_out (host).  Returns after the stream has
+ * drained.  Errors: CER_E_INVALID (null W_dev, bits out of range, count < 0, NaN or infinite
+ * weight), CER_E_BAD_CODEBOOK (range so narrow that two points coincide), CER_E_HIP.
+ *
+ * cer_quantize_encode_device: both steps in one call; the quantized matrix is never materialised
+ * in fp32.  Same result as cer_quantize_uniform followed by cer_encode_device on Wq_dev with the
+ * returned codebook.
+ */
+enum { CER_FORMAT_CER = 0, CER_FORMAT_CSER = 1 };
+int cer_encode_device(const float* W_dev, int64_t m, int64_t n, const float* codebook, int32_t K,
+                      int32_t format, void* stream, cer_handle_t** out);
+int cer_quantize_uniform(const float* W_dev, int64_t count, int32_t bits, uint8_t* codes_dev,
+                         float* Wq_dev, float* codebook_out, int32_t* K_out, void* stream);
+int cer_quantize_encode_device(const float* W_dev, int64_t m, int64_t n, int32_t bits, int32_t format,
+                               void* stream, float* codebook_out, int32_t* K_out, cer_handle_t** out);
+
+/*
  * cer_stream_copy -- plain device-to-device copy of `bytes` bytes (rounded down to a multiple of
  * 16; both pointers 16-byte aligned) by a simple HIP kernel.  A measurement aid: a kernel of
  * exactly known memory traffic against which hardware byte counters (and the attainable copy

@@ -34,7 +34,10 @@ EXPORTS = [
     "cer_device_bytes", "cer_free", "dense_matmul", "cer_stream_copy", "cer_strerror", "cer_last_hip_error",
     "csr_encode", "csr_matmul", "csr_decode", "csr_get_array", "csr_storage_bits", "csr_device_bytes",
     "csr_clone_device", "csr_free", "cer_cost_model", "csr_cost_model", "dense_cost_model",
+    "cer_encode_device", "cer_quantize_uniform", "cer_quantize_encode_device",
 ]
+
+CER_FORMAT_CER, CER_FORMAT_CSER = 0, 1
 
 _lib = None
 
@@ -120,6 +123,12 @@ def lib() -> ctypes.CDLL:
         L.csr_cost_model.argtypes = [vp, ctypes.c_int, ctypes.POINTER(CostT)]
         L.dense_cost_model.restype = ctypes.c_int
         L.dense_cost_model.argtypes = [i64, i64, ctypes.c_int, ctypes.POINTER(CostT)]
+        L.cer_encode_device.restype = ctypes.c_int
+        L.cer_encode_device.argtypes = [vp, i64, i64, vp, i32, i32, vp, pvp]
+        L.cer_quantize_uniform.restype = ctypes.c_int
+        L.cer_quantize_uniform.argtypes = [vp, i64, i32, vp, vp, vp, ctypes.POINTER(i32), vp]
+        L.cer_quantize_encode_device.restype = ctypes.c_int
+        L.cer_quantize_encode_device.argtypes = [vp, i64, i64, i32, i32, vp, vp, ctypes.POINTER(i32), pvp]
         L.cer_stream_copy.restype = ctypes.c_int
         L.cer_stream_copy.argtypes = [vp, vp, i64, vp]
         L.cer_strerror.restype = ctypes.c_char_p
@@ -183,6 +192,48 @@ def cer_encode(W: np.ndarray, codebook: np.ndarray) -> Handle:
 
 def cser_encode(W: np.ndarray, codebook: np.ndarray) -> Handle:
     return _encode("cser_encode", W, codebook)
+
+
+def _fmt_code(fmt: str) -> int:
+    if fmt not in ("cer", "cser"):
+        raise ValueError("format must be 'cer' or 'cser'")
+    return CER_FORMAT_CSER if fmt == "cser" else CER_FORMAT_CER
+
+
+def cer_encode_device(W, m: int, n: int, codebook: np.ndarray, fmt: str = "cer", stream=None) -> Handle:
+    """W: fp32 device tensor (m x n, row-major) whose elements are codebook values."""
+    cb = np.ascontiguousarray(codebook, dtype=np.float32)
+    out = ctypes.c_void_p()
+    rc = lib().cer_encode_device(_dev_ptr(W) if m * n else 0, m, n, cb.ctypes.data, len(cb), _fmt_code(fmt),
+                                 _stream_ptr(stream), ctypes.byref(out))
+    _check(rc, "cer_encode_device")
+    return Handle(out.value, fmt)
+
+
+def cer_quantize_uniform(W, count: int, bits: int, codes=None, Wq=None, stream=None) -> np.ndarray:
+    """Quantizes `count` fp32 device elements; fills the optional device tensors `codes` (uint8) and
+    `Wq` (fp32) and returns the codebook."""
+    cb = np.zeros(1 << max(bits, 0), np.float32)
+    K = ctypes.c_int32(0)
+    if codes is not None and (not codes.is_cuda or codes.dtype.itemsize != 1 or not codes.is_contiguous()):
+        raise ValueError("codes must be a contiguous uint8 tensor in device memory")
+    rc = lib().cer_quantize_uniform(_dev_ptr(W) if count else 0, count, bits,
+                                    codes.data_ptr() if codes is not None else 0,
+                                    _dev_ptr(Wq) if Wq is not None else 0, cb.ctypes.data, ctypes.byref(K),
+                                    _stream_ptr(stream))
+    _check(rc, "cer_quantize_uniform")
+    return cb[:K.value].copy()
+
+
+def cer_quantize_encode_device(W, m: int, n: int, bits: int, fmt: str = "cer", stream=None):
+    """Unquantized fp32 device tensor -> (handle, codebook)."""
+    cb = np.zeros(1 << max(bits, 0), np.float32)
+    K = ctypes.c_int32(0)
+    out = ctypes.c_void_p()
+    rc = lib().cer_quantize_encode_device(_dev_ptr(W) if m * n else 0, m, n, bits, _fmt_code(fmt), _stream_ptr(stream),
+                                          cb.ctypes.data, ctypes.byref(K), ctypes.byref(out))
+    _check(rc, "cer_quantize_encode_device")
+    return Handle(out.value, fmt), cb[:K.value].copy()
 
 
 def cer_matmul(h: Handle, X, Y, batch: int, stream=None) -> None:

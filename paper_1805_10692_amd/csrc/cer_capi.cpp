@@ -34,9 +34,50 @@ std::vector<uint32_t> widen(const cer::HostArray& a) {
     return out;
 }
 
-// One allocation: [colI | 8 KiB pad][OmegaPtr u32][rowPtr u32][OmegaI][Omega][row descriptors], each 256-byte
-// aligned.  The row descriptors {rowPtr[r], OmegaPtr[rowPtr[r]]} are derived from the format arrays: they let a
-// wave find its row's slice of colI with one load instead of two dependent ones.
+}  // namespace
+
+cer::DeviceLayout cer::DeviceLayout::make(size_t colI_bytes, int64_t G, int64_t m, size_t omegaI_bytes, int32_t K) {
+    DeviceLayout l;
+    l.colI_bytes = colI_bytes;
+    l.omegaI_bytes = omegaI_bytes;
+    l.off_colI = 0;
+    l.off_optr = align_up(l.off_colI + colI_bytes + 8192, 256);  // the product reads ahead of a row's end
+    l.off_rptr = align_up(l.off_optr + (size_t)(G + 1) * 4 + 16, 256);
+    l.off_oi = align_up(l.off_rptr + (size_t)(m + 1) * 4 + 16, 256);
+    l.off_om = align_up(l.off_oi + omegaI_bytes + 16, 256);
+    l.off_ri = align_up(l.off_om + (size_t)std::max(K, 1) * 4, 256);
+    l.total = align_up(l.off_ri + (size_t)(m + 1) * 8, 256);
+    return l;
+}
+
+void cer::bind_device(cer_matrix* h, int dev, void* base, const DeviceLayout& l) {
+    const HostMatrix& A = *h->host;
+    auto* b = static_cast<unsigned char*>(base);
+    h->device = dev;
+    h->d_base = base;
+    h->d_bytes = l.total;
+    h->stream_bytes = (int64_t)(l.colI_bytes + (size_t)(A.G + 1) * 4 + (size_t)(A.m + 1) * 4 + l.omegaI_bytes +
+                                A.omega.size() * 4);
+    DeviceView& v = h->view;
+    v.colI = b + l.off_colI;
+    v.omegaPtr = reinterpret_cast<const uint32_t*>(b + l.off_optr);
+    v.rowPtr = reinterpret_cast<const uint32_t*>(b + l.off_rptr);
+    v.omegaI = b + l.off_oi;
+    v.omega = reinterpret_cast<const float*>(b + l.off_om);
+    v.rowInfo = b + l.off_ri;
+    v.colI_bits = A.colI.bits;
+    v.omegaI_bits = A.omegaI.bits;
+    v.cser = A.cser ? 1 : 0;
+    v.K = A.K;
+    v.m = A.m;
+    v.n = A.n;
+    v.max_row_groups = A.max_row_groups;
+    v.omega0 = A.K > 0 ? A.omega[0] : 0.f;
+}
+
+namespace {
+
+// Copies the host arrays into one fresh device allocation (layout: cer::DeviceLayout).
 int upload(cer_matrix* h) {
     const cer::HostMatrix& A = *h->host;
     int ndev = 0;
@@ -49,64 +90,37 @@ int upload(cer_matrix* h) {
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return hip_fail(e);
 
-    const size_t colI_bytes = A.colI.bytes.size();
-    const size_t off_colI = 0;
-    const size_t off_optr = align_up(off_colI + colI_bytes + 8192, 256);  // the product reads ahead of a row's end
-    const size_t off_rptr = align_up(off_optr + (size_t)(A.G + 1) * 4 + 16, 256);
-    const size_t off_oi = align_up(off_rptr + (size_t)(A.m + 1) * 4 + 16, 256);
-    const size_t off_om = align_up(off_oi + A.omegaI.bytes.size() + 16, 256);
-    const size_t off_ri = align_up(off_om + (size_t)std::max(A.K, 1) * 4, 256);
-    const size_t total = align_up(off_ri + (size_t)(A.m + 1) * 8, 256);
-
+    const cer::DeviceLayout l = cer::DeviceLayout::make(A.colI.bytes.size(), A.G, A.m, A.omegaI.bytes.size(), A.K);
     void* base = nullptr;
-    e = hipMalloc(&base, total);
+    e = hipMalloc(&base, l.total);
     if (e != hipSuccess) return hip_fail(e);
     auto* b = static_cast<unsigned char*>(base);
-    e = hipMemset(base, 0, total);
+    e = hipMemset(base, 0, l.total);
     auto put = [&](size_t off, const void* src, size_t bytes) {
         if (e == hipSuccess && bytes) e = hipMemcpy(b + off, src, bytes, hipMemcpyHostToDevice);
     };
-    put(off_colI, A.colI.bytes.data(), colI_bytes);
+    put(l.off_colI, A.colI.bytes.data(), l.colI_bytes);
     {
         std::vector<uint32_t> w = widen(A.omegaPtr);
-        put(off_optr, w.data(), w.size() * 4);
+        put(l.off_optr, w.data(), w.size() * 4);
     }
     {
         std::vector<uint32_t> w = widen(A.rowPtr);
-        put(off_rptr, w.data(), w.size() * 4);
+        put(l.off_rptr, w.data(), w.size() * 4);
         std::vector<uint32_t> info((size_t)(A.m + 1) * 2);
         for (int64_t r = 0; r <= A.m; ++r) {
             info[(size_t)r * 2] = w[(size_t)r];
             info[(size_t)r * 2 + 1] = (uint32_t)A.omegaPtr.at((int64_t)w[(size_t)r]);
         }
-        put(off_ri, info.data(), info.size() * 4);
+        put(l.off_ri, info.data(), info.size() * 4);
     }
-    put(off_oi, A.omegaI.bytes.data(), A.omegaI.bytes.size());
-    put(off_om, A.omega.data(), A.omega.size() * 4);
+    put(l.off_oi, A.omegaI.bytes.data(), l.omegaI_bytes);
+    put(l.off_om, A.omega.data(), A.omega.size() * 4);
     if (e != hipSuccess) {
         (void)hipFree(base);
         return hip_fail(e);
     }
-    h->device = dev;
-    h->d_base = base;
-    h->d_bytes = total;
-    h->stream_bytes = (int64_t)(colI_bytes + (size_t)(A.G + 1) * 4 + (size_t)(A.m + 1) * 4 + A.omegaI.bytes.size() +
-                                A.omega.size() * 4);
-    cer::DeviceView& v = h->view;
-    v.colI = b + off_colI;
-    v.omegaPtr = reinterpret_cast<const uint32_t*>(b + off_optr);
-    v.rowPtr = reinterpret_cast<const uint32_t*>(b + off_rptr);
-    v.omegaI = b + off_oi;
-    v.omega = reinterpret_cast<const float*>(b + off_om);
-    v.rowInfo = b + off_ri;
-    v.colI_bits = A.colI.bits;
-    v.omegaI_bits = A.omegaI.bits;
-    v.cser = A.cser ? 1 : 0;
-    v.K = A.K;
-    v.m = A.m;
-    v.n = A.n;
-    v.max_row_groups = A.max_row_groups;
-    v.omega0 = A.K > 0 ? A.omega[0] : 0.f;
+    cer::bind_device(h, dev, base, l);
     return CER_OK;
 }
 
@@ -255,6 +269,57 @@ int cer_clone_device(const cer_handle_t* h, cer_handle_t** out) {
         *out = c;
         return CER_OK;
     } catch (const std::bad_alloc&) {
+        return CER_E_NOMEM;
+    }
+}
+
+static int device_front_end(const float* W, int64_t m, int64_t n, const float* codebook, int32_t K, int32_t bits,
+                            int32_t format, void* stream, float* codebook_out, int32_t* K_out, cer_handle_t** out) {
+    if (!out) return CER_E_INVALID;
+    *out = nullptr;
+    if (K_out) *K_out = 0;
+    if (m < 0 || n < 0 || (format != CER_FORMAT_CER && format != CER_FORMAT_CSER)) return CER_E_INVALID;
+    if (m > 0 && n > 0 && !W) return CER_E_INVALID;
+    if (m > 0x7FFFFFFFll || n > (int64_t)0xFFFFFFFFll) return CER_E_TOO_LARGE;
+    const bool cser = format == CER_FORMAT_CSER;
+    if (m == 0 || n == 0) return encode_any(nullptr, m, n, codebook, bits > 0 ? 0 : K, cser, out);  // nothing to read
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) {
+        (void)hipGetLastError();
+        return hip_fail(hipErrorNoDevice);
+    }
+    try {
+        return cer::encode_device(W, m, n, codebook, K, bits, cser, stream, codebook_out, K_out, out);
+    } catch (const std::bad_alloc&) {
+        return CER_E_NOMEM;
+    } catch (...) {
+        return CER_E_INVALID;
+    }
+}
+
+int cer_encode_device(const float* W, int64_t m, int64_t n, const float* codebook, int32_t K, int32_t format, void* stream,
+                      cer_handle_t** out) {
+    if (K < 0 || (K > 0 && !codebook)) return CER_E_INVALID;
+    if (K > 256) return CER_E_TOO_LARGE;
+    if (m > 0 && n > 0 && K == 0) return CER_E_NOT_IN_CODEBOOK;
+    return device_front_end(W, m, n, codebook, K, 0, format, stream, nullptr, nullptr, out);
+}
+
+int cer_quantize_encode_device(const float* W, int64_t m, int64_t n, int32_t bits, int32_t format, void* stream,
+                               float* codebook_out, int32_t* K_out, cer_handle_t** out) {
+    if (bits < 1 || bits > 8) return CER_E_INVALID;
+    return device_front_end(W, m, n, nullptr, 0, bits, format, stream, codebook_out, K_out, out);
+}
+
+int cer_quantize_uniform(const float* W, int64_t count, int32_t bits, uint8_t* codes, float* Wq, float* codebook_out,
+                         int32_t* K_out, void* stream) {
+    if (K_out) *K_out = 0;
+    if (bits < 1 || bits > 8 || count < 0 || (count > 0 && !W)) return CER_E_INVALID;
+    if (count == 0) return CER_OK;
+    if (count > ((int64_t)1 << 42)) return CER_E_TOO_LARGE;
+    try {
+        return cer::quantize_device(W, count, bits, codes, Wq, codebook_out, K_out, stream);
+    } catch (...) {
         return CER_E_NOMEM;
     }
 }

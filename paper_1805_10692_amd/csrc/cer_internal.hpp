@@ -5,6 +5,8 @@
 #include <memory>
 #include <vector>
 
+struct cer_matrix;
+
 namespace cer {
 
 // One index array of the format, kept on the host at its minimal width (Section V).
@@ -51,6 +53,15 @@ struct DeviceView {
     float omega0 = 0.f;
 };
 
+// The handle's single device allocation: [colI | 8 KiB readable pad][OmegaPtr u32][rowPtr u32][OmegaI][Omega]
+// [row descriptors], each part 256-byte aligned.  The row descriptors {rowPtr[r], OmegaPtr[rowPtr[r]]} are derived
+// from the format arrays: they let a wave find its row's slice of colI with one load instead of two dependent ones.
+struct DeviceLayout {
+    size_t colI_bytes = 0, omegaI_bytes = 0;
+    size_t off_colI = 0, off_optr = 0, off_rptr = 0, off_oi = 0, off_om = 0, off_ri = 0, total = 0;
+    static DeviceLayout make(size_t colI_bytes, int64_t G, int64_t m, size_t omegaI_bytes, int32_t K);
+};
+
 // Host encoder (cer_host.cpp).  Returns a CER_* code.
 int encode_host(const float* W, int64_t m, int64_t n, const float* codebook, int32_t K, bool cser,
                 std::shared_ptr<HostMatrix>* out);
@@ -62,9 +73,20 @@ int launch_matmul(const DeviceView& v, const float* X, float* Y, int64_t L, void
 int launch_dense(const float* W, const float* X, float* Y, int64_t m, int64_t n, int64_t L, void* stream);
 int launch_stream_copy(void* dst, const void* src, int64_t bytes, void* stream);
 
+// Device front-end (frontend.hip): W_dev holds codebook values, or (bits > 0) unquantized weights.
+int encode_device(const float* W_dev, int64_t m, int64_t n, const float* codebook, int32_t K, int32_t bits, bool cser,
+                  void* stream, float* codebook_out, int32_t* K_out, cer_matrix** out);
+int quantize_device(const float* W_dev, int64_t count, int32_t bits, uint8_t* codes_dev, float* Wq_dev,
+                    float* codebook_out, int32_t* K_out, void* stream);
+
 // Remembers a HIP error for cer_last_hip_error() and returns CER_E_HIP (cer_capi.cpp).
 int record_hip_error(int hip_error);
 
+}  // namespace cer
+
+namespace cer {
+// Points h's view into `base`, an allocation laid out by `l` that already holds h->host's arrays (cer_capi.cpp).
+void bind_device(cer_matrix* h, int dev, void* base, const DeviceLayout& l);
 }  // namespace cer
 
 struct cer_matrix {

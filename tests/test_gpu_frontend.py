@@ -1,0 +1,195 @@
+"""GPU parity of the device front-end (uniform quantizer of Section V-B, device-side CER / CSER
+encoder) against the CPU oracle, through the C ABI.  Everything here is integer / byte work, so the
+bar is bit-exact: codes, codebook bit patterns, and every array of the encoded handle."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import quantizer as oq
+from paper_1805_10692_amd import binding as B
+from paper_1805_10692_amd import workloads as wl
+from test_host_library import _compare
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+def _gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: GPU parity tests need a real MI355X")
+    return torch.device("cuda:0")
+
+
+def _to_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(_gpu())
+
+
+def _check_product(h, fmt, W, X):
+    A_scale = oracle.abs_dot_dense(W, X, threads=8)
+    want = oracle.dot_dense(W, X, threads=8)
+    Yd = torch.full((W.shape[0], X.shape[1]), float("nan"), dtype=torch.float32, device=_gpu())
+    (B.cer_matmul if fmt == "cer" else B.cser_matmul)(h, _to_dev(X), Yd, X.shape[1])
+    torch.cuda.synchronize()
+    Y = Yd.cpu().numpy().astype(np.float64)
+    assert np.isfinite(Y).all()
+    assert np.all(np.abs(Y - want) <= TOL * A_scale)
+
+
+ENCODE_CASES = {
+    "c1": lambda: wl.config1(),
+    "alexnet_s8": lambda: wl.alexnet_fc6(L=2, scale=8),
+    "vgg_s8": lambda: wl.vgg_fc6(L=1, scale=8),
+    "sweep_K256_p99": lambda: wl.sweep_cell(256, 0.99, L=3, scale=4),
+    "sweep_K256_p50": lambda: wl.sweep_cell(256, 0.5, L=3, scale=4),
+    "sweep_K2_p70": lambda: wl.sweep_cell(2, 0.7, L=3, scale=4),
+    "conv_s4": lambda: wl.conv3x3(L=5, scale=4),
+    "conv_s4_dom": lambda: wl.conv3x3(L=5, nonzero_dominant=True, scale=4),
+    "u8_index": lambda: wl.random_lowentropy(m=70, n=250, K=6, p_dom=0.6, L=1, seed=31),
+    "u32_index": lambda: wl.random_lowentropy(m=9, n=70001, K=8, p_dom=0.9, L=2, seed=33),
+    "one_row": lambda: wl.random_lowentropy(m=1, n=3000, K=16, p_dom=0.7, L=1, seed=36),
+    "one_col": lambda: wl.random_lowentropy(m=300, n=1, K=3, p_dom=0.5, L=4, seed=37),
+    "constant": lambda: wl.random_lowentropy(m=10, n=100, K=1, p_dom=1.0, L=3, seed=38),
+    "ragged_63": lambda: wl.random_lowentropy(m=131, n=63, K=9, p_dom=0.4, L=2, seed=41),
+    "ragged_65": lambda: wl.random_lowentropy(m=5, n=65, K=200, p_dom=0.2, L=2, seed=42, ratio=0.99),
+    "K256_flat": lambda: wl.random_lowentropy(m=37, n=1999, K=256, p_dom=0.05, L=2, seed=43, ratio=0.999),
+}
+
+
+@pytest.mark.parametrize("fmt", ["cer", "cser"])
+@pytest.mark.parametrize("name", list(ENCODE_CASES))
+def test_encode_device_matches_oracle(name, fmt):
+    w = ENCODE_CASES[name]()
+    print(f"case {w.name} {fmt} m={w.m} n={w.n}", flush=True)
+    A = oracle.encode(w.W, w.codebook, fmt)
+    h = B.cer_encode_device(_to_dev(w.W), w.m, w.n, w.codebook, fmt)
+    _compare(h, A)
+    assert np.array_equal((B.cer_decode if fmt == "cer" else B.cser_decode)(h).view(np.uint32),
+                          (w.W + np.float32(0)).view(np.uint32))
+    _check_product(h, fmt, w.W, w.X)
+    B.cer_free(h)
+
+
+def test_encode_device_rows_without_entries_and_ties():
+    """Rows that hold only the most frequent value, a row whose single entry has the highest rank
+    (CER pads it with repeated pointers), and two values with equal counts (codebook order decides)."""
+    cb = np.array([5.0, 0.0, -1.0, 2.0, 7.0], np.float32)
+    W = np.zeros((9, 130), np.float32)
+    W[1, 3] = 7.0
+    W[1, 100] = 7.0
+    W[4, ::2] = -1.0
+    W[4, 1::2] = 2.0        # -1 and 2 occur 65 times each: -1 comes first (lower codebook position)
+    W[7, 129] = 5.0
+    W[8, 0] = 5.0
+    for fmt in ("cer", "cser"):
+        A = oracle.encode(W, cb, fmt)
+        assert A.omega.tolist() == [0.0, -1.0, 2.0, 5.0, 7.0]   # 5 and 7 tie as well: 5 is earlier in the codebook
+        h = B.cer_encode_device(_to_dev(W), 9, 130, cb, fmt)
+        _compare(h, A)
+        B.cer_free(h)
+
+
+@pytest.mark.parametrize("bits", [1, 2, 4, 7, 8])
+@pytest.mark.parametrize("shape", [(37, 1000), (3, 4097), (1, 5), (64, 4096)])
+def test_quantizer_codes_bit_exact(shape, bits):
+    W = wl.dense_weights(*shape, seed=50 + bits)
+    codes, cb = oq.uniform_quantize(W, bits)
+    Wd = _to_dev(W)
+    cd = torch.full((W.size,), 255, dtype=torch.uint8, device=_gpu())
+    Wq = torch.full((W.size,), float("nan"), dtype=torch.float32, device=_gpu())
+    got_cb = B.cer_quantize_uniform(Wd, W.size, bits, cd, Wq)
+    torch.cuda.synchronize()
+    assert got_cb.tobytes() == cb.tobytes()
+    assert np.array_equal(cd.cpu().numpy().astype(np.int64), codes.reshape(-1))
+    assert Wq.cpu().numpy().tobytes() == cb[codes].reshape(-1).tobytes()
+
+
+def test_quantizer_ties_and_exact_grid():
+    """The hand-checkable grid of the oracle's pin: range [0, 7], 3 bits, halves go to the even code."""
+    w = np.array([0.0, 7.0, 0.49, 0.5, 0.51, 1.5, 2.5, 3.5, 2.49, 6.5, 6.51, 5.5, 4.5, 3.0, 1.0, 6.99], np.float32)
+    cd = torch.zeros(w.size, dtype=torch.uint8, device=_gpu())
+    cb = B.cer_quantize_uniform(_to_dev(w), w.size, 3, cd)
+    assert cb.tolist() == [0, 1, 2, 3, 4, 5, 6, 7]
+    assert cd.cpu().tolist() == [0, 7, 0, 0, 1, 2, 2, 4, 2, 6, 7, 6, 4, 3, 1, 7]
+    assert cd.cpu().tolist() == oq.uniform_quantize(w, 3)[0].tolist()
+
+
+@pytest.mark.parametrize("fmt", ["cer", "cser"])
+@pytest.mark.parametrize("shape,bits", [((64, 1152), 7), ((131, 777), 4), ((40, 300), 8), ((12, 70000), 5), ((5, 200), 1)])
+def test_quantize_encode_device_matches_oracle(shape, bits, fmt):
+    W = wl.dense_weights(*shape, seed=60 + bits)
+    codes, cb = oq.uniform_quantize(W, bits)
+    Wq = cb[codes]
+    A = oracle.encode(Wq, cb, fmt)
+    h, got_cb = B.cer_quantize_encode_device(_to_dev(W), shape[0], shape[1], bits, fmt)
+    assert got_cb.tobytes() == cb.tobytes()
+    _compare(h, A)
+    X = wl.sample_X(np.random.Generator(np.random.PCG64(7)), shape[1], 3)
+    _check_product(h, fmt, Wq, X)
+    B.cer_free(h)
+
+
+def test_front_end_degenerate_and_errors():
+    dev = _gpu()
+    # constant matrix: one point, no indices
+    W = np.full((6, 50), 0.125, np.float32)
+    h, cb = B.cer_quantize_encode_device(_to_dev(W), 6, 50, 7, "cer")
+    assert cb.tolist() == [0.125]
+    d = B.cer_get_dims(h)
+    assert (d["K"], d["nnz"], d["groups"]) == (1, 0, 0)
+    _check_product(h, "cer", W, np.ones((50, 2), np.float32))
+    B.cer_free(h)
+    # empty matrices go through without touching the device arrays
+    h = B.cer_encode_device(None, 0, 17, np.array([0.0, 1.0], np.float32), "cser")
+    assert B.cer_get_dims(h)["nnz"] == 0
+    B.cer_free(h)
+    # error codes
+    Wd = _to_dev(np.array([[0.0, 1.0, 3.0]], np.float32))
+    with pytest.raises(B.CerError) as e:
+        B.cer_encode_device(Wd, 1, 3, np.array([0.0, 1.0], np.float32))
+    assert e.value.code == B.CER_E_NOT_IN_CODEBOOK
+    with pytest.raises(B.CerError) as e:
+        B.cer_encode_device(Wd, 1, 3, np.array([0.0, 1.0, 1.0, 3.0], np.float32))
+    assert e.value.code == B.CER_E_BAD_CODEBOOK
+    with pytest.raises(B.CerError) as e:
+        B.cer_encode_device(Wd, 1, 3, np.arange(300, dtype=np.float32))
+    assert e.value.code == B.CER_E_TOO_LARGE
+    bad = _to_dev(np.array([[0.0, np.nan, 3.0]], np.float32))
+    with pytest.raises(B.CerError) as e:
+        B.cer_quantize_encode_device(bad, 1, 3, 4)
+    assert e.value.code == B.CER_E_INVALID
+    with pytest.raises(B.CerError) as e:
+        B.cer_quantize_uniform(bad, 3, 4)
+    assert e.value.code == B.CER_E_INVALID
+    narrow = _to_dev(np.array([[1.0, 1.0 + 8 * 2.0 ** -23]], np.float32))
+    with pytest.raises(B.CerError) as e:
+        B.cer_quantize_encode_device(narrow, 1, 2, 8)
+    assert e.value.code == B.CER_E_BAD_CODEBOOK
+    with pytest.raises(B.CerError) as e:
+        B.cer_quantize_uniform(Wd, 3, 9)
+    assert e.value.code == B.CER_E_INVALID
+    del dev
+
+
+def test_full_size_vgg_fc6_encode_device():
+    """The headline matrix (4096 x 25088, 16 values) converted on the device: every array equals the oracle's."""
+    w = wl.vgg_fc6(L=1)
+    Wd = _to_dev(w.W)
+    for fmt in ("cer", "cser"):
+        print(f"full-size encode {fmt}", flush=True)
+        A = oracle.encode(w.W, w.codebook, fmt)
+        h = B.cer_encode_device(Wd, w.m, w.n, w.codebook, fmt)
+        _compare(h, A)
+        B.cer_free(h)
+
+
+def test_full_size_alexnet_fc6_quantize_encode_device():
+    """An unquantized 4096 x 9216 layer through the 7-bit quantizer and into CER, all on the device."""
+    W = wl.dense_weights(4096, 9216, seed=9)
+    codes, cb = oq.uniform_quantize(W, 7)
+    A = oracle.encode(cb[codes], cb, "cer")
+    h, got_cb = B.cer_quantize_encode_device(_to_dev(W), 4096, 9216, 7, "cer")
+    assert got_cb.tobytes() == cb.tobytes()
+    _compare(h, A)
+    B.cer_free(h)

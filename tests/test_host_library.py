@@ -144,3 +144,17 @@ def test_csr_comparator_host_side(example):
     nnz = len(C.val)
     assert B.csr_storage_bits(h) == nnz * 32 + nnz * oracle.min_bits(w.n - 1) + (w.m + 1) * oracle.min_bits(nnz)
     B.csr_free(h)
+
+
+def test_device_front_end_without_a_device_fails_loudly():
+    """No CPU fallback: with no GPU the device encoder reports a HIP error instead of encoding on the host."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    out = __import__("ctypes").c_void_p()
+    W = np.zeros((2, 2), np.float32)
+    cb = np.zeros(1, np.float32)
+    rc = B.lib().cer_encode_device(W.ctypes.data, 2, 2, cb.ctypes.data, 1, 0, None, __import__("ctypes").byref(out))
+    assert rc == B.CER_E_HIP and not out.value
+    rc = B.lib().cer_encode_device(W.ctypes.data, 2, 2, cb.ctypes.data, 1, 7, None, __import__("ctypes").byref(out))
+    assert rc == B.CER_E_INVALID
