@@ -240,8 +240,78 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
     return out
 
 
+def run_front_end(kind: str, shape: str, fmt: str, bits: int, steps: int, with_cpu: bool) -> dict:
+    """Times the device front-end (not part of the headline metric): `encode` converts an already quantized
+    matrix that lives in HBM, `quantize` takes unquantized weights through the uniform quantizer first.
+    Every call is checked against the oracle's arrays before it is timed."""
+    import torch
+
+    import oracle
+    from oracle import quantizer as oq
+    from paper_1805_10692_amd import binding as B
+    from paper_1805_10692_amd import workloads as wl
+
+    dev = torch.device("cuda:0")
+    if kind == "encode":
+        w = {"vgg_fc6": lambda: wl.vgg_fc6(L=1), "alexnet_fc6": lambda: wl.alexnet_fc6(L=1),
+             "conv3x3": lambda: wl.conv3x3(L=1)}[shape]()
+        W, cb = w.W, w.codebook
+        call = lambda Wd: B.cer_encode_device(Wd, W.shape[0], W.shape[1], cb, fmt)
+        t0 = time.perf_counter()
+        A = oracle.encode(W, cb, fmt)
+        t_cpu = time.perf_counter() - t0
+        passes = 1
+    else:
+        m, n = {"vgg_fc6": (4096, 25088), "alexnet_fc6": (4096, 9216), "conv3x3": (512, 4608)}[shape]
+        W = wl.dense_weights(m, n, seed=9)
+        call = lambda Wd: B.cer_quantize_encode_device(Wd, m, n, bits, fmt)[0]
+        t0 = time.perf_counter()
+        codes, cb = oq.uniform_quantize(W, bits)
+        A = oracle.encode(cb[codes], cb, fmt)
+        t_cpu = time.perf_counter() - t0
+        passes = 2  # the range has to be known before the first element can be quantized
+    m, n = W.shape
+    Wd = torch.from_numpy(W).to(dev)
+    h = call(Wd)
+    for which, name in ((B.CER_ARRAY_COLI, "colI"), (B.CER_ARRAY_OMEGAPTR, "omegaPtr"), (B.CER_ARRAY_ROWPTR, "rowPtr"),
+                        (B.CER_ARRAY_OMEGAI, "omegaI")):
+        got = B.cer_get_array(h, which).astype(np.int64)
+        if fmt == "cer" and name == "omegaI":
+            continue
+        if not np.array_equal(got, getattr(A, name)):
+            raise SystemExit(f"front-end parity failed on {name}")
+    if B.cer_get_array(h, B.CER_ARRAY_OMEGA).tobytes() != A.omega.tobytes():
+        raise SystemExit("front-end parity failed on Omega")
+    enc_bytes = B.cer_device_bytes(h)
+    stats = B.cer_get_stats(h)
+    B.cer_free(h)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        B.cer_free(call(Wd))
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    alg = passes * 4 * m * n + enc_bytes
+    out = {"metric": "front_end_dense_input_GBps", "value": 4 * m * n / dt / 1e9, "unit": "GB/s of fp32 input",
+           "ms_per_step": dt * 1e3, "steps": steps, "n_gpus": 1, "dtype": "f32->u8/u16", "data": "synthetic",
+           "config": {"workload": f"{kind}_{shape}", "format": fmt, "m": m, "n": n, "bits": bits if kind == "quantize" else None,
+                      "K": int(A.K), "H_bits": round(stats["H"], 3), "p0": round(stats["p0"], 4)},
+           "roofline": {"bound": "hbm", "achieved": alg / dt / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": alg / dt / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                        "note": "whole call, host mirror and synchronisation included; per-kernel times in profiles/",
+                        "algorithmic_bytes_per_call": alg}}
+    if with_cpu:
+        out["cpu_baseline"] = {"value": 4 * m * n / t_cpu / 1e9, "unit": "GB/s of fp32 input", "cores": 1,
+                               "kind": "oracle", "sample": "one whole conversion of the same matrix", "ms_per_step": t_cpu * 1e3}
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
+    ap.add_argument("--front-end", default=None, choices=("encode", "quantize"),
+                    help="time the device front-end instead of the product (shape from --shape)")
+    ap.add_argument("--shape", default="vgg_fc6", choices=("vgg_fc6", "alexnet_fc6", "conv3x3"))
+    ap.add_argument("--bits", type=int, default=7)
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
@@ -263,6 +333,12 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
+
+    if args.front_end:
+        fe_steps = args.steps if args.steps != ap.get_default("steps") else 20
+        print(json.dumps(run_front_end(args.front_end, args.shape, "cser" if args.format == "cser" else "cer",
+                                       args.bits, fe_steps, not args.no_cpu)), flush=True)
+        return 0
 
     r = run_one(args.workload, args.format, args.steps, args.warmup, args.warm, not args.no_cpu, not args.no_dense)
     traffic = read_traffic(args.workload, args.format)

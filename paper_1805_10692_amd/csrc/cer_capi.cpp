@@ -73,6 +73,41 @@ void cer::bind_device(cer_matrix* h, int dev, void* base, const DeviceLayout& l)
     v.n = A.n;
     v.max_row_groups = A.max_row_groups;
     v.omega0 = A.K > 0 ? A.omega[0] : 0.f;
+    h->layout = l;
+}
+
+int cer::ensure_host_arrays(const cer_matrix* h) {
+    const HostMatrix& A = *h->host;
+    if (A.arrays_on_host.load(std::memory_order_acquire)) return CER_OK;
+    std::lock_guard<std::mutex> lock(A.fetch_mutex);
+    if (A.arrays_on_host.load(std::memory_order_relaxed)) return CER_OK;
+    if (h->device < 0 || !h->d_base) return CER_E_INVALID;
+    const auto* b = static_cast<const unsigned char*>(h->d_base);
+    const DeviceLayout& l = h->layout;
+    hipError_t e = hipSuccess;
+    auto get = [&](void* dst, size_t off, size_t bytes) {
+        if (e == hipSuccess && bytes) e = hipMemcpy(dst, b + off, bytes, hipMemcpyDeviceToHost);
+    };
+    auto narrow = [](const std::vector<uint32_t>& src, HostArray& dst) {  // dst.len and dst.bits are already set
+        dst.bytes.resize(src.size() * (size_t)(dst.bits / 8));
+        for (size_t i = 0; i < src.size(); ++i) {
+            if (dst.bits == 8) dst.bytes[i] = (uint8_t)src[i];
+            else if (dst.bits == 16) reinterpret_cast<uint16_t*>(dst.bytes.data())[i] = (uint16_t)src[i];
+            else reinterpret_cast<uint32_t*>(dst.bytes.data())[i] = src[i];
+        }
+    };
+    A.colI.bytes.resize(l.colI_bytes);
+    get(A.colI.bytes.data(), l.off_colI, l.colI_bytes);
+    A.omegaI.bytes.resize(l.omegaI_bytes);
+    get(A.omegaI.bytes.data(), l.off_oi, l.omegaI_bytes);
+    std::vector<uint32_t> optr((size_t)A.G + 1), rptr((size_t)A.m + 1);
+    get(optr.data(), l.off_optr, optr.size() * 4);
+    get(rptr.data(), l.off_rptr, rptr.size() * 4);
+    if (e != hipSuccess) return hip_fail(e);
+    narrow(optr, A.omegaPtr);
+    narrow(rptr, A.rowPtr);
+    A.arrays_on_host.store(true, std::memory_order_release);
+    return CER_OK;
 }
 
 namespace {
@@ -171,6 +206,8 @@ int decode_any(const cer_handle_t* h, bool want_cser, float* W_out) {
     if (h->host->cser != want_cser) return CER_E_FORMAT;
     if (!W_out && h->host->m * h->host->n > 0) return CER_E_INVALID;
     try {
+        const int rc = cer::ensure_host_arrays(h);
+        if (rc != CER_OK) return rc;
         return cer::decode_host(*h->host, W_out);
     } catch (...) {
         return CER_E_NOMEM;
@@ -210,6 +247,12 @@ int cer_get_array(const cer_handle_t* h, int which, const void** host_ptr, int64
         case CER_ARRAY_ROWPTR: a = &A.rowPtr; break;
         case CER_ARRAY_OMEGAI: a = &A.omegaI; break;
         default: return CER_E_INVALID;
+    }
+    try {
+        const int rc = cer::ensure_host_arrays(h);
+        if (rc != CER_OK) return rc;
+    } catch (...) {
+        return CER_E_NOMEM;
     }
     *host_ptr = a->bytes.data();
     *len = a->len;
@@ -259,9 +302,11 @@ int cer_clone_device(const cer_handle_t* h, cer_handle_t** out) {
     if (!h || !out) return CER_E_INVALID;
     *out = nullptr;
     try {
+        int rc = cer::ensure_host_arrays(h);
+        if (rc != CER_OK) return rc;
         auto* c = new cer_matrix();
         c->host = h->host;
-        const int rc = upload(c);
+        rc = upload(c);
         if (rc != CER_OK) {
             delete c;
             return rc;

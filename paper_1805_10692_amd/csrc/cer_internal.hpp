@@ -1,8 +1,10 @@
 // Internal declarations shared by the host encoder, the C ABI and the HIP launchers.
 #pragma once
 
+#include <atomic>
 #include <cstdint>
 #include <memory>
+#include <mutex>
 #include <vector>
 
 struct cer_matrix;
@@ -33,7 +35,11 @@ struct HostMatrix {
     int64_t max_row_groups = 0;  // largest number of (raw) groups in one row
     std::vector<float> omega;
     std::vector<int64_t> count;
-    HostArray colI, omegaPtr, rowPtr, omegaI;
+    // len and bits are always set.  A handle encoded on the device leaves `bytes` empty until somebody asks for
+    // the arrays on the host (inspection, decode, clone); they are then copied back once from its device copy.
+    mutable HostArray colI, omegaPtr, rowPtr, omegaI;
+    mutable std::atomic<bool> arrays_on_host{true};
+    mutable std::mutex fetch_mutex;
 };
 
 // What the kernels see: device pointers into the handle's single allocation.
@@ -87,12 +93,16 @@ int record_hip_error(int hip_error);
 namespace cer {
 // Points h's view into `base`, an allocation laid out by `l` that already holds h->host's arrays (cer_capi.cpp).
 void bind_device(cer_matrix* h, int dev, void* base, const DeviceLayout& l);
+// Makes sure h->host holds the index arrays (copies them back from h's device copy if they are not there yet).
+// Thread-safe.  Returns a CER_* code.
+int ensure_host_arrays(const cer_matrix* h);
 }  // namespace cer
 
 struct cer_matrix {
     std::shared_ptr<const cer::HostMatrix> host;
     int device = -1;          // -1: host-only handle
     void* d_base = nullptr;   // the one device allocation
+    cer::DeviceLayout layout; // where the arrays sit inside it
     size_t d_bytes = 0;       // its size
     int64_t stream_bytes = 0; // bytes of format arrays a product reads
     cer::DeviceView view;

@@ -84,6 +84,12 @@ int csr_cost_model(const csr_handle_t* h, int convention, cer_cost_t* c) {
 
 int cer_cost_model(const cer_handle_t* h, int convention, cer_cost_t* c) {
     if (!h || !c || (convention != CER_COUNT_THEOREM && convention != CER_COUNT_EXAMPLE)) return CER_E_INVALID;
+    try {
+        const int rc = cer::ensure_host_arrays(h);
+        if (rc != CER_OK) return rc;
+    } catch (...) {
+        return CER_E_NOMEM;
+    }
     const cer::HostMatrix& A = *h->host;
     *c = cer_cost_t{};
     c->read_colI = A.nnz;

@@ -54,8 +54,6 @@ struct FrontState {
     uint32_t pos_of[kCodes];           // rank -> codebook position
 };
 
-__device__ __forceinline__ uint32_t lane_id() { return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)); }
-
 // LDS traffic of one wave is ordered; this only keeps the compiler from moving accesses across.
 __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -68,17 +66,28 @@ __device__ __forceinline__ float canonical(float v) { return v == 0.0f ? 0.0f : 
 // ------------------------------------------------------------------------------------------------
 // range: min / max / finiteness
 // ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void range_take(float w, float& lo, float& hi, uint32_t& bad) {
+    bad |= (uint32_t)!(fabsf(w) <= 3.402823466e+38f);
+    lo = fminf(lo, w);
+    hi = fmaxf(hi, w);
+}
+
 __global__ __launch_bounds__(256) void range_kernel(const float* __restrict__ W, int64_t N, float* __restrict__ part_min,
                                                     float* __restrict__ part_max, uint32_t* __restrict__ part_bad) {
     float lo = INFINITY, hi = -INFINITY;
     uint32_t bad = 0;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N; i += stride) {
-        const float w = W[i];
-        bad |= (uint32_t)!(fabsf(w) <= 3.402823466e+38f);
-        lo = fminf(lo, w);
-        hi = fmaxf(hi, w);
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
+    // the bulk in 16-byte pieces (W is aligned by the caller's allocator or the scalar loop below takes it all)
+    const int64_t N4 = ((reinterpret_cast<uintptr_t>(W) & 15u) == 0) ? N / 4 : 0;
+    const float4* W4 = reinterpret_cast<const float4*>(W);
+    for (int64_t i = tid; i < N4; i += stride) {
+        const float4 w = W4[i];
+        range_take(w.x, lo, hi, bad);
+        range_take(w.y, lo, hi, bad);
+        range_take(w.z, lo, hi, bad);
+        range_take(w.w, lo, hi, bad);
     }
+    for (int64_t i = N4 * 4 + tid; i < N; i += stride) range_take(W[i], lo, hi, bad);
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         lo = fminf(lo, __shfl_xor(lo, off, kWave));
@@ -144,14 +153,13 @@ __global__ __launch_bounds__(256) void points_kernel(const float* __restrict__ p
     }
     s_pts[t] = p;
     __syncthreads();
-    uint32_t flags = s_bad[0] ? kFlagNonFinite : 0u;
     if (t + 1 < K && !(s_pts[t + 1] > s_pts[t])) atomicOr(&st->flags, kFlagCollide);
     if (t == 0) {
         st->wmin = wmin;
         st->wmax = wmax;
         st->step = step;
         st->K = K;
-        if (flags) atomicOr(&st->flags, flags);
+        if (s_bad[0]) atomicOr(&st->flags, kFlagNonFinite);
     }
 }
 
@@ -159,65 +167,102 @@ __global__ __launch_bounds__(256) void points_kernel(const float* __restrict__ p
 // codes: element -> codebook position; per-row histogram.  One workgroup per row (a flat array is
 // cut into rows of row_len elements).
 // ------------------------------------------------------------------------------------------------
+struct CodeCtx {
+    uint32_t K;
+    float wmin, step, top;
+    const float* val;     // LDS: quantizer -> points by position; look-up -> codebook sorted by value
+    const uint32_t* pos;  // LDS: look-up -> position of each sorted value
+};
+
+template <bool kQuant>
+__device__ __forceinline__ uint32_t code_of(float w, const CodeCtx& c, bool& missing) {
+#pragma clang fp contract(off)
+    if (kQuant) {
+        // nearest point, decided in binary32: round-half-even of the scaled coordinate
+        float q = 0.f;
+        if (c.K > 1) {
+            const float d = w - c.wmin;
+            q = fminf(fmaxf(rintf(d / c.step), 0.f), c.top);
+        }
+        return (uint32_t)q;
+    }
+    const float v = canonical(w);
+    uint32_t lo = 0, hi = c.K;  // first sorted value that is not below v
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (c.val[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    const bool hit = lo < c.K && __float_as_uint(c.val[lo]) == __float_as_uint(v);
+    missing |= !hit;
+    return hit ? c.pos[lo] : 0u;
+}
+
+// Each thread takes four consecutive elements per round: one 16-byte load, four codes, one 4-byte
+// store (a row whose length or address does not allow that falls back to single elements).
 template <bool kQuant>
 __global__ __launch_bounds__(256) void codes_kernel(const float* __restrict__ W, int64_t total, int64_t row_len,
                                                     FrontState* __restrict__ st, uint8_t* __restrict__ codes,
-                                                    uint32_t* __restrict__ cnt, float* __restrict__ Wq) {
-#pragma clang fp contract(off)
+                                                    uint32_t* __restrict__ cnt, float* __restrict__ Wq, int vec_ok) {
     __shared__ uint32_t s_hist[kCodes];
     __shared__ float s_val[kCodes];
     __shared__ uint32_t s_pos[kCodes];
     const uint32_t t = threadIdx.x;
     const int64_t r = blockIdx.x;
-    const uint32_t K = st->K;
+    CodeCtx c;
+    c.K = st->K;
     s_hist[t] = 0;
     if (kQuant) {
-        s_val[t] = t < K ? st->codebook[t] : 0.f;
+        s_val[t] = t < c.K ? st->codebook[t] : 0.f;
     } else {
-        s_val[t] = t < K ? st->sorted_val[t] : 0.f;
-        s_pos[t] = t < K ? st->sorted_pos[t] : 0u;
+        s_val[t] = t < c.K ? st->sorted_val[t] : 0.f;
+        s_pos[t] = t < c.K ? st->sorted_pos[t] : 0u;
     }
     __syncthreads();
-    const float wmin = st->wmin, step = st->step, top = (float)(K - 1);
+    c.wmin = st->wmin;
+    c.step = st->step;
+    c.top = (float)(c.K - 1);
+    c.val = s_val;
+    c.pos = s_pos;
     const float* row = W + r * row_len;
     uint8_t* crow = codes ? codes + r * row_len : nullptr;
+    float* qrow = Wq ? Wq + r * row_len : nullptr;
     const int64_t n = min(row_len, total - r * row_len);  // the last row of a flat array may be short
     bool missing = false;
-    for (int64_t j0 = 0; j0 < n; j0 += 256) {
-        const int64_t j = j0 + t;
-        const bool in = j < n;
-        uint32_t code = 0;
-        if (in) {
-            const float w = row[j];
-            if (kQuant) {
-                // nearest point, decided in binary32: round-half-even of the scaled coordinate
-                float q = 0.f;
-                if (K > 1) {
-                    const float d = w - wmin;
-                    q = fminf(fmaxf(rintf(d / step), 0.f), top);
+    for (int64_t j0 = 0; j0 < n; j0 += 1024) {
+        const int64_t j = j0 + 4 * (int64_t)t;
+        uint32_t code[4] = {0, 0, 0, 0};
+        const int valid = (int)max((int64_t)0, min((int64_t)4, n - j));
+        if (valid == 4 && vec_ok) {
+            const float4 w = *reinterpret_cast<const float4*>(row + j);
+            code[0] = code_of<kQuant>(w.x, c, missing);
+            code[1] = code_of<kQuant>(w.y, c, missing);
+            code[2] = code_of<kQuant>(w.z, c, missing);
+            code[3] = code_of<kQuant>(w.w, c, missing);
+            if (crow) *reinterpret_cast<uint32_t*>(crow + j) = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
+            if (kQuant && qrow)
+                *reinterpret_cast<float4*>(qrow + j) = make_float4(s_val[code[0]], s_val[code[1]], s_val[code[2]], s_val[code[3]]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (e < valid) {
+                    code[e] = code_of<kQuant>(row[j + e], c, missing);
+                    if (crow) crow[j + e] = (uint8_t)code[e];
+                    if (kQuant && qrow) qrow[j + e] = s_val[code[e]];
                 }
-                code = (uint32_t)q;
-                if (Wq) Wq[r * row_len + j] = s_val[code];
-            } else {
-                const float c = canonical(w);
-                uint32_t lo = 0, hi = K;  // first sorted value that is not below c
-                while (lo < hi) {
-                    const uint32_t mid = (lo + hi) >> 1;
-                    if (s_val[mid] < c) lo = mid + 1; else hi = mid;
-                }
-                const bool hit = lo < K && __float_as_uint(s_val[lo]) == __float_as_uint(c);
-                missing |= !hit;
-                code = hit ? s_pos[lo] : 0u;
             }
-            if (crow) crow[j] = (uint8_t)code;
         }
-        // histogram: the lanes that share the first active lane's code are counted with one add
-        const uint64_t act = __ballot(in);
+        // histogram: everything that equals the first active lane's first code is counted with one add
+        const uint64_t act = __ballot(valid > 0);
         if (act) {
-            const uint32_t lead = (uint32_t)__builtin_amdgcn_readfirstlane((int)code);
-            const uint64_t same = __ballot(in && code == lead);
-            if (in && code != lead) atomicAdd(&s_hist[code], 1u);
-            if ((uint64_t)__builtin_ctzll(act) == (uint64_t)(t & 63u)) atomicAdd(&s_hist[lead], (uint32_t)__popcll(same));
+            const uint32_t lead = (uint32_t)__builtin_amdgcn_readfirstlane((int)code[0]);
+            uint32_t same = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool in = e < valid;
+                same += (uint32_t)__popcll(__ballot(in && code[e] == lead));
+                if (in && code[e] != lead) atomicAdd(&s_hist[code[e]], 1u);
+            }
+            if ((uint32_t)__builtin_ctzll(act) == (t & 63u)) atomicAdd(&s_hist[lead], same);
         }
     }
     if (__syncthreads_or(missing) && t == 0) atomicOr(&st->flags, kFlagMissing);
@@ -258,11 +303,11 @@ __global__ __launch_bounds__(256) void rank_kernel(FrontState* __restrict__ st) 
 }
 
 // ------------------------------------------------------------------------------------------------
-// layout: per row, the number of indexed elements and of groups.  One wave per row.
+// layout: per row, the number of indexed elements, of groups and of non-empty groups.  One wave per row.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void row_layout_kernel(const uint32_t* __restrict__ cnt, int64_t m, int cser,
-                                                         FrontState* __restrict__ st, uint32_t* __restrict__ rowG,
-                                                         uint32_t* __restrict__ rowN) {
+                                                         const FrontState* __restrict__ st, uint32_t* __restrict__ rowG,
+                                                         uint32_t* __restrict__ rowN, uint32_t* __restrict__ rowP) {
     const uint32_t lane = threadIdx.x & 63u;
     const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= m) return;
@@ -285,26 +330,31 @@ __global__ __launch_bounds__(256) void row_layout_kernel(const uint32_t* __restr
         topk = max(topk, (uint32_t)__shfl_xor((int)topk, off, kWave));
     }
     if (lane == 0) {
-        const uint32_t g = cser ? present : topk;  // CER keeps the empty groups below the row's highest rank
-        rowG[r] = g;
+        rowG[r] = cser ? present : topk;  // CER keeps the empty groups below the row's highest rank
         rowN[r] = nn;
-        if (present) atomicAdd(&st->nonempty, (unsigned long long)present);
-        atomicMax(&st->max_row_groups, g);
+        rowP[r] = present;
     }
 }
 
-// Exclusive prefix sums of rowG and rowN over the rows, m + 1 entries each.  One block.
+// Exclusive prefix sums of rowG and rowN over the rows (m + 1 entries each), the number of
+// non-empty groups and the largest group count of a row.  One block.
 __global__ __launch_bounds__(1024) void scan_rows_kernel(const uint32_t* __restrict__ rowG, const uint32_t* __restrict__ rowN,
-                                                         int64_t m, uint32_t* __restrict__ rowPtr, uint32_t* __restrict__ rowOff,
+                                                         const uint32_t* __restrict__ rowP, int64_t m,
+                                                         uint32_t* __restrict__ rowPtr, uint32_t* __restrict__ rowOff,
                                                          FrontState* __restrict__ st) {
-    __shared__ unsigned long long s_g[16], s_n[16];
+    __shared__ unsigned long long s_g[16], s_n[16], s_p[16];
+    __shared__ uint32_t s_mx[16];
     __shared__ unsigned long long s_carry[2];
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     if (t == 0) s_carry[0] = s_carry[1] = 0;
+    unsigned long long my_p = 0;
+    uint32_t my_mx = 0;
     __syncthreads();
     for (int64_t base = 0; base < m; base += 1024) {
         const int64_t r = base + t;
         const unsigned long long g = r < m ? rowG[r] : 0u, nn = r < m ? rowN[r] : 0u;
+        my_p += r < m ? rowP[r] : 0u;
+        my_mx = max(my_mx, (uint32_t)g);
         unsigned long long ig = g, in_ = nn;  // inclusive scans inside the wave
 #pragma unroll
         for (int off = 1; off < kWave; off <<= 1) {
@@ -335,10 +385,28 @@ __global__ __launch_bounds__(1024) void scan_rows_kernel(const uint32_t* __restr
         }
         __syncthreads();
     }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        my_p += __shfl_xor(my_p, off, kWave);
+        my_mx = max(my_mx, (uint32_t)__shfl_xor((int)my_mx, off, kWave));
+    }
+    if (lane == 0) {
+        s_p[wave] = my_p;
+        s_mx[wave] = my_mx;
+    }
+    __syncthreads();
     if (t == 0) {
+        unsigned long long p = 0;
+        uint32_t mx = 0;
+        for (int w = 0; w < 16; ++w) {
+            p += s_p[w];
+            mx = max(mx, s_mx[w]);
+        }
         const unsigned long long G = s_carry[0], nnz = s_carry[1];
         st->G = G;
         st->nnz = nnz;
+        st->nonempty = p;
+        st->max_row_groups = mx;
         rowPtr[m] = (uint32_t)G;
         rowOff[m] = (uint32_t)nnz;
         // the product kernels address colI and OmegaPtr with 32-bit offsets and read ahead of a row's end
@@ -350,6 +418,28 @@ __global__ __launch_bounds__(1024) void scan_rows_kernel(const uint32_t* __restr
 // ------------------------------------------------------------------------------------------------
 // emit: the row's pointers and its columns, grouped by rank.  One wave per row.
 // ------------------------------------------------------------------------------------------------
+// 64 consecutive columns: lanes with the same rank are found with one ballot per bit of the rank
+// and take consecutive slots of that rank's bucket in lane (= column) order.
+template <typename ColT>
+__device__ __forceinline__ void scatter64(uint32_t k, int64_t j, uint32_t nbits, uint64_t below, uint32_t* fill,
+                                          ColT* __restrict__ colI) {
+    const bool act = k >= 1;
+    uint64_t peers = __ballot(act);
+    if (!peers) return;
+    for (uint32_t b = 0; b < nbits; ++b) {
+        const bool bit = (k >> b) & 1u;
+        const uint64_t votes = __ballot(bit);
+        peers &= bit ? votes : ~votes;
+    }
+    if (act) {
+        const uint32_t before = (uint32_t)__popcll(peers & below);
+        const uint32_t slot = fill[k];
+        colI[slot + before] = (ColT)j;
+        if (before == 0) fill[k] = slot + (uint32_t)__popcll(peers);
+    }
+    wave_lds_sync();
+}
+
 template <typename ColT, typename OiT>
 __global__ __launch_bounds__(256) void emit_kernel(const uint8_t* __restrict__ codes, const uint32_t* __restrict__ cnt,
                                                    const uint32_t* __restrict__ rowPtrTmp, const uint32_t* __restrict__ rowOffTmp,
@@ -405,66 +495,64 @@ __global__ __launch_bounds__(256) void emit_kernel(const uint8_t* __restrict__ c
         carry += (uint32_t)__shfl((int)inc, 63, kWave);
     }
     wave_lds_sync();
-    // stable scatter: 64 consecutive columns at a time; lanes with the same rank are found with one
-    // ballot per bit of the rank and take consecutive slots in lane (= column) order
+    // stable scatter of the row's columns into the buckets
     const uint32_t nbits = 32u - (uint32_t)__builtin_clz(Kp > 1 ? Kp - 1 : 1u);
     const uint64_t below = (1ull << lane) - 1ull;
     const uint8_t* crow = codes + r * n;
-    for (int64_t j0 = 0; j0 < n; j0 += kWave) {
-        const int64_t j = j0 + lane;
-        const uint32_t k = j < n ? s_rank[crow[j]] : 0u;
-        const bool act = k >= 1;
-        uint64_t peers = __ballot(act);
-        if (!peers) continue;
-        for (uint32_t b = 0; b < nbits; ++b) {
-            const bool bit = (k >> b) & 1u;
-            const uint64_t votes = __ballot(bit);
-            peers &= bit ? votes : ~votes;
+    if ((n & 3) == 0 && (reinterpret_cast<uintptr_t>(codes) & 3u) == 0) {
+        // 256 columns per round: each lane loads four codes at once (the next round's are requested
+        // before this round's are used); a shuffle hands every lane the code of its own column
+        const uint32_t* crow4 = reinterpret_cast<const uint32_t*>(crow);
+        const int64_t n4 = n >> 2;
+        uint32_t next = lane < n4 ? crow4[lane] : 0u;
+        for (int64_t j0 = 0; j0 < n; j0 += 256) {
+            const uint32_t cur = next;
+            const int64_t q = ((j0 + 256) >> 2) + lane;
+            next = q < n4 ? crow4[q] : 0u;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int64_t j = j0 + 64 * s + lane;
+                const uint32_t v = (uint32_t)__shfl((int)cur, 16 * s + (int)(lane >> 2), kWave);
+                const uint32_t code = (v >> (8u * (lane & 3u))) & 0xFFu;
+                scatter64<ColT>(j < n ? s_rank[code] : 0u, j, nbits, below, fill, colI);
+            }
         }
-        if (act) {
-            const uint32_t before = (uint32_t)__popcll(peers & below);
-            const uint32_t slot = fill[k];
-            colI[slot + before] = (ColT)j;
-            if (before == 0) fill[k] = slot + (uint32_t)__popcll(peers);
+    } else {
+        for (int64_t j0 = 0; j0 < n; j0 += kWave) {
+            const int64_t j = j0 + lane;
+            scatter64<ColT>(j < n ? s_rank[crow[j]] : 0u, j, nbits, below, fill, colI);
         }
-        wave_lds_sync();
     }
 }
 
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
+// Temporary device memory from the stream-ordered pool: released when the work queued before the
+// release has run, so the buffers can be dropped as soon as the last kernel using them is queued.
 struct DeviceBuf {
     void* p = nullptr;
+    hipStream_t s = nullptr;
     ~DeviceBuf() {
-        if (p) (void)hipFree(p);
+        if (p) (void)hipFreeAsync(p, s);
     }
-    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 1); }
+    hipError_t alloc(size_t bytes, hipStream_t stream) {
+        s = stream;
+        return hipMallocAsync(&p, bytes ? bytes : 1, stream);
+    }
     template <typename T>
     T* as() const {
         return static_cast<T*>(p);
     }
 };
 
-void narrow_u32(const std::vector<uint32_t>& src, int bits, cer::HostArray* dst) {
-    dst->len = (int64_t)src.size();
-    dst->bits = bits;
-    dst->bytes.resize(src.size() * (size_t)(bits / 8));
-    if (bits == 8) {
-        for (size_t i = 0; i < src.size(); ++i) dst->bytes[i] = (uint8_t)src[i];
-    } else if (bits == 16) {
-        auto* p = reinterpret_cast<uint16_t*>(dst->bytes.data());
-        for (size_t i = 0; i < src.size(); ++i) p[i] = (uint16_t)src[i];
-    } else if (!src.empty()) {
-        std::memcpy(dst->bytes.data(), src.data(), src.size() * 4);
-    }
-}
-
-#define HIP_TRY(expr)                                   \
-    do {                                                \
-        const hipError_t e_ = (expr);                   \
+#define HIP_TRY(expr)                                                \
+    do {                                                             \
+        const hipError_t e_ = (expr);                                \
         if (e_ != hipSuccess) return cer::record_hip_error((int)e_); \
     } while (0)
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Runs range/points (bits > 0) or takes the caller's codebook, then codes + per-row histograms over
 // `rows` rows of row_len elements (the last one possibly shorter).  Returns after the stream has drained.
@@ -472,17 +560,19 @@ int run_codes(const float* W, int64_t total, int64_t rows, int64_t row_len, cons
               hipStream_t s, FrontState* st_dev, uint8_t* codes, uint32_t* cnt, float* Wq) {
     FrontState init;
     std::memset(&init, 0, sizeof init);
+    const int vec_ok = (row_len % 4 == 0 && aligned16(W) && (!Wq || aligned16(Wq)) &&
+                        (!codes || (reinterpret_cast<uintptr_t>(codes) & 3u) == 0)) ? 1 : 0;
     DeviceBuf part;
     if (bits > 0) {
-        const int nparts = (int)std::min<int64_t>(2048, (total + 255) / 256);
-        HIP_TRY(part.alloc((size_t)nparts * 12));
+        const int nparts = (int)std::min<int64_t>(2048, (total + 1023) / 1024);
+        HIP_TRY(part.alloc((size_t)nparts * 12, s));
         float* pmin = part.as<float>();
         float* pmax = pmin + nparts;
         uint32_t* pbad = reinterpret_cast<uint32_t*>(pmax + nparts);
         HIP_TRY(hipMemcpyAsync(st_dev, &init, sizeof init, hipMemcpyHostToDevice, s));
         range_kernel<<<nparts, 256, 0, s>>>(W, total, pmin, pmax, pbad);
         points_kernel<<<1, 256, 0, s>>>(pmin, pmax, pbad, nparts, bits, st_dev);
-        codes_kernel<true><<<(unsigned)rows, 256, 0, s>>>(W, total, row_len, st_dev, codes, cnt, Wq);
+        codes_kernel<true><<<(unsigned)rows, 256, 0, s>>>(W, total, row_len, st_dev, codes, cnt, Wq, vec_ok);
     } else {
         // codebook sorted by value for the look-up; duplicates and non-finite values are refused
         std::vector<uint32_t> order((size_t)K);
@@ -499,10 +589,10 @@ int run_codes(const float* W, int64_t total, int64_t rows, int64_t row_len, cons
         }
         init.K = (uint32_t)K;
         HIP_TRY(hipMemcpyAsync(st_dev, &init, sizeof init, hipMemcpyHostToDevice, s));
-        codes_kernel<false><<<(unsigned)rows, 256, 0, s>>>(W, total, row_len, st_dev, codes, cnt, nullptr);
+        codes_kernel<false><<<(unsigned)rows, 256, 0, s>>>(W, total, row_len, st_dev, codes, cnt, nullptr, vec_ok);
     }
     HIP_TRY(hipGetLastError());
-    HIP_TRY(hipStreamSynchronize(s));  // `part` and `init` must outlive the work queued on them
+    HIP_TRY(hipStreamSynchronize(s));  // `init` lives on this frame
     return CER_OK;
 }
 
@@ -515,17 +605,14 @@ int flags_to_error(uint32_t flags) {
 }
 
 template <typename ColT>
-void launch_emit(int oi_bits, unsigned blocks, hipStream_t s, const uint8_t* codes, const uint32_t* cnt,
-                 const uint32_t* rowPtrTmp, const uint32_t* rowOffTmp, const FrontState* st, int64_t m, int64_t n, int cser,
-                 unsigned char* b, const cer::DeviceLayout& l) {
-    auto* colI = reinterpret_cast<ColT*>(b + l.off_colI);
-    auto* optr = reinterpret_cast<uint32_t*>(b + l.off_optr);
-    auto* rptr = reinterpret_cast<uint32_t*>(b + l.off_rptr);
-    auto* info = reinterpret_cast<uint2*>(b + l.off_ri);
+void launch_emit(unsigned blocks, hipStream_t s, const uint8_t* codes, const uint32_t* cnt, const uint32_t* rowPtrTmp,
+                 const uint32_t* rowOffTmp, const FrontState* st, int64_t m, int64_t n, int cser, unsigned char* b,
+                 const cer::DeviceLayout& l) {
     // rank < K <= 256, so OmegaI is always one byte wide here
-    (void)oi_bits;
-    emit_kernel<ColT, uint8_t><<<blocks, 256, 0, s>>>(codes, cnt, rowPtrTmp, rowOffTmp, st, m, n, cser, colI, optr, rptr, info,
-                                                      reinterpret_cast<uint8_t*>(b + l.off_oi));
+    emit_kernel<ColT, uint8_t><<<blocks, 256, 0, s>>>(
+        codes, cnt, rowPtrTmp, rowOffTmp, st, m, n, cser, reinterpret_cast<ColT*>(b + l.off_colI),
+        reinterpret_cast<uint32_t*>(b + l.off_optr), reinterpret_cast<uint32_t*>(b + l.off_rptr),
+        reinterpret_cast<uint2*>(b + l.off_ri), reinterpret_cast<uint8_t*>(b + l.off_oi));
 }
 
 }  // namespace
@@ -537,12 +624,13 @@ int quantize_device(const float* W, int64_t count, int32_t bits, uint8_t* codes,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t row_len = 4096, rows = (count + row_len - 1) / row_len;
     DeviceBuf st, cnt;
-    HIP_TRY(st.alloc(sizeof(FrontState)));
-    HIP_TRY(cnt.alloc((size_t)rows * kCodes * 4));
+    HIP_TRY(st.alloc(sizeof(FrontState), s));
+    HIP_TRY(cnt.alloc((size_t)rows * kCodes * 4, s));
     int rc = run_codes(W, count, rows, row_len, nullptr, 0, bits, s, st.as<FrontState>(), codes, cnt.as<uint32_t>(), Wq);
     if (rc != CER_OK) return rc;
     FrontState h;
-    HIP_TRY(hipMemcpy(&h, st.p, sizeof h, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpyAsync(&h, st.p, sizeof h, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
     rc = flags_to_error(h.flags);
     if (rc != CER_OK) return rc;
     if (K_out) *K_out = (int32_t)h.K;
@@ -557,25 +645,26 @@ int encode_device(const float* W, int64_t m, int64_t n, const float* codebook, i
     int dev = 0;
     HIP_TRY(hipGetDevice(&dev));
 
-    DeviceBuf st, codes, cnt, rowG, rowN, rowPtrTmp, rowOffTmp;
-    HIP_TRY(st.alloc(sizeof(FrontState)));
-    HIP_TRY(codes.alloc((size_t)N));
-    HIP_TRY(cnt.alloc((size_t)m * kCodes * 4));
-    HIP_TRY(rowG.alloc((size_t)m * 4));
-    HIP_TRY(rowN.alloc((size_t)m * 4));
-    HIP_TRY(rowPtrTmp.alloc((size_t)(m + 1) * 4));
-    HIP_TRY(rowOffTmp.alloc((size_t)(m + 1) * 4));
+    DeviceBuf st, codes, cnt, rows;
+    HIP_TRY(st.alloc(sizeof(FrontState), s));
+    HIP_TRY(codes.alloc((size_t)N, s));
+    HIP_TRY(cnt.alloc((size_t)m * kCodes * 4, s));
+    HIP_TRY(rows.alloc((size_t)(5 * m + 2) * 4, s));  // rowG, rowN, rowP [m] and rowPtrTmp, rowOffTmp [m + 1]
     FrontState* sd = st.as<FrontState>();
+    uint32_t* rowG = rows.as<uint32_t>();
+    uint32_t* rowN = rowG + m;
+    uint32_t* rowP = rowN + m;
+    uint32_t* rowPtrTmp = rowP + m;
+    uint32_t* rowOffTmp = rowPtrTmp + m + 1;
 
     int rc = run_codes(W, N, m, n, codebook, K, bits, s, sd, codes.as<uint8_t>(), cnt.as<uint32_t>(), nullptr);
     if (rc != CER_OK) return rc;
     const unsigned row_blocks = (unsigned)((m + 3) / 4);
-    const int64_t rows_per_block = 64;
+    const int64_t rows_per_block = 16;
     hist_kernel<<<(unsigned)((m + rows_per_block - 1) / rows_per_block), 256, 0, s>>>(cnt.as<uint32_t>(), m, rows_per_block, sd);
     rank_kernel<<<1, 256, 0, s>>>(sd);
-    row_layout_kernel<<<row_blocks, 256, 0, s>>>(cnt.as<uint32_t>(), m, cser ? 1 : 0, sd, rowG.as<uint32_t>(), rowN.as<uint32_t>());
-    scan_rows_kernel<<<1, 1024, 0, s>>>(rowG.as<uint32_t>(), rowN.as<uint32_t>(), m, rowPtrTmp.as<uint32_t>(),
-                                        rowOffTmp.as<uint32_t>(), sd);
+    row_layout_kernel<<<row_blocks, 256, 0, s>>>(cnt.as<uint32_t>(), m, cser ? 1 : 0, sd, rowG, rowN, rowP);
+    scan_rows_kernel<<<1, 1024, 0, s>>>(rowG, rowN, rowP, m, rowPtrTmp, rowOffTmp, sd);
     HIP_TRY(hipGetLastError());
     FrontState h;
     HIP_TRY(hipMemcpyAsync(&h, sd, sizeof h, hipMemcpyDeviceToHost, s));
@@ -585,7 +674,7 @@ int encode_device(const float* W, int64_t m, int64_t n, const float* codebook, i
     if (K_out) *K_out = (int32_t)h.K;
     if (codebook_out) std::memcpy(codebook_out, h.codebook, (size_t)h.K * 4);
 
-    // sizes are known: the handle's allocation, filled in place
+    // sizes are known: the handle's own allocation, filled in place by the emit kernel
     auto A = std::make_shared<HostMatrix>();
     A->cser = cser;
     A->m = m;
@@ -597,53 +686,46 @@ int encode_device(const float* W, int64_t m, int64_t n, const float* codebook, i
     A->max_row_groups = (int64_t)h.max_row_groups;
     A->omega.assign(h.omega, h.omega + h.Kp);
     A->count.assign(h.count, h.count + h.Kp);
-    const int col_bits = min_index_bits(n > 0 ? (uint64_t)(n - 1) : 0);
-    const int oi_bits = min_index_bits(A->K > 0 ? (uint64_t)(A->K - 1) : 0);
-    const size_t colI_bytes = (size_t)A->nnz * (size_t)(col_bits / 8);
-    const size_t oi_bytes = cser ? (size_t)A->G * (size_t)(oi_bits / 8) : 0;
-    const DeviceLayout l = DeviceLayout::make(colI_bytes, A->G, m, oi_bytes, A->K);
-    DeviceBuf base;
-    HIP_TRY(base.alloc(l.total));
-    auto* b = base.as<unsigned char>();
-    HIP_TRY(hipMemsetAsync(b, 0, l.total, s));
-    HIP_TRY(hipMemcpyAsync(b + l.off_om, h.omega, (size_t)h.Kp * 4, hipMemcpyHostToDevice, s));
-    switch (col_bits) {
-        case 8:
-            launch_emit<uint8_t>(oi_bits, row_blocks, s, codes.as<uint8_t>(), cnt.as<uint32_t>(), rowPtrTmp.as<uint32_t>(),
-                                 rowOffTmp.as<uint32_t>(), sd, m, n, cser ? 1 : 0, b, l);
-            break;
-        case 16:
-            launch_emit<uint16_t>(oi_bits, row_blocks, s, codes.as<uint8_t>(), cnt.as<uint32_t>(), rowPtrTmp.as<uint32_t>(),
-                                  rowOffTmp.as<uint32_t>(), sd, m, n, cser ? 1 : 0, b, l);
-            break;
-        default:
-            launch_emit<uint32_t>(oi_bits, row_blocks, s, codes.as<uint8_t>(), cnt.as<uint32_t>(), rowPtrTmp.as<uint32_t>(),
-                                  rowOffTmp.as<uint32_t>(), sd, m, n, cser ? 1 : 0, b, l);
-    }
-    HIP_TRY(hipGetLastError());
-
-    // host mirror of the arrays (inspection, decode, clones), pointer arrays at their minimal widths
-    std::vector<uint32_t> optr((size_t)A->G + 1), rptr((size_t)m + 1);
+    // the index arrays stay on the device until somebody asks for them on the host
     A->colI.len = A->nnz;
-    A->colI.bits = col_bits;
-    A->colI.bytes.resize(colI_bytes);
-    if (colI_bytes) HIP_TRY(hipMemcpyAsync(A->colI.bytes.data(), b + l.off_colI, colI_bytes, hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipMemcpyAsync(optr.data(), b + l.off_optr, optr.size() * 4, hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipMemcpyAsync(rptr.data(), b + l.off_rptr, rptr.size() * 4, hipMemcpyDeviceToHost, s));
+    A->colI.bits = min_index_bits(n > 0 ? (uint64_t)(n - 1) : 0);
+    A->omegaPtr.len = A->G + 1;
+    A->omegaPtr.bits = min_index_bits((uint64_t)A->nnz);
+    A->rowPtr.len = m + 1;
+    A->rowPtr.bits = min_index_bits((uint64_t)A->G);
     if (cser) {
         A->omegaI.len = A->G;
-        A->omegaI.bits = oi_bits;
-        A->omegaI.bytes.resize(oi_bytes);
-        if (oi_bytes) HIP_TRY(hipMemcpyAsync(A->omegaI.bytes.data(), b + l.off_oi, oi_bytes, hipMemcpyDeviceToHost, s));
+        A->omegaI.bits = min_index_bits(A->K > 0 ? (uint64_t)(A->K - 1) : 0);
     }
-    HIP_TRY(hipStreamSynchronize(s));
-    narrow_u32(optr, min_index_bits((uint64_t)A->nnz), &A->omegaPtr);
-    narrow_u32(rptr, min_index_bits((uint64_t)A->G), &A->rowPtr);
+    A->arrays_on_host.store(false);
+    const size_t colI_bytes = (size_t)A->nnz * (size_t)(A->colI.bits / 8);
+    const size_t oi_bytes = cser ? (size_t)A->G * (size_t)(A->omegaI.bits / 8) : 0;
+    const DeviceLayout l = DeviceLayout::make(colI_bytes, A->G, m, oi_bytes, A->K);
+    void* base = nullptr;
+    HIP_TRY(hipMalloc(&base, l.total));
+    auto* b = static_cast<unsigned char*>(base);
+    auto fail = [&](hipError_t e) {
+        (void)hipStreamSynchronize(s);
+        (void)hipFree(base);
+        return record_hip_error((int)e);
+    };
+    // everything behind the indices is cleared (read-ahead padding, gaps); colI itself is written completely
+    hipError_t e = hipMemsetAsync(b + colI_bytes, 0, l.total - colI_bytes, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(b + l.off_om, h.omega, (size_t)h.Kp * 4, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return fail(e);
+    const int cs = cser ? 1 : 0;
+    switch (A->colI.bits) {
+        case 8: launch_emit<uint8_t>(row_blocks, s, codes.as<uint8_t>(), cnt.as<uint32_t>(), rowPtrTmp, rowOffTmp, sd, m, n, cs, b, l); break;
+        case 16: launch_emit<uint16_t>(row_blocks, s, codes.as<uint8_t>(), cnt.as<uint32_t>(), rowPtrTmp, rowOffTmp, sd, m, n, cs, b, l); break;
+        default: launch_emit<uint32_t>(row_blocks, s, codes.as<uint8_t>(), cnt.as<uint32_t>(), rowPtrTmp, rowOffTmp, sd, m, n, cs, b, l);
+    }
+    e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(s);  // `h.omega` lives on this frame; errors surface here
+    if (e != hipSuccess) return fail(e);
 
     auto* hnd = new cer_matrix();
     hnd->host = std::move(A);
-    bind_device(hnd, dev, base.p, l);
-    base.p = nullptr;  // now owned by the handle
+    bind_device(hnd, dev, base, l);
     *out = hnd;
     return CER_OK;
 }
