@@ -109,6 +109,22 @@ int cer_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t 
 int cser_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t batch, void* stream);
 
 /*
+ * cer_matmul_path -- which kernel cer_matmul / cser_matmul runs for this handle and batch:
+ *   0  batch-1 kernel: X staged in LDS per workgroup, one wave per row
+ *   1  batched kernel that gathers rows of X from L2, one wave per (row, tile of 32 columns)
+ *   2  batched kernel with the input resident in LDS -- the reuse of input elements that the
+ *      paper's Section V-C names as the missing optimisation: a tile of 4 or 8 batch columns of all
+ *      n input rows is staged once per workgroup and serves many rows of W.  Applicable when
+ *      n.16 bytes fit in LDS (n <= about 10000), K <= 64 and no row has more than 63 groups;
+ *      for such a product a stream-ordered temporary of about the size of X is used.
+ * On MI355X kernel 2 was slower than kernel 1 on every measured workload (random LDS gathers are
+ * bank-conflict bound), so it runs only when the environment variable CER_XTILE is 1 and it is
+ * applicable; CER_XTILE=0 or unset selects kernel 1.  Errors: CER_E_INVALID, CER_E_HIP (no device
+ * copy).
+ */
+int cer_matmul_path(const cer_handle_t* h, int64_t batch);
+
+/*
  * cer_decode / cser_decode -- arrays -> dense matrix (Section II-A: M can be reconstructed
  * uniquely).  W_host_out: [m][n] fp32, host, written completely; equals the encoder's input bit
  * for bit (with -0.0 returned as +0.0).  Host-side.  Errors: CER_E_INVALID, CER_E_FORMAT.

@@ -34,7 +34,7 @@ EXPORTS = [
     "cer_device_bytes", "cer_free", "dense_matmul", "cer_stream_copy", "cer_strerror", "cer_last_hip_error",
     "csr_encode", "csr_matmul", "csr_decode", "csr_get_array", "csr_storage_bits", "csr_device_bytes",
     "csr_clone_device", "csr_free", "cer_cost_model", "csr_cost_model", "dense_cost_model",
-    "cer_encode_device", "cer_quantize_uniform", "cer_quantize_encode_device",
+    "cer_encode_device", "cer_quantize_uniform", "cer_quantize_encode_device", "cer_matmul_path",
 ]
 
 CER_FORMAT_CER, CER_FORMAT_CSER = 0, 1
@@ -123,6 +123,8 @@ def lib() -> ctypes.CDLL:
         L.csr_cost_model.argtypes = [vp, ctypes.c_int, ctypes.POINTER(CostT)]
         L.dense_cost_model.restype = ctypes.c_int
         L.dense_cost_model.argtypes = [i64, i64, ctypes.c_int, ctypes.POINTER(CostT)]
+        L.cer_matmul_path.restype = ctypes.c_int
+        L.cer_matmul_path.argtypes = [vp, i64]
         L.cer_encode_device.restype = ctypes.c_int
         L.cer_encode_device.argtypes = [vp, i64, i64, vp, i32, i32, vp, pvp]
         L.cer_quantize_uniform.restype = ctypes.c_int
@@ -238,6 +240,14 @@ def cer_quantize_encode_device(W, m: int, n: int, bits: int, fmt: str = "cer", s
 
 def cer_matmul(h: Handle, X, Y, batch: int, stream=None) -> None:
     _check(lib().cer_matmul(h.ptr, _dev_ptr(X), _dev_ptr(Y), batch, _stream_ptr(stream)), "cer_matmul")
+
+
+def cer_matmul_path(h: Handle, batch: int) -> int:
+    """0 = batch-1 kernel, 1 = batched kernel gathering from L2, 2 = batched kernel with X resident in LDS."""
+    rc = lib().cer_matmul_path(h.ptr, batch)
+    if rc < 0:
+        _check(rc, "cer_matmul_path")
+    return rc
 
 
 def cser_matmul(h: Handle, X, Y, batch: int, stream=None) -> None:

@@ -72,6 +72,7 @@ void cer::bind_device(cer_matrix* h, int dev, void* base, const DeviceLayout& l)
     v.m = A.m;
     v.n = A.n;
     v.max_row_groups = A.max_row_groups;
+    v.nnz = A.nnz;
     v.omega0 = A.K > 0 ? A.omega[0] : 0.f;
     h->layout = l;
 }
@@ -230,6 +231,12 @@ int cer_matmul(const cer_handle_t* h, const float* X, float* Y, int64_t batch, v
 }
 int cser_matmul(const cer_handle_t* h, const float* X, float* Y, int64_t batch, void* stream) {
     return matmul_any(h, true, X, Y, batch, stream);
+}
+
+int cer_matmul_path(const cer_handle_t* h, int64_t batch) {
+    if (!h || batch < 1) return CER_E_INVALID;
+    if (h->device < 0 || !h->d_base) return CER_E_HIP;
+    return cer::matmul_path(h->view, batch);
 }
 
 int cer_decode(const cer_handle_t* h, float* W_out) { return decode_any(h, false, W_out); }

@@ -56,6 +56,7 @@ struct DeviceView {
     int32_t K = 0;
     int64_t m = 0, n = 0;
     int64_t max_row_groups = 0;
+    int64_t nnz = 0;
     float omega0 = 0.f;
 };
 
@@ -76,6 +77,9 @@ int min_index_bits(uint64_t max_value);
 
 // HIP launchers (cer_kernels.hip).  Return a hipError_t value as int (0 = success).
 int launch_matmul(const DeviceView& v, const float* X, float* Y, int64_t L, void* stream);
+// Which product kernel launch_matmul picks for batch L: 0 = batch-1 kernel, 1 = batched, gathers from L2,
+// 2 = batched, input tile resident in LDS.
+int matmul_path(const DeviceView& v, int64_t L);
 int launch_dense(const float* W, const float* X, float* Y, int64_t m, int64_t n, int64_t L, void* stream);
 int launch_stream_copy(void* dst, const void* src, int64_t bytes, void* stream);
 
