@@ -467,37 +467,63 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
 
 constexpr int kGemmGroupTile = 256;  // raw groups turned into one LDS list at a time
 
-// The stream of one tile of groups, colI offsets [ts, te): two batches of U wave instructions are
-// kept in flight (ping-pong) -- while one batch is summed, the gathers of the next and the index
-// loads of the one after are under way.  With kPre the indices of the first two batches (ia, ib)
-// were requested by the caller.
+// Index registers of the batched kernel.  One register holds the indices of 64 consecutive colI
+// positions (one coalesced load per wave); a wave instruction of the gather needs only S = 64/P of
+// them, which every lane fetches from the register by a cross-lane read.  A batch of U windows
+// covers PB = U.S positions = KQ registers, and D batches of indices are kept in flight.
+template <int P>
+struct GemmIdx {
+    static constexpr int S = kWave / P, U = 8, PB = U * S;
+    static constexpr int KQ = PB >= kWave ? PB / kWave : 1;
+    static constexpr int D = KQ <= 4 ? 4 : 2;
+};
+
+// The stream of one tile of groups, colI offsets [ts, te): while one batch of U windows is summed,
+// the gathers of the next batch and the index loads D batches ahead are under way.  With kPre the
+// index registers of the first D batches were requested by the caller.
 template <typename IdxT, int V, int P, bool kPre>
 __device__ __forceinline__ void gemm_tile(const IdxT* colI, const float* xgather, uint32_t L, uint32_t ts, uint32_t te,
-                                          uint32_t sub, uint32_t lane, uint32_t (&ia)[8], uint32_t (&ib)[8], UCursor& cur,
-                                          Vec<V>& run, Vec<V>& acc, const uint32_t* ends, const float* wts) {
-    constexpr int S = kWave / P, U = 8;
-    constexpr uint32_t SU = S * U;
+                                          uint32_t sub, uint32_t lane, uint32_t (&iq)[GemmIdx<P>::D][GemmIdx<P>::KQ],
+                                          UCursor& cur, Vec<V>& run, Vec<V>& acc, const uint32_t* ends, const float* wts) {
+    using G = GemmIdx<P>;
+    constexpr int S = G::S, U = G::U, KQ = G::KQ, D = G::D;
+    constexpr uint32_t PB = G::PB;
     Vec<V> xa[U], xb[U];
-#define CER_LOAD_IDX(ix, b) \
-    _Pragma("unroll") for (int u = 0; u < U; ++u) ix[u] = (uint32_t)colI[(b) + u * S + sub];
-#define CER_GATHER(xv, ix) \
-    _Pragma("unroll") for (int u = 0; u < U; ++u) xv[u].load(xgather + (size_t)ix[u] * L);
+#define CER_LOADQ(d, b) \
+    _Pragma("unroll") for (int q = 0; q < KQ; ++q) iq[d][q] = (uint32_t)colI[(b) + q * kWave + lane];
+#define CER_GATHER(xv, d)                                                                             \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                   \
+        const uint32_t reg_ = iq[d][(u * S) / kWave];                                                 \
+        const uint32_t idx_ = S == kWave ? reg_ : (uint32_t)__shfl((int)reg_, (int)((u * S) % kWave + sub), kWave); \
+        xv[u].load(xgather + (size_t)idx_ * L);                                                       \
+    }
 #define CER_CONSUME(xv, b) \
     _Pragma("unroll") for (int u = 0; u < U; ++u) cer_step<S, V>(xv[u], sub, (b) + u * S, cur, run, acc, ends, wts, lane);
-    if (!kPre) { CER_LOAD_IDX(ia, ts) }
-    CER_GATHER(xa, ia)
-    if (!kPre) { CER_LOAD_IDX(ib, ts + SU) }
-    for (uint32_t base = ts; base < te; base += 2 * SU) {
-        CER_GATHER(xb, ib)
-        CER_LOAD_IDX(ia, base + 2 * SU)
-        CER_CONSUME(xa, base)
-        CER_GATHER(xa, ia)
-        CER_LOAD_IDX(ib, base + 3 * SU)
-        CER_CONSUME(xb, base + SU)
+#define CER_STEP(xcur, xnext, dn, dl, k)   \
+    CER_GATHER(xnext, dn)                  \
+    CER_LOADQ(dl, base + ((k) + D) * PB)   \
+    CER_CONSUME(xcur, base + (k) * PB)
+    if (!kPre) {
+        _Pragma("unroll") for (int d = 0; d < D; ++d) { CER_LOADQ(d, ts + d * PB) }
     }
-#undef CER_LOAD_IDX
+    CER_GATHER(xa, 0)
+    for (uint32_t base = ts; base < te; base += D * PB) {
+        CER_STEP(xa, xb, 1, 0, 0)
+        if (D == 2) {
+            CER_STEP(xb, xa, 0, 1, 1)
+        } else {
+            if (base + PB >= te) break;
+            CER_STEP(xb, xa, 2, 1, 1)
+            if (base + 2 * PB >= te) break;
+            CER_STEP(xa, xb, 3 % D, 2 % D, 2)
+            if (base + 3 * PB >= te) break;
+            CER_STEP(xb, xa, 0, 3 % D, 3)
+        }
+    }
+#undef CER_LOADQ
 #undef CER_GATHER
 #undef CER_CONSUME
+#undef CER_STEP
 }
 
 // V floats per lane, P lanes per index: one wave instruction gathers 64/P rows of X, each
@@ -506,9 +532,7 @@ template <typename IdxT, int V, int P>
 __global__ __launch_bounds__(256) void cer_gemm_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
                                                        const float* __restrict__ T, uint32_t L, uint32_t ntiles,
                                                        uint32_t rowblocks, uint32_t items_per_xcd) {
-    constexpr int S = kWave / P;  // consecutive colI positions per wave instruction
-    constexpr int U = 8;          // wave instructions per batch
-    constexpr int TW = V * P;     // batch columns per tile
+    constexpr int TW = V * P;  // batch columns per tile; a wave instruction covers 64 / P colI positions
     __shared__ uint32_t s_ends[4][kGemmGroupTile + 2];
     __shared__ float s_wts[4][kGemmGroupTile + 2];
 
@@ -535,16 +559,16 @@ __global__ __launch_bounds__(256) void cer_gemm_kernel(KView v, const float* __r
     const uint2 d0 = v.rowInfo[r], d1 = v.rowInfo[r + 1];  // scalar loads: r is wave-uniform
     const uint32_t g0 = d0.x, rs = d0.y, g1 = d1.x, re = d1.y;
     // Everything the first tile needs is requested at once -- 64 group pointers, Omega by lane, the
-    // indices of the first two batches -- so that their latencies overlap instead of adding up.
+    // indices of the first batches -- so that their latencies overlap instead of adding up.
     const bool cser = v.cser != 0;
     const uint32_t tg_end0 = min(g1, g0 + (uint32_t)kGemmGroupTile);
     const PtrTile pt0 = load_ptr_tile(v, cser, g0, g0, min(tg_end0, g0 + (uint32_t)kWave), lane);
     const float om_l = v.omega[lane < v.K ? lane : 0u];
-    uint32_t ia[U], ib[U];
+    uint32_t iq[GemmIdx<P>::D][GemmIdx<P>::KQ];
 #pragma unroll
-    for (int u = 0; u < U; ++u) ia[u] = (uint32_t)colI[rs + u * S + sub];
+    for (int d = 0; d < GemmIdx<P>::D; ++d)
 #pragma unroll
-    for (int u = 0; u < U; ++u) ib[u] = (uint32_t)colI[rs + (U + u) * S + sub];
+        for (int q = 0; q < GemmIdx<P>::KQ; ++q) iq[d][q] = (uint32_t)colI[rs + d * GemmIdx<P>::PB + q * kWave + lane];
 
     Vec<V> acc, run;
     acc.zero();
@@ -562,7 +586,7 @@ __global__ __launch_bounds__(256) void cer_gemm_kernel(KView v, const float* __r
         if (count > 0) {
             ucursor_start(cur, ends, wts, count, lane);
             run.zero();
-            gemm_tile<IdxT, V, P, true>(colI, xgather, L, rs, te, sub, lane, ia, ib, cur, run, acc, ends, wts);
+            gemm_tile<IdxT, V, P, true>(colI, xgather, L, rs, te, sub, lane, iq, cur, run, acc, ends, wts);
             acc.fma(run, cur.w);
         }
         wave_lds_sync();
@@ -577,8 +601,7 @@ __global__ __launch_bounds__(256) void cer_gemm_kernel(KView v, const float* __r
         if (count > 0) {
             ucursor_start(cur, ends, wts, count, lane);
             run.zero();
-            uint32_t ja[U], jb[U];
-            gemm_tile<IdxT, V, P, false>(colI, xgather, L, ts, te, sub, lane, ja, jb, cur, run, acc, ends, wts);
+            gemm_tile<IdxT, V, P, false>(colI, xgather, L, ts, te, sub, lane, iq, cur, run, acc, ends, wts);
             acc.fma(run, cur.w);
         }
         wave_lds_sync();
