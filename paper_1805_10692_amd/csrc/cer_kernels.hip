@@ -475,7 +475,7 @@ template <int P>
 struct GemmIdx {
     static constexpr int S = kWave / P, U = 8, PB = U * S;
     static constexpr int KQ = PB >= kWave ? PB / kWave : 1;
-    static constexpr int D = KQ <= 4 ? 4 : 2;
+    static constexpr int D = KQ == 1 ? 8 : (KQ <= 4 ? 4 : 2);
 };
 
 // The stream of one tile of groups, colI offsets [ts, te): while one batch of U windows is summed,
@@ -508,16 +508,24 @@ __device__ __forceinline__ void gemm_tile(const IdxT* colI, const float* xgather
     }
     CER_GATHER(xa, 0)
     for (uint32_t base = ts; base < te; base += D * PB) {
-        CER_STEP(xa, xb, 1, 0, 0)
-        if (D == 2) {
-            CER_STEP(xb, xa, 0, 1, 1)
-        } else {
-            if (base + PB >= te) break;
-            CER_STEP(xb, xa, 2, 1, 1)
+        CER_STEP(xa, xb, 1 % D, 0, 0)
+        if (D > 2 && base + PB >= te) break;
+        CER_STEP(xb, xa, 2 % D, 1 % D, 1)
+        if (D > 2) {
             if (base + 2 * PB >= te) break;
             CER_STEP(xa, xb, 3 % D, 2 % D, 2)
             if (base + 3 * PB >= te) break;
-            CER_STEP(xb, xa, 0, 3 % D, 3)
+            CER_STEP(xb, xa, 4 % D, 3 % D, 3)
+        }
+        if (D > 4) {
+            if (base + 4 * PB >= te) break;
+            CER_STEP(xa, xb, 5 % D, 4 % D, 4)
+            if (base + 5 * PB >= te) break;
+            CER_STEP(xb, xa, 6 % D, 5 % D, 5)
+            if (base + 6 * PB >= te) break;
+            CER_STEP(xa, xb, 7 % D, 6 % D, 6)
+            if (base + 7 * PB >= te) break;
+            CER_STEP(xb, xa, 0, 7 % D, 7)
         }
     }
 #undef CER_LOADQ
