@@ -238,3 +238,26 @@ def test_csr_matmul(name):
     want = oracle.dot_csr(oracle.csr_encode(w.W), w.X)
     check(Yd.cpu().numpy(), want, oracle.abs_dot_dense(w.W, w.X), f"csr {w.name}")
     B.csr_free(h)
+
+
+@pytest.mark.parametrize("shape", [(5, 0, 1), (5, 0, 3), (0, 7, 1), (0, 7, 4), (3, 2, 1), (3, 2, 70000)])
+def test_degenerate_shapes(shape):
+    """No columns (Y = 0), no rows (nothing written), and a batch far wider than the matrix."""
+    m, n, L = shape
+    dev = _gpu()
+    cb = np.array([0.0, 1.0], np.float32)
+    W = np.zeros((m, n), np.float32)
+    if m and n:
+        W[0, 1] = 1.0
+    X = torch.ones((max(n, 1), L), dtype=torch.float32, device=dev)   # a valid pointer even when n = 0
+    for fmt in ("cer", "cser"):
+        h = (B.cer_encode if fmt == "cer" else B.cser_encode)(W, cb)
+        Y = torch.full((max(m, 1), L), float("nan"), dtype=torch.float32, device=dev)
+        (B.cer_matmul if fmt == "cer" else B.cser_matmul)(h, X, Y, L)
+        torch.cuda.synchronize()
+        B.cer_free(h)
+        if m:
+            want = W @ np.ones((n, L), np.float32) if n else np.zeros((m, L), np.float32)
+            assert np.array_equal(Y[:m].cpu().numpy(), want)
+        else:
+            assert torch.isnan(Y).all()
