@@ -261,3 +261,34 @@ def test_degenerate_shapes(shape):
             assert np.array_equal(Y[:m].cpu().numpy(), want)
         else:
             assert torch.isnan(Y).all()
+
+
+def test_graph_capture_and_replay():
+    """A product with a zero most frequent value launches kernels only (no allocation, no memset), so a caller
+    can record it into a HIP graph.  Every replay, with eager work and synchronisation in between and new
+    inputs in the same buffers, must equal the eager result."""
+    dev = _gpu()
+    cases = [wl.vgg_fc6(L=1, scale=8), wl.alexnet_fc6(L=32, scale=8)]
+    for w in cases:
+        h = B.cer_encode(w.W, w.codebook)
+        Xd = torch.from_numpy(w.X).to(dev)
+        Yg = torch.zeros((w.m, w.L), dtype=torch.float32, device=dev)
+        Ye = torch.zeros_like(Yg)
+        B.cer_matmul(h, Xd, Ye, w.L)            # warm-up outside the capture (one-time kernel attributes)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            B.cer_matmul(h, Xd, Yg, w.L)        # recorded on the capture stream, which is the current stream here
+        rng = np.random.default_rng(3)
+        for rep in range(4):
+            Xd.copy_(torch.from_numpy(rng.standard_normal(w.X.shape).astype(np.float32)))
+            Yg.fill_(float("nan"))
+            torch.cuda.synchronize()
+            g.replay()
+            B.cer_matmul(h, Xd, Ye, w.L)        # eager, same inputs
+            torch.cuda.synchronize()
+            assert torch.equal(Yg, Ye), f"{w.name}: replay {rep} differs from the eager product"
+            scale = oracle.abs_dot_dense(w.W, Xd.cpu().numpy(), threads=8)
+            want = oracle.dot_dense(w.W, Xd.cpu().numpy(), threads=8)
+            check(Yg.cpu().numpy(), want, scale, f"{w.name} replay {rep}")
+        B.cer_free(h)
