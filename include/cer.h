@@ -102,7 +102,9 @@ int cser_encode(const float* W_host, int64_t m, int64_t n, const float* codebook
  * Work is enqueued on `stream` and the call returns without synchronising.  The caller keeps
  * ownership of X and Y and must keep them alive until the stream has run the work.  When
  * Omega[0] != 0 a stream-ordered temporary of batch floats (plus partial sums) is allocated and
- * released on `stream`.  fp32 arithmetic; the summation order differs from a sequential loop.
+ * released on `stream`; when Omega[0] = 0 (and kernel 2 of cer_matmul_path is not selected) the call
+ * only launches kernels and may be recorded into a HIP graph after one eager call on the device.
+ * fp32 arithmetic; the summation order differs from a sequential loop.
  * Errors: CER_E_INVALID (null pointers, batch < 1), CER_E_FORMAT, CER_E_HIP.
  */
 int cer_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t batch, void* stream);
