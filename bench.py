@@ -106,6 +106,32 @@ def probe_copy(mib: int, reps: int = 20) -> dict:
     return {"MiB": mib, "us_per_launch": ev * 1e3, "GBps_read_plus_write": 2 * n * 4 / (ev * 1e-3) / 1e9}
 
 
+def probe_stream(nbytes: int, steps: int = 1000) -> dict:
+    """What one launch that does nothing but read `nbytes` costs here, cold (rotation over slices of a buffer
+    larger than twice the last-level cache), and what a launch that reads 16 bytes costs: the ceiling and the
+    floor between which a product of that size lives.  Uses the library's cer_stream_read kernel."""
+    import torch
+    from paper_1805_10692_amd import binding as B
+    piece = (nbytes + 4095) // 4096 * 4096
+    R = max(2, -(-2 * LAST_LEVEL_CACHE_BYTES // piece))
+    buf = torch.zeros(R * piece, dtype=torch.uint8, device="cuda:0")
+    sink = torch.zeros(16384, dtype=torch.uint8, device="cuda:0")
+    base, sp = buf.data_ptr(), sink.data_ptr()
+    stream = torch.cuda.current_stream().cuda_stream
+    lib = B.lib()
+
+    def big(i):
+        lib.cer_stream_read(base + (i % R) * piece, nbytes, sp, stream)
+
+    def tiny(i):
+        lib.cer_stream_read(base, 16, sp, stream)
+
+    _, ev_big = time_steps(big, steps, 50)
+    _, ev_tiny = time_steps(tiny, steps, 50)
+    return {"bytes": nbytes, "read_only_launch_us": ev_big * 1e3, "read_only_GBps": nbytes / (ev_big * 1e-3) / 1e9,
+            "read_only_frac_of_peak": nbytes / (ev_big * 1e-3) / 1e9 / HBM_PEAK_GBS, "empty_launch_us": ev_tiny * 1e3}
+
+
 def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: bool, with_dense: bool) -> dict:
     import torch
 
@@ -320,6 +346,7 @@ def main() -> int:
     ap.add_argument("--warm", action="store_true", help="reuse one device copy (cache-resident)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-probe", action="store_true", help="skip the read-only stream probe of the batch-1 line")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="MiB",
                     help="also launch the plain copy kernel on this many MiB (calibrates byte counters)")
     ap.add_argument("--report", default=None, help="write a table over workloads/formats to this JSON file")
@@ -361,6 +388,11 @@ def main() -> int:
     }
     if args.probe_copy:
         line["copy_probe"] = probe_copy(args.probe_copy)
+    if r["L"] == 1 and not args.warm and not args.no_probe:
+        # the HBM-bound case: how fast a launch that only streams the same bytes is on this machine
+        sp = probe_stream(r["algorithmic_bytes"])
+        line["roofline"]["stream_probe"] = sp
+        line["roofline"]["frac_of_read_only_launch"] = sp["read_only_launch_us"] / (r["event_ms_per_step"] * 1e3)
     print(json.dumps(line), flush=True)
 
     if args.report:

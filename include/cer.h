@@ -264,6 +264,16 @@ int cer_quantize_encode_device(const float* W_dev, int64_t m, int64_t n, int32_t
  */
 int cer_stream_copy(void* dst_dev, const void* src_dev, int64_t bytes, void* stream);
 
+/*
+ * cer_stream_read -- reads `bytes` bytes (rounded down to a multiple of 16; src_dev 16-byte aligned)
+ * with 16-byte loads and nothing else, in the launch shape of the batch-1 product kernel (256
+ * workgroups of 1024 threads); sink_dev receives 16 KiB of folded words that keep the loads alive.
+ * A measurement aid: what one launch that only streams as many bytes as a product reads costs on
+ * this machine -- the ceiling against which the product kernel's time is read.  Enqueued on
+ * `stream`, no synchronisation.  Errors: CER_E_INVALID, CER_E_HIP.
+ */
+int cer_stream_read(const void* src_dev, int64_t bytes, void* sink_dev, void* stream);
+
 const char* cer_strerror(int code);
 int cer_last_hip_error(void);
 

@@ -34,7 +34,7 @@ EXPORTS = [
     "cer_device_bytes", "cer_free", "dense_matmul", "cer_stream_copy", "cer_strerror", "cer_last_hip_error",
     "csr_encode", "csr_matmul", "csr_decode", "csr_get_array", "csr_storage_bits", "csr_device_bytes",
     "csr_clone_device", "csr_free", "cer_cost_model", "csr_cost_model", "dense_cost_model",
-    "cer_encode_device", "cer_quantize_uniform", "cer_quantize_encode_device", "cer_matmul_path",
+    "cer_encode_device", "cer_quantize_uniform", "cer_quantize_encode_device", "cer_matmul_path", "cer_stream_read",
 ]
 
 CER_FORMAT_CER, CER_FORMAT_CSER = 0, 1
@@ -123,6 +123,8 @@ def lib() -> ctypes.CDLL:
         L.csr_cost_model.argtypes = [vp, ctypes.c_int, ctypes.POINTER(CostT)]
         L.dense_cost_model.restype = ctypes.c_int
         L.dense_cost_model.argtypes = [i64, i64, ctypes.c_int, ctypes.POINTER(CostT)]
+        L.cer_stream_read.restype = ctypes.c_int
+        L.cer_stream_read.argtypes = [vp, i64, vp, vp]
         L.cer_matmul_path.restype = ctypes.c_int
         L.cer_matmul_path.argtypes = [vp, i64]
         L.cer_encode_device.restype = ctypes.c_int
@@ -330,6 +332,12 @@ def cer_stream_copy(dst, src, nbytes: int, stream=None) -> None:
     def raw(t):
         return t if isinstance(t, int) else t.data_ptr()
     _check(lib().cer_stream_copy(raw(dst), raw(src), nbytes, _stream_ptr(stream)), "cer_stream_copy")
+
+
+def cer_stream_read(src, nbytes: int, sink, stream=None) -> None:
+    def raw(t):
+        return t if isinstance(t, int) else t.data_ptr()
+    _check(lib().cer_stream_read(raw(src), nbytes, raw(sink), _stream_ptr(stream)), "cer_stream_read")
 
 
 class CsrHandle:

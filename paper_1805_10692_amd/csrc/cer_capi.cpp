@@ -398,6 +398,13 @@ int cer_stream_copy(void* dst, const void* src, int64_t bytes, void* stream) {
     return rc == 0 ? CER_OK : hip_fail((hipError_t)rc);
 }
 
+int cer_stream_read(const void* src, int64_t bytes, void* sink, void* stream) {
+    if (!src || !sink || bytes < 0) return CER_E_INVALID;
+    if ((reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return CER_E_INVALID;
+    const int rc = cer::launch_stream_read(src, bytes, sink, stream);
+    return rc == 0 ? CER_OK : hip_fail((hipError_t)rc);
+}
+
 const char* cer_strerror(int code) {
     switch (code) {
         case CER_OK: return "ok";

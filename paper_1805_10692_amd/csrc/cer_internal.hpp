@@ -82,6 +82,7 @@ int launch_matmul(const DeviceView& v, const float* X, float* Y, int64_t L, void
 int matmul_path(const DeviceView& v, int64_t L);
 int launch_dense(const float* W, const float* X, float* Y, int64_t m, int64_t n, int64_t L, void* stream);
 int launch_stream_copy(void* dst, const void* src, int64_t bytes, void* stream);
+int launch_stream_read(const void* src, int64_t bytes, void* sink, void* stream);
 
 // Device front-end (frontend.hip): W_dev holds codebook values, or (bits > 0) unquantized weights.
 int encode_device(const float* W_dev, int64_t m, int64_t n, const float* codebook, int32_t K, int32_t bits, bool cser,

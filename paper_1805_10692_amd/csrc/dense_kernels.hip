@@ -210,6 +210,26 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const uint4* __restric
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
+// Reads n16 16-byte pieces and keeps the loads alive by folding them into one word per wave.
+// Launch shape of the batch-1 product kernel (256 workgroups of 1024 threads): what a kernel that
+// does nothing but stream the same number of bytes costs.
+__global__ __launch_bounds__(1024) void stream_read_kernel(const uint4* __restrict__ src, size_t n16, uint32_t* __restrict__ sink) {
+    uint32_t acc = 0;
+    const size_t stride = (size_t)gridDim.x * 1024;
+    size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    for (; i < n16; i += stride) {
+        const uint4 a = src[i];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc ^= (uint32_t)__shfl_xor((int)acc, off, 64);
+    if ((threadIdx.x & 63u) == 0) sink[blockIdx.x * 16u + (threadIdx.x >> 6)] = acc;
+}
+
 template <int BM, int BN, int WM, int WN>
 hipError_t launch_gemm_cfg(const float* W, const float* X, float* Y, uint32_t m, uint32_t n, uint32_t L,
                            hipStream_t stream) {
@@ -277,6 +297,13 @@ int launch_stream_copy(void* dst, const void* src, int64_t bytes, void* stream_v
     const uint32_t blocks = (uint32_t)std::min<size_t>((n16 + 255) / 256, 256 * 32);
     hipLaunchKernelGGL(stream_copy_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<const uint4*>(src),
                        static_cast<uint4*>(dst), n16);
+    return (int)hipGetLastError();
+}
+
+int launch_stream_read(const void* src, int64_t bytes, void* sink, void* stream_v) {
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    hipLaunchKernelGGL(stream_read_kernel, dim3(256), dim3(1024), 0, stream, static_cast<const uint4*>(src),
+                       (size_t)bytes / 16, static_cast<uint32_t*>(sink));
     return (int)hipGetLastError();
 }
 
