@@ -39,10 +39,9 @@ def make_workload(name: str):
         return wl.vgg_fc6(L=1)
     if name == "vgg_fc6_L64":
         return wl.vgg_fc6(L=64)
-    if name == "alexnet_fc6_L32":
-        return wl.alexnet_fc6(L=32)
-    if name == "alexnet_fc6_L1":
-        return wl.alexnet_fc6(L=1)
+    m = re.fullmatch(r"alexnet_fc6_L(\d+)", name)
+    if m:
+        return wl.alexnet_fc6(L=int(m.group(1)))
     if name == "conv3x3_L3136":
         return wl.conv3x3()
     if name == "conv3x3_dom_L3136":
