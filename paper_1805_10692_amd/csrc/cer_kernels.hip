@@ -18,8 +18,11 @@
 //   * batch = 1: X is staged into LDS once per workgroup and gathered from there; the 64 lane
 //     totals are combined with DPP cross-lane adds;
 //   * batch > 1: P lanes x V floats cover a tile of batch columns, 64/P indices are gathered per
-//     wave instruction from L2, two batches of gathers are kept in flight, workgroups are numbered
-//     so that one XCD's L2 sees as few batch tiles of X as possible.
+//     wave instruction from L2 (whole 128-byte rows of X for the default 32-column tile), two
+//     batches of gathers are kept in flight; the indices come from one coalesced load per 64
+//     positions and a cross-lane read, several batches ahead; workgroups are numbered so that one
+//     XCD's L2 sees as few batch tiles of X as possible.  A second batched kernel keeps a narrow
+//     tile of X in LDS instead (reuse of the input); it is slower on this machine and opt-in.
 // Every load that feeds the streams is unconditional and issued in straight-line code (colI is
 // followed by readable padding); positions past a row's end pick up some valid input that lands in
 // a running sum multiplied by the list sentinel's weight 0.

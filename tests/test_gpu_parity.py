@@ -292,3 +292,35 @@ def test_graph_capture_and_replay():
             want = oracle.dot_dense(w.W, Xd.cpu().numpy(), threads=8)
             check(Yg.cpu().numpy(), want, scale, f"{w.name} replay {rep}")
         B.cer_free(h)
+
+
+@pytest.mark.parametrize("L", [1, 4, 8, 32])
+def test_unaligned_device_pointers(L):
+    """X and Y that start 4 bytes into an allocation: the 16-byte load / store paths must not be taken."""
+    dev = _gpu()
+    w = wl.random_lowentropy(m=77, n=1203, K=12, p_dom=0.8, L=L, seed=300 + L)
+    scale = oracle.abs_dot_dense(w.W, w.X, threads=4)
+    want = oracle.dot_dense(w.W, w.X, threads=4)
+    xbuf = torch.zeros(w.n * L + 1, dtype=torch.float32, device=dev)
+    ybuf = torch.full((w.m * L + 1,), float("nan"), dtype=torch.float32, device=dev)
+    Xd, Yd = xbuf[1:], ybuf[1:]
+    assert Xd.data_ptr() % 16 == 4 and Yd.data_ptr() % 16 == 4
+    Xd.copy_(torch.from_numpy(w.X.reshape(-1)))
+    for fmt in ("cer", "cser"):
+        h = (B.cer_encode if fmt == "cer" else B.cser_encode)(w.W, w.codebook)
+        for xt in ("0", "1"):
+            import os
+            os.environ["CER_XTILE"] = xt
+            try:
+                Yd.fill_(float("nan"))
+                (B.cer_matmul if fmt == "cer" else B.cser_matmul)(h, Xd, Yd, L)
+                torch.cuda.synchronize()
+            finally:
+                del os.environ["CER_XTILE"]
+            check(Yd.cpu().numpy().reshape(w.m, L), want, scale, f"unaligned {fmt} L={L} xtile={xt}")
+        B.cer_free(h)
+    Wd = torch.from_numpy(w.W).to(dev)
+    Yd.fill_(float("nan"))
+    B.dense_matmul(Wd, Xd, Yd, w.m, w.n, L)
+    torch.cuda.synchronize()
+    check(Yd.cpu().numpy().reshape(w.m, L), want, scale, f"unaligned dense L={L}")
