@@ -246,6 +246,11 @@ int dense_cost_model(int64_t m, int64_t n, int convention, cer_cost_t* out);
  * cer_quantize_encode_device: both steps in one call; the quantized matrix is never materialised
  * in fp32.  Same result as cer_quantize_uniform followed by cer_encode_device on Wq_dev with the
  * returned codebook.
+ *
+ * cer_decode_device: the handle's device arrays -> dense matrix in device memory (W_dev_out:
+ * [m][n] fp32, row-major, written completely; CER and CSER handles alike).  Same values as
+ * cer_decode / cser_decode.  Enqueued on `stream`, no synchronisation.  Errors: CER_E_INVALID,
+ * CER_E_HIP (no device copy, wrong device).
  */
 enum { CER_FORMAT_CER = 0, CER_FORMAT_CSER = 1 };
 int cer_encode_device(const float* W_dev, int64_t m, int64_t n, const float* codebook, int32_t K,
@@ -254,6 +259,7 @@ int cer_quantize_uniform(const float* W_dev, int64_t count, int32_t bits, uint8_
                          float* Wq_dev, float* codebook_out, int32_t* K_out, void* stream);
 int cer_quantize_encode_device(const float* W_dev, int64_t m, int64_t n, int32_t bits, int32_t format,
                                void* stream, float* codebook_out, int32_t* K_out, cer_handle_t** out);
+int cer_decode_device(const cer_handle_t* h, float* W_dev_out, void* stream);
 
 /*
  * cer_stream_copy -- plain device-to-device copy of `bytes` bytes (rounded down to a multiple of

@@ -35,6 +35,7 @@ EXPORTS = [
     "csr_encode", "csr_matmul", "csr_decode", "csr_get_array", "csr_storage_bits", "csr_device_bytes",
     "csr_clone_device", "csr_free", "cer_cost_model", "csr_cost_model", "dense_cost_model",
     "cer_encode_device", "cer_quantize_uniform", "cer_quantize_encode_device", "cer_matmul_path", "cer_stream_read",
+    "cer_decode_device",
 ]
 
 CER_FORMAT_CER, CER_FORMAT_CSER = 0, 1
@@ -123,6 +124,8 @@ def lib() -> ctypes.CDLL:
         L.csr_cost_model.argtypes = [vp, ctypes.c_int, ctypes.POINTER(CostT)]
         L.dense_cost_model.restype = ctypes.c_int
         L.dense_cost_model.argtypes = [i64, i64, ctypes.c_int, ctypes.POINTER(CostT)]
+        L.cer_decode_device.restype = ctypes.c_int
+        L.cer_decode_device.argtypes = [vp, vp, vp]
         L.cer_stream_read.restype = ctypes.c_int
         L.cer_stream_read.argtypes = [vp, i64, vp, vp]
         L.cer_matmul_path.restype = ctypes.c_int
@@ -242,6 +245,13 @@ def cer_quantize_encode_device(W, m: int, n: int, bits: int, fmt: str = "cer", s
 
 def cer_matmul(h: Handle, X, Y, batch: int, stream=None) -> None:
     _check(lib().cer_matmul(h.ptr, _dev_ptr(X), _dev_ptr(Y), batch, _stream_ptr(stream)), "cer_matmul")
+
+
+def cer_decode_device(h: Handle, W_out, stream=None) -> None:
+    """Writes the dense m x n matrix into the fp32 device tensor W_out."""
+    d = cer_get_dims(h)
+    _check(lib().cer_decode_device(h.ptr, _dev_ptr(W_out) if d["m"] * d["n"] else 0, _stream_ptr(stream)),
+           "cer_decode_device")
 
 
 def cer_matmul_path(h: Handle, batch: int) -> int:

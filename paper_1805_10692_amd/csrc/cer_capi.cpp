@@ -363,6 +363,18 @@ int cer_quantize_encode_device(const float* W, int64_t m, int64_t n, int32_t bit
     return device_front_end(W, m, n, nullptr, 0, bits, format, stream, codebook_out, K_out, out);
 }
 
+int cer_decode_device(const cer_handle_t* h, float* W, void* stream) {
+    if (!h) return CER_E_INVALID;
+    if (!W && h->host->m * h->host->n > 0) return CER_E_INVALID;
+    if (h->device < 0 || !h->d_base) return hip_fail(hipErrorNoDevice);
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev != h->device) return hip_fail(hipErrorInvalidDevice);
+    if (h->host->m * h->host->n > 0 && h->host->K < 1) return CER_E_INVALID;
+    return cer::decode_device(h->view, W, stream);
+}
+
 int cer_quantize_uniform(const float* W, int64_t count, int32_t bits, uint8_t* codes, float* Wq, float* codebook_out,
                          int32_t* K_out, void* stream) {
     if (K_out) *K_out = 0;

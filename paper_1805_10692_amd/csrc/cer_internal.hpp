@@ -87,6 +87,7 @@ int launch_stream_read(const void* src, int64_t bytes, void* sink, void* stream)
 // Device front-end (frontend.hip): W_dev holds codebook values, or (bits > 0) unquantized weights.
 int encode_device(const float* W_dev, int64_t m, int64_t n, const float* codebook, int32_t K, int32_t bits, bool cser,
                   void* stream, float* codebook_out, int32_t* K_out, cer_matrix** out);
+int decode_device(const DeviceView& v, float* W_dev, void* stream);
 int quantize_device(const float* W_dev, int64_t count, int32_t bits, uint8_t* codes_dev, float* Wq_dev,
                     float* codebook_out, int32_t* K_out, void* stream);
 

@@ -526,6 +526,36 @@ __global__ __launch_bounds__(256) void emit_kernel(const uint8_t* __restrict__ c
 }
 
 // ------------------------------------------------------------------------------------------------
+// decode: format arrays -> dense matrix (Section II-A: M is reconstructed uniquely).  One wave per
+// row: the row is filled with Omega[0], then every group writes its value at its columns.
+// ------------------------------------------------------------------------------------------------
+template <typename ColT>
+__global__ __launch_bounds__(256) void decode_kernel(const ColT* __restrict__ colI, const uint32_t* __restrict__ omegaPtr,
+                                                     const uint32_t* __restrict__ rowPtr, const uint8_t* __restrict__ omegaI,
+                                                     int oi_bits, const float* __restrict__ omega, int cser, int64_t m,
+                                                     int64_t n, float* __restrict__ W) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= m) return;
+    float* row = W + r * n;
+    const float w0 = omega[0];
+    for (int64_t j = lane; j < n; j += kWave) row[j] = w0;
+    __threadfence_block();  // the fill has reached memory before another lane overwrites one of its elements
+    const uint32_t g0 = rowPtr[r], g1 = rowPtr[r + 1];
+    for (uint32_t g = g0; g < g1; ++g) {
+        uint32_t rank = g - g0 + 1u;  // Algorithm 3: position in the row; Algorithm 4: OmegaI
+        if (cser) {
+            rank = oi_bits == 8 ? omegaI[g]
+                                : (oi_bits == 16 ? reinterpret_cast<const uint16_t*>(omegaI)[g]
+                                                 : reinterpret_cast<const uint32_t*>(omegaI)[g]);
+        }
+        const float wv = omega[rank];
+        const uint32_t s = omegaPtr[g], e = omegaPtr[g + 1];
+        for (uint32_t i = s + lane; i < e; i += kWave) row[colI[i]] = wv;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
 // Temporary device memory from the stream-ordered pool: released when the work queued before the
@@ -618,6 +648,28 @@ void launch_emit(unsigned blocks, hipStream_t s, const uint8_t* codes, const uin
 }  // namespace
 
 namespace cer {
+
+int decode_device(const DeviceView& v, float* W, void* stream) {
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (v.m == 0 || v.n == 0) return CER_OK;
+    const unsigned blocks = (unsigned)((v.m + 3) / 4);
+    const auto* oi = static_cast<const uint8_t*>(v.omegaI);
+    switch (v.colI_bits) {
+        case 8:
+            decode_kernel<uint8_t><<<blocks, 256, 0, s>>>(static_cast<const uint8_t*>(v.colI), v.omegaPtr, v.rowPtr, oi,
+                                                           v.omegaI_bits, v.omega, v.cser, v.m, v.n, W);
+            break;
+        case 16:
+            decode_kernel<uint16_t><<<blocks, 256, 0, s>>>(static_cast<const uint16_t*>(v.colI), v.omegaPtr, v.rowPtr, oi,
+                                                            v.omegaI_bits, v.omega, v.cser, v.m, v.n, W);
+            break;
+        default:
+            decode_kernel<uint32_t><<<blocks, 256, 0, s>>>(static_cast<const uint32_t*>(v.colI), v.omegaPtr, v.rowPtr, oi,
+                                                            v.omegaI_bits, v.omega, v.cser, v.m, v.n, W);
+    }
+    HIP_TRY(hipGetLastError());
+    return CER_OK;
+}
 
 int quantize_device(const float* W, int64_t count, int32_t bits, uint8_t* codes, float* Wq, float* codebook_out,
                     int32_t* K_out, void* stream) {

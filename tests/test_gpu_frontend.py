@@ -193,3 +193,43 @@ def test_full_size_alexnet_fc6_quantize_encode_device():
     assert got_cb.tobytes() == cb.tobytes()
     _compare(h, A)
     B.cer_free(h)
+
+
+DECODE_CASES = dict(ENCODE_CASES)
+DECODE_CASES["many_groups_u16_ranks"] = lambda: wl.random_lowentropy(m=40, n=9000, K=700, p_dom=0.3, L=1, seed=39, ratio=0.995)
+DECODE_CASES["dominant_nonzero"] = lambda: wl.random_lowentropy(m=33, n=500, K=7, p_dom=0.5, L=1, seed=46, dominant=0)
+
+
+@pytest.mark.parametrize("fmt", ["cer", "cser"])
+@pytest.mark.parametrize("name", list(DECODE_CASES))
+def test_decode_device_round_trip(name, fmt):
+    """Host-encoded handle -> dense matrix on the device: bit for bit the encoder's input (Section II-A)."""
+    w = DECODE_CASES[name]()
+    h = (B.cer_encode if fmt == "cer" else B.cser_encode)(w.W, w.codebook)
+    out = torch.full((w.m, w.n), float("nan"), dtype=torch.float32, device=_gpu())
+    B.cer_decode_device(h, out)
+    torch.cuda.synchronize()
+    B.cer_free(h)
+    want = oracle.decode(oracle.encode(w.W, w.codebook, fmt))
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    assert np.array_equal(want.view(np.uint32), (w.W + np.float32(0)).view(np.uint32))
+
+
+def test_device_only_round_trip_full_size():
+    """Unquantized 4096 x 9216 layer -> quantize + encode -> decode, never leaving the device: the decoded
+    matrix equals the quantizer's own output (cer_quantize_uniform's Wq) and the oracle's, bit for bit."""
+    dev = _gpu()
+    W = wl.dense_weights(4096, 9216, seed=9)
+    Wd = torch.from_numpy(W).to(dev)
+    Wq = torch.empty_like(Wd)
+    cb = B.cer_quantize_uniform(Wd, W.size, 7, None, Wq)
+    for fmt in ("cer", "cser"):
+        h, cb2 = B.cer_quantize_encode_device(Wd, 4096, 9216, 7, fmt)
+        assert cb2.tobytes() == cb.tobytes()
+        out = torch.full_like(Wd, float("nan"))
+        B.cer_decode_device(h, out)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int32), (Wq + 0.0).view(torch.int32))
+        B.cer_free(h)
+    codes, ocb = oq.uniform_quantize(W, 7)
+    assert np.array_equal(Wq.cpu().numpy().view(np.uint32), ocb[codes].view(np.uint32))
