@@ -278,6 +278,44 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
     return out
 
 
+def run_decode(shape: str, fmt: str, steps: int, with_cpu: bool) -> dict:
+    """Times cer_decode_device (handle -> dense fp32 matrix in HBM); checked bit for bit against the matrix that
+    was encoded."""
+    import torch
+
+    from paper_1805_10692_amd import binding as B
+    from paper_1805_10692_amd import workloads as wl
+
+    w = {"vgg_fc6": lambda: wl.vgg_fc6(L=1), "alexnet_fc6": lambda: wl.alexnet_fc6(L=1),
+         "conv3x3": lambda: wl.conv3x3(L=1)}[shape]()
+    h = (B.cser_encode if fmt == "cser" else B.cer_encode)(w.W, w.codebook)
+    out = torch.empty((w.m, w.n), dtype=torch.float32, device="cuda:0")
+    B.cer_decode_device(h, out)
+    torch.cuda.synchronize()
+    if not np.array_equal(out.cpu().numpy().view(np.uint32), (w.W + np.float32(0)).view(np.uint32)):
+        raise SystemExit("decode parity failed")
+    lib, hp, op, stream = B.lib(), h.ptr, out.data_ptr(), torch.cuda.current_stream().cuda_stream
+    wall, ev = time_steps(lambda i: lib.cer_decode_device(hp, op, stream), steps, 3)
+    enc_bytes = B.cer_device_bytes(h)
+    alg = 4 * w.m * w.n + enc_bytes
+    res = {"metric": "decode_dense_output_GBps", "value": 4 * w.m * w.n / (wall * 1e-3) / 1e9, "unit": "GB/s of fp32 output",
+           "ms_per_step": wall, "steps": steps, "n_gpus": 1, "dtype": "u16->f32", "data": "synthetic",
+           "config": {"workload": f"decode_{shape}", "format": fmt, "m": w.m, "n": w.n},
+           "roofline": {"bound": "hbm", "achieved": alg / (ev * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": alg / (ev * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                        "algorithmic_bytes_per_call": alg, "event_us_per_launch": ev * 1e3}}
+    if with_cpu:
+        import oracle
+        A = oracle.encode(w.W, w.codebook, fmt)
+        t0 = time.perf_counter()
+        oracle.decode(A)
+        t_cpu = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": 4 * w.m * w.n / t_cpu / 1e9, "unit": "GB/s of fp32 output", "cores": 1, "kind": "oracle",
+                               "sample": "one whole decode of the same matrix", "ms_per_step": t_cpu * 1e3}
+    B.cer_free(h)
+    return res
+
+
 def run_front_end(kind: str, shape: str, fmt: str, bits: int, steps: int, with_cpu: bool) -> dict:
     """Times the device front-end (not part of the headline metric): `encode` converts an already quantized
     matrix that lives in HBM, `quantize` takes unquantized weights through the uniform quantizer first.
@@ -364,7 +402,7 @@ def run_front_end(kind: str, shape: str, fmt: str, bits: int, steps: int, with_c
 
 def main() -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("--front-end", default=None, choices=("encode", "quantize"),
+    ap.add_argument("--front-end", default=None, choices=("encode", "quantize", "decode"),
                     help="time the device front-end instead of the product (shape from --shape)")
     ap.add_argument("--shape", default="vgg_fc6", choices=("vgg_fc6", "alexnet_fc6", "conv3x3"))
     ap.add_argument("--bits", type=int, default=7)
@@ -393,8 +431,12 @@ def main() -> int:
 
     if args.front_end:
         fe_steps = args.steps if args.steps != ap.get_default("steps") else 20
-        print(json.dumps(run_front_end(args.front_end, args.shape, "cser" if args.format == "cser" else "cer",
-                                       args.bits, fe_steps, not args.no_cpu)), flush=True)
+        fe_fmt = "cser" if args.format == "cser" else "cer"
+        if args.front_end == "decode":
+            print(json.dumps(run_decode(args.shape, fe_fmt, fe_steps, not args.no_cpu)), flush=True)
+        else:
+            print(json.dumps(run_front_end(args.front_end, args.shape, fe_fmt, args.bits, fe_steps, not args.no_cpu)),
+                  flush=True)
         return 0
 
     r = run_one(args.workload, args.format, args.steps, args.warmup, args.warm, not args.no_cpu, not args.no_dense)
