@@ -233,3 +233,26 @@ def test_device_only_round_trip_full_size():
         B.cer_free(h)
     codes, ocb = oq.uniform_quantize(W, 7)
     assert np.array_equal(Wq.cpu().numpy().view(np.uint32), ocb[codes].view(np.uint32))
+
+
+def test_device_encoded_handle_clones_and_inspects_lazily():
+    """A handle encoded on the device has no host copy of its arrays until asked: cloning it, inspecting it,
+    pricing it and decoding it on the host must all fetch them and agree with a host-encoded handle."""
+    dev = _gpu()
+    w = wl.vgg_fc6(L=3, scale=8)
+    Wd = _to_dev(w.W)
+    for fmt in ("cer", "cser"):
+        A = oracle.encode(w.W, w.codebook, fmt)
+        hd = B.cer_encode_device(Wd, w.m, w.n, w.codebook, fmt)
+        hh = (B.cer_encode if fmt == "cer" else B.cser_encode)(w.W, w.codebook)
+        assert B.cer_storage_bits(hd) == B.cer_storage_bits(hh) == oracle.storage_bits(A)     # needs no arrays
+        assert B.cer_cost_model(hd) == B.cer_cost_model(hh)                                    # fetches them
+        assert B.cer_cost_model(hd, B.CER_COUNT_EXAMPLE) == B.cer_cost_model(hh, B.CER_COUNT_EXAMPLE)
+        hc = B.cer_clone_device(hd)
+        B.cer_free(hd)                                                                         # the clone stands alone
+        _compare(hc, A)
+        _check_product(hc, fmt, w.W, w.X)
+        assert np.array_equal((B.cer_decode if fmt == "cer" else B.cser_decode)(hc).view(np.uint32), w.W.view(np.uint32))
+        B.cer_free(hc)
+        B.cer_free(hh)
+    del dev
