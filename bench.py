@@ -35,10 +35,9 @@ METRIC = "CER/CSER W.X dense-equiv GFLOP/s and achieved HBM GB/s (% of peak) vs 
 
 def make_workload(name: str):
     from paper_1805_10692_amd import workloads as wl
-    if name == "vgg_fc6_L1":
-        return wl.vgg_fc6(L=1)
-    if name == "vgg_fc6_L64":
-        return wl.vgg_fc6(L=64)
+    m = re.fullmatch(r"vgg_fc6_L(\d+)", name)
+    if m:
+        return wl.vgg_fc6(L=int(m.group(1)))
     m = re.fullmatch(r"alexnet_fc6_L(\d+)", name)
     if m:
         return wl.alexnet_fc6(L=int(m.group(1)))

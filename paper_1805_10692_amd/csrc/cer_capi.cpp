@@ -73,6 +73,7 @@ void cer::bind_device(cer_matrix* h, int dev, void* base, const DeviceLayout& l)
     v.n = A.n;
     v.max_row_groups = A.max_row_groups;
     v.nnz = A.nnz;
+    v.nonempty_groups = A.nonempty_groups;
     v.omega0 = A.K > 0 ? A.omega[0] : 0.f;
     h->layout = l;
 }

@@ -57,6 +57,7 @@ struct DeviceView {
     int64_t m = 0, n = 0;
     int64_t max_row_groups = 0;
     int64_t nnz = 0;
+    int64_t nonempty_groups = 0;
     float omega0 = 0.f;
 };
 
