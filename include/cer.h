@@ -113,7 +113,10 @@ int cser_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t
 /*
  * cer_matmul_path -- which kernel cer_matmul / cser_matmul runs for this handle and batch:
  *   0  batch-1 kernel: X staged in LDS per workgroup, one wave per row
- *   1  batched kernel that gathers rows of X from L2, one wave per (row, tile of 32 columns)
+ *   1  batched kernel that gathers rows of X from L2, one wave per (row, tile of 32 columns).  By
+ *      default the group values are expanded per colI position into LDS and every gathered row is
+ *      multiplied by its position's value; with the environment variable CER_GEMM_EXPAND=0 the
+ *      gathered rows of a group are summed first and multiplied once (slower on MI355X)
  *   2  batched kernel with the input resident in LDS -- the reuse of input elements that the
  *      paper's Section V-C names as the missing optimisation: a tile of 4 or 8 batch columns of all
  *      n input rows is staged once per workgroup and serves many rows of W.  Applicable when

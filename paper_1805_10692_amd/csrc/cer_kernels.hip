@@ -21,8 +21,11 @@
 //     wave instruction from L2 (whole 128-byte rows of X for the default 32-column tile), two
 //     batches of gathers are kept in flight; the indices come from one coalesced load per 64
 //     positions and a cross-lane read, several batches ahead; workgroups are numbered so that one
-//     XCD's L2 sees as few batch tiles of X as possible.  A second batched kernel keeps a narrow
-//     tile of X in LDS instead (reuse of the input); it is slower on this machine and opt-in.
+//     XCD's L2 sees as few batch tiles of X as possible.  The default batched kernel expands the
+//     group values into a per-position array in LDS and multiplies every gathered row by its
+//     position's value (no cursor in the stream; a multiply-add costs what an add costs); the
+//     cursor variant that sums a group before its one multiplication, and a variant that keeps a
+//     narrow tile of X in LDS (reuse of the input), are slower on this machine and opt-in.
 // Every load that feeds the streams is unconditional and issued in straight-line code (colI is
 // followed by readable padding); positions past a row's end pick up some valid input that lands in
 // a running sum multiplied by the list sentinel's weight 0.
