@@ -77,12 +77,24 @@ __global__ __launch_bounds__(1024) void csr_gemv_kernel(const float* __restrict_
 
 // batch > 1: P lanes x 4 floats (or 1 float when the batch is not a multiple of 4) cover a tile of
 // batch columns, the wave's 64/P sub-groups take consecutive elements.
+template <int P>
+struct CsrIdx {  // one register = 64 consecutive positions; a batch of U windows covers PB positions = KQ registers
+    static constexpr int S = kWave / P, U = 8, PB = U * S;
+    static constexpr int KQ = PB >= kWave ? PB / kWave : 1;
+    static constexpr int D = KQ == 1 ? 8 : (KQ <= 4 ? 4 : 2);  // batches of (index, value) registers in flight
+};
+
+// Same streaming structure as the CER batched kernel, so that the comparison isolates the format: indices AND
+// values are fetched with one coalesced load per 64 positions each and handed to the lanes by cross-lane reads,
+// D batches ahead; two batches of gathers are in flight; every gathered row is multiplied by its element's value.
 template <typename IdxT, int V, int P>
 __global__ __launch_bounds__(256) void csr_gemm_kernel(const float* __restrict__ val, const IdxT* __restrict__ colI,
                                                        const uint32_t* __restrict__ rowPtr, const float* __restrict__ X,
                                                        float* __restrict__ Y, uint32_t m, uint32_t L, uint32_t ntiles,
                                                        uint32_t rowblocks, uint32_t items_per_xcd) {
-    constexpr int S = kWave / P, U = 8, TW = V * P;
+    using G = CsrIdx<P>;
+    constexpr int S = G::S, U = G::U, KQ = G::KQ, D = G::D, TW = V * P;
+    constexpr uint32_t PB = G::PB;
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t xcd = blockIdx.x & 7u, q = blockIdx.x >> 3;
@@ -99,33 +111,65 @@ __global__ __launch_bounds__(256) void csr_gemm_kernel(const float* __restrict__
     float acc[V];
 #pragma unroll
     for (int k = 0; k < V; ++k) acc[k] = 0.f;
-    for (uint32_t base = rs; base < re; base += S * U) {
-        uint32_t idx[U];
-        float w[U];
+
+    uint32_t iq[D][KQ];
+    float vq[D][KQ];
+    float xa[U][V], xb[U][V], wa[U], wb[U];
+#define CSR_LOADQ(d, b)                                             \
+    _Pragma("unroll") for (int qq = 0; qq < KQ; ++qq) {             \
+        iq[d][qq] = (uint32_t)colI[(b) + qq * kWave + lane];        \
+        vq[d][qq] = val[(b) + qq * kWave + lane];                   \
+    }
+#define CSR_GATHER(xv, wv, d)                                                                          \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                    \
+        const int src_ = (int)((u * S) % kWave + sub);                                                 \
+        const uint32_t idx_ = S == kWave ? iq[d][(u * S) / kWave] : (uint32_t)__shfl((int)iq[d][(u * S) / kWave], src_, kWave); \
+        wv[u] = S == kWave ? vq[d][(u * S) / kWave] : __shfl(vq[d][(u * S) / kWave], src_, kWave);     \
+        const float* p_ = xg + (size_t)idx_ * L;                                                       \
+        if (V == 4) {                                                                                  \
+            const float4 t_ = *reinterpret_cast<const float4*>(p_);                                    \
+            xv[u][0] = t_.x; xv[u][1 % V] = t_.y; xv[u][2 % V] = t_.z; xv[u][3 % V] = t_.w;            \
+        } else {                                                                                       \
+            xv[u][0] = p_[0];                                                                          \
+        }                                                                                              \
+    }
+#define CSR_CONSUME(xv, wv, b)                                                         \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) {                                    \
+        const float w_ = ((b) + u * S + sub < re) ? wv[u] : 0.f; /* past the row */    \
+        _Pragma("unroll") for (int k = 0; k < V; ++k) acc[k] = fmaf(w_, xv[u][k], acc[k]); \
+    }
+#define CSR_STEP(xcur, wcur, xnext, wnext, dn, dl, k) \
+    CSR_GATHER(xnext, wnext, dn)                      \
+    CSR_LOADQ(dl, base + ((k) + D) * PB)              \
+    CSR_CONSUME(xcur, wcur, base + (k) * PB)
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t pos = base + u * S + sub;
-            idx[u] = (uint32_t)colI[pos];
-            w[u] = val[pos];
+    for (int d = 0; d < D; ++d) { CSR_LOADQ(d, rs + d * PB) }
+    CSR_GATHER(xa, wa, 0)
+    for (uint32_t base = rs; base < re; base += D * PB) {
+        CSR_STEP(xa, wa, xb, wb, 1 % D, 0, 0)
+        if (D > 2 && base + PB >= re) break;
+        CSR_STEP(xb, wb, xa, wa, 2 % D, 1 % D, 1)
+        if (D > 2) {
+            if (base + 2 * PB >= re) break;
+            CSR_STEP(xa, wa, xb, wb, 3 % D, 2 % D, 2)
+            if (base + 3 * PB >= re) break;
+            CSR_STEP(xb, wb, xa, wa, 4 % D, 3 % D, 3)
         }
-        float xv[U][V];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float* p = xg + (size_t)idx[u] * L;
-            if (V == 4) {
-                const float4 t = *reinterpret_cast<const float4*>(p);
-                xv[u][0] = t.x; xv[u][1 % V] = t.y; xv[u][2 % V] = t.z; xv[u][3 % V] = t.w;
-            } else {
-                xv[u][0] = p[0];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float wu = (base + u * S + sub < re) ? w[u] : 0.f;
-#pragma unroll
-            for (int k = 0; k < V; ++k) acc[k] = fmaf(wu, xv[u][k], acc[k]);
+        if (D > 4) {
+            if (base + 4 * PB >= re) break;
+            CSR_STEP(xa, wa, xb, wb, 5 % D, 4 % D, 4)
+            if (base + 5 * PB >= re) break;
+            CSR_STEP(xb, wb, xa, wa, 6 % D, 5 % D, 5)
+            if (base + 6 * PB >= re) break;
+            CSR_STEP(xa, wa, xb, wb, 7 % D, 6 % D, 6)
+            if (base + 7 * PB >= re) break;
+            CSR_STEP(xb, wb, xa, wa, 0, 7 % D, 7)
         }
     }
+#undef CSR_LOADQ
+#undef CSR_GATHER
+#undef CSR_CONSUME
+#undef CSR_STEP
 #pragma unroll
     for (int off = P; off < kWave; off <<= 1)
 #pragma unroll
