@@ -703,16 +703,37 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const flo
     uint32_t gcur = g0;  // first raw group that may reach into the current chunk
     for (uint32_t c0 = rs; c0 < re; c0 += kExpChunk) {
         const uint32_t c1 = min(re, c0 + (uint32_t)kExpChunk);
+        // request order = arrival order: the chunk's first 64 group pointers, then its indices, then (below) the
+        // first gathers; the expansion then waits for the pointers only and runs under the gathers' L2 latency
+        const PtrTile p_first = load_ptr_tile(v, cser, g0, gcur, g1, lane);
+        const uint32_t g_first = gcur;
         uint32_t iq[D][KQ];
 #pragma unroll
         for (int d = 0; d < D; ++d)
 #pragma unroll
             for (int qq = 0; qq < KQ; ++qq) iq[d][qq] = (uint32_t)colI[c0 + d * PB + qq * kWave + lane];
 
+        Vec<V> xa[U], xb[U];
+#define CER_LOADQ(d, b) \
+    _Pragma("unroll") for (int qq = 0; qq < KQ; ++qq) iq[d][qq] = (uint32_t)colI[(b) + qq * kWave + lane];
+#define CER_GATHER(xv, d)                                                                             \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                   \
+        const uint32_t reg_ = iq[d][(u * S) / kWave];                                                 \
+        const uint32_t idx_ = S == kWave ? reg_ : (uint32_t)__shfl((int)reg_, (int)((u * S) % kWave + sub), kWave); \
+        xv[u].load(xgather + (size_t)idx_ * L);                                                       \
+    }
+#define CER_CONSUME(xv, b) \
+    _Pragma("unroll") for (int u = 0; u < U; ++u) acc.fma(xv[u], val[(b) - c0 + u * S + sub]);
+#define CER_STEP(xcur, xnext, dn, dl, k)   \
+    CER_GATHER(xnext, dn)                  \
+    CER_LOADQ(dl, base + ((k) + D) * PB)   \
+    CER_CONSUME(xcur, base + (k) * PB)
+        CER_GATHER(xa, 0)
+
         // ---- expansion: value of every position of [c0, c1); zeros behind it
         for (uint32_t i = c1 - c0 + lane; i < min(c1 - c0 + PAD, (uint32_t)kExpChunk + PAD); i += kWave) val[i] = 0.f;
         for (uint32_t gt = gcur; gt < g1; gt += kWave) {
-            const PtrTile p = load_ptr_tile(v, cser, g0, gt, g1, lane);
+            const PtrTile p = gt == g_first ? p_first : load_ptr_tile(v, cser, g0, gt, g1, lane);
             const float w = (omega_by_lane ? __shfl(om_l, (int)(p.rank & 63u), kWave) : v.omega[p.rank < v.K ? p.rank : 0u]) - v.omega0;
             const uint32_t s = max(p.s, c0), e = min(p.e, c1);
             const uint32_t len = e > s ? e - s : 0u;
@@ -736,23 +757,7 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const flo
         }
         wave_lds_sync();
 
-        // ---- stream of the chunk: gather, multiply by the position's value, add
-        Vec<V> xa[U], xb[U];
-#define CER_LOADQ(d, b) \
-    _Pragma("unroll") for (int qq = 0; qq < KQ; ++qq) iq[d][qq] = (uint32_t)colI[(b) + qq * kWave + lane];
-#define CER_GATHER(xv, d)                                                                             \
-    _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                   \
-        const uint32_t reg_ = iq[d][(u * S) / kWave];                                                 \
-        const uint32_t idx_ = S == kWave ? reg_ : (uint32_t)__shfl((int)reg_, (int)((u * S) % kWave + sub), kWave); \
-        xv[u].load(xgather + (size_t)idx_ * L);                                                       \
-    }
-#define CER_CONSUME(xv, b) \
-    _Pragma("unroll") for (int u = 0; u < U; ++u) acc.fma(xv[u], val[(b) - c0 + u * S + sub]);
-#define CER_STEP(xcur, xnext, dn, dl, k)   \
-    CER_GATHER(xnext, dn)                  \
-    CER_LOADQ(dl, base + ((k) + D) * PB)   \
-    CER_CONSUME(xcur, base + (k) * PB)
-        CER_GATHER(xa, 0)
+        // ---- stream of the chunk: multiply every gathered row by its position's value, add
         for (uint32_t base = c0; base < c1; base += D * PB) {
             CER_STEP(xa, xb, 1 % D, 0, 0)
             if (D > 2 && base + PB >= c1) break;
