@@ -41,16 +41,24 @@ def make_workload(name: str):
     m = re.fullmatch(r"alexnet_fc6_L(\d+)", name)
     if m:
         return wl.alexnet_fc6(L=int(m.group(1)))
-    if name == "conv3x3_L3136":
-        return wl.conv3x3()
-    if name == "conv3x3_dom_L3136":
-        return wl.conv3x3(nonzero_dominant=True)
+    m = re.fullmatch(r"conv3x3(_dom)?_L(\d+)", name)
+    if m:
+        return wl.conv3x3(L=int(m.group(2)), nonzero_dominant=bool(m.group(1)))
     if name == "c1":
         return wl.config1()
     m = re.fullmatch(r"sweep_K(\d+)_p([0-9.]+)(?:_L(\d+))?", name)
     if m:
         return wl.sweep_cell(int(m.group(1)), float(m.group(2)), L=int(m.group(3) or 16))
     raise SystemExit(f"unknown workload {name}")
+
+
+def kernel_name(fmt: str, L: int, path) -> str:
+    """The kernel that dominates a product (cer_matmul_path's numbering for cer / cser)."""
+    if fmt == "csr":
+        return "csr_gemv_kernel" if L == 1 else "csr_gemm_kernel"
+    return {0: "cer_gemv_kernel",
+            1: "cer_gemm_kernel" if os.environ.get("CER_GEMM_EXPAND", "1") == "0" else "cer_gemm_expand_kernel",
+            2: "cer_xtile_kernel", 3: "decode_kernel + dense_gemm_mfma_kernel"}[path]
 
 
 def algorithmic_bytes(dims: dict, bits: dict, L: int) -> int:
@@ -207,6 +215,7 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
         "algorithmic_GBps": alg_bytes / (ev_ms * 1e-3) / 1e9,
         "gather_GBps_onchip": dims["nnz"] * 4.0 * L / (ev_ms * 1e-3) / 1e9,
         "dense_bytes": 4 * (w.m * w.n + w.n * L + w.m * L),
+        "path": None if fmt == "csr" else B.cer_matmul_path(h0, L),
     }
     for h in handles[1:]:
         free(h)
@@ -445,10 +454,10 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {k: r[k] for k in ("workload", "format", "m", "n", "L", "K", "nnz", "groups", "H_bits", "p0",
-                                     "k_bar", "k_tilde", "cache_state")},
+                                     "k_bar", "k_tilde", "cache_state", "path")},
         "roofline": {"bound": "hbm", "achieved": r["algorithmic_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": r["algorithmic_GBps"] / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": ("csr" if args.format == "csr" else "cer") + ("_gemv_kernel" if r["L"] == 1 else "_gemm_kernel"),
+                     "kernel": kernel_name(args.format, r["L"], r["path"]),
                      "algorithmic_bytes_per_launch": r["algorithmic_bytes"],
                      "event_us_per_launch": r["event_ms_per_step"] * 1e3},
         "cpu_baseline": r.get("cpu_baseline"),

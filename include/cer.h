@@ -102,7 +102,7 @@ int cser_encode(const float* W_host, int64_t m, int64_t n, const float* codebook
  * Work is enqueued on `stream` and the call returns without synchronising.  The caller keeps
  * ownership of X and Y and must keep them alive until the stream has run the work.  When
  * Omega[0] != 0 a stream-ordered temporary of batch floats (plus partial sums) is allocated and
- * released on `stream`; when Omega[0] = 0 (and kernel 2 of cer_matmul_path is not selected) the call
+ * released on `stream`; when Omega[0] = 0 (and cer_matmul_path reports kernel 0 or 1) the call
  * only launches kernels and may be recorded into a HIP graph after one eager call on the device.
  * fp32 arithmetic; the summation order differs from a sequential loop.
  * Errors: CER_E_INVALID (null pointers, batch < 1), CER_E_FORMAT, CER_E_HIP.
@@ -122,6 +122,12 @@ int cser_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t
  *      n input rows is staged once per workgroup and serves many rows of W.  Applicable when
  *      n.16 bytes fit in LDS (n <= about 10000), K <= 64 and no row has more than 63 groups;
  *      for such a product a stream-ordered temporary of about the size of X is used.
+ *   3  decode + dense: the matrix is decoded into a stream-ordered temporary of 4.m.n bytes and
+ *      multiplied on the fp32 matrix cores.  Chosen for batch >= 128 when the estimated time of
+ *      the gathers (4.batch bytes per indexed element through the L1/L2 path) exceeds that of the
+ *      dense contraction, i.e. for matrices with more than about one indexed element in five;
+ *      CER_DENSIFY=1 forces it for every batch > 1, CER_DENSIFY=0 switches it off.  The
+ *      arithmetic is then that of a dense fp32 product (same error bound), not Algorithm 3 / 4.
  * On MI355X kernel 2 was slower than kernel 1 on every measured workload (random LDS gathers are
  * bank-conflict bound), so it runs only when the environment variable CER_XTILE is 1 and it is
  * applicable; CER_XTILE=0 or unset selects kernel 1.  Errors: CER_E_INVALID, CER_E_HIP (no device

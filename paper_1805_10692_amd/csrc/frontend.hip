@@ -18,6 +18,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "../../include/cer.h"
@@ -526,32 +527,125 @@ __global__ __launch_bounds__(256) void emit_kernel(const uint8_t* __restrict__ c
 }
 
 // ------------------------------------------------------------------------------------------------
-// decode: format arrays -> dense matrix (Section II-A: M is reconstructed uniquely).  One wave per
-// row: the row is filled with Omega[0], then every group writes its value at its columns.
+// decode: format arrays -> dense matrix (Section II-A: M is reconstructed uniquely).  One workgroup
+// per row (large matrices) or per (row, every gridDim.y-th segment).  A segment of up to kDecSeg
+// columns is assembled in LDS -- filled with Omega[0], then every indexed position of the row whose
+// column falls into the segment writes its group's value -- and written out once with 16-byte stores,
+// so that HBM sees every line of W exactly once.  Positions are spread over the threads, kDecPer per
+// thread with all index loads issued together; a position finds its group by a binary search in the
+// row's pointers (up to kDecThreads groups at a time in LDS; repeated pointers, CER's empty groups,
+// are skipped by the search).  A row of at most kDecThreads groups and kDecThreads.kDecPer positions
+// keeps its columns and values in registers for all its segments; a larger row reloads them per
+// segment.  Index loads may run past the row's last position into the next row or the readable
+// padding behind colI.
 // ------------------------------------------------------------------------------------------------
+constexpr uint32_t kDecThreads = 256, kDecPer = 8, kDecSeg = 4096;
+
 template <typename ColT>
-__global__ __launch_bounds__(256) void decode_kernel(const ColT* __restrict__ colI, const uint32_t* __restrict__ omegaPtr,
-                                                     const uint32_t* __restrict__ rowPtr, const uint8_t* __restrict__ omegaI,
-                                                     int oi_bits, const float* __restrict__ omega, int cser, int64_t m,
-                                                     int64_t n, float* __restrict__ W) {
-    const uint32_t lane = threadIdx.x & 63u;
-    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (r >= m) return;
-    float* row = W + r * n;
+__global__ __launch_bounds__(kDecThreads) void decode_kernel(
+    const ColT* __restrict__ colI, const uint32_t* __restrict__ omegaPtr, const uint32_t* __restrict__ rowPtr,
+    const uint8_t* __restrict__ omegaI, int oi_bits, const float* __restrict__ omega, int cser, int64_t n,
+    uint32_t seg, uint32_t nseg, float* __restrict__ W) {
+    extern __shared__ __align__(16) float s_row[];  // seg floats
+    __shared__ uint32_t s_ptr[kDecThreads + 1];
+    __shared__ float s_val[kDecThreads];
+    constexpr uint32_t T = kDecThreads, P = kDecPer;
+    const uint32_t tid = threadIdx.x;
+    const int64_t r = blockIdx.x;
     const float w0 = omega[0];
-    for (int64_t j = lane; j < n; j += kWave) row[j] = w0;
-    __threadfence_block();  // the fill has reached memory before another lane overwrites one of its elements
     const uint32_t g0 = rowPtr[r], g1 = rowPtr[r + 1];
-    for (uint32_t g = g0; g < g1; ++g) {
-        uint32_t rank = g - g0 + 1u;  // Algorithm 3: position in the row; Algorithm 4: OmegaI
-        if (cser) {
-            rank = oi_bits == 8 ? omegaI[g]
-                                : (oi_bits == 16 ? reinterpret_cast<const uint16_t*>(omegaI)[g]
-                                                 : reinterpret_cast<const uint32_t*>(omegaI)[g]);
+
+    // pointers and values of the groups gb .. gb + cnt - 1 of this row -> LDS
+    auto stage_groups = [&](uint32_t gb, uint32_t cnt) {
+        if (tid < cnt) {
+            const uint32_t g = gb + tid;
+            uint32_t rank = g - g0 + 1u;  // Algorithm 3: position in the row; Algorithm 4: OmegaI
+            if (cser) {
+                rank = oi_bits == 8 ? omegaI[g]
+                                    : (oi_bits == 16 ? reinterpret_cast<const uint16_t*>(omegaI)[g]
+                                                     : reinterpret_cast<const uint32_t*>(omegaI)[g]);
+            }
+            s_ptr[tid] = omegaPtr[g];
+            s_val[tid] = omega[rank];
         }
-        const float wv = omega[rank];
-        const uint32_t s = omegaPtr[g], e = omegaPtr[g + 1];
-        for (uint32_t i = s + lane; i < e; i += kWave) row[colI[i]] = wv;
+        if (tid == 0) s_ptr[cnt] = omegaPtr[gb + cnt];
+    };
+    // columns and values of the positions pb + tid + k.T < pe (k < P) of the staged groups -> registers
+    uint32_t col[P];
+    float val[P];
+    uint32_t ok = 0;
+    auto load_positions = [&](uint32_t pb, uint32_t pe, uint32_t cnt) {
+        ok = 0;
+#pragma unroll
+        for (uint32_t k = 0; k < P; ++k) col[k] = (uint32_t)colI[pb + tid + k * T];
+#pragma unroll
+        for (uint32_t k = 0; k < P; ++k) {
+            const uint32_t p = pb + tid + k * T;
+            val[k] = 0.f;
+            if (p < pe) {
+                uint32_t lo = 0, hi = cnt;  // s_ptr[lo] <= p < s_ptr[hi]
+                while (hi - lo > 1u) {
+                    const uint32_t mid = (lo + hi) >> 1;
+                    if (s_ptr[mid] <= p) lo = mid; else hi = mid;
+                }
+                val[k] = s_val[lo];
+                ok |= 1u << k;
+            }
+        }
+    };
+    auto scatter = [&](int64_t c0, uint32_t len) {
+#pragma unroll
+        for (uint32_t k = 0; k < P; ++k) {
+            const uint64_t rel = (uint64_t)col[k] - (uint64_t)c0;  // huge when left of the segment
+            if (((ok >> k) & 1u) && rel < len) s_row[rel] = val[k];
+        }
+    };
+
+    const uint32_t ngroups = g1 - g0;
+    bool resident = ngroups <= T;
+    if (resident && ngroups > 0) {
+        stage_groups(g0, ngroups);
+        __syncthreads();
+        const uint32_t pb = s_ptr[0], pe = s_ptr[ngroups];
+        resident = pe - pb <= T * P;  // uniform over the workgroup
+        if (resident) load_positions(pb, pe, ngroups);
+    }
+
+    for (uint32_t si = blockIdx.y; si < nseg; si += gridDim.y) {  // uniform over the workgroup
+        const int64_t c0 = (int64_t)si * seg;
+        if (c0 >= n) break;
+        const uint32_t len = (uint32_t)((n - c0) < (int64_t)seg ? (n - c0) : (int64_t)seg);  // 1 .. seg
+        {
+            const float4 f4 = make_float4(w0, w0, w0, w0);
+            const uint32_t n4 = (len + 3u) >> 2;
+            for (uint32_t j = tid; j < n4; j += T) reinterpret_cast<float4*>(s_row)[j] = f4;
+        }
+        __syncthreads();
+        if (resident) {
+            scatter(c0, len);
+        } else {
+            for (uint32_t gb = g0; gb < g1; gb += T) {
+                const uint32_t cnt = g1 - gb < T ? g1 - gb : T;
+                __syncthreads();  // nobody still searches the previous groups
+                stage_groups(gb, cnt);
+                __syncthreads();
+                const uint32_t pe = s_ptr[cnt];
+                for (uint32_t pb = s_ptr[0]; pb < pe; pb += T * P) {
+                    load_positions(pb, pe, cnt);
+                    scatter(c0, len);
+                }
+            }
+        }
+        __syncthreads();
+        float* out = W + r * n + c0;
+        if ((reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
+            const uint32_t n4 = len >> 2;
+            for (uint32_t j = tid; j < n4; j += T) reinterpret_cast<float4*>(out)[j] = reinterpret_cast<const float4*>(s_row)[j];
+            for (uint32_t j = (n4 << 2) + tid; j < len; j += T) out[j] = s_row[j];
+        } else {
+            for (uint32_t j = tid; j < len; j += T) out[j] = s_row[j];
+        }
+        __syncthreads();  // the segment has been read before the next one is filled
     }
 }
 
@@ -649,26 +743,31 @@ void launch_emit(unsigned blocks, hipStream_t s, const uint8_t* codes, const uin
 
 namespace cer {
 
+namespace {
+template <typename ColT>
+int launch_decode(const DeviceView& v, float* W, hipStream_t s) {
+    // segments of equal length (a multiple of 4 columns, so that aligned rows give aligned segments)
+    const int64_t nseg = (v.n + kDecSeg - 1) / kDecSeg;
+    const uint32_t seg = (uint32_t)((((v.n + nseg - 1) / nseg) + 3) & ~(int64_t)3);
+    if (v.m > 0x7FFFFFFFll || nseg > 0x7FFFFFFFll) return CER_E_INVALID;
+    // one workgroup per row walks all its segments, unless that gives too few workgroups to fill the chip
+    const int64_t split = std::min<int64_t>(std::min<int64_t>(nseg, 65535), std::max<int64_t>(1, 4096 / v.m));
+    decode_kernel<ColT><<<dim3((unsigned)v.m, (unsigned)split), kDecThreads, (size_t)seg * sizeof(float), s>>>(
+        static_cast<const ColT*>(v.colI), v.omegaPtr, v.rowPtr, static_cast<const uint8_t*>(v.omegaI), v.omegaI_bits,
+        v.omega, v.cser, v.n, seg, (uint32_t)nseg, W);
+    HIP_TRY(hipGetLastError());
+    return CER_OK;
+}
+}  // namespace
+
 int decode_device(const DeviceView& v, float* W, void* stream) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (v.m == 0 || v.n == 0) return CER_OK;
-    const unsigned blocks = (unsigned)((v.m + 3) / 4);
-    const auto* oi = static_cast<const uint8_t*>(v.omegaI);
     switch (v.colI_bits) {
-        case 8:
-            decode_kernel<uint8_t><<<blocks, 256, 0, s>>>(static_cast<const uint8_t*>(v.colI), v.omegaPtr, v.rowPtr, oi,
-                                                           v.omegaI_bits, v.omega, v.cser, v.m, v.n, W);
-            break;
-        case 16:
-            decode_kernel<uint16_t><<<blocks, 256, 0, s>>>(static_cast<const uint16_t*>(v.colI), v.omegaPtr, v.rowPtr, oi,
-                                                            v.omegaI_bits, v.omega, v.cser, v.m, v.n, W);
-            break;
-        default:
-            decode_kernel<uint32_t><<<blocks, 256, 0, s>>>(static_cast<const uint32_t*>(v.colI), v.omegaPtr, v.rowPtr, oi,
-                                                            v.omegaI_bits, v.omega, v.cser, v.m, v.n, W);
+        case 8: return launch_decode<uint8_t>(v, W, s);
+        case 16: return launch_decode<uint16_t>(v, W, s);
+        default: return launch_decode<uint32_t>(v, W, s);
     }
-    HIP_TRY(hipGetLastError());
-    return CER_OK;
 }
 
 int quantize_device(const float* W, int64_t count, int32_t bits, uint8_t* codes, float* Wq, float* codebook_out,

@@ -197,6 +197,8 @@ def test_full_size_alexnet_fc6_quantize_encode_device():
 
 DECODE_CASES = dict(ENCODE_CASES)
 DECODE_CASES["many_groups_u16_ranks"] = lambda: wl.random_lowentropy(m=40, n=9000, K=700, p_dom=0.3, L=1, seed=39, ratio=0.995)
+DECODE_CASES["wide_rows_many_groups"] = lambda: wl.random_lowentropy(m=6, n=20003, K=1500, p_dom=0.3, L=1, seed=47, ratio=0.9995)
+DECODE_CASES["wide_rows_aligned"] = lambda: wl.random_lowentropy(m=5, n=12288, K=40, p_dom=0.8, L=1, seed=48)
 DECODE_CASES["dominant_nonzero"] = lambda: wl.random_lowentropy(m=33, n=500, K=7, p_dom=0.5, L=1, seed=46, dominant=0)
 
 
@@ -213,6 +215,21 @@ def test_decode_device_round_trip(name, fmt):
     want = oracle.decode(oracle.encode(w.W, w.codebook, fmt))
     assert np.array_equal(out.cpu().numpy().view(np.uint32), want.view(np.uint32))
     assert np.array_equal(want.view(np.uint32), (w.W + np.float32(0)).view(np.uint32))
+
+
+def test_decode_device_full_size_vgg_fc6():
+    """The 4096 x 25088 matrix of the headline workload, decoded on the device, equals the encoder's input."""
+    dev = _gpu()
+    w = wl.vgg_fc6(L=1)
+    Wd = torch.from_numpy(w.W).to(dev)
+    for fmt in ("cer", "cser"):
+        print(f"full-size decode {fmt}", flush=True)
+        h = (B.cer_encode if fmt == "cer" else B.cser_encode)(w.W, w.codebook)
+        out = torch.full_like(Wd, float("nan"))
+        B.cer_decode_device(h, out)
+        torch.cuda.synchronize()
+        B.cer_free(h)
+        assert torch.equal(out.view(torch.int32), (Wd + 0.0).view(torch.int32))
 
 
 def test_device_only_round_trip_full_size():

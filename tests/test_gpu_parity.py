@@ -202,7 +202,8 @@ def test_full_sweep_cells_all_outputs(K, p0):
 
 
 @pytest.mark.parametrize("variant", [False, True])
-def test_full_conv_batch3136_sampled(variant):
+def test_full_conv_batch3136_sampled(variant, monkeypatch):
+    monkeypatch.setenv("CER_DENSIFY", "0")   # the gather kernels; the decode + dense route has its own test file
     w = wl.conv3x3(nonzero_dominant=variant)
     rows = np.random.default_rng(2).choice(w.m, 6, replace=False)
     sampled_check(w, ("cer", "cser"), np.sort(rows))
