@@ -9,6 +9,7 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <mutex>
 
 #include "cer_internal.hpp"
 
@@ -87,7 +88,23 @@ __global__ __launch_bounds__(256) void dense_gemm_mfma_kernel(const float* __res
     Out += (size_t)blockIdx.z * split_stride;
 
     float4 ra[A_UNITS], rb[B_UNITS];
+    const bool full_mn = kVec && row0 + BM <= m && col0 + BN <= L;  // uniform over the workgroup
     auto fetch = [&](uint32_t k0) {
+        if (full_mn && k0 + BK <= k_end) {
+            // interior tile: no bounds to check
+#pragma unroll
+            for (int i = 0; i < A_UNITS; ++i) {
+                const int u = tid + i * 256;
+                ra[i] = *reinterpret_cast<const float4*>(W + (size_t)(row0 + u / 4) * n + k0 + (u % 4) * 4);
+            }
+#pragma unroll
+            for (int i = 0; i < B_UNITS; ++i) {
+                const int u = tid + i * 256;
+                if (u < BK * BN / 4)
+                    rb[i] = *reinterpret_cast<const float4*>(X + (size_t)(k0 + u / (BN / 4)) * L + col0 + (u % (BN / 4)) * 4);
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < A_UNITS; ++i) {
             const int u = tid + i * 256;
@@ -230,16 +247,48 @@ __global__ __launch_bounds__(1024) void stream_read_kernel(const uint4* __restri
     if ((threadIdx.x & 63u) == 0) sink[blockIdx.x * 16u + (threadIdx.x >> 6)] = acc;
 }
 
+// Compute units of the current device (256 on MI355X).
+int compute_units() {
+    static int units[16];
+    static std::once_flag once[16];
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    if (dev < 0 || dev >= 16) dev = 0;
+    std::call_once(once[dev], [dev] {
+        hipDeviceProp_t p;
+        units[dev] = (hipGetDeviceProperties(&p, dev) == hipSuccess && p.multiProcessorCount > 0) ? p.multiProcessorCount : 256;
+    });
+    return units[dev];
+}
+
 template <int BM, int BN, int WM, int WN>
 hipError_t launch_gemm_cfg(const float* W, const float* X, float* Y, uint32_t m, uint32_t n, uint32_t L,
                            hipStream_t stream) {
     const bool vec = (n % 4 == 0) && (L % 4 == 0) && ((reinterpret_cast<uintptr_t>(W) & 15u) == 0) &&
                      ((reinterpret_cast<uintptr_t>(X) & 15u) == 0);
     const uint32_t gx = (L + BN - 1) / BN, gy = (m + BM - 1) / BM;
-    // split along n until there are about two workgroups per compute unit
+    // Split along n so that the workgroups spread evenly over the compute units: the kernel lasts as long as the
+    // busiest unit, rounds = ceil(workgroups / units) workgroups of ksteps / splits steps each.  A second workgroup
+    // per unit hides the first one's waits; every split costs a partial result written and read again.
     uint32_t splits = 1;
     const uint32_t tiles = gx * gy, ksteps = (n + 15) / 16;
-    if (tiles < 512) splits = std::min<uint32_t>(std::min<uint32_t>((512 + tiles - 1) / tiles, 32u), std::max<uint32_t>(ksteps / 8, 1u));
+    if (tiles < 1024) {
+        const uint32_t units = (uint32_t)std::max(compute_units(), 1);
+        const uint32_t max_splits = std::min<uint32_t>(32u, std::max<uint32_t>(ksteps / 8, 1u));
+        const double step_cycles = (WM / 32) * (WN / 32) * 8 * 64.0;  // matrix-core cycles per step and wave
+        double best = 1e300;
+        for (uint32_t sp = 1; sp <= max_splits; ++sp) {
+            const uint32_t rounds = (tiles * sp + units - 1) / units;
+            const uint32_t steps = (ksteps + sp - 1) / sp;
+            double cost = (double)rounds * steps * step_cycles * (rounds == 1 ? 1.35 : 1.0);
+            // the partial sums: one more launch, and about 6 bytes per cycle and unit written and read again
+            if (sp > 1) cost += 7000.0 + (double)sp * BM * BN * 8.0 * ((double)tiles / units) / 6.0;
+            if (cost < best) {
+                best = cost;
+                splits = sp;
+            }
+        }
+    }
     const uint32_t kchunk = ((ksteps + splits - 1) / splits) * 16;
     splits = (n + kchunk - 1) / kchunk;
     if (splits < 1) splits = 1;
