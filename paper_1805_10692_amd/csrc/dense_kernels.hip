@@ -177,20 +177,27 @@ __global__ __launch_bounds__(256) void dense_gemm_mfma_kernel(const float* __res
     for (uint32_t k0 = k_begin; k0 < k_end; k0 += BK) {
         const bool more = k0 + BK < k_end;
         if (more) fetch(k0 + BK);
+        // operands of the next pair of n-steps are read from LDS while the matrix cores work on the current pair; the
+        // next tile goes to the other LDS buffer three quarters through, under the last products
+        float a[2][TM], b[2][TN];
+        auto frag = [&](int kk, int slot) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[slot][i] = As[buf][kk + (lane >> 5)][wm * WM + i * 32 + (lane & 31)];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[slot][j] = Bs[buf][kk + (lane >> 5)][wn * WN + j * 32 + (lane & 31)];
+        };
+        frag(0, 0);
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
-            float a[TM], b[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = As[buf][kk + (lane >> 5)][wm * WM + i * 32 + (lane & 31)];
-#pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = Bs[buf][kk + (lane >> 5)][wn * WN + j * 32 + (lane & 31)];
+            const int cur = (kk >> 1) & 1;
+            if (kk + 2 < BK) frag(kk + 2, cur ^ 1);
+            if (kk == (3 * BK) / 4 && more) stash(buf ^ 1);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
         }
-        if (more) stash(buf ^ 1);
         __syncthreads();
         buf ^= 1;
     }
