@@ -168,11 +168,17 @@ __global__ __launch_bounds__(256) void points_kernel(const float* __restrict__ p
 // codes: element -> codebook position; per-row histogram.  One workgroup per row (a flat array is
 // cut into rows of row_len elements).
 // ------------------------------------------------------------------------------------------------
+// Look-up of a value's codebook position: open-addressing hash table in LDS over the bit patterns of the (at most
+// 256) codebook values; a free slot holds a pattern no finite value has.
+constexpr uint32_t kHashSlots = 1024, kHashFree = 0xFFFFFFFFu;
+__device__ __forceinline__ uint32_t hash_slot(uint32_t bits) { return (bits * 2654435761u) >> 22; }
+
 struct CodeCtx {
     uint32_t K;
     float wmin, step, top;
-    const float* val;     // LDS: quantizer -> points by position; look-up -> codebook sorted by value
-    const uint32_t* pos;  // LDS: look-up -> position of each sorted value
+    const float* val;      // LDS: quantizer -> points by position
+    const uint32_t* hkey;  // LDS: look-up -> bit pattern stored in each hash slot
+    const uint32_t* hpos;  // LDS: look-up -> codebook position of that value
 };
 
 template <bool kQuant>
@@ -187,15 +193,17 @@ __device__ __forceinline__ uint32_t code_of(float w, const CodeCtx& c, bool& mis
         }
         return (uint32_t)q;
     }
-    const float v = canonical(w);
-    uint32_t lo = 0, hi = c.K;  // first sorted value that is not below v
-    while (lo < hi) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (c.val[mid] < v) lo = mid + 1; else hi = mid;
+    const uint32_t bits = __float_as_uint(canonical(w));
+    uint32_t h = hash_slot(bits);
+    for (;;) {
+        const uint32_t key = c.hkey[h];
+        if (key == kHashFree) {  // not a codebook value (the table always has free slots)
+            missing = true;
+            return 0u;
+        }
+        if (key == bits) return c.hpos[h];
+        h = (h + 1u) & (kHashSlots - 1u);
     }
-    const bool hit = lo < c.K && __float_as_uint(c.val[lo]) == __float_as_uint(v);
-    missing |= !hit;
-    return hit ? c.pos[lo] : 0u;
 }
 
 // Each thread takes four consecutive elements per round: one 16-byte load, four codes, one 4-byte
@@ -206,7 +214,7 @@ __global__ __launch_bounds__(256) void codes_kernel(const float* __restrict__ W,
                                                     uint32_t* __restrict__ cnt, float* __restrict__ Wq, int vec_ok) {
     __shared__ uint32_t s_hist[kCodes];
     __shared__ float s_val[kCodes];
-    __shared__ uint32_t s_pos[kCodes];
+    __shared__ uint32_t s_hkey[kQuant ? 1 : kHashSlots], s_hpos[kQuant ? 1 : kHashSlots];
     const uint32_t t = threadIdx.x;
     const int64_t r = blockIdx.x;
     CodeCtx c;
@@ -215,26 +223,37 @@ __global__ __launch_bounds__(256) void codes_kernel(const float* __restrict__ W,
     if (kQuant) {
         s_val[t] = t < c.K ? st->codebook[t] : 0.f;
     } else {
-        s_val[t] = t < c.K ? st->sorted_val[t] : 0.f;
-        s_pos[t] = t < c.K ? st->sorted_pos[t] : 0u;
+        for (uint32_t i = t; i < kHashSlots; i += 256) s_hkey[i] = kHashFree;
+        __syncthreads();
+        if (t < c.K) {
+            const uint32_t bits = __float_as_uint(canonical(st->sorted_val[t]));
+            uint32_t h = hash_slot(bits);
+            while (atomicCAS(&s_hkey[h], kHashFree, bits) != kHashFree) h = (h + 1u) & (kHashSlots - 1u);
+            s_hpos[h] = st->sorted_pos[t];
+        }
     }
     __syncthreads();
     c.wmin = st->wmin;
     c.step = st->step;
     c.top = (float)(c.K - 1);
     c.val = s_val;
-    c.pos = s_pos;
+    c.hkey = s_hkey;
+    c.hpos = s_hpos;
     const float* row = W + r * row_len;
     uint8_t* crow = codes ? codes + r * row_len : nullptr;
     float* qrow = Wq ? Wq + r * row_len : nullptr;
     const int64_t n = min(row_len, total - r * row_len);  // the last row of a flat array may be short
     bool missing = false;
+    // the next round's four elements are requested before this round's are coded
+    float4 ahead = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (vec_ok && 4 * (int64_t)t + 4 <= n) ahead = *reinterpret_cast<const float4*>(row + 4 * (int64_t)t);
     for (int64_t j0 = 0; j0 < n; j0 += 1024) {
         const int64_t j = j0 + 4 * (int64_t)t;
         uint32_t code[4] = {0, 0, 0, 0};
         const int valid = (int)max((int64_t)0, min((int64_t)4, n - j));
+        const float4 w = ahead;
+        if (vec_ok && j + 1024 + 4 <= n) ahead = *reinterpret_cast<const float4*>(row + j + 1024);
         if (valid == 4 && vec_ok) {
-            const float4 w = *reinterpret_cast<const float4*>(row + j);
             code[0] = code_of<kQuant>(w.x, c, missing);
             code[1] = code_of<kQuant>(w.y, c, missing);
             code[2] = code_of<kQuant>(w.z, c, missing);
@@ -423,39 +442,56 @@ __global__ __launch_bounds__(1024) void scan_rows_kernel(const uint32_t* __restr
 // and take consecutive slots of that rank's bucket in lane (= column) order.
 template <typename ColT>
 __device__ __forceinline__ void scatter64(uint32_t k, int64_t j, uint32_t nbits, uint64_t below, uint32_t* fill,
-                                          ColT* __restrict__ colI) {
+                                          unsigned long long* marks, ColT* __restrict__ colI) {
     const bool act = k >= 1;
     uint64_t peers = __ballot(act);
     if (!peers) return;
-    for (uint32_t b = 0; b < nbits; ++b) {
-        const bool bit = (k >> b) & 1u;
-        const uint64_t votes = __ballot(bit);
-        peers &= bit ? votes : ~votes;
+    if (nbits > 3) {
+        // many ranks: the lanes of a rank meet in that rank's 64-bit word in LDS (all words are zero between calls)
+        if (act) atomicOr(&marks[k], below + 1ull);  // below = 2^lane - 1
+        wave_lds_sync();
+        if (act) peers = marks[k];
+    } else {
+        for (uint32_t b = 0; b < nbits; ++b) {
+            const bool bit = (k >> b) & 1u;
+            const uint64_t votes = __ballot(bit);
+            peers &= bit ? votes : ~votes;
+        }
     }
     if (act) {
         const uint32_t before = (uint32_t)__popcll(peers & below);
         const uint32_t slot = fill[k];
         colI[slot + before] = (ColT)j;
-        if (before == 0) fill[k] = slot + (uint32_t)__popcll(peers);
+        if (before == 0) {
+            fill[k] = slot + (uint32_t)__popcll(peers);
+            if (nbits > 3) marks[k] = 0ull;
+        }
     }
     wave_lds_sync();
 }
+
+constexpr uint32_t kEmitStage = 1024;  // staged entries per wave
 
 template <typename ColT, typename OiT>
 __global__ __launch_bounds__(256) void emit_kernel(const uint8_t* __restrict__ codes, const uint32_t* __restrict__ cnt,
                                                    const uint32_t* __restrict__ rowPtrTmp, const uint32_t* __restrict__ rowOffTmp,
                                                    const FrontState* __restrict__ st, int64_t m, int64_t n, int cser,
-                                                   ColT* __restrict__ colI, uint32_t* __restrict__ omegaPtr,
+                                                   int sparse, ColT* __restrict__ colI, uint32_t* __restrict__ omegaPtr,
                                                    uint32_t* __restrict__ rowPtr, uint2* __restrict__ rowInfo,
                                                    OiT* __restrict__ omegaI) {
     __shared__ uint32_t s_rank[kCodes];
     __shared__ uint32_t s_fill[4][kCodes];  // next free colI slot of each rank's bucket
+    __shared__ uint32_t s_stage[4][kEmitStage];  // (column << 8) | rank of the columns waiting for the scatter
+    __shared__ unsigned long long s_marks[4][kCodes];  // per rank: the lanes of the current batch that hold it
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     s_rank[threadIdx.x] = st->rank_of[threadIdx.x];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) s_marks[w][threadIdx.x] = 0ull;
     __syncthreads();
     const int64_t r = (int64_t)blockIdx.x * 4 + wave;
     if (r >= m) return;
     uint32_t* fill = s_fill[wave];
+    unsigned long long* marks = s_marks[wave];
     const uint32_t Kp = st->Kp;
     const uint32_t g0 = rowPtrTmp[r], off0 = rowOffTmp[r];
     const uint32_t groups = rowPtrTmp[r + 1] - g0;
@@ -500,28 +536,104 @@ __global__ __launch_bounds__(256) void emit_kernel(const uint8_t* __restrict__ c
     const uint32_t nbits = 32u - (uint32_t)__builtin_clz(Kp > 1 ? Kp - 1 : 1u);
     const uint64_t below = (1ull << lane) - 1ull;
     const uint8_t* crow = codes + r * n;
-    if ((n & 3) == 0 && (reinterpret_cast<uintptr_t>(codes) & 3u) == 0) {
-        // 256 columns per round: each lane loads four codes at once (the next round's are requested
-        // before this round's are used); a shuffle hands every lane the code of its own column
+    if (sparse && (n & 3) == 0 && (reinterpret_cast<uintptr_t>(codes) & 3u) == 0 && n <= (int64_t)1 << 24) {
+        // 256 columns per round: each lane loads the codes of four consecutive columns at once (the
+        // next round's are requested before this round's are used).  Most columns hold the most
+        // frequent value and take no part in the scatter: the others are first packed, in column order,
+        // as (column, rank) into a buffer in LDS -- four ballots per 256 columns -- and the scatter with
+        // its ballot per rank bit then runs over full batches of 64 buffered entries.
+        uint32_t* buf = s_stage[wave];
+        uint32_t held = 0;  // wave-uniform
+        auto drain = [&](uint32_t keep_below) {
+            // scatters buffered entries in batches of 64 until fewer than keep_below remain
+            uint32_t done = 0;
+            while (held - done >= keep_below && held > done) {
+                const uint32_t i = done + lane;
+                const uint32_t e = i < held ? buf[i] : 0u;
+                scatter64<ColT>(e & 0xFFu, (int64_t)(e >> 8), nbits, below, fill, marks, colI);
+                done += kWave;
+            }
+            if (done >= held) {
+                held = 0;
+            } else {
+                // fewer than 64 left: move them to the front
+                const uint32_t rest = held - done;
+                const uint32_t e = lane < rest ? buf[done + lane] : 0u;
+                wave_lds_sync();
+                if (lane < rest) buf[lane] = e;
+                wave_lds_sync();
+                held = rest;
+            }
+        };
         const uint32_t* crow4 = reinterpret_cast<const uint32_t*>(crow);
         const int64_t n4 = n >> 2;
-        uint32_t next = lane < n4 ? crow4[lane] : 0u;
-        for (int64_t j0 = 0; j0 < n; j0 += 256) {
-            const uint32_t cur = next;
-            const int64_t q = ((j0 + 256) >> 2) + lane;
-            next = q < n4 ? crow4[q] : 0u;
+        // the code words of four rounds are in flight: a round is short against the memory latency
+        constexpr int kAhead = 4;
+        uint32_t ring[kAhead];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const int64_t j = j0 + 64 * s + lane;
-                const uint32_t v = (uint32_t)__shfl((int)cur, 16 * s + (int)(lane >> 2), kWave);
-                const uint32_t code = (v >> (8u * (lane & 3u))) & 0xFFu;
-                scatter64<ColT>(j < n ? s_rank[code] : 0u, j, nbits, below, fill, colI);
+        for (int d = 0; d < kAhead; ++d) ring[d] = 64 * d + lane < n4 ? crow4[64 * d + lane] : 0u;
+        for (int64_t jb = 0; jb < n; jb += 256 * kAhead) {
+#pragma unroll
+            for (int d = 0; d < kAhead; ++d) {
+                const int64_t j0 = jb + 256 * d;  // may lie beyond the row: then no lane is inside
+                const uint32_t cur = ring[d];
+                const int64_t q = ((j0 + 256 * kAhead) >> 2) + lane;
+                ring[d] = q < n4 ? crow4[q] : 0u;
+                // this lane's four columns are consecutive, so lane order is column order
+                const uint32_t c0 = (uint32_t)j0 + 4u * lane;
+                const bool inside = j0 + 4 * (int64_t)lane < n;
+                uint32_t k[4];
+                uint32_t pos = held, total = 0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    k[i] = inside ? s_rank[(cur >> (8 * i)) & 0xFFu] : 0u;
+                    const uint64_t some = __ballot(k[i] >= 1);
+                    pos += (uint32_t)__popcll(some & below);
+                    total += (uint32_t)__popcll(some);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (k[i] >= 1) buf[pos++] = ((c0 + (uint32_t)i) << 8) | k[i];
+                }
+                held += total;
+                if (held > kEmitStage - 256) {
+                    wave_lds_sync();
+                    drain(kWave);
+                }
+            }
+        }
+        wave_lds_sync();
+        drain(1);
+    } else if ((n & 3) == 0 && (reinterpret_cast<uintptr_t>(codes) & 3u) == 0) {
+        // as above without the buffer (most columns take part): a shuffle hands every lane the code of its own
+        // column, 64 consecutive columns per scatter
+        const uint32_t* crow4 = reinterpret_cast<const uint32_t*>(crow);
+        const int64_t n4 = n >> 2;
+        constexpr int kAhead = 4;
+        uint32_t ring[kAhead];
+#pragma unroll
+        for (int d = 0; d < kAhead; ++d) ring[d] = 64 * d + lane < n4 ? crow4[64 * d + lane] : 0u;
+        for (int64_t jb = 0; jb < n; jb += 256 * kAhead) {
+#pragma unroll
+            for (int d = 0; d < kAhead; ++d) {
+                const int64_t j0 = jb + 256 * d;
+                const uint32_t cur = ring[d];
+                const int64_t q = ((j0 + 256 * kAhead) >> 2) + lane;
+                ring[d] = q < n4 ? crow4[q] : 0u;
+                if (j0 >= n) break;  // uniform
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const int64_t j = j0 + 64 * s + lane;
+                    const uint32_t v = (uint32_t)__shfl((int)cur, 16 * s + (int)(lane >> 2), kWave);
+                    const uint32_t code = (v >> (8u * (lane & 3u))) & 0xFFu;
+                    scatter64<ColT>(j < n ? s_rank[code] : 0u, j, nbits, below, fill, marks, colI);
+                }
             }
         }
     } else {
         for (int64_t j0 = 0; j0 < n; j0 += kWave) {
             const int64_t j = j0 + lane;
-            scatter64<ColT>(j < n ? s_rank[crow[j]] : 0u, j, nbits, below, fill, colI);
+            scatter64<ColT>(j < n ? s_rank[crow[j]] : 0u, j, nbits, below, fill, marks, colI);
         }
     }
 }
@@ -730,11 +842,11 @@ int flags_to_error(uint32_t flags) {
 
 template <typename ColT>
 void launch_emit(unsigned blocks, hipStream_t s, const uint8_t* codes, const uint32_t* cnt, const uint32_t* rowPtrTmp,
-                 const uint32_t* rowOffTmp, const FrontState* st, int64_t m, int64_t n, int cser, unsigned char* b,
-                 const cer::DeviceLayout& l) {
+                 const uint32_t* rowOffTmp, const FrontState* st, int64_t m, int64_t n, int cser, int sparse,
+                 unsigned char* b, const cer::DeviceLayout& l) {
     // rank < K <= 256, so OmegaI is always one byte wide here
     emit_kernel<ColT, uint8_t><<<blocks, 256, 0, s>>>(
-        codes, cnt, rowPtrTmp, rowOffTmp, st, m, n, cser, reinterpret_cast<ColT*>(b + l.off_colI),
+        codes, cnt, rowPtrTmp, rowOffTmp, st, m, n, cser, sparse, reinterpret_cast<ColT*>(b + l.off_colI),
         reinterpret_cast<uint32_t*>(b + l.off_optr), reinterpret_cast<uint32_t*>(b + l.off_rptr),
         reinterpret_cast<uint2*>(b + l.off_ri), reinterpret_cast<uint8_t*>(b + l.off_oi));
 }
@@ -796,25 +908,29 @@ int encode_device(const float* W, int64_t m, int64_t n, const float* codebook, i
     int dev = 0;
     HIP_TRY(hipGetDevice(&dev));
 
-    DeviceBuf st, codes, cnt, rows;
-    HIP_TRY(st.alloc(sizeof(FrontState), s));
-    HIP_TRY(codes.alloc((size_t)N, s));
-    HIP_TRY(cnt.alloc((size_t)m * kCodes * 4, s));
-    HIP_TRY(rows.alloc((size_t)(5 * m + 2) * 4, s));  // rowG, rowN, rowP [m] and rowPtrTmp, rowOffTmp [m + 1]
-    FrontState* sd = st.as<FrontState>();
-    uint32_t* rowG = rows.as<uint32_t>();
+    // one stream-ordered temporary: [state][codes: N bytes][per-row histograms][rowG, rowN, rowP [m], rowPtrTmp, rowOffTmp [m + 1]]
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const size_t off_codes = up(sizeof(FrontState)), off_cnt = off_codes + up((size_t)N);
+    const size_t off_rows = off_cnt + up((size_t)m * kCodes * 4), tmp_bytes = off_rows + up((size_t)(5 * m + 2) * 4);
+    DeviceBuf tmp;
+    HIP_TRY(tmp.alloc(tmp_bytes, s));
+    unsigned char* tp = tmp.as<unsigned char>();
+    FrontState* sd = reinterpret_cast<FrontState*>(tp);
+    uint8_t* codes_d = tp + off_codes;
+    uint32_t* cnt_d = reinterpret_cast<uint32_t*>(tp + off_cnt);
+    uint32_t* rowG = reinterpret_cast<uint32_t*>(tp + off_rows);
     uint32_t* rowN = rowG + m;
     uint32_t* rowP = rowN + m;
     uint32_t* rowPtrTmp = rowP + m;
     uint32_t* rowOffTmp = rowPtrTmp + m + 1;
 
-    int rc = run_codes(W, N, m, n, codebook, K, bits, s, sd, codes.as<uint8_t>(), cnt.as<uint32_t>(), nullptr);
+    int rc = run_codes(W, N, m, n, codebook, K, bits, s, sd, codes_d, cnt_d, nullptr);
     if (rc != CER_OK) return rc;
     const unsigned row_blocks = (unsigned)((m + 3) / 4);
     const int64_t rows_per_block = 16;
-    hist_kernel<<<(unsigned)((m + rows_per_block - 1) / rows_per_block), 256, 0, s>>>(cnt.as<uint32_t>(), m, rows_per_block, sd);
+    hist_kernel<<<(unsigned)((m + rows_per_block - 1) / rows_per_block), 256, 0, s>>>(cnt_d, m, rows_per_block, sd);
     rank_kernel<<<1, 256, 0, s>>>(sd);
-    row_layout_kernel<<<row_blocks, 256, 0, s>>>(cnt.as<uint32_t>(), m, cser ? 1 : 0, sd, rowG, rowN, rowP);
+    row_layout_kernel<<<row_blocks, 256, 0, s>>>(cnt_d, m, cser ? 1 : 0, sd, rowG, rowN, rowP);
     scan_rows_kernel<<<1, 1024, 0, s>>>(rowG, rowN, rowP, m, rowPtrTmp, rowOffTmp, sd);
     HIP_TRY(hipGetLastError());
     FrontState h;
@@ -865,10 +981,12 @@ int encode_device(const float* W, int64_t m, int64_t n, const float* codebook, i
     if (e == hipSuccess) e = hipMemcpyAsync(b + l.off_om, h.omega, (size_t)h.Kp * 4, hipMemcpyHostToDevice, s);
     if (e != hipSuccess) return fail(e);
     const int cs = cser ? 1 : 0;
+    // with fewer than half of the elements indexed the emitter packs them in LDS before it scatters them
+    const int sp = (double)A->nnz * 2.0 < (double)m * (double)n ? 1 : 0;
     switch (A->colI.bits) {
-        case 8: launch_emit<uint8_t>(row_blocks, s, codes.as<uint8_t>(), cnt.as<uint32_t>(), rowPtrTmp, rowOffTmp, sd, m, n, cs, b, l); break;
-        case 16: launch_emit<uint16_t>(row_blocks, s, codes.as<uint8_t>(), cnt.as<uint32_t>(), rowPtrTmp, rowOffTmp, sd, m, n, cs, b, l); break;
-        default: launch_emit<uint32_t>(row_blocks, s, codes.as<uint8_t>(), cnt.as<uint32_t>(), rowPtrTmp, rowOffTmp, sd, m, n, cs, b, l);
+        case 8: launch_emit<uint8_t>(row_blocks, s, codes_d, cnt_d, rowPtrTmp, rowOffTmp, sd, m, n, cs, sp, b, l); break;
+        case 16: launch_emit<uint16_t>(row_blocks, s, codes_d, cnt_d, rowPtrTmp, rowOffTmp, sd, m, n, cs, sp, b, l); break;
+        default: launch_emit<uint32_t>(row_blocks, s, codes_d, cnt_d, rowPtrTmp, rowOffTmp, sd, m, n, cs, sp, b, l);
     }
     e = hipGetLastError();
     if (e == hipSuccess) e = hipStreamSynchronize(s);  // `h.omega` lives on this frame; errors surface here
