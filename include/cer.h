@@ -121,17 +121,19 @@ int cser_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t
  *      paper's Section V-C names as the missing optimisation: a tile of 4 or 8 batch columns of all
  *      n input rows is staged once per workgroup and serves many rows of W.  Applicable when
  *      n.16 bytes fit in LDS (n <= about 10000), K <= 64 and no row has more than 63 groups;
- *      for such a product a stream-ordered temporary of about the size of X is used.
+ *      for a batch of more than one tile a stream-ordered temporary of about the size of X is
+ *      used (a tile-major copy of X).
  *   3  decode + dense: the matrix is decoded into a stream-ordered temporary of 4.m.n bytes and
  *      multiplied on the fp32 matrix cores.  Chosen for batch >= 128 when the estimated time of
  *      the gathers (4.batch bytes per indexed element through the L1/L2 path) exceeds that of the
  *      dense contraction, i.e. for matrices with more than about one indexed element in five;
  *      CER_DENSIFY=1 forces it for every batch > 1, CER_DENSIFY=0 switches it off.  The
  *      arithmetic is then that of a dense fp32 product (same error bound), not Algorithm 3 / 4.
- * On MI355X kernel 2 was slower than kernel 1 on every measured workload (random LDS gathers are
- * bank-conflict bound), so it runs only when the environment variable CER_XTILE is 1 and it is
- * applicable; CER_XTILE=0 or unset selects kernel 1.  Errors: CER_E_INVALID, CER_E_HIP (no device
- * copy).
+ * On MI355X kernel 2 beats kernel 1 for narrow batches of large matrices (kernel 1 moves a whole
+ * 128-byte line per index however narrow the batch) and loses for wide ones (random LDS gathers
+ * are bank-conflict bound): it is chosen when it is applicable, batch <= 8 and the matrix holds
+ * at least 2.5 million indices.  CER_XTILE=1 selects it whenever applicable, CER_XTILE=0 never.
+ * Errors: CER_E_INVALID, CER_E_HIP (no device copy).
  */
 int cer_matmul_path(const cer_handle_t* h, int64_t batch);
 

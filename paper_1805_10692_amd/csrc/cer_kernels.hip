@@ -925,7 +925,8 @@ __device__ __forceinline__ void xt_gather(float (&x)[V], const float* xs, uint32
 template <typename IdxT, int V, int U, bool kCser>
 __global__ __launch_bounds__(kXtWaves* kWave) void cer_xtile_kernel(KView v, const float* __restrict__ Xp,
                                                                    float* __restrict__ Y, const float* __restrict__ T,
-                                                                   uint32_t L, uint32_t ntiles, uint32_t rpw, uint32_t pcap) {
+                                                                   uint32_t L, uint32_t ntiles, uint32_t rpw, uint32_t pcap,
+                                                                   uint32_t raw_x) {
     extern __shared__ __align__(16) unsigned char xt_smem[];
     constexpr uint32_t SU = U * kWave;
     const uint32_t lane = threadIdx.x & (kWave - 1);
@@ -940,7 +941,13 @@ __global__ __launch_bounds__(kXtWaves* kWave) void cer_xtile_kernel(KView v, con
     const uint32_t r_begin = min(v.m, (rb * kXtWaves + wave) * rpw), r_end = min(v.m, r_begin + rpw);
     const uint32_t nrows = r_end - r_begin;
     const uint2 info = v.rowInfo[min(r_begin + lane, r_end)];
-    {   // the input tile: one contiguous piece of Xp
+    if (raw_x) {
+        // Xp is the caller's X, [n][L] row-major with L <= V (one tile): widened to V columns on the way in
+        for (uint32_t i = threadIdx.x; i < xfloats; i += kXtWaves * kWave) {
+            const uint32_t c = i / V, col = i % V;
+            xs[i] = col < L ? Xp[(size_t)c * L + col] : 0.f;
+        }
+    } else {  // the input tile: one contiguous piece of Xp
         const float4* src = reinterpret_cast<const float4*>(Xp + (size_t)tile * xfloats);
         float4* dst = reinterpret_cast<float4*>(xs);
         for (uint32_t i = threadIdx.x; i < xfloats / 4; i += kXtWaves * kWave) dst[i] = src[i];
@@ -1201,7 +1208,7 @@ hipError_t launch_gemm(const KView& k, const float* X, float* Y, const float* T,
         // tile width: all of L up to 32 columns, 32 beyond: one gather = one 128-byte line of an X row, and a
         // wider batch gives more waves (measured on MI355X: 32 beats 16, 64, 128 and 256 at L = 32, 64, 3136)
         uint32_t tw = std::min<uint32_t>(pow2_ceil(L), 32u);
-        tw = std::max<uint32_t>(tw, 4u);
+        tw = std::max<uint32_t>(tw, 8u);  // 4-column tiles (64 distinct rows per gather instruction) measured 1.4 - 3 x slower
         tw = (uint32_t)env_int("CER_GEMM_TILE", (int)tw);
         switch (tw) {
             case 4: return launch_gemm_vp<IdxT, 4, 1>(k, X, Y, T, L, stream);
@@ -1279,22 +1286,24 @@ XtilePlan plan_xtile(const DeviceView& d, uint32_t L) {
     return p;
 }
 
-// Whether the LDS variant is expected to beat the kernel that gathers from L2.  Measured on MI355X it
-// never did: gathers of 16- or 32-byte pieces at random LDS addresses are bank-conflict bound at
-// 32 - 43 B/clk per CU, while the L2 kernel's gathers of whole 128-byte rows sustain 27 - 48 B/clk per
-// CU and amortise every group boundary over 32 batch columns instead of 4 or 8
-// (AlexNet-fc6 shape, batch 32: 62 us against 50 us; 3x3 convolution shape, batch 3136: 536 us
-// against 459 us; 2048 x 2048 cells: 24 us against 8 - 19 us).  The variant therefore runs only on
-// request (CER_XTILE=1).
+// Whether the LDS variant is expected to beat the kernel that gathers from L2.  Measured on MI355X: for wide
+// batches it never does -- gathers of 16- or 32-byte pieces at random LDS addresses are bank-conflict bound at
+// 32 - 43 B/clk per CU, while the L2 kernel's gathers of whole 128-byte rows sustain 27 - 48 B/clk per CU and
+// amortise the group structure over 32 batch columns instead of 4 or 8 (AlexNet-fc6 shape, batch 32: 62 us against
+// 35 us; 3x3 convolution shape, batch 3136: 536 us against 378 us).  For narrow batches it does: the L2 kernel
+// still moves a whole 128-byte line per index, the LDS kernel 16 or 32 bytes (AlexNet-fc6 shape, batch 2 / 3 / 4 /
+// 6 / 8: 28 / 29 / 29 / 37 / 31 us from L2, 23 / 22 / 13 / 28 / 28 us from LDS with the tile-major copy, less
+// without it), provided the matrix is large enough for the gathers to dominate the launch (2048 x 2048 cells with
+// 0.2 - 2 million indices: 6 - 12 us either way, the L2 kernel ahead).
 bool xtile_pays(const XtilePlan& p, const DeviceView& d, uint32_t L) {
-    (void)p; (void)d; (void)L;
-    return false;
+    (void)p;
+    return L <= 8 && d.nnz >= 2500000;
 }
 
 template <typename IdxT, int V, int U>
-hipError_t launch_xtile_v(const KView& k, const XtilePlan& p, const float* Xp, float* Y, const float* T, uint32_t L,
-                          hipStream_t stream, int slot) {
-    using Kern = void (*)(KView, const float*, float*, const float*, uint32_t, uint32_t, uint32_t, uint32_t);
+hipError_t launch_xtile_v(const KView& k, const XtilePlan& p, const float* Xp, uint32_t raw_x, float* Y, const float* T,
+                          uint32_t L, hipStream_t stream, int slot) {
+    using Kern = void (*)(KView, const float*, float*, const float*, uint32_t, uint32_t, uint32_t, uint32_t, uint32_t);
     Kern kern = k.cser ? cer_xtile_kernel<IdxT, V, U, true> : cer_xtile_kernel<IdxT, V, U, false>;
     slot = slot * 2 + (k.cser ? 1 : 0);
     if (p.lds > 48 * 1024) {
@@ -1311,17 +1320,20 @@ hipError_t launch_xtile_v(const KView& k, const XtilePlan& p, const float* Xp, f
             granted[slot][dev] = true;
         }
     }
-    hipLaunchKernelGGL(kern, dim3(p.blocks), dim3(kXtWaves * kWave), p.lds, stream, k, Xp, Y, T, L, p.ntiles, p.rpw, p.pcap);
+    hipLaunchKernelGGL(kern, dim3(p.blocks), dim3(kXtWaves * kWave), p.lds, stream, k, Xp, Y, T, L, p.ntiles, p.rpw, p.pcap,
+                       raw_x);
     return hipGetLastError();
 }
 
 template <typename IdxT>
 hipError_t launch_xtile(const KView& k, const XtilePlan& p, const float* X, float* Y, const float* T, uint32_t L,
                         hipStream_t stream, int idx_slot) {
-    // tile-major copy of X in a stream-ordered temporary (skipped when X is one tile already)
+    // tile-major copy of X in a stream-ordered temporary; a batch of one tile is staged straight from X
     const float* Xp = X;
     float* tmp = nullptr;
-    if (!(p.ntiles == 1 && L == (uint32_t)p.V && (reinterpret_cast<uintptr_t>(X) & 15u) == 0)) {
+    const bool one_tile = p.ntiles == 1;
+    const uint32_t raw_x = one_tile && !(L == (uint32_t)p.V && (reinterpret_cast<uintptr_t>(X) & 15u) == 0) ? 1u : 0u;
+    if (!one_tile) {
         hipError_t e = hipMallocAsync(reinterpret_cast<void**>(&tmp), (size_t)p.ntiles * k.n * p.V * sizeof(float), stream);
         if (e != hipSuccess) return e;
         const int vec_ok = (L % 4 == 0 && (reinterpret_cast<uintptr_t>(X) & 15u) == 0) ? 1 : 0;
@@ -1337,8 +1349,8 @@ hipError_t launch_xtile(const KView& k, const XtilePlan& p, const float* X, floa
         }
         Xp = tmp;
     }
-    hipError_t e = p.V == 8 ? launch_xtile_v<IdxT, 8, 3>(k, p, Xp, Y, T, L, stream, idx_slot * 2 + 1)
-                            : launch_xtile_v<IdxT, 4, 8>(k, p, Xp, Y, T, L, stream, idx_slot * 2);
+    hipError_t e = p.V == 8 ? launch_xtile_v<IdxT, 8, 3>(k, p, Xp, raw_x, Y, T, L, stream, idx_slot * 2 + 1)
+                            : launch_xtile_v<IdxT, 4, 8>(k, p, Xp, raw_x, Y, T, L, stream, idx_slot * 2);
     if (tmp) {
         hipError_t f = hipFreeAsync(tmp, stream);
         if (e == hipSuccess) e = f;

@@ -22,7 +22,7 @@ def force_lds_variant():
     os.environ["CER_XTILE"] = "1"
     yield
     if old is None:
-        del os.environ["CER_XTILE"]
+        os.environ.pop("CER_XTILE", None)
     else:
         os.environ["CER_XTILE"] = old
 
@@ -129,3 +129,39 @@ def test_full_size_alexnet_fc6_batch32_sampled():
         B.cer_free(h)
         assert np.isfinite(Y).all()
         assert np.all(np.abs(Y[rows].astype(np.float64) - want) <= TOL * scale)
+
+
+def test_automatic_choice_for_narrow_batches():
+    """Left to itself the library takes this kernel for narrow batches of a large matrix whose input fits in LDS
+    (measured 1.1 - 2.2 x faster there) and nowhere else; the products it then computes match the oracle."""
+    del os.environ["CER_XTILE"]          # the fixture restores it
+    dev = _gpu()
+    w = wl.alexnet_fc6(L=3)
+    h = B.cer_encode(w.W, w.codebook)
+    assert [B.cer_matmul_path(h, L) for L in (1, 2, 3, 4, 8, 9, 32)] == [0, 2, 2, 2, 2, 1, 1]
+    rows = np.sort(np.random.default_rng(5).choice(w.m, 256, replace=False))
+    Wr = np.ascontiguousarray(w.W[rows])
+    rng = np.random.default_rng(6)
+    for L in (2, 3, 4, 7):
+        X = rng.standard_normal((w.n, L)).astype(np.float32)
+        # at an address that is only 4-byte aligned as well: the tile is then staged element by element
+        for shift in (0, 1):
+            buf = torch.zeros(w.n * L + 1, dtype=torch.float32, device=dev)
+            Xd = buf[shift:shift + w.n * L]
+            Xd.copy_(torch.from_numpy(X).reshape(-1))
+            Yd = torch.full((w.m, L), float("nan"), dtype=torch.float32, device=dev)
+            B.cer_matmul(h, Xd, Yd, L)
+            torch.cuda.synchronize()
+            Y = Yd.cpu().numpy().astype(np.float64)
+            want, scale = oracle.dot_dense(Wr, X, threads=8), oracle.abs_dot_dense(Wr, X, threads=8)
+            assert np.isfinite(Y).all()
+            assert np.all(np.abs(Y[rows] - want) <= TOL * scale), f"L={L} shift={shift}"
+    B.cer_free(h)
+    small = wl.sweep_cell(16, 0.9, L=4)             # 0.4 million indices: the launch dominates, L2 gathers stay
+    h = B.cer_encode(small.W, small.codebook)
+    assert B.cer_matmul_path(h, 4) == 1
+    B.cer_free(h)
+    big = wl.vgg_fc6(L=4)                           # 25088 input rows do not fit in LDS
+    h = B.cer_encode(big.W, big.codebook)
+    assert B.cer_matmul_path(h, 4) == 1
+    B.cer_free(h)
