@@ -113,7 +113,9 @@ int cser_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t
 /*
  * cer_matmul_path -- which kernel cer_matmul / cser_matmul runs for this handle and batch:
  *   0  batch-1 kernel: X staged in LDS per workgroup, one wave per row
- *   1  batched kernel that gathers rows of X from L2, one wave per (row, tile of 32 columns).  By
+ *   1  batched kernel that gathers rows of X from L2, one wave per (row, tile of batch columns: 32
+ *      when a row of X is a whole number of 128-byte lines, else 32, 64 or 128 by the cache lines
+ *      the gathers touch; any width and 4-byte aligned X / Y are served by 16-byte gathers).  By
  *      default the group values are expanded per colI position into LDS and every gathered row is
  *      multiplied by its position's value; with the environment variable CER_GEMM_EXPAND=0 the
  *      gathered rows of a group are summed first and multiplied once (slower on MI355X)

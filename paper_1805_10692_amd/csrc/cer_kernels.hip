@@ -36,6 +36,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <mutex>
+#include <numeric>
 
 #include "cer_internal.hpp"
 
@@ -200,6 +201,7 @@ template <> struct Vec<1> {
     __device__ __forceinline__ void fma(const Vec& r, float w) { a = fmaf(r.a, w, a); }
     __device__ __forceinline__ void fma_if(bool c, const Vec& r, float w) { a = fmaf(c ? r.a : 0.f, w, a); }
     __device__ __forceinline__ void load(const float* p) { a = *p; }
+    __device__ __forceinline__ void load_unaligned(const float* p) { a = *p; }
     __device__ __forceinline__ void store(float* p) const { *p = a; }
     __device__ __forceinline__ void xor_add(int off) { a += __shfl_xor(a, off, kWave); }
     __device__ __forceinline__ void add_scaled(const float* t, float s) { a = fmaf(s, t[0], a); }
@@ -222,6 +224,12 @@ template <> struct Vec<4> {
         a.z = fmaf(c ? r.a.z : 0.f, w, a.z); a.w = fmaf(c ? r.a.w : 0.f, w, a.w);
     }
     __device__ __forceinline__ void load(const float* p) { a = *reinterpret_cast<const float4*>(p); }
+    // the same 16-byte load from an address that is only 4-byte aligned (legal for global memory on this target)
+    __device__ __forceinline__ void load_unaligned(const float* p) {
+        typedef float F4u __attribute__((ext_vector_type(4), aligned(4)));
+        const F4u t = *reinterpret_cast<const F4u*>(p);
+        a = make_float4(t.x, t.y, t.z, t.w);
+    }
     __device__ __forceinline__ void store(float* p) const { *reinterpret_cast<float4*>(p) = a; }
     __device__ __forceinline__ void xor_add(int off) {
         a.x += __shfl_xor(a.x, off, kWave); a.y += __shfl_xor(a.y, off, kWave);
@@ -662,10 +670,26 @@ __global__ __launch_bounds__(256) void cer_gemm_kernel(KView v, const float* __r
 // one multiplication saves nothing on this machine -- a fused multiply-add costs what an add costs --
 // so this kernel beat the cursor kernel above on every measured workload, not only on short groups.
 
+// Writes the columns colx .. colx + 3 of a row that are not below `first` (the lane's nominal first column).
+__device__ __forceinline__ void ragged_store(const Vec<4>& acc, float* yrow, const float* T, float omega0, uint32_t colx,
+                                             uint32_t first) {
+    const float o[4] = {acc.a.x, acc.a.y, acc.a.z, acc.a.w};
+#pragma unroll
+    for (uint32_t e = 0; e < 4; ++e) {
+        const uint32_t c = colx + e;
+        if (c >= first) yrow[c] = omega0 != 0.f ? fmaf(omega0, T[c], o[e]) : o[e];
+    }
+}
+__device__ __forceinline__ void ragged_store(const Vec<1>&, float*, const float*, float, uint32_t, uint32_t) {}
+
 constexpr int kExpChunk = 2048;  // colI positions whose values one expansion holds (8 KiB per wave)
 constexpr uint32_t kExpLong = 16;  // groups longer than this are written by the whole wave
 
-template <typename IdxT, int V, int P>
+// kRagged (V = 4 only): the batch width is not a multiple of 4 or X / Y are only 4-byte aligned.  The gathers are
+// 16-byte loads from 4-byte aligned addresses; the lanes of the last, partial column group take the row's last four
+// columns instead (all loads stay inside the row) and write only the columns no other lane owns; Y is written
+// element by element.
+template <typename IdxT, int V, int P, bool kRagged>
 __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
                                                               const float* __restrict__ T, uint32_t L, uint32_t ntiles,
                                                               uint32_t rowblocks, uint32_t items_per_xcd) {
@@ -689,7 +713,9 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const flo
     const uint32_t sub = lane / P;
     const uint32_t col0 = tile * TW + (lane % P) * V;
     const bool active = col0 < L;
-    const float* xgather = X + (active ? col0 : 0u);
+    static_assert(!kRagged || V == 4, "ragged batches are gathered four columns at a time");
+    const uint32_t colx = kRagged ? min(col0, L - 4u) : col0;  // ragged: L >= 4 (the launcher sees to it)
+    const float* xgather = X + (active ? colx : 0u);
     const IdxT* colI = static_cast<const IdxT*>(v.colI);
     float* val = s_val[wave];
 
@@ -721,7 +747,7 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const flo
     _Pragma("unroll") for (int u = 0; u < U; ++u) {                                                   \
         const uint32_t reg_ = iq[d][(u * S) / kWave];                                                 \
         const uint32_t idx_ = S == kWave ? reg_ : (uint32_t)__shfl((int)reg_, (int)((u * S) % kWave + sub), kWave); \
-        xv[u].load(xgather + (size_t)idx_ * L);                                                       \
+        if (kRagged) xv[u].load_unaligned(xgather + (size_t)idx_ * L); else xv[u].load(xgather + (size_t)idx_ * L); \
     }
 #define CER_CONSUME(xv, b) \
     _Pragma("unroll") for (int u = 0; u < U; ++u) acc.fma(xv[u], val[(b) - c0 + u * S + sub]);
@@ -789,8 +815,12 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const flo
 #pragma unroll
     for (int off = P; off < kWave; off <<= 1) acc.xor_add(off);
     if (sub == 0 && active) {
-        if (v.omega0 != 0.f) acc.add_scaled(T + col0, v.omega0);
-        acc.store(Y + (size_t)r * L + col0);
+        if (kRagged) {
+            ragged_store(acc, Y + (size_t)r * L, T, v.omega0, colx, col0);
+        } else {
+            if (v.omega0 != 0.f) acc.add_scaled(T + col0, v.omega0);
+            acc.store(Y + (size_t)r * L + col0);
+        }
     }
 }
 
@@ -1186,11 +1216,25 @@ hipError_t launch_gemm_vp(const KView& k, const float* X, float* Y, const float*
     if (nitems > 0x7FFFFFFFull / 8) return hipErrorInvalidValue;
     const uint32_t ipx = (uint32_t)((nitems + 7) / 8);
     if (env_int("CER_GEMM_EXPAND", 1) != 0)
-        hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, V, P>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L, ntiles,
-                           rowblocks, ipx);
+        hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, V, P, false>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L,
+                           ntiles, rowblocks, ipx);
     else
         hipLaunchKernelGGL((cer_gemm_kernel<IdxT, V, P>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L, ntiles,
                            rowblocks, ipx);
+    return hipGetLastError();
+}
+
+// The default kernel on a batch whose width is not a multiple of 4, or whose X / Y are only 4-byte aligned (L >= 4).
+template <typename IdxT, int P>
+hipError_t launch_gemm_ragged(const KView& k, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream) {
+    constexpr uint32_t TW = 4 * P;
+    const uint32_t ntiles = (L + TW - 1) / TW;
+    const uint32_t rowblocks = (k.m + 3) / 4;
+    const uint64_t nitems = (uint64_t)ntiles * rowblocks;
+    if (nitems > 0x7FFFFFFFull / 8 || L < 4) return hipErrorInvalidValue;
+    const uint32_t ipx = (uint32_t)((nitems + 7) / 8);
+    hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, P, true>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L, ntiles,
+                       rowblocks, ipx);
     return hipGetLastError();
 }
 
@@ -1198,6 +1242,38 @@ inline uint32_t pow2_ceil(uint32_t x) {
     uint32_t p = 1;
     while (p < x) p <<= 1;
     return p;
+}
+
+// Tile width (32, 64 or 128 batch columns) for a batch wider than 32 columns.  A gather instruction costs what the
+// cache lines it touches cost: when a row of X is a whole number of 128-byte lines, 32-column tiles touch exactly the
+// lines they need; otherwise every piece of a row touches up to one line more than its width, and wider tiles mean
+// fewer pieces.  Against that stand the lanes a wide tile leaves idle on a narrow batch and the waves it leaves
+// unlaunched on a matrix of few rows.  Measured on MI355X (AlexNet-fc6 shape, 32 / 64 / 128 columns per tile):
+// batch 96: 91 / 115 / 107 us; batch 100: 186 / 145 / 120 us; batch 40: 99 / 67 / 105 us; 3x3 convolution shape,
+// batch 100 (512 rows): 35 / 30 / 44 us.
+uint32_t pick_wide_tile(uint32_t L, uint32_t m, const float* X, uint32_t max_tile) {
+    const uint32_t row_bytes = L * 4u, base = (uint32_t)(reinterpret_cast<uintptr_t>(X) & 127u);
+    const uint32_t step = std::gcd(row_bytes, 128u);  // rows start at base + multiples of this within a line
+    auto lines = [&](uint32_t offset, uint32_t bytes) {  // average number of lines a piece of a row touches
+        double sum = 0;
+        uint32_t cnt = 0;
+        for (uint32_t ph = 0; ph < 128u; ph += step, ++cnt) sum += (double)(((base + ph + offset) % 128u + bytes + 127u) / 128u);
+        return sum / cnt;
+    };
+    uint32_t best_tile = 32;
+    double best = 1e300;
+    for (uint32_t tw = 32; tw <= max_tile; tw *= 2) {
+        const uint32_t ntiles = (L + tw - 1) / tw, last_cols = L - (ntiles - 1) * tw;
+        const double fill = (double)L / ((double)ntiles * tw);
+        const double waves = (double)m * ntiles;
+        double cost = (ntiles - 1) * lines(0, tw * 4u) + lines(((ntiles - 1) * tw * 4u) % 128u, last_cols * 4u);
+        cost *= std::max(1.0, 0.62 / fill) / std::min(1.0, waves / 1024.0);
+        if (cost < 0.95 * best) {
+            best = cost;
+            best_tile = tw;
+        }
+    }
+    return best_tile;
 }
 
 template <typename IdxT>
@@ -1209,6 +1285,7 @@ hipError_t launch_gemm(const KView& k, const float* X, float* Y, const float* T,
         // wider batch gives more waves (measured on MI355X: 32 beats 16, 64, 128 and 256 at L = 32, 64, 3136)
         uint32_t tw = std::min<uint32_t>(pow2_ceil(L), 32u);
         tw = std::max<uint32_t>(tw, 8u);  // 4-column tiles (64 distinct rows per gather instruction) measured 1.4 - 3 x slower
+        if (L > 32) tw = pick_wide_tile(L, k.m, X, 128u);
         tw = (uint32_t)env_int("CER_GEMM_TILE", (int)tw);
         switch (tw) {
             case 4: return launch_gemm_vp<IdxT, 4, 1>(k, X, Y, T, L, stream);
@@ -1219,6 +1296,18 @@ hipError_t launch_gemm(const KView& k, const float* X, float* Y, const float* T,
             case 128: return launch_gemm_vp<IdxT, 4, 32>(k, X, Y, T, L, stream);
             case 256: return launch_gemm_vp<IdxT, 4, 64>(k, X, Y, T, L, stream);
             default: return hipErrorInvalidValue;
+        }
+    }
+    if (L >= 4 && env_int("CER_GEMM_EXPAND", 1) != 0 && env_int("CER_GEMM_RAGGED", 1) != 0) {
+        // ragged width or 4-byte aligned buffers: still four columns per lane (CER_GEMM_RAGGED=0: one column per lane)
+        uint32_t rtw = std::max<uint32_t>(std::min<uint32_t>(pow2_ceil(L), 32u), 8u);
+        if (L > 32) rtw = pick_wide_tile(L, k.m, X, 128u);
+        switch (rtw) {
+            case 8: return launch_gemm_ragged<IdxT, 2>(k, X, Y, T, L, stream);
+            case 16: return launch_gemm_ragged<IdxT, 4>(k, X, Y, T, L, stream);
+            case 32: return launch_gemm_ragged<IdxT, 8>(k, X, Y, T, L, stream);
+            case 64: return launch_gemm_ragged<IdxT, 16>(k, X, Y, T, L, stream);
+            default: return launch_gemm_ragged<IdxT, 32>(k, X, Y, T, L, stream);
         }
     }
     const uint32_t tw = std::min<uint32_t>(pow2_ceil(L), 64u);

@@ -1,7 +1,8 @@
-"""GPU parity of both batched kernels that gather from L2 -- the default one (group values expanded per
-position in LDS, then a plain multiply-add stream; CER_GEMM_EXPAND=1) and the cursor variant that sums each
-group before its one multiplication (CER_GEMM_EXPAND=0) -- on every kind of matrix, against the oracle under
-the usual bound."""
+"""GPU parity of the batched kernels that gather from L2 -- the default one (group values expanded per
+position in LDS, then a plain multiply-add stream; CER_GEMM_EXPAND=1), the cursor variant that sums each
+group before its one multiplication (CER_GEMM_EXPAND=0), and the default one with ragged batch widths served
+one column per lane instead of by 16-byte gathers (CER_GEMM_RAGGED=0) -- on every kind of matrix, against the
+oracle under the usual bound."""
 import os
 
 import numpy as np
@@ -13,15 +14,23 @@ from test_gpu_parity import full_check
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=["1", "0"], ids=["expand", "cursor"])
+VARIANTS = {
+    "expand": {"CER_GEMM_EXPAND": "1", "CER_GEMM_RAGGED": "1"},            # the defaults
+    "cursor": {"CER_GEMM_EXPAND": "0", "CER_GEMM_RAGGED": "1"},
+    "expand_one_column_per_lane": {"CER_GEMM_EXPAND": "1", "CER_GEMM_RAGGED": "0"},   # ragged widths without 16-byte gathers
+}
+
+
+@pytest.fixture(autouse=True, params=list(VARIANTS), ids=list(VARIANTS))
 def variant(request):
-    old = os.environ.get("CER_GEMM_EXPAND")
-    os.environ["CER_GEMM_EXPAND"] = request.param
+    old = {k: os.environ.get(k) for k in VARIANTS[request.param]}
+    os.environ.update(VARIANTS[request.param])
     yield
-    if old is None:
-        del os.environ["CER_GEMM_EXPAND"]
-    else:
-        os.environ["CER_GEMM_EXPAND"] = old
+    for k, v in old.items():
+        if v is None:
+            os.environ.pop(k, None)
+        else:
+            os.environ[k] = v
 
 
 CASES = {
@@ -50,7 +59,7 @@ def test_batched_variants_all_elements(name):
     full_check(CASES[name]())
 
 
-@pytest.mark.parametrize("L", [2, 3, 4, 5, 16, 17, 33, 64, 65, 100, 260])
+@pytest.mark.parametrize("L", [2, 3, 4, 5, 6, 7, 9, 13, 16, 17, 31, 33, 34, 50, 64, 65, 100, 260])
 def test_batched_variants_ragged_batch_widths(L):
     full_check(wl.random_lowentropy(m=67, n=1500, K=48, p_dom=0.3, L=L, seed=400 + L, ratio=0.97))
 

@@ -97,8 +97,8 @@ def test_rows_without_entries_and_unaligned_pointers():
         want = oracle.dot(oracle.encode(w.W, w.codebook, fmt), w.X)
         check(run_matmul(fmt, w.W, w.codebook, w.X), want, scale, f"empty rows/{fmt}")
     # X and Y at addresses that are only 4-byte aligned (vector paths must not be taken)
-    for L in (1, 4):
-        X = w.X[:, :L].copy()
+    for L in (1, 4, 7, 12, 40):
+        X = wl.sample_X(np.random.Generator(np.random.PCG64(900 + L)), w.n, L)
         h = B.cer_encode(w.W, w.codebook)
         Xbuf = torch.zeros(X.size + 1, dtype=torch.float32, device=dev)
         Ybuf = torch.full((w.m * L + 1,), float("nan"), dtype=torch.float32, device=dev)
