@@ -1459,7 +1459,7 @@ hipError_t launch_colsum(const float* X, uint32_t n, uint32_t L, float* part, ui
 
 // Large batches of a matrix that is not sparse enough: the gathers move nnz.4.batch bytes through the L1/L2 path
 // (measured 18 - 31 TB/s chip-wide, 24 taken here), the fp32 matrix cores need 2.m.n.batch flops (the dense kernel
-// of this library: about 20 us + flops / 80 TFLOP/s below 30 GFLOP, / 105 TFLOP/s above), so from about one indexed
+// of this library: 12 - 20 us + flops / 90 ... 120 TFLOP/s, rising with the size), so from about one indexed
 // element in five upwards the dense contraction is the faster way to the same Y.  The matrix is then decoded into a
 // stream-ordered temporary (4.m.n bytes, bounded here; written at about 4.5 TB/s) and multiplied on the matrix
 // cores.  Measured on MI355X, gathers against decode + dense: 3x3 convolution shape (60 % zeros) batch 3136
@@ -1472,7 +1472,8 @@ bool densify_pays(const DeviceView& d, uint32_t L) {
     if (mn * 4.0 > (double)(1ull << 30)) return false;
     const double flops = 2.0 * mn * L;
     const double t_gather = (double)d.nnz * 4.0 * L / 24e12;
-    const double t_dense = 20e-6 + flops / (flops < 3e10 ? 80e12 : 105e12) + 4.0 * mn / 4.5e12 + 3e-6;
+    const double rate = flops < 1.5e10 ? 90e12 : (flops < 1e11 ? 105e12 : 120e12);
+    const double t_dense = (flops < 5e9 ? 20e-6 : 12e-6) + flops / rate + 4.0 * mn / 4.5e12 + 3e-6;
     return t_gather > 1.1 * t_dense;
 }
 
