@@ -10,6 +10,9 @@ reside in device memory.  By default successive steps rotate over R independent 
 the encoded matrix, R chosen so that the copies exceed twice the 256 MB last-level cache: every
 step then streams its arrays from HBM ("cold").  --warm reuses one copy (cache-resident numbers).
 
+Workloads: vgg_fc6_L<L> (default vgg_fc6_L1), alexnet_fc6_L<L>, conv3x3_L<L>, conv3x3_dom_L<L>, c1,
+sweep_K<K>_p<p0>[_L<L>].  --front-end encode|quantize|decode times the device-side conversion calls instead.
+
 Prints ONE JSON line on stdout; --report writes a table over several workloads to a file.
 """
 from __future__ import annotations

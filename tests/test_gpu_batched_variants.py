@@ -85,3 +85,11 @@ def test_batched_variants_hand_built_rows():
     w = Case()
     w.name, w.W, w.codebook, w.X, w.m, w.n, w.L = "hand-built", W, cb, X, 12, n, 8
     full_check(w)
+
+
+@pytest.mark.parametrize("L", [36, 40, 50, 72, 99, 100, 130, 200])
+def test_batched_variants_tile_widths_by_cache_lines(L):
+    """Enough rows for the launcher to pick 64- and 128-column tiles when the rows of X are not whole
+    cache lines (widths 40, 72, 100, 200: aligned; 50, 99, 130: served by 16-byte gathers from 4-byte
+    aligned rows; 36: one partial tile)."""
+    full_check(wl.random_lowentropy(m=1100, n=700, K=12, p_dom=0.8, L=L, seed=700 + L), fmts=("cer",))
