@@ -104,7 +104,9 @@ int cser_encode(const float* W_host, int64_t m, int64_t n, const float* codebook
  * Omega[0] != 0 a stream-ordered temporary of batch floats (plus partial sums) is allocated and
  * released on `stream`; when Omega[0] = 0 (and cer_matmul_path reports kernel 0 or 1) the call
  * only launches kernels and may be recorded into a HIP graph after one eager call on the device.
- * fp32 arithmetic; the summation order differs from a sequential loop.
+ * fp32 arithmetic; the summation order differs from a sequential loop.  With Omega[0] != 0 the
+ * rounding error is relative to sum|w||x| + |Omega[0]|.sum|x|: Appendix A-A1 adds that term and
+ * subtracts it again inside the groups' weights.
  * Errors: CER_E_INVALID (null pointers, batch < 1), CER_E_FORMAT, CER_E_HIP.
  */
 int cer_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t batch, void* stream);

@@ -325,3 +325,27 @@ def test_unaligned_device_pointers(L):
     B.dense_matmul(Wd, Xd, Yd, w.m, w.n, L)
     torch.cuda.synchronize()
     check(Yd.cpu().numpy().reshape(w.m, L), want, scale, f"unaligned dense L={L}")
+
+
+def test_dominant_value_term_error_scale():
+    """Appendix A-A1 adds Omega[0].sum_i x_i and subtracts Omega[0] inside every group's weight, so with a non-zero
+    most frequent value the rounding error scales with |Omega[0]|.sum|x| as well.  A matrix of one column whose most
+    frequent value is large against its other weights (one of them 0) shows it: the results stay inside
+    1e-5 (sum|w||x| + |Omega[0]| sum|x|), and the rows whose weight IS the most frequent value are exact."""
+    dev = _gpu()
+    cb = np.array([5.0, 0.0, 0.125, -0.25], np.float32)
+    W = np.full((300, 1), 5.0, np.float32)
+    W[::7, 0] = 0.0
+    W[3::7, 0] = 0.125
+    W[5::11, 0] = -0.25
+    rng = np.random.default_rng(77)
+    for L in (1, 3, 8, 50):
+        X = rng.standard_normal((1, L)).astype(np.float32)
+        want = W.astype(np.float64) @ X.astype(np.float64)
+        bound = TOL * (np.abs(W).astype(np.float64) @ np.abs(X).astype(np.float64) + 5.0 * np.abs(X).astype(np.float64).sum(axis=0))
+        for fmt in ("cer", "cser"):
+            Y = run_matmul(fmt, W, cb, X).astype(np.float64)
+            assert np.isfinite(Y).all()
+            assert (np.abs(Y - want) <= bound).all(), f"{fmt} L={L}"
+            dom = W[:, 0] == 5.0
+            assert (np.abs(Y[dom] - want[dom]) <= TOL * np.abs(want[dom])).all(), f"{fmt} L={L}: dominant rows"
