@@ -436,7 +436,25 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
     }
     if (kXinLds || omega_in_lds) __syncthreads();
 
-    const float t_off = (v.omega0 != 0.f) ? v.omega0 * T[0] : 0.f;
+    // Appendix A-A1: Omega[0] . sum_i X[i].  With X staged in LDS the workgroup sums it there (short per-thread
+    // chains, then a tree); otherwise the launcher has computed it into T.
+    float t_off = 0.f;
+    if (v.omega0 != 0.f) {  // uniform over the grid
+        float tsum;
+        if (kXinLds) {
+            __shared__ float s_part[16];
+            float part = 0.f;
+            for (uint32_t i = threadIdx.x; i < v.n; i += blockDim.x) part += xs[i];
+            part = wave_sum(part);
+            if (lane == 0) s_part[wave] = part;
+            __syncthreads();
+            tsum = 0.f;
+            for (uint32_t w = 0; w < nwaves; ++w) tsum += s_part[w];
+        } else {
+            tsum = T[0];
+        }
+        t_off = v.omega0 * tsum;
+    }
 
     // The first batch of the first row runs from the prefetched indices when its list is ready
     // (the common case); everything else -- later batches, rows with many groups, later rows --
@@ -1144,30 +1162,42 @@ int env_int(const char* name, int fallback) {
     return (s && *s) ? std::atoi(s) : fallback;
 }
 
+// LDS the batch-1 kernel may claim dynamically: the device's limit less its few static words.
+size_t gemv_lds_budget() { return device_info().lds_per_block - 256; }
+
+// Whether the batch-1 kernel stages X in LDS for this matrix: whenever it fits beside Omega and the group lists of
+// 4 waves (with at least 64 entries each).
+bool gemv_stages_x(const KView& k, uint32_t max_row_groups) {
+    const size_t x_bytes = (((size_t)k.n + 3) & ~(size_t)3) * sizeof(float);
+    const size_t om_bytes = k.K <= 4096 ? (((size_t)k.K + 3) & ~(size_t)3) * sizeof(float) : 0;
+    const uint32_t gcap = std::max<uint32_t>(1u, std::min<uint32_t>(max_row_groups, 1022u));
+    return env_int("CER_GEMV_X_GLOBAL", 0) == 0 &&
+           x_bytes + om_bytes + (size_t)4 * (std::min<uint32_t>(gcap, 64u) + 2) * 8 <= gemv_lds_budget();
+}
+
 template <typename IdxT>
 hipError_t launch_gemv(const KView& k, uint32_t max_row_groups, const float* X, float* Y, const float* T,
                        hipStream_t stream) {
     const DeviceInfo& di = device_info();
+    const size_t budget = gemv_lds_budget();
     const size_t x_bytes = (((size_t)k.n + 3) & ~(size_t)3) * sizeof(float);
     const bool omega_in_lds = k.K <= 4096;
     const size_t om_bytes = omega_in_lds ? (((size_t)k.K + 3) & ~(size_t)3) * sizeof(float) : 0;
     // per-wave list of non-empty groups: as long as the longest row needs, at most 1022 entries
     uint32_t gcap = std::max<uint32_t>(1u, std::min<uint32_t>(max_row_groups, 1022u));
     auto list_bytes = [&](int waves) { return (size_t)waves * (gcap + 2) * 8; };
-    // X is staged in LDS whenever it fits beside Omega and the lists of 4 waves (with at least 64 entries)
-    bool x_in_lds = env_int("CER_GEMV_X_GLOBAL", 0) == 0 &&
-                    x_bytes + om_bytes + (size_t)4 * (std::min<uint32_t>(gcap, 64u) + 2) * 8 <= di.lds_per_block;
+    const bool x_in_lds = gemv_stages_x(k, max_row_groups);
     const size_t fixed = (x_in_lds ? x_bytes : 0) + om_bytes;
     // a workgroup that stages a large X should own many rows: 16 waves; small X: 4 waves, more workgroups
     int waves = (x_in_lds && x_bytes > 40 * 1024) ? 16 : 4;
     waves = env_int("CER_GEMV_WAVES", waves);
     if (waves < 1 || waves > 16) return hipErrorInvalidValue;
-    while (fixed + list_bytes(waves) > di.lds_per_block && waves > 4) waves >>= 1;
-    while (fixed + list_bytes(waves) > di.lds_per_block && gcap > 64) gcap = std::max<uint32_t>(64u, gcap / 2);
+    while (fixed + list_bytes(waves) > budget && waves > 4) waves >>= 1;
+    while (fixed + list_bytes(waves) > budget && gcap > 64) gcap = std::max<uint32_t>(64u, gcap / 2);
     const size_t lds = fixed + list_bytes(waves);
-    if (lds > di.lds_per_block) return hipErrorInvalidValue;
+    if (lds > budget) return hipErrorInvalidValue;
     // resident workgroups per CU, limited by LDS and by 32 waves per CU
-    size_t per_cu = std::min<size_t>(di.lds_per_block / lds, (size_t)(32 / waves));
+    size_t per_cu = std::min<size_t>(di.lds_per_block / (lds + 256), (size_t)(32 / waves));
     per_cu = std::max<size_t>(1, std::min<size_t>(per_cu, 8));
     const uint64_t slots = (uint64_t)di.cus * per_cu;
     uint32_t iters = (uint32_t)((k.m + slots * waves - 1) / (slots * waves));
@@ -1194,7 +1224,7 @@ hipError_t launch_gemv(const KView& k, uint32_t max_row_groups, const float* X, 
         std::lock_guard<std::mutex> lock(mu);
         if (!granted[kslot][dev]) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)di.lds_per_block);
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)budget);
             if (e != hipSuccess) return e;
             granted[kslot][dev] = true;
         }
@@ -1516,7 +1546,8 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
     float* T = nullptr;
     float* scratch = nullptr;
     hipError_t e = hipSuccess;
-    if (d.omega0 != 0.f) {
+    const bool gemv_sums_x = L == 1 && gemv_stages_x(k, (uint32_t)d.max_row_groups);
+    if (d.omega0 != 0.f && !gemv_sums_x) {
         // T[l] = sum_i X[i,l] in a stream-ordered temporary: [T: L rounded to 64][partials: nslabs x L]
         const uint32_t CB = std::min<uint32_t>(256u, pow2_ceil(L));
         const uint32_t coltiles = (L + CB - 1) / CB;
