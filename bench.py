@@ -61,7 +61,7 @@ def kernel_name(fmt: str, L: int, path) -> str:
         return "csr_gemv_kernel" if L == 1 else "csr_gemm_kernel"
     return {0: "cer_gemv_kernel",
             1: "cer_gemm_kernel" if os.environ.get("CER_GEMM_EXPAND", "1") == "0" else "cer_gemm_expand_kernel",
-            2: "cer_xtile_kernel", 3: "decode_kernel + dense_gemm_mfma_kernel"}[path]
+            2: "cer_xtile_kernel", 3: "decode_kernel + dense_gemm_mfma_kernel", 4: "cer_gemv_expand_kernel"}[path]
 
 
 def algorithmic_bytes(dims: dict, bits: dict, L: int) -> int:

@@ -115,7 +115,12 @@ int cser_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t
 
 /*
  * cer_matmul_path -- which kernel cer_matmul / cser_matmul runs for this handle and batch:
- *   0  batch-1 kernel: X staged in LDS per workgroup, one wave per row
+ *   0  batch-1 kernel: X staged in LDS per workgroup, one wave per row, the paper's arithmetic (the
+ *      inputs of a group are summed, then multiplied once)
+ *   4  batch-1 kernel for rows of many short groups (fewer than 30 indices per non-empty group on
+ *      average, e.g. 8-bit codebooks): the group values are expanded per colI position into LDS
+ *      and every input is multiplied by its position's value; needs X to fit in LDS.
+ *      CER_GEMV_EXPAND=1 selects it whenever X fits, CER_GEMV_EXPAND=0 never
  *   1  batched kernel that gathers rows of X from L2, one wave per (row, tile of batch columns: 32
  *      when a row of X is a whole number of 128-byte lines, else 32, 64 or 128 by the cache lines
  *      the gathers touch; any width and 4-byte aligned X / Y are served by 16-byte gathers).  By

@@ -256,7 +256,8 @@ def cer_decode_device(h: Handle, W_out, stream=None) -> None:
 
 def cer_matmul_path(h: Handle, batch: int) -> int:
     """0 = batch-1 kernel, 1 = batched kernel gathering from L2, 2 = batched kernel with X resident in LDS,
-    3 = decode into a dense temporary + fp32 matrix-core product (large batches of not-so-sparse matrices)."""
+    3 = decode into a dense temporary + fp32 matrix-core product (large batches of not-so-sparse matrices),
+    4 = batch-1 kernel for rows of many short groups."""
     rc = lib().cer_matmul_path(h.ptr, batch)
     if rc < 0:
         _check(rc, "cer_matmul_path")

@@ -843,6 +843,132 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const flo
 }
 
 // ------------------------------------------------------------------------------------------------
+// batch = 1, rows made of many short groups
+// ------------------------------------------------------------------------------------------------
+//
+// With hundreds of values per row (8-bit codebooks) a group holds a handful of elements and the cursor of
+// the kernel above crosses several group ends in every window of 64 positions.  This kernel expands the group
+// structure instead, as the default batched kernel does: per chunk of kGemvExpChunk colI positions the value of
+// every position goes to an array in LDS (long groups written by the whole wave, short ones by one lane each) and
+// the stream is acc += X[colI[p]] . val[p], lane = position, X staged in LDS.  One wave per row; the index loads
+// of a chunk are issued before its expansion starts and run into the next row or the padding behind colI.
+
+constexpr uint32_t kGemvExpShort = 32;  // groups up to this length are written by one lane each, longer ones by the whole wave
+constexpr uint32_t kGemvExpChunk = 2048;  // positions per expansion: 32 index registers per lane, 8 KiB of values per wave
+
+template <typename IdxT, bool kCser>
+__global__ __launch_bounds__(1024) void cer_gemv_expand_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
+                                                               uint32_t rows_per_block, int omega_in_lds) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr uint32_t NW = kGemvExpChunk / kWave;  // windows per chunk
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = uniform(threadIdx.x >> 6);
+    const uint32_t nwaves = blockDim.x >> 6;
+
+    // LDS: [X: n floats, rounded to 4][Omega: K floats, optional][values: nwaves x (chunk + 64)]
+    float* xs = reinterpret_cast<float*>(smem);
+    const uint32_t x_floats = (v.n + 3u) & ~3u;
+    float* oms = xs + x_floats;
+    const uint32_t om_floats = omega_in_lds ? ((v.K + 3u) & ~3u) : 0u;
+    float* val = oms + om_floats + wave * (kGemvExpChunk + kWave);
+    const float* omega = omega_in_lds ? oms : v.omega;
+
+    if ((reinterpret_cast<uintptr_t>(X) & 15u) == 0) {
+        const float4* X4 = reinterpret_cast<const float4*>(X);
+        float4* xs4 = reinterpret_cast<float4*>(xs);
+        const uint32_t n4 = v.n >> 2;
+        for (uint32_t i = threadIdx.x; i < n4; i += blockDim.x) xs4[i] = X4[i];
+        for (uint32_t i = (n4 << 2) + threadIdx.x; i < v.n; i += blockDim.x) xs[i] = X[i];
+    } else {
+        for (uint32_t i = threadIdx.x; i < v.n; i += blockDim.x) xs[i] = X[i];
+    }
+    if (omega_in_lds)
+        for (uint32_t i = threadIdx.x; i < v.K; i += blockDim.x) oms[i] = v.omega[i];
+    __syncthreads();
+
+    // Appendix A-A1: Omega[0] . sum_i X[i], summed from the staged copy
+    float t_off = 0.f;
+    if (v.omega0 != 0.f) {  // uniform over the grid
+        __shared__ float s_part[16];
+        float part = 0.f;
+        for (uint32_t i = threadIdx.x; i < v.n; i += blockDim.x) part += xs[i];
+        part = wave_sum(part);
+        if (lane == 0) s_part[wave] = part;
+        __syncthreads();
+        float tsum = 0.f;
+        for (uint32_t w = 0; w < nwaves; ++w) tsum += s_part[w];
+        t_off = v.omega0 * tsum;
+    }
+
+    const IdxT* colI = static_cast<const IdxT*>(v.colI);
+    const bool cser = kCser;
+    const uint32_t row_begin = blockIdx.x * rows_per_block;
+    const uint32_t row_end = min(v.m, row_begin + rows_per_block);
+    for (uint32_t r = row_begin + wave; r < row_end; r += nwaves) {  // wave-uniform
+        const uint2 d0 = v.rowInfo[r], d1 = v.rowInfo[r + 1];
+        const uint32_t g0 = d0.x, rs = d0.y, g1 = d1.x, re = d1.y;
+        float acc = 0.f;
+        uint32_t gcur = g0;  // first raw group that may reach into the current chunk
+        // the pointers of the row's first 256 raw groups are requested together (tiles past the row's last group read
+        // the padding behind the pointer arrays and come back empty)
+        constexpr int kPre = 4;
+        PtrTile pre[kPre];
+#pragma unroll
+        for (int t = 0; t < kPre; ++t) pre[t] = load_ptr_tile(v, cser, g0, min(g0 + (uint32_t)t * kWave, g1), g1, lane);
+        for (uint32_t c0 = rs; c0 < re; c0 += kGemvExpChunk) {
+            const uint32_t c1 = min(re, c0 + kGemvExpChunk);
+            const uint32_t nwin = (c1 - c0 + kWave - 1u) / kWave;
+            uint32_t ix[NW];
+#pragma unroll
+            for (uint32_t w = 0; w < NW; ++w) ix[w] = (uint32_t)colI[c0 + w * kWave + lane];
+
+            // values of the positions [c0, c1), zeros up to the end of the last window
+            if (c1 - c0 + lane < nwin * kWave) val[c1 - c0 + lane] = 0.f;
+            // one tile of 64 raw groups starting at gt; false: the next group reaches beyond the chunk or the row is done
+            auto expand_tile = [&](const PtrTile& p, uint32_t gt) {
+                const float w = omega[p.rank < v.K ? p.rank : 0u] - v.omega0;
+                const uint32_t s = max(p.s, c0), e = min(p.e, c1);
+                const uint32_t len = e > s ? e - s : 0u;
+                uint64_t longs = __ballot(len > kGemvExpShort);
+                while (longs) {
+                    const int b = __builtin_ctzll(longs);
+                    longs &= longs - 1;
+                    const uint32_t s_b = __builtin_amdgcn_readlane(s, b), e_b = __builtin_amdgcn_readlane(e, b);
+                    const float w_b = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), b));
+                    for (uint32_t pos = s_b + lane; pos < e_b; pos += kWave) val[pos - c0] = w_b;
+                }
+                {   // short groups, one lane each: as many rounds as the longest of them needs (8, 16 or 32)
+                    const uint32_t mine = len <= kGemvExpShort ? len : 0u;
+                    const uint32_t rounds = __ballot(mine > 16u) ? 32u : (__ballot(mine > 8u) ? 16u : 8u);
+                    for (uint32_t k0 = 0; k0 < rounds; k0 += 8) {
+#pragma unroll
+                        for (uint32_t k = 0; k < 8; ++k)
+                            if (k0 + k < mine) val[s - c0 + k0 + k] = w;
+                    }
+                }
+                const uint32_t done = (uint32_t)__popcll(__ballot(gt + lane < g1 && p.e <= c1));
+                gcur = gt + done;
+                return done == (uint32_t)kWave && gcur < g1;
+            };
+            bool more = gcur < g1;
+            if (c0 == rs) {  // the first chunk starts at the row's first group: the prefetched tiles apply
+#pragma unroll
+                for (int t = 0; t < kPre; ++t)
+                    if (more) more = expand_tile(pre[t], g0 + (uint32_t)t * kWave);
+            }
+            while (more) more = expand_tile(load_ptr_tile(v, cser, g0, gcur, g1, lane), gcur);
+            wave_lds_sync();
+#pragma unroll
+            for (uint32_t w = 0; w < NW; ++w)
+                if (w < nwin) acc = fmaf(xs[ix[w]], val[w * kWave + lane], acc);
+            wave_lds_sync();  // the next chunk overwrites the values
+        }
+        const float y = wave_sum(acc);
+        if (lane == 0) Y[r] = y + t_off;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // batch > 1 with the input tile resident in LDS (reuse of the input, Section V-C)
 // ------------------------------------------------------------------------------------------------
 //
@@ -1234,6 +1360,71 @@ hipError_t launch_gemv(const KView& k, uint32_t max_row_groups, const float* X, 
     return hipGetLastError();
 }
 
+// Launch shape of the batch-1 expansion kernel; waves == 0: X, Omega and the value arrays of four waves do not fit in LDS.
+struct GemvExpandPlan {
+    int waves = 0;
+    size_t lds = 0;
+    bool omega_in_lds = false;
+};
+
+GemvExpandPlan plan_gemv_expand(const KView& k) {
+    GemvExpandPlan p;
+    const size_t budget = gemv_lds_budget();
+    const size_t x_bytes = (((size_t)k.n + 3) & ~(size_t)3) * sizeof(float);
+    p.omega_in_lds = k.K <= 4096;
+    const size_t om_bytes = p.omega_in_lds ? (((size_t)k.K + 3) & ~(size_t)3) * sizeof(float) : 0;
+    const size_t per_wave = (kGemvExpChunk + kWave) * sizeof(float);
+    // a workgroup that stages a large X should own many rows; a small X leaves room for more, smaller workgroups
+    int waves = x_bytes > 40 * 1024 ? 16 : (k.m >= 8192 ? 16 : (k.m >= 4096 ? 8 : 4));
+    while (waves > 4 && x_bytes + om_bytes + waves * per_wave > budget) waves >>= 1;
+    if (x_bytes + om_bytes + waves * per_wave > budget) return p;
+    p.waves = waves;
+    p.lds = x_bytes + om_bytes + waves * per_wave;
+    return p;
+}
+
+// Rows of short groups go to the expansion kernel.  Measured on 2048 x 2048 matrices, cursor kernel / expansion
+// kernel, by indices per non-empty group: 4 (256 values, 50 % zeros) 24.2 / 7.8 us; 1.5 (256 values, 90 %) 16.4 /
+// 6.3 us; 16 (64 values, 50 %) 9.4 / 6.6 us; 3 (64 values, 90 %) 8.5 / 5.4 us; 41 (16 values, 70 %) 6.7 / 7.5 us;
+// 68 (16 values, 50 %) 6.7 / 8.1 us; AlexNet-fc6 shape (45) 10.2 / 10.5 us; VGG-fc6 shape (90) 8.5 / 16.4 us.
+bool gemv_expand_pays(const DeviceView& d) {
+    const double per_group = (double)d.nnz / (double)std::max<int64_t>(d.nonempty_groups, 1);
+    return per_group < 30.0;
+}
+
+// The batch-1 expansion kernel's plan for this matrix if cer_matmul would use it (waves == 0 otherwise).
+// CER_GEMV_EXPAND: 1 = whenever X fits in LDS, 0 = never, unset = for rows of short groups.
+GemvExpandPlan gemv_expand_choice(const DeviceView& d, const KView& k) {
+    const int mode = env_int("CER_GEMV_EXPAND", -1);
+    if (mode == 1 || (mode != 0 && gemv_expand_pays(d))) return plan_gemv_expand(k);
+    return GemvExpandPlan{};
+}
+
+template <typename IdxT>
+hipError_t launch_gemv_expand(const KView& k, const GemvExpandPlan& p, const float* X, float* Y, hipStream_t stream) {
+    using Kern = void (*)(KView, const float*, float*, uint32_t, int);
+    Kern kern = k.cser ? cer_gemv_expand_kernel<IdxT, true> : cer_gemv_expand_kernel<IdxT, false>;
+    if (p.lds > 48 * 1024) {
+        static std::mutex mu;
+        static bool granted[2][16] = {};
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        dev = (dev >= 0 && dev < 16) ? dev : 0;
+        std::lock_guard<std::mutex> lock(mu);
+        if (!granted[k.cser ? 1 : 0][dev]) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               (int)gemv_lds_budget());
+            if (e != hipSuccess) return e;
+            granted[k.cser ? 1 : 0][dev] = true;
+        }
+    }
+    const uint32_t rows_per_block = (uint32_t)p.waves;
+    const uint32_t blocks = (k.m + rows_per_block - 1) / rows_per_block;
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(p.waves * kWave), p.lds, stream, k, X, Y, rows_per_block,
+                       p.omega_in_lds ? 1 : 0);
+    return hipGetLastError();
+}
+
 // The kernel that expands the group values per position is the default: measured on MI355X it beats the cursor
 // kernel on every workload (1.05 - 1.2 x on the layer shapes, up to 2 x on rows of many short groups).
 // CER_GEMM_EXPAND=0 selects the cursor kernel.
@@ -1527,7 +1718,7 @@ bool use_densified(const DeviceView& d, int64_t L) {
 }  // namespace
 
 int matmul_path(const DeviceView& d, int64_t L) {
-    if (L <= 1) return 0;
+    if (L <= 1) return gemv_expand_choice(d, make_kview(d)).waves > 0 ? 4 : 0;
     if (use_densified(d, L)) return 3;
     const int mode = env_int("CER_XTILE", -1);
     if (mode == 0 || L > 0x7FFFFFFFll) return 1;
@@ -1546,7 +1737,8 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
     float* T = nullptr;
     float* scratch = nullptr;
     hipError_t e = hipSuccess;
-    const bool gemv_sums_x = L == 1 && gemv_stages_x(k, (uint32_t)d.max_row_groups);
+    const GemvExpandPlan gx = L == 1 ? gemv_expand_choice(d, k) : GemvExpandPlan{};
+    const bool gemv_sums_x = L == 1 && (gx.waves > 0 || gemv_stages_x(k, (uint32_t)d.max_row_groups));
     if (d.omega0 != 0.f && !gemv_sums_x) {
         // T[l] = sum_i X[i,l] in a stream-ordered temporary: [T: L rounded to 64][partials: nslabs x L]
         const uint32_t CB = std::min<uint32_t>(256u, pow2_ceil(L));
@@ -1564,7 +1756,13 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
             return (int)e;
         }
     }
-    if (L == 1) {
+    if (L == 1 && gx.waves > 0) {
+        switch (d.colI_bits) {
+            case 8: e = launch_gemv_expand<uint8_t>(k, gx, X, Y, stream); break;
+            case 16: e = launch_gemv_expand<uint16_t>(k, gx, X, Y, stream); break;
+            default: e = launch_gemv_expand<uint32_t>(k, gx, X, Y, stream); break;
+        }
+    } else if (L == 1) {
         switch (d.colI_bits) {
             case 8: e = launch_gemv<uint8_t>(k, (uint32_t)d.max_row_groups, X, Y, T, stream); break;
             case 16: e = launch_gemv<uint16_t>(k, (uint32_t)d.max_row_groups, X, Y, T, stream); break;
