@@ -11,7 +11,7 @@ the encoded matrix, R chosen so that the copies exceed twice the 256 MB last-lev
 step then streams its arrays from HBM ("cold").  --warm reuses one copy (cache-resident numbers).
 
 Workloads: vgg_fc6_L<L> (default vgg_fc6_L1), alexnet_fc6_L<L>, conv3x3_L<L>, conv3x3_dom_L<L>, c1,
-sweep_K<K>_p<p0>[_L<L>].  --front-end encode|quantize|decode times the device-side conversion calls instead.
+sweep_K<K>_p<p0>[_L<L>], quant<bits>_fc6_L<L> (dense Laplace weights, 4096 x 9216, through the device quantizer).  --front-end encode|quantize|decode times the device-side conversion calls instead.
 
 Prints ONE JSON line on stdout; --report writes a table over several workloads to a file.
 """
@@ -47,6 +47,20 @@ def make_workload(name: str):
     m = re.fullmatch(r"conv3x3(_dom)?_L(\d+)", name)
     if m:
         return wl.conv3x3(L=int(m.group(2)), nonzero_dominant=bool(m.group(1)))
+    m = re.fullmatch(r"quant(\d)_fc6_L(\d+)", name)
+    if m:
+        # a dense Laplace layer (AlexNet-fc6 size) through the library's own uniform quantizer: the regime of the
+        # paper's dense, low-entropy networks (p0 about 0.3, 3 - 4 bits of entropy)
+        import torch
+        from paper_1805_10692_amd import binding as B
+        bits, L = int(m.group(1)), int(m.group(2))
+        W0 = wl.dense_weights(4096, 9216, seed=9)
+        Wd = torch.from_numpy(W0).to("cuda:0")
+        Wq = torch.empty_like(Wd)
+        cb = B.cer_quantize_uniform(Wd, W0.size, bits, None, Wq)
+        torch.cuda.synchronize()
+        X = wl.sample_X(np.random.Generator(np.random.PCG64(10)), 9216, L)
+        return wl.Workload(name, Wq.cpu().numpy(), np.asarray(cb, np.float32), X, np.zeros(len(cb)), 9)
     if name == "c1":
         return wl.config1()
     m = re.fullmatch(r"sweep_K(\d+)_p([0-9.]+)(?:_L(\d+))?", name)

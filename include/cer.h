@@ -134,9 +134,10 @@ int cser_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t
  *      for a batch of more than one tile a stream-ordered temporary of about the size of X is
  *      used (a tile-major copy of X).
  *   3  decode + dense: the matrix is decoded into a stream-ordered temporary of 4.m.n bytes and
- *      multiplied on the fp32 matrix cores.  Chosen for batch >= 128 when the estimated time of
- *      the gathers (4.batch bytes per indexed element through the L1/L2 path) exceeds that of the
- *      dense contraction, i.e. for matrices with more than about one indexed element in five;
+ *      multiplied on the fp32 matrix cores.  Chosen when the estimated time of the gathers
+ *      (max(4.batch, 128) bytes per indexed element through the L1/L2 path) exceeds that of the
+ *      decode and the dense contraction: wide batches of matrices with more than about one
+ *      indexed element in five, any batch > 1 of matrices with most elements indexed;
  *      CER_DENSIFY=1 forces it for every batch > 1, CER_DENSIFY=0 switches it off.  The
  *      arithmetic is then that of a dense fp32 product (same error bound), not Algorithm 3 / 4.
  * On MI355X kernel 2 beats kernel 1 for narrow batches of large matrices (kernel 1 moves a whole

@@ -1687,14 +1687,19 @@ hipError_t launch_colsum(const float* X, uint32_t n, uint32_t L, float* part, ui
 // 391 / 201 us, batch 784 165 / 75 us, batch 256 44 / 45 us; AlexNet-fc6 shape (85 %) batch 2048 1917 / 1466 us,
 // batch 512 419 / 421 us; VGG-fc6 shape (95 %) batch 1024 1187 / 2017 us; 2048 x 2048, batch 1024: 70 % zeros
 // 187 / 119 us, 80 % 139 / 119 us, 90 % 89 / 118 us.
+// Narrow batches of a dense-ish matrix take the same route: a gather moves a whole 128-byte line however narrow the
+// batch, so a 4096 x 9216 layer quantized to 7 bits (71 % of the elements indexed) costs 171 us at batch 32 by
+// gathers, 70 us decoded (30 us) and multiplied by the dense kernel (40 us, itself bound by reading the matrix).
 bool densify_pays(const DeviceView& d, uint32_t L) {
-    if (L < 128 || d.m < 128 || d.n < 256) return false;
+    if (L < 2 || d.m < 128 || d.n < 256) return false;
     const double mn = (double)d.m * (double)d.n;
     if (mn * 4.0 > (double)(1ull << 30)) return false;
     const double flops = 2.0 * mn * L;
-    const double t_gather = (double)d.nnz * 4.0 * L / 24e12;
+    const double t_gather = (double)d.nnz * std::max(4.0 * L, 128.0) / 24e12;
     const double rate = flops < 1.5e10 ? 90e12 : (flops < 1e11 ? 105e12 : 120e12);
-    const double t_dense = (flops < 5e9 ? 20e-6 : 12e-6) + flops / rate + 4.0 * mn / 4.5e12 + 3e-6;
+    const double t_write = 4.0 * mn / 4.5e12;  // the decoded matrix goes to memory once and is read back at least once
+    const double t_decode = t_write + (double)d.nnz * 1.5e-12 + 3e-6;  // measured 30 us (5.7 M indices) ... 88 us (28.7 M)
+    const double t_dense = (flops < 5e9 ? 20e-6 : 12e-6) + std::max(flops / rate, t_write) + t_decode;
     return t_gather > 1.1 * t_dense;
 }
 
@@ -1708,22 +1713,28 @@ hipError_t launch_densified(const DeviceView& d, const float* X, float* Y, uint3
     return e == hipSuccess ? f : e;
 }
 
-// CER_DENSIFY: 1 = decode + dense product for every batch > 1, 0 = never, unset = by the estimate above
-bool use_densified(const DeviceView& d, int64_t L) {
-    if (L <= 1 || L > 0x7FFFFFFFll || d.m <= 0 || d.n <= 0) return false;
-    const int mode = env_int("CER_DENSIFY", -1);
-    return mode == 1 || (mode != 0 && densify_pays(d, (uint32_t)L));
+// Which kernel serves a batch of L > 1 columns (cer_matmul_path's numbering: 1, 2 or 3).
+//   CER_DENSIFY: 1 = decode + dense product for every batch > 1, 0 = never, unset = by the estimate above
+//   CER_XTILE:   1 = input tile in LDS whenever applicable, 0 = never, unset = by estimate (narrow batches)
+int choose_batched_path(const DeviceView& d, uint32_t L, XtilePlan* plan_out) {
+    const int dense_mode = env_int("CER_DENSIFY", -1), lds_mode = env_int("CER_XTILE", -1);
+    const bool has_elements = d.m > 0 && d.n > 0;
+    if (dense_mode == 1 && has_elements) return 3;
+    const XtilePlan plan = lds_mode == 0 ? XtilePlan{} : plan_xtile(d, L);
+    if (plan.valid && (lds_mode == 1 || xtile_pays(plan, d, L))) {
+        if (plan_out) *plan_out = plan;
+        return 2;
+    }
+    if (dense_mode != 0 && has_elements && densify_pays(d, L)) return 3;
+    return 1;
 }
 
 }  // namespace
 
 int matmul_path(const DeviceView& d, int64_t L) {
     if (L <= 1) return gemv_expand_choice(d, make_kview(d)).waves > 0 ? 4 : 0;
-    if (use_densified(d, L)) return 3;
-    const int mode = env_int("CER_XTILE", -1);
-    if (mode == 0 || L > 0x7FFFFFFFll) return 1;
-    const XtilePlan plan = plan_xtile(d, (uint32_t)L);
-    return (plan.valid && (mode == 1 || xtile_pays(plan, d, (uint32_t)L))) ? 2 : 1;
+    if (L > 0x7FFFFFFFll) return 1;
+    return choose_batched_path(d, (uint32_t)L, nullptr);
 }
 
 int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, void* stream_v) {
@@ -1731,7 +1742,9 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
     if (d.m == 0) return (int)hipSuccess;
     if (L64 > 0x7FFFFFFFll || d.m > 0x7FFFFFFFll) return (int)hipErrorInvalidValue;
     const uint32_t L = (uint32_t)L64;
-    if (use_densified(d, L64)) return (int)launch_densified(d, X, Y, L, stream);
+    XtilePlan plan;
+    const int batched_path = L > 1 ? choose_batched_path(d, L, &plan) : 0;
+    if (batched_path == 3) return (int)launch_densified(d, X, Y, L, stream);
     const KView k = make_kview(d);
 
     float* T = nullptr;
@@ -1769,10 +1782,7 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
             default: e = launch_gemv<uint32_t>(k, (uint32_t)d.max_row_groups, X, Y, T, stream); break;
         }
     } else {
-        // CER_XTILE: 1 = input tile in LDS whenever applicable, 0 = never, unset = by estimate
-        const int mode = env_int("CER_XTILE", -1);
-        const XtilePlan plan = mode == 0 ? XtilePlan{} : plan_xtile(d, L);
-        if (plan.valid && (mode == 1 || xtile_pays(plan, d, L))) {
+        if (batched_path == 2) {
             switch (d.colI_bits) {
                 case 8: e = launch_xtile<uint8_t>(k, plan, X, Y, T, L, stream, 0); break;
                 case 16: e = launch_xtile<uint16_t>(k, plan, X, Y, T, L, stream, 1); break;

@@ -648,12 +648,12 @@ __global__ __launch_bounds__(256) void emit_kernel(const uint8_t* __restrict__ c
 // row's pointers (up to kDecThreads groups at a time in LDS; repeated pointers, CER's empty groups,
 // are skipped by the search).  A row of at most kDecThreads groups and kDecThreads.kDecPer positions
 // keeps its columns and values in registers for all its segments; a larger row reloads them per
-// segment.  Index loads may run past the row's last position into the next row or the readable
-// padding behind colI.
+// segment.
 // ------------------------------------------------------------------------------------------------
-constexpr uint32_t kDecThreads = 256, kDecPer = 8, kDecSeg = 4096;
+constexpr uint32_t kDecThreads = 256, kDecSeg = 4096;
 
-template <typename ColT>
+// kDecPer = positions a thread keeps in registers: 8 for sparse rows, 32 where rows hold thousands of indices
+template <typename ColT, uint32_t kDecPer>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(
     const ColT* __restrict__ colI, const uint32_t* __restrict__ omegaPtr, const uint32_t* __restrict__ rowPtr,
     const uint8_t* __restrict__ omegaI, int oi_bits, const float* __restrict__ omega, int cser, int64_t n,
@@ -688,17 +688,21 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(
     uint32_t ok = 0;
     auto load_positions = [&](uint32_t pb, uint32_t pe, uint32_t cnt) {
         ok = 0;
+        const uint32_t last = pe > pb ? pe - 1u : pb;  // loads behind the last position are redirected to it
 #pragma unroll
-        for (uint32_t k = 0; k < P; ++k) col[k] = (uint32_t)colI[pb + tid + k * T];
+        for (uint32_t k = 0; k < P; ++k) col[k] = (uint32_t)colI[min(pb + tid + k * T, last)];
+        uint32_t lo = 0;  // a thread's positions grow with k, and so do their groups: the search resumes where it was
 #pragma unroll
         for (uint32_t k = 0; k < P; ++k) {
             const uint32_t p = pb + tid + k * T;
             val[k] = 0.f;
             if (p < pe) {
-                uint32_t lo = 0, hi = cnt;  // s_ptr[lo] <= p < s_ptr[hi]
-                while (hi - lo > 1u) {
-                    const uint32_t mid = (lo + hi) >> 1;
-                    if (s_ptr[mid] <= p) lo = mid; else hi = mid;
+                if (s_ptr[lo + 1u] <= p) {  // not the same group as the previous position
+                    uint32_t hi = cnt;      // s_ptr[lo] <= p < s_ptr[hi]
+                    while (hi - lo > 1u) {
+                        const uint32_t mid = (lo + hi) >> 1;
+                        if (s_ptr[mid] <= p) lo = mid; else hi = mid;
+                    }
                 }
                 val[k] = s_val[lo];
                 ok |= 1u << k;
@@ -864,9 +868,16 @@ int launch_decode(const DeviceView& v, float* W, hipStream_t s) {
     if (v.m > 0x7FFFFFFFll || nseg > 0x7FFFFFFFll) return CER_E_INVALID;
     // one workgroup per row walks all its segments, unless that gives too few workgroups to fill the chip
     const int64_t split = std::min<int64_t>(std::min<int64_t>(nseg, 65535), std::max<int64_t>(1, 4096 / v.m));
-    decode_kernel<ColT><<<dim3((unsigned)v.m, (unsigned)split), kDecThreads, (size_t)seg * sizeof(float), s>>>(
-        static_cast<const ColT*>(v.colI), v.omegaPtr, v.rowPtr, static_cast<const uint8_t*>(v.omegaI), v.omegaI_bits,
-        v.omega, v.cser, v.n, seg, (uint32_t)nseg, W);
+    const dim3 grid((unsigned)v.m, (unsigned)split);
+    const size_t lds = (size_t)seg * sizeof(float);
+    if (v.nnz > v.m * 1500)  // rows of thousands of indices: keep up to 8192 of them in registers over the row's segments
+        decode_kernel<ColT, 32><<<grid, kDecThreads, lds, s>>>(
+            static_cast<const ColT*>(v.colI), v.omegaPtr, v.rowPtr, static_cast<const uint8_t*>(v.omegaI), v.omegaI_bits,
+            v.omega, v.cser, v.n, seg, (uint32_t)nseg, W);
+    else
+        decode_kernel<ColT, 8><<<grid, kDecThreads, lds, s>>>(
+            static_cast<const ColT*>(v.colI), v.omegaPtr, v.rowPtr, static_cast<const uint8_t*>(v.omegaI), v.omegaI_bits,
+            v.omega, v.cser, v.n, seg, (uint32_t)nseg, W);
     HIP_TRY(hipGetLastError());
     return CER_OK;
 }
