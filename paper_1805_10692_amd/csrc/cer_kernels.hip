@@ -34,6 +34,7 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <cmath>
 #include <cstdlib>
 #include <mutex>
 #include <numeric>
@@ -854,9 +855,10 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const flo
 // of a chunk are issued before its expansion starts and run into the next row or the padding behind colI.
 
 constexpr uint32_t kGemvExpShort = 32;  // groups up to this length are written by one lane each, longer ones by the whole wave
-constexpr uint32_t kGemvExpChunk = 2048;  // positions per expansion: 32 index registers per lane, 8 KiB of values per wave
 
-template <typename IdxT, bool kCser>
+// kGemvExpChunk = positions per expansion: 2048 (32 index registers per lane, 8 KiB of values per wave), or 512 for
+// matrices of short rows, whose waves then leave room in LDS for several workgroups per compute unit
+template <typename IdxT, bool kCser, uint32_t kGemvExpChunk>
 __global__ __launch_bounds__(1024) void cer_gemv_expand_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
                                                                uint32_t rows_per_block, int omega_in_lds) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -1363,17 +1365,19 @@ hipError_t launch_gemv(const KView& k, uint32_t max_row_groups, const float* X, 
 // Launch shape of the batch-1 expansion kernel; waves == 0: X, Omega and the value arrays of four waves do not fit in LDS.
 struct GemvExpandPlan {
     int waves = 0;
+    uint32_t chunk = 2048;
     size_t lds = 0;
     bool omega_in_lds = false;
 };
 
-GemvExpandPlan plan_gemv_expand(const KView& k) {
+GemvExpandPlan plan_gemv_expand(const DeviceView& d, const KView& k) {
     GemvExpandPlan p;
     const size_t budget = gemv_lds_budget();
     const size_t x_bytes = (((size_t)k.n + 3) & ~(size_t)3) * sizeof(float);
     p.omega_in_lds = k.K <= 4096;
     const size_t om_bytes = p.omega_in_lds ? (((size_t)k.K + 3) & ~(size_t)3) * sizeof(float) : 0;
-    const size_t per_wave = (kGemvExpChunk + kWave) * sizeof(float);
+    p.chunk = d.nnz <= d.m * 384 ? 512u : 2048u;  // by the average row
+    const size_t per_wave = (p.chunk + kWave) * sizeof(float);
     // a workgroup that stages a large X should own many rows; a small X leaves room for more, smaller workgroups
     int waves = x_bytes > 40 * 1024 ? 16 : (k.m >= 8192 ? 16 : (k.m >= 4096 ? 8 : 4));
     while (waves > 4 && x_bytes + om_bytes + waves * per_wave > budget) waves >>= 1;
@@ -1387,35 +1391,40 @@ GemvExpandPlan plan_gemv_expand(const KView& k) {
 // kernel, by indices per non-empty group: 4 (256 values, 50 % zeros) 24.2 / 7.8 us; 1.5 (256 values, 90 %) 16.4 /
 // 6.3 us; 16 (64 values, 50 %) 9.4 / 6.6 us; 3 (64 values, 90 %) 8.5 / 5.4 us; 41 (16 values, 70 %) 6.7 / 7.5 us;
 // 68 (16 values, 50 %) 6.7 / 8.1 us; AlexNet-fc6 shape (45) 10.2 / 10.5 us; VGG-fc6 shape (90) 8.5 / 16.4 us.
+// Short rows (a few hundred indices at most) go there as well: the cursor kernel requests 24 windows of indices per
+// row whatever its length (16384 x 512 matrices: 11 - 12 us against 7 - 8 us).
 bool gemv_expand_pays(const DeviceView& d) {
     const double per_group = (double)d.nnz / (double)std::max<int64_t>(d.nonempty_groups, 1);
-    return per_group < 30.0;
+    return per_group < 30.0 || d.nnz <= d.m * 384;
 }
 
 // The batch-1 expansion kernel's plan for this matrix if cer_matmul would use it (waves == 0 otherwise).
 // CER_GEMV_EXPAND: 1 = whenever X fits in LDS, 0 = never, unset = for rows of short groups.
 GemvExpandPlan gemv_expand_choice(const DeviceView& d, const KView& k) {
     const int mode = env_int("CER_GEMV_EXPAND", -1);
-    if (mode == 1 || (mode != 0 && gemv_expand_pays(d))) return plan_gemv_expand(k);
+    if (mode == 1 || (mode != 0 && gemv_expand_pays(d))) return plan_gemv_expand(d, k);
     return GemvExpandPlan{};
 }
 
 template <typename IdxT>
 hipError_t launch_gemv_expand(const KView& k, const GemvExpandPlan& p, const float* X, float* Y, hipStream_t stream) {
     using Kern = void (*)(KView, const float*, float*, uint32_t, int);
-    Kern kern = k.cser ? cer_gemv_expand_kernel<IdxT, true> : cer_gemv_expand_kernel<IdxT, false>;
+    const bool small = p.chunk == 512;
+    Kern kern = k.cser ? (small ? cer_gemv_expand_kernel<IdxT, true, 512> : cer_gemv_expand_kernel<IdxT, true, 2048>)
+                       : (small ? cer_gemv_expand_kernel<IdxT, false, 512> : cer_gemv_expand_kernel<IdxT, false, 2048>);
     if (p.lds > 48 * 1024) {
         static std::mutex mu;
-        static bool granted[2][16] = {};
+        static bool granted[4][16] = {};
+        const int slot = (k.cser ? 1 : 0) + (small ? 2 : 0);
         int dev = 0;
         (void)hipGetDevice(&dev);
         dev = (dev >= 0 && dev < 16) ? dev : 0;
         std::lock_guard<std::mutex> lock(mu);
-        if (!granted[k.cser ? 1 : 0][dev]) {
+        if (!granted[slot][dev]) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                                (int)gemv_lds_budget());
             if (e != hipSuccess) return e;
-            granted[k.cser ? 1 : 0][dev] = true;
+            granted[slot][dev] = true;
         }
     }
     const uint32_t rows_per_block = (uint32_t)p.waves;
@@ -1695,7 +1704,11 @@ bool densify_pays(const DeviceView& d, uint32_t L) {
     const double mn = (double)d.m * (double)d.n;
     if (mn * 4.0 > (double)(1ull << 30)) return false;
     const double flops = 2.0 * mn * L;
-    const double t_gather = (double)d.nnz * std::max(4.0 * L, 128.0) / 24e12;
+    // every (row, tile) is a wave whose start-up chain (descriptor -> pointers -> indices -> first gathers) takes about
+    // 4 us, 4096 of them in flight: what bounds matrices of many short rows (16384 x 512: batch 128 64 - 84 us,
+    // batch 512 160 - 440 us by gathers; 44 - 49 us and 94 - 103 us decoded and multiplied)
+    const double tiles = std::ceil((double)L / 32.0);
+    const double t_gather = std::max((double)d.nnz * std::max(4.0 * L, 128.0) / 24e12, (double)d.m * tiles * 4e-6 / 4096.0);
     const double rate = flops < 1.5e10 ? 90e12 : (flops < 1e11 ? 105e12 : 120e12);
     const double t_write = 4.0 * mn / 4.5e12;  // the decoded matrix goes to memory once and is read back at least once
     const double t_decode = t_write + (double)d.nnz * 1.5e-12 + 3e-6;  // measured 30 us (5.7 M indices) ... 88 us (28.7 M)

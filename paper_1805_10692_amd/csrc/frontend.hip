@@ -650,10 +650,12 @@ __global__ __launch_bounds__(256) void emit_kernel(const uint8_t* __restrict__ c
 // keeps its columns and values in registers for all its segments; a larger row reloads them per
 // segment.
 // ------------------------------------------------------------------------------------------------
-constexpr uint32_t kDecThreads = 256, kDecSeg = 4096;
+constexpr uint32_t kDecSeg = 4096;
 
-// kDecPer = positions a thread keeps in registers: 8 for sparse rows, 32 where rows hold thousands of indices
-template <typename ColT, uint32_t kDecPer>
+// kDecThreads = workgroup size: 256, or 64 for matrices of short rows (a row is then little work, and four times as
+// many workgroups are in flight).  kDecPer = positions a thread keeps in registers: 8 for sparse rows, 32 where rows
+// hold thousands of indices.
+template <typename ColT, uint32_t kDecThreads, uint32_t kDecPer>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(
     const ColT* __restrict__ colI, const uint32_t* __restrict__ omegaPtr, const uint32_t* __restrict__ rowPtr,
     const uint8_t* __restrict__ omegaI, int oi_bits, const float* __restrict__ omega, int cser, int64_t n,
@@ -871,11 +873,15 @@ int launch_decode(const DeviceView& v, float* W, hipStream_t s) {
     const dim3 grid((unsigned)v.m, (unsigned)split);
     const size_t lds = (size_t)seg * sizeof(float);
     if (v.nnz > v.m * 1500)  // rows of thousands of indices: keep up to 8192 of them in registers over the row's segments
-        decode_kernel<ColT, 32><<<grid, kDecThreads, lds, s>>>(
+        decode_kernel<ColT, 256, 32><<<grid, 256, lds, s>>>(
+            static_cast<const ColT*>(v.colI), v.omegaPtr, v.rowPtr, static_cast<const uint8_t*>(v.omegaI), v.omegaI_bits,
+            v.omega, v.cser, v.n, seg, (uint32_t)nseg, W);
+    else if (v.n <= 1024)  // short rows: one wave per row
+        decode_kernel<ColT, 64, 8><<<grid, 64, lds, s>>>(
             static_cast<const ColT*>(v.colI), v.omegaPtr, v.rowPtr, static_cast<const uint8_t*>(v.omegaI), v.omegaI_bits,
             v.omega, v.cser, v.n, seg, (uint32_t)nseg, W);
     else
-        decode_kernel<ColT, 8><<<grid, kDecThreads, lds, s>>>(
+        decode_kernel<ColT, 256, 8><<<grid, 256, lds, s>>>(
             static_cast<const ColT*>(v.colI), v.omegaPtr, v.rowPtr, static_cast<const uint8_t*>(v.omegaI), v.omegaI_bits,
             v.omega, v.cser, v.n, seg, (uint32_t)nseg, W);
     HIP_TRY(hipGetLastError());

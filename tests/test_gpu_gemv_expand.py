@@ -73,3 +73,21 @@ def test_automatic_choice_keeps_the_layer_shapes_on_the_cursor_kernel():
         h = B.cer_encode(w.W, w.codebook)
         assert B.cer_matmul_path(h, 1) == 0
         B.cer_free(h)
+
+
+def test_short_row_variant_with_a_few_long_rows(forced):
+    """The variant for matrices of short rows (chosen by the average row) must still walk a long row chunk by
+    chunk: most rows hold about 90 indices, three hold 1300 - 2900, one group straddles a chunk boundary."""
+    rng = np.random.default_rng(61)
+    cb = np.array([0.0, 0.5, -1.0, 2.0, 0.25, -0.125], np.float32)
+    W = cb[rng.choice(6, size=(60, 3000), p=[0.97, 0.01, 0.008, 0.006, 0.004, 0.002])].astype(np.float32)
+    W[7] = cb[rng.integers(0, 6, size=3000)]            # about 2500 indices in five groups
+    W[20, :1300] = 0.5                                   # one group of 1300: crosses two chunk boundaries
+    W[41] = cb[rng.choice(6, size=3000, p=[0.04, 0.3, 0.3, 0.2, 0.1, 0.06])]
+    X = rng.standard_normal((3000, 1)).astype(np.float32)
+
+    class Case:
+        pass
+    w = Case()
+    w.name, w.W, w.codebook, w.X, w.m, w.n, w.L = "short rows with long ones", W, cb, X, 60, 3000, 1
+    full_check(w)
