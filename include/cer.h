@@ -11,7 +11,10 @@
  * and computes Y = W.X on the GPU from those arrays (Appendix A-C, Algorithms 3 and 4): per row,
  * the inputs selected by one group of column indices are summed and the sum is multiplied once
  * by the group's value; the most frequent value Omega[0] owns no indices and is handled by a
- * constant term (Appendix A-A1).
+ * constant term (Appendix A-A1).  That order of operations is kept where it is the fastest on
+ * this machine (one input vector, rows of long groups); elsewhere the same sum is formed with
+ * one multiply-add per indexed element, or from the decoded matrix on the matrix cores --
+ * cer_matmul_path tells which.
  *
  * Conventions
  *   - Every function returns CER_OK (0) or a negative CER_E_* code; nothing aborts or throws
