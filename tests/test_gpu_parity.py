@@ -349,3 +349,51 @@ def test_dominant_value_term_error_scale():
             assert (np.abs(Y - want) <= bound).all(), f"{fmt} L={L}"
             dom = W[:, 0] == 5.0
             assert (np.abs(Y[dom] - want[dom]) <= TOL * np.abs(want[dom])).all(), f"{fmt} L={L}: dominant rows"
+
+
+def test_concurrent_calls_on_one_handle():
+    """Four host threads, each with its own stream and its own inputs, call every kind of product on the same
+    handles at the same time (the handle is immutable, the library's one-time set-up is guarded): every result
+    must match the oracle."""
+    import threading
+    dev = _gpu()
+    cases = []
+    for w, L in ((wl.alexnet_fc6(L=1, scale=8), 1), (wl.sweep_cell(256, 0.5, L=1, scale=4), 1),
+                 (wl.alexnet_fc6(L=32, scale=8), 32), (wl.conv3x3(L=7, nonzero_dominant=True, scale=4), 7)):
+        cases.append((w, L, B.cer_encode(w.W, w.codebook), B.cser_encode(w.W, w.codebook)))
+    errors = []
+
+    def worker(tid):
+        try:
+            stream = torch.cuda.Stream(device=dev)
+            rng = np.random.default_rng(300 + tid)
+            with torch.cuda.stream(stream):
+                for rep in range(6):
+                    for w, L, hc, hs in cases:
+                        X = rng.standard_normal((w.n, L)).astype(np.float32)
+                        Xd = torch.from_numpy(X).to(dev, non_blocking=False)
+                        Yc = torch.full((w.m, L), float("nan"), dtype=torch.float32, device=dev)
+                        Ys = torch.full((w.m, L), float("nan"), dtype=torch.float32, device=dev)
+                        B.cer_matmul(hc, Xd, Yc, L, stream)
+                        B.cser_matmul(hs, Xd, Ys, L, stream)
+                        stream.synchronize()
+                        want = w.W.astype(np.float64) @ X.astype(np.float64)
+                        scale = np.abs(w.W).astype(np.float64) @ np.abs(X).astype(np.float64)
+                        om0 = float(B.cer_get_array(hc, B.CER_ARRAY_OMEGA)[0])
+                        bound = TOL * (scale + abs(om0) * np.abs(X).astype(np.float64).sum(axis=0)[None, :])
+                        for Y in (Yc, Ys):
+                            y = Y.cpu().numpy().astype(np.float64)
+                            if not (np.isfinite(y).all() and (np.abs(y - want) <= bound).all()):
+                                errors.append(f"thread {tid} rep {rep} {w.name} L={L}")
+        except Exception as e:  # noqa: BLE001 - reported below
+            errors.append(f"thread {tid}: {e!r}")
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    for _, _, hc, hs in cases:
+        B.cer_free(hc)
+        B.cer_free(hs)
+    assert not errors, errors[:5]
