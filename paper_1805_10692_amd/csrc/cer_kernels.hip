@@ -701,14 +701,16 @@ __device__ __forceinline__ void ragged_store(const Vec<4>& acc, float* yrow, con
 }
 __device__ __forceinline__ void ragged_store(const Vec<1>&, float*, const float*, float, uint32_t, uint32_t) {}
 
-constexpr int kExpChunk = 2048;  // colI positions whose values one expansion holds (8 KiB per wave)
+// colI positions whose values one expansion holds: 2048 (8 KiB per wave), or 512 for matrices of short rows, whose
+// waves are bound by their start-up chain and gain from six instead of four workgroups per compute unit
+constexpr int kExpChunkLong = 2048, kExpChunkShort = 512;
 constexpr uint32_t kExpLong = 16;  // groups longer than this are written by the whole wave
 
 // kRagged (V = 4 only): the batch width is not a multiple of 4 or X / Y are only 4-byte aligned.  The gathers are
 // 16-byte loads from 4-byte aligned addresses; the lanes of the last, partial column group take the row's last four
 // columns instead (all loads stay inside the row) and write only the columns no other lane owns; Y is written
 // element by element.
-template <typename IdxT, int V, int P, bool kRagged>
+template <typename IdxT, int V, int P, bool kRagged, int kExpChunk = kExpChunkLong>
 __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
                                                               const float* __restrict__ T, uint32_t L, uint32_t ntiles,
                                                               uint32_t rowblocks, uint32_t items_per_xcd) {
@@ -1438,17 +1440,22 @@ hipError_t launch_gemv_expand(const KView& k, const GemvExpandPlan& p, const flo
 // kernel on every workload (1.05 - 1.2 x on the layer shapes, up to 2 x on rows of many short groups).
 // CER_GEMM_EXPAND=0 selects the cursor kernel.
 template <typename IdxT, int V, int P>
-hipError_t launch_gemm_vp(const KView& k, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream) {
+hipError_t launch_gemm_vp(const KView& k, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream,
+                          bool short_rows = false) {
     constexpr uint32_t TW = V * P;
     const uint32_t ntiles = (L + TW - 1) / TW;
     const uint32_t rowblocks = (k.m + 3) / 4;
     const uint64_t nitems = (uint64_t)ntiles * rowblocks;
     if (nitems > 0x7FFFFFFFull / 8) return hipErrorInvalidValue;
     const uint32_t ipx = (uint32_t)((nitems + 7) / 8);
-    if (env_int("CER_GEMM_EXPAND", 1) != 0)
-        hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, V, P, false>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L,
-                           ntiles, rowblocks, ipx);
-    else
+    if (env_int("CER_GEMM_EXPAND", 1) != 0) {
+        if (TW == 32 && V == 4 && short_rows)
+            hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, 8, false, kExpChunkShort>), dim3(ipx * 8), dim3(256), 0, stream,
+                               k, X, Y, T, L, ntiles, rowblocks, ipx);
+        else
+            hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, V, P, false>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L,
+                               ntiles, rowblocks, ipx);
+    } else
         hipLaunchKernelGGL((cer_gemm_kernel<IdxT, V, P>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L, ntiles,
                            rowblocks, ipx);
     return hipGetLastError();
@@ -1456,15 +1463,20 @@ hipError_t launch_gemm_vp(const KView& k, const float* X, float* Y, const float*
 
 // The default kernel on a batch whose width is not a multiple of 4, or whose X / Y are only 4-byte aligned (L >= 4).
 template <typename IdxT, int P>
-hipError_t launch_gemm_ragged(const KView& k, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream) {
+hipError_t launch_gemm_ragged(const KView& k, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream,
+                              bool short_rows = false) {
     constexpr uint32_t TW = 4 * P;
     const uint32_t ntiles = (L + TW - 1) / TW;
     const uint32_t rowblocks = (k.m + 3) / 4;
     const uint64_t nitems = (uint64_t)ntiles * rowblocks;
     if (nitems > 0x7FFFFFFFull / 8 || L < 4) return hipErrorInvalidValue;
     const uint32_t ipx = (uint32_t)((nitems + 7) / 8);
-    hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, P, true>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L, ntiles,
-                       rowblocks, ipx);
+    if (P == 8 && short_rows)
+        hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, 8, true, kExpChunkShort>), dim3(ipx * 8), dim3(256), 0, stream, k, X,
+                           Y, T, L, ntiles, rowblocks, ipx);
+    else
+        hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, P, true>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L,
+                           ntiles, rowblocks, ipx);
     return hipGetLastError();
 }
 
@@ -1507,7 +1519,8 @@ uint32_t pick_wide_tile(uint32_t L, uint32_t m, const float* X, uint32_t max_til
 }
 
 template <typename IdxT>
-hipError_t launch_gemm(const KView& k, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream) {
+hipError_t launch_gemm(const KView& k, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream,
+                       bool short_rows) {
     const bool vec4 = (L % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15u) == 0) &&
                       ((reinterpret_cast<uintptr_t>(Y) & 15u) == 0) && ((reinterpret_cast<uintptr_t>(T) & 15u) == 0);
     if (vec4) {
@@ -1521,7 +1534,7 @@ hipError_t launch_gemm(const KView& k, const float* X, float* Y, const float* T,
             case 4: return launch_gemm_vp<IdxT, 4, 1>(k, X, Y, T, L, stream);
             case 8: return launch_gemm_vp<IdxT, 4, 2>(k, X, Y, T, L, stream);
             case 16: return launch_gemm_vp<IdxT, 4, 4>(k, X, Y, T, L, stream);
-            case 32: return launch_gemm_vp<IdxT, 4, 8>(k, X, Y, T, L, stream);
+            case 32: return launch_gemm_vp<IdxT, 4, 8>(k, X, Y, T, L, stream, short_rows);
             case 64: return launch_gemm_vp<IdxT, 4, 16>(k, X, Y, T, L, stream);
             case 128: return launch_gemm_vp<IdxT, 4, 32>(k, X, Y, T, L, stream);
             case 256: return launch_gemm_vp<IdxT, 4, 64>(k, X, Y, T, L, stream);
@@ -1535,7 +1548,7 @@ hipError_t launch_gemm(const KView& k, const float* X, float* Y, const float* T,
         switch (rtw) {
             case 8: return launch_gemm_ragged<IdxT, 2>(k, X, Y, T, L, stream);
             case 16: return launch_gemm_ragged<IdxT, 4>(k, X, Y, T, L, stream);
-            case 32: return launch_gemm_ragged<IdxT, 8>(k, X, Y, T, L, stream);
+            case 32: return launch_gemm_ragged<IdxT, 8>(k, X, Y, T, L, stream, short_rows);
             case 64: return launch_gemm_ragged<IdxT, 16>(k, X, Y, T, L, stream);
             default: return launch_gemm_ragged<IdxT, 32>(k, X, Y, T, L, stream);
         }
@@ -1802,10 +1815,13 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
                 default: e = launch_xtile<uint32_t>(k, plan, X, Y, T, L, stream, 2); break;
             }
         } else {
+            // CER_GEMM_SHORT: 0 = never the 512-position chunks, 1 = always (32-column tiles), unset = by the average row
+            const int sm = env_int("CER_GEMM_SHORT", -1);
+            const bool short_rows = sm == 1 || (sm != 0 && d.nnz <= d.m * 384);
             switch (d.colI_bits) {
-                case 8: e = launch_gemm<uint8_t>(k, X, Y, T, L, stream); break;
-                case 16: e = launch_gemm<uint16_t>(k, X, Y, T, L, stream); break;
-                default: e = launch_gemm<uint32_t>(k, X, Y, T, L, stream); break;
+                case 8: e = launch_gemm<uint8_t>(k, X, Y, T, L, stream, short_rows); break;
+                case 16: e = launch_gemm<uint16_t>(k, X, Y, T, L, stream, short_rows); break;
+                default: e = launch_gemm<uint32_t>(k, X, Y, T, L, stream, short_rows); break;
             }
         }
     }

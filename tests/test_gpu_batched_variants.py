@@ -2,7 +2,8 @@
 position in LDS, then a plain multiply-add stream; CER_GEMM_EXPAND=1), the cursor variant that sums each
 group before its one multiplication (CER_GEMM_EXPAND=0), and the default one with ragged batch widths served
 one column per lane instead of by 16-byte gathers (CER_GEMM_RAGGED=0) -- on every kind of matrix, against the
-oracle under the usual bound."""
+oracle under the usual bound.  A fourth run forces the 512-position value chunks meant for matrices of short
+rows (CER_GEMM_SHORT=1) onto every matrix, so that long rows walk many chunks."""
 import os
 
 import numpy as np
@@ -18,6 +19,7 @@ VARIANTS = {
     "expand": {"CER_GEMM_EXPAND": "1", "CER_GEMM_RAGGED": "1"},            # the defaults
     "cursor": {"CER_GEMM_EXPAND": "0", "CER_GEMM_RAGGED": "1"},
     "expand_one_column_per_lane": {"CER_GEMM_EXPAND": "1", "CER_GEMM_RAGGED": "0"},   # ragged widths without 16-byte gathers
+    "expand_short_chunks": {"CER_GEMM_EXPAND": "1", "CER_GEMM_RAGGED": "1", "CER_GEMM_SHORT": "1"},  # 512-position chunks on every matrix
 }
 
 
