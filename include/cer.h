@@ -117,6 +117,17 @@ int cer_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t 
 int cser_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t batch, void* stream);
 
 /*
+ * cer_trim -- gives the device memory of released temporaries back to the system.  The products and
+ * conversions that need a temporary (see each call) take it, ordered on the caller's stream, from
+ * a memory pool of the library's own on the current device; the pool keeps what it has handed out
+ * once, because getting a few hundred megabytes from the system again costs more than the product
+ * that needs them.  Its size settles at the largest amount in use at one time.  cer_trim releases
+ * whatever is not in use at the moment of the call on the current device; it does not synchronise
+ * and may be called at any time.  Errors: CER_E_HIP.
+ */
+int cer_trim(void);
+
+/*
  * cer_matmul_path -- which kernel cer_matmul / cser_matmul runs for this handle and batch:
  *   0  batch-1 kernel: X staged in LDS per workgroup, one wave per row, the paper's arithmetic (the
  *      inputs of a group are summed, then multiplied once)

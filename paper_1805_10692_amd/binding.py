@@ -35,7 +35,7 @@ EXPORTS = [
     "csr_encode", "csr_matmul", "csr_decode", "csr_get_array", "csr_storage_bits", "csr_device_bytes",
     "csr_clone_device", "csr_free", "cer_cost_model", "csr_cost_model", "dense_cost_model",
     "cer_encode_device", "cer_quantize_uniform", "cer_quantize_encode_device", "cer_matmul_path", "cer_stream_read",
-    "cer_decode_device",
+    "cer_decode_device", "cer_trim",
 ]
 
 CER_FORMAT_CER, CER_FORMAT_CSER = 0, 1
@@ -128,6 +128,8 @@ def lib() -> ctypes.CDLL:
         L.cer_decode_device.argtypes = [vp, vp, vp]
         L.cer_stream_read.restype = ctypes.c_int
         L.cer_stream_read.argtypes = [vp, i64, vp, vp]
+        L.cer_trim.restype = ctypes.c_int
+        L.cer_trim.argtypes = []
         L.cer_matmul_path.restype = ctypes.c_int
         L.cer_matmul_path.argtypes = [vp, i64]
         L.cer_encode_device.restype = ctypes.c_int
@@ -252,6 +254,11 @@ def cer_decode_device(h: Handle, W_out, stream=None) -> None:
     d = cer_get_dims(h)
     _check(lib().cer_decode_device(h.ptr, _dev_ptr(W_out) if d["m"] * d["n"] else 0, _stream_ptr(stream)),
            "cer_decode_device")
+
+
+def cer_trim() -> None:
+    """Releases the device memory the library keeps for its temporaries on the current device."""
+    _check(lib().cer_trim(), "cer_trim")
 
 
 def cer_matmul_path(h: Handle, batch: int) -> int:

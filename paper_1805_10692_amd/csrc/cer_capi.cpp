@@ -3,6 +3,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "../../include/cer.h"
@@ -25,6 +26,52 @@ int cer::record_hip_error(int hip_error) {
     g_last_hip_error = hip_error;
     return CER_E_HIP;
 }
+
+// ---- stream-ordered temporaries from a pool of the library's own ------------------------------------------------
+namespace {
+struct TempPool {
+    std::mutex mu;
+    bool tried = false;
+    hipMemPool_t pool = nullptr;  // nullptr after a failed creation: the device's default pool serves instead
+};
+TempPool g_temp_pools[16];
+
+// The library's pool on the current device, created on first use.
+hipMemPool_t temp_pool() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
+    TempPool& t = g_temp_pools[dev];
+    std::lock_guard<std::mutex> lock(t.mu);
+    if (!t.tried) {
+        t.tried = true;
+        hipMemPoolProps props;
+        std::memset(&props, 0, sizeof props);
+        props.allocType = hipMemAllocationTypePinned;
+        props.handleTypes = hipMemHandleTypeNone;
+        props.location.type = hipMemLocationTypeDevice;
+        props.location.id = dev;
+        hipMemPool_t pool = nullptr;
+        if (hipMemPoolCreate(&pool, &props) == hipSuccess) {
+            uint64_t keep = UINT64_MAX;  // nothing goes back to the system before cer_trim
+            if (hipMemPoolSetAttribute(pool, hipMemPoolAttrReleaseThreshold, &keep) == hipSuccess)
+                t.pool = pool;
+            else
+                (void)hipMemPoolDestroy(pool);
+        }
+        (void)hipGetLastError();  // a failed creation is not an error of the call that asked for memory
+    }
+    return t.pool;
+}
+}  // namespace
+
+int cer::temp_alloc(void** p, size_t bytes, void* stream) {
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipMemPool_t pool = temp_pool();
+    return (int)(pool ? hipMallocFromPoolAsync(p, bytes, pool, s) : hipMallocAsync(p, bytes, s));
+}
+
+int cer::temp_free(void* p, void* stream) { return (int)hipFreeAsync(p, static_cast<hipStream_t>(stream)); }
+
 
 namespace {
 
@@ -416,6 +463,17 @@ int cer_stream_read(const void* src, int64_t bytes, void* sink, void* stream) {
     if ((reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return CER_E_INVALID;
     const int rc = cer::launch_stream_read(src, bytes, sink, stream);
     return rc == 0 ? CER_OK : hip_fail((hipError_t)rc);
+}
+
+int cer_trim(void) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return hip_fail(hipGetLastError());
+    if (dev < 0 || dev >= 16) return CER_OK;
+    TempPool& t = g_temp_pools[dev];
+    std::lock_guard<std::mutex> lock(t.mu);
+    if (!t.pool) return CER_OK;
+    const hipError_t e = hipMemPoolTrimTo(t.pool, 0);
+    return e == hipSuccess ? CER_OK : hip_fail(e);
 }
 
 const char* cer_strerror(int code) {

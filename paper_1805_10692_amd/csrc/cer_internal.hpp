@@ -95,6 +95,13 @@ int quantize_device(const float* W_dev, int64_t count, int32_t bits, uint8_t* co
 // Remembers a HIP error for cer_last_hip_error() and returns CER_E_HIP (cer_capi.cpp).
 int record_hip_error(int hip_error);
 
+// Stream-ordered temporaries (cer_capi.cpp).  They come from a memory pool of the library's own on the current
+// device, which keeps what it has handed out once (release threshold: none) -- the default pool gives its memory
+// back at every synchronisation, and getting a few hundred megabytes again costs more than the product that needs
+// them.  cer_trim() releases what is cached.  Both return a hipError_t value as int.
+int temp_alloc(void** p, size_t bytes, void* stream);
+int temp_free(void* p, void* stream);
+
 }  // namespace cer
 
 namespace cer {

@@ -1666,7 +1666,7 @@ hipError_t launch_xtile(const KView& k, const XtilePlan& p, const float* X, floa
     const bool one_tile = p.ntiles == 1;
     const uint32_t raw_x = one_tile && !(L == (uint32_t)p.V && (reinterpret_cast<uintptr_t>(X) & 15u) == 0) ? 1u : 0u;
     if (!one_tile) {
-        hipError_t e = hipMallocAsync(reinterpret_cast<void**>(&tmp), (size_t)p.ntiles * k.n * p.V * sizeof(float), stream);
+        hipError_t e = (hipError_t)temp_alloc(reinterpret_cast<void**>(&tmp), (size_t)p.ntiles * k.n * p.V * sizeof(float), stream);
         if (e != hipSuccess) return e;
         const int vec_ok = (L % 4 == 0 && (reinterpret_cast<uintptr_t>(X) & 15u) == 0) ? 1 : 0;
         const dim3 grid((k.n + 63) / 64, (p.ntiles + 15) / 16);
@@ -1676,7 +1676,7 @@ hipError_t launch_xtile(const KView& k, const XtilePlan& p, const float* X, floa
             hipLaunchKernelGGL(xtile_pack_kernel<4>, grid, dim3(256), 0, stream, X, k.n, L, p.ntiles, vec_ok, tmp);
         e = hipGetLastError();
         if (e != hipSuccess) {
-            (void)hipFreeAsync(tmp, stream);
+            (void)temp_free(tmp, stream);
             return e;
         }
         Xp = tmp;
@@ -1684,7 +1684,7 @@ hipError_t launch_xtile(const KView& k, const XtilePlan& p, const float* X, floa
     hipError_t e = p.V == 8 ? launch_xtile_v<IdxT, 8, 3>(k, p, Xp, raw_x, Y, T, L, stream, idx_slot * 2 + 1)
                             : launch_xtile_v<IdxT, 4, 8>(k, p, Xp, raw_x, Y, T, L, stream, idx_slot * 2);
     if (tmp) {
-        hipError_t f = hipFreeAsync(tmp, stream);
+        hipError_t f = (hipError_t)temp_free(tmp, stream);
         if (e == hipSuccess) e = f;
     }
     return e;
@@ -1731,11 +1731,11 @@ bool densify_pays(const DeviceView& d, uint32_t L) {
 
 hipError_t launch_densified(const DeviceView& d, const float* X, float* Y, uint32_t L, hipStream_t stream) {
     float* W = nullptr;
-    hipError_t e = hipMallocAsync(reinterpret_cast<void**>(&W), (size_t)d.m * (size_t)d.n * sizeof(float), stream);
+    hipError_t e = (hipError_t)temp_alloc(reinterpret_cast<void**>(&W), (size_t)d.m * (size_t)d.n * sizeof(float), stream);
     if (e != hipSuccess) return e;
     if (decode_device(d, W, stream) != 0) e = hipErrorLaunchFailure;  // a CER_* code: only a failed launch is possible
     if (e == hipSuccess) e = (hipError_t)launch_dense(W, X, Y, d.m, d.n, (int64_t)L, stream);
-    const hipError_t f = hipFreeAsync(W, stream);
+    const hipError_t f = (hipError_t)temp_free(W, stream);
     return e == hipSuccess ? f : e;
 }
 
@@ -1786,12 +1786,12 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
         nslabs = std::max<uint32_t>(nslabs, 1u);
         const uint32_t slab = ((uint32_t)d.n + nslabs - 1) / nslabs;
         const size_t t_floats = ((size_t)L + 63) & ~(size_t)63;
-        e = hipMallocAsync(reinterpret_cast<void**>(&scratch), (t_floats + (size_t)nslabs * L) * sizeof(float), stream);
+        e = (hipError_t)temp_alloc(reinterpret_cast<void**>(&scratch), (t_floats + (size_t)nslabs * L) * sizeof(float), stream);
         if (e != hipSuccess) return (int)e;
         T = scratch;
         e = launch_colsum(X, (uint32_t)d.n, L, scratch + t_floats, nslabs, std::max<uint32_t>(slab, 1u), CB, T, stream);
         if (e != hipSuccess) {
-            (void)hipFreeAsync(scratch, stream);
+            (void)temp_free(scratch, stream);
             return (int)e;
         }
     }
@@ -1826,7 +1826,7 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
         }
     }
     if (scratch) {
-        hipError_t f = hipFreeAsync(scratch, stream);
+        hipError_t f = (hipError_t)temp_free(scratch, stream);
         if (e == hipSuccess) e = f;
     }
     return (int)e;

@@ -303,7 +303,7 @@ hipError_t launch_gemm_cfg(const float* W, const float* X, float* Y, uint32_t m,
     const size_t count = (size_t)m * L;
     hipError_t e = hipSuccess;
     if (splits > 1) {
-        e = hipMallocAsync(reinterpret_cast<void**>(&part), count * splits * sizeof(float), stream);
+        e = (hipError_t)temp_alloc(reinterpret_cast<void**>(&part), count * splits * sizeof(float), stream);
         if (e != hipSuccess) return e;
     }
     float* out = splits > 1 ? part : Y;
@@ -320,7 +320,7 @@ hipError_t launch_gemm_cfg(const float* W, const float* X, float* Y, uint32_t m,
                                splits);
             e = hipGetLastError();
         }
-        hipError_t f = hipFreeAsync(part, stream);
+        hipError_t f = (hipError_t)temp_free(part, stream);
         if (e == hipSuccess) e = f;
     }
     return e;

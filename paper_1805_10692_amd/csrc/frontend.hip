@@ -776,11 +776,11 @@ struct DeviceBuf {
     void* p = nullptr;
     hipStream_t s = nullptr;
     ~DeviceBuf() {
-        if (p) (void)hipFreeAsync(p, s);
+        if (p) (void)cer::temp_free(p, s);
     }
     hipError_t alloc(size_t bytes, hipStream_t stream) {
         s = stream;
-        return hipMallocAsync(&p, bytes ? bytes : 1, stream);
+        return (hipError_t)cer::temp_alloc(&p, bytes ? bytes : 1, stream);
     }
     template <typename T>
     T* as() const {

@@ -91,3 +91,17 @@ def test_automatic_full_conv_batch3136_sampled(automatic):
     w = wl.conv3x3(nonzero_dominant=True)
     rows = np.random.default_rng(3).choice(w.m, 6, replace=False)
     sampled_check(w, ("cer", "cser"), np.sort(rows))
+
+
+def test_trim_releases_cached_temporaries_and_products_go_on(forced):
+    """cer_trim gives the pooled temporaries back; the next products allocate again and stay correct."""
+    import torch
+    w = wl.conv3x3(L=200, scale=4)
+    full_check(w)
+    before = torch.cuda.mem_get_info()[0]
+    B.cer_trim()
+    after = torch.cuda.mem_get_info()[0]
+    assert after >= before                      # nothing is taken by a trim; what was cached is free again
+    full_check(w)
+    B.cer_trim()
+    B.cer_trim()                                # trimming an empty pool is fine
