@@ -107,7 +107,8 @@ int cser_encode(const float* W_host, int64_t m, int64_t n, const float* codebook
  * Omega[0] != 0 and batch > 1 (or X does not fit in LDS) a stream-ordered temporary of batch floats
  * (plus partial sums) is allocated and released on `stream`; otherwise (and when cer_matmul_path
  * reports kernel 0 or 1) the call
- * only launches kernels and may be recorded into a HIP graph after one eager call on the device.
+ * only launches kernels and may be recorded into a HIP graph after one eager call on the device
+ * (a batched product of a matrix with split rows, cer_long_row_parts > 0, allocates as well).
  * fp32 arithmetic; the summation order differs from a sequential loop.  With Omega[0] != 0 the
  * rounding error is relative to sum|w||x| + |Omega[0]|.sum|x|: Appendix A-A1 adds that term and
  * subtracts it again inside the groups' weights.
@@ -199,6 +200,15 @@ int cer_clone_device(const cer_handle_t* h, cer_handle_t** out);
 /* Bytes of device memory the product reads from the handle's arrays in one call (colI at its
  * width + uint32 OmegaPtr and rowPtr + OmegaI + Omega); 0 for a host-only handle. */
 int64_t cer_device_bytes(const cer_handle_t* h);
+
+/* When a matrix has rows much longer than its average row (one of more than 3 P indexed elements,
+ * P = 1.5 x the average rounded up to a multiple of 2048), its rows of more than 2 P elements are
+ * served in parts of P elements by the batched product, so that one long row does not outlast
+ * the rest of the launch; such a product uses a
+ * stream-ordered temporary of batch floats per part.  Returns the number of parts beyond the
+ * rows' first ones (0: no row is split; also for host-only handles and for handles made by the
+ * device-side encoder, whose rows stay whole). */
+int64_t cer_long_row_parts(const cer_handle_t* h);
 
 /* Frees host and device memory.  NULL is allowed. */
 void cer_free(cer_handle_t* h);

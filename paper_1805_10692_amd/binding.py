@@ -31,7 +31,7 @@ CER_ARRAY_OMEGA, CER_ARRAY_COLI, CER_ARRAY_OMEGAPTR, CER_ARRAY_ROWPTR, CER_ARRAY
 EXPORTS = [
     "cer_encode", "cser_encode", "cer_matmul", "cser_matmul", "cer_decode", "cser_decode",
     "cer_get_array", "cer_get_dims", "cer_storage_bits", "cer_get_stats", "cer_clone_device",
-    "cer_device_bytes", "cer_free", "dense_matmul", "cer_stream_copy", "cer_strerror", "cer_last_hip_error",
+    "cer_device_bytes", "cer_long_row_parts", "cer_free", "dense_matmul", "cer_stream_copy", "cer_strerror", "cer_last_hip_error",
     "csr_encode", "csr_matmul", "csr_decode", "csr_get_array", "csr_storage_bits", "csr_device_bytes",
     "csr_clone_device", "csr_free", "cer_cost_model", "csr_cost_model", "dense_cost_model",
     "cer_encode_device", "cer_quantize_uniform", "cer_quantize_encode_device", "cer_matmul_path", "cer_stream_read",
@@ -98,6 +98,8 @@ def lib() -> ctypes.CDLL:
         L.cer_clone_device.argtypes = [vp, pvp]
         L.cer_device_bytes.restype = i64
         L.cer_device_bytes.argtypes = [vp]
+        L.cer_long_row_parts.restype = i64
+        L.cer_long_row_parts.argtypes = [vp]
         L.cer_free.restype = None
         L.cer_free.argtypes = [vp]
         L.dense_matmul.restype = ctypes.c_int
@@ -335,6 +337,11 @@ def cer_clone_device(h: Handle) -> Handle:
 
 def cer_device_bytes(h: Handle) -> int:
     return int(lib().cer_device_bytes(h.ptr))
+
+
+def cer_long_row_parts(h: Handle) -> int:
+    """Number of further parts into which the batched product splits rows much longer than the average (0: none)."""
+    return int(lib().cer_long_row_parts(h.ptr))
 
 
 def cer_free(h: Handle) -> None:

@@ -161,6 +161,59 @@ int cer::ensure_host_arrays(const cer_matrix* h) {
 
 namespace {
 
+// Rows much longer than the average row would keep one wave busy long after the rest of a batched product is
+// done.  When some row holds more than 3 P positions, P = 1.5 x the average row rounded up to a multiple of 2048,
+// the rows of more than 2 P positions are served in parts of P positions: the table lists every part but a row's first.  Matrices of rows of
+// similar length (all of the paper's layer shapes with independent elements) have no such row and no table.
+int upload_split_table(cer_matrix* h) {
+    const cer::HostMatrix& A = *h->host;
+    if (A.m <= 0 || A.nnz <= 0) return CER_OK;
+    const uint64_t mean = (uint64_t)(A.nnz / A.m);
+    const uint64_t len = ((std::max<uint64_t>(mean + mean / 2, 2048) + 2047) / 2048) * 2048;
+    if (2 * len >= (uint64_t)A.n || len > 0x3FFFFFFFull) return CER_OK;  // no row can be longer than n
+    // the second kernel and the temporary cost about 6 us per product: only when some row would keep its wave busy
+    // for long, i.e. holds more than 3 P positions
+    uint64_t longest = 0;
+    for (int64_t r = 0; r < A.m; ++r)
+        longest = std::max<uint64_t>(longest, A.omegaPtr.at((int64_t)A.rowPtr.at(r + 1)) - A.omegaPtr.at((int64_t)A.rowPtr.at(r)));
+    if (longest <= 3 * len) return CER_OK;
+    std::vector<uint32_t> parts, rows;
+    for (int64_t r = 0; r < A.m; ++r) {
+        const uint64_t rs = A.omegaPtr.at((int64_t)A.rowPtr.at(r)), re = A.omegaPtr.at((int64_t)A.rowPtr.at(r + 1));
+        if (re - rs <= 2 * len) continue;
+        const uint32_t first = (uint32_t)(parts.size() / 4);
+        for (uint64_t b = rs + len; b < re; b += len) {
+            parts.push_back((uint32_t)r);
+            parts.push_back((uint32_t)b);
+            parts.push_back((uint32_t)std::min(re, b + len));
+            parts.push_back(0u);
+        }
+        rows.push_back((uint32_t)r);
+        rows.push_back(first);
+        rows.push_back((uint32_t)(parts.size() / 4) - first);
+        rows.push_back(0u);
+    }
+    if (rows.empty()) return CER_OK;
+    const size_t part_bytes = parts.size() * 4, row_bytes = rows.size() * 4;
+    void* base = nullptr;
+    hipError_t e = hipMalloc(&base, part_bytes + row_bytes);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipMemcpy(base, parts.data(), part_bytes, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(static_cast<unsigned char*>(base) + part_bytes, rows.data(), row_bytes, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(base);
+        return hip_fail(e);
+    }
+    h->d_split = base;
+    h->view.split_parts = base;
+    h->view.split_rows = static_cast<unsigned char*>(base) + part_bytes;
+    h->view.n_split_parts = (uint32_t)(parts.size() / 4);
+    h->view.n_split_rows = (uint32_t)(rows.size() / 4);
+    h->view.split_len = (uint32_t)len;
+    h->view.split_min = (uint32_t)(2 * len);
+    return CER_OK;
+}
+
 // Copies the host arrays into one fresh device allocation (layout: cer::DeviceLayout).
 int upload(cer_matrix* h) {
     const cer::HostMatrix& A = *h->host;
@@ -205,7 +258,7 @@ int upload(cer_matrix* h) {
         return hip_fail(e);
     }
     cer::bind_device(h, dev, base, l);
-    return CER_OK;
+    return upload_split_table(h);
 }
 
 int encode_any(const float* W, int64_t m, int64_t n, const float* codebook, int32_t K, bool cser, cer_handle_t** out) {
@@ -223,7 +276,7 @@ int encode_any(const float* W, int64_t m, int64_t n, const float* codebook, int3
         h->host = std::move(host);
         rc = upload(h);
         if (rc != CER_OK) {
-            delete h;
+            cer_free(h);
             return rc;
         }
         *out = h;
@@ -363,7 +416,7 @@ int cer_clone_device(const cer_handle_t* h, cer_handle_t** out) {
         c->host = h->host;
         rc = upload(c);
         if (rc != CER_OK) {
-            delete c;
+            cer_free(c);
             return rc;
         }
         *out = c;
@@ -438,9 +491,12 @@ int cer_quantize_uniform(const float* W, int64_t count, int32_t bits, uint8_t* c
 
 int64_t cer_device_bytes(const cer_handle_t* h) { return (h && h->device >= 0) ? h->stream_bytes : 0; }
 
+int64_t cer_long_row_parts(const cer_handle_t* h) { return (h && h->device >= 0) ? (int64_t)h->view.n_split_parts : 0; }
+
 void cer_free(cer_handle_t* h) {
     if (!h) return;
     if (h->d_base) (void)hipFree(h->d_base);
+    if (h->d_split) (void)hipFree(h->d_split);
     delete h;
 }
 

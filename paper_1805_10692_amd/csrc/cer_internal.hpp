@@ -59,6 +59,14 @@ struct DeviceView {
     int64_t nnz = 0;
     int64_t nonempty_groups = 0;
     float omega0 = 0.f;
+    // Rows much longer than the average, served in parts by the default batched kernel (none: n_split_parts = 0).
+    // split_parts[i] = {row, first position, end position, 0} for every part but a row's first;
+    // split_rows[j] = {row, its first entry in split_parts, its number of entries, 0}.
+    const void* split_parts = nullptr;
+    const void* split_rows = nullptr;
+    uint32_t n_split_parts = 0, n_split_rows = 0;
+    uint32_t split_len = 0;  // positions per part
+    uint32_t split_min = 0;  // rows with more positions than this are split
 };
 
 // The handle's single device allocation: [colI | 8 KiB readable pad][OmegaPtr u32][rowPtr u32][OmegaI][Omega]
@@ -115,7 +123,8 @@ int ensure_host_arrays(const cer_matrix* h);
 struct cer_matrix {
     std::shared_ptr<const cer::HostMatrix> host;
     int device = -1;          // -1: host-only handle
-    void* d_base = nullptr;   // the one device allocation
+    void* d_base = nullptr;   // the device allocation of the format arrays
+    void* d_split = nullptr;  // table of the long rows' parts (a second, small allocation; null: no row is split)
     cer::DeviceLayout layout; // where the arrays sit inside it
     size_t d_bytes = 0;       // its size
     int64_t stream_bytes = 0; // bytes of format arrays a product reads

@@ -62,6 +62,21 @@ struct KView {
     float omega0;
 };
 
+// Rows much longer than the matrix's average are served in parts by the default batched kernel, so that one wave
+// does not outlast the whole launch: the row's own work item takes its first `len` positions, every further part
+// {row, first position, end position} is a work item of its own whose sums go to out[part][batch column] and are
+// added to Y by a second kernel.  nparts == 0: no row is split.
+struct SplitArgs {
+    const uint4* parts = nullptr;
+    float* out = nullptr;
+    uint32_t nparts = 0;
+    uint32_t len = 0;          // positions per part
+    uint32_t min = 0;          // rows with more positions than this are split
+    uint32_t base_blocks = 0;  // workgroups of the ordinary work list; the parts follow
+    const uint4* rows = nullptr;  // host side only: {row, first part, number of parts} per split row
+    uint32_t nrows = 0;
+};
+
 // OmegaI[g] for an 8-, 16- or 32-bit array, without a branch on the width: the aligned 32-bit
 // word that holds the element is loaded and the element is shifted out (the array is padded).
 __device__ __forceinline__ uint32_t load_rank(const void* p, int bits, uint32_t g) {
@@ -710,10 +725,10 @@ constexpr uint32_t kExpLong = 16;  // groups longer than this are written by the
 // 16-byte loads from 4-byte aligned addresses; the lanes of the last, partial column group take the row's last four
 // columns instead (all loads stay inside the row) and write only the columns no other lane owns; Y is written
 // element by element.
-template <typename IdxT, int V, int P, bool kRagged, int kExpChunk = kExpChunkLong>
+template <typename IdxT, int V, int P, bool kRagged, int kExpChunk = kExpChunkLong, bool kSplit = false>
 __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
                                                               const float* __restrict__ T, uint32_t L, uint32_t ntiles,
-                                                              uint32_t rowblocks, uint32_t items_per_xcd) {
+                                                              uint32_t rowblocks, uint32_t items_per_xcd, SplitArgs sp) {
     using G = GemmIdx<P>;
     constexpr int S = G::S, U = G::U, KQ = G::KQ, D = G::D;
     constexpr uint32_t PB = G::PB;
@@ -723,13 +738,27 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const flo
 
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = uniform(threadIdx.x >> 6);
-    const uint32_t xcd = blockIdx.x & 7u, q = blockIdx.x >> 3;
-    const uint32_t nitems = ntiles * rowblocks;
-    const uint32_t item = xcd * items_per_xcd + q;
-    if (q >= items_per_xcd || item >= nitems) return;
-    const uint32_t tile = item / rowblocks;
-    const uint32_t r = (item - tile * rowblocks) * 4u + wave;
-    if (r >= v.m) return;
+    uint32_t tile, r;
+    uint32_t part = 0, part_begin = 0, part_end = 0;
+    const bool is_part = kSplit && blockIdx.x >= sp.base_blocks;  // a further part of a long row
+    if (is_part) {
+        const uint32_t e = (blockIdx.x - sp.base_blocks) * 4u + wave;  // tile-major over (tile, part)
+        if (e >= ntiles * sp.nparts) return;
+        tile = e / sp.nparts;
+        part = e - tile * sp.nparts;
+        const uint4 d = sp.parts[part];
+        r = uniform(d.x);
+        part_begin = uniform(d.y);
+        part_end = uniform(d.z);
+    } else {
+        const uint32_t xcd = blockIdx.x & 7u, q = blockIdx.x >> 3;
+        const uint32_t nitems = ntiles * rowblocks;
+        const uint32_t item = xcd * items_per_xcd + q;
+        if (q >= items_per_xcd || item >= nitems) return;
+        tile = item / rowblocks;
+        r = (item - tile * rowblocks) * 4u + wave;
+        if (r >= v.m) return;
+    }
 
     const uint32_t sub = lane / P;
     const uint32_t col0 = tile * TW + (lane % P) * V;
@@ -741,14 +770,24 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const flo
     float* val = s_val[wave];
 
     const uint2 d0 = v.rowInfo[r], d1 = v.rowInfo[r + 1];
-    const uint32_t g0 = d0.x, rs = d0.y, g1 = d1.x, re = d1.y;
+    const uint32_t g0 = d0.x, g1 = d1.x;
+    uint32_t rs = d0.y, re = d1.y;
+    if (kSplit) {  // a part's own positions; the first part of a split row
+        if (is_part) {
+            rs = part_begin;
+            re = part_end;
+        } else if (re - rs > sp.min) {
+            re = rs + sp.len;
+        }
+    }
     const bool cser = v.cser != 0;
     const float om_l = v.omega[lane < v.K ? lane : 0u];
     const bool omega_by_lane = v.K <= (uint32_t)kWave;
 
     Vec<V> acc;
     acc.zero();
-    uint32_t gcur = g0;  // first raw group that may reach into the current chunk
+    uint32_t gcur = g0;  // first raw group that may reach into the current chunk (groups that end before it cost
+                         // a part nothing but their pointer tiles)
     for (uint32_t c0 = rs; c0 < re; c0 += kExpChunk) {
         const uint32_t c1 = min(re, c0 + (uint32_t)kExpChunk);
         // request order = arrival order: the chunk's first 64 group pointers, then its indices, then (below) the
@@ -836,12 +875,27 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const flo
 #pragma unroll
     for (int off = P; off < kWave; off <<= 1) acc.xor_add(off);
     if (sub == 0 && active) {
-        if (kRagged) {
+        if (kSplit && is_part) {  // partial sums of a further part: no constant term
+            if (kRagged) ragged_store(acc, sp.out + (size_t)part * L, T, 0.f, colx, col0);
+            else acc.store(sp.out + (size_t)part * L + col0);
+        } else if (kRagged) {
             ragged_store(acc, Y + (size_t)r * L, T, v.omega0, colx, col0);
         } else {
             if (v.omega0 != 0.f) acc.add_scaled(T + col0, v.omega0);
             acc.store(Y + (size_t)r * L + col0);
         }
+    }
+}
+
+// Y[row] += the sums of the row's further parts, in the order of the parts (deterministic).  One workgroup per
+// split row; rows[i] = {row, first part, number of parts}.
+__global__ __launch_bounds__(256) void split_add_kernel(const uint4* __restrict__ rows, const float* __restrict__ part_out,
+                                                        float* __restrict__ Y, uint32_t L) {
+    const uint4 d = rows[blockIdx.x];
+    for (uint32_t c = threadIdx.x; c < L; c += blockDim.x) {
+        float s = Y[(size_t)d.x * L + c];
+        for (uint32_t p = 0; p < d.z; ++p) s += part_out[(size_t)(d.y + p) * L + c];
+        Y[(size_t)d.x * L + c] = s;
     }
 }
 
@@ -1439,9 +1493,31 @@ hipError_t launch_gemv_expand(const KView& k, const GemvExpandPlan& p, const flo
 // The kernel that expands the group values per position is the default: measured on MI355X it beats the cursor
 // kernel on every workload (1.05 - 1.2 x on the layer shapes, up to 2 x on rows of many short groups).
 // CER_GEMM_EXPAND=0 selects the cursor kernel.
+// The default kernel on a matrix with split rows: the ordinary work list, then one wave per (batch tile, further
+// part) writing into a stream-ordered temporary, then the kernel that adds the parts' sums to Y.
+template <typename Kern>
+hipError_t launch_expand_split(Kern kern, const KView& k, const float* X, float* Y, const float* T, uint32_t L,
+                               uint32_t ntiles, uint32_t rowblocks, uint32_t ipx, SplitArgs sp, hipStream_t stream) {
+    const uint64_t blocks = (uint64_t)ipx * 8 + ((uint64_t)ntiles * sp.nparts + 3) / 4;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    float* out = nullptr;
+    hipError_t e = (hipError_t)temp_alloc(reinterpret_cast<void**>(&out), (size_t)sp.nparts * L * sizeof(float), stream);
+    if (e != hipSuccess) return e;
+    sp.out = out;
+    sp.base_blocks = ipx * 8;
+    hipLaunchKernelGGL(kern, dim3((uint32_t)blocks), dim3(256), 0, stream, k, X, Y, T, L, ntiles, rowblocks, ipx, sp);
+    e = hipGetLastError();
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(split_add_kernel, dim3(sp.nrows), dim3(256), 0, stream, sp.rows, out, Y, L);
+        e = hipGetLastError();
+    }
+    const hipError_t f = (hipError_t)temp_free(out, stream);
+    return e == hipSuccess ? f : e;
+}
+
 template <typename IdxT, int V, int P>
 hipError_t launch_gemm_vp(const KView& k, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream,
-                          bool short_rows = false) {
+                          const SplitArgs& sp, bool short_rows = false) {
     constexpr uint32_t TW = V * P;
     const uint32_t ntiles = (L + TW - 1) / TW;
     const uint32_t rowblocks = (k.m + 3) / 4;
@@ -1449,12 +1525,15 @@ hipError_t launch_gemm_vp(const KView& k, const float* X, float* Y, const float*
     if (nitems > 0x7FFFFFFFull / 8) return hipErrorInvalidValue;
     const uint32_t ipx = (uint32_t)((nitems + 7) / 8);
     if (env_int("CER_GEMM_EXPAND", 1) != 0) {
+        if (sp.nparts > 0)
+            return launch_expand_split(cer_gemm_expand_kernel<IdxT, V, P, false, kExpChunkLong, true>, k, X, Y, T, L, ntiles,
+                                       rowblocks, ipx, sp, stream);
         if (TW == 32 && V == 4 && short_rows)
             hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, 8, false, kExpChunkShort>), dim3(ipx * 8), dim3(256), 0, stream,
-                               k, X, Y, T, L, ntiles, rowblocks, ipx);
+                               k, X, Y, T, L, ntiles, rowblocks, ipx, SplitArgs{});
         else
             hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, V, P, false>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L,
-                               ntiles, rowblocks, ipx);
+                               ntiles, rowblocks, ipx, SplitArgs{});
     } else
         hipLaunchKernelGGL((cer_gemm_kernel<IdxT, V, P>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L, ntiles,
                            rowblocks, ipx);
@@ -1464,19 +1543,22 @@ hipError_t launch_gemm_vp(const KView& k, const float* X, float* Y, const float*
 // The default kernel on a batch whose width is not a multiple of 4, or whose X / Y are only 4-byte aligned (L >= 4).
 template <typename IdxT, int P>
 hipError_t launch_gemm_ragged(const KView& k, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream,
-                              bool short_rows = false) {
+                              const SplitArgs& sp, bool short_rows = false) {
     constexpr uint32_t TW = 4 * P;
     const uint32_t ntiles = (L + TW - 1) / TW;
     const uint32_t rowblocks = (k.m + 3) / 4;
     const uint64_t nitems = (uint64_t)ntiles * rowblocks;
     if (nitems > 0x7FFFFFFFull / 8 || L < 4) return hipErrorInvalidValue;
     const uint32_t ipx = (uint32_t)((nitems + 7) / 8);
+    if (sp.nparts > 0)
+        return launch_expand_split(cer_gemm_expand_kernel<IdxT, 4, P, true, kExpChunkLong, true>, k, X, Y, T, L, ntiles,
+                                   rowblocks, ipx, sp, stream);
     if (P == 8 && short_rows)
         hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, 8, true, kExpChunkShort>), dim3(ipx * 8), dim3(256), 0, stream, k, X,
-                           Y, T, L, ntiles, rowblocks, ipx);
+                           Y, T, L, ntiles, rowblocks, ipx, SplitArgs{});
     else
         hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, P, true>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L,
-                           ntiles, rowblocks, ipx);
+                           ntiles, rowblocks, ipx, SplitArgs{});
     return hipGetLastError();
 }
 
@@ -1520,7 +1602,7 @@ uint32_t pick_wide_tile(uint32_t L, uint32_t m, const float* X, uint32_t max_til
 
 template <typename IdxT>
 hipError_t launch_gemm(const KView& k, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream,
-                       bool short_rows) {
+                       const SplitArgs& sp, bool short_rows) {
     const bool vec4 = (L % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15u) == 0) &&
                       ((reinterpret_cast<uintptr_t>(Y) & 15u) == 0) && ((reinterpret_cast<uintptr_t>(T) & 15u) == 0);
     if (vec4) {
@@ -1531,13 +1613,13 @@ hipError_t launch_gemm(const KView& k, const float* X, float* Y, const float* T,
         if (L > 32) tw = pick_wide_tile(L, k.m, X, 128u);
         tw = (uint32_t)env_int("CER_GEMM_TILE", (int)tw);
         switch (tw) {
-            case 4: return launch_gemm_vp<IdxT, 4, 1>(k, X, Y, T, L, stream);
-            case 8: return launch_gemm_vp<IdxT, 4, 2>(k, X, Y, T, L, stream);
-            case 16: return launch_gemm_vp<IdxT, 4, 4>(k, X, Y, T, L, stream);
-            case 32: return launch_gemm_vp<IdxT, 4, 8>(k, X, Y, T, L, stream, short_rows);
-            case 64: return launch_gemm_vp<IdxT, 4, 16>(k, X, Y, T, L, stream);
-            case 128: return launch_gemm_vp<IdxT, 4, 32>(k, X, Y, T, L, stream);
-            case 256: return launch_gemm_vp<IdxT, 4, 64>(k, X, Y, T, L, stream);
+            case 4: return launch_gemm_vp<IdxT, 4, 1>(k, X, Y, T, L, stream, sp);
+            case 8: return launch_gemm_vp<IdxT, 4, 2>(k, X, Y, T, L, stream, sp);
+            case 16: return launch_gemm_vp<IdxT, 4, 4>(k, X, Y, T, L, stream, sp);
+            case 32: return launch_gemm_vp<IdxT, 4, 8>(k, X, Y, T, L, stream, sp, short_rows);
+            case 64: return launch_gemm_vp<IdxT, 4, 16>(k, X, Y, T, L, stream, sp);
+            case 128: return launch_gemm_vp<IdxT, 4, 32>(k, X, Y, T, L, stream, sp);
+            case 256: return launch_gemm_vp<IdxT, 4, 64>(k, X, Y, T, L, stream, sp);
             default: return hipErrorInvalidValue;
         }
     }
@@ -1546,21 +1628,21 @@ hipError_t launch_gemm(const KView& k, const float* X, float* Y, const float* T,
         uint32_t rtw = std::max<uint32_t>(std::min<uint32_t>(pow2_ceil(L), 32u), 8u);
         if (L > 32) rtw = pick_wide_tile(L, k.m, X, 128u);
         switch (rtw) {
-            case 8: return launch_gemm_ragged<IdxT, 2>(k, X, Y, T, L, stream);
-            case 16: return launch_gemm_ragged<IdxT, 4>(k, X, Y, T, L, stream);
-            case 32: return launch_gemm_ragged<IdxT, 8>(k, X, Y, T, L, stream, short_rows);
-            case 64: return launch_gemm_ragged<IdxT, 16>(k, X, Y, T, L, stream);
-            default: return launch_gemm_ragged<IdxT, 32>(k, X, Y, T, L, stream);
+            case 8: return launch_gemm_ragged<IdxT, 2>(k, X, Y, T, L, stream, sp);
+            case 16: return launch_gemm_ragged<IdxT, 4>(k, X, Y, T, L, stream, sp);
+            case 32: return launch_gemm_ragged<IdxT, 8>(k, X, Y, T, L, stream, sp, short_rows);
+            case 64: return launch_gemm_ragged<IdxT, 16>(k, X, Y, T, L, stream, sp);
+            default: return launch_gemm_ragged<IdxT, 32>(k, X, Y, T, L, stream, sp);
         }
     }
     const uint32_t tw = std::min<uint32_t>(pow2_ceil(L), 64u);
     switch (tw) {
-        case 1: case 2: return launch_gemm_vp<IdxT, 1, 2>(k, X, Y, T, L, stream);
-        case 4: return launch_gemm_vp<IdxT, 1, 4>(k, X, Y, T, L, stream);
-        case 8: return launch_gemm_vp<IdxT, 1, 8>(k, X, Y, T, L, stream);
-        case 16: return launch_gemm_vp<IdxT, 1, 16>(k, X, Y, T, L, stream);
-        case 32: return launch_gemm_vp<IdxT, 1, 32>(k, X, Y, T, L, stream);
-        default: return launch_gemm_vp<IdxT, 1, 64>(k, X, Y, T, L, stream);
+        case 1: case 2: return launch_gemm_vp<IdxT, 1, 2>(k, X, Y, T, L, stream, sp);
+        case 4: return launch_gemm_vp<IdxT, 1, 4>(k, X, Y, T, L, stream, sp);
+        case 8: return launch_gemm_vp<IdxT, 1, 8>(k, X, Y, T, L, stream, sp);
+        case 16: return launch_gemm_vp<IdxT, 1, 16>(k, X, Y, T, L, stream, sp);
+        case 32: return launch_gemm_vp<IdxT, 1, 32>(k, X, Y, T, L, stream, sp);
+        default: return launch_gemm_vp<IdxT, 1, 64>(k, X, Y, T, L, stream, sp);
     }
 }
 
@@ -1818,10 +1900,19 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
             // CER_GEMM_SHORT: 0 = never the 512-position chunks, 1 = always (32-column tiles), unset = by the average row
             const int sm = env_int("CER_GEMM_SHORT", -1);
             const bool short_rows = sm == 1 || (sm != 0 && d.nnz <= d.m * 384);
+            SplitArgs sp;  // CER_GEMM_SPLIT=0: long rows stay whole
+            if (d.n_split_parts > 0 && env_int("CER_GEMM_SPLIT", 1) != 0) {
+                sp.parts = static_cast<const uint4*>(d.split_parts);
+                sp.rows = static_cast<const uint4*>(d.split_rows);
+                sp.nparts = d.n_split_parts;
+                sp.nrows = d.n_split_rows;
+                sp.len = d.split_len;
+                sp.min = d.split_min;
+            }
             switch (d.colI_bits) {
-                case 8: e = launch_gemm<uint8_t>(k, X, Y, T, L, stream, short_rows); break;
-                case 16: e = launch_gemm<uint16_t>(k, X, Y, T, L, stream, short_rows); break;
-                default: e = launch_gemm<uint32_t>(k, X, Y, T, L, stream, short_rows); break;
+                case 8: e = launch_gemm<uint8_t>(k, X, Y, T, L, stream, sp, short_rows); break;
+                case 16: e = launch_gemm<uint16_t>(k, X, Y, T, L, stream, sp, short_rows); break;
+                default: e = launch_gemm<uint32_t>(k, X, Y, T, L, stream, sp, short_rows); break;
             }
         }
     }
