@@ -1,7 +1,7 @@
 """Rows much longer than the average row (pruned layers have them; matrices of independent elements do not).
 
 The default batched kernel serves such rows in parts (the row's own work item takes the first part, every
-further part is a work item of its own, a second kernel adds the parts' sums to Y).  Checked here against the
+further part is a work item of its own, a second kernel adds the parts' sums to Y); batch 1 keeps them whole.  Checked here against the
 oracle element by element, for both formats, aligned and ragged batch widths, few and many groups per row, a
 non-zero most frequent value, and against the same product with the rows left whole."""
 import os
@@ -53,7 +53,7 @@ def test_long_rows_in_parts(K, dominant):
         # average row about 700 indexed elements -> parts of 2048; rows of 12000, 10800, 6600, 4320 elements
         # -> 5 + 5 + 3 + 2 further parts
         assert B.cer_long_row_parts(h) == 15, f"{fmt}: {B.cer_long_row_parts(h)} parts"
-        for L in (2, 7, 32, 33, 64, 100):
+        for L in (1, 2, 7, 32, 33, 64, 100):
             rng = np.random.default_rng(100 + L)
             X = rng.standard_normal((n, L)).astype(np.float32)
             want = oracle.dot_dense(W, X, threads=8)
