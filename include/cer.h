@@ -201,10 +201,11 @@ int cer_clone_device(const cer_handle_t* h, cer_handle_t** out);
  * width + uint32 OmegaPtr and rowPtr + OmegaI + Omega); 0 for a host-only handle. */
 int64_t cer_device_bytes(const cer_handle_t* h);
 
-/* When a matrix has rows much longer than its average row (one of more than 3 P indexed elements,
- * P = 1.5 x the average rounded up to a multiple of 2048), its rows of more than 2 P elements are
- * served in parts of P elements by the batched product, so that one long row does not outlast
- * the rest of the launch; such a product uses a
+/* Matrices with rows of unequal length (longest row above twice the average and at least 2048
+ * indexed elements): the batched product takes the rows in descending order of length.  When a
+ * row holds more than 3 P indexed elements, P = 1.5 x the average rounded up to a multiple of
+ * 2048, the rows of more than 2 P elements are served in parts of P elements, so that one long
+ * row does not outlast the rest of the launch; such a product uses a
  * stream-ordered temporary of batch floats per part.  Returns the number of parts beyond the
  * rows' first ones (0: no row is split; also for host-only handles and for handles made by the
  * device-side encoder, whose rows stay whole). */

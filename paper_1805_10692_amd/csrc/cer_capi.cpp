@@ -1,4 +1,5 @@
 // extern "C" boundary of the library: argument checks, handle lifetime, device upload.
+#include <algorithm>
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -161,56 +162,70 @@ int cer::ensure_host_arrays(const cer_matrix* h) {
 
 namespace {
 
-// Rows much longer than the average row would keep one wave busy long after the rest of a batched product is
-// done.  When some row holds more than 3 P positions, P = 1.5 x the average row rounded up to a multiple of 2048,
-// the rows of more than 2 P positions are served in parts of P positions: the table lists every part but a row's first.  Matrices of rows of
-// similar length (all of the paper's layer shapes with independent elements) have no such row and no table.
+// Rows of unequal length (pruned layers; matrices of independent elements have none).  One wave serves one row per
+// batch tile and a workgroup holds its resources until its longest row is done, so the batched product
+//  - takes the rows in descending order of length when the longest row holds more than twice the average (and at
+//    least 2048 positions): the four rows of a workgroup are then about equally long and the long rows start first;
+//  - serves rows in parts when one of them would outlast the launch: if some row holds more than 3 P positions, P =
+//    1.5 x the average row rounded up to a multiple of 2048, the rows of more than 2 P positions are split into parts
+//    of P positions (the table lists every part but a row's first; the second kernel and the temporary that the parts
+//    need cost about 6 us per product, hence the 3 P).
+// Device table: [order: m x uint32][parts: {row, first position, end position, 0}][rows: {row, first part, parts, 0}].
 int upload_split_table(cer_matrix* h) {
     const cer::HostMatrix& A = *h->host;
     if (A.m <= 0 || A.nnz <= 0) return CER_OK;
-    const uint64_t mean = (uint64_t)(A.nnz / A.m);
-    const uint64_t len = ((std::max<uint64_t>(mean + mean / 2, 2048) + 2047) / 2048) * 2048;
-    if (2 * len >= (uint64_t)A.n || len > 0x3FFFFFFFull) return CER_OK;  // no row can be longer than n
-    // the second kernel and the temporary cost about 6 us per product: only when some row would keep its wave busy
-    // for long, i.e. holds more than 3 P positions
+    std::vector<uint64_t> start((size_t)A.m + 1);
+    for (int64_t r = 0; r <= A.m; ++r) start[(size_t)r] = A.omegaPtr.at((int64_t)A.rowPtr.at(r));
     uint64_t longest = 0;
-    for (int64_t r = 0; r < A.m; ++r)
-        longest = std::max<uint64_t>(longest, A.omegaPtr.at((int64_t)A.rowPtr.at(r + 1)) - A.omegaPtr.at((int64_t)A.rowPtr.at(r)));
-    if (longest <= 3 * len) return CER_OK;
+    for (int64_t r = 0; r < A.m; ++r) longest = std::max(longest, start[(size_t)r + 1] - start[(size_t)r]);
+    const uint64_t mean = (uint64_t)(A.nnz / A.m);
+    if (longest < 2048 || longest <= 2 * mean) return CER_OK;
+
+    std::vector<uint32_t> order((size_t)A.m);
+    for (int64_t r = 0; r < A.m; ++r) order[(size_t)r] = (uint32_t)r;
+    std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
+        return start[(size_t)a + 1] - start[a] > start[(size_t)b + 1] - start[b];
+    });
+
     std::vector<uint32_t> parts, rows;
-    for (int64_t r = 0; r < A.m; ++r) {
-        const uint64_t rs = A.omegaPtr.at((int64_t)A.rowPtr.at(r)), re = A.omegaPtr.at((int64_t)A.rowPtr.at(r + 1));
-        if (re - rs <= 2 * len) continue;
-        const uint32_t first = (uint32_t)(parts.size() / 4);
-        for (uint64_t b = rs + len; b < re; b += len) {
-            parts.push_back((uint32_t)r);
-            parts.push_back((uint32_t)b);
-            parts.push_back((uint32_t)std::min(re, b + len));
-            parts.push_back(0u);
+    const uint64_t len = ((std::max<uint64_t>(mean + mean / 2, 2048) + 2047) / 2048) * 2048;
+    if (longest > 3 * len && len <= 0x3FFFFFFFull) {
+        for (int64_t r = 0; r < A.m; ++r) {
+            const uint64_t rs = start[(size_t)r], re = start[(size_t)r + 1];
+            if (re - rs <= 2 * len) continue;
+            const uint32_t first = (uint32_t)(parts.size() / 4);
+            for (uint64_t b = rs + len; b < re; b += len) {
+                parts.push_back((uint32_t)r);
+                parts.push_back((uint32_t)b);
+                parts.push_back((uint32_t)std::min(re, b + len));
+                parts.push_back(0u);
+            }
+            rows.push_back((uint32_t)r);
+            rows.push_back(first);
+            rows.push_back((uint32_t)(parts.size() / 4) - first);
+            rows.push_back(0u);
         }
-        rows.push_back((uint32_t)r);
-        rows.push_back(first);
-        rows.push_back((uint32_t)(parts.size() / 4) - first);
-        rows.push_back(0u);
     }
-    if (rows.empty()) return CER_OK;
-    const size_t part_bytes = parts.size() * 4, row_bytes = rows.size() * 4;
+    const size_t order_bytes = (order.size() * 4 + 15) & ~(size_t)15, part_bytes = parts.size() * 4, row_bytes = rows.size() * 4;
     void* base = nullptr;
-    hipError_t e = hipMalloc(&base, part_bytes + row_bytes);
+    hipError_t e = hipMalloc(&base, order_bytes + part_bytes + row_bytes + 16);
     if (e != hipSuccess) return hip_fail(e);
-    e = hipMemcpy(base, parts.data(), part_bytes, hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(static_cast<unsigned char*>(base) + part_bytes, rows.data(), row_bytes, hipMemcpyHostToDevice);
+    auto* b8 = static_cast<unsigned char*>(base);
+    e = hipMemcpy(b8, order.data(), order.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess && part_bytes) e = hipMemcpy(b8 + order_bytes, parts.data(), part_bytes, hipMemcpyHostToDevice);
+    if (e == hipSuccess && row_bytes) e = hipMemcpy(b8 + order_bytes + part_bytes, rows.data(), row_bytes, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
         (void)hipFree(base);
         return hip_fail(e);
     }
     h->d_split = base;
-    h->view.split_parts = base;
-    h->view.split_rows = static_cast<unsigned char*>(base) + part_bytes;
+    h->view.row_order = base;
+    h->view.split_parts = b8 + order_bytes;
+    h->view.split_rows = b8 + order_bytes + part_bytes;
     h->view.n_split_parts = (uint32_t)(parts.size() / 4);
     h->view.n_split_rows = (uint32_t)(rows.size() / 4);
     h->view.split_len = (uint32_t)len;
-    h->view.split_min = (uint32_t)(2 * len);
+    h->view.split_min = parts.empty() ? 0xFFFFFFFFu : (uint32_t)(2 * len);
     return CER_OK;
 }
 

@@ -59,9 +59,11 @@ struct DeviceView {
     int64_t nnz = 0;
     int64_t nonempty_groups = 0;
     float omega0 = 0.f;
-    // Rows much longer than the average, served in parts by the default batched kernel (none: n_split_parts = 0).
-    // split_parts[i] = {row, first position, end position, 0} for every part but a row's first;
+    // Matrices with rows of unequal length (null / 0 otherwise), for the default batched kernel:
+    // row_order[i] = the row served i-th (descending length);
+    // split_parts[i] = {row, first position, end position, 0} for every part of a long row but its first;
     // split_rows[j] = {row, its first entry in split_parts, its number of entries, 0}.
+    const void* row_order = nullptr;
     const void* split_parts = nullptr;
     const void* split_rows = nullptr;
     uint32_t n_split_parts = 0, n_split_rows = 0;
@@ -124,7 +126,7 @@ struct cer_matrix {
     std::shared_ptr<const cer::HostMatrix> host;
     int device = -1;          // -1: host-only handle
     void* d_base = nullptr;   // the device allocation of the format arrays
-    void* d_split = nullptr;  // table of the long rows' parts (a second, small allocation; null: no row is split)
+    void* d_split = nullptr;  // row order and parts of long rows (a second, small allocation; null: rows of similar length)
     cer::DeviceLayout layout; // where the arrays sit inside it
     size_t d_bytes = 0;       // its size
     int64_t stream_bytes = 0; // bytes of format arrays a product reads

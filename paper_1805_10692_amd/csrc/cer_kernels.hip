@@ -62,17 +62,20 @@ struct KView {
     float omega0;
 };
 
-// Rows much longer than the matrix's average are served in parts by the default batched kernel, so that one wave
-// does not outlast the whole launch: the row's own work item takes its first `len` positions, every further part
-// {row, first position, end position} is a work item of its own whose sums go to out[part][batch column] and are
-// added to Y by a second kernel.  nparts == 0: no row is split.
+// Matrices with rows of unequal length, default batched kernel (kSplit instantiation).  The rows are taken in
+// descending order of length (order[i] = the row served i-th), so that the four rows of a workgroup are about
+// equally long and the long rows start first.  Rows much longer than the average are served in parts, so that one
+// wave does not outlast the whole launch: the row's own work item takes its first `len` positions, every further
+// part {row, first position, end position} is a work item of its own (they come first in the grid) whose sums go
+// to out[part][batch column] and are added to Y by a second kernel.  nparts == 0: no row is split.
 struct SplitArgs {
+    const uint32_t* order = nullptr;
     const uint4* parts = nullptr;
     float* out = nullptr;
     uint32_t nparts = 0;
     uint32_t len = 0;          // positions per part
     uint32_t min = 0;          // rows with more positions than this are split
-    uint32_t base_blocks = 0;  // workgroups of the ordinary work list; the parts follow
+    uint32_t part_blocks = 0;  // workgroups at the front of the grid that serve parts (a multiple of 8)
     const uint4* rows = nullptr;  // host side only: {row, first part, number of parts} per split row
     uint32_t nrows = 0;
 };
@@ -740,9 +743,9 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const flo
     const uint32_t wave = uniform(threadIdx.x >> 6);
     uint32_t tile, r;
     uint32_t part = 0, part_begin = 0, part_end = 0;
-    const bool is_part = kSplit && blockIdx.x >= sp.base_blocks;  // a further part of a long row
+    const bool is_part = kSplit && blockIdx.x < sp.part_blocks;  // a further part of a long row
     if (is_part) {
-        const uint32_t e = (blockIdx.x - sp.base_blocks) * 4u + wave;  // tile-major over (tile, part)
+        const uint32_t e = blockIdx.x * 4u + wave;  // tile-major over (tile, part)
         if (e >= ntiles * sp.nparts) return;
         tile = e / sp.nparts;
         part = e - tile * sp.nparts;
@@ -751,13 +754,40 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const flo
         part_begin = uniform(d.y);
         part_end = uniform(d.z);
     } else {
-        const uint32_t xcd = blockIdx.x & 7u, q = blockIdx.x >> 3;
+        const uint32_t b = kSplit ? blockIdx.x - sp.part_blocks : blockIdx.x;  // part_blocks is a multiple of 8
+        const uint32_t xcd = b & 7u, q = b >> 3;
         const uint32_t nitems = ntiles * rowblocks;
         const uint32_t item = xcd * items_per_xcd + q;
         if (q >= items_per_xcd || item >= nitems) return;
         tile = item / rowblocks;
-        r = (item - tile * rowblocks) * 4u + wave;
-        if (r >= v.m) return;
+        const uint32_t rb = item - tile * rowblocks;
+        if (kSplit) {
+            // Rows by descending length.  S XCDs share a batch tile, each walking a contiguous range of rb: deal the
+            // length ranks round-robin to those ranges (range j takes ranks j, j + S, ...), so that every XCD gets
+            // rows of every length and meets them longest first.
+            const uint32_t S = ntiles >= 8u ? 1u : 8u / ntiles;
+            const uint32_t q0 = rowblocks / S, rem = rowblocks - q0 * S;
+            uint32_t rank_block = rb;
+            if (S > 1u && q0 > 0u) {
+                uint32_t i, j;
+                if (rb < rem * (q0 + 1u)) {
+                    j = rb / (q0 + 1u);
+                    i = rb - j * (q0 + 1u);
+                } else {
+                    const uint32_t rb2 = rb - rem * (q0 + 1u);
+                    j = rb2 / q0;
+                    i = rb2 - j * q0;
+                    j += rem;
+                }
+                rank_block = i * S + j;
+            }
+            const uint32_t rank = rank_block * 4u + wave;
+            if (rank >= v.m) return;
+            r = uniform(sp.order[rank]);
+        } else {
+            r = rb * 4u + wave;
+            if (r >= v.m) return;
+        }
     }
 
     const uint32_t sub = lane / P;
@@ -1493,26 +1523,34 @@ hipError_t launch_gemv_expand(const KView& k, const GemvExpandPlan& p, const flo
 // The kernel that expands the group values per position is the default: measured on MI355X it beats the cursor
 // kernel on every workload (1.05 - 1.2 x on the layer shapes, up to 2 x on rows of many short groups).
 // CER_GEMM_EXPAND=0 selects the cursor kernel.
-// The default kernel on a matrix with split rows: the ordinary work list, then one wave per (batch tile, further
-// part) writing into a stream-ordered temporary, then the kernel that adds the parts' sums to Y.
+// The default kernel on a matrix with rows of unequal length: one wave per (batch tile, further part of a long row)
+// writing into a stream-ordered temporary, then the ordinary work list in descending order of row length, then the
+// kernel that adds the parts' sums to Y.
 template <typename Kern>
 hipError_t launch_expand_split(Kern kern, const KView& k, const float* X, float* Y, const float* T, uint32_t L,
                                uint32_t ntiles, uint32_t rowblocks, uint32_t ipx, SplitArgs sp, hipStream_t stream) {
-    const uint64_t blocks = (uint64_t)ipx * 8 + ((uint64_t)ntiles * sp.nparts + 3) / 4;
+    const uint64_t part_blocks = ((((uint64_t)ntiles * sp.nparts + 3) / 4) + 7) & ~(uint64_t)7;
+    const uint64_t blocks = (uint64_t)ipx * 8 + part_blocks;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     float* out = nullptr;
-    hipError_t e = (hipError_t)temp_alloc(reinterpret_cast<void**>(&out), (size_t)sp.nparts * L * sizeof(float), stream);
-    if (e != hipSuccess) return e;
+    hipError_t e = hipSuccess;
+    if (sp.nparts > 0) {
+        e = (hipError_t)temp_alloc(reinterpret_cast<void**>(&out), (size_t)sp.nparts * L * sizeof(float), stream);
+        if (e != hipSuccess) return e;
+    }
     sp.out = out;
-    sp.base_blocks = ipx * 8;
+    sp.part_blocks = (uint32_t)part_blocks;
     hipLaunchKernelGGL(kern, dim3((uint32_t)blocks), dim3(256), 0, stream, k, X, Y, T, L, ntiles, rowblocks, ipx, sp);
     e = hipGetLastError();
-    if (e == hipSuccess) {
-        hipLaunchKernelGGL(split_add_kernel, dim3(sp.nrows), dim3(256), 0, stream, sp.rows, out, Y, L);
-        e = hipGetLastError();
+    if (sp.nparts > 0) {
+        if (e == hipSuccess) {
+            hipLaunchKernelGGL(split_add_kernel, dim3(sp.nrows), dim3(256), 0, stream, sp.rows, out, Y, L);
+            e = hipGetLastError();
+        }
+        const hipError_t f = (hipError_t)temp_free(out, stream);
+        if (e == hipSuccess) e = f;
     }
-    const hipError_t f = (hipError_t)temp_free(out, stream);
-    return e == hipSuccess ? f : e;
+    return e;
 }
 
 template <typename IdxT, int V, int P>
@@ -1525,7 +1563,7 @@ hipError_t launch_gemm_vp(const KView& k, const float* X, float* Y, const float*
     if (nitems > 0x7FFFFFFFull / 8) return hipErrorInvalidValue;
     const uint32_t ipx = (uint32_t)((nitems + 7) / 8);
     if (env_int("CER_GEMM_EXPAND", 1) != 0) {
-        if (sp.nparts > 0)
+        if (sp.order)
             return launch_expand_split(cer_gemm_expand_kernel<IdxT, V, P, false, kExpChunkLong, true>, k, X, Y, T, L, ntiles,
                                        rowblocks, ipx, sp, stream);
         if (TW == 32 && V == 4 && short_rows)
@@ -1550,7 +1588,7 @@ hipError_t launch_gemm_ragged(const KView& k, const float* X, float* Y, const fl
     const uint64_t nitems = (uint64_t)ntiles * rowblocks;
     if (nitems > 0x7FFFFFFFull / 8 || L < 4) return hipErrorInvalidValue;
     const uint32_t ipx = (uint32_t)((nitems + 7) / 8);
-    if (sp.nparts > 0)
+    if (sp.order)
         return launch_expand_split(cer_gemm_expand_kernel<IdxT, 4, P, true, kExpChunkLong, true>, k, X, Y, T, L, ntiles,
                                    rowblocks, ipx, sp, stream);
     if (P == 8 && short_rows)
@@ -1900,8 +1938,9 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
             // CER_GEMM_SHORT: 0 = never the 512-position chunks, 1 = always (32-column tiles), unset = by the average row
             const int sm = env_int("CER_GEMM_SHORT", -1);
             const bool short_rows = sm == 1 || (sm != 0 && d.nnz <= d.m * 384);
-            SplitArgs sp;  // CER_GEMM_SPLIT=0: long rows stay whole
-            if (d.n_split_parts > 0 && env_int("CER_GEMM_SPLIT", 1) != 0) {
+            SplitArgs sp;  // CER_GEMM_SPLIT=0: rows in their own order, long rows whole
+            if (d.row_order && env_int("CER_GEMM_SPLIT", 1) != 0) {
+                sp.order = static_cast<const uint32_t*>(d.row_order);
                 sp.parts = static_cast<const uint4*>(d.split_parts);
                 sp.rows = static_cast<const uint4*>(d.split_rows);
                 sp.nparts = d.n_split_parts;

@@ -83,6 +83,40 @@ def test_long_rows_in_parts(K, dominant):
         B.cer_free(h)
 
 
+@pytest.mark.parametrize("m", [203, 64, 9])
+def test_rows_in_order_of_length_without_parts(m):
+    """Longest row 2400 indices against 280 on average: the batched kernel takes the rows in descending order of
+    length (no row is long enough to be split).  Row counts that are not multiples of 4 or of the 8 XCD ranges."""
+    dev = _gpu()
+    n = 4000
+    W, cb, _ = skewed_matrix(3 + m, m, n, 16, 0.0, [0.6, 0.6, 0.55, 0.3])
+    for fmt, enc, mm in (("cer", B.cer_encode, B.cer_matmul), ("cser", B.cser_encode, B.cser_matmul)):
+        h = enc(W, cb)
+        assert B.cer_long_row_parts(h) == 0
+        for L in (2, 8, 32, 33, 64, 100, 300):
+            X = np.random.default_rng(L).standard_normal((n, L)).astype(np.float32)
+            want = oracle.dot_dense(W, X, threads=8)
+            scale = oracle.abs_dot_dense(W, X, threads=8)
+            Xd = torch.from_numpy(X).to(dev)
+            results = {}
+            for split in ("1", "0"):
+                os.environ.update({"CER_GEMM_SPLIT": split, "CER_DENSIFY": "0", "CER_XTILE": "0"})
+                try:
+                    print(f"{fmt} m={m} L={L} split={split}", flush=True)
+                    Yd = torch.full((m, L), float("nan"), dtype=torch.float32, device=dev)
+                    mm(h, Xd, Yd, L)
+                    torch.cuda.synchronize()
+                finally:
+                    for k in ("CER_GEMM_SPLIT", "CER_DENSIFY", "CER_XTILE"):
+                        os.environ.pop(k, None)
+                Y = Yd.cpu().numpy().astype(np.float64)
+                assert np.isfinite(Y).all(), f"{fmt} m={m} L={L} split={split}: unwritten output"
+                assert (np.abs(Y - want) <= TOL * scale).all(), f"{fmt} m={m} L={L} split={split}"
+                results[split] = Y
+            assert np.array_equal(results["1"], results["0"]), f"{fmt} m={m} L={L}: a row's arithmetic does not depend on the order"
+        B.cer_free(h)
+
+
 def test_layer_shapes_have_no_split_rows():
     """Matrices of independent elements (the benchmark's shapes) keep every row whole, so their products run the
     same kernels as before."""
