@@ -202,7 +202,8 @@ int cer_clone_device(const cer_handle_t* h, cer_handle_t** out);
 int64_t cer_device_bytes(const cer_handle_t* h);
 
 /* Matrices with rows of unequal length (longest row above twice the average and at least 2048
- * indexed elements): the batched product takes the rows in descending order of length.  When a
+ * indexed elements, average row at least 256 unless a row is split): the batched product takes
+ * the rows in descending order of length.  When a
  * row holds more than 3 P indexed elements, P = 1.5 x the average rounded up to a multiple of
  * 2048, the rows of more than 2 P elements are served in parts of P elements, so that one long
  * row does not outlast the rest of the launch; such a product uses a

@@ -1563,9 +1563,13 @@ hipError_t launch_gemm_vp(const KView& k, const float* X, float* Y, const float*
     if (nitems > 0x7FFFFFFFull / 8) return hipErrorInvalidValue;
     const uint32_t ipx = (uint32_t)((nitems + 7) / 8);
     if (env_int("CER_GEMM_EXPAND", 1) != 0) {
-        if (sp.order)
+        if (sp.order) {
+            if (TW == 32 && V == 4 && short_rows)
+                return launch_expand_split(cer_gemm_expand_kernel<IdxT, 4, 8, false, kExpChunkShort, true>, k, X, Y, T, L,
+                                           ntiles, rowblocks, ipx, sp, stream);
             return launch_expand_split(cer_gemm_expand_kernel<IdxT, V, P, false, kExpChunkLong, true>, k, X, Y, T, L, ntiles,
                                        rowblocks, ipx, sp, stream);
+        }
         if (TW == 32 && V == 4 && short_rows)
             hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, 8, false, kExpChunkShort>), dim3(ipx * 8), dim3(256), 0, stream,
                                k, X, Y, T, L, ntiles, rowblocks, ipx, SplitArgs{});
@@ -1588,9 +1592,13 @@ hipError_t launch_gemm_ragged(const KView& k, const float* X, float* Y, const fl
     const uint64_t nitems = (uint64_t)ntiles * rowblocks;
     if (nitems > 0x7FFFFFFFull / 8 || L < 4) return hipErrorInvalidValue;
     const uint32_t ipx = (uint32_t)((nitems + 7) / 8);
-    if (sp.order)
+    if (sp.order) {
+        if (P == 8 && short_rows)
+            return launch_expand_split(cer_gemm_expand_kernel<IdxT, 4, 8, true, kExpChunkShort, true>, k, X, Y, T, L, ntiles,
+                                       rowblocks, ipx, sp, stream);
         return launch_expand_split(cer_gemm_expand_kernel<IdxT, 4, P, true, kExpChunkLong, true>, k, X, Y, T, L, ntiles,
                                    rowblocks, ipx, sp, stream);
+    }
     if (P == 8 && short_rows)
         hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, 8, true, kExpChunkShort>), dim3(ipx * 8), dim3(256), 0, stream, k, X,
                            Y, T, L, ntiles, rowblocks, ipx, SplitArgs{});
