@@ -208,8 +208,7 @@ int64_t cer_device_bytes(const cer_handle_t* h);
  * 2048, the rows of more than 2 P elements are served in parts of P elements, so that one long
  * row does not outlast the rest of the launch; such a product uses a
  * stream-ordered temporary of batch floats per part.  Returns the number of parts beyond the
- * rows' first ones (0: no row is split; also for host-only handles and for handles made by the
- * device-side encoder, whose rows stay whole). */
+ * rows' first ones (0: no row is split; also for host-only handles). */
 int64_t cer_long_row_parts(const cer_handle_t* h);
 
 /* Frees host and device memory.  NULL is allowed. */

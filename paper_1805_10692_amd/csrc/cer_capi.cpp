@@ -162,6 +162,31 @@ int cer::ensure_host_arrays(const cer_matrix* h) {
 
 namespace {
 
+// The row schedule of a host-encoded handle, from its host arrays.
+int upload_split_table(cer_matrix* h) {
+    const cer::HostMatrix& A = *h->host;
+    if (A.m <= 0 || A.nnz <= 0) return CER_OK;
+    std::vector<uint64_t> start((size_t)A.m + 1);
+    for (int64_t r = 0; r <= A.m; ++r) start[(size_t)r] = A.omegaPtr.at((int64_t)A.rowPtr.at(r));
+    return cer::build_row_schedule(h, start);
+}
+
+}  // namespace
+
+namespace {
+// P: positions per part of a long row
+uint64_t part_length(uint64_t mean) { return ((std::max<uint64_t>(mean + mean / 2, 2048) + 2047) / 2048) * 2048; }
+}  // namespace
+
+bool cer::row_schedule_wanted(uint64_t nnz, uint64_t m, uint64_t longest) {
+    if (m == 0 || nnz == 0) return false;
+    const uint64_t mean = nnz / m;
+    if (longest < 2048 || longest <= 2 * mean) return false;
+    // rows of a few dozen indices are bound by their wave's start-up chain, to which the look-up of the row adds a
+    // step: 16384 x 4096 with 41 indices per row and three rows of about 3000 measured 8 % slower in order
+    return mean >= 256 || longest > 3 * part_length(mean);
+}
+
 // Rows of unequal length (pruned layers; matrices of independent elements have none).  One wave serves one row per
 // batch tile and a workgroup holds its resources until its longest row is done, so the batched product
 //  - takes the rows in descending order of length when the longest row holds more than twice the average (and at
@@ -172,19 +197,14 @@ namespace {
 //    of P positions (the table lists every part but a row's first; the second kernel and the temporary that the parts
 //    need cost about 6 us per product, hence the 3 P).
 // Device table: [order: m x uint32][parts: {row, first position, end position, 0}][rows: {row, first part, parts, 0}].
-int upload_split_table(cer_matrix* h) {
+int cer::build_row_schedule(cer_matrix* h, const std::vector<uint64_t>& start) {
     const cer::HostMatrix& A = *h->host;
-    if (A.m <= 0 || A.nnz <= 0) return CER_OK;
-    std::vector<uint64_t> start((size_t)A.m + 1);
-    for (int64_t r = 0; r <= A.m; ++r) start[(size_t)r] = A.omegaPtr.at((int64_t)A.rowPtr.at(r));
+    if (A.m <= 0 || A.nnz <= 0 || h->device < 0) return CER_OK;
     uint64_t longest = 0;
     for (int64_t r = 0; r < A.m; ++r) longest = std::max(longest, start[(size_t)r + 1] - start[(size_t)r]);
+    if (!row_schedule_wanted((uint64_t)A.nnz, (uint64_t)A.m, longest)) return CER_OK;
     const uint64_t mean = (uint64_t)(A.nnz / A.m);
-    if (longest < 2048 || longest <= 2 * mean) return CER_OK;
-    const uint64_t len = ((std::max<uint64_t>(mean + mean / 2, 2048) + 2047) / 2048) * 2048;
-    // rows of a few dozen indices are bound by their wave's start-up chain, to which the look-up of the row adds a
-    // step: 16384 x 4096 with 41 indices per row and three rows of about 3000 measured 8 % slower in order
-    if (mean < 256 && longest <= 3 * len) return CER_OK;
+    const uint64_t len = part_length(mean);
 
     std::vector<uint32_t> order((size_t)A.m);
     for (int64_t r = 0; r < A.m; ++r) order[(size_t)r] = (uint32_t)r;
@@ -232,6 +252,8 @@ int upload_split_table(cer_matrix* h) {
     h->view.split_min = parts.empty() ? 0xFFFFFFFFu : (uint32_t)(2 * len);
     return CER_OK;
 }
+
+namespace {
 
 // Copies the host arrays into one fresh device allocation (layout: cer::DeviceLayout).
 int upload(cer_matrix* h) {

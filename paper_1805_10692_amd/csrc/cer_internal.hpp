@@ -80,6 +80,12 @@ struct DeviceLayout {
     static DeviceLayout make(size_t colI_bytes, int64_t G, int64_t m, size_t omegaI_bytes, int32_t K);
 };
 
+// Row order and parts of long rows for the batched product (cer_capi.cpp): whether a matrix of m rows, nnz indexed
+// elements and the given longest row gets the table, and its construction from the rows' first colI positions
+// (m + 1 entries); a CER_* code.
+bool row_schedule_wanted(uint64_t nnz, uint64_t m, uint64_t longest);
+int build_row_schedule(cer_matrix* h, const std::vector<uint64_t>& start);
+
 // Host encoder (cer_host.cpp).  Returns a CER_* code.
 int encode_host(const float* W, int64_t m, int64_t n, const float* codebook, int32_t K, bool cser,
                 std::shared_ptr<HostMatrix>* out);

@@ -43,7 +43,7 @@ struct FrontState {
     uint32_t K;         // codebook positions in use (caller's K, or the quantizer's point count)
     uint32_t Kp;        // values that occur = length of Omega
     uint32_t max_row_groups;
-    uint32_t pad_;
+    uint32_t max_row_nnz;  // indexed elements of the longest row
     unsigned long long nnz, G, nonempty;
     unsigned long long hist[kCodes];   // occurrences by codebook position
     unsigned long long count[kCodes];  // occurrences by rank
@@ -363,18 +363,19 @@ __global__ __launch_bounds__(1024) void scan_rows_kernel(const uint32_t* __restr
                                                          uint32_t* __restrict__ rowPtr, uint32_t* __restrict__ rowOff,
                                                          FrontState* __restrict__ st) {
     __shared__ unsigned long long s_g[16], s_n[16], s_p[16];
-    __shared__ uint32_t s_mx[16];
+    __shared__ uint32_t s_mx[16], s_ml[16];
     __shared__ unsigned long long s_carry[2];
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     if (t == 0) s_carry[0] = s_carry[1] = 0;
     unsigned long long my_p = 0;
-    uint32_t my_mx = 0;
+    uint32_t my_mx = 0, my_ml = 0;
     __syncthreads();
     for (int64_t base = 0; base < m; base += 1024) {
         const int64_t r = base + t;
         const unsigned long long g = r < m ? rowG[r] : 0u, nn = r < m ? rowN[r] : 0u;
         my_p += r < m ? rowP[r] : 0u;
         my_mx = max(my_mx, (uint32_t)g);
+        my_ml = max(my_ml, (uint32_t)nn);
         unsigned long long ig = g, in_ = nn;  // inclusive scans inside the wave
 #pragma unroll
         for (int off = 1; off < kWave; off <<= 1) {
@@ -409,19 +410,23 @@ __global__ __launch_bounds__(1024) void scan_rows_kernel(const uint32_t* __restr
     for (int off = 32; off > 0; off >>= 1) {
         my_p += __shfl_xor(my_p, off, kWave);
         my_mx = max(my_mx, (uint32_t)__shfl_xor((int)my_mx, off, kWave));
+        my_ml = max(my_ml, (uint32_t)__shfl_xor((int)my_ml, off, kWave));
     }
     if (lane == 0) {
         s_p[wave] = my_p;
         s_mx[wave] = my_mx;
+        s_ml[wave] = my_ml;
     }
     __syncthreads();
     if (t == 0) {
         unsigned long long p = 0;
-        uint32_t mx = 0;
+        uint32_t mx = 0, ml = 0;
         for (int w = 0; w < 16; ++w) {
             p += s_p[w];
             mx = max(mx, s_mx[w]);
+            ml = max(ml, s_ml[w]);
         }
+        st->max_row_nnz = ml;
         const unsigned long long G = s_carry[0], nnz = s_carry[1];
         st->G = G;
         st->nnz = nnz;
@@ -1012,6 +1017,23 @@ int encode_device(const float* W, int64_t m, int64_t n, const float* codebook, i
     auto* hnd = new cer_matrix();
     hnd->host = std::move(A);
     bind_device(hnd, dev, base, l);
+    // rows of unequal length: the batched product wants them ordered (and the longest in parts); the row starts
+    // come back from the device only when the longest row says that the table will be built
+    if (row_schedule_wanted((uint64_t)hnd->host->nnz, (uint64_t)m, (uint64_t)h.max_row_nnz)) {
+        std::vector<uint32_t> info((size_t)(m + 1) * 2);
+        e = hipMemcpy(info.data(), b + l.off_ri, info.size() * 4, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) {
+            cer_free(hnd);
+            return record_hip_error((int)e);
+        }
+        std::vector<uint64_t> start((size_t)m + 1);
+        for (int64_t r = 0; r <= m; ++r) start[(size_t)r] = info[(size_t)r * 2 + 1];
+        const int rc = build_row_schedule(hnd, start);
+        if (rc != CER_OK) {
+            cer_free(hnd);
+            return rc;
+        }
+    }
     *out = hnd;
     return CER_OK;
 }

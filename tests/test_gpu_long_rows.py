@@ -119,6 +119,40 @@ def test_rows_in_order_of_length_without_parts(m):
         B.cer_free(h)
 
 
+@pytest.mark.parametrize("fmt", ["cer", "cser"])
+def test_device_encoder_builds_the_same_schedule(fmt):
+    """A handle made by the device-side encoder serves long rows in the same parts as the host encoder's, and the
+    products of the two handles are the same numbers."""
+    dev = _gpu()
+    m, n = 96, 12000
+    W, cb, _ = skewed_matrix(77, m, n, 16, 0.0, [1.0, 0.9, 0.55, 0.36])
+    enc = B.cer_encode if fmt == "cer" else B.cser_encode
+    mm = B.cer_matmul if fmt == "cer" else B.cser_matmul
+    hh = enc(W, cb)
+    hd = B.cer_encode_device(torch.from_numpy(W).to(dev), m, n, cb, fmt)
+    assert B.cer_long_row_parts(hh) == 15
+    assert B.cer_long_row_parts(hd) == 15
+    for L in (8, 64, 100):
+        X = np.random.default_rng(L).standard_normal((n, L)).astype(np.float32)
+        Xd = torch.from_numpy(X).to(dev)
+        Yh = torch.full((m, L), float("nan"), dtype=torch.float32, device=dev)
+        Yd = torch.full((m, L), float("nan"), dtype=torch.float32, device=dev)
+        os.environ.update({"CER_DENSIFY": "0", "CER_XTILE": "0"})
+        try:
+            mm(hh, Xd, Yh, L)
+            mm(hd, Xd, Yd, L)
+            torch.cuda.synchronize()
+        finally:
+            os.environ.pop("CER_DENSIFY", None)
+            os.environ.pop("CER_XTILE", None)
+        want = oracle.dot_dense(W, X, threads=8)
+        scale = oracle.abs_dot_dense(W, X, threads=8)
+        assert (np.abs(Yd.cpu().numpy().astype(np.float64) - want) <= TOL * scale).all(), f"{fmt} L={L}"
+        assert torch.equal(Yh, Yd), f"{fmt} L={L}"
+    B.cer_free(hh)
+    B.cer_free(hd)
+
+
 def test_layer_shapes_have_no_split_rows():
     """Matrices of independent elements (the benchmark's shapes) keep every row whole, so their products run the
     same kernels as before."""
