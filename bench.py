@@ -41,6 +41,9 @@ def make_workload(name: str):
     m = re.fullmatch(r"vgg_fc6_L(\d+)", name)
     if m:
         return wl.vgg_fc6(L=int(m.group(1)))
+    m = re.fullmatch(r"vgg_fc6_rows([0-9.]+)_L(\d+)", name)
+    if m:  # log-normal row lengths (standard deviation of the logarithm), otherwise the vgg_fc6 matrix
+        return wl.vgg_fc6_unequal_rows(L=int(m.group(2)), sigma=float(m.group(1)))
     m = re.fullmatch(r"alexnet_fc6_L(\d+)", name)
     if m:
         return wl.alexnet_fc6(L=int(m.group(1)))

@@ -145,6 +145,26 @@ def vgg_fc6(L: int = 1, scale: int = 1, seed: int = 2) -> Workload:
     return Workload(f"vgg_fc6_{m}x{n}_K16_p0.95_L{L}", W, cb, X, pmf, seed)
 
 
+def vgg_fc6_unequal_rows(L: int = 64, sigma: float = 1.0, scale: int = 1, seed: int = 7) -> Workload:
+    """The vgg_fc6 shape, values and number of indexed elements (5 % on average), but with log-normal row lengths
+    (standard deviation `sigma` of the logarithm, capped at a full row): a stand-in for pruned layers, whose rows
+    are not equally long.  Not one of the benchmark's configurations."""
+    cb = np.array([(j - 8) * 0.01 for j in range(16)], dtype=np.float64).astype(np.float32)
+    pmf = pmf_geometric(cb, dominant=8, p_dom=0.95, ratio=0.6)
+    m, n = _shrink(4096, scale, 3), _shrink(25088, scale, 5)
+    rng = np.random.Generator(np.random.PCG64(seed))
+    density = np.minimum(0.05 * np.exp(sigma * rng.standard_normal(m) - sigma * sigma / 2), 1.0)
+    others = np.array([j for j in range(16) if j != 8])
+    tail = pmf[others] / pmf[others].sum()
+    W = np.zeros((m, n), dtype=np.float32)
+    for r in range(m):
+        count = int(rng.binomial(n, density[r]))
+        cols = rng.choice(n, size=count, replace=False)
+        W[r, cols] = cb[others[rng.choice(len(others), size=count, p=tail)]]
+    X = sample_X(rng, n, L)
+    return Workload(f"vgg_fc6_unequal_rows_{m}x{n}_sigma{sigma}_L{L}", W, cb, X, pmf, seed)
+
+
 SWEEP_K = (2, 4, 16, 64, 256)
 SWEEP_P0 = (0.5, 0.7, 0.9, 0.99)
 
