@@ -517,12 +517,30 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
                 run.zero();
             }
             if (count > 0) {
-                for (; b0 < te; b0 += NP * kWave) {
-                    uint32_t ix[NP];
-                    const IdxT* p = colI + b0 + lane;
-#pragma unroll
-                    for (int s = 0; s < NP; ++s) ix[s] = (uint32_t)p[s * kWave];
-                    gemv_batch(ix, xsrc, b0, te, lane, cur, run, acc, ends, wts);
+                if (b0 < te) {
+                    // Two sets of index registers: the next batch is requested before the current one is summed, so
+                    // that a wave working alone on a long row (the others of its compute unit are done) does not
+                    // wait out the memory latency once per batch.  Past the row's end the current batch is requested
+                    // again (in bounds, unused) to keep the loads unconditional.
+                    uint32_t ixa[NP], ixb[NP];
+#define CER_REQUEST(ix, b)                                                     \
+    {                                                                          \
+        const IdxT* p_ = colI + (b) + lane;                                    \
+        _Pragma("unroll") for (int s = 0; s < NP; ++s) ix[s] = (uint32_t)p_[s * kWave]; \
+    }
+                    CER_REQUEST(ixa, b0)
+                    for (;;) {
+                        const uint32_t b1 = b0 + NP * kWave;
+                        CER_REQUEST(ixb, b1 < te ? b1 : b0)
+                        gemv_batch(ixa, xsrc, b0, te, lane, cur, run, acc, ends, wts);
+                        if (b1 >= te) break;
+                        const uint32_t b2 = b1 + NP * kWave;
+                        CER_REQUEST(ixa, b2 < te ? b2 : b1)
+                        gemv_batch(ixb, xsrc, b1, te, lane, cur, run, acc, ends, wts);
+                        if (b2 >= te) break;
+                        b0 = b2;
+                    }
+#undef CER_REQUEST
                 }
                 acc.fma(run, cur.w);
             }
