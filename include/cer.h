@@ -105,10 +105,10 @@ int cser_encode(const float* W_host, int64_t m, int64_t n, const float* codebook
  * Work is enqueued on `stream` and the call returns without synchronising.  The caller keeps
  * ownership of X and Y and must keep them alive until the stream has run the work.  When
  * Omega[0] != 0 and batch > 1 (or X does not fit in LDS) a stream-ordered temporary of batch floats
- * (plus partial sums) is allocated and released on `stream`; otherwise (and when cer_matmul_path
- * reports kernel 0 or 1) the call
- * only launches kernels and may be recorded into a HIP graph after one eager call on the device
- * (a batched product of a matrix with split rows, cer_long_row_parts > 0, allocates as well).
+ * (plus partial sums) is allocated and released on `stream`, and so is one for a batched product
+ * of a matrix with split rows (cer_long_row_parts > 0); otherwise (and when cer_matmul_path
+ * reports kernel 0 or 1) the call only launches kernels and may be recorded into a HIP graph
+ * after one eager call on the device.
  * fp32 arithmetic; the summation order differs from a sequential loop.  With Omega[0] != 0 the
  * rounding error is relative to sum|w||x| + |Omega[0]|.sum|x|: Appendix A-A1 adds that term and
  * subtracts it again inside the groups' weights.
@@ -203,12 +203,12 @@ int64_t cer_device_bytes(const cer_handle_t* h);
 
 /* Matrices with rows of unequal length (longest row above twice the average and at least 2048
  * indexed elements, average row at least 256 unless a row is split): the batched product takes
- * the rows in descending order of length.  When a
- * row holds more than 3 P indexed elements, P = 1.5 x the average rounded up to a multiple of
- * 2048, the rows of more than 2 P elements are served in parts of P elements, so that one long
- * row does not outlast the rest of the launch; such a product uses a
- * stream-ordered temporary of batch floats per part.  Returns the number of parts beyond the
- * rows' first ones (0: no row is split; also for host-only handles). */
+ * the rows in descending order of length.  When a row holds more than 3 P indexed elements,
+ * P = 1.5 x the average rounded up to a multiple of 2048, the rows of more than 2 P elements
+ * are served in parts of P elements, so that one long row does not outlast the rest of the
+ * launch; such a product uses a stream-ordered temporary of batch floats per part.  Returns
+ * the number of parts beyond the rows' first ones (0: no row is split; also for host-only
+ * handles). */
 int64_t cer_long_row_parts(const cer_handle_t* h);
 
 /* Frees host and device memory.  NULL is allowed. */
