@@ -191,8 +191,10 @@ __device__ __forceinline__ void ucursor_load(UCursor& c, const uint32_t* ends, c
     c.next = 0;
 }
 
+// kFew: the list (sentinels included) fits the 64 lanes, so the registers are never reloaded.
+template <bool kFew = false>
 __device__ __forceinline__ void ucursor_advance(UCursor& c, const uint32_t* ends, const float* wts, uint32_t lane) {
-    if (__builtin_expect(c.next == kWave, 0)) {
+    if (!kFew && __builtin_expect(c.next == kWave, 0)) {
         c.chunk += kWave;
         ucursor_load(c, ends, wts, lane);
     }
@@ -262,7 +264,7 @@ template <> struct Vec<4> {
 // One step: the wave instruction covered colI offsets [w0, w0 + WIN); this lane's input x belongs to
 // offset w0 + who (who = lane for batch 1, the lane's sub-group for a batch tile).  The current
 // group's end is never below w0; the sentinel end (2^32 - 1) is beyond every window.
-template <int WIN, int V>
+template <int WIN, int V, bool kFew = false>
 __device__ __forceinline__ void cer_step(const Vec<V>& x, uint32_t who, uint32_t w0, UCursor& c, Vec<V>& run,
                                          Vec<V>& acc, const uint32_t* ends, const float* wts, uint32_t lane) {
     if (__builtin_expect(c.end - w0 >= (uint32_t)WIN, 1)) {  // no boundary inside the window
@@ -272,12 +274,12 @@ __device__ __forceinline__ void cer_step(const Vec<V>& x, uint32_t who, uint32_t
     uint32_t lo = c.end - w0;  // the boundary, as a value of `who`
     run.add_if(who < lo, x);
     acc.fma(run, c.w);  // the one multiplication of this lane for the group that ends here
-    ucursor_advance(c, ends, wts, lane);
+    ucursor_advance<kFew>(c, ends, wts, lane);
     while (c.end - w0 < (uint32_t)WIN) {  // groups wholly inside the window: at most one element per lane
         const uint32_t hi = c.end - w0;
         acc.fma_if(who >= lo && who < hi, x, c.w);
         lo = hi;
-        ucursor_advance(c, ends, wts, lane);
+        ucursor_advance<kFew>(c, ends, wts, lane);
     }
     run.set_if(who >= lo, x);
 }
@@ -320,6 +322,7 @@ constexpr int kGemvSteps = 24;  // index loads in flight per lane: one batch cov
 // later steps are still on their way from HBM: gathers run eight steps ahead of the sums, and
 // scheduling barriers keep the compiler from hoisting every gather (and with it the wait for the
 // last index) above the first sum.
+template <bool kFew>
 __device__ __forceinline__ void gemv_batch(const uint32_t (&ix)[kGemvSteps], const float* xsrc, uint32_t b0, uint32_t te,
                                            uint32_t lane, UCursor& cur, Vec<1>& run, Vec<1>& acc, const uint32_t* ends,
                                            const float* wts) {
@@ -328,7 +331,7 @@ __device__ __forceinline__ void gemv_batch(const uint32_t (&ix)[kGemvSteps], con
 #define CER_GATHER4(S)                                                             \
     xv[S].a = xsrc[ix[S]]; xv[(S) + 1].a = xsrc[ix[(S) + 1]];                      \
     xv[(S) + 2].a = xsrc[ix[(S) + 2]]; xv[(S) + 3].a = xsrc[ix[(S) + 3]];
-#define CER_STEP(S) cer_step<kWave, 1>(xv[S], lane, b0 + (S) * kWave, cur, run, acc, ends, wts, lane)
+#define CER_STEP(S) cer_step<kWave, 1, kFew>(xv[S], lane, b0 + (S) * kWave, cur, run, acc, ends, wts, lane)
     // four steps at a time: one boundary test when the next 256 positions hold none
 #define CER_STEP4(S)                                                               \
     if (cur.end - (b0 + (S) * kWave) >= 4u * kWave) {                              \
@@ -355,7 +358,9 @@ __device__ __forceinline__ void gemv_batch(const uint32_t (&ix)[kGemvSteps], con
 #undef CER_STEP
 }
 
-template <typename IdxT, bool kXinLds, bool kVec4, bool kCser>
+// kFew: no row has more than 62 non-empty groups (the launcher knows the longest list), so a row's list and its
+// two sentinels fit the cursor's 64 lanes and the cursor never reloads them.
+template <typename IdxT, bool kXinLds, bool kVec4, bool kCser, bool kFew>
 __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
                                                         const float* __restrict__ T, uint32_t rows_per_block,
                                                         int omega_in_lds, uint32_t gcap) {
@@ -486,7 +491,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
     if (r < row_end && count0 > 0) {
         wave_lds_sync();
         ucursor_start(cur, ends, wts, count0, lane);
-        gemv_batch(idx0, xsrc, rs, re, lane, cur, run, acc, ends, wts);
+        gemv_batch<kFew>(idx0, xsrc, rs, re, lane, cur, run, acc, ends, wts);
         resume = true;
     }
 
@@ -532,11 +537,11 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
                     for (;;) {
                         const uint32_t b1 = b0 + NP * kWave;
                         CER_REQUEST(ixb, b1 < te ? b1 : b0)
-                        gemv_batch(ixa, xsrc, b0, te, lane, cur, run, acc, ends, wts);
+                        gemv_batch<kFew>(ixa, xsrc, b0, te, lane, cur, run, acc, ends, wts);
                         if (b1 >= te) break;
                         const uint32_t b2 = b1 + NP * kWave;
                         CER_REQUEST(ixa, b2 < te ? b2 : b1)
-                        gemv_batch(ixb, xsrc, b1, te, lane, cur, run, acc, ends, wts);
+                        gemv_batch<kFew>(ixb, xsrc, b1, te, lane, cur, run, acc, ends, wts);
                         if (b2 >= te) break;
                         b0 = b2;
                     }
@@ -1439,17 +1444,20 @@ hipError_t launch_gemv(const KView& k, uint32_t max_row_groups, const float* X, 
     const bool vec4 = (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && k.n >= 4;
     using Kern = void (*)(KView, const float*, float*, const float*, uint32_t, int, uint32_t);
     Kern kern;
+    const bool few = gcap <= 62;  // gcap is still the longest row's number of groups here
+#define CER_GEMV_PICK(CSER, FEW)                                                                                 \
+    (x_in_lds ? (vec4 ? cer_gemv_kernel<IdxT, true, true, CSER, FEW> : cer_gemv_kernel<IdxT, true, false, CSER, FEW>) \
+              : cer_gemv_kernel<IdxT, false, false, CSER, FEW>)
     if (k.cser)
-        kern = x_in_lds ? (vec4 ? cer_gemv_kernel<IdxT, true, true, true> : cer_gemv_kernel<IdxT, true, false, true>)
-                        : cer_gemv_kernel<IdxT, false, false, true>;
+        kern = few ? CER_GEMV_PICK(true, true) : CER_GEMV_PICK(true, false);
     else
-        kern = x_in_lds ? (vec4 ? cer_gemv_kernel<IdxT, true, true, false> : cer_gemv_kernel<IdxT, true, false, false>)
-                        : cer_gemv_kernel<IdxT, false, false, false>;
-    const int kslot = (x_in_lds ? (vec4 ? 2 : 1) : 0) + (k.cser ? 3 : 0);
+        kern = few ? CER_GEMV_PICK(false, true) : CER_GEMV_PICK(false, false);
+#undef CER_GEMV_PICK
+    const int kslot = (x_in_lds ? (vec4 ? 2 : 1) : 0) + (k.cser ? 3 : 0) + (few ? 6 : 0);
     if (lds > 48 * 1024) {
         // raise the kernel's dynamic-LDS limit once per (kernel, device)
         static std::mutex mu;
-        static bool granted[6][16] = {};
+        static bool granted[12][16] = {};
         int dev = 0;
         (void)hipGetDevice(&dev);
         dev = (dev >= 0 && dev < 16) ? dev : 0;
