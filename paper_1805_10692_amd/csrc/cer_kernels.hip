@@ -453,7 +453,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
     // here, before the workgroup barrier, from the pointer tile (which arrives ahead of the indices)
     // and a lane shuffle of Omega: the wait for the other waves' share of X hides it.
     int count0 = -1;
-    if (v.K <= (uint32_t)kWave && g1 - g0 <= min(gcap, (uint32_t)kWave)) {
+    if (v.K <= (uint32_t)kWave && (kFew || g1 - g0 <= min(gcap, (uint32_t)kWave))) {
         const float w = __shfl(om_l, (int)(pt0.rank & 63u), kWave) - v.omega0;
         count0 = list_append(pt0, w, ends, wts, 0);
         list_close(ends, wts, count0, lane);
@@ -502,11 +502,11 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
             g0 = e0.x; rs = e0.y; g1 = e1.x; re = e1.y;
             acc.zero();
         }
-        // a row is one tile unless it has more raw groups than the wave's list holds
+        // a row is one tile unless it has more raw groups than the wave's list holds (never with kFew)
         for (uint32_t tg = g0; tg < g1; tg += gcap) {
-            const uint32_t tg_end = min(g1, tg + gcap);
-            const uint32_t ts = (tg == g0) ? rs : uniform(v.omegaPtr[tg]);
-            const uint32_t te = (tg_end == g1) ? re : uniform(v.omegaPtr[tg_end]);
+            const uint32_t tg_end = kFew ? g1 : min(g1, tg + gcap);
+            const uint32_t ts = (kFew || tg == g0) ? rs : uniform(v.omegaPtr[tg]);
+            const uint32_t te = (kFew || tg_end == g1) ? re : uniform(v.omegaPtr[tg_end]);
             const bool resumed = first_row && resume;  // single tile, first batch done, list and cursor live
             uint32_t b0 = ts;
             int count;
@@ -550,6 +550,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
                 acc.fma(run, cur.w);
             }
             wave_lds_sync();  // the list is rebuilt by the next tile / row
+            if (kFew) break;  // one tile per row
         }
         const float y = wave_sum(acc.a);
         if (lane == 0) Y[r] = y + t_off;
