@@ -360,7 +360,9 @@ __device__ __forceinline__ void gemv_batch(const uint32_t (&ix)[kGemvSteps], con
 
 // kFew: no row has more than 62 non-empty groups (the launcher knows the longest list), so a row's list and its
 // two sentinels fit the cursor's 64 lanes and the cursor never reloads them.
-template <typename IdxT, bool kXinLds, bool kVec4, bool kCser, bool kFew>
+// kOneRow: the launch gives every wave at most one row (matrices of up to 16 rows per compute unit and workgroup
+// slot), so the loop over a wave's rows and what it keeps alive fall away.
+template <typename IdxT, bool kXinLds, bool kVec4, bool kCser, bool kFew, bool kOneRow>
 __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
                                                         const float* __restrict__ T, uint32_t rows_per_block,
                                                         int omega_in_lds, uint32_t gcap) {
@@ -554,6 +556,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
         }
         const float y = wave_sum(acc.a);
         if (lane == 0) Y[r] = y + t_off;
+        if (kOneRow) break;
         first_row = false;
     }
 }
@@ -1446,19 +1449,21 @@ hipError_t launch_gemv(const KView& k, uint32_t max_row_groups, const float* X, 
     using Kern = void (*)(KView, const float*, float*, const float*, uint32_t, int, uint32_t);
     Kern kern;
     const bool few = gcap <= 62;  // gcap is still the longest row's number of groups here
-#define CER_GEMV_PICK(CSER, FEW)                                                                                 \
-    (x_in_lds ? (vec4 ? cer_gemv_kernel<IdxT, true, true, CSER, FEW> : cer_gemv_kernel<IdxT, true, false, CSER, FEW>) \
-              : cer_gemv_kernel<IdxT, false, false, CSER, FEW>)
+    const bool one = few && rows_per_block == (uint32_t)waves;  // a wave has at most one row
+#define CER_GEMV_PICK(CSER, FEW, ONE)                                                            \
+    (x_in_lds ? (vec4 ? cer_gemv_kernel<IdxT, true, true, CSER, FEW, ONE>                        \
+                      : cer_gemv_kernel<IdxT, true, false, CSER, FEW, ONE>)                      \
+              : cer_gemv_kernel<IdxT, false, false, CSER, FEW, ONE>)
     if (k.cser)
-        kern = few ? CER_GEMV_PICK(true, true) : CER_GEMV_PICK(true, false);
+        kern = one ? CER_GEMV_PICK(true, true, true) : few ? CER_GEMV_PICK(true, true, false) : CER_GEMV_PICK(true, false, false);
     else
-        kern = few ? CER_GEMV_PICK(false, true) : CER_GEMV_PICK(false, false);
+        kern = one ? CER_GEMV_PICK(false, true, true) : few ? CER_GEMV_PICK(false, true, false) : CER_GEMV_PICK(false, false, false);
 #undef CER_GEMV_PICK
-    const int kslot = (x_in_lds ? (vec4 ? 2 : 1) : 0) + (k.cser ? 3 : 0) + (few ? 6 : 0);
+    const int kslot = (x_in_lds ? (vec4 ? 2 : 1) : 0) + (k.cser ? 3 : 0) + (few ? 6 : 0) + (one ? 6 : 0);
     if (lds > 48 * 1024) {
         // raise the kernel's dynamic-LDS limit once per (kernel, device)
         static std::mutex mu;
-        static bool granted[12][16] = {};
+        static bool granted[18][16] = {};
         int dev = 0;
         (void)hipGetDevice(&dev);
         dev = (dev >= 0 && dev < 16) ? dev : 0;
