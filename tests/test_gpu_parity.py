@@ -351,6 +351,25 @@ def test_dominant_value_term_error_scale():
             assert (np.abs(Y[dom] - want[dom]) <= TOL * np.abs(want[dom])).all(), f"{fmt} L={L}: dominant rows"
 
 
+def test_batch1_several_rows_per_wave():
+    """More rows than one round of waves holds: the batch-1 kernel's loop over a wave's rows (matrices of up to 4096 -
+    8192 rows run a variant without it).  10245 rows of few groups, then rows of up to 255 groups."""
+    dev = _gpu()
+    for w, rep in ((wl.alexnet_fc6(L=1, scale=2), 5), (wl.sweep_cell(256, 0.7, L=1, scale=1), 5)):
+        W = np.vstack([w.W[::(-1) ** i] for i in range(rep)])
+        X = np.ascontiguousarray(w.X[:, :1])
+        want = oracle.dot_dense(W, X, threads=8)
+        scale = oracle.abs_dot_dense(W, X, threads=8)
+        import os
+        os.environ["CER_GEMV_EXPAND"] = "0"
+        try:
+            for fmt in ("cer", "cser"):
+                print(f"{w.name} x{rep} {fmt}", flush=True)
+                check(run_matmul(fmt, W, w.codebook, X), want, scale, f"{w.name} x{rep} {fmt}")
+        finally:
+            os.environ.pop("CER_GEMV_EXPAND", None)
+
+
 def test_concurrent_calls_on_one_handle():
     """Four host threads, each with its own stream and its own inputs, call every kind of product on the same
     handles at the same time (the handle is immutable, the library's one-time set-up is guarded): every result
