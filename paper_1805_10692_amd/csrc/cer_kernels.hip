@@ -358,8 +358,9 @@ __device__ __forceinline__ void gemv_batch(const uint32_t (&ix)[kGemvSteps], con
 #undef CER_STEP
 }
 
-// kFew: no row has more than 62 non-empty groups (the launcher knows the longest list), so a row's list and its
-// two sentinels fit the cursor's 64 lanes and the cursor never reloads them.
+// kFew: no row has more than 62 groups (the launcher knows the longest list) and there are at most 64 values, so a
+// row's list and its two sentinels fit the cursor's 64 lanes, the cursor never reloads them, and every list is built
+// from one pointer tile and a lane shuffle of Omega.
 // kOneRow: the launch gives every wave at most one row (matrices of up to 16 rows per compute unit and workgroup
 // slot), so the loop over a wave's rows and what it keeps alive fall away.
 template <typename IdxT, bool kXinLds, bool kVec4, bool kCser, bool kFew, bool kOneRow>
@@ -455,7 +456,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
     // here, before the workgroup barrier, from the pointer tile (which arrives ahead of the indices)
     // and a lane shuffle of Omega: the wait for the other waves' share of X hides it.
     int count0 = -1;
-    if (v.K <= (uint32_t)kWave && (kFew || g1 - g0 <= min(gcap, (uint32_t)kWave))) {
+    if (kFew || (v.K <= (uint32_t)kWave && g1 - g0 <= min(gcap, (uint32_t)kWave))) {  // kFew: at most 64 values, too
         const float w = __shfl(om_l, (int)(pt0.rank & 63u), kWave) - v.omega0;
         count0 = list_append(pt0, w, ends, wts, 0);
         list_close(ends, wts, count0, lane);
@@ -517,8 +518,9 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
                 b0 = ts + NP * kWave;
             } else {
                 const bool pre = first_row && tg == g0;
-                count = (pre && count0 >= 0) ? count0
-                                             : list_build(v, kCser, omega, g0, tg, tg_end, pre, pt0, ends, wts, lane);
+                count = ((kFew && kOneRow) || (pre && count0 >= 0))
+                            ? count0
+                            : list_build(v, kCser, omega, g0, tg, tg_end, pre, pt0, ends, wts, lane);
                 wave_lds_sync();
                 if (count > 0) ucursor_start(cur, ends, wts, count, lane);
                 run.zero();
@@ -1448,7 +1450,7 @@ hipError_t launch_gemv(const KView& k, uint32_t max_row_groups, const float* X, 
     const bool vec4 = (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && k.n >= 4;
     using Kern = void (*)(KView, const float*, float*, const float*, uint32_t, int, uint32_t);
     Kern kern;
-    const bool few = gcap <= 62;  // gcap is still the longest row's number of groups here
+    const bool few = gcap <= 62 && k.K <= 64;  // gcap is still the longest row's number of groups here
     const bool one = few && rows_per_block == (uint32_t)waves;  // a wave has at most one row
 #define CER_GEMV_PICK(CSER, FEW, ONE)                                                            \
     (x_in_lds ? (vec4 ? cer_gemv_kernel<IdxT, true, true, CSER, FEW, ONE>                        \
