@@ -130,38 +130,73 @@ int cer_trim(void);
 
 /*
  * cer_matmul_path -- which kernel cer_matmul / cser_matmul runs for this handle and batch:
- *   0  batch-1 kernel: X staged in LDS per workgroup, one wave per row, the paper's arithmetic (the
- *      inputs of a group are summed, then multiplied once)
- *   4  batch-1 kernel for rows of many short groups (fewer than 30 indices per non-empty group on
- *      average, e.g. 8-bit codebooks): the group values are expanded per colI position into LDS
- *      and every input is multiplied by its position's value; needs X to fit in LDS.
- *      CER_GEMV_EXPAND=1 selects it whenever X fits, CER_GEMV_EXPAND=0 never
- *   1  batched kernel that gathers rows of X from L2, one wave per (row, tile of batch columns: 32
- *      when a row of X is a whole number of 128-byte lines, else 32, 64 or 128 by the cache lines
- *      the gathers touch; any width and 4-byte aligned X / Y are served by 16-byte gathers).  By
- *      default the group values are expanded per colI position into LDS and every gathered row is
- *      multiplied by its position's value; with the environment variable CER_GEMM_EXPAND=0 the
+ *   0  CER_PATH_GEMV: batch-1 kernel: X staged in LDS per workgroup, one wave per row, the paper's
+ *      arithmetic (the inputs of a group are summed, then multiplied once)
+ *   4  CER_PATH_GEMV_EXPAND: batch-1 kernel for rows of many short groups (fewer than 30 indices per
+ *      non-empty group on average, e.g. 8-bit codebooks) and for short rows: the group values are
+ *      expanded per colI position into LDS and every input is multiplied by its position's value;
+ *      needs X to fit in LDS
+ *   1  CER_PATH_GEMM: batched kernel that gathers rows of X from L2, one wave per (row, tile of batch
+ *      columns: 32 when a row of X is a whole number of 128-byte lines, else 32, 64 or 128 by the
+ *      cache lines the gathers touch; any width and 4-byte aligned X / Y are served by 16-byte
+ *      gathers).  By default the group values are expanded per colI position into LDS and every
+ *      gathered row is multiplied by its position's value; with CER_OPT_SUM_THEN_MULTIPLY the
  *      gathered rows of a group are summed first and multiplied once (slower on MI355X)
- *   2  batched kernel with the input resident in LDS -- the reuse of input elements that the
- *      paper's Section V-C names as the missing optimisation: a tile of 4 or 8 batch columns of all
- *      n input rows is staged once per workgroup and serves many rows of W.  Applicable when
+ *   2  CER_PATH_XTILE: batched kernel with the input resident in LDS -- the reuse of input elements
+ *      that the paper's Section V-C names as the missing optimisation: a tile of 4 or 8 batch columns
+ *      of all n input rows is staged once per workgroup and serves many rows of W.  Applicable when
  *      n.16 bytes fit in LDS (n <= about 10000), K <= 64 and no row has more than 63 groups;
  *      for a batch of more than one tile a stream-ordered temporary of about the size of X is
  *      used (a tile-major copy of X).
- *   3  decode + dense: the matrix is decoded into a stream-ordered temporary of 4.m.n bytes and
- *      multiplied on the fp32 matrix cores.  Chosen when the estimated time of the gathers
+ *   3  CER_PATH_DENSE: decode + dense: the matrix is decoded into a stream-ordered temporary of 4.m.n
+ *      bytes and multiplied on the fp32 matrix cores.  Chosen when the estimated time of the gathers
  *      (max(4.batch, 128) bytes per indexed element through the L1/L2 path) exceeds that of the
  *      decode and the dense contraction: wide batches of matrices with more than about one
- *      indexed element in five, any batch > 1 of matrices with most elements indexed;
- *      CER_DENSIFY=1 forces it for every batch > 1, CER_DENSIFY=0 switches it off.  The
+ *      indexed element in five, any batch > 1 of matrices with most elements indexed.  The
  *      arithmetic is then that of a dense fp32 product (same error bound), not Algorithm 3 / 4.
  * On MI355X kernel 2 beats kernel 1 for narrow batches of large matrices (kernel 1 moves a whole
  * 128-byte line per index however narrow the batch) and loses for wide ones (random LDS gathers
  * are bank-conflict bound): it is chosen when it is applicable, batch <= 8 and the matrix holds
- * at least 2.5 million indices.  CER_XTILE=1 selects it whenever applicable, CER_XTILE=0 never.
+ * at least 2.5 million indices.
  * Errors: CER_E_INVALID, CER_E_HIP (no device copy).
  */
 int cer_matmul_path(const cer_handle_t* h, int64_t batch);
+
+/*
+ * cer_matmul_ex -- cer_matmul / cser_matmul (it accepts handles of both formats) with the caller's
+ * choices instead of the library's; the result is the same Y within the same error bound.  The
+ * library reads no environment variable: this call is the only way to steer it.
+ *   opts->path       CER_PATH_AUTO, or the kernel to prefer (numbering of cer_matmul_path).  A
+ *                    preferred kernel is taken whenever it is applicable to the handle and the batch
+ *                    (0 / 4 for batch 1, 1 / 2 / 3 for batch > 1); where it is not, the library
+ *                    chooses as cer_matmul does.  cer_matmul_path_ex tells which kernel will run.
+ *   opts->tile_cols  kernel 1, batch a multiple of 4 with 16-byte aligned X and Y: batch columns per
+ *                    tile, 8, 16, 32, 64 or 128; 0 = the library's choice
+ *   opts->flags      CER_OPT_SUM_THEN_MULTIPLY    kernel 1: the variant that sums a group's gathered
+ *                                                 rows before its one multiplication
+ *                    CER_OPT_ROWS_WHOLE           kernel 1: rows in their own order and never in parts
+ *                                                 (see cer_long_row_parts)
+ *                    CER_OPT_X_FROM_GLOBAL        kernel 0: gather X from global memory, no LDS copy
+ *                    CER_OPT_ONE_COLUMN_PER_LANE  kernel 1, ragged batch widths: one batch column per
+ *                                                 lane instead of 16-byte gathers
+ *                    CER_OPT_SHORT_CHUNKS / CER_OPT_LONG_CHUNKS  kernel 1: group values expanded 512 /
+ *                                                 2048 positions at a time (default: by the average row)
+ * opts == NULL is cer_matmul's behaviour.  Errors: those of cer_matmul; CER_E_INVALID also for an
+ * undefined path, tile width or flag.
+ */
+enum { CER_PATH_AUTO = -1, CER_PATH_GEMV = 0, CER_PATH_GEMM = 1, CER_PATH_XTILE = 2, CER_PATH_DENSE = 3,
+       CER_PATH_GEMV_EXPAND = 4 };
+enum { CER_OPT_SUM_THEN_MULTIPLY = 1, CER_OPT_ROWS_WHOLE = 2, CER_OPT_X_FROM_GLOBAL = 4,
+       CER_OPT_ONE_COLUMN_PER_LANE = 8, CER_OPT_SHORT_CHUNKS = 16, CER_OPT_LONG_CHUNKS = 32 };
+typedef struct {
+    int32_t path;
+    int32_t tile_cols;
+    uint32_t flags;
+    uint32_t reserved; /* 0 */
+} cer_matmul_opts_t;
+int cer_matmul_ex(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t batch, void* stream,
+                  const cer_matmul_opts_t* opts);
+int cer_matmul_path_ex(const cer_handle_t* h, int64_t batch, const cer_matmul_opts_t* opts);
 
 /*
  * cer_decode / cser_decode -- arrays -> dense matrix (Section II-A: M can be reconstructed

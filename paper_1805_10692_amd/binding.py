@@ -35,10 +35,14 @@ EXPORTS = [
     "csr_encode", "csr_matmul", "csr_decode", "csr_get_array", "csr_storage_bits", "csr_device_bytes",
     "csr_clone_device", "csr_free", "cer_cost_model", "csr_cost_model", "dense_cost_model",
     "cer_encode_device", "cer_quantize_uniform", "cer_quantize_encode_device", "cer_matmul_path", "cer_stream_read",
-    "cer_decode_device", "cer_trim",
+    "cer_decode_device", "cer_trim", "cer_matmul_ex", "cer_matmul_path_ex",
 ]
 
 CER_FORMAT_CER, CER_FORMAT_CSER = 0, 1
+
+CER_PATH_AUTO, CER_PATH_GEMV, CER_PATH_GEMM, CER_PATH_XTILE, CER_PATH_DENSE, CER_PATH_GEMV_EXPAND = -1, 0, 1, 2, 3, 4
+CER_OPT_SUM_THEN_MULTIPLY, CER_OPT_ROWS_WHOLE, CER_OPT_X_FROM_GLOBAL = 1, 2, 4
+CER_OPT_ONE_COLUMN_PER_LANE, CER_OPT_SHORT_CHUNKS, CER_OPT_LONG_CHUNKS = 8, 16, 32
 
 _lib = None
 
@@ -55,6 +59,15 @@ class CostT(ctypes.Structure):
         d["reads"] = sum(v for k, v in d.items() if k.startswith("read_"))
         d["ops"] = d["reads"] + d["mul"] + d["add"] + d["write"]
         return d
+
+
+class MatmulOpts(ctypes.Structure):
+    """cer_matmul_opts_t: preferred kernel, tile width and CER_OPT_* flags of cer_matmul_ex."""
+    _fields_ = [("path", ctypes.c_int32), ("tile_cols", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32)]
+
+    def __init__(self, path: int = CER_PATH_AUTO, tile_cols: int = 0, flags: int = 0):
+        super().__init__(path, tile_cols, flags, 0)
 
 
 class CerError(RuntimeError):
@@ -134,6 +147,10 @@ def lib() -> ctypes.CDLL:
         L.cer_trim.argtypes = []
         L.cer_matmul_path.restype = ctypes.c_int
         L.cer_matmul_path.argtypes = [vp, i64]
+        L.cer_matmul_ex.restype = ctypes.c_int
+        L.cer_matmul_ex.argtypes = [vp, vp, vp, i64, vp, ctypes.POINTER(MatmulOpts)]
+        L.cer_matmul_path_ex.restype = ctypes.c_int
+        L.cer_matmul_path_ex.argtypes = [vp, i64, ctypes.POINTER(MatmulOpts)]
         L.cer_encode_device.restype = ctypes.c_int
         L.cer_encode_device.argtypes = [vp, i64, i64, vp, i32, i32, vp, pvp]
         L.cer_quantize_uniform.restype = ctypes.c_int
@@ -270,6 +287,18 @@ def cer_matmul_path(h: Handle, batch: int) -> int:
     rc = lib().cer_matmul_path(h.ptr, batch)
     if rc < 0:
         _check(rc, "cer_matmul_path")
+    return rc
+
+
+def cer_matmul_ex(h: Handle, X, Y, batch: int, stream=None, opts: "MatmulOpts | None" = None) -> None:
+    _check(lib().cer_matmul_ex(h.ptr, _dev_ptr(X), _dev_ptr(Y), batch, _stream_ptr(stream),
+                               ctypes.byref(opts) if opts is not None else None), "cer_matmul_ex")
+
+
+def cer_matmul_path_ex(h: Handle, batch: int, opts: "MatmulOpts | None" = None) -> int:
+    rc = lib().cer_matmul_path_ex(h.ptr, batch, ctypes.byref(opts) if opts is not None else None)
+    if rc < 0:
+        _check(rc, "cer_matmul_path_ex")
     return rc
 
 

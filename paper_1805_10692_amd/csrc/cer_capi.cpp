@@ -98,6 +98,30 @@ cer::DeviceLayout cer::DeviceLayout::make(size_t colI_bytes, int64_t G, int64_t 
     return l;
 }
 
+namespace {
+// Compute units and LDS per workgroup of a device, read once per device.
+struct DeviceProps {
+    std::once_flag once;
+    int cus = 256;
+    size_t lds_per_block = 64 * 1024;
+};
+DeviceProps g_device_props[16];
+
+const DeviceProps& device_props(int dev) {
+    DeviceProps& p = g_device_props[(dev >= 0 && dev < 16) ? dev : 0];
+    std::call_once(p.once, [&p, dev] {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) == hipSuccess) {
+            p.cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+            p.lds_per_block = std::max<size_t>(prop.sharedMemPerBlock, prop.maxSharedMemoryPerMultiProcessor);
+        } else {
+            (void)hipGetLastError();
+        }
+    });
+    return p;
+}
+}  // namespace
+
 void cer::bind_device(cer_matrix* h, int dev, void* base, const DeviceLayout& l) {
     const HostMatrix& A = *h->host;
     auto* b = static_cast<unsigned char*>(base);
@@ -123,6 +147,9 @@ void cer::bind_device(cer_matrix* h, int dev, void* base, const DeviceLayout& l)
     v.nnz = A.nnz;
     v.nonempty_groups = A.nonempty_groups;
     v.omega0 = A.K > 0 ? A.omega[0] : 0.f;
+    const DeviceProps& dp = device_props(dev);
+    v.cus = dp.cus;
+    v.lds_per_block = dp.lds_per_block;
     h->layout = l;
 }
 
@@ -329,9 +356,27 @@ int encode_any(const float* W, int64_t m, int64_t n, const float* codebook, int3
     }
 }
 
-int matmul_any(const cer_handle_t* h, bool want_cser, const float* X, float* Y, int64_t batch, void* stream) {
-    if (!h || !X || !Y || batch < 1) return CER_E_INVALID;
-    if (h->host->cser != want_cser) return CER_E_FORMAT;
+// cer_matmul_opts_t -> the launchers' options; false: a field holds a value the header does not define.
+bool read_options(const cer_matmul_opts_t* in, cer::MatmulOptions* out) {
+    *out = cer::MatmulOptions{};
+    if (!in) return true;
+    constexpr uint32_t known = CER_OPT_SUM_THEN_MULTIPLY | CER_OPT_ROWS_WHOLE | CER_OPT_X_FROM_GLOBAL |
+                               CER_OPT_ONE_COLUMN_PER_LANE | CER_OPT_SHORT_CHUNKS | CER_OPT_LONG_CHUNKS;
+    if (in->path < CER_PATH_AUTO || in->path > CER_PATH_GEMV_EXPAND) return false;
+    if (in->flags & ~known) return false;
+    if ((in->flags & CER_OPT_SHORT_CHUNKS) && (in->flags & CER_OPT_LONG_CHUNKS)) return false;
+    switch (in->tile_cols) {
+        case 0: case 8: case 16: case 32: case 64: case 128: break;
+        default: return false;
+    }
+    out->path = in->path;
+    out->tile_cols = in->tile_cols;
+    out->flags = in->flags;
+    return true;
+}
+
+// The handle's device is the current one and holds its arrays; else the CER_* code to return.
+int check_device(const cer_handle_t* h) {
     if (h->device < 0 || !h->d_base) {
         g_last_hip_error = (int)hipErrorNoDevice;
         return CER_E_HIP;
@@ -340,7 +385,18 @@ int matmul_any(const cer_handle_t* h, bool want_cser, const float* X, float* Y, 
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return hip_fail(e);
     if (dev != h->device) return hip_fail(hipErrorInvalidDevice);
-    const int rc = cer::launch_matmul(h->view, X, Y, batch, stream);
+    return CER_OK;
+}
+
+int matmul_any(const cer_handle_t* h, int want_cser /* -1: either */, const float* X, float* Y, int64_t batch, void* stream,
+               const cer_matmul_opts_t* opts) {
+    if (!h || !X || !Y || batch < 1) return CER_E_INVALID;
+    if (want_cser >= 0 && h->host->cser != (want_cser != 0)) return CER_E_FORMAT;
+    cer::MatmulOptions o;
+    if (!read_options(opts, &o)) return CER_E_INVALID;
+    const int dc = check_device(h);
+    if (dc != CER_OK) return dc;
+    const int rc = cer::launch_matmul(h->view, X, Y, batch, stream, o);
     return rc == 0 ? CER_OK : hip_fail((hipError_t)rc);
 }
 
@@ -369,17 +425,24 @@ int cser_encode(const float* W, int64_t m, int64_t n, const float* codebook, int
 }
 
 int cer_matmul(const cer_handle_t* h, const float* X, float* Y, int64_t batch, void* stream) {
-    return matmul_any(h, false, X, Y, batch, stream);
+    return matmul_any(h, 0, X, Y, batch, stream, nullptr);
 }
 int cser_matmul(const cer_handle_t* h, const float* X, float* Y, int64_t batch, void* stream) {
-    return matmul_any(h, true, X, Y, batch, stream);
+    return matmul_any(h, 1, X, Y, batch, stream, nullptr);
+}
+int cer_matmul_ex(const cer_handle_t* h, const float* X, float* Y, int64_t batch, void* stream,
+                  const cer_matmul_opts_t* opts) {
+    return matmul_any(h, -1, X, Y, batch, stream, opts);
 }
 
-int cer_matmul_path(const cer_handle_t* h, int64_t batch) {
+int cer_matmul_path_ex(const cer_handle_t* h, int64_t batch, const cer_matmul_opts_t* opts) {
     if (!h || batch < 1) return CER_E_INVALID;
+    cer::MatmulOptions o;
+    if (!read_options(opts, &o)) return CER_E_INVALID;
     if (h->device < 0 || !h->d_base) return CER_E_HIP;
-    return cer::matmul_path(h->view, batch);
+    return cer::matmul_path(h->view, batch, o);
 }
+int cer_matmul_path(const cer_handle_t* h, int64_t batch) { return cer_matmul_path_ex(h, batch, nullptr); }
 
 int cer_decode(const cer_handle_t* h, float* W_out) { return decode_any(h, false, W_out); }
 int cser_decode(const cer_handle_t* h, float* W_out) { return decode_any(h, true, W_out); }

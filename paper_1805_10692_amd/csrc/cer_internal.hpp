@@ -59,6 +59,9 @@ struct DeviceView {
     int64_t nnz = 0;
     int64_t nonempty_groups = 0;
     float omega0 = 0.f;
+    // the device the arrays live on, as the launchers need it (read once, when the handle is bound to its memory)
+    int32_t cus = 256;
+    size_t lds_per_block = 64 * 1024;
     // Matrices with rows of unequal length (null / 0 otherwise), for the default batched kernel:
     // row_order[i] = the row served i-th (descending length);
     // split_parts[i] = {row, first position, end position, 0} for every part of a long row but its first;
@@ -92,11 +95,25 @@ int encode_host(const float* W, int64_t m, int64_t n, const float* codebook, int
 int decode_host(const HostMatrix& A, float* W_out);
 int min_index_bits(uint64_t max_value);
 
-// HIP launchers (cer_kernels.hip).  Return a hipError_t value as int (0 = success).
-int launch_matmul(const DeviceView& v, const float* X, float* Y, int64_t L, void* stream);
-// Which product kernel launch_matmul picks for batch L: 0 = batch-1 kernel, 1 = batched, gathers from L2,
-// 2 = batched, input tile resident in LDS.
-int matmul_path(const DeviceView& v, int64_t L);
+// Per-call choices of cer_matmul_ex (include/cer.h: cer_matmul_opts_t); the defaults are what cer_matmul does.
+struct MatmulOptions {
+    int path = -1;      // preferred kernel (numbering of cer_matmul_path), -1 = the library's choice
+    int tile_cols = 0;  // batched kernels that gather from L2: batch columns per tile, 0 = the library's choice
+    uint32_t flags = 0; // CER_OPT_* bits
+};
+constexpr uint32_t kOptSumThenMultiply = 1, kOptRowsWhole = 2, kOptXFromGlobal = 4, kOptOneColumnPerLane = 8,
+                   kOptShortChunks = 16, kOptLongChunks = 32;
+
+// HIP launchers (cer_matmul.hip).  Return a hipError_t value as int (0 = success).
+// workspace == nullptr: temporaries are stream-ordered allocations.  Otherwise the call allocates nothing: the column
+// sums of X (Omega[0] != 0) go to `workspace` (device memory, workspace_floats floats; hipErrorInvalidValue if that
+// is fewer than matmul_workspace_floats), and only kernels that need no other temporary are chosen.
+int launch_matmul(const DeviceView& v, const float* X, float* Y, int64_t L, void* stream, const MatmulOptions& o,
+                  float* workspace = nullptr, size_t workspace_floats = 0);
+// Floats of workspace a product of batch L needs (0 when Omega[0] == 0, or when the batch-1 kernel sums X itself).
+size_t matmul_workspace_floats(const DeviceView& v, int64_t L, const MatmulOptions& o);
+// Which product kernel launch_matmul picks for batch L (numbering of cer_matmul_path).
+int matmul_path(const DeviceView& v, int64_t L, const MatmulOptions& o);
 int launch_dense(const float* W, const float* X, float* Y, int64_t m, int64_t n, int64_t L, void* stream);
 int launch_stream_copy(void* dst, const void* src, int64_t bytes, void* stream);
 int launch_stream_read(const void* src, int64_t bytes, void* sink, void* stream);

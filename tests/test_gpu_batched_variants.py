@@ -1,38 +1,41 @@
 """GPU parity of the batched kernels that gather from L2 -- the default one (group values expanded per
-position in LDS, then a plain multiply-add stream; CER_GEMM_EXPAND=1), the cursor variant that sums each
-group before its one multiplication (CER_GEMM_EXPAND=0), and the default one with ragged batch widths served
-one column per lane instead of by 16-byte gathers (CER_GEMM_RAGGED=0) -- on every kind of matrix, against the
-oracle under the usual bound.  A fourth run forces the 512-position value chunks meant for matrices of short
-rows (CER_GEMM_SHORT=1) onto every matrix, so that long rows walk many chunks."""
-import os
-
+position in LDS, then a plain multiply-add stream), the cursor variant that sums each group before its one
+multiplication (CER_OPT_SUM_THEN_MULTIPLY), and the default one with ragged batch widths served one column per
+lane instead of by 16-byte gathers (CER_OPT_ONE_COLUMN_PER_LANE) -- on every kind of matrix, against the oracle
+under the usual bound.  A fourth run forces the 512-position value chunks meant for matrices of short rows
+(CER_OPT_SHORT_CHUNKS) onto every matrix, so that long rows walk many chunks.  The variants are selected per call
+through cer_matmul_ex."""
 import numpy as np
 import pytest
 
+from paper_1805_10692_amd import binding as B
 from paper_1805_10692_amd import workloads as wl
-from test_gpu_parity import full_check
+from test_gpu_parity import full_check as _full_check
 
 pytestmark = pytest.mark.gpu
 
 
 VARIANTS = {
-    "expand": {"CER_GEMM_EXPAND": "1", "CER_GEMM_RAGGED": "1"},            # the defaults
-    "cursor": {"CER_GEMM_EXPAND": "0", "CER_GEMM_RAGGED": "1"},
-    "expand_one_column_per_lane": {"CER_GEMM_EXPAND": "1", "CER_GEMM_RAGGED": "0"},   # ragged widths without 16-byte gathers
-    "expand_short_chunks": {"CER_GEMM_EXPAND": "1", "CER_GEMM_RAGGED": "1", "CER_GEMM_SHORT": "1"},  # 512-position chunks on every matrix
+    "expand": 0,                                                    # the defaults
+    "cursor": B.CER_OPT_SUM_THEN_MULTIPLY,
+    "expand_one_column_per_lane": B.CER_OPT_ONE_COLUMN_PER_LANE,    # ragged widths without 16-byte gathers
+    "expand_short_chunks": B.CER_OPT_SHORT_CHUNKS,                  # 512-position chunks on every matrix
 }
 
 
 @pytest.fixture(autouse=True, params=list(VARIANTS), ids=list(VARIANTS))
 def variant(request):
-    old = {k: os.environ.get(k) for k in VARIANTS[request.param]}
-    os.environ.update(VARIANTS[request.param])
+    global _opts
+    _opts = B.MatmulOpts(path=B.CER_PATH_GEMM, flags=VARIANTS[request.param])
     yield
-    for k, v in old.items():
-        if v is None:
-            os.environ.pop(k, None)
-        else:
-            os.environ[k] = v
+    _opts = None
+
+
+_opts = None
+
+
+def full_check(w, fmts=("cer", "cser")):
+    _full_check(w, fmts, opts=_opts, want_path=B.CER_PATH_GEMM)
 
 
 CASES = {

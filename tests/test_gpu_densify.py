@@ -1,42 +1,18 @@
 """GPU parity of the large-batch route of cer_matmul / cser_matmul that decodes the matrix into a dense
-temporary and multiplies it on the fp32 matrix cores (cer_matmul_path = 3).  Forced on with CER_DENSIFY=1
+temporary and multiplies it on the fp32 matrix cores (cer_matmul_path = 3).  Preferred through cer_matmul_ex
 for every kind of matrix and checked element by element against the oracle under the bound of every other
 product, |Y - Y_oracle| <= 1e-5 * sum_c |W[r,c]| |X[c,l]|; then the automatic choice is checked on the
 full-size workloads: it must take the route where the matrix is not sparse enough for the gathers to win
 and leave it alone elsewhere."""
-import os
-
-import numpy as np
 import pytest
 
 from paper_1805_10692_amd import binding as B
 from paper_1805_10692_amd import workloads as wl
-from test_gpu_parity import full_check, sampled_check
+from test_gpu_parity import full_check
 
 pytestmark = pytest.mark.gpu
 
-
-def _set(value):
-    old = os.environ.get("CER_DENSIFY")
-    if value is None:
-        os.environ.pop("CER_DENSIFY", None)
-    else:
-        os.environ["CER_DENSIFY"] = value
-    return old
-
-
-@pytest.fixture
-def forced():
-    old = _set("1")
-    yield
-    _set(old)
-
-
-@pytest.fixture
-def automatic():
-    old = _set(None)
-    yield
-    _set(old)
+DENSE = B.MatmulOpts(path=B.CER_PATH_DENSE)
 
 
 CASES = {
@@ -58,21 +34,21 @@ CASES = {
 
 
 @pytest.mark.parametrize("name", list(CASES))
-def test_densified_all_elements(forced, name):
+def test_densified_all_elements(name):
     w = CASES[name]()
     h = B.cer_encode(w.W, w.codebook)
-    assert B.cer_matmul_path(h, w.L) == 3
-    assert B.cer_matmul_path(h, 1) in (0, 4)     # a single input vector never takes this route
+    assert B.cer_matmul_path_ex(h, w.L, DENSE) == 3
+    assert B.cer_matmul_path_ex(h, 1, DENSE) in (0, 4)     # a single input vector never takes this route
     B.cer_free(h)
-    full_check(w)
+    full_check(w, opts=DENSE)
 
 
 @pytest.mark.parametrize("L", [2, 3, 33, 65, 100, 129, 260])
-def test_densified_ragged_batch_widths(forced, L):
-    full_check(wl.random_lowentropy(m=67, n=1501, K=48, p_dom=0.3, L=L, seed=500 + L, ratio=0.97))
+def test_densified_ragged_batch_widths(L):
+    full_check(wl.random_lowentropy(m=67, n=1501, K=48, p_dom=0.3, L=L, seed=500 + L, ratio=0.97), opts=DENSE, want_path=3)
 
 
-def test_automatic_choice_on_full_size_workloads(automatic):
+def test_automatic_choice_on_full_size_workloads():
     picks = {}
     for name, w in (("conv3x3_L3136", wl.conv3x3()), ("alexnet_fc6_L32", wl.alexnet_fc6(L=32)),
                     ("vgg_fc6_L64", wl.vgg_fc6(L=64)), ("sweep_K256_p0.5_L16", wl.sweep_cell(256, 0.5))):
@@ -87,21 +63,21 @@ def test_automatic_choice_on_full_size_workloads(automatic):
                                                         # 4 indices per group: batch 1 takes the expansion kernel
 
 
-def test_automatic_full_conv_batch3136_sampled(automatic):
-    w = wl.conv3x3(nonzero_dominant=True)
-    rows = np.random.default_rng(3).choice(w.m, 6, replace=False)
-    sampled_check(w, ("cer", "cser"), np.sort(rows))
+@pytest.mark.parametrize("variant", [False, True], ids=["zero_dominant", "nonzero_dominant"])
+def test_automatic_full_conv_batch3136_all_outputs(variant):
+    """The convolution shape at its full size with the library's own choice of kernel (decode + dense)."""
+    full_check(wl.conv3x3(nonzero_dominant=variant), want_path=B.CER_PATH_DENSE)
 
 
-def test_trim_releases_cached_temporaries_and_products_go_on(forced):
+def test_trim_releases_cached_temporaries_and_products_go_on():
     """cer_trim gives the pooled temporaries back; the next products allocate again and stay correct."""
     import torch
     w = wl.conv3x3(L=200, scale=4)
-    full_check(w)
+    full_check(w, opts=DENSE)
     before = torch.cuda.mem_get_info()[0]
     B.cer_trim()
     after = torch.cuda.mem_get_info()[0]
     assert after >= before                      # nothing is taken by a trim; what was cached is free again
-    full_check(w)
+    full_check(w, opts=DENSE)
     B.cer_trim()
     B.cer_trim()                                # trimming an empty pool is fine

@@ -1,27 +1,17 @@
 """GPU parity of the batch-1 kernel that expands the group values per position (meant for rows of many short
-groups, e.g. 8-bit codebooks), forced on with CER_GEMV_EXPAND=1 for every kind of matrix and checked element by
+groups, e.g. 8-bit codebooks), preferred through cer_matmul_ex for every kind of matrix and checked element by
 element against the oracle under the bound of every other product; then the automatic choice on full-size cells
 of the entropy sweep."""
-import os
-
 import numpy as np
 import pytest
 
+from paper_1805_10692_amd import binding as B
 from paper_1805_10692_amd import workloads as wl
 from test_gpu_parity import full_check
 
 pytestmark = pytest.mark.gpu
 
-
-@pytest.fixture
-def forced():
-    old = os.environ.get("CER_GEMV_EXPAND")
-    os.environ["CER_GEMV_EXPAND"] = "1"
-    yield
-    if old is None:
-        os.environ.pop("CER_GEMV_EXPAND", None)
-    else:
-        os.environ["CER_GEMV_EXPAND"] = old
+EXPAND = B.MatmulOpts(path=B.CER_PATH_GEMV_EXPAND)
 
 
 CASES = {
@@ -47,18 +37,17 @@ CASES = {
 
 
 @pytest.mark.parametrize("name", list(CASES))
-def test_gemv_expand_all_elements(forced, name):
-    full_check(CASES[name]())
+def test_gemv_expand_all_elements(name):
+    # X too big for LDS: the preference cannot be met and the cursor kernel runs
+    full_check(CASES[name](), opts=EXPAND, want_path=0 if name == "u32_index_L1" else 4)
 
 
-def test_gemv_expand_full_size_vgg_fc6(forced):
-    full_check(wl.vgg_fc6(L=1))
+def test_gemv_expand_full_size_vgg_fc6():
+    full_check(wl.vgg_fc6(L=1), opts=EXPAND, want_path=4)
 
 
 @pytest.mark.parametrize("K,p0,path", [(256, 0.5, 4), (256, 0.9, 4), (64, 0.5, 4), (16, 0.5, 0)])
 def test_automatic_choice_full_sweep_cells(K, p0, path):
-    from paper_1805_10692_amd import binding as B
-    os.environ.pop("CER_GEMV_EXPAND", None)
     w = wl.sweep_cell(K, p0, L=1)
     h = B.cer_encode(w.W, w.codebook)
     assert B.cer_matmul_path(h, 1) == path
@@ -67,15 +56,13 @@ def test_automatic_choice_full_sweep_cells(K, p0, path):
 
 
 def test_automatic_choice_keeps_the_layer_shapes_on_the_cursor_kernel():
-    from paper_1805_10692_amd import binding as B
-    os.environ.pop("CER_GEMV_EXPAND", None)
     for w in (wl.vgg_fc6(L=1), wl.alexnet_fc6(L=1)):
         h = B.cer_encode(w.W, w.codebook)
         assert B.cer_matmul_path(h, 1) == 0
         B.cer_free(h)
 
 
-def test_short_row_variant_with_a_few_long_rows(forced):
+def test_short_row_variant_with_a_few_long_rows():
     """The variant for matrices of short rows (chosen by the average row) must still walk a long row chunk by
     chunk: most rows hold about 90 indices, three hold 1300 - 2900, one group straddles a chunk boundary."""
     rng = np.random.default_rng(61)
@@ -90,4 +77,4 @@ def test_short_row_variant_with_a_few_long_rows(forced):
         pass
     w = Case()
     w.name, w.W, w.codebook, w.X, w.m, w.n, w.L = "short rows with long ones", W, cb, X, 60, 3000, 1
-    full_check(w)
+    full_check(w, opts=EXPAND, want_path=4)

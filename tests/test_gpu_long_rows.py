@@ -4,8 +4,6 @@ The default batched kernel serves such rows in parts (the row's own work item ta
 further part is a work item of its own, a second kernel adds the parts' sums to Y); batch 1 keeps them whole.  Checked here against the
 oracle element by element, for both formats, aligned and ragged batch widths, few and many groups per row, a
 non-zero most frequent value, and against the same product with the rows left whole."""
-import os
-
 import numpy as np
 import pytest
 
@@ -16,6 +14,8 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 TOL = 1e-5
+GATHER = B.MatmulOpts(path=B.CER_PATH_GEMM)                                      # the kernel that gathers from L2
+GATHER_ROWS_WHOLE = B.MatmulOpts(path=B.CER_PATH_GEMM, flags=B.CER_OPT_ROWS_WHOLE)  # ... rows in place and whole
 
 
 def _gpu():
@@ -58,21 +58,14 @@ def test_long_rows_in_parts(K, dominant):
             rng = np.random.default_rng(100 + L)
             X = rng.standard_normal((n, L)).astype(np.float32)
             want = oracle.dot_dense(W, X, threads=8)
-            scale = oracle.abs_dot_dense(W, X, threads=8) + abs(dominant) * np.abs(X.astype(np.float64)).sum(axis=0)[None, :]
+            scale = oracle.abs_dot_dense(W, X, threads=8)     # the stated bound, also with a non-zero most frequent value
             Xd = torch.from_numpy(X).to(dev)
             results = {}
             for split in ("1", "0"):
-                os.environ["CER_GEMM_SPLIT"] = split
-                os.environ["CER_DENSIFY"] = "0"
-                os.environ["CER_XTILE"] = "0"
-                try:
-                    print(f"{fmt} K={K} L={L} split={split}", flush=True)
-                    Yd = torch.full((m, L), float("nan"), dtype=torch.float32, device=dev)
-                    mm(h, Xd, Yd, L)
-                    torch.cuda.synchronize()
-                finally:
-                    for k in ("CER_GEMM_SPLIT", "CER_DENSIFY", "CER_XTILE"):
-                        os.environ.pop(k, None)
+                print(f"{fmt} K={K} L={L} split={split}", flush=True)
+                Yd = torch.full((m, L), float("nan"), dtype=torch.float32, device=dev)
+                B.cer_matmul_ex(h, Xd, Yd, L, None, GATHER if split == "1" else GATHER_ROWS_WHOLE)
+                torch.cuda.synchronize()
                 Y = Yd.cpu().numpy().astype(np.float64)
                 assert np.isfinite(Y).all(), f"{fmt} K={K} L={L} split={split}: unwritten output"
                 bad = np.abs(Y - want) > TOL * scale
@@ -102,15 +95,10 @@ def test_rows_in_order_of_length_without_parts(m):
             Xd = torch.from_numpy(X).to(dev)
             results = {}
             for split in ("1", "0"):
-                os.environ.update({"CER_GEMM_SPLIT": split, "CER_DENSIFY": "0", "CER_XTILE": "0"})
-                try:
-                    print(f"{fmt} m={m} L={L} split={split}", flush=True)
-                    Yd = torch.full((m, L), float("nan"), dtype=torch.float32, device=dev)
-                    mm(h, Xd, Yd, L)
-                    torch.cuda.synchronize()
-                finally:
-                    for k in ("CER_GEMM_SPLIT", "CER_DENSIFY", "CER_XTILE"):
-                        os.environ.pop(k, None)
+                print(f"{fmt} m={m} L={L} split={split}", flush=True)
+                Yd = torch.full((m, L), float("nan"), dtype=torch.float32, device=dev)
+                B.cer_matmul_ex(h, Xd, Yd, L, None, GATHER if split == "1" else GATHER_ROWS_WHOLE)
+                torch.cuda.synchronize()
                 Y = Yd.cpu().numpy().astype(np.float64)
                 assert np.isfinite(Y).all(), f"{fmt} m={m} L={L} split={split}: unwritten output"
                 assert (np.abs(Y - want) <= TOL * scale).all(), f"{fmt} m={m} L={L} split={split}"
@@ -127,7 +115,6 @@ def test_device_encoder_builds_the_same_schedule(fmt):
     m, n = 96, 12000
     W, cb, _ = skewed_matrix(77, m, n, 16, 0.0, [1.0, 0.9, 0.55, 0.36])
     enc = B.cer_encode if fmt == "cer" else B.cser_encode
-    mm = B.cer_matmul if fmt == "cer" else B.cser_matmul
     hh = enc(W, cb)
     hd = B.cer_encode_device(torch.from_numpy(W).to(dev), m, n, cb, fmt)
     assert B.cer_long_row_parts(hh) == 15
@@ -137,14 +124,9 @@ def test_device_encoder_builds_the_same_schedule(fmt):
         Xd = torch.from_numpy(X).to(dev)
         Yh = torch.full((m, L), float("nan"), dtype=torch.float32, device=dev)
         Yd = torch.full((m, L), float("nan"), dtype=torch.float32, device=dev)
-        os.environ.update({"CER_DENSIFY": "0", "CER_XTILE": "0"})
-        try:
-            mm(hh, Xd, Yh, L)
-            mm(hd, Xd, Yd, L)
-            torch.cuda.synchronize()
-        finally:
-            os.environ.pop("CER_DENSIFY", None)
-            os.environ.pop("CER_XTILE", None)
+        B.cer_matmul_ex(hh, Xd, Yh, L, None, GATHER)
+        B.cer_matmul_ex(hd, Xd, Yd, L, None, GATHER)
+        torch.cuda.synchronize()
         want = oracle.dot_dense(W, X, threads=8)
         scale = oracle.abs_dot_dense(W, X, threads=8)
         assert (np.abs(Yd.cpu().numpy().astype(np.float64) - want) <= TOL * scale).all(), f"{fmt} L={L}"

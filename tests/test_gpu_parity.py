@@ -21,12 +21,19 @@ def _gpu():
     return torch.device("cuda:0")
 
 
-def run_matmul(fmt, W, codebook, X, stream=None):
+def run_matmul(fmt, W, codebook, X, stream=None, opts=None, want_path=None):
+    """One product through the C ABI.  opts: a MatmulOpts for cer_matmul_ex (None: cer_matmul / cser_matmul);
+    want_path: the kernel that cer_matmul_path_ex must announce for this call."""
     dev = _gpu()
     h = (B.cer_encode if fmt == "cer" else B.cser_encode)(W, codebook)
     Xd = torch.from_numpy(np.ascontiguousarray(X)).to(dev)
     Yd = torch.full((W.shape[0], X.shape[1]), float("nan"), dtype=torch.float32, device=dev)
-    (B.cer_matmul if fmt == "cer" else B.cser_matmul)(h, Xd, Yd, X.shape[1], stream)
+    if want_path is not None and W.size:
+        assert B.cer_matmul_path_ex(h, X.shape[1], opts) == want_path
+    if opts is None:
+        (B.cer_matmul if fmt == "cer" else B.cser_matmul)(h, Xd, Yd, X.shape[1], stream)
+    else:
+        B.cer_matmul_ex(h, Xd, Yd, X.shape[1], stream, opts)
     torch.cuda.synchronize()
     Y = Yd.cpu().numpy()
     B.cer_free(h)
@@ -42,13 +49,14 @@ def check(Y, want, scale, what):
                            f"{float((err / np.maximum(scale, 1e-300)).max()):.3e} at {np.argwhere(bad)[:4].tolist()}")
 
 
-def full_check(w, fmts=("cer", "cser")):
+def full_check(w, fmts=("cer", "cser"), opts=None, want_path=None):
+    """Every element of Y against the oracle's group-sum product (Algorithm 3 / 4 in fp64) of its own encoding."""
     print(f"case {w.name} m={w.m} n={w.n} L={w.L}", flush=True)
     scale = oracle.abs_dot_dense(w.W, w.X, threads=8)
     for fmt in fmts:
         A = oracle.encode(w.W, w.codebook, fmt)
         want = oracle.dot(A, w.X, threads=8)
-        Y = run_matmul(fmt, w.W, w.codebook, w.X)
+        Y = run_matmul(fmt, w.W, w.codebook, w.X, opts=opts, want_path=want_path)
         check(Y, want, scale, f"{w.name}/{fmt}")
 
 
@@ -168,45 +176,32 @@ def test_stream_copy_probe():
 
 # ------------------------------------------------------------------ full sizes of the named workloads
 
-def sampled_check(w, fmts, rows):
-    """Full-size run on the GPU; the oracle recomputes a sample of output rows (all batch columns)."""
-    print(f"case {w.name} m={w.m} n={w.n} L={w.L} sampled rows={len(rows)}", flush=True)
-    Wr = np.ascontiguousarray(w.W[rows])
-    want = oracle.dot_dense(Wr, w.X, threads=8)
-    scale = oracle.abs_dot_dense(Wr, w.X, threads=8)
-    for fmt in fmts:
-        Y = run_matmul(fmt, w.W, w.codebook, w.X)
-        assert np.isfinite(Y).all()
-        check(Y[rows], want, scale, f"{w.name}/{fmt}")
-
+# Every output element of every benchmark configuration at its full size: the oracle's group-sum product costs
+# nnz.L additions (a few seconds on the host's cores even for the convolution shape), so nothing is sampled.
 
 def test_full_vgg_fc6_gemv_all_outputs():
     full_check(wl.vgg_fc6(L=1))
 
 
-def test_full_vgg_fc6_batch64_sampled():
-    w = wl.vgg_fc6(L=64)
-    rows = np.random.default_rng(0).choice(w.m, 96, replace=False)
-    sampled_check(w, ("cer", "cser"), np.sort(rows))
+def test_full_vgg_fc6_batch64_all_outputs():
+    full_check(wl.vgg_fc6(L=64))
 
 
-def test_full_alexnet_fc6_batch32_sampled():
-    w = wl.alexnet_fc6(L=32)
-    rows = np.random.default_rng(1).choice(w.m, 96, replace=False)
-    sampled_check(w, ("cer", "cser"), np.sort(rows))
+def test_full_alexnet_fc6_batch32_all_outputs():
+    full_check(wl.alexnet_fc6(L=32))
 
 
-@pytest.mark.parametrize("K,p0", [(256, 0.99), (16, 0.9)])
+@pytest.mark.parametrize("p0", wl.SWEEP_P0)
+@pytest.mark.parametrize("K", wl.SWEEP_K)
 def test_full_sweep_cells_all_outputs(K, p0):
     full_check(wl.sweep_cell(K, p0))
 
 
-@pytest.mark.parametrize("variant", [False, True])
-def test_full_conv_batch3136_sampled(variant, monkeypatch):
-    monkeypatch.setenv("CER_DENSIFY", "0")   # the gather kernels; the decode + dense route has its own test file
-    w = wl.conv3x3(nonzero_dominant=variant)
-    rows = np.random.default_rng(2).choice(w.m, 6, replace=False)
-    sampled_check(w, ("cer", "cser"), np.sort(rows))
+@pytest.mark.parametrize("variant", [False, True], ids=["zero_dominant", "nonzero_dominant"])
+def test_full_conv_batch3136_gather_kernel_all_outputs(variant):
+    """The convolution shape on the gather kernel (Algorithm 3 / 4); the library's own choice for this shape, the
+    decode + dense route, is checked at full size in test_gpu_densify.py."""
+    full_check(wl.conv3x3(nonzero_dominant=variant), opts=B.MatmulOpts(path=B.CER_PATH_GEMM), want_path=B.CER_PATH_GEMM)
 
 
 # ------------------------------------------------------------------ CSR comparator (Algorithm 2)
@@ -309,16 +304,11 @@ def test_unaligned_device_pointers(L):
     Xd.copy_(torch.from_numpy(w.X.reshape(-1)))
     for fmt in ("cer", "cser"):
         h = (B.cer_encode if fmt == "cer" else B.cser_encode)(w.W, w.codebook)
-        for xt in ("0", "1"):
-            import os
-            os.environ["CER_XTILE"] = xt
-            try:
-                Yd.fill_(float("nan"))
-                (B.cer_matmul if fmt == "cer" else B.cser_matmul)(h, Xd, Yd, L)
-                torch.cuda.synchronize()
-            finally:
-                del os.environ["CER_XTILE"]
-            check(Yd.cpu().numpy().reshape(w.m, L), want, scale, f"unaligned {fmt} L={L} xtile={xt}")
+        for path in (B.CER_PATH_GEMM, B.CER_PATH_XTILE):      # for L = 1 neither applies: the batch-1 kernel runs
+            Yd.fill_(float("nan"))
+            B.cer_matmul_ex(h, Xd, Yd, L, None, B.MatmulOpts(path=path))
+            torch.cuda.synchronize()
+            check(Yd.cpu().numpy().reshape(w.m, L), want, scale, f"unaligned {fmt} L={L} path={path}")
         B.cer_free(h)
     Wd = torch.from_numpy(w.W).to(dev)
     Yd.fill_(float("nan"))
@@ -360,14 +350,10 @@ def test_batch1_several_rows_per_wave():
         X = np.ascontiguousarray(w.X[:, :1])
         want = oracle.dot_dense(W, X, threads=8)
         scale = oracle.abs_dot_dense(W, X, threads=8)
-        import os
-        os.environ["CER_GEMV_EXPAND"] = "0"
-        try:
-            for fmt in ("cer", "cser"):
-                print(f"{w.name} x{rep} {fmt}", flush=True)
-                check(run_matmul(fmt, W, w.codebook, X), want, scale, f"{w.name} x{rep} {fmt}")
-        finally:
-            os.environ.pop("CER_GEMV_EXPAND", None)
+        for fmt in ("cer", "cser"):
+            print(f"{w.name} x{rep} {fmt}", flush=True)
+            Y = run_matmul(fmt, W, w.codebook, X, opts=B.MatmulOpts(path=B.CER_PATH_GEMV), want_path=B.CER_PATH_GEMV)
+            check(Y, want, scale, f"{w.name} x{rep} {fmt}")
 
 
 def test_concurrent_calls_on_one_handle():

@@ -1,8 +1,6 @@
 """GPU parity of the batched kernel that keeps the input tile in LDS (reuse of X, Section V-C),
-forced on with CER_XTILE=1 and checked element by element against the oracle, under the same bound
+preferred through cer_matmul_ex and checked element by element against the oracle, under the same bound
 as every other product:  |Y - Y_oracle| <= 1e-5 * sum_c |W[r,c]| |X[c,l]|."""
-import os
-
 import numpy as np
 import pytest
 
@@ -16,15 +14,7 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-5
 
 
-@pytest.fixture(autouse=True)
-def force_lds_variant():
-    old = os.environ.get("CER_XTILE")
-    os.environ["CER_XTILE"] = "1"
-    yield
-    if old is None:
-        os.environ.pop("CER_XTILE", None)
-    else:
-        os.environ["CER_XTILE"] = old
+XTILE = B.MatmulOpts(path=B.CER_PATH_XTILE)
 
 
 def _gpu():
@@ -42,9 +32,9 @@ def run_and_check(W, codebook, X, what, expect_path=2, fmts=("cer", "cser")):
     Xd = torch.from_numpy(np.ascontiguousarray(X)).to(dev)
     for fmt in fmts:
         h = (B.cer_encode if fmt == "cer" else B.cser_encode)(W, codebook)
-        assert B.cer_matmul_path(h, L) == expect_path, f"{what}/{fmt}: kernel {B.cer_matmul_path(h, L)}"
+        assert B.cer_matmul_path_ex(h, L, XTILE) == expect_path, f"{what}/{fmt}: kernel {B.cer_matmul_path_ex(h, L, XTILE)}"
         Yd = torch.full((W.shape[0], L), float("nan"), dtype=torch.float32, device=dev)
-        (B.cer_matmul if fmt == "cer" else B.cser_matmul)(h, Xd, Yd, L)
+        B.cer_matmul_ex(h, Xd, Yd, L, None, XTILE)
         torch.cuda.synchronize()
         Y = Yd.cpu().numpy().astype(np.float64)
         B.cer_free(h)
@@ -112,29 +102,14 @@ def test_falls_back_when_not_applicable():
     run_and_check(w.W, w.codebook, w.X, w.name, expect_path=1)
 
 
-def test_full_size_alexnet_fc6_batch32_sampled():
+def test_full_size_alexnet_fc6_batch32_all_outputs():
     w = wl.alexnet_fc6(L=32)
-    dev = _gpu()
-    rows = np.sort(np.random.default_rng(1).choice(w.m, 256, replace=False))
-    Wr = np.ascontiguousarray(w.W[rows])
-    want, scale = oracle.dot_dense(Wr, w.X, threads=8), oracle.abs_dot_dense(Wr, w.X, threads=8)
-    Xd = torch.from_numpy(w.X).to(dev)
-    for fmt in ("cer", "cser"):
-        h = (B.cer_encode if fmt == "cer" else B.cser_encode)(w.W, w.codebook)
-        assert B.cer_matmul_path(h, 32) == 2
-        Yd = torch.full((w.m, 32), float("nan"), dtype=torch.float32, device=dev)
-        (B.cer_matmul if fmt == "cer" else B.cser_matmul)(h, Xd, Yd, 32)
-        torch.cuda.synchronize()
-        Y = Yd.cpu().numpy()
-        B.cer_free(h)
-        assert np.isfinite(Y).all()
-        assert np.all(np.abs(Y[rows].astype(np.float64) - want) <= TOL * scale)
+    run_and_check(w.W, w.codebook, w.X, w.name)
 
 
 def test_automatic_choice_for_narrow_batches():
     """Left to itself the library takes this kernel for narrow batches of a large matrix whose input fits in LDS
     (measured 1.1 - 2.2 x faster there) and nowhere else; the products it then computes match the oracle."""
-    del os.environ["CER_XTILE"]          # the fixture restores it
     dev = _gpu()
     w = wl.alexnet_fc6(L=3)
     h = B.cer_encode(w.W, w.codebook)

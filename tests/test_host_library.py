@@ -74,6 +74,53 @@ def test_encoder_matches_oracle_bit_exact(make):
         B.cer_free(h)
 
 
+FULL_SIZE = {
+    "alexnet_fc6": lambda: wl.alexnet_fc6(L=1),
+    "vgg_fc6": lambda: wl.vgg_fc6(L=1),
+    "conv3x3": lambda: wl.conv3x3(L=1),
+    "conv3x3_nonzero_dominant": lambda: wl.conv3x3(L=1, nonzero_dominant=True),
+}
+FULL_SIZE.update({f"sweep_K{K}_p{p0}": (lambda K=K, p0=p0: wl.sweep_cell(K, p0, L=1)) for K in wl.SWEEP_K for p0 in wl.SWEEP_P0})
+
+
+@pytest.mark.parametrize("name", list(FULL_SIZE))
+def test_encoder_matches_oracle_bit_exact_at_full_size(name):
+    """Every benchmark configuration at the size the benchmark runs it (config 1 is in the list above): all arrays,
+    widths, counts, storage bits and statistics of the library's host encoder against the oracle's, both formats,
+    and the decode round trip."""
+    w = FULL_SIZE[name]()
+    for fmt, enc, dec in (("cer", B.cer_encode, B.cer_decode), ("cser", B.cser_encode, B.cser_decode)):
+        h = enc(w.W, w.codebook)
+        _compare(h, oracle.encode(w.W, w.codebook, fmt))
+        assert dec(h).tobytes() == w.W.tobytes()
+        B.cer_free(h)
+
+
+def test_matmul_options_are_validated_before_anything_runs():
+    """cer_matmul_ex / cer_matmul_path_ex reject paths, tile widths and flags that the header does not define; on a
+    machine without a device a valid call then fails with CER_E_HIP (there is no CPU product)."""
+    import ctypes
+    h = B.cer_encode(np.array([[0, 1, 2], [2, 2, 0]], np.float32), np.array([0.0, 1.0, 2.0], np.float32))
+    L = B.lib()
+    for bad in (B.MatmulOpts(path=5), B.MatmulOpts(path=-2), B.MatmulOpts(tile_cols=24), B.MatmulOpts(flags=64),
+                B.MatmulOpts(flags=B.CER_OPT_SHORT_CHUNKS | B.CER_OPT_LONG_CHUNKS)):
+        assert L.cer_matmul_ex(h.ptr, 16, 16, 1, None, ctypes.byref(bad)) == B.CER_E_INVALID
+        assert L.cer_matmul_path_ex(h.ptr, 1, ctypes.byref(bad)) == B.CER_E_INVALID
+    assert L.cer_matmul_ex(h.ptr, None, 16, 1, None, None) == B.CER_E_INVALID
+    assert L.cer_matmul_path_ex(None, 1, None) == B.CER_E_INVALID
+    assert L.cer_matmul_path_ex(h.ptr, 0, None) == B.CER_E_INVALID
+    try:
+        import torch
+        has_gpu = torch.cuda.is_available()
+    except ImportError:
+        has_gpu = False
+    if not has_gpu:
+        ok = B.MatmulOpts(path=B.CER_PATH_GEMM, tile_cols=32, flags=B.CER_OPT_ROWS_WHOLE)
+        assert L.cer_matmul_ex(h.ptr, 16, 16, 2, None, ctypes.byref(ok)) == B.CER_E_HIP
+        assert L.cer_matmul_path_ex(h.ptr, 2, ctypes.byref(ok)) == B.CER_E_HIP
+    B.cer_free(h)
+
+
 def test_worked_example_through_the_library(example):
     M = example["M"].astype(np.float32)
     h = B.cer_encode(M, np.array([0, 2, 3, 4], np.float32))

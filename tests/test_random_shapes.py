@@ -71,17 +71,16 @@ def test_products_random(seed):
     scale = oracle.abs_dot_dense(W, X, threads=4)
     Xd = torch.from_numpy(X).to(dev)
     print(f"seed {seed}: m={m} n={n} K={K} L={L}", flush=True)
-    import os
     for fmt, enc, mm in (("cer", B.cer_encode, B.cer_matmul), ("cser", B.cser_encode, B.cser_matmul)):
         h = enc(W, cb)
-        for xt in ("0", "1"):
-            os.environ["CER_XTILE"] = xt
-            try:
-                Yd = torch.full((m, L), float("nan"), dtype=torch.float32, device=dev)
+        # the library's own choice, then each kernel family preferred in turn (taken where it applies)
+        for xt in (None, B.CER_PATH_GEMM, B.CER_PATH_XTILE, B.CER_PATH_DENSE, B.CER_PATH_GEMV, B.CER_PATH_GEMV_EXPAND):
+            Yd = torch.full((m, L), float("nan"), dtype=torch.float32, device=dev)
+            if xt is None:
                 mm(h, Xd, Yd, L)
-                torch.cuda.synchronize()
-            finally:
-                del os.environ["CER_XTILE"]
+            else:
+                B.cer_matmul_ex(h, Xd, Yd, L, None, B.MatmulOpts(path=xt))
+            torch.cuda.synchronize()
             Y = Yd.cpu().numpy().astype(np.float64)
             assert np.isfinite(Y).all(), (fmt, xt)
             assert np.all(np.abs(Y - want) <= TOL * scale), (fmt, xt, float(np.abs(Y - want).max()))
