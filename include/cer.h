@@ -118,6 +118,24 @@ int cer_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t 
 int cser_matmul(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t batch, void* stream);
 
 /*
+ * cer_matmul_noalloc -- the same product for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Accepts CER and CSER
+ * handles.  It calls no allocating routine: the one temporary a product can need here, the column
+ * sums of X for a non-zero most frequent value (batch floats plus partial sums), lives in a fixed
+ * 2 MiB device array that is part of the library's code object (one per GPU, kept until the process
+ * ends), and only kernels that need no other temporary are chosen: the batch-1 kernels, the batched
+ * kernel that gathers from L2 with every row whole, the LDS-resident kernel for batches of one tile;
+ * never the decode + dense route.  Y equals cer_matmul's within the same error bound (bit for bit
+ * where both run the same kernel).  A product whose column sums would not fit the array (batch above
+ * about 260 000 columns with Omega[0] != 0) is refused with CER_E_TOO_LARGE.
+ * All calls on one GPU share the array: two such calls that overlap in time on one GPU (different
+ * streams or threads) race when Omega[0] != 0; calls on one stream are ordered and safe.  Nothing in
+ * the array has to survive between calls, and every word a call reads it has written before.
+ * Arguments, stream semantics and the other errors are those of cer_matmul.
+ */
+int cer_matmul_noalloc(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t batch, void* stream);
+
+/*
  * cer_trim -- gives the device memory of released temporaries back to the system.  The products and
  * conversions that need a temporary (see each call) take it, ordered on the caller's stream, from
  * a memory pool of the library's own on the current device; the pool keeps what it has handed out

@@ -35,7 +35,7 @@ EXPORTS = [
     "csr_encode", "csr_matmul", "csr_decode", "csr_get_array", "csr_storage_bits", "csr_device_bytes",
     "csr_clone_device", "csr_free", "cer_cost_model", "csr_cost_model", "dense_cost_model",
     "cer_encode_device", "cer_quantize_uniform", "cer_quantize_encode_device", "cer_matmul_path", "cer_stream_read",
-    "cer_decode_device", "cer_trim", "cer_matmul_ex", "cer_matmul_path_ex",
+    "cer_decode_device", "cer_trim", "cer_matmul_ex", "cer_matmul_path_ex", "cer_matmul_noalloc",
 ]
 
 CER_FORMAT_CER, CER_FORMAT_CSER = 0, 1
@@ -147,6 +147,8 @@ def lib() -> ctypes.CDLL:
         L.cer_trim.argtypes = []
         L.cer_matmul_path.restype = ctypes.c_int
         L.cer_matmul_path.argtypes = [vp, i64]
+        L.cer_matmul_noalloc.restype = ctypes.c_int
+        L.cer_matmul_noalloc.argtypes = [vp, vp, vp, i64, vp]
         L.cer_matmul_ex.restype = ctypes.c_int
         L.cer_matmul_ex.argtypes = [vp, vp, vp, i64, vp, ctypes.POINTER(MatmulOpts)]
         L.cer_matmul_path_ex.restype = ctypes.c_int
@@ -293,6 +295,10 @@ def cer_matmul_path(h: Handle, batch: int) -> int:
 def cer_matmul_ex(h: Handle, X, Y, batch: int, stream=None, opts: "MatmulOpts | None" = None) -> None:
     _check(lib().cer_matmul_ex(h.ptr, _dev_ptr(X), _dev_ptr(Y), batch, _stream_ptr(stream),
                                ctypes.byref(opts) if opts is not None else None), "cer_matmul_ex")
+
+
+def cer_matmul_noalloc(h: Handle, X, Y, batch: int, stream=None) -> None:
+    _check(lib().cer_matmul_noalloc(h.ptr, _dev_ptr(X), _dev_ptr(Y), batch, _stream_ptr(stream)), "cer_matmul_noalloc")
 
 
 def cer_matmul_path_ex(h: Handle, batch: int, opts: "MatmulOpts | None" = None) -> int:

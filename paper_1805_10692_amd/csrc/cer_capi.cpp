@@ -435,6 +435,20 @@ int cer_matmul_ex(const cer_handle_t* h, const float* X, float* Y, int64_t batch
     return matmul_any(h, -1, X, Y, batch, stream, opts);
 }
 
+int cer_matmul_noalloc(const cer_handle_t* h, const float* X, float* Y, int64_t batch, void* stream) {
+    if (!h || !X || !Y || batch < 1) return CER_E_INVALID;
+    const int dc = check_device(h);
+    if (dc != CER_OK) return dc;
+    float* ws = nullptr;
+    size_t ws_floats = 0;
+    const int we = cer::static_workspace(&ws, &ws_floats);
+    if (we != 0) return hip_fail((hipError_t)we);
+    const cer::MatmulOptions o;
+    if (cer::matmul_workspace_floats(h->view, batch, o) > ws_floats) return CER_E_TOO_LARGE;
+    const int rc = cer::launch_matmul(h->view, X, Y, batch, stream, o, ws, ws_floats);
+    return rc == 0 ? CER_OK : hip_fail((hipError_t)rc);
+}
+
 int cer_matmul_path_ex(const cer_handle_t* h, int64_t batch, const cer_matmul_opts_t* opts) {
     if (!h || batch < 1) return CER_E_INVALID;
     cer::MatmulOptions o;

@@ -110,6 +110,9 @@ constexpr uint32_t kOptSumThenMultiply = 1, kOptRowsWhole = 2, kOptXFromGlobal =
 // is fewer than matmul_workspace_floats), and only kernels that need no other temporary are chosen.
 int launch_matmul(const DeviceView& v, const float* X, float* Y, int64_t L, void* stream, const MatmulOptions& o,
                   float* workspace = nullptr, size_t workspace_floats = 0);
+// The library's fixed workspace on the current device (a __device__ array; nothing is allocated): its device
+// address and its size in floats.  A hipError_t value as int.
+int static_workspace(float** ptr, size_t* floats);
 // Floats of workspace a product of batch L needs (0 when Omega[0] == 0, or when the batch-1 kernel sums X itself).
 size_t matmul_workspace_floats(const DeviceView& v, int64_t L, const MatmulOptions& o);
 // Which product kernel launch_matmul picks for batch L (numbering of cer_matmul_path).

@@ -2,6 +2,13 @@
 // a non-zero most frequent value (Appendix A-A1), and the decode + dense route.
 #include "cer_device.hpp"
 
+// Workspace of the entry point that allocates nothing: one array per GPU, part of the loaded code object, so it
+// exists from the moment the library is loaded on a device until the process ends.  Host code never uses the
+// array's name as an address: the address on the current device comes from hipGetSymbolAddress, once per device.
+// (No `used` attribute: it keeps the symbol local to the code object, where the runtime's look-up by name cannot find it.)
+constexpr size_t kStaticWorkspaceFloats = 512 * 1024;  // 2 MiB
+static __device__ __align__(256) float scratch[kStaticWorkspaceFloats];
+
 namespace cer {
 namespace {
 
@@ -155,6 +162,26 @@ size_t matmul_workspace_floats(const DeviceView& d, int64_t L, const MatmulOptio
     if (d.m == 0 || L < 1 || L > 0x7FFFFFFFll || d.omega0 == 0.f) return 0;
     if (L == 1 && gemv_sums_x(d, o)) return 0;
     return plan_colsum((uint32_t)d.n, (uint32_t)L).floats;
+}
+
+int static_workspace(float** ptr, size_t* floats) {
+    static std::mutex mu;
+    static float* addr[16] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= 16) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return (int)e;
+        if (!p) return (int)hipErrorInvalidSymbol;
+        addr[dev] = static_cast<float*>(p);
+    }
+    *ptr = addr[dev];
+    *floats = kStaticWorkspaceFloats;
+    return (int)hipSuccess;
 }
 
 int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, void* stream_v, const MatmulOptions& o_in,
