@@ -77,7 +77,7 @@ def kernel_name(fmt: str, L: int, path) -> str:
     if fmt == "csr":
         return "csr_gemv_kernel" if L == 1 else "csr_gemm_kernel"
     return {0: "cer_gemv_kernel",
-            1: "cer_gemm_kernel" if os.environ.get("CER_GEMM_EXPAND", "1") == "0" else "cer_gemm_expand_kernel",
+            1: "cer_gemm_expand_kernel",
             2: "cer_xtile_kernel", 3: "decode_kernel + dense_gemm_mfma_kernel", 4: "cer_gemv_expand_kernel"}[path]
 
 
@@ -158,7 +158,7 @@ def probe_stream(nbytes: int, steps: int = 1000) -> dict:
             "read_only_frac_of_peak": nbytes / (ev_big * 1e-3) / 1e9 / HBM_PEAK_GBS, "empty_launch_us": ev_tiny * 1e3}
 
 
-def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: bool, with_dense: bool) -> dict:
+def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: bool, with_dense: bool, opts=None) -> dict:
     import torch
 
     from paper_1805_10692_amd import binding as B
@@ -199,7 +199,10 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
     if with_cpu:
         import oracle
         want, scale = oracle.dot_dense(Wr, w.X, threads=8), oracle.abs_dot_dense(Wr, w.X, threads=8)
-    mm(h0, Xd, Yd, L)
+    if opts is not None and fmt != "csr":
+        B.cer_matmul_ex(h0, Xd, Yd, L, None, opts)
+    else:
+        mm(h0, Xd, Yd, L)
     torch.cuda.synchronize()
     y_rows = Yd.cpu().numpy()[rows].astype(np.float64)
     if with_cpu:
@@ -216,6 +219,11 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
     cfn = {"cer": lib.cer_matmul, "cser": lib.cser_matmul, "csr": lib.csr_matmul}[fmt]
     ptrs = [h.ptr for h in handles]
     xp, yp = Xd.data_ptr(), Yd.data_ptr()
+
+    if opts is not None and fmt != "csr":   # the caller's choice of kernel instead of the library's
+        import ctypes
+        ex, optr = lib.cer_matmul_ex, ctypes.byref(opts)
+        cfn = lambda h, x, y, l, st: ex(h, x, y, l, st, optr)  # noqa: E731
 
     def step(i):
         rc = cfn(ptrs[i % R], xp, yp, L, stream)
@@ -235,7 +243,7 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
         "algorithmic_GBps": alg_bytes / (ev_ms * 1e-3) / 1e9,
         "gather_GBps_onchip": dims["nnz"] * 4.0 * L / (ev_ms * 1e-3) / 1e9,
         "dense_bytes": 4 * (w.m * w.n + w.n * L + w.m * L),
-        "path": None if fmt == "csr" else B.cer_matmul_path(h0, L),
+        "path": None if fmt == "csr" else B.cer_matmul_path_ex(h0, L, opts),
     }
     for h in handles[1:]:
         free(h)
@@ -445,6 +453,9 @@ def main() -> int:
     ap.add_argument("--no-probe", action="store_true", help="skip the read-only stream probe of the batch-1 line")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="MiB",
                     help="also launch the plain copy kernel on this many MiB (calibrates byte counters)")
+    ap.add_argument("--path", type=int, default=-1, help="kernel to prefer (numbering of cer_matmul_path), -1 = the library's choice")
+    ap.add_argument("--flags", type=int, default=0, help="CER_OPT_* bits for cer_matmul_ex")
+    ap.add_argument("--tile-cols", type=int, default=0, help="batch columns per tile for cer_matmul_ex")
     ap.add_argument("--report", default=None, help="write a table over workloads/formats to this JSON file")
     ap.add_argument("--all", action="store_true", help="with --report: all named workloads and the entropy sweep")
     args = ap.parse_args()
@@ -467,7 +478,11 @@ def main() -> int:
                   flush=True)
         return 0
 
-    r = run_one(args.workload, args.format, args.steps, args.warmup, args.warm, not args.no_cpu, not args.no_dense)
+    opts = None
+    if args.path != -1 or args.flags or args.tile_cols:
+        from paper_1805_10692_amd import binding as B
+        opts = B.MatmulOpts(path=args.path, tile_cols=args.tile_cols, flags=args.flags)
+    r = run_one(args.workload, args.format, args.steps, args.warmup, args.warm, not args.no_cpu, not args.no_dense, opts)
     traffic = read_traffic(args.workload, args.format)
     line = {
         "metric": METRIC, "value": r["dense_equiv_gflops"], "unit": "GFLOP/s (dense-equivalent, 2*m*n*L/t)",

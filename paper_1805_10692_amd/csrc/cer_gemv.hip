@@ -1,90 +1,149 @@
 // Batch 1 (one input vector): Y = W.x with W in CER / CSER form (Appendix A-C, Algorithms 3 and 4 of the paper; the
 // constant term of a non-zero most frequent value, Appendix A-A1, is summed from the staged copy of x).
 //
-// X is staged into LDS once per workgroup and gathered from there; one wave per row, lane l of step s owns the
-// row's (64 s + l)-th index; the 64 lane totals are combined with DPP cross-lane adds.  Two kernels: the cursor
-// kernel keeps the paper's order of operations (sum a group's inputs, multiply once), the expansion kernel serves
-// rows of many short groups.
+// X is staged into LDS once per workgroup and gathered from there; one wave per row; the 64 lane totals are combined
+// with DPP cross-lane adds.  Two kernels: the stream kernel below, and the expansion kernel for rows of many short
+// groups and for short rows.
 #include "cer_device.hpp"
 
 namespace cer {
 namespace {
 
 // ------------------------------------------------------------------------------------------------
-// batch = 1
+// batch = 1: the stream kernel
 // ------------------------------------------------------------------------------------------------
 //
-// Lane l of step s owns the row's (64 s + l)-th index: the index loads are plain coalesced IdxT
-// loads (one cache line per wave instruction), all issued before the first is used, and so are the
-// LDS gathers of X.  A step without a boundary costs two vector instructions (address shift, add)
-// plus the LDS gather; once the stream is in flight the wave's instruction count bounds the kernel.
+// What bounds a launch of this size on MI355X is the number of vector-memory instructions a compute unit has to
+// issue (a wave instruction costs the texture-address unit 16 - 26 clocks whatever its width: 4 lanes per clock), then
+// the vector ALU (16 waves share 4 SIMDs) and the LDS gathers.  Hence:
+//   * the index stream is read with 16-byte loads: lane l of a window holds PPL consecutive colI positions (8 for
+//     16-bit indices), a batch of NW windows is in flight per lane -- 3 loads per 1536 positions instead of 24;
+//   * a batch starts at a position that is a multiple of PPL (aligned 16-byte loads); the positions in front of the
+//     row's first one belong to a pseudo group of weight 0;
+//   * the group structure is turned into per-position weights without any search or data-dependent branch: the lanes
+//     that hold a group's end set one bit per boundary in an LDS bitmap of the batch; the index (in the row's list of
+//     non-empty groups) of the group a position belongs to is the number of boundary bits in front of it = a prefix
+//     count per 32-bit word (one wave scan per batch) + a popcount inside the word; the weight is one LDS read of the
+//     list.  None of this depends on the indices or on X, so it runs while the index stream is on its way from HBM;
+//   * the stream itself is, per position, an LDS gather of X and one fused multiply-add with the position's weight
+//     (a multiply-add costs what an add costs; summing a group first would need the branches this design avoids).
 
-constexpr int kGemvSteps = 24;  // index loads in flight per lane: one batch covers 64 * 24 positions
+template <typename IdxT>
+struct GemvShape {
+    static constexpr int PPL = 16 / (int)sizeof(IdxT);  // positions per lane and 16-byte load: 16, 8, 4
+    static constexpr int WIN = kWave * PPL;             // positions per window (one load per lane)
+    static constexpr int NW = sizeof(IdxT) == 1 ? 2 : (sizeof(IdxT) == 2 ? 3 : 4);  // windows per batch
+    static constexpr int BATCH = NW * WIN;              // 2048, 1536, 1024 positions
+    static constexpr int NWORDS = BATCH / 32;           // bitmap words per batch: 64, 48, 32 (at most one per lane)
+    static constexpr int WPW = WIN / 32;                // bitmap words per window
+};
 
-// One batch of 24 steps of a row: offsets [b0, b0 + 1536) of colI, whose indices ix[] were requested
-// earlier.  The index loads return in order, so step s is gathered and summed while the indices of
-// later steps are still on their way from HBM: gathers run eight steps ahead of the sums, and
-// scheduling barriers keep the compiler from hoisting every gather (and with it the wait for the
-// last index) above the first sum.
-template <bool kFew>
-__device__ __forceinline__ void gemv_batch(const uint32_t (&ix)[kGemvSteps], const float* xsrc, uint32_t b0, uint32_t te,
-                                           uint32_t lane, UCursor& cur, Vec<1>& run, Vec<1>& acc, const uint32_t* ends,
-                                           const float* wts) {
-    static_assert(kGemvSteps == 24, "steps are spelled out");
-    Vec<1> xv[kGemvSteps];
-#define CER_GATHER4(S)                                                             \
-    xv[S].a = xsrc[ix[S]]; xv[(S) + 1].a = xsrc[ix[(S) + 1]];                      \
-    xv[(S) + 2].a = xsrc[ix[(S) + 2]]; xv[(S) + 3].a = xsrc[ix[(S) + 3]];
-#define CER_STEP(S) cer_step<kWave, 1, kFew>(xv[S], lane, b0 + (S) * kWave, cur, run, acc, ends, wts, lane)
-    // four steps at a time: one boundary test when the next 256 positions hold none
-#define CER_STEP4(S)                                                               \
-    if (cur.end - (b0 + (S) * kWave) >= 4u * kWave) {                              \
-        run.a += (xv[S].a + xv[(S) + 1].a) + (xv[(S) + 2].a + xv[(S) + 3].a);      \
-    } else {                                                                       \
-        CER_STEP(S); CER_STEP((S) + 1); CER_STEP((S) + 2); CER_STEP((S) + 3);      \
-    }
-#define CER_PIN __builtin_amdgcn_sched_barrier(0);
-    CER_GATHER4(0) CER_GATHER4(4) CER_PIN
-    CER_GATHER4(8) CER_PIN CER_STEP4(0) CER_PIN
-    CER_GATHER4(12) CER_PIN CER_STEP4(4) CER_PIN
-    CER_GATHER4(16) CER_PIN CER_STEP4(8) CER_PIN
-    CER_GATHER4(20) CER_PIN
-    if (b0 + 12 * kWave < te) {
-        CER_STEP4(12)
-        if (b0 + 16 * kWave < te) {
-            CER_STEP4(16)
-            if (b0 + 20 * kWave < te) { CER_STEP4(20) }
-        }
-    }
-#undef CER_PIN
-#undef CER_GATHER4
-#undef CER_STEP4
-#undef CER_STEP
+// Inclusive prefix sum over the 64 lanes: four shifted adds inside each row of 16 lanes, then the totals of rows 0
+// and 2 are added to rows 1 and 3, then the total of rows 0 - 1 to rows 2 - 3.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+#define CER_SCAN_STEP(CTRL, ROWS) v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROWS, 0xF, false);
+    CER_SCAN_STEP(0x111, 0xF)  // row_shr:1
+    CER_SCAN_STEP(0x112, 0xF)  // row_shr:2
+    CER_SCAN_STEP(0x114, 0xF)  // row_shr:4
+    CER_SCAN_STEP(0x118, 0xF)  // row_shr:8
+    CER_SCAN_STEP(0x142, 0xA)  // row_bcast:15 into rows 1 and 3
+    CER_SCAN_STEP(0x143, 0xC)  // row_bcast:31 into rows 2 and 3
+#undef CER_SCAN_STEP
+    return v;
 }
 
-// kFew: no row has more than 62 groups (the launcher knows the longest list) and there are at most 64 values, so a
-// row's list and its two sentinels fit the cursor's 64 lanes, the cursor never reloads them, and every list is built
-// from one pointer tile and a lane shuffle of Omega.
+// Boundary bitmap of the batch [b0, b0 + BATCH): bit p is set when a list entry ends at position b0 + p + 1, i.e.
+// position b0 + p is the last one of its group.  `first` = number of list entries that end at or before b0 (the
+// list index of the group position b0 belongs to); `last` = index of the list's second sentinel.  Afterwards
+// wpre[j] = first + the number of boundary bits in words 0 .. j-1, and `first` has moved past the batch.
+template <typename S>
+__device__ __forceinline__ void bitmap_build(const uint32_t* ends, uint32_t last, uint32_t& first, uint32_t b0,
+                                             uint32_t* bmp, uint32_t* wpre, uint32_t lane) {
+    if (lane < (uint32_t)S::NWORDS) bmp[lane] = 0u;
+    wave_lds_sync();
+    for (uint32_t i = first;; i += kWave) {
+        const uint32_t e = ends[min(i + lane, last)];  // the sentinels (2^32 - 1) are beyond every batch
+        const uint32_t rel = e - b0 - 1u;
+        if (rel < (uint32_t)S::BATCH) atomicOr(&bmp[rel >> 5], 1u << (rel & 31u));  // LDS operations of a wave run in order
+        if (__builtin_amdgcn_readlane(e, kWave - 1) - b0 > (uint32_t)S::BATCH) break;  // wave-uniform
+    }
+    wave_lds_sync();
+    const uint32_t pc = lane < (uint32_t)S::NWORDS ? (uint32_t)__builtin_popcount(bmp[min(lane, (uint32_t)S::NWORDS - 1u)]) : 0u;
+    const uint32_t incl = wave_inclusive_scan(pc);
+    if (lane < (uint32_t)S::NWORDS) wpre[lane] = first + incl - pc;
+    first += __builtin_amdgcn_readlane(incl, kWave - 1);
+    wave_lds_sync();
+}
+
+// Weights of the PPL positions lane l holds in window W of the batch: wl[k] = value - Omega[0] of the group that
+// position b0 + W.WIN + PPL.l + k belongs to (0 in front of the row and behind it).
+template <typename S>
+__device__ __forceinline__ void window_weights(int W, const uint32_t* bmp, const uint32_t* wpre, const float* wts,
+                                               uint32_t lane, float (&wl)[S::PPL]) {
+    const uint32_t bit0 = (uint32_t)S::PPL * lane;  // the lane's first bit inside the window
+    const uint32_t wj = (uint32_t)W * S::WPW + (bit0 >> 5), sh = bit0 & 31u;
+    const uint32_t word = bmp[wj];
+    const uint32_t pre = wpre[wj] + (uint32_t)__builtin_popcount(word & ((1u << sh) - 1u));
+    const uint32_t field = word >> sh;  // bits above PPL are masked out below
+#pragma unroll
+    for (int k = 0; k < S::PPL; ++k)
+        wl[k] = wts[pre + (uint32_t)__builtin_popcount(field & ((1u << k) - 1u))];
+}
+
+// Column index of the k-th of the positions packed into one 16-byte load.
+template <typename IdxT>
+__device__ __forceinline__ uint32_t packed_index(const uint4& q, int k) {
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+    if (sizeof(IdxT) == 4) return w[k];
+    if (sizeof(IdxT) == 2) return (k & 1) ? (w[k >> 1] >> 16) : (w[k >> 1] & 0xFFFFu);
+    return (w[k >> 2] >> (8 * (k & 3))) & 0xFFu;
+}
+
+// One batch: gathers and multiply-adds, window by window as the index loads return (they return in order); windows
+// that start at or behind the row's end (te) are skipped.
+template <typename IdxT>
+__device__ __forceinline__ void gemv_batch(const uint4 (&ix)[GemvShape<IdxT>::NW], const float* xsrc, uint32_t b0,
+                                           uint32_t te, const float (&wl)[GemvShape<IdxT>::NW][GemvShape<IdxT>::PPL],
+                                           float& acc0, float& acc1) {
+    using S = GemvShape<IdxT>;
+#pragma unroll
+    for (int W = 0; W < S::NW; ++W) {
+        if (W > 0 && b0 + (uint32_t)W * S::WIN >= te) break;  // wave-uniform
+        float xv[S::PPL];
+#pragma unroll
+        for (int k = 0; k < S::PPL; ++k) xv[k] = xsrc[packed_index<IdxT>(ix[W], k)];
+#pragma unroll
+        for (int k = 0; k < S::PPL; k += 2) {
+            acc0 = fmaf(xv[k], wl[W][k], acc0);
+            acc1 = fmaf(xv[k + 1], wl[W][k + 1], acc1);
+        }
+    }
+}
+
 // kOneRow: the launch gives every wave at most one row (matrices of up to 16 rows per compute unit and workgroup
 // slot), so the loop over a wave's rows and what it keeps alive fall away.
-template <typename IdxT, bool kXinLds, bool kVec4, bool kCser, bool kFew, bool kOneRow>
+template <typename IdxT, bool kXinLds, bool kVec4, bool kCser, bool kOneRow>
 __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
                                                         const float* __restrict__ T, uint32_t rows_per_block,
                                                         int omega_in_lds, uint32_t gcap) {
+    using S = GemvShape<IdxT>;
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int NP = kGemvSteps;
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = uniform(threadIdx.x >> 6);
     const uint32_t nwaves = blockDim.x >> 6;
 
-    // LDS: [X: n floats, rounded to 4] [Omega: K floats, optional] [ends | wts: nwaves x (gcap + 2)]
+    // LDS: [X: n floats, rounded to 4] [Omega: K floats, optional] [ends | wts: nwaves x (gcap + 3)]
+    //      [bitmap | word prefix: nwaves x NWORDS]
     float* xs = reinterpret_cast<float*>(smem);
     const uint32_t x_floats = kXinLds ? ((v.n + 3u) & ~3u) : 0u;
     float* oms = xs + x_floats;
     const uint32_t om_floats = omega_in_lds ? ((v.K + 3u) & ~3u) : 0u;
+    const uint32_t lcap = gcap + 3u;  // the pseudo group in front of the row, the groups, two sentinels
     uint32_t* list0 = reinterpret_cast<uint32_t*>(oms + om_floats);
-    uint32_t* ends = list0 + wave * (gcap + 2);
-    float* wts = reinterpret_cast<float*>(list0 + nwaves * (gcap + 2)) + wave * (gcap + 2);
+    uint32_t* ends = list0 + wave * lcap;
+    float* wts = reinterpret_cast<float*>(list0 + nwaves * lcap) + wave * lcap;
+    uint32_t* bmp = list0 + 2u * nwaves * lcap + wave * (uint32_t)S::NWORDS;
+    uint32_t* wpre = list0 + 2u * nwaves * lcap + (nwaves + wave) * (uint32_t)S::NWORDS;
     const float* omega = omega_in_lds ? oms : v.omega;
     const float* xsrc = kXinLds ? xs : X;
 
@@ -100,47 +159,40 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
         g0 = d0.x; rs = d0.y; g1 = d1.x; re = d1.y;
     }
 
-    // (2) X and Omega on their way to LDS: eight 16-byte loads per thread are issued here and stay in
-    //     flight while the first row's pointers and indices are requested (named registers: an
-    //     indexed array would end up in scratch memory)
+    // (2) X and Omega on their way to LDS: up to eight 16-byte loads per thread, only those that hold part of X
+    //     (wave-uniform tests), in named registers (an indexed array would end up in scratch memory)
     typedef float F4 __attribute__((ext_vector_type(4)));
     F4 xr0, xr1, xr2, xr3, xr4, xr5, xr6, xr7;
+    xr0 = xr1 = xr2 = xr3 = xr4 = xr5 = xr6 = xr7 = F4{0.f, 0.f, 0.f, 0.f};
     const uint32_t n4 = kVec4 ? (v.n >> 2) : 0u;
     const F4* X4 = reinterpret_cast<const F4*>(X);
+    const uint32_t wave_first = wave * kWave;  // the wave's first thread
 #define CER_STAGE_IDX(k) ((k) * blockDim.x + threadIdx.x)
-#define CER_STAGE_LOAD(k) xr##k = X4[CER_STAGE_IDX(k) < n4 ? CER_STAGE_IDX(k) : n4 - 1u]
-    if (kXinLds && kVec4) {  // clamped: every load is issued, none leaves X (the launcher guarantees n4 > 0)
+#define CER_STAGE_LOAD(k) if ((k) * blockDim.x + wave_first < n4) xr##k = X4[min(CER_STAGE_IDX(k), n4 - 1u)]
+    if (kXinLds && kVec4) {
         CER_STAGE_LOAD(0); CER_STAGE_LOAD(1); CER_STAGE_LOAD(2); CER_STAGE_LOAD(3);
         CER_STAGE_LOAD(4); CER_STAGE_LOAD(5); CER_STAGE_LOAD(6); CER_STAGE_LOAD(7);
     }
     const float om_r = v.omega[threadIdx.x < v.K ? threadIdx.x : 0u];
     const float om_l = v.omega[lane < v.K ? lane : 0u];  // Omega[lane]: lets a wave look values up by lane shuffle
-    // loads return in issue order: keep the X loads ahead of the index loads, so that staging can finish
-    // while the (much longer) index stream is still arriving -- within this wave (scheduling barrier) and
-    // within the compute unit, whose memory pipeline is shared by all waves (workgroup barrier: no wave
-    // requests indices from HBM before every wave has requested its share of X from L2)
-    __builtin_amdgcn_sched_barrier(0);
-    if (kXinLds) __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
 
-    // (3) first row: its first 64 group pointers and its first 64 * NP indices, all unconditional
+    // (3) first row: its first 64 group pointers and the indices of its first batch, all unconditional.  A batch
+    //     starts at a multiple of PPL positions; what lies in front of the row gets the weight 0.
     const PtrTile pt0 = load_ptr_tile(v, kCser, g0, g0, min(g1, g0 + min(gcap, (uint32_t)kWave)), lane);
-    uint32_t idx0[NP];  // used by one piece of code only (no merge with re-loaded values, which would make the
-                        // compiler widen -- and so wait for -- all of them at the merge point)
+    uint4 idx0[S::NW];  // used by one piece of code only (no merge with re-loaded values, which would make the
+                        // compiler wait for all of them at the merge point)
+    const uint32_t b00 = rs & ~((uint32_t)S::PPL - 1u);
     {
-        const IdxT* p = colI + rs + lane;
+        const uint4* p = reinterpret_cast<const uint4*>(colI + b00) + lane;
 #pragma unroll
-        for (int s = 0; s < NP; ++s) idx0[s] = (uint32_t)p[s * kWave];
+        for (int W = 0; W < S::NW; ++W) idx0[W] = p[W * kWave];
     }
-
     __builtin_amdgcn_sched_barrier(0);
 
     // (4) finish staging
     if (kXinLds) {
         if (kVec4) {
-            // all eight values are used here unconditionally, which keeps the compiler from sinking a load
-            // into its (conditional) store below the index loads
-            asm volatile("" ::"v"(xr0), "v"(xr1), "v"(xr2), "v"(xr3), "v"(xr4), "v"(xr5), "v"(xr6), "v"(xr7));
             F4* xs4 = reinterpret_cast<F4*>(xs);
 #define CER_STAGE_STORE(k) if (CER_STAGE_IDX(k) < n4) xs4[CER_STAGE_IDX(k)] = xr##k
             CER_STAGE_STORE(0); CER_STAGE_STORE(1); CER_STAGE_STORE(2); CER_STAGE_STORE(3);
@@ -156,14 +208,24 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
         if (threadIdx.x < v.K) oms[threadIdx.x] = om_r;
         for (uint32_t i = blockDim.x + threadIdx.x; i < v.K; i += blockDim.x) oms[i] = v.omega[i];
     }
-    // With at most 64 values and at most 64 raw groups in the first row, its group list is built
-    // here, before the workgroup barrier, from the pointer tile (which arrives ahead of the indices)
-    // and a lane shuffle of Omega: the wait for the other waves' share of X hides it.
-    int count0 = -1;
-    if (kFew || (v.K <= (uint32_t)kWave && g1 - g0 <= min(gcap, (uint32_t)kWave))) {  // kFew: at most 64 values, too
+    // With at most 64 values and at most 64 raw groups in the first row, its group list, the first batch's bitmap and
+    // the weights of the first batch are built here, before the workgroup barrier, from the pointer tile (which
+    // arrives ahead of the indices) and a lane shuffle of Omega.
+    int count0 = -1;   // entries of the first row's list, the pseudo group included; -1: not built here
+    uint32_t first = 0;  // list index of the group the next batch's first position belongs to
+    float wl0[S::NW][S::PPL];
+    if (v.K <= (uint32_t)kWave && g1 - g0 <= min(gcap, (uint32_t)kWave)) {
         const float w = __shfl(om_l, (int)(pt0.rank & 63u), kWave) - v.omega0;
-        count0 = list_append(pt0, w, ends, wts, 0);
+        if (lane == 0) { ends[0] = rs; wts[0] = 0.f; }
+        count0 = list_append(pt0, w, ends, wts, 1);
         list_close(ends, wts, count0, lane);
+        if (count0 > 1) {
+            wave_lds_sync();
+            first = rs > b00 ? 0u : 1u;
+            bitmap_build<S>(ends, (uint32_t)count0 + 1u, first, b00, bmp, wpre, lane);
+#pragma unroll
+            for (int W = 0; W < S::NW; ++W) window_weights<S>(W, bmp, wpre, wts, lane, wl0[W]);
+        }
     }
     if (kXinLds || omega_in_lds) __syncthreads();
 
@@ -187,18 +249,12 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
         t_off = v.omega0 * tsum;
     }
 
-    // The first batch of the first row runs from the prefetched indices when its list is ready
-    // (the common case); everything else -- later batches, rows with many groups, later rows --
-    // goes through the general loop below, which picks up the cursor and sums where this left off.
-    UCursor cur;
-    Vec<1> run, acc;
-    run.zero();
-    acc.zero();
+    // The first batch of the first row runs from the prefetched indices when its list is ready (the common case);
+    // everything else -- later batches, rows with many groups, later rows -- goes through the general loop below.
+    float acc0 = 0.f, acc1 = 0.f;
     bool resume = false;
-    if (r < row_end && count0 > 0) {
-        wave_lds_sync();
-        ucursor_start(cur, ends, wts, count0, lane);
-        gemv_batch<kFew>(idx0, xsrc, rs, re, lane, cur, run, acc, ends, wts);
+    if (r < row_end && count0 > 1) {
+        gemv_batch<IdxT>(idx0, xsrc, b00, re, wl0, acc0, acc1);
         resume = true;
     }
 
@@ -207,65 +263,76 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
         if (!first_row) {
             const uint2 e0 = v.rowInfo[r], e1 = v.rowInfo[r + 1];
             g0 = e0.x; rs = e0.y; g1 = e1.x; re = e1.y;
-            acc.zero();
+            acc0 = acc1 = 0.f;
         }
-        // a row is one tile unless it has more raw groups than the wave's list holds (never with kFew)
+        // a row is one tile unless it has more raw groups than the wave's list holds
         for (uint32_t tg = g0; tg < g1; tg += gcap) {
-            const uint32_t tg_end = kFew ? g1 : min(g1, tg + gcap);
-            const uint32_t ts = (kFew || tg == g0) ? rs : uniform(v.omegaPtr[tg]);
-            const uint32_t te = (kFew || tg_end == g1) ? re : uniform(v.omegaPtr[tg_end]);
-            const bool resumed = first_row && resume;  // single tile, first batch done, list and cursor live
-            uint32_t b0 = ts;
+            const uint32_t tg_end = min(g1, tg + gcap);
+            const uint32_t ts = tg == g0 ? rs : uniform(v.omegaPtr[tg]);
+            const uint32_t te = tg_end == g1 ? re : uniform(v.omegaPtr[tg_end]);
+            const bool resumed = first_row && resume;  // single tile, first batch done, list live
+            uint32_t b0 = ts & ~((uint32_t)S::PPL - 1u);
             int count;
             if (resumed) {
                 count = count0;
-                b0 = ts + NP * kWave;
+                b0 += S::BATCH;
             } else {
                 const bool pre = first_row && tg == g0;
-                count = ((kFew && kOneRow) || (pre && count0 >= 0))
-                            ? count0
-                            : list_build(v, kCser, omega, g0, tg, tg_end, pre, pt0, ends, wts, lane);
-                wave_lds_sync();
-                if (count > 0) ucursor_start(cur, ends, wts, count, lane);
-                run.zero();
-            }
-            if (count > 0) {
-                if (b0 < te) {
-                    // Two sets of index registers: the next batch is requested before the current one is summed, so
-                    // that a wave working alone on a long row (the others of its compute unit are done) does not
-                    // wait out the memory latency once per batch.  Past the row's end the current batch is requested
-                    // again (in bounds, unused) to keep the loads unconditional.
-                    uint32_t ixa[NP], ixb[NP];
-#define CER_REQUEST(ix, b)                                                     \
-    {                                                                          \
-        const IdxT* p_ = colI + (b) + lane;                                    \
-        _Pragma("unroll") for (int s = 0; s < NP; ++s) ix[s] = (uint32_t)p_[s * kWave]; \
-    }
-                    CER_REQUEST(ixa, b0)
-                    for (;;) {
-                        const uint32_t b1 = b0 + NP * kWave;
-                        CER_REQUEST(ixb, b1 < te ? b1 : b0)
-                        gemv_batch<kFew>(ixa, xsrc, b0, te, lane, cur, run, acc, ends, wts);
-                        if (b1 >= te) break;
-                        const uint32_t b2 = b1 + NP * kWave;
-                        CER_REQUEST(ixa, b2 < te ? b2 : b1)
-                        gemv_batch<kFew>(ixb, xsrc, b1, te, lane, cur, run, acc, ends, wts);
-                        if (b2 >= te) break;
-                        b0 = b2;
+                if (pre && count0 >= 0) {
+                    count = count0;
+                } else {
+                    // the pseudo group in front of the tile, then its non-empty groups
+                    if (lane == 0) { ends[0] = ts; wts[0] = 0.f; }
+                    count = 1;
+                    for (uint32_t j0 = tg; j0 < tg_end; j0 += kWave) {
+                        const PtrTile p = (pre && j0 == tg) ? pt0 : load_ptr_tile(v, kCser, g0, j0, tg_end, lane);
+                        count = list_append(p, omega[p.rank < v.K ? p.rank : 0u] - v.omega0, ends, wts, count);
                     }
-#undef CER_REQUEST
+                    list_close(ends, wts, count, lane);
                 }
-                acc.fma(run, cur.w);
+                wave_lds_sync();
+                first = ts > b0 ? 0u : 1u;
+            }
+            if (count > 1 && b0 < te) {
+                // Two sets of index registers: the next batch is requested before the current one is summed, so
+                // that a wave working alone on a long row (the others of its compute unit are done) does not
+                // wait out the memory latency once per batch.  Past the row's end the current batch is requested
+                // again (in bounds, unused) to keep the loads unconditional.
+                uint4 ixa[S::NW], ixb[S::NW];
+                float wl[S::NW][S::PPL];
+#define CER_REQUEST(ix, b)                                                                       \
+    {                                                                                            \
+        const uint4* p_ = reinterpret_cast<const uint4*>(colI + (b)) + lane;                     \
+        _Pragma("unroll") for (int W = 0; W < S::NW; ++W) ix[W] = p_[W * kWave];                 \
+    }
+#define CER_BATCH(ix, b)                                                                         \
+    bitmap_build<S>(ends, (uint32_t)count + 1u, first, b, bmp, wpre, lane);                      \
+    _Pragma("unroll") for (int W = 0; W < S::NW; ++W) window_weights<S>(W, bmp, wpre, wts, lane, wl[W]); \
+    gemv_batch<IdxT>(ix, xsrc, b, te, wl, acc0, acc1);
+                CER_REQUEST(ixa, b0)
+                for (;;) {
+                    const uint32_t b1 = b0 + S::BATCH;
+                    CER_REQUEST(ixb, b1 < te ? b1 : b0)
+                    CER_BATCH(ixa, b0)
+                    if (b1 >= te) break;
+                    const uint32_t b2 = b1 + S::BATCH;
+                    CER_REQUEST(ixa, b2 < te ? b2 : b1)
+                    CER_BATCH(ixb, b1)
+                    if (b2 >= te) break;
+                    b0 = b2;
+                }
+#undef CER_BATCH
+#undef CER_REQUEST
             }
             wave_lds_sync();  // the list is rebuilt by the next tile / row
-            if (kFew) break;  // one tile per row
         }
-        const float y = wave_sum(acc.a);
+        const float y = wave_sum(acc0 + acc1);
         if (lane == 0) Y[r] = y + t_off;
         if (kOneRow) break;
         first_row = false;
     }
 }
+
 // ------------------------------------------------------------------------------------------------
 // batch = 1, rows made of many short groups
 // ------------------------------------------------------------------------------------------------
@@ -407,7 +474,7 @@ bool gemv_stages_x(const DeviceView& d, const MatmulOptions& o) {
     const size_t om_bytes = d.K <= 4096 ? (((size_t)d.K + 3) & ~(size_t)3) * sizeof(float) : 0;
     const uint32_t gcap = std::max<uint32_t>(1u, (uint32_t)std::min<int64_t>(d.max_row_groups, 1022));
     return (o.flags & kOptXFromGlobal) == 0 &&
-           x_bytes + om_bytes + (size_t)4 * (std::min<uint32_t>(gcap, 64u) + 2) * 8 <= gemv_lds_budget(d);
+           x_bytes + om_bytes + (size_t)4 * ((std::min<uint32_t>(gcap, 64u) + 3) * 8 + 64 * 8) <= gemv_lds_budget(d);
 }
 
 template <typename IdxT>
@@ -419,7 +486,8 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
     const size_t om_bytes = omega_in_lds ? (((size_t)k.K + 3) & ~(size_t)3) * sizeof(float) : 0;
     // per-wave list of non-empty groups: as long as the longest row needs, at most 1022 entries
     uint32_t gcap = std::max<uint32_t>(1u, (uint32_t)std::min<int64_t>(d.max_row_groups, 1022));
-    auto list_bytes = [&](int waves) { return (size_t)waves * (gcap + 2) * 8; };
+    // per wave: the list (a pseudo group, the groups, two sentinels), the batch's bitmap and its word prefix
+    auto list_bytes = [&](int waves) { return (size_t)waves * ((gcap + 3) * 8 + GemvShape<IdxT>::NWORDS * 8); };
     const bool x_in_lds = gemv_stages_x(d, o);
     const size_t fixed = (x_in_lds ? x_bytes : 0) + om_bytes;
     // a workgroup that stages a large X should own many rows: 16 waves; small X: 4 waves, more workgroups
@@ -438,22 +506,21 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
     const bool vec4 = (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && k.n >= 4;
     using Kern = void (*)(KView, const float*, float*, const float*, uint32_t, int, uint32_t);
     Kern kern;
-    const bool few = gcap <= 62 && k.K <= 64;  // gcap is still the longest row's number of groups here
-    const bool one = few && rows_per_block == (uint32_t)waves;  // a wave has at most one row
-#define CER_GEMV_PICK(CSER, FEW, ONE)                                                            \
-    (x_in_lds ? (vec4 ? cer_gemv_kernel<IdxT, true, true, CSER, FEW, ONE>                        \
-                      : cer_gemv_kernel<IdxT, true, false, CSER, FEW, ONE>)                      \
-              : cer_gemv_kernel<IdxT, false, false, CSER, FEW, ONE>)
+    const bool one = rows_per_block == (uint32_t)waves;  // a wave has at most one row
+#define CER_GEMV_PICK(CSER, ONE)                                                                 \
+    (x_in_lds ? (vec4 ? cer_gemv_kernel<IdxT, true, true, CSER, ONE>                             \
+                      : cer_gemv_kernel<IdxT, true, false, CSER, ONE>)                           \
+              : cer_gemv_kernel<IdxT, false, false, CSER, ONE>)
     if (k.cser)
-        kern = one ? CER_GEMV_PICK(true, true, true) : few ? CER_GEMV_PICK(true, true, false) : CER_GEMV_PICK(true, false, false);
+        kern = one ? CER_GEMV_PICK(true, true) : CER_GEMV_PICK(true, false);
     else
-        kern = one ? CER_GEMV_PICK(false, true, true) : few ? CER_GEMV_PICK(false, true, false) : CER_GEMV_PICK(false, false, false);
+        kern = one ? CER_GEMV_PICK(false, true) : CER_GEMV_PICK(false, false);
 #undef CER_GEMV_PICK
     if (lds > 48 * 1024) {
-        static LdsGrant<3 * 18> grant;  // per index width
-        const int kslot = (x_in_lds ? (vec4 ? 2 : 1) : 0) + (k.cser ? 3 : 0) + (few ? 6 : 0) + (one ? 6 : 0);
+        static LdsGrant<3 * 12> grant;  // per index width
+        const int kslot = (x_in_lds ? (vec4 ? 2 : 1) : 0) + (k.cser ? 3 : 0) + (one ? 6 : 0);
         const int wslot = sizeof(IdxT) == 1 ? 0 : (sizeof(IdxT) == 2 ? 1 : 2);
-        const hipError_t e = grant.ensure(wslot * 18 + kslot, reinterpret_cast<const void*>(kern), budget);
+        const hipError_t e = grant.ensure(wslot * 12 + kslot, reinterpret_cast<const void*>(kern), budget);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(waves * kWave), lds, stream, k, X, Y, T, rows_per_block,
