@@ -17,7 +17,10 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-u
          # fp32 division rounds correctly (the quantizer's codes must equal a binary32 reference bit for bit)
          "-fhip-fp32-correctly-rounded-divide-sqrt",
          # packed-fp32 instructions are kept out of the generated code on purpose
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # the first 16 dwords of a kernel's arguments arrive in scalar registers with the wave (kernels whose leading
+         # arguments are plain pointers and integers start without waiting for a load of their arguments)
+         "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 
 
 def _compile(src: str, verbose: bool) -> str:

@@ -123,10 +123,19 @@ __device__ __forceinline__ void gemv_batch(const uint4 (&ix)[GemvShape<IdxT>::NW
 // kOneRow: the launch gives every wave at most one row (matrices of up to 16 rows per compute unit and workgroup
 // slot), so the loop over a wave's rows and what it keeps alive fall away.
 template <typename IdxT, bool kXinLds, bool kVec4, bool kCser, bool kOneRow>
-__global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
-                                                        const float* __restrict__ T, uint32_t rows_per_block,
-                                                        int omega_in_lds, uint32_t gcap) {
+__global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__ colI_, const uint2* __restrict__ rowInfo_,
+                                                        const float* __restrict__ X, float* __restrict__ Y,
+                                                        const uint32_t* __restrict__ omegaPtr_, const float* __restrict__ omega_,
+                                                        uint32_t n_, uint32_t m_, uint32_t K_, uint32_t rows_per_block,
+                                                        uint32_t gcap, float omega0_, const void* __restrict__ omegaI_,
+                                                        const float* __restrict__ T, int omegaI_bits_, int omega_in_lds) {
+    // Plain pointers and integers, the ones the first instructions need in front: the first 16 dwords of a kernel's
+    // arguments are preloaded into scalar registers when the wave is launched (the library is built with kernel-
+    // argument preloading), so the row descriptor and the first X loads do not wait for a load of the arguments.
     using S = GemvShape<IdxT>;
+    KView v;
+    v.colI = colI_; v.omegaPtr = omegaPtr_; v.rowPtr = nullptr; v.rowInfo = rowInfo_; v.omegaI = omegaI_; v.omega = omega_;
+    v.K = K_; v.omegaI_bits = omegaI_bits_; v.cser = kCser ? 1 : 0; v.m = m_; v.n = n_; v.omega0 = omega0_;
     extern __shared__ __align__(16) unsigned char smem[];
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = uniform(threadIdx.x >> 6);
@@ -176,6 +185,16 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
     const float om_r = v.omega[threadIdx.x < v.K ? threadIdx.x : 0u];
     const float om_l = v.omega[lane < v.K ? lane : 0u];  // Omega[lane]: lets a wave look values up by lane shuffle
     __builtin_amdgcn_sched_barrier(0);
+    // The waves do not meet at a barrier once X is staged (that would make every wave wait for the slowest one's group
+    // list and weights): each wave counts itself in when its part of X is in LDS and, before its first gather, waits
+    // until all have.  The counter starts at zero: one early barrier, which every wave reaches before it waits for
+    // anything (and which keeps the X loads of the whole workgroup ahead of the first index load in the memory pipe).
+    __shared__ uint32_t s_staged;
+    if (kXinLds || omega_in_lds) {
+        if (threadIdx.x == 0) s_staged = 0u;
+        __syncthreads();
+    }
+    __builtin_amdgcn_sched_barrier(0);
 
     // (3) first row: its first 64 group pointers and the indices of its first batch, all unconditional.  A batch
     //     starts at a multiple of PPL positions; what lies in front of the row gets the weight 0.
@@ -208,6 +227,10 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
         if (threadIdx.x < v.K) oms[threadIdx.x] = om_r;
         for (uint32_t i = blockDim.x + threadIdx.x; i < v.K; i += blockDim.x) oms[i] = v.omega[i];
     }
+    if (kXinLds || omega_in_lds) {
+        wave_lds_sync();  // the LDS operations of a wave are executed in order: its stores, then its count
+        if (lane == 0) __hip_atomic_fetch_add(&s_staged, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
     // With at most 64 values and at most 64 raw groups in the first row, its group list, the first batch's bitmap and
     // the weights of the first batch are built here, before the workgroup barrier, from the pointer tile (which
     // arrives ahead of the indices) and a lane shuffle of Omega.
@@ -227,7 +250,15 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(KView v, const float* __
             for (int W = 0; W < S::NW; ++W) window_weights<S>(W, bmp, wpre, wts, lane, wl0[W]);
         }
     }
-    if (kXinLds || omega_in_lds) __syncthreads();
+    if (kXinLds || omega_in_lds) {
+        // every wave of the workgroup has counted itself in, or will without waiting for anything but its own loads;
+        // the bound on the spin only keeps a broken launch from hanging
+        for (uint32_t spin = 0; spin < (1u << 22); ++spin) {
+            if (__hip_atomic_load(&s_staged, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) >= nwaves) break;
+            __builtin_amdgcn_s_sleep(1);
+        }
+        wave_lds_sync();
+    }
 
     // Appendix A-A1: Omega[0] . sum_i X[i].  With X staged in LDS the workgroup sums it there (short per-thread
     // chains, then a tree); otherwise the launcher has computed it into T.
@@ -504,7 +535,8 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
     const uint32_t rows_per_block = iters * waves;
     const uint32_t blocks = (k.m + rows_per_block - 1) / rows_per_block;
     const bool vec4 = (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && k.n >= 4;
-    using Kern = void (*)(KView, const float*, float*, const float*, uint32_t, int, uint32_t);
+    using Kern = void (*)(const void*, const uint2*, const float*, float*, const uint32_t*, const float*, uint32_t, uint32_t,
+                          uint32_t, uint32_t, uint32_t, float, const void*, const float*, int, int);
     Kern kern;
     const bool one = rows_per_block == (uint32_t)waves;  // a wave has at most one row
 #define CER_GEMV_PICK(CSER, ONE)                                                                 \
@@ -523,8 +555,8 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
         const hipError_t e = grant.ensure(wslot * 12 + kslot, reinterpret_cast<const void*>(kern), budget);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(waves * kWave), lds, stream, k, X, Y, T, rows_per_block,
-                       omega_in_lds ? 1 : 0, gcap);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(waves * kWave), lds, stream, k.colI, k.rowInfo, X, Y, k.omegaPtr, k.omega, k.n,
+                       k.m, k.K, rows_per_block, gcap, k.omega0, k.omegaI, T, k.omegaI_bits, omega_in_lds ? 1 : 0);
     return hipGetLastError();
 }
 
