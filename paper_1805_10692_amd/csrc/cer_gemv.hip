@@ -182,7 +182,6 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
         CER_STAGE_LOAD(0); CER_STAGE_LOAD(1); CER_STAGE_LOAD(2); CER_STAGE_LOAD(3);
         CER_STAGE_LOAD(4); CER_STAGE_LOAD(5); CER_STAGE_LOAD(6); CER_STAGE_LOAD(7);
     }
-    const float om_r = v.omega[threadIdx.x < v.K ? threadIdx.x : 0u];
     const float om_l = v.omega[lane < v.K ? lane : 0u];  // Omega[lane]: lets a wave look values up by lane shuffle
     __builtin_amdgcn_sched_barrier(0);
     // The waves do not meet at a barrier once X is staged (that would make every wave wait for the slowest one's group
@@ -224,8 +223,8 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
 #undef CER_STAGE_LOAD
 #undef CER_STAGE_IDX
     if (omega_in_lds) {
-        if (threadIdx.x < v.K) oms[threadIdx.x] = om_r;
-        for (uint32_t i = blockDim.x + threadIdx.x; i < v.K; i += blockDim.x) oms[i] = v.omega[i];
+        if (threadIdx.x < min(v.K, (uint32_t)kWave)) oms[threadIdx.x] = om_l;  // the first wave
+        for (uint32_t i = kWave + threadIdx.x; i < v.K; i += blockDim.x) oms[i] = v.omega[i];
     }
     if (kXinLds || omega_in_lds) {
         wave_lds_sync();  // the LDS operations of a wave are executed in order: its stores, then its count
