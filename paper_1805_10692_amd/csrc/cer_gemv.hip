@@ -520,8 +520,16 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
     auto list_bytes = [&](int waves) { return (size_t)waves * ((gcap + 3) * 8 + GemvShape<IdxT>::NWORDS * 8); };
     const bool x_in_lds = gemv_stages_x(d, o);
     const size_t fixed = (x_in_lds ? x_bytes : 0) + om_bytes;
-    // a workgroup that stages a large X should own many rows: 16 waves; small X: 4 waves, more workgroups
-    int waves = (x_in_lds && x_bytes > 40 * 1024) ? 16 : 4;
+    // Staging X is what a launch costs a compute unit (about 26 clocks of its vector-memory pipeline per kilobyte), so
+    // X should be staged once per compute unit: as many waves per workgroup as the rows spread over all compute units
+    // need, at most 16 (a power of two); matrices of few rows get small workgroups on every compute unit.
+    // An X of a few kilobytes costs little to stage: workgroups of 4 waves, several per compute unit (measured equal or
+    // faster on 2048 x 2048 and 512 x 4608 matrices).
+    int waves = 4;
+    if (x_in_lds && x_bytes > 24 * 1024) {
+        const uint32_t per_unit = (k.m + (uint32_t)d.cus - 1) / (uint32_t)d.cus;
+        waves = (int)std::min<uint32_t>(16u, pow2_ceil(std::max<uint32_t>(per_unit, 4u)));
+    }
     while (fixed + list_bytes(waves) > budget && waves > 4) waves >>= 1;
     while (fixed + list_bytes(waves) > budget && gcap > 64) gcap = std::max<uint32_t>(64u, gcap / 2);
     const size_t lds = fixed + list_bytes(waves);
