@@ -108,22 +108,32 @@ struct PtrTile {
     uint32_t s, e, rank;
 };
 
-// Loads for raw groups j0 + lane, clamped to the tile so that every lane issues the same straight-line loads; lanes
-// past the tile read as an empty group.  One vector-memory instruction for the pointers (a wave instruction costs the
-// memory pipeline the same whatever it fetches): a lane's group ends where its right-hand neighbour's begins, so the
-// end comes from the neighbour lane (DPP wave_shl:1); the last lane of a full tile loads its own.  OmegaPtr / OmegaI are
-// padded.
+// Loads for raw groups j0 + lane, clamped to the tile so that every lane issues the same
+// straight-line loads; lanes past the tile read as an empty group.  OmegaPtr / OmegaI are padded.
 __device__ __forceinline__ PtrTile load_ptr_tile(const KView& v, bool cser, uint32_t g0, uint32_t j0, uint32_t tg_end,
                                                  uint32_t lane) {
+    const uint32_t g = j0 + lane;
+    const uint32_t gc = g < tg_end ? g : (tg_end > j0 ? tg_end - 1u : j0);
+    PtrTile p;
+    p.s = v.omegaPtr[gc];
+    p.e = v.omegaPtr[gc + 1];
+    p.rank = cser ? load_rank(v.omegaI, v.omegaI_bits, gc) : gc - g0 + 1u;
+    if (g >= tg_end) p.e = p.s;
+    return p;
+}
+
+// The same for the first tile of a row, which in most matrices is the row's only one and holds fewer than 64 groups:
+// one vector-memory instruction for the pointers instead of two (a wave instruction costs the memory pipeline the
+// same whatever it fetches) -- a lane's group ends where its right-hand neighbour's begins, so the end comes from
+// the neighbour lane (DPP wave_shl:1).  A full tile takes the two independent loads above.
+__device__ __forceinline__ PtrTile load_ptr_tile_first(const KView& v, bool cser, uint32_t g0, uint32_t j0, uint32_t tg_end,
+                                                 uint32_t lane) {
+    if (tg_end > j0 && tg_end - j0 >= (uint32_t)kWave) return load_ptr_tile(v, cser, g0, j0, tg_end, lane);  // wave-uniform
     const uint32_t g = j0 + lane;
     const uint32_t gc = min(g, tg_end);  // lanes past the tile load the tile's end pointer
     PtrTile p;
     p.s = v.omegaPtr[gc];
     p.e = (uint32_t)__builtin_amdgcn_update_dpp((int)p.s, (int)p.s, 0x130 /* wave_shl:1 */, 0xF, 0xF, false);
-    if (tg_end - j0 >= (uint32_t)kWave && tg_end > j0) {  // wave-uniform: a full tile
-        const uint32_t e_last = v.omegaPtr[j0 + kWave];
-        if (lane == kWave - 1) p.e = e_last;
-    }
     const uint32_t gr = g < tg_end ? g : (tg_end > j0 ? tg_end - 1u : j0);
     p.rank = cser ? load_rank(v.omegaI, v.omegaI_bits, gr) : gr - g0 + 1u;
     if (g >= tg_end) p.e = p.s;

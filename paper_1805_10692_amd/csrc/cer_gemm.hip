@@ -120,7 +120,7 @@ __global__ __launch_bounds__(256) void cer_gemm_kernel(KView v, const float* __r
     // indices of the first batches -- so that their latencies overlap instead of adding up.
     const bool cser = v.cser != 0;
     const uint32_t tg_end0 = min(g1, g0 + (uint32_t)kGemmGroupTile);
-    const PtrTile pt0 = load_ptr_tile(v, cser, g0, g0, min(tg_end0, g0 + (uint32_t)kWave), lane);
+    const PtrTile pt0 = load_ptr_tile_first(v, cser, g0, g0, min(tg_end0, g0 + (uint32_t)kWave), lane);
     const float om_l = v.omega[lane < v.K ? lane : 0u];
     uint32_t iq[GemmIdx<P>::D][GemmIdx<P>::KQ];
 #pragma unroll
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const flo
         const uint32_t c1 = min(re, c0 + (uint32_t)kExpChunk);
         // request order = arrival order: the chunk's first 64 group pointers, then its indices, then (below) the
         // first gathers; the expansion then waits for the pointers only and runs under the gathers' L2 latency
-        const PtrTile p_first = load_ptr_tile(v, cser, g0, gcur, g1, lane);
+        const PtrTile p_first = load_ptr_tile_first(v, cser, g0, gcur, g1, lane);
         const uint32_t g_first = gcur;
         uint32_t iq[D][KQ];
 #pragma unroll

@@ -197,7 +197,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
 
     // (3) first row: its first 64 group pointers and the indices of its first batch, all unconditional.  A batch
     //     starts at a multiple of PPL positions; what lies in front of the row gets the weight 0.
-    const PtrTile pt0 = load_ptr_tile(v, kCser, g0, g0, min(g1, g0 + min(gcap, (uint32_t)kWave)), lane);
+    const PtrTile pt0 = load_ptr_tile_first(v, kCser, g0, g0, min(g1, g0 + min(gcap, (uint32_t)kWave)), lane);
     uint4 idx0[S::NW];  // used by one piece of code only (no merge with re-loaded values, which would make the
                         // compiler wait for all of them at the merge point)
     const uint32_t b00 = rs & ~((uint32_t)S::PPL - 1u);
@@ -283,8 +283,29 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
     // everything else -- later batches, rows with many groups, later rows -- goes through the general loop below.
     float acc0 = 0.f, acc1 = 0.f;
     bool resume = false;
+    uint32_t te0 = re;  // end of the first row's first tile of groups
+    if (count0 < 0 && r < row_end && g1 > g0) {
+        // more than 64 values or raw groups: the list of the first tile is built here, with Omega from LDS; the
+        // indices of its first batch are the ones requested in the prologue
+        const uint32_t tg_end0 = min(g1, g0 + gcap);
+        if (tg_end0 != g1) te0 = uniform(v.omegaPtr[tg_end0]);
+        if (lane == 0) { ends[0] = rs; wts[0] = 0.f; }
+        count0 = 1;
+        for (uint32_t j0 = g0; j0 < tg_end0; j0 += kWave) {
+            const PtrTile p = j0 == g0 ? pt0 : load_ptr_tile(v, kCser, g0, j0, tg_end0, lane);
+            count0 = list_append(p, omega[p.rank < v.K ? p.rank : 0u] - v.omega0, ends, wts, count0);
+        }
+        list_close(ends, wts, count0, lane);
+        if (count0 > 1) {
+            wave_lds_sync();
+            first = rs > b00 ? 0u : 1u;
+            bitmap_build<S>(ends, (uint32_t)count0 + 1u, first, b00, bmp, wpre, lane);
+#pragma unroll
+            for (int W = 0; W < S::NW; ++W) window_weights<S>(W, bmp, wpre, wts, lane, wl0[W]);
+        }
+    }
     if (r < row_end && count0 > 1) {
-        gemv_batch<IdxT>(idx0, xsrc, b00, re, wl0, acc0, acc1);
+        gemv_batch<IdxT>(idx0, xsrc, b00, te0, wl0, acc0, acc1);
         resume = true;
     }
 
@@ -300,7 +321,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
             const uint32_t tg_end = min(g1, tg + gcap);
             const uint32_t ts = tg == g0 ? rs : uniform(v.omegaPtr[tg]);
             const uint32_t te = tg_end == g1 ? re : uniform(v.omegaPtr[tg_end]);
-            const bool resumed = first_row && resume;  // single tile, first batch done, list live
+            const bool resumed = first_row && resume && tg == g0;  // the tile's first batch is done, its list is live
             uint32_t b0 = ts & ~((uint32_t)S::PPL - 1u);
             int count;
             if (resumed) {
