@@ -91,16 +91,18 @@ def algorithmic_bytes(dims: dict, bits: dict, L: int) -> int:
 
 
 def read_traffic(workload: str, fmt: str):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", f"traffic_{fmt}_{workload}.txt")
+    """(HBM bytes per launch, where they come from).  The counters are not collected in this run: the figure is the one
+    recorded in the committed rocprofv3 --pmc summary of the same command, if there is one (None otherwise)."""
+    rel = os.path.join("profiles", f"traffic_{fmt}_{workload}.txt")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
+        return None, None
     txt = open(path).read()
     f = re.search(r"^fetch_bytes_per_launch:\s*([0-9.eE+]+)", txt, re.M)
     w = re.search(r"^write_bytes_per_launch:\s*([0-9.eE+]+)", txt, re.M)
     if not f or not w:
-        return None
-    return float(f.group(1)) + float(w.group(1))
+        return None, None
+    return float(f.group(1)) + float(w.group(1)), rel + " (recorded rocprofv3 --pmc runs of this command; not collected in this run)"
 
 
 def time_steps(fn, steps: int, warmup: int):
@@ -158,7 +160,9 @@ def probe_stream(nbytes: int, steps: int = 1000) -> dict:
             "read_only_frac_of_peak": nbytes / (ev_big * 1e-3) / 1e9 / HBM_PEAK_GBS, "empty_launch_us": ev_tiny * 1e3}
 
 
-def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: bool, with_dense: bool, opts=None) -> dict:
+def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: bool, with_dense: bool, opts=None,
+            cpu_timing: bool = True) -> dict:
+    """with_cpu: the oracle checks sampled rows of the timed buffers (and, with cpu_timing, is timed as cpu_baseline)."""
     import torch
 
     from paper_1805_10692_amd import binding as B
@@ -284,7 +288,7 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
         out["speedup_vs_dense_rocblas"] = t_wall / wall_ms
         del Wd
 
-    if with_cpu:
+    if with_cpu and cpu_timing:
         import oracle
         A = oracle.csr_encode(w.W) if fmt == "csr" else oracle.encode(w.W, w.codebook, fmt)
         odot = (lambda th: oracle.dot_csr(A, w.X)) if fmt == "csr" else (lambda th: oracle.dot(A, w.X, threads=th))
@@ -451,6 +455,7 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-probe", action="store_true", help="skip the read-only stream probe of the batch-1 line")
+    ap.add_argument("--no-steady", action="store_true", help="skip the HBM-bound companion measurement of the default line")
     ap.add_argument("--probe-copy", type=int, default=0, metavar="MiB",
                     help="also launch the plain copy kernel on this many MiB (calibrates byte counters)")
     ap.add_argument("--path", type=int, default=-1, help="kernel to prefer (numbering of cer_matmul_path), -1 = the library's choice")
@@ -483,7 +488,7 @@ def main() -> int:
         from paper_1805_10692_amd import binding as B
         opts = B.MatmulOpts(path=args.path, tile_cols=args.tile_cols, flags=args.flags)
     r = run_one(args.workload, args.format, args.steps, args.warmup, args.warm, not args.no_cpu, not args.no_dense, opts)
-    traffic = read_traffic(args.workload, args.format)
+    traffic, traffic_source = read_traffic(args.workload, args.format)
     line = {
         "metric": METRIC, "value": r["dense_equiv_gflops"], "unit": "GFLOP/s (dense-equivalent, 2*m*n*L/t)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
@@ -491,7 +496,7 @@ def main() -> int:
         "config": {k: r[k] for k in ("workload", "format", "m", "n", "L", "K", "nnz", "groups", "H_bits", "p0",
                                      "k_bar", "k_tilde", "cache_state", "path")},
         "roofline": {"bound": "hbm", "achieved": r["algorithmic_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": r["algorithmic_GBps"] / HBM_PEAK_GBS, "traffic": traffic,
+                     "frac": r["algorithmic_GBps"] / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": kernel_name(args.format, r["L"], r["path"]),
                      "algorithmic_bytes_per_launch": r["algorithmic_bytes"],
                      "event_us_per_launch": r["event_ms_per_step"] * 1e3},
@@ -508,6 +513,24 @@ def main() -> int:
         sp = probe_stream(r["algorithmic_bytes"])
         line["roofline"]["stream_probe"] = sp
         line["roofline"]["frac_of_read_only_launch"] = sp["read_only_launch_us"] / (r["event_ms_per_step"] * 1e3)
+    if args.workload == ap.get_default("workload") and not args.warm and not args.no_steady and args.format != "csr":
+        # The default workload is 10.6 MB, about the size of a launch.  The same kernel where HBM is the roof: a 4096 x
+        # 9216 layer quantized to 7 bits (57 MB of indices), cold, with a read-only launch of the same bytes beside it.
+        sname = "quant7_fc6_L1"
+        rs = run_one(sname, args.format, min(args.steps, 1000), min(args.warmup, 100), False, not args.no_cpu, False, opts,
+                     cpu_timing=False)
+        st, st_src = read_traffic(sname, args.format)
+        steady = {"workload": sname, "bound": "hbm", "achieved": rs["algorithmic_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                  "frac": rs["algorithmic_GBps"] / HBM_PEAK_GBS, "traffic": st, "traffic_source": st_src,
+                  "kernel": kernel_name(args.format, rs["L"], rs["path"]),
+                  "algorithmic_bytes_per_launch": rs["algorithmic_bytes"], "event_us_per_launch": rs["event_ms_per_step"] * 1e3,
+                  "m": rs["m"], "n": rs["n"], "nnz": rs["nnz"], "K": rs["K"], "H_bits": rs["H_bits"], "p0": rs["p0"],
+                  "cache_state": rs["cache_state"]}
+        if not args.no_probe:
+            sp = probe_stream(rs["algorithmic_bytes"], steps=300)
+            steady["stream_probe"] = sp
+            steady["frac_of_read_only_launch"] = sp["read_only_launch_us"] / (rs["event_ms_per_step"] * 1e3)
+        line["roofline_steady"] = steady
     print(json.dumps(line), flush=True)
 
     if args.report:

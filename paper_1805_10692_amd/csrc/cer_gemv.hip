@@ -171,8 +171,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
     // (2) X and Omega on their way to LDS: up to eight 16-byte loads per thread, only those that hold part of X
     //     (wave-uniform tests), in named registers (an indexed array would end up in scratch memory)
     typedef float F4 __attribute__((ext_vector_type(4)));
-    F4 xr0, xr1, xr2, xr3, xr4, xr5, xr6, xr7;
-    xr0 = xr1 = xr2 = xr3 = xr4 = xr5 = xr6 = xr7 = F4{0.f, 0.f, 0.f, 0.f};
+    F4 xr0, xr1, xr2, xr3, xr4, xr5, xr6, xr7;  // a register is stored only where it was loaded (the same bound)
     const uint32_t n4 = kVec4 ? (v.n >> 2) : 0u;
     const F4* X4 = reinterpret_cast<const F4*>(X);
     const uint32_t wave_first = wave * kWave;  // the wave's first thread
