@@ -78,7 +78,8 @@ def kernel_name(fmt: str, L: int, path) -> str:
         return "csr_gemv_kernel" if L == 1 else "csr_gemm_kernel"
     return {0: "cer_gemv_kernel",
             1: "cer_gemm_expand_kernel",
-            2: "cer_xtile_kernel", 3: "decode_kernel + dense_gemm_mfma_kernel", 4: "cer_gemv_expand_kernel"}[path]
+            2: "cer_xtile_kernel", 3: "decode_kernel + dense_gemm_mfma_kernel", 4: "cer_gemv_expand_kernel",
+            5: "cer_strip_kernel"}[path]
 
 
 def algorithmic_bytes(dims: dict, bits: dict, L: int) -> int:
@@ -204,6 +205,8 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
         import oracle
         want, scale = oracle.dot_dense(Wr, w.X, threads=8), oracle.abs_dot_dense(Wr, w.X, threads=8)
     if opts is not None and fmt != "csr":
+        if opts.path == B.CER_PATH_STRIP:
+            B.cer_prepare_strips(h0)
         B.cer_matmul_ex(h0, Xd, Yd, L, None, opts)
     else:
         mm(h0, Xd, Yd, L)
@@ -218,6 +221,9 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
     R = 1 if warm else max(2, -(-2 * LAST_LEVEL_CACHE_BYTES // max(fmt_bytes, 1)))
     R = min(R, 256)
     handles = [h0] + [clone(h0) for _ in range(R - 1)]
+    if opts is not None and fmt != "csr" and opts.path == B.CER_PATH_STRIP:
+        for h in handles:
+            B.cer_prepare_strips(h)   # the strip-major index is per device copy
     stream = torch.cuda.current_stream().cuda_stream
     lib = B.lib()
     cfn = {"cer": lib.cer_matmul, "cser": lib.cser_matmul, "csr": lib.csr_matmul}[fmt]

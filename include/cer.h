@@ -172,6 +172,8 @@ int cer_trim(void);
  *      decode and the dense contraction: wide batches of matrices with more than about one
  *      indexed element in five, any batch > 1 of matrices with most elements indexed.  The
  *      arithmetic is then that of a dense fp32 product (same error bound), not Algorithm 3 / 4.
+ *   5  CER_PATH_STRIP: batched kernel with strips of 1024 input rows resident in LDS (see cer_prepare_strips);
+ *      never chosen by the library itself
  * On MI355X kernel 2 beats kernel 1 for narrow batches of large matrices (kernel 1 moves a whole
  * 128-byte line per index however narrow the batch) and loses for wide ones (random LDS gathers
  * are bank-conflict bound): it is chosen when it is applicable, batch <= 8 and the matrix holds
@@ -203,7 +205,7 @@ int cer_matmul_path(const cer_handle_t* h, int64_t batch);
  * undefined path, tile width or flag.
  */
 enum { CER_PATH_AUTO = -1, CER_PATH_GEMV = 0, CER_PATH_GEMM = 1, CER_PATH_XTILE = 2, CER_PATH_DENSE = 3,
-       CER_PATH_GEMV_EXPAND = 4 };
+       CER_PATH_GEMV_EXPAND = 4, CER_PATH_STRIP = 5 };
 enum { CER_OPT_SUM_THEN_MULTIPLY = 1, CER_OPT_ROWS_WHOLE = 2, CER_OPT_X_FROM_GLOBAL = 4,
        CER_OPT_ONE_COLUMN_PER_LANE = 8, CER_OPT_SHORT_CHUNKS = 16, CER_OPT_LONG_CHUNKS = 32 };
 typedef struct {
@@ -215,6 +217,22 @@ typedef struct {
 int cer_matmul_ex(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t batch, void* stream,
                   const cer_matmul_opts_t* opts);
 int cer_matmul_path_ex(const cer_handle_t* h, int64_t batch, const cer_matmul_opts_t* opts);
+
+/*
+ * cer_prepare_strips -- builds, once per handle, the strip-major index that kernel 5 (CER_PATH_STRIP) needs: the
+ * column-blocked reuse of input elements (Section V-C).  X is cut into strips of 1024 consecutive rows; for
+ * every strip and every row of W the index lists the row's indexed elements whose column falls into the strip, each
+ * as 16 bits: the column inside the strip (10 bits) and the rank of the element's value in Omega (6 bits).  It is
+ * DERIVED from the format arrays (which stay as they are): 2 bytes per indexed element plus 4 bytes per strip and
+ * row of device memory.  Kernel 5 copies one strip of 32 batch columns into LDS per workgroup (128 KB), multiplies
+ * every element of the strip's share of its rows by Omega[rank] - Omega[0], and leaves one partial sum per strip and
+ * row in a stream-ordered temporary of strips x m x batch floats, which a second kernel adds up in strip order.
+ * Applicable to codebooks of at most 64 values (CER_E_TOO_LARGE otherwise), batches that are a multiple of 32 columns
+ * and 16-byte aligned X and Y; it runs only when cer_matmul_ex prefers CER_PATH_STRIP.
+ * Not thread-safe against products running on the same handle: call it before the handle is shared.  A second call
+ * is a no-op.  Errors: CER_E_INVALID, CER_E_TOO_LARGE, CER_E_NOMEM, CER_E_HIP (no device copy, allocation failed).
+ */
+int cer_prepare_strips(cer_handle_t* h);
 
 /*
  * cer_decode / cser_decode -- arrays -> dense matrix (Section II-A: M can be reconstructed

@@ -35,12 +35,12 @@ EXPORTS = [
     "csr_encode", "csr_matmul", "csr_decode", "csr_get_array", "csr_storage_bits", "csr_device_bytes",
     "csr_clone_device", "csr_free", "cer_cost_model", "csr_cost_model", "dense_cost_model",
     "cer_encode_device", "cer_quantize_uniform", "cer_quantize_encode_device", "cer_matmul_path", "cer_stream_read",
-    "cer_decode_device", "cer_trim", "cer_matmul_ex", "cer_matmul_path_ex", "cer_matmul_noalloc",
+    "cer_decode_device", "cer_trim", "cer_matmul_ex", "cer_matmul_path_ex", "cer_matmul_noalloc", "cer_prepare_strips",
 ]
 
 CER_FORMAT_CER, CER_FORMAT_CSER = 0, 1
 
-CER_PATH_AUTO, CER_PATH_GEMV, CER_PATH_GEMM, CER_PATH_XTILE, CER_PATH_DENSE, CER_PATH_GEMV_EXPAND = -1, 0, 1, 2, 3, 4
+CER_PATH_AUTO, CER_PATH_GEMV, CER_PATH_GEMM, CER_PATH_XTILE, CER_PATH_DENSE, CER_PATH_GEMV_EXPAND, CER_PATH_STRIP = -1, 0, 1, 2, 3, 4, 5
 CER_OPT_SUM_THEN_MULTIPLY, CER_OPT_ROWS_WHOLE, CER_OPT_X_FROM_GLOBAL = 1, 2, 4
 CER_OPT_ONE_COLUMN_PER_LANE, CER_OPT_SHORT_CHUNKS, CER_OPT_LONG_CHUNKS = 8, 16, 32
 
@@ -147,6 +147,8 @@ def lib() -> ctypes.CDLL:
         L.cer_trim.argtypes = []
         L.cer_matmul_path.restype = ctypes.c_int
         L.cer_matmul_path.argtypes = [vp, i64]
+        L.cer_prepare_strips.restype = ctypes.c_int
+        L.cer_prepare_strips.argtypes = [vp]
         L.cer_matmul_noalloc.restype = ctypes.c_int
         L.cer_matmul_noalloc.argtypes = [vp, vp, vp, i64, vp]
         L.cer_matmul_ex.restype = ctypes.c_int
@@ -295,6 +297,11 @@ def cer_matmul_path(h: Handle, batch: int) -> int:
 def cer_matmul_ex(h: Handle, X, Y, batch: int, stream=None, opts: "MatmulOpts | None" = None) -> None:
     _check(lib().cer_matmul_ex(h.ptr, _dev_ptr(X), _dev_ptr(Y), batch, _stream_ptr(stream),
                                ctypes.byref(opts) if opts is not None else None), "cer_matmul_ex")
+
+
+def cer_prepare_strips(h: Handle) -> None:
+    """Builds the strip-major index that cer_matmul_ex needs for CER_PATH_STRIP (once per handle)."""
+    _check(lib().cer_prepare_strips(h.ptr), "cer_prepare_strips")
 
 
 def cer_matmul_noalloc(h: Handle, X, Y, batch: int, stream=None) -> None:

@@ -11,7 +11,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcer_hip.so")
-SOURCES = ["cer_host.cpp", "cer_capi.cpp", "cer_gemv.hip", "cer_gemm.hip", "cer_xtile.hip", "cer_matmul.hip", "dense_kernels.hip", "csr.hip", "cost_model.cpp", "frontend.hip"]
+SOURCES = ["cer_host.cpp", "cer_capi.cpp", "cer_gemv.hip", "cer_gemm.hip", "cer_xtile.hip", "cer_strip.hip", "cer_matmul.hip", "dense_kernels.hip", "csr.hip", "cost_model.cpp", "frontend.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",
          # fp32 division rounds correctly (the quantizer's codes must equal a binary32 reference bit for bit)

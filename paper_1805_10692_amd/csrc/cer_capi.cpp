@@ -362,7 +362,7 @@ bool read_options(const cer_matmul_opts_t* in, cer::MatmulOptions* out) {
     if (!in) return true;
     constexpr uint32_t known = CER_OPT_SUM_THEN_MULTIPLY | CER_OPT_ROWS_WHOLE | CER_OPT_X_FROM_GLOBAL |
                                CER_OPT_ONE_COLUMN_PER_LANE | CER_OPT_SHORT_CHUNKS | CER_OPT_LONG_CHUNKS;
-    if (in->path < CER_PATH_AUTO || in->path > CER_PATH_GEMV_EXPAND) return false;
+    if (in->path < CER_PATH_AUTO || in->path > CER_PATH_STRIP) return false;
     if (in->flags & ~known) return false;
     if ((in->flags & CER_OPT_SHORT_CHUNKS) && (in->flags & CER_OPT_LONG_CHUNKS)) return false;
     switch (in->tile_cols) {
@@ -607,6 +607,64 @@ int cer_quantize_uniform(const float* W, int64_t count, int32_t bits, uint8_t* c
     }
 }
 
+int cer_prepare_strips(cer_handle_t* h) {
+    if (!h) return CER_E_INVALID;
+    if (h->d_strip) return CER_OK;
+    const cer::HostMatrix& A = *h->host;
+    if (A.K > 64) return CER_E_TOO_LARGE;  // the rank shares 16 bits with the column inside the strip
+    if (h->device < 0 || !h->d_base) return hip_fail(hipErrorNoDevice);
+    if (A.m <= 0 || A.n <= 0) return CER_OK;
+    const int dc = check_device(h);
+    if (dc != CER_OK) return dc;
+    try {
+        const int rc = cer::ensure_host_arrays(h);
+        if (rc != CER_OK) return rc;
+        const uint64_t S = cer::kStripRows, ns = ((uint64_t)A.n + S - 1) / S, m = (uint64_t)A.m;
+        if (ns * (m + 1) > 0x7FFFFFFFull) return CER_E_TOO_LARGE;
+        // rank of every raw group (Algorithm 3: position in the row + 1; Algorithm 4: OmegaI)
+        std::vector<uint32_t> ptr((size_t)(ns * (m + 1)) + 1, 0u);
+        auto for_each = [&](auto&& fn) {
+            for (uint64_t r = 0; r < m; ++r) {
+                const uint64_t ga = A.rowPtr.at((int64_t)r), gb = A.rowPtr.at((int64_t)r + 1);
+                for (uint64_t g = ga; g < gb; ++g) {
+                    const uint32_t rank = A.cser ? (uint32_t)A.omegaI.at((int64_t)g) : (uint32_t)(g - ga + 1);
+                    const uint64_t pa = A.omegaPtr.at((int64_t)g), pb = A.omegaPtr.at((int64_t)g + 1);
+                    for (uint64_t p = pa; p < pb; ++p) fn(r, rank, (uint64_t)A.colI.at((int64_t)p));
+                }
+            }
+        };
+        for_each([&](uint64_t r, uint32_t, uint64_t c) { ++ptr[(size_t)((c / S) * (m + 1) + r) + 1]; });
+        // counts -> offsets; the entry after each strip's m rows stays a running total, so ptr[s * (m + 1) + m] closes row m - 1
+        for (size_t i = 1; i < ptr.size(); ++i) ptr[i] += ptr[i - 1];
+        std::vector<uint16_t> idx((size_t)A.nnz);
+        std::vector<uint32_t> fill(ptr.begin(), ptr.end() - 1);
+        for_each([&](uint64_t r, uint32_t rank, uint64_t c) {
+            const uint64_t s = c / S;
+            idx[fill[(size_t)(s * (m + 1) + r)]++] = (uint16_t)((rank << 10) | (uint32_t)(c - s * S));
+        });
+        const size_t idx_bytes = (idx.size() * 2 + 255) & ~(size_t)255, ptr_bytes = (ptr.size() - 1) * 4;
+        void* base = nullptr;
+        hipError_t e = hipMalloc(&base, idx_bytes + ptr_bytes + 256);
+        if (e != hipSuccess) return hip_fail(e);
+        auto* b8 = static_cast<unsigned char*>(base);
+        if (!idx.empty()) e = hipMemcpy(b8, idx.data(), idx.size() * 2, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(b8 + idx_bytes, ptr.data(), ptr_bytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            (void)hipFree(base);
+            return hip_fail(e);
+        }
+        h->d_strip = base;
+        h->view.strip_idx = base;
+        h->view.strip_ptr = reinterpret_cast<const uint32_t*>(b8 + idx_bytes);
+        h->view.n_strips = (uint32_t)ns;
+        return CER_OK;
+    } catch (const std::bad_alloc&) {
+        return CER_E_NOMEM;
+    } catch (...) {
+        return CER_E_INVALID;
+    }
+}
+
 int64_t cer_device_bytes(const cer_handle_t* h) { return (h && h->device >= 0) ? h->stream_bytes : 0; }
 
 int64_t cer_long_row_parts(const cer_handle_t* h) { return (h && h->device >= 0) ? (int64_t)h->view.n_split_parts : 0; }
@@ -615,6 +673,7 @@ void cer_free(cer_handle_t* h) {
     if (!h) return;
     if (h->d_base) (void)hipFree(h->d_base);
     if (h->d_split) (void)hipFree(h->d_split);
+    if (h->d_strip) (void)hipFree(h->d_strip);
     delete h;
 }
 

@@ -380,4 +380,8 @@ XtilePlan plan_xtile(const DeviceView& d, uint32_t L);
 hipError_t launch_xtile_any(const DeviceView& d, const XtilePlan& p, const float* X, float* Y, const float* T, uint32_t L,
                             hipStream_t stream);
 
+// cer_strip.hip -- batch > 1, strips of X resident in LDS (needs the strip-major index of cer_prepare_strips)
+bool strip_applicable(const DeviceView& d, const float* X, const float* Y, uint32_t L);
+hipError_t launch_strip(const DeviceView& d, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream);
+
 }  // namespace cer

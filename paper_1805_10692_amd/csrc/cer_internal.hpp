@@ -72,7 +72,14 @@ struct DeviceView {
     uint32_t n_split_parts = 0, n_split_rows = 0;
     uint32_t split_len = 0;  // positions per part
     uint32_t split_min = 0;  // rows with more positions than this are split
+    // Strip-major index (derived by cer_prepare_strips; null otherwise): for strip s (kStripRows consecutive columns of
+    // W) and row r, entries strip_ptr[s * (m + 1) + r] .. strip_ptr[s * (m + 1) + r + 1] of strip_idx, each
+    // (rank << 10) | (column - s * kStripRows) as uint16.
+    const void* strip_idx = nullptr;
+    const uint32_t* strip_ptr = nullptr;
+    uint32_t n_strips = 0;
 };
+constexpr uint32_t kStripRows = 1024;
 
 // The handle's single device allocation: [colI | 8 KiB readable pad][OmegaPtr u32][rowPtr u32][OmegaI][Omega]
 // [row descriptors], each part 256-byte aligned.  The row descriptors {rowPtr[r], OmegaPtr[rowPtr[r]]} are derived
@@ -101,6 +108,7 @@ struct MatmulOptions {
     int tile_cols = 0;  // batched kernels that gather from L2: batch columns per tile, 0 = the library's choice
     uint32_t flags = 0; // CER_OPT_* bits
 };
+constexpr int kPathStrip = 5;
 constexpr uint32_t kOptSumThenMultiply = 1, kOptRowsWhole = 2, kOptXFromGlobal = 4, kOptOneColumnPerLane = 8,
                    kOptShortChunks = 16, kOptLongChunks = 32;
 
@@ -153,6 +161,7 @@ struct cer_matrix {
     int device = -1;          // -1: host-only handle
     void* d_base = nullptr;   // the device allocation of the format arrays
     void* d_split = nullptr;  // row order and parts of long rows (a second, small allocation; null: rows of similar length)
+    void* d_strip = nullptr;  // strip-major index (cer_prepare_strips; null: not prepared)
     cer::DeviceLayout layout; // where the arrays sit inside it
     size_t d_bytes = 0;       // its size
     int64_t stream_bytes = 0; // bytes of format arrays a product reads

@@ -118,8 +118,12 @@ bool xtile_pays(const DeviceView& d, uint32_t L) { return L <= 8 && d.nnz >= 250
 // Which kernel serves a batch of L > 1 columns (cer_matmul_path's numbering: 1, 2 or 3).  A preferred kernel is
 // taken whenever it is applicable; otherwise the estimates decide.  no_temporaries: only kernels that need no
 // temporary memory (the decode + dense route and batches of more than one LDS tile are left out).
-int choose_batched_path(const DeviceView& d, uint32_t L, const MatmulOptions& o, bool no_temporaries, XtilePlan* plan_out) {
+int choose_batched_path(const DeviceView& d, uint32_t L, const MatmulOptions& o, bool no_temporaries, XtilePlan* plan_out,
+                        const float* X = nullptr, const float* Y = nullptr) {
     const bool has_elements = d.m > 0 && d.n > 0;
+    // strips of X in LDS: on request (and only when the strip-major index was prepared); the partial sums of the strips
+    // need a temporary.  X == nullptr: the question is asked without buffers (cer_matmul_path_ex): aligned ones assumed.
+    if (o.path == kPathStrip && !no_temporaries && strip_applicable(d, X, Y, L)) return kPathStrip;
     if (o.path == 3 && has_elements && !no_temporaries) return 3;
     if (o.path != 1 && o.path != 3) {
         const XtilePlan plan = plan_xtile(d, L);
@@ -194,7 +198,7 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
     MatmulOptions o = o_in;
     if (no_temporaries) o.flags |= kOptRowsWhole;  // the parts of split rows meet in a temporary
     XtilePlan plan;
-    const int batched_path = L > 1 ? choose_batched_path(d, L, o, no_temporaries, &plan) : 0;
+    const int batched_path = L > 1 ? choose_batched_path(d, L, o, no_temporaries, &plan, X, Y) : 0;
     if (batched_path == 3) return (int)launch_densified(d, X, Y, L, stream);
 
     float* T = nullptr;
@@ -222,6 +226,8 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
         e = launch_gemv_any(d, X, Y, T, stream, o);
     else if (batched_path == 2)
         e = launch_xtile_any(d, plan, X, Y, T, L, stream);
+    else if (batched_path == kPathStrip)
+        e = launch_strip(d, X, Y, T, L, stream);
     else
         e = launch_gemm_any(d, X, Y, T, L, stream, o);
     if (scratch) {

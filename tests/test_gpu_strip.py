@@ -1,0 +1,76 @@
+"""GPU parity of the batched kernel that keeps strips of 1024 input rows in LDS (the column-blocked reuse of input
+elements, Section V-C), preferred through cer_matmul_ex after cer_prepare_strips, against the oracle element by
+element under the bound of every other product, |Y - Y_oracle| <= 1e-5 * sum_c |W[r,c]| |X[c,l]|."""
+import numpy as np
+import pytest
+
+from paper_1805_10692_amd import binding as B
+from paper_1805_10692_amd import workloads as wl
+from test_gpu_parity import check, _gpu
+import oracle
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+STRIP = B.MatmulOpts(path=B.CER_PATH_STRIP)
+
+
+def strip_check(w, fmts=("cer", "cser"), expect=B.CER_PATH_STRIP):
+    dev = _gpu()
+    print(f"strip case {w.name} m={w.m} n={w.n} L={w.L}", flush=True)
+    scale = oracle.abs_dot_dense(w.W, w.X, threads=8)
+    Xd = torch.from_numpy(np.ascontiguousarray(w.X)).to(dev)
+    for fmt in fmts:
+        A = oracle.encode(w.W, w.codebook, fmt)
+        want = oracle.dot(A, w.X, threads=8)
+        h = (B.cer_encode if fmt == "cer" else B.cser_encode)(w.W, w.codebook)
+        assert B.cer_matmul_path_ex(h, w.L, STRIP) != B.CER_PATH_STRIP      # not before the index is built
+        B.cer_prepare_strips(h)
+        B.cer_prepare_strips(h)                                            # a second call changes nothing
+        assert B.cer_matmul_path_ex(h, w.L, STRIP) == expect
+        Yd = torch.full((w.m, w.L), float("nan"), dtype=torch.float32, device=dev)
+        B.cer_matmul_ex(h, Xd, Yd, w.L, None, STRIP)
+        torch.cuda.synchronize()
+        check(Yd.cpu().numpy(), want, scale, f"{w.name}/{fmt}")
+        B.cer_free(h)
+
+
+CASES = {
+    "alexnet_s8_L32": lambda: wl.alexnet_fc6(L=32, scale=8),              # n = 1152 + remainder: two strips
+    "vgg_s8_L64": lambda: wl.vgg_fc6(L=64, scale=8),                      # four strips, two tiles
+    "sweep_K64_p50_L32": lambda: wl.sweep_cell(64, 0.5, L=32, scale=4),   # 63 ranks: the limit
+    "sweep_K2_p70_L32": lambda: wl.sweep_cell(2, 0.7, L=32, scale=4),
+    "conv_s4_L96": lambda: wl.conv3x3(L=96, scale=4),
+    "conv_s4_dom_L96": lambda: wl.conv3x3(L=96, nonzero_dominant=True, scale=4),   # constant term added with the strips' sums
+    "one_strip": lambda: wl.random_lowentropy(m=70, n=250, K=6, p_dom=0.6, L=32, seed=32),
+    "strip_edge": lambda: wl.random_lowentropy(m=33, n=2048, K=5, p_dom=0.4, L=64, seed=61),    # exactly two full strips
+    "strip_edge_plus_one": lambda: wl.random_lowentropy(m=33, n=2049, K=5, p_dom=0.4, L=32, seed=62),
+    "wide_input": lambda: wl.random_lowentropy(m=9, n=70001, K=8, p_dom=0.9, L=32, seed=34),    # 69 strips, 32-bit colI
+    "one_row": lambda: wl.random_lowentropy(m=1, n=3000, K=16, p_dom=0.7, L=32, seed=36),
+    "constant": lambda: wl.random_lowentropy(m=10, n=100, K=1, p_dom=1.0, L=32, seed=38),
+    "sparse_rows": lambda: wl.random_lowentropy(m=333, n=900, K=5, p_dom=0.998, L=32, seed=45),  # most rows empty
+    "rows_1025": lambda: wl.random_lowentropy(m=1025, n=700, K=12, p_dom=0.85, L=160, seed=44),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_strip_kernel_all_elements(name):
+    strip_check(CASES[name]())
+
+
+def test_full_size_alexnet_fc6_batch32_and_vgg_fc6_batch64():
+    strip_check(wl.alexnet_fc6(L=32), fmts=("cer",))
+    strip_check(wl.vgg_fc6(L=64), fmts=("cser",))
+
+
+def test_not_applicable_cases_fall_back():
+    """Batch widths that are not multiples of 32 run the library's own choice; codebooks of more than 64 values cannot
+    be prepared."""
+    w = wl.random_lowentropy(m=67, n=1500, K=16, p_dom=0.8, L=40, seed=140)
+    strip_check(w, expect=B.CER_PATH_GEMM)
+    big = wl.random_lowentropy(m=40, n=2000, K=200, p_dom=0.3, L=32, seed=40, ratio=0.995)
+    h = B.cer_encode(big.W, big.codebook)
+    with pytest.raises(B.CerError) as e:
+        B.cer_prepare_strips(h)
+    assert e.value.code == B.CER_E_TOO_LARGE
+    B.cer_free(h)
