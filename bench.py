@@ -552,6 +552,13 @@ def main() -> int:
                     big = nm.startswith("conv")
                     rr = run_one(nm, fmt, 20 if big else 300, 3 if big else 30, warm, False, not warm)
                     table.append(rr)
+                    if fmt != "csr" and rr["path"] == 3:
+                        # the library chose decode + dense: the method's own number is the gather kernel's
+                        from paper_1805_10692_amd import binding as B
+                        rg = run_one(nm, fmt, 20 if big else 300, 3 if big else 30, warm, False, not warm,
+                                     B.MatmulOpts(path=B.CER_PATH_GEMM))
+                        rg["format"] = fmt + " (gather kernel)"
+                        table.append(rg)
                     print(f"[report] {nm} {fmt} {'warm' if warm else 'cold'}: {rr['ms_per_step'] * 1e3:.2f} us/step, "
                           f"{rr['algorithmic_GBps']:.0f} GB/s alg, speedup vs dense "
                           f"{rr.get('speedup_vs_dense_hip', float('nan')):.2f}", file=sys.stderr, flush=True)

@@ -5,8 +5,8 @@
  * one of K codebook values) in the two formats of Wiedemann, Mueller, Samek, "Compact and
  * Computationally Efficient Representation of Deep Neural Networks":
  *
- *   CER  (Compressed Entropy Row,          Section II-A): Omega, colI, OmegaPtr, rowPtr
- *   CSER (Compressed Shared Elements Row,  Section II-A): the same plus OmegaI
+ *   CER  (Compressed Entropy Row,          Section III-A): Omega, colI, OmegaPtr, rowPtr
+ *   CSER (Compressed Shared Elements Row,  Section III-A): the same plus OmegaI
  *
  * and computes Y = W.X on the GPU from those arrays (Appendix A-C, Algorithms 3 and 4): per row,
  * the inputs selected by one group of column indices are summed and the sum is multiplied once
@@ -61,7 +61,7 @@ enum {
 };
 
 /*
- * cer_encode / cser_encode -- dense matrix + codebook -> CER / CSER handle (Section II-A, the
+ * cer_encode / cser_encode -- dense matrix + codebook -> CER / CSER handle (Section III-A, the
  * four format steps; CSER paragraph).  Host-side, O(m.n); not part of the timed product, as in
  * the paper's experiments (Section V).
  *
@@ -235,15 +235,15 @@ int cer_matmul_path_ex(const cer_handle_t* h, int64_t batch, const cer_matmul_op
 int cer_prepare_strips(cer_handle_t* h);
 
 /*
- * cer_decode / cser_decode -- arrays -> dense matrix (Section II-A: M can be reconstructed
- * uniquely).  W_host_out: [m][n] fp32, host, written completely; equals the encoder's input bit
+ * cer_decode / cser_decode -- arrays -> dense matrix (Section III-A: the arrays
+ * determine M).  W_host_out: [m][n] fp32, host, written completely; equals the encoder's input bit
  * for bit (with -0.0 returned as +0.0).  Host-side.  Errors: CER_E_INVALID, CER_E_FORMAT.
  */
 int cer_decode(const cer_handle_t* h, float* W_host_out);
 int cser_decode(const cer_handle_t* h, float* W_host_out);
 
 /*
- * Inspection (host copies of the arrays of Section II-A; lengths as in the proofs of Theorems 1
+ * Inspection (host copies of the arrays of Section III-A; lengths as in the proofs of Theorems 1
  * and 2, with the pointer arrays' leading zeros included).
  *
  * cer_get_array: *host_ptr is borrowed and valid until cer_free; *len = number of elements,
@@ -251,7 +251,7 @@ int cser_decode(const cer_handle_t* h, float* W_host_out);
  * CER_ARRAY_OMEGAI on a CER handle yields len 0.  cer_get_dims: any output pointer may be NULL;
  * nnz = len(colI), groups = len(OmegaPtr) - 1.  cer_storage_bits = sum over the format's arrays
  * of length x width (negative code on error).  cer_get_stats: entropy H = -sum p_k log2 p_k of
- * the element distribution (Section II), p0 = share of Omega[0], k_bar = mean number of
+ * the element distribution (Section III), p0 = share of Omega[0], k_bar = mean number of
  * non-empty groups per row, k_tilde = mean number of empty (padding) groups per row (Theorem 1).
  */
 int cer_get_array(const cer_handle_t* h, int which, const void** host_ptr, int64_t* len,
@@ -295,7 +295,7 @@ int dense_matmul(const float* W_dev, const float* X_dev, float* Y_dev, int64_t m
                  int64_t batch, void* stream);
 
 /*
- * CSR comparator (Section II-A "Sparse format", Algorithm 2): the paper's main sparse baseline in
+ * CSR comparator (Section III-A "Sparse format", Algorithm 2): the paper's main sparse baseline in
  * the same harness.  csr_encode stores the elements different from 0.0 in row-major order (values
  * fp32, column indices at the minimal 8/16/32-bit width, row pointers; on the device the row
  * pointers are uint32); csr_matmul computes Y = W.X from them (one multiply-add per stored
@@ -314,12 +314,12 @@ int csr_clone_device(const csr_handle_t* h, csr_handle_t** out);
 void csr_free(csr_handle_t* h);
 
 /*
- * Cost model (host-side analytics; Sections II-B, III and V): elementary operations of ONE
+ * Cost model (host-side analytics; Sections III-B, IIII and V): elementary operations of ONE
  * matrix-vector product (batch 1) per format, the storage of the format, and the energy that
  * Table I (45 nm CMOS, pJ) assigns to those operations -- reads and writes priced by the width of
  * the value and the size of the array that holds it, 32-bit float add 0.9 pJ, mul 3.7 pJ.
  *   CER_COUNT_THEOREM  counts as Eq. (2), (4), (10), (12) price them (proofs of Theorems 1, 2)
- *   CER_COUNT_EXAMPLE  the hand count of Section II-B: both ends of a row's pointer range are read
+ *   CER_COUNT_EXAMPLE  the hand count of Section III-B: both ends of a row's pointer range are read
  *                      and summing k terms costs k - 1 additions (dense 48, CSR 32, CER 24 for the
  *                      example row)
  * A non-zero most frequent value adds n input reads, n + m additions, one multiplication and one

@@ -1,7 +1,7 @@
 """CPU ORACLE -- TEST INFRASTRUCTURE, NOT PART OF THE PRODUCT.
 
 Thin ctypes wrapper around ``cer_oracle.c`` (the plain C implementation written from the paper)
-plus the storage-cost and statistics formulas of Sections III and V.  Only ``tests/``, the smoke
+plus the storage-cost and statistics formulas of Sections IIII and V.  Only ``tests/``, the smoke
 check and the benchmark's ``cpu_baseline`` leg may import this package; the HIP library and its
 Python binding never do, and this package never imports them.
 """
@@ -84,7 +84,7 @@ class OracleError(RuntimeError):
 
 @dataclasses.dataclass
 class Encoded:
-    """The arrays of Section II-A.  ``omegaI`` is None for CER."""
+    """The arrays of Section III-A.  ``omegaI`` is None for CER."""
     fmt: str                 # "cer" | "cser"
     m: int
     n: int
@@ -114,7 +114,7 @@ def min_bits(max_value: int) -> int:
 
 
 def encode(W: np.ndarray, codebook: np.ndarray, fmt: str) -> Encoded:
-    """Dense matrix + codebook -> CER or CSER arrays (Section II-A)."""
+    """Dense matrix + codebook -> CER or CSER arrays (Section III-A)."""
     assert fmt in ("cer", "cser")
     W, Wp = _f32(W)
     cb, cbp = _f32(codebook)
@@ -210,7 +210,7 @@ class CSR:
 
 
 def csr_encode(W: np.ndarray) -> CSR:
-    """CSR of Section II-A (non-zero values, their columns, row pointers)."""
+    """CSR of Section III-A (non-zero values, their columns, row pointers)."""
     W, Wp = _f32(W)
     m, n = W.shape
     rowPtr = np.empty(m + 1, np.int64)
@@ -234,12 +234,12 @@ def dot_csr(A: CSR, X: np.ndarray) -> np.ndarray:
 
 
 # ---------------------------------------------------------------------------------------------
-# Storage cost (Section III-C, Theorems 1 and 2 and their proofs) and statistics (Section II, III).
+# Storage cost (Section IV-C, Theorems 1 and 2 and their proofs) and statistics (Section III, III).
 # ---------------------------------------------------------------------------------------------
 
 def entries(A: Encoded) -> int:
     """Number of stored entries, every array counted with its leading-zero sentinel, as in the
-    worked example of Section II-A (49 for CER, 59 for CSER of the 5x12 matrix)."""
+    worked example of Section III-A (49 for CER, 59 for CSER of the 5x12 matrix)."""
     e = A.K + A.nnz + len(A.omegaPtr) + len(A.rowPtr)
     if A.omegaI is not None:
         e += len(A.omegaI)
@@ -267,7 +267,7 @@ def storage_bits(A: Encoded) -> int:
 
 
 def stats(A: Encoded) -> dict:
-    """p_k = #(w_k)/N, H = -sum p_k log2 p_k (Section II); k_bar = mean number of distinct
+    """p_k = #(w_k)/N, H = -sum p_k log2 p_k (Section III); k_bar = mean number of distinct
     non-dominant values per row, k_tilde = mean number of padding (empty) groups per row
     (Theorem 1)."""
     N = A.m * A.n

@@ -7,15 +7,15 @@
  * may call it.  It shares no code, header, table or helper with the HIP library.
  *
  * Contents
- *   orc_encode / orc_free / orc_get_*   dense -> CER or CSER arrays      (Section II-A, format steps 1-4)
- *   orc_decode                          CER / CSER arrays -> dense       (Section II-A: M is uniquely
+ *   orc_encode / orc_free / orc_get_*   dense -> CER or CSER arrays      (Section III-A, format steps 1-4)
+ *   orc_decode                          CER / CSER arrays -> dense       (Section III-A: M is uniquely
  *                                                                         reconstructible)
  *   orc_dot_cer / orc_dot_cser          group-sum product, fp64 sums     (Appendix A-C, Algorithms 3, 4;
- *                                                                         Section II-B prose steps 1-5;
+ *                                                                         Section III-B prose steps 1-5;
  *                                                                         Appendix A-A1 for a non-zero
  *                                                                         most-frequent value)
  *   orc_dot_dense                       three-loop product, fp64 sums    (Algorithm 1)
- *   orc_csr_encode_count / orc_dot_csr  CSR comparator                   (Section II-A, Algorithm 2)
+ *   orc_csr_encode_count / orc_dot_csr  CSR comparator                   (Section III-A, Algorithm 2)
  *   orc_min_bits                        8/16/32-bit index width rule     (Section V, index arrays)
  *
  * All index arrays are exchanged as int64 so that the caller never has to know a width; widths are
@@ -84,7 +84,7 @@ void orc_free(orc_matrix *A) {
 }
 
 /*
- * Section II-A, steps 1-4 of the CER description and the CSER paragraph.
+ * Section III-A, steps 1-4 of the CER description and the CSER paragraph.
  * W: m x n row-major fp32; codebook: Kc distinct finite values.
  */
 int orc_encode(const float *W, int64_t m, int64_t n, const float *codebook, int64_t Kc, int cser,
@@ -97,7 +97,7 @@ int orc_encode(const float *W, int64_t m, int64_t n, const float *codebook, int6
             if (same_value(codebook[a], codebook[b])) return ORC_E_BAD_CODEBOOK;
     }
 
-    /* symbol of every element, and how often each codebook value occurs (Section II: p_k = #(w_k)/N) */
+    /* symbol of every element, and how often each codebook value occurs (Section III: p_k = #(w_k)/N) */
     int32_t *sym = (int32_t *)malloc((size_t)(N > 0 ? N : 1) * sizeof(int32_t));
     int64_t *cnt = (int64_t *)calloc((size_t)(Kc > 0 ? Kc : 1), sizeof(int64_t));
     if (!sym || !cnt) { free(sym); free(cnt); return ORC_E_NOMEM; }
@@ -183,7 +183,7 @@ void orc_get_arrays(const orc_matrix *A, float *omega, int64_t *count, int64_t *
 }
 
 /*
- * Decode (Section II-A: the arrays determine M).  Every element starts as Omega[0]; group g of
+ * Decode (Section III-A: the arrays determine M).  Every element starts as Omega[0]; group g of
  * row r overwrites its columns with Omega[rank], rank = position in the row + 1 (CER) or
  * OmegaI[g] (CSER, omegaI != NULL).
  */
@@ -278,7 +278,7 @@ void orc_abs_dot_dense(const float *A, int64_t m, int64_t n, const float *X, int
     }
 }
 
-/* CSR (Section II-A): non-zero values in row-major order, their columns, row pointers. */
+/* CSR (Section III-A): non-zero values in row-major order, their columns, row pointers. */
 int64_t orc_csr_encode(const float *W, int64_t m, int64_t n, float *val, int64_t *colI, int64_t *rowPtr) {
     int64_t k = 0;
     rowPtr[0] = 0;

@@ -9,7 +9,7 @@ Two ways of counting, both from the paper:
   "theorem"  what Eq. (2), (4), (10), (12) and the proofs of Theorems 1 and 2 charge: the end of the
              previous row / group is carried over, so a row reads one rowPtr entry and each group one
              OmegaPtr entry; every element that takes part costs one addition.
-  "example"  the hand count of Section II-B for a single row: both ends of the row's pointer range
+  "example"  the hand count of Section III-B for a single row: both ends of the row's pointer range
              are read, and a sum of k terms costs k - 1 additions.
 """
 from __future__ import annotations

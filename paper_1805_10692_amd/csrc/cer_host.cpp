@@ -1,8 +1,8 @@
-// Host-side encoder and decoder of the CER / CSER formats (Section II-A of the paper).
+// Host-side encoder and decoder of the CER / CSER formats (Section III-A of the paper).
 //
 // The encoder is a three-pass, row-parallel counting sort:
 //   pass 1  element -> codebook symbol through a hash of the fp32 bit pattern; global histogram
-//   (order) symbols ranked by count (Section II-A step 1: frequency-major Omega)
+//   (order) symbols ranked by count (Section III-A step 1: frequency-major Omega)
 //   pass 2  per row: histogram over ranks -> number of indexed elements and of groups
 //   (scan)  exclusive prefix sums give every row its slice of colI / OmegaPtr / OmegaI
 //   pass 3  per row: scatter the columns into their rank bucket (ascending inside a bucket because

@@ -1,5 +1,5 @@
 // Host-side analytics: elementary-operation counts, storage and modelled energy of one
-// matrix-vector product per format (Sections II-B, III and V of the paper).
+// matrix-vector product per format (Sections III-B, IIII and V of the paper).
 //
 // Counting conventions
 //   CER_COUNT_THEOREM  the accounting of Eq. (2), (4), (10), (12) and of the proofs of Theorems 1 and 2 with
@@ -7,7 +7,7 @@
 //                      end is carried), one addition per element that takes part (dense: every element,
 //                      CSR / CER / CSER: every indexed element), one multiplication and one Omega read per
 //                      non-empty group.
-//   CER_COUNT_EXAMPLE  the hand count of Section II-B for a single row: both ends of the row's pointer
+//   CER_COUNT_EXAMPLE  the hand count of Section III-B for a single row: both ends of the row's pointer
 //                      range are read (2 rowPtr entries, groups + 1 OmegaPtr entries) and summing k
 //                      terms costs k - 1 additions.  (Dense 48, CSR 32, CER 24 for the example row.)
 // Energy: every count is priced with Table I (45 nm CMOS, pJ): 32-bit float add 0.9, mul 3.7; a read or

@@ -1,4 +1,4 @@
-// CSR comparator (Section II-A "Sparse format" and Algorithm 2 of the paper) in the same harness as
+// CSR comparator (Section III-A "Sparse format" and Algorithm 2 of the paper) in the same harness as
 // the CER / CSER path: host encoder / decoder, device upload, and the product kernels.
 //
 // The kernels mirror the CER ones so that the comparison isolates the format: one wave per row,
@@ -21,7 +21,6 @@
 namespace {
 
 constexpr int kWave = 64;
-constexpr int kSteps = 16;  // (index, value) load pairs in flight per lane
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -31,8 +30,28 @@ __device__ __forceinline__ float wave_sum(float x) {
     return x;
 }
 
-// batch = 1.  colI and the values are followed by readable padding, so all loads of a batch are
-// unconditional; positions past the row's end are given the value 0.
+// batch = 1.  Same treatment as the CER batch-1 kernel, so that the comparison isolates the format: what bounds a
+// launch of this size is the number of vector-memory instructions a compute unit issues, so values and indices are
+// read with wide loads (a lane holds 4 consecutive elements of a window of 256: one 16-byte load of values, one load
+// of 4 indices), four windows in flight, a batch starting at a multiple of 4 elements (aligned loads); X is staged
+// into LDS with 16-byte loads.  colI and the values are followed by readable padding, so all loads of a batch are
+// unconditional; elements in front of the row or past its end are given the value 0.
+constexpr int kCsrWindows = 4;  // windows of 256 elements in flight per wave
+
+template <typename IdxT>
+__device__ __forceinline__ void csr_load_indices(const IdxT* p, uint32_t (&idx)[4]) {  // p is 4-element aligned
+    if (sizeof(IdxT) == 4) {
+        const uint4 q = *reinterpret_cast<const uint4*>(p);
+        idx[0] = q.x; idx[1] = q.y; idx[2] = q.z; idx[3] = q.w;
+    } else if (sizeof(IdxT) == 2) {
+        const uint2 q = *reinterpret_cast<const uint2*>(p);
+        idx[0] = q.x & 0xFFFFu; idx[1] = q.x >> 16; idx[2] = q.y & 0xFFFFu; idx[3] = q.y >> 16;
+    } else {
+        const uint32_t q = *reinterpret_cast<const uint32_t*>(p);
+        idx[0] = q & 0xFFu; idx[1] = (q >> 8) & 0xFFu; idx[2] = (q >> 16) & 0xFFu; idx[3] = q >> 24;
+    }
+}
+
 template <typename IdxT, bool kXinLds>
 __global__ __launch_bounds__(1024) void csr_gemv_kernel(const float* __restrict__ val, const IdxT* __restrict__ colI,
                                                         const uint32_t* __restrict__ rowPtr, const float* __restrict__ X,
@@ -44,7 +63,15 @@ __global__ __launch_bounds__(1024) void csr_gemv_kernel(const float* __restrict_
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t nwaves = blockDim.x >> 6;
     if (kXinLds) {
-        for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) xs[i] = X[i];
+        if ((reinterpret_cast<uintptr_t>(X) & 15u) == 0) {
+            const uint32_t n4 = n >> 2;
+            const float4* X4 = reinterpret_cast<const float4*>(X);
+            float4* xs4 = reinterpret_cast<float4*>(xs);
+            for (uint32_t i = threadIdx.x; i < n4; i += blockDim.x) xs4[i] = X4[i];
+            for (uint32_t i = (n4 << 2) + threadIdx.x; i < n; i += blockDim.x) xs[i] = X[i];
+        } else {
+            for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) xs[i] = X[i];
+        }
         __syncthreads();
     }
     const float* xsrc = kXinLds ? xs : X;
@@ -53,21 +80,24 @@ __global__ __launch_bounds__(1024) void csr_gemv_kernel(const float* __restrict_
     for (uint32_t r = row_begin + wave; r < row_end; r += nwaves) {
         const uint32_t rs = rowPtr[r], re = rowPtr[r + 1];
         float acc0 = 0.f, acc1 = 0.f;
-        for (uint32_t b0 = rs; b0 < re; b0 += kSteps * kWave) {
-            uint32_t idx[kSteps];
-            float w[kSteps];
+        for (uint32_t b0 = rs & ~3u; b0 < re; b0 += kCsrWindows * 4 * kWave) {
+            float4 w[kCsrWindows];
+            uint32_t idx[kCsrWindows][4];
 #pragma unroll
-            for (int s = 0; s < kSteps; ++s) {
-                idx[s] = (uint32_t)colI[b0 + s * kWave + lane];
-                w[s] = val[b0 + s * kWave + lane];
+            for (int W = 0; W < kCsrWindows; ++W) {
+                const uint32_t pos = b0 + (uint32_t)W * 4u * kWave + 4u * lane;
+                w[W] = *reinterpret_cast<const float4*>(val + pos);
+                csr_load_indices<IdxT>(colI + pos, idx[W]);
             }
 #pragma unroll
-            for (int s = 0; s < kSteps; s += 2) {
-                const float x0 = xsrc[idx[s]], x1 = xsrc[idx[s + 1]];
-                const float w0 = (b0 + s * kWave + lane < re) ? w[s] : 0.f;
-                const float w1 = (b0 + (s + 1) * kWave + lane < re) ? w[s + 1] : 0.f;
-                acc0 = fmaf(w0, x0, acc0);
-                acc1 = fmaf(w1, x1, acc1);
+            for (int W = 0; W < kCsrWindows; ++W) {
+                if (W > 0 && b0 + (uint32_t)W * 4u * kWave >= re) break;  // wave-uniform
+                const uint32_t pos = b0 + (uint32_t)W * 4u * kWave + 4u * lane;
+                const float x0 = xsrc[idx[W][0]], x1 = xsrc[idx[W][1]], x2 = xsrc[idx[W][2]], x3 = xsrc[idx[W][3]];
+                acc0 = fmaf((pos >= rs && pos < re) ? w[W].x : 0.f, x0, acc0);
+                acc1 = fmaf((pos + 1u >= rs && pos + 1u < re) ? w[W].y : 0.f, x1, acc1);
+                acc0 = fmaf((pos + 2u >= rs && pos + 2u < re) ? w[W].z : 0.f, x2, acc0);
+                acc1 = fmaf((pos + 3u >= rs && pos + 3u < re) ? w[W].w : 0.f, x3, acc1);
             }
         }
         const float y = wave_sum(acc0 + acc1);
@@ -202,7 +232,14 @@ hipError_t launch_gemv(const csr_matrix& h, const float* X, float* Y, hipStream_
     const uint32_t m = (uint32_t)h.host->m, n = (uint32_t)h.host->n;
     const size_t x_bytes = (size_t)n * 4;
     const bool x_in_lds = x_bytes <= di.lds;
-    const int waves = (x_in_lds && x_bytes > 40 * 1024) ? 16 : 4;
+    // as for the CER batch-1 kernel: an X of tens of kilobytes is staged once per compute unit
+    int waves = 4;
+    if (x_in_lds && x_bytes > 24 * 1024) {
+        const uint32_t per_unit = (m + (uint32_t)di.cus - 1) / (uint32_t)di.cus;
+        uint32_t w2 = 4;
+        while (w2 < per_unit && w2 < 16) w2 <<= 1;
+        waves = (int)w2;
+    }
     const size_t lds = x_in_lds ? x_bytes : 0;
     size_t per_cu = std::min<size_t>(lds ? di.lds / lds : 8, (size_t)(32 / waves));
     per_cu = std::max<size_t>(1, std::min<size_t>(per_cu, 8));

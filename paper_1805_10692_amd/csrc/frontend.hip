@@ -4,7 +4,7 @@
 //   range     min / max of W (quantizer only); the K = 2^b points of the codebook
 //   codes     element -> codebook position (quantizer: nearest point; otherwise: exact look-up),
 //             one byte per element, and a per-row histogram over the positions
-//   rank      global histogram -> frequency-major order Omega (Section II-A, step 1)
+//   rank      global histogram -> frequency-major order Omega (Section III-A, step 1)
 //   layout    per row: number of indexed elements and of groups; exclusive scans over the rows give
 //             every row its slice of colI and of OmegaPtr / OmegaI
 //   emit      per row: a stable counting sort of the columns by rank writes colI, the bucket ends are
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(256) void hist_kernel(const uint32_t* __restrict__ 
 }
 
 // Frequency-major order: higher count first, equal counts in codebook order; values that never
-// occur are left out (Section II-A, step 1).  One block of 256 threads, K <= 256: each thread
+// occur are left out (Section III-A, step 1).  One block of 256 threads, K <= 256: each thread
 // finds its own position by counting who comes before it.
 __global__ __launch_bounds__(256) void rank_kernel(FrontState* __restrict__ st) {
     __shared__ unsigned long long s_h[kCodes];
@@ -644,7 +644,7 @@ __global__ __launch_bounds__(256) void emit_kernel(const uint8_t* __restrict__ c
 }
 
 // ------------------------------------------------------------------------------------------------
-// decode: format arrays -> dense matrix (Section II-A: M is reconstructed uniquely).  One workgroup
+// decode: format arrays -> dense matrix (Section III-A: M is reconstructed uniquely).  One workgroup
 // per row (large matrices) or per (row, every gridDim.y-th segment).  A segment of up to kDecSeg
 // columns is assembled in LDS -- filled with Omega[0], then every indexed position of the row whose
 // column falls into the segment writes its group's value -- and written out once with 16-byte stores,

@@ -15,7 +15,7 @@ KEYS = ("read_weight", "read_omega", "read_colI", "read_omegaPtr", "read_rowPtr"
 
 
 def test_paper_example_row_counts(example):
-    """Section II-B: second row of M: dense 24 loads + 12 mul + 11 add + 1 write = 48; CSR 20 + 6 + 5 + 1 = 32;
+    """Section III-B: second row of M: dense 24 loads + 12 mul + 11 add + 1 write = 48; CSR 20 + 6 + 5 + 1 = 32;
     CER 17 loads (2 rowPtr, 2 OmegaPtr, 1 Omega, 6 colI, 6 input) + 1 mul + 5 add + 1 write = 24."""
     row = example["M"][1:2].astype(np.float32)
     d = cm.count_dense(row, "example")
@@ -90,7 +90,7 @@ def test_energy_equals_theorem_formulas():
 
 
 def test_model_favours_cer_on_low_entropy_and_csr_on_spike_and_slab():
-    """Section III-D / Fig. 4 trend, on the model: geometric tail (low entropy) -> CER cheaper than CSR;
+    """Section IV-D / Fig. 4 trend, on the model: geometric tail (low entropy) -> CER cheaper than CSR;
     uniform tail over many values at modest sparsity -> dense or CSR cheaper than CER."""
     lo = wl.random_lowentropy(m=64, n=2000, K=16, p_dom=0.9, L=1, seed=55, ratio=0.5)
     e_cer = B.cer_cost_model(B.cer_encode(lo.W, lo.codebook))["energy_pj"]

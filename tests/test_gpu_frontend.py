@@ -205,7 +205,7 @@ DECODE_CASES["dominant_nonzero"] = lambda: wl.random_lowentropy(m=33, n=500, K=7
 @pytest.mark.parametrize("fmt", ["cer", "cser"])
 @pytest.mark.parametrize("name", list(DECODE_CASES))
 def test_decode_device_round_trip(name, fmt):
-    """Host-encoded handle -> dense matrix on the device: bit for bit the encoder's input (Section II-A)."""
+    """Host-encoded handle -> dense matrix on the device: bit for bit the encoder's input (Section III-A)."""
     w = DECODE_CASES[name]()
     h = (B.cer_encode if fmt == "cer" else B.cser_encode)(w.W, w.codebook)
     out = torch.full((w.m, w.n), float("nan"), dtype=torch.float32, device=_gpu())

@@ -91,7 +91,7 @@ def test_product_on_printed_arrays(example):
 
 
 def test_factorised_second_row(example):
-    """Section II-B: row 2 of M times a equals 4*(a_1+a_2+a_6+a_9+a_10+a_12)."""
+    """Section III-B: row 2 of M times a equals 4*(a_1+a_2+a_6+a_9+a_10+a_12)."""
     M = example["M"].astype(np.float32)
     a = np.arange(1, 13, dtype=np.float32)[:, None] * 0.5
     cols = ints(example["row1_columns"])
@@ -305,7 +305,7 @@ def test_storage_formulas(case):
 
 
 def test_limits_of_kbar():
-    """Section III-C: k_bar -> K-1 for a uniform distribution with many columns; -> 0 as H -> 0;
+    """Section IV-C: k_bar -> K-1 for a uniform distribution with many columns; -> 0 as H -> 0;
     CER and CSER storage approach each other as n grows (padding disappears)."""
     rng = np.random.default_rng(9)
     cb = np.arange(8, dtype=np.float32)
