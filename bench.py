@@ -69,6 +69,10 @@ def make_workload(name: str):
     m = re.fullmatch(r"sweep_K(\d+)_p([0-9.]+)(?:_L(\d+))?", name)
     if m:
         return wl.sweep_cell(int(m.group(1)), float(m.group(2)), L=int(m.group(3) or 16))
+    m = re.fullmatch(r"rand_(\d+)x(\d+)_K(\d+)_p([0-9.]+)_L(\d+)", name)
+    if m:  # any shape: K values, the most frequent one with the given probability, the rest uniform
+        return wl.random_lowentropy(int(m.group(1)), int(m.group(2)), int(m.group(3)), float(m.group(4)),
+                                    int(m.group(5)), seed=11)
     raise SystemExit(f"unknown workload {name}")
 
 

@@ -2,8 +2,8 @@
 // constant term of a non-zero most frequent value, Appendix A-A1, is summed from the staged copy of x).
 //
 // X is staged into LDS once per workgroup and gathered from there; one wave per row; the 64 lane totals are combined
-// with DPP cross-lane adds.  Two kernels: the stream kernel below, and the expansion kernel for rows of many short
-// groups and for short rows.
+// with DPP cross-lane adds.  Two kernels: the stream kernel below, which the library uses, and the expansion kernel
+// (an earlier design, kept as a variant that callers can ask for).
 #include "cer_device.hpp"
 
 namespace cer {
@@ -75,6 +75,17 @@ __device__ __forceinline__ void bitmap_build(const uint32_t* ends, uint32_t last
     wave_lds_sync();
 }
 
+// Number of entries of the wave's list (count entries, sentinels behind them) that end at or before position b: the
+// list index of the group position b belongs to.
+__device__ __forceinline__ uint32_t list_rank_of(const uint32_t* ends, int count, uint32_t b, uint32_t lane) {
+    uint32_t f = 0;
+    for (int i = 0; i < count; i += kWave) {
+        const uint32_t e = ends[min(i + (int)lane, count)];
+        f += (uint32_t)__popcll(__ballot(i + (int)lane < count && e <= b));
+    }
+    return f;
+}
+
 // Weights of the PPL positions lane l holds in window W of the batch: wl[k] = value - Omega[0] of the group that
 // position b0 + W.WIN + PPL.l + k belongs to (0 in front of the row and behind it).
 template <typename S>
@@ -99,6 +110,23 @@ __device__ __forceinline__ uint32_t packed_index(const uint4& q, int k) {
     return (w[k >> 2] >> (8 * (k & 3))) & 0xFFu;
 }
 
+// Appends the non-empty groups among raw groups [j0, tg_end) of the row that starts at group g0 to the wave's list.
+// The pointer tiles are requested four at a time (tiles past tg_end read the padding behind the pointer arrays and
+// come back empty): a row of 256 raw groups waits for memory once, not four times.
+__device__ __forceinline__ int list_append_tiles(const KView& v, bool cser, const float* omega, uint32_t g0, uint32_t j0,
+                                                 uint32_t tg_end, uint32_t* ends, float* wts, int count, uint32_t lane) {
+    for (; j0 < tg_end; j0 += 4u * kWave) {
+        PtrTile p[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) p[t] = load_ptr_tile(v, cser, g0, min(j0 + (uint32_t)t * kWave, tg_end), tg_end, lane);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            if (j0 + (uint32_t)t * kWave < tg_end)  // wave-uniform
+                count = list_append(p[t], omega[p[t].rank < v.K ? p[t].rank : 0u] - v.omega0, ends, wts, count);
+    }
+    return count;
+}
+
 // One batch: gathers and multiply-adds, window by window as the index loads return (they return in order); windows
 // that start at or behind the row's end (te) are skipped.
 template <typename IdxT>
@@ -121,12 +149,16 @@ __device__ __forceinline__ void gemv_batch(const uint4 (&ix)[GemvShape<IdxT>::NW
 }
 
 // kOneRow: the launch gives every wave at most one row (matrices of up to 16 rows per compute unit and workgroup
-// slot), so the loop over a wave's rows and what it keeps alive fall away.
+// slot), so the loop over a wave's rows and what it keeps alive fall away.  Such a launch may also give a row to
+// 2, 4 or 8 consecutive waves of a workgroup (matrices of so few rows that one wave per row would leave most of the
+// chip idle): the row's windows of WIN positions are dealt to them in equal contiguous shares, every wave builds the
+// row's group list and starts its bitmap at its own share, and the partial sums meet in LDS (added in wave order by
+// the first of them).  `rows_and_parts` = rows per workgroup | log2(waves per row) << 28.
 template <typename IdxT, bool kXinLds, bool kVec4, bool kCser, bool kOneRow>
 __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__ colI_, const uint2* __restrict__ rowInfo_,
                                                         const float* __restrict__ X, float* __restrict__ Y,
                                                         const uint32_t* __restrict__ omegaPtr_, const float* __restrict__ omega_,
-                                                        uint32_t n_, uint32_t m_, uint32_t K_, uint32_t rows_per_block,
+                                                        uint32_t n_, uint32_t m_, uint32_t K_, uint32_t rows_and_parts,
                                                         uint32_t gcap, float omega0_, const void* __restrict__ omegaI_,
                                                         const float* __restrict__ T, int omegaI_bits_, int omega_in_lds) {
     // Plain pointers and integers, the ones the first instructions need in front: the first 16 dwords of a kernel's
@@ -156,10 +188,13 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
     const float* omega = omega_in_lds ? oms : v.omega;
     const float* xsrc = kXinLds ? xs : X;
 
+    const uint32_t rows_per_block = rows_and_parts & 0x0FFFFFFFu;
+    const uint32_t part_shift = kOneRow ? rows_and_parts >> 28 : 0u;
+    const uint32_t parts = 1u << part_shift, part = wave & (parts - 1u);
     const uint32_t row_begin = blockIdx.x * rows_per_block;
     const uint32_t row_end = min(v.m, row_begin + rows_per_block);
     const IdxT* colI = static_cast<const IdxT*>(v.colI);
-    uint32_t r = row_begin + wave;  // wave-uniform: the descriptor loads below are scalar loads
+    uint32_t r = row_begin + (wave >> part_shift);  // wave-uniform: the descriptor loads below are scalar loads
 
     // (1) descriptor of the wave's first row: {first group, first colI offset} of rows r and r+1
     uint32_t g0 = 0, g1 = 0, rs = 0, re = 0;
@@ -199,24 +234,62 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
     const PtrTile pt0 = load_ptr_tile_first(v, kCser, g0, g0, min(g1, g0 + min(gcap, (uint32_t)kWave)), lane);
     uint4 idx0[S::NW];  // used by one piece of code only (no merge with re-loaded values, which would make the
                         // compiler wait for all of them at the merge point)
-    const uint32_t b00 = rs & ~((uint32_t)S::PPL - 1u);
+    uint32_t b00 = rs & ~((uint32_t)S::PPL - 1u);
+    uint32_t re0 = re;  // end of this wave's share of the first row
+    if (kOneRow && parts > 1u) {
+        const uint32_t nwin = (re - b00 + (uint32_t)S::WIN - 1u) / (uint32_t)S::WIN;
+        const uint32_t share = ((nwin + parts - 1u) >> part_shift) * (uint32_t)S::WIN;
+        const uint32_t mine = b00 + part * share;
+        if (mine < re) { b00 = mine; re0 = min(re, mine + share); } else { re0 = b00; }  // an empty share does nothing
+    }
     {
         const uint4* p = reinterpret_cast<const uint4*>(colI + b00) + lane;
 #pragma unroll
         for (int W = 0; W < S::NW; ++W) idx0[W] = p[W * kWave];
     }
+    // a first row of more than 64 raw groups: the next three pointer tiles as well (behind the indices in the queue)
+    const uint32_t tg_end0 = min(g1, g0 + gcap);
+    const bool many0 = tg_end0 - g0 > (uint32_t)kWave;  // wave-uniform
+    PtrTile pt1, pt2, pt3;
+    if (many0) {
+        pt1 = load_ptr_tile(v, kCser, g0, min(g0 + 1u * kWave, tg_end0), tg_end0, lane);
+        pt2 = load_ptr_tile(v, kCser, g0, min(g0 + 2u * kWave, tg_end0), tg_end0, lane);
+        pt3 = load_ptr_tile(v, kCser, g0, min(g0 + 3u * kWave, tg_end0), tg_end0, lane);
+    }
     __builtin_amdgcn_sched_barrier(0);
 
-    // (4) finish staging
+    // (4) finish staging.  Appendix A-A1 needs sum_i X[i] when the most frequent value is not 0: every thread adds
+    //     up what it stages (a short chain), the wave's total goes to LDS before the wave counts itself in.
+    __shared__ float s_xsum[16];
+    const bool want_xsum = kXinLds && v.omega0 != 0.f;  // uniform over the grid
+    float xpart = 0.f;
     if (kXinLds) {
         if (kVec4) {
             F4* xs4 = reinterpret_cast<F4*>(xs);
 #define CER_STAGE_STORE(k) if (CER_STAGE_IDX(k) < n4) xs4[CER_STAGE_IDX(k)] = xr##k
             CER_STAGE_STORE(0); CER_STAGE_STORE(1); CER_STAGE_STORE(2); CER_STAGE_STORE(3);
             CER_STAGE_STORE(4); CER_STAGE_STORE(5); CER_STAGE_STORE(6); CER_STAGE_STORE(7);
-            for (uint32_t i = 8u * blockDim.x + threadIdx.x; i < n4; i += blockDim.x) xs4[i] = X4[i];
+#define CER_STAGE_SUM(k) if (CER_STAGE_IDX(k) < n4) xpart += (xr##k.x + xr##k.y) + (xr##k.z + xr##k.w)
+            if (want_xsum) {
+                CER_STAGE_SUM(0); CER_STAGE_SUM(1); CER_STAGE_SUM(2); CER_STAGE_SUM(3);
+                CER_STAGE_SUM(4); CER_STAGE_SUM(5); CER_STAGE_SUM(6); CER_STAGE_SUM(7);
+            }
+#undef CER_STAGE_SUM
+            for (uint32_t i = 8u * blockDim.x + threadIdx.x; i < n4; i += blockDim.x) {
+                const F4 x4 = X4[i];
+                xs4[i] = x4;
+                xpart += (x4.x + x4.y) + (x4.z + x4.w);
+            }
         }
-        for (uint32_t i = (n4 << 2) + threadIdx.x; i < v.n; i += blockDim.x) xs[i] = X[i];
+        for (uint32_t i = (n4 << 2) + threadIdx.x; i < v.n; i += blockDim.x) {
+            const float x1 = X[i];
+            xs[i] = x1;
+            xpart += x1;
+        }
+        if (want_xsum) {
+            xpart = wave_sum(xpart);
+            if (lane == 0) s_xsum[wave] = xpart;
+        }
     }
 #undef CER_STAGE_STORE
 #undef CER_STAGE_LOAD
@@ -242,10 +315,11 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
         list_close(ends, wts, count0, lane);
         if (count0 > 1) {
             wave_lds_sync();
-            first = rs > b00 ? 0u : 1u;
+            first = (kOneRow && part > 0u) ? list_rank_of(ends, count0, b00, lane) : (rs > b00 ? 0u : 1u);
             bitmap_build<S>(ends, (uint32_t)count0 + 1u, first, b00, bmp, wpre, lane);
 #pragma unroll
-            for (int W = 0; W < S::NW; ++W) window_weights<S>(W, bmp, wpre, wts, lane, wl0[W]);
+            for (int W = 0; W < S::NW; ++W)
+                if (W == 0 || b00 + (uint32_t)W * S::WIN < re0) window_weights<S>(W, bmp, wpre, wts, lane, wl0[W]);
         }
     }
     if (kXinLds || omega_in_lds) {
@@ -258,20 +332,14 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
         wave_lds_sync();
     }
 
-    // Appendix A-A1: Omega[0] . sum_i X[i].  With X staged in LDS the workgroup sums it there (short per-thread
-    // chains, then a tree); otherwise the launcher has computed it into T.
+    // Appendix A-A1: Omega[0] . sum_i X[i].  With X staged in LDS the waves' totals are in LDS by now (added in wave
+    // order); otherwise the launcher has computed the sum into T.
     float t_off = 0.f;
     if (v.omega0 != 0.f) {  // uniform over the grid
         float tsum;
         if (kXinLds) {
-            __shared__ float s_part[16];
-            float part = 0.f;
-            for (uint32_t i = threadIdx.x; i < v.n; i += blockDim.x) part += xs[i];
-            part = wave_sum(part);
-            if (lane == 0) s_part[wave] = part;
-            __syncthreads();
             tsum = 0.f;
-            for (uint32_t w = 0; w < nwaves; ++w) tsum += s_part[w];
+            for (uint32_t w = 0; w < nwaves; ++w) tsum += s_xsum[w];
         } else {
             tsum = T[0];
         }
@@ -282,33 +350,36 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
     // everything else -- later batches, rows with many groups, later rows -- goes through the general loop below.
     float acc0 = 0.f, acc1 = 0.f;
     bool resume = false;
-    uint32_t te0 = re;  // end of the first row's first tile of groups
+    uint32_t te0 = re0;  // end of the first row's first tile of groups (of this wave's share of it)
     if (count0 < 0 && r < row_end && g1 > g0) {
         // more than 64 values or raw groups: the list of the first tile is built here, with Omega from LDS; the
         // indices of its first batch are the ones requested in the prologue
-        const uint32_t tg_end0 = min(g1, g0 + gcap);
         if (tg_end0 != g1) te0 = uniform(v.omegaPtr[tg_end0]);
         if (lane == 0) { ends[0] = rs; wts[0] = 0.f; }
-        count0 = 1;
-        for (uint32_t j0 = g0; j0 < tg_end0; j0 += kWave) {
-            const PtrTile p = j0 == g0 ? pt0 : load_ptr_tile(v, kCser, g0, j0, tg_end0, lane);
-            count0 = list_append(p, omega[p.rank < v.K ? p.rank : 0u] - v.omega0, ends, wts, count0);
+        count0 = list_append(pt0, omega[pt0.rank < v.K ? pt0.rank : 0u] - v.omega0, ends, wts, 1);
+        if (many0) {
+            count0 = list_append(pt1, omega[pt1.rank < v.K ? pt1.rank : 0u] - v.omega0, ends, wts, count0);
+            count0 = list_append(pt2, omega[pt2.rank < v.K ? pt2.rank : 0u] - v.omega0, ends, wts, count0);
+            count0 = list_append(pt3, omega[pt3.rank < v.K ? pt3.rank : 0u] - v.omega0, ends, wts, count0);
+            count0 = list_append_tiles(v, kCser, omega, g0, g0 + 4u * kWave, tg_end0, ends, wts, count0, lane);
         }
         list_close(ends, wts, count0, lane);
         if (count0 > 1) {
             wave_lds_sync();
-            first = rs > b00 ? 0u : 1u;
+            first = (kOneRow && part > 0u) ? list_rank_of(ends, count0, b00, lane) : (rs > b00 ? 0u : 1u);
             bitmap_build<S>(ends, (uint32_t)count0 + 1u, first, b00, bmp, wpre, lane);
 #pragma unroll
-            for (int W = 0; W < S::NW; ++W) window_weights<S>(W, bmp, wpre, wts, lane, wl0[W]);
+            for (int W = 0; W < S::NW; ++W)
+                if (W == 0 || b00 + (uint32_t)W * S::WIN < te0) window_weights<S>(W, bmp, wpre, wts, lane, wl0[W]);
         }
     }
-    if (r < row_end && count0 > 1) {
+    if (r < row_end && count0 > 1 && b00 < te0) {
         gemv_batch<IdxT>(idx0, xsrc, b00, te0, wl0, acc0, acc1);
         resume = true;
     }
 
     bool first_row = true;
+    float y_share = 0.f;
     for (; r < row_end; r += nwaves) {
         if (!first_row) {
             const uint2 e0 = v.rowInfo[r], e1 = v.rowInfo[r + 1];
@@ -319,9 +390,10 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
         for (uint32_t tg = g0; tg < g1; tg += gcap) {
             const uint32_t tg_end = min(g1, tg + gcap);
             const uint32_t ts = tg == g0 ? rs : uniform(v.omegaPtr[tg]);
-            const uint32_t te = tg_end == g1 ? re : uniform(v.omegaPtr[tg_end]);
+            uint32_t te = tg_end == g1 ? re : uniform(v.omegaPtr[tg_end]);
             const bool resumed = first_row && resume && tg == g0;  // the tile's first batch is done, its list is live
             uint32_t b0 = ts & ~((uint32_t)S::PPL - 1u);
+            if (kOneRow && parts > 1u) { b0 = b00; te = te0; }  // a shared row is one tile of groups: this wave's share
             int count;
             if (resumed) {
                 count = count0;
@@ -333,11 +405,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
                 } else {
                     // the pseudo group in front of the tile, then its non-empty groups
                     if (lane == 0) { ends[0] = ts; wts[0] = 0.f; }
-                    count = 1;
-                    for (uint32_t j0 = tg; j0 < tg_end; j0 += kWave) {
-                        const PtrTile p = (pre && j0 == tg) ? pt0 : load_ptr_tile(v, kCser, g0, j0, tg_end, lane);
-                        count = list_append(p, omega[p.rank < v.K ? p.rank : 0u] - v.omega0, ends, wts, count);
-                    }
+                    count = list_append_tiles(v, kCser, omega, g0, tg, tg_end, ends, wts, 1, lane);
                     list_close(ends, wts, count, lane);
                 }
                 wave_lds_sync();
@@ -357,7 +425,8 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
     }
 #define CER_BATCH(ix, b)                                                                         \
     bitmap_build<S>(ends, (uint32_t)count + 1u, first, b, bmp, wpre, lane);                      \
-    _Pragma("unroll") for (int W = 0; W < S::NW; ++W) window_weights<S>(W, bmp, wpre, wts, lane, wl[W]); \
+    _Pragma("unroll") for (int W = 0; W < S::NW; ++W)                                            \
+        if (W == 0 || (b) + (uint32_t)W * S::WIN < te) window_weights<S>(W, bmp, wpre, wts, lane, wl[W]); \
     gemv_batch<IdxT>(ix, xsrc, b, te, wl, acc0, acc1);
                 CER_REQUEST(ixa, b0)
                 for (;;) {
@@ -377,22 +446,33 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
             wave_lds_sync();  // the list is rebuilt by the next tile / row
         }
         const float y = wave_sum(acc0 + acc1);
+        if (kOneRow && parts > 1u) { y_share = y; break; }
         if (lane == 0) Y[r] = y + t_off;
         if (kOneRow) break;
         first_row = false;
     }
+    if (kOneRow && parts > 1u) {  // uniform over the workgroup
+        __shared__ float s_share[16];
+        if (lane == 0) s_share[wave] = y_share;
+        __syncthreads();
+        if (part == 0u && r < row_end && lane == 0) {
+            float y = s_share[wave];
+            for (uint32_t q = 1; q < parts; ++q) y += s_share[wave + q];
+            Y[r] = y + t_off;
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
-// batch = 1, rows made of many short groups
+// batch = 1, values expanded per position (on request)
 // ------------------------------------------------------------------------------------------------
 //
-// With hundreds of values per row (8-bit codebooks) a group holds a handful of elements and the cursor of
-// the kernel above crosses several group ends in every window of 64 positions.  This kernel expands the group
-// structure instead, as the default batched kernel does: per chunk of kGemvExpChunk colI positions the value of
-// every position goes to an array in LDS (long groups written by the whole wave, short ones by one lane each) and
-// the stream is acc += X[colI[p]] . val[p], lane = position, X staged in LDS.  One wave per row; the index loads
-// of a chunk are issued before its expansion starts and run into the next row or the padding behind colI.
+// The group structure is expanded as in the default batched kernel: per chunk of kGemvExpChunk colI positions the
+// value of every position goes to an array in LDS (long groups written by the whole wave, short ones by one lane
+// each) and the stream is acc += X[colI[p]] . val[p], lane = position, X staged in LDS.  One wave per row; the index
+// loads of a chunk are issued before its expansion starts and run into the next row or the padding behind colI.
+// The expansion costs a pass over the groups per chunk and one 2-byte index load per position and lane; the stream
+// kernel's bitmap needs neither, which is why this kernel is no longer chosen by the library.
 
 constexpr uint32_t kGemvExpShort = 32;  // groups up to this length are written by one lane each, longer ones by the whole wave
 
@@ -517,7 +597,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_expand_kernel(KView v, const fl
 // LDS the batch-1 kernels may claim dynamically: the device's limit less its few static words.
 size_t gemv_lds_budget(const DeviceView& d) { return d.lds_per_block - 256; }
 
-// Whether the cursor kernel stages X in LDS for this matrix: whenever it fits beside Omega and the group lists of
+// Whether the stream kernel stages X in LDS for this matrix: whenever it fits beside Omega and the group lists of
 // 4 waves (with at least 64 entries each).
 bool gemv_stages_x(const DeviceView& d, const MatmulOptions& o) {
     const size_t x_bytes = (((size_t)d.n + 3) & ~(size_t)3) * sizeof(float);
@@ -550,6 +630,26 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
         const uint32_t per_unit = (k.m + (uint32_t)d.cus - 1) / (uint32_t)d.cus;
         waves = (int)std::min<uint32_t>(16u, pow2_ceil(std::max<uint32_t>(per_unit, 4u)));
     }
+    // Few rows (at most 2 per compute unit) of at least 3 windows each: a row is shared by 4 or 8 waves, and a
+    // workgroup holds as many rows as spread the matrix over all compute units.  Measured against whole rows: 512 x
+    // 4608 with 1840 indices per row 4.84 against 5.29 us, 256 x 25088 (1250) 5.2 against 6.8 us, 64 x 4096 (2050)
+    // 4.85 against 5.25 us; with 4 or 8 rows per compute unit (1024 x 9216, 2048 x 9216) or rows of 2 windows (512 x
+    // 2048) sharing lost 0.2 - 0.6 us (every wave builds the row's group list; 16 waves per compute unit contend).
+    uint32_t part_shift = 0, rows_shared = 0;
+    if (x_in_lds && (o.flags & kOptRowsWhole) == 0 && k.m > 0 && (uint64_t)k.m <= 2ull * (uint64_t)d.cus &&
+        (uint32_t)d.max_row_groups <= gcap) {
+        const uint32_t per_unit = pow2_ceil((k.m + (uint32_t)d.cus - 1) / (uint32_t)d.cus);  // 1 or 2
+        const uint64_t windows = ((uint64_t)d.nnz / k.m + GemvShape<IdxT>::WIN - 1) / GemvShape<IdxT>::WIN;  // average row
+        uint32_t p = windows >= 3 ? std::min<uint32_t>(8u / per_unit, pow2_ceil((uint32_t)std::min<uint64_t>(windows, 8))) : 1u;
+        while (p > 1 && fixed + list_bytes((int)(per_unit * p)) > budget) p >>= 1;
+        if (p > 1) {
+            rows_shared = per_unit;
+            while ((1u << part_shift) < p) ++part_shift;
+            // idle waves beyond the rows' help to stage a large X (8 KB per wave)
+            waves = (int)std::max<uint32_t>(per_unit * p, std::min<uint32_t>(16u, pow2_ceil((uint32_t)(x_bytes / 8192))));
+            while (waves > (int)(per_unit * p) && fixed + list_bytes(waves) > budget) waves >>= 1;
+        }
+    }
     while (fixed + list_bytes(waves) > budget && waves > 4) waves >>= 1;
     while (fixed + list_bytes(waves) > budget && gcap > 64) gcap = std::max<uint32_t>(64u, gcap / 2);
     const size_t lds = fixed + list_bytes(waves);
@@ -559,13 +659,14 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
     per_cu = std::max<size_t>(1, std::min<size_t>(per_cu, 8));
     const uint64_t slots = (uint64_t)d.cus * per_cu;
     const uint32_t iters = std::max<uint32_t>((uint32_t)((k.m + slots * waves - 1) / (slots * waves)), 1u);
-    const uint32_t rows_per_block = iters * waves;
+    const uint32_t rows_per_block = rows_shared ? rows_shared : iters * waves;
     const uint32_t blocks = (k.m + rows_per_block - 1) / rows_per_block;
+    if (rows_per_block >= (1u << 28)) return hipErrorInvalidValue;
     const bool vec4 = (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && k.n >= 4;
     using Kern = void (*)(const void*, const uint2*, const float*, float*, const uint32_t*, const float*, uint32_t, uint32_t,
                           uint32_t, uint32_t, uint32_t, float, const void*, const float*, int, int);
     Kern kern;
-    const bool one = rows_per_block == (uint32_t)waves;  // a wave has at most one row
+    const bool one = rows_shared != 0 || rows_per_block == (uint32_t)waves;  // a wave has at most one row
 #define CER_GEMV_PICK(CSER, ONE)                                                                 \
     (x_in_lds ? (vec4 ? cer_gemv_kernel<IdxT, true, true, CSER, ONE>                             \
                       : cer_gemv_kernel<IdxT, true, false, CSER, ONE>)                           \
@@ -583,7 +684,7 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(waves * kWave), lds, stream, k.colI, k.rowInfo, X, Y, k.omegaPtr, k.omega, k.n,
-                       k.m, k.K, rows_per_block, gcap, k.omega0, k.omegaI, T, k.omegaI_bits, omega_in_lds ? 1 : 0);
+                       k.m, k.K, rows_per_block | (part_shift << 28), gcap, k.omega0, k.omegaI, T, k.omegaI_bits, omega_in_lds ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -612,21 +713,12 @@ GemvExpandPlan plan_gemv_expand(const DeviceView& d) {
     return p;
 }
 
-// Rows of short groups go to the expansion kernel.  Measured on 2048 x 2048 matrices, cursor kernel / expansion
-// kernel, by indices per non-empty group: 4 (256 values, 50 % zeros) 24.2 / 7.8 us; 1.5 (256 values, 90 %) 16.4 /
-// 6.3 us; 16 (64 values, 50 %) 9.4 / 6.6 us; 3 (64 values, 90 %) 8.5 / 5.4 us; 41 (16 values, 70 %) 6.7 / 7.5 us;
-// 68 (16 values, 50 %) 6.7 / 8.1 us; AlexNet-fc6 shape (45) 10.2 / 10.5 us; VGG-fc6 shape (90) 8.5 / 16.4 us.
-// Short rows (a few hundred indices at most) go there as well: the cursor kernel requests 24 windows of indices per
-// row whatever its length (16384 x 512 matrices: 11 - 12 us against 7 - 8 us).
-bool gemv_expand_pays(const DeviceView& d) {
-    const double per_group = (double)d.nnz / (double)std::max<int64_t>(d.nonempty_groups, 1);
-    return per_group < 30.0 || d.nnz <= d.m * 384;
-}
-
-// The expansion kernel's plan for this matrix if the product would use it (waves == 0 otherwise): preferred by the
-// caller (whenever X fits in LDS), ruled out by a preference for the cursor kernel, else for rows of short groups.
+// The expansion kernel's plan for this matrix if the caller prefers that kernel and X fits in LDS (waves == 0
+// otherwise).  The library itself always takes the stream kernel: alternating measurements on 2048 x 2048 matrices
+// with 4 to 256 values and 50 - 99 % zeros, on matrices of 16384 short rows and on the layer shapes show it equal
+// or faster everywhere but on 256-value matrices with 90 % zeros or more (6.5 against 6.1 us).
 GemvExpandPlan gemv_expand_choice(const DeviceView& d, const MatmulOptions& o) {
-    if (o.path == 4 || (o.path != 0 && gemv_expand_pays(d))) return plan_gemv_expand(d);
+    if (o.path == 4) return plan_gemv_expand(d);
     return GemvExpandPlan{};
 }
 

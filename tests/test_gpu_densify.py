@@ -59,8 +59,8 @@ def test_automatic_choice_on_full_size_workloads():
     assert picks["conv3x3_L3136"] == (3, 3, 0)          # 40 % of the elements indexed: dense wins at large batches
     assert picks["alexnet_fc6_L32"][0] == 1 and picks["alexnet_fc6_L32"][2] == 0
     assert picks["vgg_fc6_L64"] == (1, 1, 0)            # 5 % indexed: the gathers win at every batch
-    assert picks["sweep_K256_p0.5_L16"] == (1, 3, 4)    # half of the elements indexed: small batch stays HBM-bound;
-                                                        # 4 indices per group: batch 1 takes the expansion kernel
+    assert picks["sweep_K256_p0.5_L16"] == (1, 3, 0)    # half of the elements indexed: small batch stays HBM-bound;
+                                                        # batch 1 is always the stream kernel
 
 
 @pytest.mark.parametrize("variant", [False, True], ids=["zero_dominant", "nonzero_dominant"])

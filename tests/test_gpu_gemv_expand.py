@@ -1,7 +1,7 @@
-"""GPU parity of the batch-1 kernel that expands the group values per position (meant for rows of many short
-groups, e.g. 8-bit codebooks), preferred through cer_matmul_ex for every kind of matrix and checked element by
-element against the oracle under the bound of every other product; then the automatic choice on full-size cells
-of the entropy sweep."""
+"""GPU parity of the batch-1 kernel that expands the group values per position (a variant callers can ask for
+through cer_matmul_ex), run on every kind of matrix and checked element by element against the oracle under the
+bound of every other product; then the automatic choice (always the stream kernel) on full-size cells of the
+entropy sweep."""
 import numpy as np
 import pytest
 
@@ -24,7 +24,7 @@ CASES = {
     "sweep_K2_p70_L1": lambda: wl.sweep_cell(2, 0.7, L=1, scale=4),
     "conv_s4_dom_L1": lambda: wl.conv3x3(L=1, nonzero_dominant=True, scale=4),  # Omega[0] != 0
     "u8_index": lambda: wl.random_lowentropy(m=70, n=250, K=6, p_dom=0.6, L=1, seed=31),
-    "u32_index_L1": lambda: wl.random_lowentropy(m=9, n=70001, K=8, p_dom=0.9, L=1, seed=33),   # X too big for LDS: cursor kernel
+    "u32_index_L1": lambda: wl.random_lowentropy(m=9, n=70001, K=8, p_dom=0.9, L=1, seed=33),   # X too big for LDS: stream kernel
     "chunk_edges": lambda: wl.random_lowentropy(m=33, n=5000, K=5, p_dom=0.38, L=1, seed=51),    # about 3100 indices per row: 4 chunks
     "exactly_one_chunk": lambda: wl.random_lowentropy(m=20, n=2048, K=3, p_dom=0.5, L=1, seed=52),
     "one_row": lambda: wl.random_lowentropy(m=1, n=3000, K=16, p_dom=0.7, L=1, seed=36),
@@ -38,7 +38,7 @@ CASES = {
 
 @pytest.mark.parametrize("name", list(CASES))
 def test_gemv_expand_all_elements(name):
-    # X too big for LDS: the preference cannot be met and the cursor kernel runs
+    # X too big for LDS: the preference cannot be met and the stream kernel runs
     full_check(CASES[name](), opts=EXPAND, want_path=0 if name == "u32_index_L1" else 4)
 
 
@@ -46,7 +46,7 @@ def test_gemv_expand_full_size_vgg_fc6():
     full_check(wl.vgg_fc6(L=1), opts=EXPAND, want_path=4)
 
 
-@pytest.mark.parametrize("K,p0,path", [(256, 0.5, 4), (256, 0.9, 4), (64, 0.5, 4), (16, 0.5, 0)])
+@pytest.mark.parametrize("K,p0,path", [(256, 0.5, 0), (256, 0.9, 0), (64, 0.5, 0), (16, 0.5, 0)])
 def test_automatic_choice_full_sweep_cells(K, p0, path):
     w = wl.sweep_cell(K, p0, L=1)
     h = B.cer_encode(w.W, w.codebook)
@@ -55,7 +55,7 @@ def test_automatic_choice_full_sweep_cells(K, p0, path):
     full_check(w)
 
 
-def test_automatic_choice_keeps_the_layer_shapes_on_the_cursor_kernel():
+def test_automatic_choice_keeps_the_layer_shapes_on_the_stream_kernel():
     for w in (wl.vgg_fc6(L=1), wl.alexnet_fc6(L=1)):
         h = B.cer_encode(w.W, w.codebook)
         assert B.cer_matmul_path(h, 1) == 0

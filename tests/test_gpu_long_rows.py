@@ -71,9 +71,11 @@ def test_long_rows_in_parts(K, dominant):
                 bad = np.abs(Y - want) > TOL * scale
                 assert not bad.any(), f"{fmt} K={K} L={L} split={split}: {int(bad.sum())} elements, rows {np.unique(np.nonzero(bad)[0])[:8]}"
                 results[split] = Y
-            # rows that are not split are computed by the same code either way
+            # rows that are not split are computed by the same code either way (batch 1: with so few rows the stream
+            # kernel shares every row between waves unless told to keep rows whole, so only the bound applies)
             short = np.setdiff1d(np.arange(m), where)
-            assert np.array_equal(results["1"][short], results["0"][short]), f"{fmt} K={K} L={L}"
+            if L > 1:
+                assert np.array_equal(results["1"][short], results["0"][short]), f"{fmt} K={K} L={L}"
         B.cer_free(h)
 
 
