@@ -195,19 +195,26 @@ int cer_matmul_path(const cer_handle_t* h, int64_t batch);
  *   opts->flags      CER_OPT_SUM_THEN_MULTIPLY    kernel 1: the variant that sums a group's gathered
  *                                                 rows before its one multiplication
  *                    CER_OPT_ROWS_WHOLE           kernel 1: rows in their own order and never in parts
- *                                                 (see cer_long_row_parts)
+ *                                                 (see cer_long_row_parts); kernel 0: a row is never
+ *                                                 shared between waves
  *                    CER_OPT_X_FROM_GLOBAL        kernel 0: gather X from global memory, no LDS copy
  *                    CER_OPT_ONE_COLUMN_PER_LANE  kernel 1, ragged batch widths: one batch column per
  *                                                 lane instead of 16-byte gathers
  *                    CER_OPT_SHORT_CHUNKS / CER_OPT_LONG_CHUNKS  kernel 1: group values expanded 512 /
  *                                                 2048 positions at a time (default: by the average row)
+ *                    CER_OPT_NO_RANK_TABLE        kernel 0: find the group boundaries through rowPtr and
+ *                                                 OmegaPtr even when the handle has a rank table
+ *                                                 (a derived array of handles with 2 - 64 values: per
+ *                                                 row its first colI position and the end of the group
+ *                                                 of every rank, at a fixed stride)
  * opts == NULL is cer_matmul's behaviour.  Errors: those of cer_matmul; CER_E_INVALID also for an
  * undefined path, tile width or flag.
  */
 enum { CER_PATH_AUTO = -1, CER_PATH_GEMV = 0, CER_PATH_GEMM = 1, CER_PATH_XTILE = 2, CER_PATH_DENSE = 3,
        CER_PATH_GEMV_EXPAND = 4, CER_PATH_STRIP = 5 };
 enum { CER_OPT_SUM_THEN_MULTIPLY = 1, CER_OPT_ROWS_WHOLE = 2, CER_OPT_X_FROM_GLOBAL = 4,
-       CER_OPT_ONE_COLUMN_PER_LANE = 8, CER_OPT_SHORT_CHUNKS = 16, CER_OPT_LONG_CHUNKS = 32 };
+       CER_OPT_ONE_COLUMN_PER_LANE = 8, CER_OPT_SHORT_CHUNKS = 16, CER_OPT_LONG_CHUNKS = 32,
+       CER_OPT_NO_RANK_TABLE = 64 };
 typedef struct {
     int32_t path;
     int32_t tile_cols;

@@ -42,7 +42,7 @@ CER_FORMAT_CER, CER_FORMAT_CSER = 0, 1
 
 CER_PATH_AUTO, CER_PATH_GEMV, CER_PATH_GEMM, CER_PATH_XTILE, CER_PATH_DENSE, CER_PATH_GEMV_EXPAND, CER_PATH_STRIP = -1, 0, 1, 2, 3, 4, 5
 CER_OPT_SUM_THEN_MULTIPLY, CER_OPT_ROWS_WHOLE, CER_OPT_X_FROM_GLOBAL = 1, 2, 4
-CER_OPT_ONE_COLUMN_PER_LANE, CER_OPT_SHORT_CHUNKS, CER_OPT_LONG_CHUNKS = 8, 16, 32
+CER_OPT_ONE_COLUMN_PER_LANE, CER_OPT_SHORT_CHUNKS, CER_OPT_LONG_CHUNKS, CER_OPT_NO_RANK_TABLE = 8, 16, 32, 64
 
 _lib = None
 

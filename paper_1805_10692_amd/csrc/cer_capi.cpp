@@ -94,7 +94,14 @@ cer::DeviceLayout cer::DeviceLayout::make(size_t colI_bytes, int64_t G, int64_t 
     l.off_oi = align_up(l.off_rptr + (size_t)(m + 1) * 4 + 16, 256);
     l.off_om = align_up(l.off_oi + omegaI_bytes + 16, 256);
     l.off_ri = align_up(l.off_om + (size_t)std::max(K, 1) * 4, 256);
-    l.total = align_up(l.off_ri + (size_t)(m + 1) * 8, 256);
+    l.off_tab = align_up(l.off_ri + (size_t)(m + 1) * 8, 256);
+    size_t tab_bytes = 0;
+    if (K >= 2 && K <= 64 && m > 0) {  // rank table: 4 .. 64 words per row
+        l.tab_shift = 2;
+        while ((1 << l.tab_shift) < K) ++l.tab_shift;
+        tab_bytes = ((size_t)m << l.tab_shift) * 4 + 256;
+    }
+    l.total = align_up(l.off_tab + tab_bytes, 256);
     return l;
 }
 
@@ -137,6 +144,8 @@ void cer::bind_device(cer_matrix* h, int dev, void* base, const DeviceLayout& l)
     v.omegaI = b + l.off_oi;
     v.omega = reinterpret_cast<const float*>(b + l.off_om);
     v.rowInfo = b + l.off_ri;
+    v.rank_tab = l.tab_shift ? reinterpret_cast<const uint32_t*>(b + l.off_tab) : nullptr;
+    v.rank_tab_shift = l.tab_shift;
     v.colI_bits = A.colI.bits;
     v.omegaI_bits = A.omegaI.bits;
     v.cser = A.cser ? 1 : 0;
@@ -326,6 +335,9 @@ int upload(cer_matrix* h) {
         return hip_fail(e);
     }
     cer::bind_device(h, dev, base, l);
+    e = (hipError_t)cer::build_rank_table(h->view, nullptr);
+    if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+    if (e != hipSuccess) return hip_fail(e);  // the caller frees the handle and with it the allocation
     return upload_split_table(h);
 }
 
@@ -361,7 +373,8 @@ bool read_options(const cer_matmul_opts_t* in, cer::MatmulOptions* out) {
     *out = cer::MatmulOptions{};
     if (!in) return true;
     constexpr uint32_t known = CER_OPT_SUM_THEN_MULTIPLY | CER_OPT_ROWS_WHOLE | CER_OPT_X_FROM_GLOBAL |
-                               CER_OPT_ONE_COLUMN_PER_LANE | CER_OPT_SHORT_CHUNKS | CER_OPT_LONG_CHUNKS;
+                               CER_OPT_ONE_COLUMN_PER_LANE | CER_OPT_SHORT_CHUNKS | CER_OPT_LONG_CHUNKS |
+                               CER_OPT_NO_RANK_TABLE;
     if (in->path < CER_PATH_AUTO || in->path > CER_PATH_STRIP) return false;
     if (in->flags & ~known) return false;
     if ((in->flags & CER_OPT_SHORT_CHUNKS) && (in->flags & CER_OPT_LONG_CHUNKS)) return false;

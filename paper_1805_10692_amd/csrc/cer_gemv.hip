@@ -95,10 +95,20 @@ __device__ __forceinline__ void window_weights(int W, const uint32_t* bmp, const
     const uint32_t wj = (uint32_t)W * S::WPW + (bit0 >> 5), sh = bit0 & 31u;
     const uint32_t word = bmp[wj];
     const uint32_t pre = wpre[wj] + (uint32_t)__builtin_popcount(word & ((1u << sh) - 1u));
-    const uint32_t field = word >> sh;  // bits above PPL are masked out below
+    const uint32_t field = word >> sh;  // bit k: position k is the last one of its group
+    // the LDS address of the position's list entry moves on by one entry behind every boundary bit: one bit-field
+    // extract and one shift-add per position
+    typedef const float __attribute__((address_space(3))) * LdsFloatPtr;
+    uint32_t addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const float*)wts + (pre << 2);
 #pragma unroll
-    for (int k = 0; k < S::PPL; ++k)
-        wl[k] = wts[pre + (uint32_t)__builtin_popcount(field & ((1u << k) - 1u))];
+    for (int k = 0; k < S::PPL; ++k) {
+        wl[k] = *reinterpret_cast<LdsFloatPtr>((uintptr_t)addr);
+        if (k + 1 < S::PPL) {
+            uint32_t bit;  // written out so that it stays one extract (the compiler turns it into shift + and)
+            asm("v_bfe_u32 %0, %1, %2, 1" : "=v"(bit) : "v"(field), "n"(k));
+            asm("v_lshl_add_u32 %0, %1, 2, %0" : "+v"(addr) : "v"(bit));  // addr += 4 * bit
+        }
+    }
 }
 
 // Column index of the k-th of the positions packed into one 16-byte load.
@@ -127,10 +137,36 @@ __device__ __forceinline__ int list_append_tiles(const KView& v, bool cser, cons
     return count;
 }
 
+// Byte offset (4 x column index) of the k-th of the positions packed into one 16-byte load: for 8- and 16-bit
+// indices one instruction that selects the byte or half-word and shifts it (sub-dword addressing of the vector ALU).
+template <typename IdxT>
+__device__ __forceinline__ uint32_t packed_offset(const uint4& q, int k, uint32_t two) {
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+    uint32_t r;
+    if (sizeof(IdxT) == 4) {
+        r = w[k] << 2;
+    } else if (sizeof(IdxT) == 2) {
+        const uint32_t d = w[k >> 1];
+        if (k & 1) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1" : "=v"(r) : "v"(two), "v"(d));
+        else asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0" : "=v"(r) : "v"(two), "v"(d));
+    } else {
+        const uint32_t d = w[k >> 2];
+        switch (k & 3) {
+            case 0: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(two), "v"(d)); break;
+            case 1: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(two), "v"(d)); break;
+            case 2: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(two), "v"(d)); break;
+            default: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(two), "v"(d)); break;
+        }
+    }
+    return r;
+}
+
 // One batch: gathers and multiply-adds, window by window as the index loads return (they return in order); windows
 // that start at or behind the row's end (te) are skipped.
-template <typename IdxT>
-__device__ __forceinline__ void gemv_batch(const uint4 (&ix)[GemvShape<IdxT>::NW], const float* xsrc, uint32_t b0,
+// kLds: X is in LDS at byte address xlds (a literal 0 where the kernel has no static LDS: the gather's address is then
+// the shifted index itself); otherwise xsrc points to X in global memory.
+template <typename IdxT, bool kLds>
+__device__ __forceinline__ void gemv_batch(const uint4 (&ix)[GemvShape<IdxT>::NW], const float* xsrc, uint32_t xlds, uint32_t b0,
                                            uint32_t te, const float (&wl)[GemvShape<IdxT>::NW][GemvShape<IdxT>::PPL],
                                            float& acc0, float& acc1) {
     using S = GemvShape<IdxT>;
@@ -138,8 +174,17 @@ __device__ __forceinline__ void gemv_batch(const uint4 (&ix)[GemvShape<IdxT>::NW
     for (int W = 0; W < S::NW; ++W) {
         if (W > 0 && b0 + (uint32_t)W * S::WIN >= te) break;  // wave-uniform
         float xv[S::PPL];
+        if (kLds) {  // X in LDS: 32-bit byte addresses
+            typedef const float __attribute__((address_space(3))) * LdsFloatPtr;
+            uint32_t two = 2u;
+            asm("" : "+v"(two));  // the shift count in a vector register (sub-dword forms take no constants)
 #pragma unroll
-        for (int k = 0; k < S::PPL; ++k) xv[k] = xsrc[packed_index<IdxT>(ix[W], k)];
+            for (int k = 0; k < S::PPL; ++k)
+                xv[k] = *reinterpret_cast<LdsFloatPtr>((uintptr_t)(xlds + packed_offset<IdxT>(ix[W], k, two)));
+        } else {
+#pragma unroll
+            for (int k = 0; k < S::PPL; ++k) xv[k] = xsrc[packed_index<IdxT>(ix[W], k)];
+        }
 #pragma unroll
         for (int k = 0; k < S::PPL; k += 2) {
             acc0 = fmaf(xv[k], wl[W][k], acc0);
@@ -187,6 +232,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
     uint32_t* wpre = list0 + 2u * nwaves * lcap + (nwaves + wave) * (uint32_t)S::NWORDS;
     const float* omega = omega_in_lds ? oms : v.omega;
     const float* xsrc = kXinLds ? xs : X;
+    const uint32_t xlds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)xs;  // LDS byte address of X
 
     const uint32_t rows_per_block = rows_and_parts & 0x0FFFFFFFu;
     const uint32_t part_shift = kOneRow ? rows_and_parts >> 28 : 0u;
@@ -374,7 +420,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
         }
     }
     if (r < row_end && count0 > 1 && b00 < te0) {
-        gemv_batch<IdxT>(idx0, xsrc, b00, te0, wl0, acc0, acc1);
+        gemv_batch<IdxT, kXinLds>(idx0, xsrc, xlds, b00, te0, wl0, acc0, acc1);
         resume = true;
     }
 
@@ -427,7 +473,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
     bitmap_build<S>(ends, (uint32_t)count + 1u, first, b, bmp, wpre, lane);                      \
     _Pragma("unroll") for (int W = 0; W < S::NW; ++W)                                            \
         if (W == 0 || (b) + (uint32_t)W * S::WIN < te) window_weights<S>(W, bmp, wpre, wts, lane, wl[W]); \
-    gemv_batch<IdxT>(ix, xsrc, b, te, wl, acc0, acc1);
+    gemv_batch<IdxT, kXinLds>(ix, xsrc, xlds, b, te, wl, acc0, acc1);
                 CER_REQUEST(ixa, b0)
                 for (;;) {
                     const uint32_t b1 = b0 + S::BATCH;
@@ -461,6 +507,296 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
             Y[r] = y + t_off;
         }
     }
+}
+
+
+// ------------------------------------------------------------------------------------------------
+// batch = 1: the stream kernel over the rank table (codebooks of at most 64 values, X in LDS)
+// ------------------------------------------------------------------------------------------------
+//
+// What a launch of a few microseconds spends most of its time on is waiting for memory that has to be asked for in
+// sequence: the row descriptor, then the group pointers and the first indices it locates, each a full trip to HBM.
+// For codebooks of at most 64 values the handle carries a rank table (derived from the format arrays, one record of
+// Kp = 4 .. 64 32-bit words per row at a fixed stride): word 0 is the row's first colI position, word k the end of its
+// group of rank k (the previous word where the row has no element of that rank).  A wave finds its record from the row
+// number alone, so the first trip to memory already brings the row's start, its end and every group boundary; the
+// second trip fetches the indices, and the group list, the boundary bitmap and the weights of the first batch are
+// built while it is on its way.  CER and CSER handles have the same table, so the kernel does not know the format.
+// Everything else -- batches, windows, bitmap, shared rows, the staging of X -- is as in the kernel above.
+// kBigX: every wave of the workgroup has six whole 16-byte loads of X (6 x the workgroup size x 16 bytes <= 4n).
+template <typename IdxT, bool kVec4, bool kOneRow, bool kBigX>
+__global__ __launch_bounds__(1024) void cer_gemv_tab_kernel(const uint32_t* __restrict__ tab, const float* __restrict__ X,
+                                                            const float* __restrict__ omega_, const void* __restrict__ colI_,
+                                                            float* __restrict__ Y, uint32_t n, uint32_t m,
+                                                            uint32_t rows_per_block, uint32_t meta) {
+    // 14 dwords of arguments: all of them are preloaded into scalar registers when a wave starts (the library is
+    // built with kernel-argument preloading), so no instruction in front of the first memory request waits for a
+    // load of the argument block.  For the same reason the workgroup size comes from `meta`, not from the dispatch
+    // packet, and Omega[0] from Omega.  meta = K | log2(words per record) << 8 | log2(waves per row) << 12 |
+    // waves per workgroup << 16.
+    using S = GemvShape<IdxT>;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const uint32_t K = meta & 0xFFu, tab_shift = (meta >> 8) & 0xFu;
+    const uint32_t nwaves = meta >> 16, bdim = nwaves * kWave;
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = uniform(threadIdx.x >> 6);
+
+    // LDS: [X: n floats, rounded to 4] [ends | wts: nwaves x 68] [bitmap | word prefix: nwaves x NWORDS]
+    //      [counter of staged waves, 16 sums of X, 16 partial row sums].  The kernel has no static LDS, so X sits at
+    //      LDS address 0 and a gather's address is 4 x the column index.
+    float* xs = reinterpret_cast<float*>(smem);
+    const uint32_t x_floats = (n + 3u) & ~3u;
+    constexpr uint32_t lcap = 68;  // the pseudo group in front of the row, at most 63 groups, two sentinels
+    uint32_t* list0 = reinterpret_cast<uint32_t*>(xs + x_floats);
+    uint32_t* ends = list0 + wave * lcap;
+    float* wts = reinterpret_cast<float*>(list0 + nwaves * lcap) + wave * lcap;
+    uint32_t* bmp = list0 + 2u * nwaves * lcap + wave * (uint32_t)S::NWORDS;
+    uint32_t* wpre = list0 + 2u * nwaves * lcap + (nwaves + wave) * (uint32_t)S::NWORDS;
+    uint32_t* s_staged = list0 + 2u * nwaves * lcap + 2u * nwaves * (uint32_t)S::NWORDS;
+    float* s_xsum = reinterpret_cast<float*>(s_staged + 4);
+    float* s_share = s_xsum + 16;
+
+    const uint32_t part_shift = kOneRow ? (meta >> 12) & 0xFu : 0u;
+    const uint32_t parts = 1u << part_shift, part = wave & (parts - 1u);
+    const uint32_t row_begin = blockIdx.x * rows_per_block;
+    const uint32_t row_end = min(m, row_begin + rows_per_block);
+    const IdxT* colI = static_cast<const IdxT*>(colI_);
+    uint32_t r = row_begin + (wave >> part_shift);  // wave-uniform
+    const uint32_t last_word = (1u << tab_shift) - 1u;
+
+    // (1) the row's record, one word per lane (a wave without a row reads the last row's and ignores it), and Omega
+    uint32_t rec = tab[((size_t)min(r, m - 1u) << tab_shift) + min(lane, last_word)];
+    const float om_l = omega_[min(lane, K - 1u)];
+    __builtin_amdgcn_sched_barrier(0);
+    // The counter of staged waves starts at zero: one early barrier that no wave waits at for memory -- in front of
+    // the X loads, whose issue is what takes time (a compute unit's vector-memory pipeline accepts a 16-byte-per-lane
+    // load about every 26 clocks: 128 of them for 98 KB of X).
+    if (threadIdx.x == 0) *s_staged = 0u;
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+
+    // (2) X on its way to LDS: up to eight 16-byte loads per thread, only those that hold part of X (wave-uniform
+    //     tests), all in front of the index loads (the earlier X is requested the earlier it is staged: measured
+    //     with 0 .. 8 loads in front).  When X is large enough for every wave to have six whole loads (what takes
+    //     time to stage), these are unconditional: the compiler can then wait for the record alone -- after
+    //     conditionally issued loads it has to assume that none was issued, and waits for all of them.
+    typedef float F4 __attribute__((ext_vector_type(4)));
+    F4 xr0, xr1, xr2, xr3, xr4, xr5, xr6, xr7;
+    const uint32_t n4 = kVec4 ? (n >> 2) : 0u;
+    const F4* X4 = reinterpret_cast<const F4*>(X);
+    F4* xs4 = reinterpret_cast<F4*>(xs);
+    const uint32_t wave_first = wave * kWave;
+    constexpr bool big = kVec4 && kBigX;
+#define CER_STAGE_IDX(k) ((k) * bdim + threadIdx.x)
+#define CER_STAGE_LOAD(k) if ((k) * bdim + wave_first < n4) xr##k = X4[min(CER_STAGE_IDX(k), n4 - 1u)]
+#define CER_STAGE_STORE(k) if (CER_STAGE_IDX(k) < n4) xs4[CER_STAGE_IDX(k)] = xr##k
+#define CER_STAGE_SUM(k) if (CER_STAGE_IDX(k) < n4) xpart += (xr##k.x + xr##k.y) + (xr##k.z + xr##k.w)
+    uint32_t rs, re;
+    float omega0, w_l;  // Omega[0] and the weight of the group of rank lane + 1 (ranks stay below K <= 64)
+#define CER_RECORD_HERE                                                                                       \
+    if (r >= row_end) rec = 0u; /* no row: no groups */                                                       \
+    rs = (uint32_t)__builtin_amdgcn_readlane((int)rec, 0);                                                    \
+    re = (uint32_t)__builtin_amdgcn_readlane((int)rec, (int)last_word);                                       \
+    omega0 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(om_l)));                            \
+    w_l = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(om_l), 0x130 /* wave_shl:1 */, 0xF, 0xF, false)) - omega0;
+    if (big) {
+        xr0 = X4[CER_STAGE_IDX(0)]; xr1 = X4[CER_STAGE_IDX(1)]; xr2 = X4[CER_STAGE_IDX(2)];
+        xr3 = X4[CER_STAGE_IDX(3)]; xr4 = X4[CER_STAGE_IDX(4)]; xr5 = X4[CER_STAGE_IDX(5)];
+        CER_STAGE_LOAD(6); CER_STAGE_LOAD(7);
+        __builtin_amdgcn_sched_barrier(0);
+        CER_RECORD_HERE
+    } else {
+        if (kVec4) {
+            CER_STAGE_LOAD(0); CER_STAGE_LOAD(1); CER_STAGE_LOAD(2); CER_STAGE_LOAD(3);
+            CER_STAGE_LOAD(4); CER_STAGE_LOAD(5); CER_STAGE_LOAD(6); CER_STAGE_LOAD(7);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        CER_RECORD_HERE
+    }
+#undef CER_RECORD_HERE
+    __builtin_amdgcn_sched_barrier(0);
+
+    // (3) the record is here (and with it Omega): the row's extent, this wave's share of it, the indices of its
+    //     first batch
+    uint32_t b00 = rs & ~((uint32_t)S::PPL - 1u);
+    uint32_t re0 = re;
+    if (kOneRow && parts > 1u) {
+        const uint32_t nwin = (re - b00 + (uint32_t)S::WIN - 1u) / (uint32_t)S::WIN;
+        const uint32_t share = ((nwin + parts - 1u) >> part_shift) * (uint32_t)S::WIN;
+        const uint32_t mine = b00 + part * share;
+        if (mine < re) { b00 = mine; re0 = min(re, mine + share); } else { re0 = b00; }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    uint4 idx0[S::NW];
+    {
+        const uint4* p = reinterpret_cast<const uint4*>(colI + b00) + lane;
+#pragma unroll
+        for (int W = 0; W < S::NW; ++W) idx0[W] = p[W * kWave];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // (4) X goes to LDS (only the index loads are behind it in the queue) and the wave counts itself in; Appendix
+    //     A-A1: every thread adds up what it stages, the wave's total goes to LDS before the count
+    const bool want_xsum = omega0 != 0.f;  // uniform over the grid
+    float xpart = 0.f;
+    if (kVec4) {
+        CER_STAGE_STORE(0); CER_STAGE_STORE(1); CER_STAGE_STORE(2); CER_STAGE_STORE(3);
+        CER_STAGE_STORE(4); CER_STAGE_STORE(5); CER_STAGE_STORE(6); CER_STAGE_STORE(7);
+        if (want_xsum) {
+            CER_STAGE_SUM(0); CER_STAGE_SUM(1); CER_STAGE_SUM(2); CER_STAGE_SUM(3);
+            CER_STAGE_SUM(4); CER_STAGE_SUM(5); CER_STAGE_SUM(6); CER_STAGE_SUM(7);
+        }
+#undef CER_STAGE_SUM
+#undef CER_STAGE_STORE
+        for (uint32_t i = 8u * bdim + threadIdx.x; i < n4; i += bdim) {
+            const F4 x4 = X4[i];
+            xs4[i] = x4;
+            xpart += (x4.x + x4.y) + (x4.z + x4.w);
+        }
+    }
+#undef CER_STAGE_LOAD
+#undef CER_STAGE_IDX
+    for (uint32_t i = (n4 << 2) + threadIdx.x; i < n; i += bdim) {
+        const float x1 = X[i];
+        xs[i] = x1;
+        xpart += x1;
+    }
+    if (want_xsum) {
+        xpart = wave_sum(xpart);
+        if (lane == 0) s_xsum[wave] = xpart;
+    }
+    wave_lds_sync();  // the LDS operations of a wave are executed in order: its stores, then its count
+    if (lane == 0) __hip_atomic_fetch_add(s_staged, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // (5) group list, bitmap and weights of the first batch, while the indices are on their way: lane l holds the
+    //     group of rank l + 1, which ends where the next lane's group begins
+    auto record_tile = [&](uint32_t rc) {
+        PtrTile p;
+        p.s = rc;
+        p.e = (uint32_t)__builtin_amdgcn_update_dpp((int)rc, (int)rc, 0x130 /* wave_shl:1 */, 0xF, 0xF, false);
+        if (lane >= last_word) p.e = p.s;
+        p.rank = lane + 1u;
+        return p;
+    };
+    if (lane == 0) { ends[0] = rs; wts[0] = 0.f; }
+    int count0 = list_append(record_tile(rec), w_l, ends, wts, 1);
+    list_close(ends, wts, count0, lane);
+    uint32_t first = 0;
+    float wl0[S::NW][S::PPL];
+    const bool run0 = count0 > 1 && b00 < re0;  // wave-uniform
+    if (run0) {
+        wave_lds_sync();
+        first = (kOneRow && part > 0u) ? list_rank_of(ends, count0, b00, lane) : (rs > b00 ? 0u : 1u);
+        bitmap_build<S>(ends, (uint32_t)count0 + 1u, first, b00, bmp, wpre, lane);
+#pragma unroll
+        for (int W = 0; W < S::NW; ++W)
+            if (W == 0 || b00 + (uint32_t)W * S::WIN < re0) window_weights<S>(W, bmp, wpre, wts, lane, wl0[W]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // every wave of the workgroup counts itself in without waiting for anything but its own loads; the bound on the
+    // spin only keeps a broken launch from hanging
+    for (uint32_t spin = 0; spin < (1u << 22); ++spin) {
+        if (__hip_atomic_load(s_staged, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) >= nwaves) break;
+        __builtin_amdgcn_s_sleep(1);
+    }
+    wave_lds_sync();
+    float t_off = 0.f;
+    if (want_xsum) {
+        float tsum = 0.f;
+        for (uint32_t w = 0; w < nwaves; ++w) tsum += s_xsum[w];
+        t_off = omega0 * tsum;
+    }
+
+    // (6) the stream: the first batch from the prefetched indices, then the rest of the row, then further rows
+    float acc0 = 0.f, acc1 = 0.f;
+    if (run0) gemv_batch<IdxT, true>(idx0, xs, 0u, b00, re0, wl0, acc0, acc1);
+    bool first_row = true;
+    float y_share = 0.f;
+    for (; r < row_end; r += nwaves) {
+        uint32_t b0, te;
+        int count;
+        if (first_row) {
+            count = run0 ? count0 : 0;
+            b0 = b00 + (uint32_t)S::BATCH;
+            te = re0;
+        } else {
+            rec = tab[((size_t)r << tab_shift) + min(lane, last_word)];
+            rs = (uint32_t)__builtin_amdgcn_readlane((int)rec, 0);
+            re = (uint32_t)__builtin_amdgcn_readlane((int)rec, (int)last_word);
+            acc0 = acc1 = 0.f;
+            if (lane == 0) { ends[0] = rs; wts[0] = 0.f; }
+            count = list_append(record_tile(rec), w_l, ends, wts, 1);
+            list_close(ends, wts, count, lane);
+            wave_lds_sync();
+            b0 = rs & ~((uint32_t)S::PPL - 1u);
+            te = re;
+            first = rs > b0 ? 0u : 1u;
+        }
+        if (count > 1 && b0 < te) {
+            // two sets of index registers: the next batch is requested before the current one is summed
+            uint4 ixa[S::NW], ixb[S::NW];
+            float wl[S::NW][S::PPL];
+#define CER_REQUEST(ix, b)                                                                       \
+    {                                                                                            \
+        const uint4* p_ = reinterpret_cast<const uint4*>(colI + (b)) + lane;                     \
+        _Pragma("unroll") for (int W = 0; W < S::NW; ++W) ix[W] = p_[W * kWave];                 \
+    }
+#define CER_BATCH(ix, b)                                                                         \
+    bitmap_build<S>(ends, (uint32_t)count + 1u, first, b, bmp, wpre, lane);                      \
+    _Pragma("unroll") for (int W = 0; W < S::NW; ++W)                                            \
+        if (W == 0 || (b) + (uint32_t)W * S::WIN < te) window_weights<S>(W, bmp, wpre, wts, lane, wl[W]); \
+    gemv_batch<IdxT, true>(ix, xs, 0u, b, te, wl, acc0, acc1);
+            CER_REQUEST(ixa, b0)
+            for (;;) {
+                const uint32_t b1 = b0 + S::BATCH;
+                CER_REQUEST(ixb, b1 < te ? b1 : b0)
+                CER_BATCH(ixa, b0)
+                if (b1 >= te) break;
+                const uint32_t b2 = b1 + S::BATCH;
+                CER_REQUEST(ixa, b2 < te ? b2 : b1)
+                CER_BATCH(ixb, b1)
+                if (b2 >= te) break;
+                b0 = b2;
+            }
+#undef CER_BATCH
+#undef CER_REQUEST
+        }
+        wave_lds_sync();  // the list is rebuilt by the next row
+        const float y = wave_sum(acc0 + acc1);
+        if (kOneRow && parts > 1u) { y_share = y; break; }
+        if (lane == 0) Y[r] = y + t_off;
+        if (kOneRow) break;
+        first_row = false;
+    }
+    if (kOneRow && parts > 1u) {  // uniform over the workgroup
+        if (lane == 0) s_share[wave] = y_share;
+        __syncthreads();
+        if (part == 0u && r < row_end && lane == 0) {
+            float y = s_share[wave];
+            for (uint32_t q = 1; q < parts; ++q) y += s_share[wave + q];
+            Y[r] = y + t_off;
+        }
+    }
+}
+
+// Builds the rank table of a handle whose codebook has 2 .. 64 values from its format arrays: one wave per row.
+__global__ __launch_bounds__(256) void rank_table_kernel(KView v, uint32_t* __restrict__ tab, uint32_t tab_shift) {
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t r = blockIdx.x * (blockDim.x >> 6) + uniform(threadIdx.x >> 6);
+    if (r >= v.m) return;
+    const uint2 d0 = v.rowInfo[r], d1 = v.rowInfo[r + 1];
+    const uint32_t g0 = d0.x, ng = d1.x - g0;  // at most 63 groups
+    // the number of the row's groups whose rank is at most `lane`: CER numbers its groups by rank (padding groups
+    // included), CSER names each group's rank in OmegaI (ascending inside a row)
+    uint32_t upto = min(lane, ng);
+    if (v.cser) {
+        const uint32_t mine = lane < ng ? load_rank(v.omegaI, v.omegaI_bits, g0 + lane) : kNoEnd;
+        upto = 0;
+        for (uint32_t j = 0; j < ng; ++j) upto += (uint32_t)__shfl((int)mine, (int)j, kWave) <= lane ? 1u : 0u;
+    }
+    if (lane < (1u << tab_shift)) tab[((size_t)r << tab_shift) + lane] = v.omegaPtr[g0 + upto];
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -612,13 +948,18 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
                        const MatmulOptions& o) {
     const size_t budget = gemv_lds_budget(d);
     const size_t x_bytes = (((size_t)k.n + 3) & ~(size_t)3) * sizeof(float);
-    const bool omega_in_lds = k.K <= 4096;
+    const bool x_in_lds = gemv_stages_x(d, o);
+    // codebooks of at most 64 values with X in LDS: the kernel over the rank table (lists of 68 entries, Omega read
+    // once per lane from global memory)
+    const bool use_tab = x_in_lds && d.rank_tab != nullptr && (o.flags & kOptNoRankTable) == 0 && k.m > 0 && k.K >= 2;
+    const bool omega_in_lds = !use_tab && k.K <= 4096;
     const size_t om_bytes = omega_in_lds ? (((size_t)k.K + 3) & ~(size_t)3) * sizeof(float) : 0;
     // per-wave list of non-empty groups: as long as the longest row needs, at most 1022 entries
-    uint32_t gcap = std::max<uint32_t>(1u, (uint32_t)std::min<int64_t>(d.max_row_groups, 1022));
+    uint32_t gcap = use_tab ? 65u : std::max<uint32_t>(1u, (uint32_t)std::min<int64_t>(d.max_row_groups, 1022));
     // per wave: the list (a pseudo group, the groups, two sentinels), the batch's bitmap and its word prefix
-    auto list_bytes = [&](int waves) { return (size_t)waves * ((gcap + 3) * 8 + GemvShape<IdxT>::NWORDS * 8); };
-    const bool x_in_lds = gemv_stages_x(d, o);
+    auto list_bytes = [&](int waves) {
+        return (size_t)waves * ((gcap + 3) * 8 + GemvShape<IdxT>::NWORDS * 8) + (use_tab ? 256u : 0u);  // + counter and sums
+    };
     const size_t fixed = (x_in_lds ? x_bytes : 0) + om_bytes;
     // Staging X is what a launch costs a compute unit (about 26 clocks of its vector-memory pipeline per kilobyte), so
     // X should be staged once per compute unit: as many waves per workgroup as the rows spread over all compute units
@@ -650,6 +991,8 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
             while (waves > (int)(per_unit * p) && fixed + list_bytes(waves) > budget) waves >>= 1;
         }
     }
+    // eight 16-byte loads per thread should cover X (what is left is copied by a plain loop)
+    if (x_in_lds) waves = std::max(waves, (int)std::min<uint32_t>(16u, pow2_ceil((uint32_t)((x_bytes / 16 + 511) / 512))));
     while (fixed + list_bytes(waves) > budget && waves > 4) waves >>= 1;
     while (fixed + list_bytes(waves) > budget && gcap > 64) gcap = std::max<uint32_t>(64u, gcap / 2);
     const size_t lds = fixed + list_bytes(waves);
@@ -659,14 +1002,48 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
     per_cu = std::max<size_t>(1, std::min<size_t>(per_cu, 8));
     const uint64_t slots = (uint64_t)d.cus * per_cu;
     const uint32_t iters = std::max<uint32_t>((uint32_t)((k.m + slots * waves - 1) / (slots * waves)), 1u);
-    const uint32_t rows_per_block = rows_shared ? rows_shared : iters * waves;
+    // one round of workgroups: no more rows per workgroup than spread the matrix over all compute units (waves
+    // without a row only help to stage X)
+    uint32_t rows_per_block = rows_shared ? rows_shared : iters * waves;
+    if (!rows_shared && iters == 1)
+        rows_per_block = std::min<uint32_t>((uint32_t)waves, std::max<uint32_t>(1u, (k.m + (uint32_t)d.cus - 1) / (uint32_t)d.cus));
     const uint32_t blocks = (k.m + rows_per_block - 1) / rows_per_block;
     if (rows_per_block >= (1u << 28)) return hipErrorInvalidValue;
     const bool vec4 = (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && k.n >= 4;
+    const bool one = rows_shared != 0 || rows_per_block <= (uint32_t)waves;  // a wave has at most one row
+    if (use_tab) {
+        using TabKern = void (*)(const uint32_t*, const float*, const float*, const void*, float*, uint32_t, uint32_t, uint32_t,
+                                 uint32_t);
+        const bool bigx = vec4 && 6ull * (uint64_t)waves * kWave <= (uint64_t)(k.n >> 2);
+        TabKern tk = bigx ? (one ? cer_gemv_tab_kernel<IdxT, true, true, true> : cer_gemv_tab_kernel<IdxT, true, false, true>)
+                     : vec4 ? (one ? cer_gemv_tab_kernel<IdxT, true, true, false> : cer_gemv_tab_kernel<IdxT, true, false, false>)
+                            : (one ? cer_gemv_tab_kernel<IdxT, false, true, false> : cer_gemv_tab_kernel<IdxT, false, false, false>);
+        if (lds > 48 * 1024) {
+            static LdsGrant<18> grant;
+            const int wslot = sizeof(IdxT) == 1 ? 0 : (sizeof(IdxT) == 2 ? 1 : 2);
+            const hipError_t e = grant.ensure(wslot * 6 + (bigx ? 4 : (vec4 ? 2 : 0)) + (one ? 1 : 0), reinterpret_cast<const void*>(tk), budget);
+            if (e != hipSuccess) return e;
+        }
+        {   // the kernel takes LDS address 0 for X: it must not have static LDS in front of the dynamic array
+            static std::atomic<int> checked[3][6] = {};
+            const int wslot = sizeof(IdxT) == 1 ? 0 : (sizeof(IdxT) == 2 ? 1 : 2);
+            std::atomic<int>& c = checked[wslot][(bigx ? 4 : (vec4 ? 2 : 0)) + (one ? 1 : 0)];
+            if (c.load(std::memory_order_acquire) == 0) {
+                hipFuncAttributes fa;
+                const hipError_t e = hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(tk));
+                if (e != hipSuccess) return e;
+                c.store(fa.sharedSizeBytes == 0 ? 1 : 2, std::memory_order_release);
+            }
+            if (c.load(std::memory_order_acquire) != 1) return hipErrorInvalidDeviceFunction;
+        }
+        const uint32_t meta = k.K | ((uint32_t)d.rank_tab_shift << 8) | (part_shift << 12) | ((uint32_t)waves << 16);
+        hipLaunchKernelGGL(tk, dim3(blocks), dim3(waves * kWave), lds, stream, d.rank_tab, X, k.omega, k.colI, Y, k.n, k.m,
+                           rows_per_block, meta);
+        return hipGetLastError();
+    }
     using Kern = void (*)(const void*, const uint2*, const float*, float*, const uint32_t*, const float*, uint32_t, uint32_t,
                           uint32_t, uint32_t, uint32_t, float, const void*, const float*, int, int);
     Kern kern;
-    const bool one = rows_shared != 0 || rows_per_block == (uint32_t)waves;  // a wave has at most one row
 #define CER_GEMV_PICK(CSER, ONE)                                                                 \
     (x_in_lds ? (vec4 ? cer_gemv_kernel<IdxT, true, true, CSER, ONE>                             \
                       : cer_gemv_kernel<IdxT, true, false, CSER, ONE>)                           \
@@ -744,6 +1121,14 @@ hipError_t launch_gemv_expand(const DeviceView& d, const KView& k, const GemvExp
 }
 
 }  // namespace
+
+int build_rank_table(const DeviceView& d, void* stream) {
+    if (!d.rank_tab || d.m <= 0) return (int)hipSuccess;
+    const KView k = make_kview(d);
+    hipLaunchKernelGGL(rank_table_kernel, dim3((uint32_t)((d.m + 3) / 4)), dim3(256), 0, static_cast<hipStream_t>(stream), k,
+                       const_cast<uint32_t*>(d.rank_tab), (uint32_t)d.rank_tab_shift);
+    return (int)hipGetLastError();
+}
 
 int gemv_path(const DeviceView& d, const MatmulOptions& o) { return gemv_expand_choice(d, o).waves > 0 ? 4 : 0; }
 

@@ -78,15 +78,21 @@ struct DeviceView {
     const void* strip_idx = nullptr;
     const uint32_t* strip_ptr = nullptr;
     uint32_t n_strips = 0;
+    // Rank table (derived; null unless the codebook has 2 .. 64 values): per row 1 << rank_tab_shift words at a fixed
+    // stride, word 0 = the row's first colI position, word k = end of its group of rank k (the previous word when the
+    // row has no element of that rank), the same for CER and CSER handles.
+    const uint32_t* rank_tab = nullptr;
+    int32_t rank_tab_shift = 0;
 };
 constexpr uint32_t kStripRows = 1024;
 
 // The handle's single device allocation: [colI | 8 KiB readable pad][OmegaPtr u32][rowPtr u32][OmegaI][Omega]
-// [row descriptors], each part 256-byte aligned.  The row descriptors {rowPtr[r], OmegaPtr[rowPtr[r]]} are derived
+// [row descriptors][rank table], each part 256-byte aligned.  The row descriptors {rowPtr[r], OmegaPtr[rowPtr[r]]} are derived
 // from the format arrays: they let a wave find its row's slice of colI with one load instead of two dependent ones.
 struct DeviceLayout {
     size_t colI_bytes = 0, omegaI_bytes = 0;
-    size_t off_colI = 0, off_optr = 0, off_rptr = 0, off_oi = 0, off_om = 0, off_ri = 0, total = 0;
+    size_t off_colI = 0, off_optr = 0, off_rptr = 0, off_oi = 0, off_om = 0, off_ri = 0, off_tab = 0, total = 0;
+    int32_t tab_shift = 0;  // log2 of the rank table's words per row; 0: no table
     static DeviceLayout make(size_t colI_bytes, int64_t G, int64_t m, size_t omegaI_bytes, int32_t K);
 };
 
@@ -110,7 +116,7 @@ struct MatmulOptions {
 };
 constexpr int kPathStrip = 5;
 constexpr uint32_t kOptSumThenMultiply = 1, kOptRowsWhole = 2, kOptXFromGlobal = 4, kOptOneColumnPerLane = 8,
-                   kOptShortChunks = 16, kOptLongChunks = 32;
+                   kOptShortChunks = 16, kOptLongChunks = 32, kOptNoRankTable = 64;
 
 // HIP launchers (cer_matmul.hip).  Return a hipError_t value as int (0 = success).
 // workspace == nullptr: temporaries are stream-ordered allocations.  Otherwise the call allocates nothing: the column
@@ -125,6 +131,9 @@ int static_workspace(float** ptr, size_t* floats);
 size_t matmul_workspace_floats(const DeviceView& v, int64_t L, const MatmulOptions& o);
 // Which product kernel launch_matmul picks for batch L (numbering of cer_matmul_path).
 int matmul_path(const DeviceView& v, int64_t L, const MatmulOptions& o);
+// Fills the handle's rank table (if its layout has one) from the format arrays already in device memory; the launch
+// is ordered on `stream`.  A hipError_t value as int.
+int build_rank_table(const DeviceView& v, void* stream);
 int launch_dense(const float* W, const float* X, float* Y, int64_t m, int64_t n, int64_t L, void* stream);
 int launch_stream_copy(void* dst, const void* src, int64_t bytes, void* stream);
 int launch_stream_read(const void* src, int64_t bytes, void* sink, void* stream);

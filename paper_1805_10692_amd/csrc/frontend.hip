@@ -1017,6 +1017,12 @@ int encode_device(const float* W, int64_t m, int64_t n, const float* codebook, i
     auto* hnd = new cer_matrix();
     hnd->host = std::move(A);
     bind_device(hnd, dev, base, l);
+    e = (hipError_t)build_rank_table(hnd->view, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) {
+        cer_free(hnd);
+        return record_hip_error((int)e);
+    }
     // rows of unequal length: the batched product wants them ordered (and the longest in parts); the row starts
     // come back from the device only when the longest row says that the table will be built
     if (row_schedule_wanted((uint64_t)hnd->host->nnz, (uint64_t)m, (uint64_t)h.max_row_nnz)) {

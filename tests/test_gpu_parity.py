@@ -91,6 +91,16 @@ def test_small_cases_all_elements(name):
     full_check(SMALL[name]())
 
 
+NO_RANK_TABLE = B.MatmulOpts(flags=B.CER_OPT_NO_RANK_TABLE)
+
+
+@pytest.mark.parametrize("name", [k for k in SMALL if SMALL[k]().L == 1])
+def test_small_batch1_cases_without_rank_table(name):
+    """Handles of at most 64 values carry a rank table for the batch-1 kernel; here the same products with the group
+    boundaries read through rowPtr and OmegaPtr."""
+    full_check(SMALL[name](), opts=NO_RANK_TABLE)
+
+
 @pytest.mark.parametrize("L", [2, 3, 4, 5, 16, 17, 33, 63, 64, 65, 100, 256, 260, 516])
 def test_ragged_batch_widths(L):
     full_check(wl.random_lowentropy(m=67, n=1500, K=16, p_dom=0.8, L=L, seed=100 + L))
@@ -181,6 +191,7 @@ def test_stream_copy_probe():
 
 def test_full_vgg_fc6_gemv_all_outputs():
     full_check(wl.vgg_fc6(L=1))
+    full_check(wl.vgg_fc6(L=1), opts=NO_RANK_TABLE)
 
 
 def test_full_vgg_fc6_batch64_all_outputs():

@@ -14,6 +14,9 @@ pytestmark = pytest.mark.gpu
 
 STREAM = B.MatmulOpts(path=B.CER_PATH_GEMV)
 WHOLE = B.MatmulOpts(path=B.CER_PATH_GEMV, flags=B.CER_OPT_ROWS_WHOLE)
+# the same kernel finding its group boundaries through rowPtr / OmegaPtr instead of the handle's rank table
+NO_TABLE = B.MatmulOpts(path=B.CER_PATH_GEMV, flags=B.CER_OPT_NO_RANK_TABLE)
+NO_TABLE_WHOLE = B.MatmulOpts(path=B.CER_PATH_GEMV, flags=B.CER_OPT_NO_RANK_TABLE | B.CER_OPT_ROWS_WHOLE)
 
 CASES = {
     # 16-bit indices: windows of 512 positions
@@ -57,6 +60,8 @@ def test_shared_rows_all_elements(name):
     w = CASES[name]()
     full_check(w, opts=STREAM, want_path=0)
     full_check(w, opts=WHOLE, want_path=0)
+    full_check(w, opts=NO_TABLE, want_path=0)
+    full_check(w, opts=NO_TABLE_WHOLE, want_path=0)
     scale = oracle.abs_dot_dense(w.W, w.X, threads=8)
     for fmt in ("cer", "cser"):
         a = run_matmul(fmt, w.W, w.codebook, w.X, opts=STREAM)
@@ -67,3 +72,4 @@ def test_shared_rows_all_elements(name):
 @pytest.mark.parametrize("dom", [False, True])
 def test_conv3x3_batch1_full_size(dom):
     full_check(wl.conv3x3(L=1, nonzero_dominant=dom))
+    full_check(wl.conv3x3(L=1, nonzero_dominant=dom), opts=NO_TABLE)

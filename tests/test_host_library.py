@@ -102,7 +102,7 @@ def test_matmul_options_are_validated_before_anything_runs():
     import ctypes
     h = B.cer_encode(np.array([[0, 1, 2], [2, 2, 0]], np.float32), np.array([0.0, 1.0, 2.0], np.float32))
     L = B.lib()
-    for bad in (B.MatmulOpts(path=6), B.MatmulOpts(path=-2), B.MatmulOpts(tile_cols=24), B.MatmulOpts(flags=64),
+    for bad in (B.MatmulOpts(path=6), B.MatmulOpts(path=-2), B.MatmulOpts(tile_cols=24), B.MatmulOpts(flags=128),
                 B.MatmulOpts(flags=B.CER_OPT_SHORT_CHUNKS | B.CER_OPT_LONG_CHUNKS)):
         assert L.cer_matmul_ex(h.ptr, 16, 16, 1, None, ctypes.byref(bad)) == B.CER_E_INVALID
         assert L.cer_matmul_path_ex(h.ptr, 1, ctypes.byref(bad)) == B.CER_E_INVALID

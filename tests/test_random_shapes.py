@@ -74,10 +74,14 @@ def test_products_random(seed):
     for fmt, enc, mm in (("cer", B.cer_encode, B.cer_matmul), ("cser", B.cser_encode, B.cser_matmul)):
         h = enc(W, cb)
         # the library's own choice, then each kernel family preferred in turn (taken where it applies)
-        for xt in (None, B.CER_PATH_GEMM, B.CER_PATH_XTILE, B.CER_PATH_DENSE, B.CER_PATH_GEMV, B.CER_PATH_GEMV_EXPAND):
+        # (the batch-1 stream kernel also without the rank table that handles of at most 64 values carry)
+        for xt in (None, B.CER_PATH_GEMM, B.CER_PATH_XTILE, B.CER_PATH_DENSE, B.CER_PATH_GEMV, B.CER_PATH_GEMV_EXPAND,
+                   "no_rank_table"):
             Yd = torch.full((m, L), float("nan"), dtype=torch.float32, device=dev)
             if xt is None:
                 mm(h, Xd, Yd, L)
+            elif xt == "no_rank_table":
+                B.cer_matmul_ex(h, Xd, Yd, L, None, B.MatmulOpts(path=B.CER_PATH_GEMV, flags=B.CER_OPT_NO_RANK_TABLE))
             else:
                 B.cer_matmul_ex(h, Xd, Yd, L, None, B.MatmulOpts(path=xt))
             torch.cuda.synchronize()
