@@ -96,7 +96,7 @@ cer::DeviceLayout cer::DeviceLayout::make(size_t colI_bytes, int64_t G, int64_t 
     l.off_ri = align_up(l.off_om + (size_t)std::max(K, 1) * 4, 256);
     l.off_tab = align_up(l.off_ri + (size_t)(m + 1) * 8, 256);
     size_t tab_bytes = 0;
-    if (K >= 2 && K <= 64 && m > 0) {  // rank table: 4 .. 64 words per row
+    if (K >= 2 && K <= 256 && m > 0) {  // rank table: 4 .. 256 words per row
         l.tab_shift = 2;
         while ((1 << l.tab_shift) < K) ++l.tab_shift;
         tab_bytes = ((size_t)m << l.tab_shift) * 4 + 256;

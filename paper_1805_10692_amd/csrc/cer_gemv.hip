@@ -511,13 +511,13 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
 
 
 // ------------------------------------------------------------------------------------------------
-// batch = 1: the stream kernel over the rank table (codebooks of at most 64 values, X in LDS)
+// batch = 1: the stream kernel over the rank table (codebooks of at most 256 values, X in LDS)
 // ------------------------------------------------------------------------------------------------
 //
 // What a launch of a few microseconds spends most of its time on is waiting for memory that has to be asked for in
 // sequence: the row descriptor, then the group pointers and the first indices it locates, each a full trip to HBM.
-// For codebooks of at most 64 values the handle carries a rank table (derived from the format arrays, one record of
-// Kp = 4 .. 64 32-bit words per row at a fixed stride): word 0 is the row's first colI position, word k the end of its
+// For codebooks of at most 256 values the handle carries a rank table (derived from the format arrays, one record of
+// Kp = 4 .. 256 32-bit words per row at a fixed stride): word 0 is the row's first colI position, word k the end of its
 // group of rank k (the previous word where the row has no element of that rank).  A wave finds its record from the row
 // number alone, so the first trip to memory already brings the row's start, its end and every group boundary; the
 // second trip fetches the indices, and the group list, the boundary bitmap and the weights of the first batch are
@@ -532,21 +532,23 @@ __global__ __launch_bounds__(1024) void cer_gemv_tab_kernel(const uint32_t* __re
     // 14 dwords of arguments: all of them are preloaded into scalar registers when a wave starts (the library is
     // built with kernel-argument preloading), so no instruction in front of the first memory request waits for a
     // load of the argument block.  For the same reason the workgroup size comes from `meta`, not from the dispatch
-    // packet, and Omega[0] from Omega.  meta = K | log2(words per record) << 8 | log2(waves per row) << 12 |
+    // packet, and Omega[0] from Omega.  meta = K | log2(words per record) << 9 | log2(waves per row) << 13 |
     // waves per workgroup << 16.
     using S = GemvShape<IdxT>;
     extern __shared__ __align__(16) unsigned char smem[];
-    const uint32_t K = meta & 0xFFu, tab_shift = (meta >> 8) & 0xFu;
+    const uint32_t K = meta & 0x1FFu, tab_shift = (meta >> 9) & 0xFu;
     const uint32_t nwaves = meta >> 16, bdim = nwaves * kWave;
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = uniform(threadIdx.x >> 6);
 
-    // LDS: [X: n floats, rounded to 4] [ends | wts: nwaves x 68] [bitmap | word prefix: nwaves x NWORDS]
+    // LDS: [X: n floats, rounded to 4] [ends | wts: nwaves x lcap] [bitmap | word prefix: nwaves x NWORDS]
     //      [counter of staged waves, 16 sums of X, 16 partial row sums].  The kernel has no static LDS, so X sits at
     //      LDS address 0 and a gather's address is 4 x the column index.
     float* xs = reinterpret_cast<float*>(smem);
     const uint32_t x_floats = (n + 3u) & ~3u;
-    constexpr uint32_t lcap = 68;  // the pseudo group in front of the row, at most 63 groups, two sentinels
+    const uint32_t last_word = (1u << tab_shift) - 1u;
+    const uint32_t ntiles = (last_word >> 6) + 1u;  // 64 ranks per tile: 1, 2 or 4 tiles
+    const uint32_t lcap = max(last_word, 63u) + 5u;  // the pseudo group in front of the row, the groups, two sentinels
     uint32_t* list0 = reinterpret_cast<uint32_t*>(xs + x_floats);
     uint32_t* ends = list0 + wave * lcap;
     float* wts = reinterpret_cast<float*>(list0 + nwaves * lcap) + wave * lcap;
@@ -556,17 +558,31 @@ __global__ __launch_bounds__(1024) void cer_gemv_tab_kernel(const uint32_t* __re
     float* s_xsum = reinterpret_cast<float*>(s_staged + 4);
     float* s_share = s_xsum + 16;
 
-    const uint32_t part_shift = kOneRow ? (meta >> 12) & 0xFu : 0u;
+    const uint32_t part_shift = kOneRow ? (meta >> 13) & 0x7u : 0u;
     const uint32_t parts = 1u << part_shift, part = wave & (parts - 1u);
     const uint32_t row_begin = blockIdx.x * rows_per_block;
     const uint32_t row_end = min(m, row_begin + rows_per_block);
     const IdxT* colI = static_cast<const IdxT*>(colI_);
     uint32_t r = row_begin + (wave >> part_shift);  // wave-uniform
-    const uint32_t last_word = (1u << tab_shift) - 1u;
 
-    // (1) the row's record, one word per lane (a wave without a row reads the last row's and ignores it), and Omega
-    uint32_t rec = tab[((size_t)min(r, m - 1u) << tab_shift) + min(lane, last_word)];
+    // (1) the row's record, one word per lane and tile (a wave without a row reads the last row's and ignores it),
+    //     and Omega: Omega[lane] (lane 0: Omega[0]; the next lane's value is the one of the group of rank lane + 1),
+    //     for further tiles the value of the lane's rank itself
+    auto load_rec = [&](uint32_t row, uint32_t t) { return tab[((size_t)row << tab_shift) + min(t * kWave + lane, last_word)]; };
+    uint32_t rec = load_rec(min(r, m - 1u), 0u), rec1 = 0u, rec2 = 0u, rec3 = 0u;
     const float om_l = omega_[min(lane, K - 1u)];
+    float wq0 = 0.f, wq1 = 0.f, wq2 = 0.f, wq3 = 0.f;
+    if (ntiles > 1u) {  // wave-uniform
+        rec1 = load_rec(min(r, m - 1u), 1u);
+        wq0 = omega_[min(lane + 1u, K - 1u)];  // lane 63: rank 64, which the shifted Omega[lane] cannot supply
+        wq1 = omega_[min(1u * kWave + lane + 1u, K - 1u)];
+    }
+    if (ntiles > 2u) {
+        rec2 = load_rec(min(r, m - 1u), 2u);
+        rec3 = load_rec(min(r, m - 1u), 3u);
+        wq2 = omega_[min(2u * kWave + lane + 1u, K - 1u)];
+        wq3 = omega_[min(3u * kWave + lane + 1u, K - 1u)];
+    }
     __builtin_amdgcn_sched_barrier(0);
     // The counter of staged waves starts at zero: one early barrier that no wave waits at for memory -- in front of
     // the X loads, whose issue is what takes time (a compute unit's vector-memory pipeline accepts a 16-byte-per-lane
@@ -594,11 +610,12 @@ __global__ __launch_bounds__(1024) void cer_gemv_tab_kernel(const uint32_t* __re
     uint32_t rs, re;
     float omega0, w_l;  // Omega[0] and the weight of the group of rank lane + 1 (ranks stay below K <= 64)
 #define CER_RECORD_HERE                                                                                       \
-    if (r >= row_end) rec = 0u; /* no row: no groups */                                                       \
+    if (r >= row_end) rec = rec1 = rec2 = rec3 = 0u; /* no row: no groups */                                  \
     rs = (uint32_t)__builtin_amdgcn_readlane((int)rec, 0);                                                    \
-    re = (uint32_t)__builtin_amdgcn_readlane((int)rec, (int)last_word);                                       \
+    re = ntiles == 1u ? (uint32_t)__builtin_amdgcn_readlane((int)rec, (int)(last_word & 63u))                 \
+                      : (uint32_t)__builtin_amdgcn_readlane((int)(ntiles == 2u ? rec1 : rec3), 63);           \
     omega0 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(om_l)));                            \
-    w_l = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(om_l), 0x130 /* wave_shl:1 */, 0xF, 0xF, false)) - omega0;
+    w_l = (ntiles > 1u ? wq0 : __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(om_l), 0x130 /* wave_shl:1 */, 0xF, 0xF, false))) - omega0;
     if (big) {
         xr0 = X4[CER_STAGE_IDX(0)]; xr1 = X4[CER_STAGE_IDX(1)]; xr2 = X4[CER_STAGE_IDX(2)];
         xr3 = X4[CER_STAGE_IDX(3)]; xr4 = X4[CER_STAGE_IDX(4)]; xr5 = X4[CER_STAGE_IDX(5)];
@@ -671,17 +688,34 @@ __global__ __launch_bounds__(1024) void cer_gemv_tab_kernel(const uint32_t* __re
 
     // (5) group list, bitmap and weights of the first batch, while the indices are on their way: lane l holds the
     //     group of rank l + 1, which ends where the next lane's group begins
-    auto record_tile = [&](uint32_t rc) {
+    // tile t of a record: lane l holds the group of rank 64 t + l + 1; `next` = the first word of the next tile
+    auto record_tile = [&](uint32_t rc, uint32_t next, uint32_t t) {
         PtrTile p;
         p.s = rc;
         p.e = (uint32_t)__builtin_amdgcn_update_dpp((int)rc, (int)rc, 0x130 /* wave_shl:1 */, 0xF, 0xF, false);
-        if (lane >= last_word) p.e = p.s;
-        p.rank = lane + 1u;
+        if (lane == (uint32_t)kWave - 1u) p.e = next;
+        if (t * kWave + lane >= last_word) p.e = p.s;
+        p.rank = t * kWave + lane + 1u;
         return p;
     };
-    if (lane == 0) { ends[0] = rs; wts[0] = 0.f; }
-    int count0 = list_append(record_tile(rec), w_l, ends, wts, 1);
-    list_close(ends, wts, count0, lane);
+    // the row's list from its record: the pseudo group in front of the row, then the non-empty groups
+    auto build_list = [&]() {
+        if (lane == 0) { ends[0] = rs; wts[0] = 0.f; }
+        const uint32_t n1 = (uint32_t)__builtin_amdgcn_readlane((int)rec1, 0);
+        int count = list_append(record_tile(rec, n1, 0u), w_l, ends, wts, 1);
+        if (ntiles > 1u) {
+            const uint32_t n2 = (uint32_t)__builtin_amdgcn_readlane((int)rec2, 0);
+            count = list_append(record_tile(rec1, n2, 1u), wq1 - omega0, ends, wts, count);
+        }
+        if (ntiles > 2u) {
+            const uint32_t n3 = (uint32_t)__builtin_amdgcn_readlane((int)rec3, 0);
+            count = list_append(record_tile(rec2, n3, 2u), wq2 - omega0, ends, wts, count);
+            count = list_append(record_tile(rec3, 0u, 3u), wq3 - omega0, ends, wts, count);
+        }
+        list_close(ends, wts, count, lane);
+        return count;
+    };
+    int count0 = build_list();
     uint32_t first = 0;
     float wl0[S::NW][S::PPL];
     const bool run0 = count0 > 1 && b00 < re0;  // wave-uniform
@@ -722,13 +756,14 @@ __global__ __launch_bounds__(1024) void cer_gemv_tab_kernel(const uint32_t* __re
             b0 = b00 + (uint32_t)S::BATCH;
             te = re0;
         } else {
-            rec = tab[((size_t)r << tab_shift) + min(lane, last_word)];
+            rec = load_rec(r, 0u);
+            if (ntiles > 1u) rec1 = load_rec(r, 1u);
+            if (ntiles > 2u) { rec2 = load_rec(r, 2u); rec3 = load_rec(r, 3u); }
             rs = (uint32_t)__builtin_amdgcn_readlane((int)rec, 0);
-            re = (uint32_t)__builtin_amdgcn_readlane((int)rec, (int)last_word);
+            re = ntiles == 1u ? (uint32_t)__builtin_amdgcn_readlane((int)rec, (int)(last_word & 63u))
+                              : (uint32_t)__builtin_amdgcn_readlane((int)(ntiles == 2u ? rec1 : rec3), 63);
             acc0 = acc1 = 0.f;
-            if (lane == 0) { ends[0] = rs; wts[0] = 0.f; }
-            count = list_append(record_tile(rec), w_l, ends, wts, 1);
-            list_close(ends, wts, count, lane);
+            count = build_list();
             wave_lds_sync();
             b0 = rs & ~((uint32_t)S::PPL - 1u);
             te = re;
@@ -781,22 +816,29 @@ __global__ __launch_bounds__(1024) void cer_gemv_tab_kernel(const uint32_t* __re
     }
 }
 
-// Builds the rank table of a handle whose codebook has 2 .. 64 values from its format arrays: one wave per row.
+// Builds the rank table of a handle whose codebook has 2 .. 256 values from its format arrays: one wave per row.
 __global__ __launch_bounds__(256) void rank_table_kernel(KView v, uint32_t* __restrict__ tab, uint32_t tab_shift) {
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t r = blockIdx.x * (blockDim.x >> 6) + uniform(threadIdx.x >> 6);
     if (r >= v.m) return;
     const uint2 d0 = v.rowInfo[r], d1 = v.rowInfo[r + 1];
-    const uint32_t g0 = d0.x, ng = d1.x - g0;  // at most 63 groups
-    // the number of the row's groups whose rank is at most `lane`: CER numbers its groups by rank (padding groups
-    // included), CSER names each group's rank in OmegaI (ascending inside a row)
-    uint32_t upto = min(lane, ng);
-    if (v.cser) {
-        const uint32_t mine = lane < ng ? load_rank(v.omegaI, v.omegaI_bits, g0 + lane) : kNoEnd;
-        upto = 0;
-        for (uint32_t j = 0; j < ng; ++j) upto += (uint32_t)__shfl((int)mine, (int)j, kWave) <= lane ? 1u : 0u;
+    const uint32_t g0 = d0.x, ng = d1.x - g0;  // at most 255 groups
+    const uint32_t words = 1u << tab_shift;
+    for (uint32_t w0 = 0; w0 < words; w0 += kWave) {
+        const uint32_t word = w0 + lane;
+        // the number of the row's groups whose rank is at most `word`: CER numbers its groups by rank (padding groups
+        // included), CSER names each group's rank in OmegaI (ascending inside a row)
+        uint32_t upto = min(word, ng);
+        if (v.cser) {
+            upto = 0;
+            for (uint32_t j0 = 0; j0 < ng; j0 += kWave) {  // wave-uniform bounds
+                const uint32_t mine = j0 + lane < ng ? load_rank(v.omegaI, v.omegaI_bits, g0 + j0 + lane) : kNoEnd;
+                const uint32_t nj = min((uint32_t)kWave, ng - j0);
+                for (uint32_t j = 0; j < nj; ++j) upto += (uint32_t)__shfl((int)mine, (int)j, kWave) <= word ? 1u : 0u;
+            }
+        }
+        if (word < words) tab[((size_t)r << tab_shift) + word] = v.omegaPtr[g0 + upto];
     }
-    if (lane < (1u << tab_shift)) tab[((size_t)r << tab_shift) + lane] = v.omegaPtr[g0 + upto];
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -951,11 +993,15 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
     const bool x_in_lds = gemv_stages_x(d, o);
     // codebooks of at most 64 values with X in LDS: the kernel over the rank table (lists of 68 entries, Omega read
     // once per lane from global memory)
-    const bool use_tab = x_in_lds && d.rank_tab != nullptr && (o.flags & kOptNoRankTable) == 0 && k.m > 0 && k.K >= 2;
+    // (its lists have a fixed length: X and the lists of four waves must fit)
+    const size_t tab_list_bytes = ((size_t)std::max<uint32_t>(64u, 1u << d.rank_tab_shift) + 4) * 8 + GemvShape<IdxT>::NWORDS * 8;
+    const bool use_tab = x_in_lds && d.rank_tab != nullptr && (o.flags & kOptNoRankTable) == 0 && k.m > 0 && k.K >= 2 &&
+                         x_bytes + 4 * tab_list_bytes + 256 <= budget;
     const bool omega_in_lds = !use_tab && k.K <= 4096;
     const size_t om_bytes = omega_in_lds ? (((size_t)k.K + 3) & ~(size_t)3) * sizeof(float) : 0;
     // per-wave list of non-empty groups: as long as the longest row needs, at most 1022 entries
-    uint32_t gcap = use_tab ? 65u : std::max<uint32_t>(1u, (uint32_t)std::min<int64_t>(d.max_row_groups, 1022));
+    uint32_t gcap = use_tab ? std::max<uint32_t>(64u, 1u << d.rank_tab_shift) + 1u  // lists of max(64, words per record) + 4
+                            : std::max<uint32_t>(1u, (uint32_t)std::min<int64_t>(d.max_row_groups, 1022));
     // per wave: the list (a pseudo group, the groups, two sentinels), the batch's bitmap and its word prefix
     auto list_bytes = [&](int waves) {
         return (size_t)waves * ((gcap + 3) * 8 + GemvShape<IdxT>::NWORDS * 8) + (use_tab ? 256u : 0u);  // + counter and sums
@@ -994,7 +1040,7 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
     // eight 16-byte loads per thread should cover X (what is left is copied by a plain loop)
     if (x_in_lds) waves = std::max(waves, (int)std::min<uint32_t>(16u, pow2_ceil((uint32_t)((x_bytes / 16 + 511) / 512))));
     while (fixed + list_bytes(waves) > budget && waves > 4) waves >>= 1;
-    while (fixed + list_bytes(waves) > budget && gcap > 64) gcap = std::max<uint32_t>(64u, gcap / 2);
+    while (!use_tab && fixed + list_bytes(waves) > budget && gcap > 64) gcap = std::max<uint32_t>(64u, gcap / 2);
     const size_t lds = fixed + list_bytes(waves);
     if (lds > budget) return hipErrorInvalidValue;
     // resident workgroups per CU, limited by LDS and by 32 waves per CU
@@ -1036,7 +1082,7 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
             }
             if (c.load(std::memory_order_acquire) != 1) return hipErrorInvalidDeviceFunction;
         }
-        const uint32_t meta = k.K | ((uint32_t)d.rank_tab_shift << 8) | (part_shift << 12) | ((uint32_t)waves << 16);
+        const uint32_t meta = k.K | ((uint32_t)d.rank_tab_shift << 9) | (part_shift << 13) | ((uint32_t)waves << 16);
         hipLaunchKernelGGL(tk, dim3(blocks), dim3(waves * kWave), lds, stream, d.rank_tab, X, k.omega, k.colI, Y, k.n, k.m,
                            rows_per_block, meta);
         return hipGetLastError();

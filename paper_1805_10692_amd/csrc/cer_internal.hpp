@@ -78,7 +78,7 @@ struct DeviceView {
     const void* strip_idx = nullptr;
     const uint32_t* strip_ptr = nullptr;
     uint32_t n_strips = 0;
-    // Rank table (derived; null unless the codebook has 2 .. 64 values): per row 1 << rank_tab_shift words at a fixed
+    // Rank table (derived; null unless the codebook has 2 .. 256 values): per row 1 << rank_tab_shift words at a fixed
     // stride, word 0 = the row's first colI position, word k = end of its group of rank k (the previous word when the
     // row has no element of that rank), the same for CER and CSER handles.
     const uint32_t* rank_tab = nullptr;
