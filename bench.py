@@ -110,9 +110,21 @@ def read_traffic(workload: str, fmt: str):
     return float(f.group(1)) + float(w.group(1)), rel + " (recorded rocprofv3 --pmc runs of this command; not collected in this run)"
 
 
+SETTLE_S = 0.1
+
+
 def time_steps(fn, steps: int, warmup: int):
     """(wall ms per step, HIP-event ms per step) over exactly `steps` calls after `warmup` calls."""
     import torch
+    # The GPU raises its clocks only under sustained load (the first 10 - 20 ms after an idle phase run up to 10 %
+    # slower): untimed launches of the same step for SETTLE_S seconds, then the warm-up steps, then the timed ones.
+    t_settle = time.perf_counter()
+    i = 0
+    while time.perf_counter() - t_settle < SETTLE_S:
+        for _ in range(50):
+            fn(i)
+            i += 1
+        torch.cuda.synchronize()
     for i in range(warmup):
         fn(i)
     torch.cuda.synchronize()
