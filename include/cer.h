@@ -9,12 +9,15 @@
  *   CSER (Compressed Shared Elements Row,  Section III-A): the same plus OmegaI
  *
  * and computes Y = W.X on the GPU from those arrays (Appendix A-C, Algorithms 3 and 4): per row,
- * the inputs selected by one group of column indices are summed and the sum is multiplied once
- * by the group's value; the most frequent value Omega[0] owns no indices and is handled by a
- * constant term (Appendix A-A1).  That order of operations is kept where it is the fastest on
- * this machine (one input vector, rows of long groups); elsewhere the same sum is formed with
- * one multiply-add per indexed element, or from the decoded matrix on the matrix cores --
- * cer_matmul_path tells which.
+ * the inputs selected by the groups of column indices, each weighted by its group's value; the
+ * most frequent value Omega[0] owns no indices and is handled by a constant term (Appendix
+ * A-A1).  The paper's algorithm sums a group's inputs first and multiplies the sum once.  On
+ * MI355X a multiply-add costs what an add costs, and what the format saves is the bytes it does
+ * not read; the default kernels therefore form the same sum with one multiply-add per indexed
+ * element (the element's weight comes from the group boundaries without any search), a variant
+ * that sums first is kept for the batched product, and wide batches of matrices that are not
+ * sparse enough are multiplied from the decoded matrix on the matrix cores -- cer_matmul_path
+ * tells which.
  *
  * Conventions
  *   - Every function returns CER_OK (0) or a negative CER_E_* code; nothing aborts or throws
@@ -83,8 +86,10 @@ enum {
  *             its largest possible value: colI n-1, OmegaPtr nnz, rowPtr G, OmegaI K-1 (Section V).
  *
  * If a HIP device is present the arrays are also uploaded to the current device (one
- * allocation; colI and OmegaI at their minimal width, the pointer arrays as uint32); with no
- * device the handle is host-only and *_matmul returns CER_E_HIP.
+ * allocation; colI and OmegaI at their minimal width, the pointer arrays as uint32, followed by
+ * two arrays derived from them on the device: 8 bytes per row that name the row's first group
+ * and first colI position, and, for 2 - 256 values, the rank table described at cer_matmul_ex);
+ * with no device the handle is host-only and *_matmul returns CER_E_HIP.
  * m = 0 or n = 0 is allowed (empty arrays).  Errors: CER_E_INVALID, CER_E_BAD_CODEBOOK,
  * CER_E_NOT_IN_CODEBOOK, CER_E_TOO_LARGE, CER_E_NOMEM, CER_E_HIP (upload failed).
  */
@@ -148,10 +153,12 @@ int cer_trim(void);
 
 /*
  * cer_matmul_path -- which kernel cer_matmul / cser_matmul runs for this handle and batch:
- *   0  CER_PATH_GEMV: batch-1 kernel: X staged in LDS per workgroup, one wave per row, the paper's
- *      arithmetic (the inputs of a group are summed, then multiplied once)
- *   4  CER_PATH_GEMV_EXPAND: batch-1 kernel for rows of many short groups (fewer than 30 indices per
- *      non-empty group on average, e.g. 8-bit codebooks) and for short rows: the group values are
+ *   0  CER_PATH_GEMV: batch-1 kernel, always taken for batch 1: X staged in LDS per workgroup (read
+ *      from global memory when it does not fit), one wave per row (4 or 8 waves per row in matrices
+ *      of at most two rows per compute unit), colI read with 16-byte loads, the weight of every
+ *      position derived from a bitmap of the group boundaries, one multiply-add per position.
+ *      Handles of 2 - 256 values with X in LDS use their rank table (below) to find the boundaries
+ *   4  CER_PATH_GEMV_EXPAND: an earlier batch-1 kernel, only on request: the group values are
  *      expanded per colI position into LDS and every input is multiplied by its position's value;
  *      needs X to fit in LDS
  *   1  CER_PATH_GEMM: batched kernel that gathers rows of X from L2, one wave per (row, tile of batch
@@ -204,9 +211,11 @@ int cer_matmul_path(const cer_handle_t* h, int64_t batch);
  *                                                 2048 positions at a time (default: by the average row)
  *                    CER_OPT_NO_RANK_TABLE        kernel 0: find the group boundaries through rowPtr and
  *                                                 OmegaPtr even when the handle has a rank table
- *                                                 (a derived array of handles with 2 - 64 values: per
- *                                                 row its first colI position and the end of the group
- *                                                 of every rank, at a fixed stride)
+ *                                                 (a derived array of handles with 2 - 256 values:
+ *                                                 per row its first colI position and the end of the
+ *                                                 group of every rank, at a fixed stride, 4 bytes per
+ *                                                 row and rank; it lets a wave fetch all boundaries
+ *                                                 of its row with its first memory request)
  * opts == NULL is cer_matmul's behaviour.  Errors: those of cer_matmul; CER_E_INVALID also for an
  * undefined path, tile width or flag.
  */
@@ -275,8 +284,10 @@ int cer_get_stats(const cer_handle_t* h, double* H, double* p0, double* k_bar, d
  */
 int cer_clone_device(const cer_handle_t* h, cer_handle_t** out);
 
-/* Bytes of device memory the product reads from the handle's arrays in one call (colI at its
- * width + uint32 OmegaPtr and rowPtr + OmegaI + Omega); 0 for a host-only handle. */
+/* Bytes of the format arrays on the device (colI at its width + uint32 OmegaPtr and rowPtr + OmegaI
+ * + Omega): the algorithmic traffic of one product; 0 for a host-only handle.  (A product that goes
+ * through the rank table reads that table -- 4 bytes per row and rank, rounded up to a power of two
+ * ranks -- in place of OmegaPtr, rowPtr and OmegaI.) */
 int64_t cer_device_bytes(const cer_handle_t* h);
 
 /* Matrices with rows of unequal length (longest row above twice the average and at least 2048

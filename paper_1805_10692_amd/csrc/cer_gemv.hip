@@ -289,9 +289,11 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
         if (mine < re) { b00 = mine; re0 = min(re, mine + share); } else { re0 = b00; }  // an empty share does nothing
     }
     {
+        // a window that lies behind the row's end asks for the first window again: the loads stay unconditional,
+        // but the next rows' indices are not fetched from memory a second time
         const uint4* p = reinterpret_cast<const uint4*>(colI + b00) + lane;
 #pragma unroll
-        for (int W = 0; W < S::NW; ++W) idx0[W] = p[W * kWave];
+        for (int W = 0; W < S::NW; ++W) idx0[W] = p[(b00 + (uint32_t)W * S::WIN < re0 ? W : 0) * kWave];
     }
     // a first row of more than 64 raw groups: the next three pointer tiles as well (behind the indices in the queue)
     const uint32_t tg_end0 = min(g1, g0 + gcap);
@@ -467,7 +469,8 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
 #define CER_REQUEST(ix, b)                                                                       \
     {                                                                                            \
         const uint4* p_ = reinterpret_cast<const uint4*>(colI + (b)) + lane;                     \
-        _Pragma("unroll") for (int W = 0; W < S::NW; ++W) ix[W] = p_[W * kWave];                 \
+        _Pragma("unroll") for (int W = 0; W < S::NW; ++W)                                        \
+            ix[W] = p_[((b) + (uint32_t)W * S::WIN < te ? W : 0) * kWave];                        \
     }
 #define CER_BATCH(ix, b)                                                                         \
     bitmap_build<S>(ends, (uint32_t)count + 1u, first, b, bmp, wpre, lane);                      \
@@ -646,9 +649,11 @@ __global__ __launch_bounds__(1024) void cer_gemv_tab_kernel(const uint32_t* __re
     __builtin_amdgcn_sched_barrier(0);
     uint4 idx0[S::NW];
     {
+        // a window that lies behind the row's end asks for the first window again: the loads stay unconditional,
+        // but the next rows' indices are not fetched from memory a second time
         const uint4* p = reinterpret_cast<const uint4*>(colI + b00) + lane;
 #pragma unroll
-        for (int W = 0; W < S::NW; ++W) idx0[W] = p[W * kWave];
+        for (int W = 0; W < S::NW; ++W) idx0[W] = p[(b00 + (uint32_t)W * S::WIN < re0 ? W : 0) * kWave];
     }
     __builtin_amdgcn_sched_barrier(0);
 
@@ -776,7 +781,8 @@ __global__ __launch_bounds__(1024) void cer_gemv_tab_kernel(const uint32_t* __re
 #define CER_REQUEST(ix, b)                                                                       \
     {                                                                                            \
         const uint4* p_ = reinterpret_cast<const uint4*>(colI + (b)) + lane;                     \
-        _Pragma("unroll") for (int W = 0; W < S::NW; ++W) ix[W] = p_[W * kWave];                 \
+        _Pragma("unroll") for (int W = 0; W < S::NW; ++W)                                        \
+            ix[W] = p_[((b) + (uint32_t)W * S::WIN < te ? W : 0) * kWave];                        \
     }
 #define CER_BATCH(ix, b)                                                                         \
     bitmap_build<S>(ends, (uint32_t)count + 1u, first, b, bmp, wpre, lane);                      \
