@@ -28,11 +28,14 @@ namespace {
 //   * the stream itself is, per position, an LDS gather of X and one fused multiply-add with the position's weight
 //     (a multiply-add costs what an add costs; summing a group first would need the branches this design avoids).
 
-template <typename IdxT>
+// kNW: windows per batch, 0 = the default (2, 3, 4 for 8-, 16-, 32-bit indices: a batch of 2048, 1536, 1024 positions --
+// one batch for the rows of the layer shapes).  Rows of many windows run faster in batches of two windows (the 7-bit
+// layer of 7000 indices per row: 15.1 us with 3 windows per batch, 14.2 with 2, 14.9 with 1, 14.7 with 4).
+template <typename IdxT, int kNW = 0>
 struct GemvShape {
     static constexpr int PPL = 16 / (int)sizeof(IdxT);  // positions per lane and 16-byte load: 16, 8, 4
     static constexpr int WIN = kWave * PPL;             // positions per window (one load per lane)
-    static constexpr int NW = sizeof(IdxT) == 1 ? 2 : (sizeof(IdxT) == 2 ? 3 : 4);  // windows per batch
+    static constexpr int NW = kNW ? kNW : (sizeof(IdxT) == 1 ? 2 : (sizeof(IdxT) == 2 ? 3 : 4));  // windows per batch
     static constexpr int BATCH = NW * WIN;              // 2048, 1536, 1024 positions
     static constexpr int NWORDS = BATCH / 32;           // bitmap words per batch: 64, 48, 32 (at most one per lane)
     static constexpr int WPW = WIN / 32;                // bitmap words per window
@@ -165,11 +168,10 @@ __device__ __forceinline__ uint32_t packed_offset(const uint4& q, int k, uint32_
 // that start at or behind the row's end (te) are skipped.
 // kLds: X is in LDS at byte address xlds (a literal 0 where the kernel has no static LDS: the gather's address is then
 // the shifted index itself); otherwise xsrc points to X in global memory.
-template <typename IdxT, bool kLds>
-__device__ __forceinline__ void gemv_batch(const uint4 (&ix)[GemvShape<IdxT>::NW], const float* xsrc, uint32_t xlds, uint32_t b0,
-                                           uint32_t te, const float (&wl)[GemvShape<IdxT>::NW][GemvShape<IdxT>::PPL],
+template <typename S, typename IdxT, bool kLds>
+__device__ __forceinline__ void gemv_batch(const uint4 (&ix)[S::NW], const float* xsrc, uint32_t xlds, uint32_t b0,
+                                           uint32_t te, const float (&wl)[S::NW][S::PPL],
                                            float& acc0, float& acc1) {
-    using S = GemvShape<IdxT>;
 #pragma unroll
     for (int W = 0; W < S::NW; ++W) {
         if (W > 0 && b0 + (uint32_t)W * S::WIN >= te) break;  // wave-uniform
@@ -422,7 +424,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
         }
     }
     if (r < row_end && count0 > 1 && b00 < te0) {
-        gemv_batch<IdxT, kXinLds>(idx0, xsrc, xlds, b00, te0, wl0, acc0, acc1);
+        gemv_batch<S, IdxT, kXinLds>(idx0, xsrc, xlds, b00, te0, wl0, acc0, acc1);
         resume = true;
     }
 
@@ -476,7 +478,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
     bitmap_build<S>(ends, (uint32_t)count + 1u, first, b, bmp, wpre, lane);                      \
     _Pragma("unroll") for (int W = 0; W < S::NW; ++W)                                            \
         if (W == 0 || (b) + (uint32_t)W * S::WIN < te) window_weights<S>(W, bmp, wpre, wts, lane, wl[W]); \
-    gemv_batch<IdxT, kXinLds>(ix, xsrc, xlds, b, te, wl, acc0, acc1);
+    gemv_batch<S, IdxT, kXinLds>(ix, xsrc, xlds, b, te, wl, acc0, acc1);
                 CER_REQUEST(ixa, b0)
                 for (;;) {
                     const uint32_t b1 = b0 + S::BATCH;
@@ -527,7 +529,8 @@ __global__ __launch_bounds__(1024) void cer_gemv_kernel(const void* __restrict__
 // built while it is on its way.  CER and CSER handles have the same table, so the kernel does not know the format.
 // Everything else -- batches, windows, bitmap, shared rows, the staging of X -- is as in the kernel above.
 // kBigX: every wave of the workgroup has six whole 16-byte loads of X (6 x the workgroup size x 16 bytes <= 4n).
-template <typename IdxT, bool kVec4, bool kOneRow, bool kBigX>
+// kShortBatch: batches of two windows (16-bit indices, rows of more than three windows on average).
+template <typename IdxT, bool kVec4, bool kOneRow, bool kBigX, bool kShortBatch = false>
 __global__ __launch_bounds__(1024) void cer_gemv_tab_kernel(const uint32_t* __restrict__ tab, const float* __restrict__ X,
                                                             const float* __restrict__ omega_, const void* __restrict__ colI_,
                                                             float* __restrict__ Y, uint32_t n, uint32_t m,
@@ -537,7 +540,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_tab_kernel(const uint32_t* __re
     // load of the argument block.  For the same reason the workgroup size comes from `meta`, not from the dispatch
     // packet, and Omega[0] from Omega.  meta = K | log2(words per record) << 9 | log2(waves per row) << 13 |
     // waves per workgroup << 16.
-    using S = GemvShape<IdxT>;
+    using S = GemvShape<IdxT, (kShortBatch && sizeof(IdxT) == 2) ? 2 : 0>;
     extern __shared__ __align__(16) unsigned char smem[];
     const uint32_t K = meta & 0x1FFu, tab_shift = (meta >> 9) & 0xFu;
     const uint32_t nwaves = meta >> 16, bdim = nwaves * kWave;
@@ -750,7 +753,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_tab_kernel(const uint32_t* __re
 
     // (6) the stream: the first batch from the prefetched indices, then the rest of the row, then further rows
     float acc0 = 0.f, acc1 = 0.f;
-    if (run0) gemv_batch<IdxT, true>(idx0, xs, 0u, b00, re0, wl0, acc0, acc1);
+    if (run0) gemv_batch<S, IdxT, true>(idx0, xs, 0u, b00, re0, wl0, acc0, acc1);
     bool first_row = true;
     float y_share = 0.f;
     for (; r < row_end; r += nwaves) {
@@ -788,7 +791,7 @@ __global__ __launch_bounds__(1024) void cer_gemv_tab_kernel(const uint32_t* __re
     bitmap_build<S>(ends, (uint32_t)count + 1u, first, b, bmp, wpre, lane);                      \
     _Pragma("unroll") for (int W = 0; W < S::NW; ++W)                                            \
         if (W == 0 || (b) + (uint32_t)W * S::WIN < te) window_weights<S>(W, bmp, wpre, wts, lane, wl[W]); \
-    gemv_batch<IdxT, true>(ix, xs, 0u, b, te, wl, acc0, acc1);
+    gemv_batch<S, IdxT, true>(ix, xs, 0u, b, te, wl, acc0, acc1);
             CER_REQUEST(ixa, b0)
             for (;;) {
                 const uint32_t b1 = b0 + S::BATCH;
@@ -1067,19 +1070,25 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
         using TabKern = void (*)(const uint32_t*, const float*, const float*, const void*, float*, uint32_t, uint32_t, uint32_t,
                                  uint32_t);
         const bool bigx = vec4 && 6ull * (uint64_t)waves * kWave <= (uint64_t)(k.n >> 2);
+        // 16-bit indices, rows of more than three windows on average: batches of two windows
+        const bool shortb = sizeof(IdxT) == 2 && vec4 && (uint64_t)d.nnz > 3ull * GemvShape<IdxT>::WIN * (uint64_t)k.m;
         TabKern tk = bigx ? (one ? cer_gemv_tab_kernel<IdxT, true, true, true> : cer_gemv_tab_kernel<IdxT, true, false, true>)
                      : vec4 ? (one ? cer_gemv_tab_kernel<IdxT, true, true, false> : cer_gemv_tab_kernel<IdxT, true, false, false>)
                             : (one ? cer_gemv_tab_kernel<IdxT, false, true, false> : cer_gemv_tab_kernel<IdxT, false, false, false>);
+        if (shortb)
+            tk = bigx ? (one ? cer_gemv_tab_kernel<IdxT, true, true, true, true> : cer_gemv_tab_kernel<IdxT, true, false, true, true>)
+                      : (one ? cer_gemv_tab_kernel<IdxT, true, true, false, true> : cer_gemv_tab_kernel<IdxT, true, false, false, true>);
         if (lds > 48 * 1024) {
-            static LdsGrant<18> grant;
+            static LdsGrant<36> grant;
             const int wslot = sizeof(IdxT) == 1 ? 0 : (sizeof(IdxT) == 2 ? 1 : 2);
-            const hipError_t e = grant.ensure(wslot * 6 + (bigx ? 4 : (vec4 ? 2 : 0)) + (one ? 1 : 0), reinterpret_cast<const void*>(tk), budget);
+            const hipError_t e = grant.ensure(wslot * 12 + (shortb ? 6 : 0) + (bigx ? 4 : (vec4 ? 2 : 0)) + (one ? 1 : 0),
+                                              reinterpret_cast<const void*>(tk), budget);
             if (e != hipSuccess) return e;
         }
         {   // the kernel takes LDS address 0 for X: it must not have static LDS in front of the dynamic array
-            static std::atomic<int> checked[3][6] = {};
+            static std::atomic<int> checked[3][12] = {};
             const int wslot = sizeof(IdxT) == 1 ? 0 : (sizeof(IdxT) == 2 ? 1 : 2);
-            std::atomic<int>& c = checked[wslot][(bigx ? 4 : (vec4 ? 2 : 0)) + (one ? 1 : 0)];
+            std::atomic<int>& c = checked[wslot][(shortb ? 6 : 0) + (bigx ? 4 : (vec4 ? 2 : 0)) + (one ? 1 : 0)];
             if (c.load(std::memory_order_acquire) == 0) {
                 hipFuncAttributes fa;
                 const hipError_t e = hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(tk));
