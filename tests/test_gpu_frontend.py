@@ -27,14 +27,17 @@ def _to_dev(a):
 
 
 def _check_product(h, fmt, W, X):
-    A_scale = oracle.abs_dot_dense(W, X, threads=8)
-    want = oracle.dot_dense(W, X, threads=8)
-    Yd = torch.full((W.shape[0], X.shape[1]), float("nan"), dtype=torch.float32, device=_gpu())
-    (B.cer_matmul if fmt == "cer" else B.cser_matmul)(h, _to_dev(X), Yd, X.shape[1])
-    torch.cuda.synchronize()
-    Y = Yd.cpu().numpy().astype(np.float64)
-    assert np.isfinite(Y).all()
-    assert np.all(np.abs(Y - want) <= TOL * A_scale)
+    """The product of a device-encoded handle at the case's batch and, where that is wider, at batch 1 as well (the
+    batch-1 kernel reads the rank table that the device-side encoder derives for the handle)."""
+    for Xb in ([X] if X.shape[1] == 1 else [X, np.ascontiguousarray(X[:, :1])]):
+        A_scale = oracle.abs_dot_dense(W, Xb, threads=8)
+        want = oracle.dot_dense(W, Xb, threads=8)
+        Yd = torch.full((W.shape[0], Xb.shape[1]), float("nan"), dtype=torch.float32, device=_gpu())
+        (B.cer_matmul if fmt == "cer" else B.cser_matmul)(h, _to_dev(Xb), Yd, Xb.shape[1])
+        torch.cuda.synchronize()
+        Y = Yd.cpu().numpy().astype(np.float64)
+        assert np.isfinite(Y).all()
+        assert np.all(np.abs(Y - want) <= TOL * A_scale)
 
 
 ENCODE_CASES = {
