@@ -178,8 +178,9 @@ def probe_stream(nbytes: int, steps: int = 1000) -> dict:
 
 
 def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: bool, with_dense: bool, opts=None,
-            cpu_timing: bool = True) -> dict:
-    """with_cpu: the oracle checks sampled rows of the timed buffers (and, with cpu_timing, is timed as cpu_baseline)."""
+            cpu_timing: bool = True, strips: bool = False) -> dict:
+    """with_cpu: the oracle checks sampled rows of the timed buffers (and, with cpu_timing, is timed as cpu_baseline).
+    strips: the handles get the strip-major index (cer_prepare_strips), so that the library may choose its strip kernel."""
     import torch
 
     from paper_1805_10692_amd import binding as B
@@ -220,9 +221,10 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
     if with_cpu:
         import oracle
         want, scale = oracle.dot_dense(Wr, w.X, threads=8), oracle.abs_dot_dense(Wr, w.X, threads=8)
+    want_strips = fmt != "csr" and L > 1 and (strips or (opts is not None and opts.path == B.CER_PATH_STRIP))
+    if want_strips:
+        B.cer_prepare_strips(h0)
     if opts is not None and fmt != "csr":
-        if opts.path == B.CER_PATH_STRIP:
-            B.cer_prepare_strips(h0)
         B.cer_matmul_ex(h0, Xd, Yd, L, None, opts)
     else:
         mm(h0, Xd, Yd, L)
@@ -237,7 +239,7 @@ def run_one(name: str, fmt: str, steps: int, warmup: int, warm: bool, with_cpu: 
     R = 1 if warm else max(2, -(-2 * LAST_LEVEL_CACHE_BYTES // max(fmt_bytes, 1)))
     R = min(R, 256)
     handles = [h0] + [clone(h0) for _ in range(R - 1)]
-    if opts is not None and fmt != "csr" and opts.path == B.CER_PATH_STRIP:
+    if want_strips:
         for h in handles:
             B.cer_prepare_strips(h)   # the strip-major index is per device copy
     stream = torch.cuda.current_stream().cuda_stream
@@ -481,6 +483,8 @@ def main() -> int:
     ap.add_argument("--probe-copy", type=int, default=0, metavar="MiB",
                     help="also launch the plain copy kernel on this many MiB (calibrates byte counters)")
     ap.add_argument("--path", type=int, default=-1, help="kernel to prefer (numbering of cer_matmul_path), -1 = the library's choice")
+    ap.add_argument("--strips", action="store_true",
+                    help="build the strip-major index of every handle (cer_prepare_strips): the library may then choose kernel 5")
     ap.add_argument("--flags", type=int, default=0, help="CER_OPT_* bits for cer_matmul_ex")
     ap.add_argument("--tile-cols", type=int, default=0, help="batch columns per tile for cer_matmul_ex")
     ap.add_argument("--report", default=None, help="write a table over workloads/formats to this JSON file")
@@ -509,7 +513,8 @@ def main() -> int:
     if args.path != -1 or args.flags or args.tile_cols:
         from paper_1805_10692_amd import binding as B
         opts = B.MatmulOpts(path=args.path, tile_cols=args.tile_cols, flags=args.flags)
-    r = run_one(args.workload, args.format, args.steps, args.warmup, args.warm, not args.no_cpu, not args.no_dense, opts)
+    r = run_one(args.workload, args.format, args.steps, args.warmup, args.warm, not args.no_cpu, not args.no_dense, opts,
+                strips=args.strips)
     traffic, traffic_source = read_traffic(args.workload, args.format)
     line = {
         "metric": METRIC, "value": r["dense_equiv_gflops"], "unit": "GFLOP/s (dense-equivalent, 2*m*n*L/t)",
@@ -575,6 +580,17 @@ def main() -> int:
                                      B.MatmulOpts(path=B.CER_PATH_GEMM))
                         rg["format"] = fmt + " (gather kernel)"
                         table.append(rg)
+                    if fmt != "csr" and rr["L"] >= 32 and rr["L"] % 32 == 0 and rr["K"] <= 64:
+                        # the same product with the strip-major index prepared: the strip kernel on request, and what
+                        # the library chooses by itself once the index exists
+                        from paper_1805_10692_amd import binding as B
+                        rs5 = run_one(nm, fmt, 20 if big else 300, 3 if big else 30, warm, False, False,
+                                      B.MatmulOpts(path=B.CER_PATH_STRIP))
+                        rs5["format"] = fmt + " (strip kernel)"
+                        table.append(rs5)
+                        ra = run_one(nm, fmt, 20 if big else 300, 3 if big else 30, warm, False, False, strips=True)
+                        ra["format"] = fmt + " (strip-major index prepared, library's choice)"
+                        table.append(ra)
                     print(f"[report] {nm} {fmt} {'warm' if warm else 'cold'}: {rr['ms_per_step'] * 1e3:.2f} us/step, "
                           f"{rr['algorithmic_GBps']:.0f} GB/s alg, speedup vs dense "
                           f"{rr.get('speedup_vs_dense_hip', float('nan')):.2f}", file=sys.stderr, flush=True)

@@ -647,13 +647,21 @@ int cer_prepare_strips(cer_handle_t* h) {
             }
         };
         for_each([&](uint64_t r, uint32_t, uint64_t c) { ++ptr[(size_t)((c / S) * (m + 1) + r) + 1]; });
-        // counts -> offsets; the entry after each strip's m rows stays a running total, so ptr[s * (m + 1) + m] closes row m - 1
-        for (size_t i = 1; i < ptr.size(); ++i) ptr[i] += ptr[i - 1];
-        std::vector<uint16_t> idx((size_t)A.nnz);
-        std::vector<uint32_t> fill(ptr.begin(), ptr.end() - 1);
+        // entries -> chunks of eight (the last chunk of a (strip, row) is padded with entries of rank 0: weight zero),
+        // then counts -> offsets; the entry after each strip's m rows stays a running total, so ptr[s * (m + 1) + m]
+        // closes row m - 1
+        for (size_t i = 1; i < ptr.size(); ++i) ptr[i] = (ptr[i] + 7u) / 8u;
+        for (size_t i = 1; i < ptr.size(); ++i) {
+            if ((uint64_t)ptr[i] + ptr[i - 1] >= 0xFFFFFFFFull) return CER_E_TOO_LARGE;
+            ptr[i] += ptr[i - 1];
+        }
+        const uint64_t nchunks = ptr.back();
+        std::vector<uint16_t> idx(((size_t)nchunks + 1) * 8, (uint16_t)0);  // one chunk of zeros closes the index
+        std::vector<uint64_t> fill(ptr.size() - 1);
+        for (size_t i = 0; i + 1 < ptr.size(); ++i) fill[i] = (uint64_t)ptr[i] * 8u;
         for_each([&](uint64_t r, uint32_t rank, uint64_t c) {
             const uint64_t s = c / S;
-            idx[fill[(size_t)(s * (m + 1) + r)]++] = (uint16_t)((rank << 10) | (uint32_t)(c - s * S));
+            idx[(size_t)fill[(size_t)(s * (m + 1) + r)]++] = (uint16_t)((rank << 10) | (uint32_t)(c - s * S));
         });
         const size_t idx_bytes = (idx.size() * 2 + 255) & ~(size_t)255, ptr_bytes = (ptr.size() - 1) * 4;
         void* base = nullptr;
@@ -670,6 +678,7 @@ int cer_prepare_strips(cer_handle_t* h) {
         h->view.strip_idx = base;
         h->view.strip_ptr = reinterpret_cast<const uint32_t*>(b8 + idx_bytes);
         h->view.n_strips = (uint32_t)ns;
+        h->view.strip_chunks = nchunks;
         return CER_OK;
     } catch (const std::bad_alloc&) {
         return CER_E_NOMEM;

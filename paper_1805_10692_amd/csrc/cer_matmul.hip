@@ -77,7 +77,8 @@ hipError_t launch_colsum(const float* X, uint32_t n, uint32_t L, float* part, ui
 // Narrow batches of a dense-ish matrix take the same route: a gather moves a whole 128-byte line however narrow the
 // batch, so a 4096 x 9216 layer quantized to 7 bits (71 % of the elements indexed) costs 171 us at batch 32 by
 // gathers, 70 us decoded (30 us) and multiplied by the dense kernel (40 us, itself bound by reading the matrix).
-bool densify_pays(const DeviceView& d, uint32_t L) {
+// Estimated durations (seconds) of the gathers and of decode + dense; false where the dense route is not available.
+bool densify_estimates(const DeviceView& d, uint32_t L, double* t_gather_out, double* t_dense_out) {
     if (L < 2 || d.m < 128 || d.n < 256) return false;
     const double mn = (double)d.m * (double)d.n;
     if (mn * 4.0 > (double)(1ull << 30)) return false;
@@ -91,7 +92,14 @@ bool densify_pays(const DeviceView& d, uint32_t L) {
     const double t_write = 4.0 * mn / 4.5e12;  // the decoded matrix goes to memory once and is read back at least once
     const double t_decode = t_write + (double)d.nnz * 1.5e-12 + 3e-6;  // measured 30 us (5.7 M indices) ... 88 us (28.7 M)
     const double t_dense = (flops < 5e9 ? 20e-6 : 12e-6) + std::max(flops / rate, t_write) + t_decode;
-    return t_gather > 1.1 * t_dense;
+    *t_gather_out = t_gather;
+    *t_dense_out = t_dense;
+    return true;
+}
+
+bool densify_pays(const DeviceView& d, uint32_t L) {
+    double t_gather = 0, t_dense = 0;
+    return densify_estimates(d, L, &t_gather, &t_dense) && t_gather > 1.1 * t_dense;
 }
 
 hipError_t launch_densified(const DeviceView& d, const float* X, float* Y, uint32_t L, hipStream_t stream) {
@@ -123,7 +131,8 @@ int choose_batched_path(const DeviceView& d, uint32_t L, const MatmulOptions& o,
     const bool has_elements = d.m > 0 && d.n > 0;
     // strips of X in LDS: on request (and only when the strip-major index was prepared); the partial sums of the strips
     // need a temporary.  X == nullptr: the question is asked without buffers (cer_matmul_path_ex): aligned ones assumed.
-    if (o.path == kPathStrip && !no_temporaries && strip_applicable(d, X, Y, L)) return kPathStrip;
+    const bool strips_ok = !no_temporaries && strip_applicable(d, X, Y, L);
+    if (o.path == kPathStrip && strips_ok) return kPathStrip;
     if (o.path == 3 && has_elements && !no_temporaries) return 3;
     if (o.path != 1 && o.path != 3) {
         const XtilePlan plan = plan_xtile(d, L);
@@ -132,7 +141,22 @@ int choose_batched_path(const DeviceView& d, uint32_t L, const MatmulOptions& o,
             return 2;
         }
     }
-    if (o.path < 0 && !no_temporaries && has_elements && densify_pays(d, L)) return 3;
+    // A handle whose strip-major index was prepared takes the strip kernel where its estimate beats that of the
+    // gathers from L2 (27 TB/s of whole 128-byte lines plus the start-up chain of a launch) and that of decode +
+    // dense: wide batches of large matrices -- AlexNet-fc6 shape, batch 32 / 64 / 128: 30 / 46 / 78 us against
+    // 33 / 57 / 107 us; VGG-fc6 shape, batch 128: 92 against 100 us (batch 32: 38 against 31 us, batch 64: 52 against
+    // 54 us: the gathers are kept; 3x3 convolution shape, batch 3136: 268 us against 159 us decoded and multiplied).
+    if (o.path < 0 && !no_temporaries && has_elements) {
+        double t_gather = 0, t_dense = 0;
+        const bool dense_ok = densify_estimates(d, L, &t_gather, &t_dense);
+        const bool dense_pays = dense_ok && t_gather > 1.1 * t_dense;
+        if (strips_ok) {
+            const double t_strip = plan_strip(d, L).est_us * 1e-6;
+            const double t_gather_l2 = 5e-6 + (double)d.nnz * std::max(4.0 * L, 128.0) / 27e12;
+            if (t_strip < 0.95 * t_gather_l2 && (!dense_pays || t_strip < t_dense)) return kPathStrip;
+        }
+        if (dense_pays) return 3;
+    }
     return 1;
 }
 

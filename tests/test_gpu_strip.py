@@ -74,3 +74,29 @@ def test_not_applicable_cases_fall_back():
         B.cer_prepare_strips(h)
     assert e.value.code == B.CER_E_TOO_LARGE
     B.cer_free(h)
+
+
+def test_library_chooses_the_strip_kernel_only_where_it_is_expected_to_win():
+    """Once the strip-major index exists the library itself may take kernel 5: wide batches of large matrices
+    (AlexNet-fc6 shape from batch 32 on), not batches whose partial sums outweigh the gain (VGG-fc6 shape at batch 32),
+    small matrices, or matrices that the dense route serves better (3 x 3 convolution shape at batch 3136); without the
+    index nothing changes.  The product of the library's own choice is checked like every other."""
+    dev = _gpu()
+    cases = [(wl.alexnet_fc6(L=32), B.CER_PATH_STRIP), (wl.alexnet_fc6(L=128), B.CER_PATH_STRIP),
+             (wl.vgg_fc6(L=32), B.CER_PATH_GEMM), (wl.sweep_cell(16, 0.9, L=32), B.CER_PATH_GEMM),
+             (wl.conv3x3(L=3136), B.CER_PATH_DENSE)]
+    for w, expect in cases:
+        print(f"auto case {w.name} L={w.L}", flush=True)
+        h = B.cer_encode(w.W, w.codebook)
+        before = B.cer_matmul_path(h, w.L)
+        assert before != B.CER_PATH_STRIP
+        B.cer_prepare_strips(h)
+        assert B.cer_matmul_path(h, w.L) == expect, (w.name, w.L)
+        if expect == B.CER_PATH_STRIP:
+            A = oracle.encode(w.W, w.codebook, "cer")
+            Xd = torch.from_numpy(np.ascontiguousarray(w.X)).to(dev)
+            Yd = torch.full((w.m, w.L), float("nan"), dtype=torch.float32, device=dev)
+            B.cer_matmul(h, Xd, Yd, w.L)
+            torch.cuda.synchronize()
+            check(Yd.cpu().numpy(), oracle.dot(A, w.X, threads=8), oracle.abs_dot_dense(w.W, w.X, threads=8), w.name)
+        B.cer_free(h)
