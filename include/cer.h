@@ -179,8 +179,10 @@ int cer_trim(void);
  *      decode and the dense contraction: wide batches of matrices with more than about one
  *      indexed element in five, any batch > 1 of matrices with most elements indexed.  The
  *      arithmetic is then that of a dense fp32 product (same error bound), not Algorithm 3 / 4.
- *   5  CER_PATH_STRIP: batched kernel with strips of 1024 input rows resident in LDS (see cer_prepare_strips);
- *      never chosen by the library itself
+ *   5  CER_PATH_STRIP: batched kernel with strips of 1024 input rows resident in LDS; needs the strip-major
+ *      index of cer_prepare_strips.  For a handle that has it the library chooses this kernel where its
+ *      estimated duration is below that of kernels 1 and 3: wide batches of large matrices (AlexNet-fc6
+ *      shape, batch 32 / 64 / 128: 30 / 46 / 78 us against 33 / 57 / 107 us with kernel 1)
  * On MI355X kernel 2 beats kernel 1 for narrow batches of large matrices (kernel 1 moves a whole
  * 128-byte line per index however narrow the batch) and loses for wide ones (random LDS gathers
  * are bank-conflict bound): it is chosen when it is applicable, batch <= 8 and the matrix holds
@@ -195,7 +197,7 @@ int cer_matmul_path(const cer_handle_t* h, int64_t batch);
  * library reads no environment variable: this call is the only way to steer it.
  *   opts->path       CER_PATH_AUTO, or the kernel to prefer (numbering of cer_matmul_path).  A
  *                    preferred kernel is taken whenever it is applicable to the handle and the batch
- *                    (0 / 4 for batch 1, 1 / 2 / 3 for batch > 1); where it is not, the library
+ *                    (0 / 4 for batch 1, 1 / 2 / 3 / 5 for batch > 1); where it is not, the library
  *                    chooses as cer_matmul does.  cer_matmul_path_ex tells which kernel will run.
  *   opts->tile_cols  kernel 1, batch a multiple of 4 with 16-byte aligned X and Y: batch columns per
  *                    tile, 8, 16, 32, 64 or 128; 0 = the library's choice
@@ -238,13 +240,16 @@ int cer_matmul_path_ex(const cer_handle_t* h, int64_t batch, const cer_matmul_op
  * cer_prepare_strips -- builds, once per handle, the strip-major index that kernel 5 (CER_PATH_STRIP) needs: the
  * column-blocked reuse of input elements (Section V-C).  X is cut into strips of 1024 consecutive rows; for
  * every strip and every row of W the index lists the row's indexed elements whose column falls into the strip, each
- * as 16 bits: the column inside the strip (10 bits) and the rank of the element's value in Omega (6 bits).  It is
- * DERIVED from the format arrays (which stay as they are): 2 bytes per indexed element plus 4 bytes per strip and
- * row of device memory.  Kernel 5 copies one strip of 32 batch columns into LDS per workgroup (128 KB), multiplies
- * every element of the strip's share of its rows by Omega[rank] - Omega[0], and leaves one partial sum per strip and
- * row in a stream-ordered temporary of strips x m x batch floats, which a second kernel adds up in strip order.
- * Applicable to codebooks of at most 64 values (CER_E_TOO_LARGE otherwise), batches that are a multiple of 32 columns
- * and 16-byte aligned X and Y; it runs only when cer_matmul_ex prefers CER_PATH_STRIP.
+ * as 16 bits: the rank of the element's value in Omega (6 bits) and the column inside the strip (10 bits), in chunks
+ * of eight entries (the last chunk of a strip's share of a row is filled up with entries of rank 0, whose weight
+ * Omega[0] - Omega[0] is zero).  It is DERIVED from the format arrays (which stay as they are): 2 bytes per indexed
+ * element, up to 14 bytes of padding and a 4-byte pointer per strip and row, in device memory of its own.  Kernel 5
+ * copies one strip of 32 batch columns into LDS per workgroup (128 KB), multiplies every element of the strip's share
+ * of its rows by Omega[rank] - Omega[0], and leaves one partial sum per strip and row in a stream-ordered temporary
+ * of strips x m x batch floats, which a second kernel adds up in strip order (the result does not depend on the
+ * launch).  Applicable to codebooks of at most 64 values (CER_E_TOO_LARGE otherwise), batches that are a multiple of
+ * 32 columns and 16-byte aligned X and Y.  Once the index exists, cer_matmul / cser_matmul choose kernel 5 by
+ * themselves where they expect it to be the fastest (cer_matmul_path tells); cer_matmul_ex can prefer or avoid it.
  * Not thread-safe against products running on the same handle: call it before the handle is shared.  A second call
  * is a no-op.  Errors: CER_E_INVALID, CER_E_TOO_LARGE, CER_E_NOMEM, CER_E_HIP (no device copy, allocation failed).
  */
