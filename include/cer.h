@@ -201,6 +201,9 @@ int cer_matmul_path(const cer_handle_t* h, int64_t batch);
  *                    chooses as cer_matmul does.  cer_matmul_path_ex tells which kernel will run.
  *   opts->tile_cols  kernel 1, batch a multiple of 4 with 16-byte aligned X and Y: batch columns per
  *                    tile, 8, 16, 32, 64 or 128; 0 = the library's choice
+ *   opts->strip_parts  kernel 5: the number of 8-lane parts of a wave that share a row of W (1, 2, 4 or 8);
+ *                    0 = the library's choice (by the rows a workgroup has and the length of a strip's share
+ *                    of a row)
  *   opts->flags      CER_OPT_SUM_THEN_MULTIPLY    kernel 1: the variant that sums a group's gathered
  *                                                 rows before its one multiplication
  *                    CER_OPT_ROWS_WHOLE           kernel 1: rows in their own order and never in parts
@@ -230,7 +233,7 @@ typedef struct {
     int32_t path;
     int32_t tile_cols;
     uint32_t flags;
-    uint32_t reserved; /* 0 */
+    uint32_t strip_parts; /* kernel 5: 0, 1, 2, 4 or 8 */
 } cer_matmul_opts_t;
 int cer_matmul_ex(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t batch, void* stream,
                   const cer_matmul_opts_t* opts);
@@ -247,8 +250,9 @@ int cer_matmul_path_ex(const cer_handle_t* h, int64_t batch, const cer_matmul_op
  * copies one strip of 32 batch columns into LDS per workgroup (128 KB), multiplies every element of the strip's share
  * of its rows by Omega[rank] - Omega[0], and leaves one partial sum per strip and row in a stream-ordered temporary
  * of strips x m x batch floats, which a second kernel adds up in strip order (the result does not depend on the
- * launch).  Applicable to codebooks of at most 64 values (CER_E_TOO_LARGE otherwise), batches that are a multiple of
- * 32 columns and 16-byte aligned X and Y.  Once the index exists, cer_matmul / cser_matmul choose kernel 5 by
+ * launch).  Applicable to codebooks of at most 64 values (CER_E_TOO_LARGE otherwise), batches of at least 32 columns
+ * that are a multiple of 4 (a last tile of fewer than 32 columns costs what a full one costs) and 16-byte aligned X
+ * and Y.  Once the index exists, cer_matmul / cser_matmul choose kernel 5 by
  * themselves where they expect it to be the fastest (cer_matmul_path tells); cer_matmul_ex can prefer or avoid it.
  * Not thread-safe against products running on the same handle: call it before the handle is shared.  A second call
  * is a no-op.  Errors: CER_E_INVALID, CER_E_TOO_LARGE, CER_E_NOMEM, CER_E_HIP (no device copy, allocation failed).

@@ -387,7 +387,8 @@ struct StripPlan {
     uint64_t blocks = 0;
     double est_us = 0;  // rough duration of the two launches
 };
-StripPlan plan_strip(const DeviceView& d, uint32_t L);
-hipError_t launch_strip(const DeviceView& d, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream);
+StripPlan plan_strip(const DeviceView& d, uint32_t L, int parts = 0);  // parts: 0 = chosen here
+hipError_t launch_strip(const DeviceView& d, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream,
+                        const MatmulOptions& o);
 
 }  // namespace cer

@@ -145,14 +145,19 @@ int choose_batched_path(const DeviceView& d, uint32_t L, const MatmulOptions& o,
     // gathers from L2 (27 TB/s of whole 128-byte lines plus the start-up chain of a launch) and that of decode +
     // dense: wide batches of large matrices -- AlexNet-fc6 shape, batch 32 / 64 / 128: 30 / 46 / 78 us against
     // 33 / 57 / 107 us; VGG-fc6 shape, batch 128: 92 against 100 us (batch 32: 38 against 31 us, batch 64: 52 against
-    // 54 us: the gathers are kept; 3x3 convolution shape, batch 3136: 268 us against 159 us decoded and multiplied).
+    // 54 us: the gathers are kept; 3x3 convolution shape, batch 3136: 268 us against 159 us decoded and multiplied);
+    // batch widths that are multiples of 4 but not of 32: AlexNet-fc6 shape batch 40 / 100: 45 / 77 us against 63 / 114 us,
+    // VGG-fc6 shape batch 100: 96 against 158 us.
     if (o.path < 0 && !no_temporaries && has_elements) {
         double t_gather = 0, t_dense = 0;
         const bool dense_ok = densify_estimates(d, L, &t_gather, &t_dense);
         const bool dense_pays = dense_ok && t_gather > 1.1 * t_dense;
         if (strips_ok) {
             const double t_strip = plan_strip(d, L).est_us * 1e-6;
-            const double t_gather_l2 = 5e-6 + (double)d.nnz * std::max(4.0 * L, 128.0) / 27e12;
+            // bytes a gather moves per index: whole 128-byte lines; a width that is not a multiple of 32 columns touches
+            // about one line more per row of X (AlexNet-fc6 shape batch 100: 114 us, VGG-fc6 shape: 158 us)
+            const double lines = L % 32u == 0 ? L / 32.0 : 0.85 * ((L + 31u) / 32u + 1.0);
+            const double t_gather_l2 = 5e-6 + (double)d.nnz * 128.0 * lines / 27e12;
             if (t_strip < 0.95 * t_gather_l2 && (!dense_pays || t_strip < t_dense)) return kPathStrip;
         }
         if (dense_pays) return 3;
@@ -251,7 +256,7 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
     else if (batched_path == 2)
         e = launch_xtile_any(d, plan, X, Y, T, L, stream);
     else if (batched_path == kPathStrip)
-        e = launch_strip(d, X, Y, T, L, stream);
+        e = launch_strip(d, X, Y, T, L, stream, o);
     else
         e = launch_gemm_any(d, X, Y, T, L, stream, o);
     if (scratch) {

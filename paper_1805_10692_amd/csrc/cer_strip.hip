@@ -94,13 +94,15 @@ __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict
     // the strip of this tile of batch columns: 8 threads copy one 128-byte row, eight loads per thread in flight
     const F4* X4 = reinterpret_cast<const F4*>(X);
     const uint32_t row_f4 = L >> 2;  // 16-byte pieces per row of X
+    const uint32_t tile_f4 = min(8u, row_f4 - tile * 8u);  // ... of this tile: fewer than 8 in a ragged last tile
     {
         const uint32_t pieces = rows_here * 8u;
         F4 xr[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const uint32_t i = min((uint32_t)k * 1024u + threadIdx.x, pieces - 1u);
-            xr[k] = X4[(size_t)(c0 + (i >> 3)) * row_f4 + tile * 8u + (i & 7u)];
+            // the pieces of the last tile that lie behind the batch's last column re-read the tile's first piece
+            xr[k] = X4[(size_t)(c0 + (i >> 3)) * row_f4 + tile * 8u + ((i & 7u) < tile_f4 ? (i & 7u) : 0u)];
         }
         for (uint32_t i = threadIdx.x; i <= rows; i += 1024u) s_end[i] = sp[i];
         if (threadIdx.x < 256u) {
@@ -153,7 +155,7 @@ __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict
                 }
             }
             if (f & 2u) {
-                if (p == 0u) out[(size_t)cr * row_f4] = sum;
+                if (p == 0u && ch < tile_f4) out[(size_t)cr * row_f4] = sum;
                 acc = F4{0.f, 0.f, 0.f, 0.f};
                 ++cr;
             }
@@ -201,7 +203,7 @@ constexpr size_t strip_lds_bytes(uint32_t rows) { return (size_t)kStripWtsBytes 
 }  // namespace
 
 bool strip_applicable(const DeviceView& d, const float* X, const float* Y, uint32_t L) {
-    return d.strip_idx != nullptr && d.n_strips > 0 && L >= kStripTile && L % kStripTile == 0 && d.m > 0 &&
+    return d.strip_idx != nullptr && d.n_strips > 0 && L >= kStripTile && L % 4u == 0 && d.m > 0 &&
            (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15u) == 0 &&
            d.lds_per_block >= strip_lds_bytes(kStripMaxRows) + 512;
 }
@@ -216,10 +218,10 @@ bool strip_applicable(const DeviceView& d, const float* X, const float* Y, uint3
 //     0.62 us per round with 16 waves on a compute unit (vector ALU and LDS both close to busy: 83 vector
 //     instructions and 17 LDS reads per 64 entries), per round of workgroups; 6 us for the launch, the staging of
 //     the strip and the tail; the second kernel reads strips x m x L partial sums.
-StripPlan plan_strip(const DeviceView& d, uint32_t L) {
+StripPlan plan_strip(const DeviceView& d, uint32_t L, int parts) {
     StripPlan p;
     const uint32_t m = (uint32_t)d.m;
-    p.ntiles = L / kStripTile;
+    p.ntiles = (L + kStripTile - 1) / kStripTile;
     const uint64_t base = (uint64_t)d.n_strips * p.ntiles;
     uint32_t nsplit = (uint32_t)std::max<uint64_t>(1, (uint64_t)d.cus / std::max<uint64_t>(base, 1));
     nsplit = std::max(nsplit, (m + kStripMaxRows - 1) / kStripMaxRows);
@@ -230,6 +232,7 @@ StripPlan plan_strip(const DeviceView& d, uint32_t L) {
     const double chunks_per_row = (double)d.strip_chunks / std::max(1.0, (double)d.n_strips * (double)m);
     p.P = 1;
     while (p.P < 8 && p.rows_per_split * p.P < 4u * 128u && chunks_per_row >= 4.0 * p.P) p.P *= 2;
+    if (parts == 1 || parts == 2 || parts == 4 || parts == 8) p.P = (uint32_t)parts;
     const double rows_per_slot = std::ceil((double)p.rows_per_split * p.P / 128.0);
     const double rounds = rows_per_slot * (chunks_per_row / p.P + (p.P - 1) / (2.0 * p.P));
     const double wg_rounds = std::ceil((double)p.blocks / std::max(d.cus, 1));
@@ -238,9 +241,10 @@ StripPlan plan_strip(const DeviceView& d, uint32_t L) {
     return p;
 }
 
-hipError_t launch_strip(const DeviceView& d, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream) {
+hipError_t launch_strip(const DeviceView& d, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream,
+                        const MatmulOptions& o) {
     const uint32_t m = (uint32_t)d.m, n = (uint32_t)d.n;
-    const StripPlan sp = plan_strip(d, L);
+    const StripPlan sp = plan_strip(d, L, o.strip_parts);
     const uint32_t ntiles = sp.ntiles, nsplit = sp.nsplit, rows_per_split = sp.rows_per_split, P = sp.P;
     const uint64_t blocks = sp.blocks;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 STRIP = B.MatmulOpts(path=B.CER_PATH_STRIP)
 
 
-def strip_check(w, fmts=("cer", "cser"), expect=B.CER_PATH_STRIP):
+def strip_check(w, fmts=("cer", "cser"), expect=B.CER_PATH_STRIP, opts=STRIP):
     dev = _gpu()
     print(f"strip case {w.name} m={w.m} n={w.n} L={w.L}", flush=True)
     scale = oracle.abs_dot_dense(w.W, w.X, threads=8)
@@ -24,12 +24,15 @@ def strip_check(w, fmts=("cer", "cser"), expect=B.CER_PATH_STRIP):
         A = oracle.encode(w.W, w.codebook, fmt)
         want = oracle.dot(A, w.X, threads=8)
         h = (B.cer_encode if fmt == "cer" else B.cser_encode)(w.W, w.codebook)
-        assert B.cer_matmul_path_ex(h, w.L, STRIP) != B.CER_PATH_STRIP      # not before the index is built
+        assert B.cer_matmul_path_ex(h, w.L, opts) != B.CER_PATH_STRIP      # not before the index is built
         B.cer_prepare_strips(h)
         B.cer_prepare_strips(h)                                            # a second call changes nothing
-        assert B.cer_matmul_path_ex(h, w.L, STRIP) == expect
+        if expect is not None:
+            assert B.cer_matmul_path_ex(h, w.L, opts) == expect
+        else:
+            assert B.cer_matmul_path_ex(h, w.L, opts) != B.CER_PATH_STRIP
         Yd = torch.full((w.m, w.L), float("nan"), dtype=torch.float32, device=dev)
-        B.cer_matmul_ex(h, Xd, Yd, w.L, None, STRIP)
+        B.cer_matmul_ex(h, Xd, Yd, w.L, None, opts)
         torch.cuda.synchronize()
         check(Yd.cpu().numpy(), want, scale, f"{w.name}/{fmt}")
         B.cer_free(h)
@@ -58,16 +61,38 @@ def test_strip_kernel_all_elements(name):
     strip_check(CASES[name]())
 
 
+@pytest.mark.parametrize("parts", [1, 2, 4, 8])
+@pytest.mark.parametrize("name", ["alexnet_s8_L32", "vgg_s8_L64", "sparse_rows", "one_row", "rows_1025", "conv_s4_dom_L96"])
+def test_every_number_of_parts_per_row(name, parts):
+    """1, 2, 4 or 8 parts of a wave share a row (the library picks by the launch shape): each one forced."""
+    strip_check(CASES[name](), fmts=("cer",), opts=B.MatmulOpts(path=B.CER_PATH_STRIP, strip_parts=parts))
+
+
+@pytest.mark.parametrize("L", [36, 40, 60, 100, 132, 260])
+def test_batch_widths_with_a_ragged_last_tile(L):
+    """Batch widths that are multiples of 4 but not of 32: the last tile holds fewer than 32 columns."""
+    # L = 60: a non-zero most frequent value (the constant term is added with the strips' sums)
+    strip_check(wl.random_lowentropy(m=150, n=2300, K=9, p_dom=0.7, L=L, seed=200 + L, dominant=1 if L == 60 else None),
+                fmts=("cer",))
+
+
 def test_full_size_alexnet_fc6_batch32_and_vgg_fc6_batch64():
     strip_check(wl.alexnet_fc6(L=32), fmts=("cer",))
     strip_check(wl.vgg_fc6(L=64), fmts=("cser",))
 
 
 def test_not_applicable_cases_fall_back():
-    """Batch widths that are not multiples of 32 run the library's own choice; codebooks of more than 64 values cannot
-    be prepared."""
-    w = wl.random_lowentropy(m=67, n=1500, K=16, p_dom=0.8, L=40, seed=140)
-    strip_check(w, expect=B.CER_PATH_GEMM)
+    """Batch widths that are not multiples of 4, or below 32, run the library's own choice; codebooks of more than 64
+    values cannot be prepared; an undefined number of parts is refused."""
+    for L in (42, 28):
+        w = wl.random_lowentropy(m=67, n=1500, K=16, p_dom=0.8, L=L, seed=140)
+        strip_check(w, expect=B.CER_PATH_GEMM if L >= 32 else None)
+    w = wl.random_lowentropy(m=20, n=300, K=4, p_dom=0.8, L=32, seed=141)
+    h = B.cer_encode(w.W, w.codebook)
+    with pytest.raises(B.CerError) as e:
+        B.cer_matmul_path_ex(h, 32, B.MatmulOpts(path=B.CER_PATH_STRIP, strip_parts=3))
+    assert e.value.code == B.CER_E_INVALID
+    B.cer_free(h)
     big = wl.random_lowentropy(m=40, n=2000, K=200, p_dom=0.3, L=32, seed=40, ratio=0.995)
     h = B.cer_encode(big.W, big.codebook)
     with pytest.raises(B.CerError) as e:
