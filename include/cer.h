@@ -201,9 +201,6 @@ int cer_matmul_path(const cer_handle_t* h, int64_t batch);
  *                    chooses as cer_matmul does.  cer_matmul_path_ex tells which kernel will run.
  *   opts->tile_cols  kernel 1, batch a multiple of 4 with 16-byte aligned X and Y: batch columns per
  *                    tile, 8, 16, 32, 64 or 128; 0 = the library's choice
- *   opts->strip_parts  kernel 5: the number of 8-lane parts of a wave that share a row of W (1, 2, 4 or 8);
- *                    0 = the library's choice (by the rows a workgroup has and the length of a strip's share
- *                    of a row)
  *   opts->flags      CER_OPT_SUM_THEN_MULTIPLY    kernel 1: the variant that sums a group's gathered
  *                                                 rows before its one multiplication
  *                    CER_OPT_ROWS_WHOLE           kernel 1: rows in their own order and never in parts
@@ -233,7 +230,7 @@ typedef struct {
     int32_t path;
     int32_t tile_cols;
     uint32_t flags;
-    uint32_t strip_parts; /* kernel 5: 0, 1, 2, 4 or 8 */
+    uint32_t reserved; /* 0 */
 } cer_matmul_opts_t;
 int cer_matmul_ex(const cer_handle_t* h, const float* X_dev, float* Y_dev, int64_t batch, void* stream,
                   const cer_matmul_opts_t* opts);

@@ -64,10 +64,10 @@ class CostT(ctypes.Structure):
 class MatmulOpts(ctypes.Structure):
     """cer_matmul_opts_t: preferred kernel, tile width and CER_OPT_* flags of cer_matmul_ex."""
     _fields_ = [("path", ctypes.c_int32), ("tile_cols", ctypes.c_int32), ("flags", ctypes.c_uint32),
-                ("strip_parts", ctypes.c_uint32)]
+                ("reserved", ctypes.c_uint32)]
 
-    def __init__(self, path: int = CER_PATH_AUTO, tile_cols: int = 0, flags: int = 0, strip_parts: int = 0):
-        super().__init__(path, tile_cols, flags, strip_parts)
+    def __init__(self, path: int = CER_PATH_AUTO, tile_cols: int = 0, flags: int = 0):
+        super().__init__(path, tile_cols, flags, 0)
 
 
 class CerError(RuntimeError):

@@ -382,12 +382,7 @@ bool read_options(const cer_matmul_opts_t* in, cer::MatmulOptions* out) {
         case 0: case 8: case 16: case 32: case 64: case 128: break;
         default: return false;
     }
-    switch (in->strip_parts) {
-        case 0: case 1: case 2: case 4: case 8: break;
-        default: return false;
-    }
     out->path = in->path;
-    out->strip_parts = (int)in->strip_parts;
     out->tile_cols = in->tile_cols;
     out->flags = in->flags;
     return true;

@@ -383,12 +383,11 @@ hipError_t launch_xtile_any(const DeviceView& d, const XtilePlan& p, const float
 // cer_strip.hip -- batch > 1, strips of X resident in LDS (needs the strip-major index of cer_prepare_strips)
 bool strip_applicable(const DeviceView& d, const float* X, const float* Y, uint32_t L);
 struct StripPlan {
-    uint32_t ntiles = 0, nsplit = 1, rows_per_split = 0, P = 1;  // P: parts of 8 lanes that share a row
+    uint32_t ntiles = 0, nsplit = 1, rows_per_split = 0;
     uint64_t blocks = 0;
     double est_us = 0;  // rough duration of the two launches
 };
-StripPlan plan_strip(const DeviceView& d, uint32_t L, int parts = 0);  // parts: 0 = chosen here
-hipError_t launch_strip(const DeviceView& d, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream,
-                        const MatmulOptions& o);
+StripPlan plan_strip(const DeviceView& d, uint32_t L);
+hipError_t launch_strip(const DeviceView& d, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream);
 
 }  // namespace cer

@@ -113,7 +113,6 @@ int min_index_bits(uint64_t max_value);
 struct MatmulOptions {
     int path = -1;      // preferred kernel (numbering of cer_matmul_path), -1 = the library's choice
     int tile_cols = 0;  // batched kernels that gather from L2: batch columns per tile, 0 = the library's choice
-    int strip_parts = 0;  // strip kernel: parts of 8 lanes that share a row (1, 2, 4, 8), 0 = the library's choice
     uint32_t flags = 0; // CER_OPT_* bits
 };
 constexpr int kPathStrip = 5;

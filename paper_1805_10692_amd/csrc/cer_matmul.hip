@@ -143,11 +143,10 @@ int choose_batched_path(const DeviceView& d, uint32_t L, const MatmulOptions& o,
     }
     // A handle whose strip-major index was prepared takes the strip kernel where its estimate beats that of the
     // gathers from L2 (27 TB/s of whole 128-byte lines plus the start-up chain of a launch) and that of decode +
-    // dense: wide batches of large matrices -- AlexNet-fc6 shape, batch 32 / 64 / 128: 30 / 46 / 78 us against
-    // 33 / 57 / 107 us; VGG-fc6 shape, batch 128: 92 against 100 us (batch 32: 38 against 31 us, batch 64: 52 against
-    // 54 us: the gathers are kept; 3x3 convolution shape, batch 3136: 268 us against 159 us decoded and multiplied);
-    // batch widths that are multiples of 4 but not of 32: AlexNet-fc6 shape batch 40 / 100: 45 / 77 us against 63 / 114 us,
-    // VGG-fc6 shape batch 100: 96 against 158 us.
+    // dense: wide batches of large matrices -- AlexNet-fc6 shape, batch 32 / 64 / 128: 25 / 38 / 61 us against
+    // 33 / 57 / 107 us; VGG-fc6 shape, batch 64 / 128: 45 / 78 against 54 / 100 us (batch 32: 33 against 31 us: the
+    // gathers are kept; 3x3 convolution shape, batch 3136: 209 us against 159 us decoded and multiplied); batch widths
+    // that are multiples of 4 but not of 32: AlexNet-fc6 shape batch 100: 61 against 114 us.
     if (o.path < 0 && !no_temporaries && has_elements) {
         double t_gather = 0, t_dense = 0;
         const bool dense_ok = densify_estimates(d, L, &t_gather, &t_dense);
@@ -256,7 +255,7 @@ int launch_matmul(const DeviceView& d, const float* X, float* Y, int64_t L64, vo
     else if (batched_path == 2)
         e = launch_xtile_any(d, plan, X, Y, T, L, stream);
     else if (batched_path == kPathStrip)
-        e = launch_strip(d, X, Y, T, L, stream, o);
+        e = launch_strip(d, X, Y, T, L, stream);
     else
         e = launch_gemm_any(d, X, Y, T, L, stream, o);
     if (scratch) {

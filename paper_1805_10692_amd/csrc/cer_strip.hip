@@ -12,15 +12,19 @@
 // chunk of 16 bytes -- with entries of rank 0, whose weight Omega[0] - Omega[0] is zero; the pointers count chunks.
 // Every element is multiplied by its own value, so the fragmentation of the groups does not matter.
 //
-// Lanes: a part of 8 lanes serves one entry at a time (16 bytes = 4 batch columns per lane: one conflict-free LDS
-// read of a 128-byte row per entry); all 8 lanes load the same chunk, so the entry reaches them without a
-// cross-lane operation, and its weight comes from a table in LDS that is addressed by the entry's top byte (rank and
-// the two top column bits; one sub-dword shift forms the address).  kP adjacent parts share one row of W at a time
-// (they take its chunks in turn and add their sums at the row's end); a workgroup's rows are dealt to its 128 / kP
-// slots in contiguous runs, so a slot walks one contiguous range of chunks, three chunks in flight.  The ends of the
+// Lanes: a quad (4 lanes) serves one entry at a time: 32 bytes = 8 batch columns per lane, read with two 16-byte LDS
+// reads -- lane j takes the pieces j and j + 4 of the entry's 128-byte row, even quads the lower piece first, odd
+// quads the upper one, so that the two quads that share an LDS cycle touch different banks.  All 4 lanes load the same
+// chunk, so the entries reach them without a cross-lane operation; the weights of a chunk's eight entries are looked
+// up once per chunk (lane j those of entries j and j + 4, from a table in LDS that is addressed by the entry's top
+// byte: rank and the two top column bits) and handed to the quad by a DPP broadcast per entry.  Per entry and lane:
+// 4 address and broadcast instructions, 2 LDS reads, 8 multiply-adds.
+// Work: a workgroup's chunks are dealt to its 256 workers (quads) in equal contiguous ranges, whatever rows they
+// belong to; a worker writes the rows that begin and end inside its range itself, keeps back the row it ends but did
+// not begin, and leaves what it summed behind its last row end as its tail; after the stream the kept-back rows are
+// completed from the tails, in worker order (deterministic).  Three chunks are in flight per worker; the ends of the
 // workgroup's rows are staged in LDS.  Each (strip, row) leaves a partial sum; a second kernel adds the strips'
-// partial sums in strip order (deterministic) and the constant term of a non-zero most frequent value (Appendix
-// A-A1).
+// partial sums in strip order and the constant term of a non-zero most frequent value (Appendix A-A1).
 #include "cer_device.hpp"
 
 namespace cer {
@@ -29,60 +33,75 @@ namespace {
 constexpr uint32_t kStripTile = 32;                               // batch columns per tile: one 128-byte row per entry
 constexpr uint32_t kStripBytes = kStripRows * kStripTile * 4u;    // the strip in LDS
 constexpr uint32_t kStripWtsBytes = 1024;                         // 256 weights in front of it (LDS address 0)
-constexpr uint32_t kStripMaxRows = 4096;                          // rows of W per workgroup (their ends sit in LDS)
+constexpr double kStripRoundUs = 0.85;                             // one chunk per worker, 16 waves per compute unit
+constexpr uint32_t kStripMaxRows = 3072;                          // rows of W per workgroup (their ends sit in LDS)
 
 typedef float F4 __attribute__((ext_vector_type(4)));
 typedef const F4 __attribute__((address_space(3))) * LdsF4Ptr;
 typedef const float __attribute__((address_space(3))) * LdsF1Ptr;
 
-// 4 x the byte `kByte` of d: the LDS address of the weight of the entry whose top byte it is.
-template <int kByte>
-__device__ __forceinline__ uint32_t weight_address(uint32_t d, uint32_t two) {
-    uint32_t r;
-    if (kByte == 1) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(two), "v"(d));
-    else asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(two), "v"(d));
-    return r;
+// The value of lane kLane of the lane's quad.
+template <int kLane>
+__device__ __forceinline__ float quad_broadcast(float w) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(w), kLane * 0x55 /* quad_perm:[k,k,k,k] */, 0xF, 0xF, false));
 }
 
-// One chunk: eight entries, each a 128-byte row of the strip times its weight.  xbase = the lane's 16 bytes inside a
-// row + the strip's LDS address.
-__device__ __forceinline__ void strip_chunk(const uint4& q, uint32_t xbase, F4& acc) {
+// The weights of the two entries of a chunk that lane j of a quad looks up (entries j and j + 4): the entry's top byte
+// x 4 is the LDS address of its weight.  half_shift = 16 (j & 1), upper_pair = j & 2.
+__device__ __forceinline__ void chunk_weights(const uint4& q, uint32_t half_shift, bool upper_pair, float& w_lo, float& w_hi) {
     uint32_t two = 2u;
     asm("" : "+v"(two));  // the shift count in a vector register (sub-dword forms take no constants)
-    const uint32_t d[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const uint32_t wa0 = weight_address<1>(d[k], two), wa1 = weight_address<3>(d[k], two);
-        uint32_t c0, c1, xa0, xa1;  // written out: one bit-field extract and one shift-add per address
-        asm("v_bfe_u32 %0, %1, 0, 10" : "=v"(c0) : "v"(d[k]));
-        asm("v_bfe_u32 %0, %1, 16, 10" : "=v"(c1) : "v"(d[k]));
-        asm("v_lshl_add_u32 %0, %1, 7, %2" : "=v"(xa0) : "v"(c0), "v"(xbase));
-        asm("v_lshl_add_u32 %0, %1, 7, %2" : "=v"(xa1) : "v"(c1), "v"(xbase));
-        const float w0 = *reinterpret_cast<LdsF1Ptr>((uintptr_t)wa0);
-        const F4 x0 = *reinterpret_cast<LdsF4Ptr>((uintptr_t)xa0);
-        const float w1 = *reinterpret_cast<LdsF1Ptr>((uintptr_t)wa1);
-        const F4 x1 = *reinterpret_cast<LdsF4Ptr>((uintptr_t)xa1);
-        acc.x = fmaf(w0, x0.x, acc.x); acc.y = fmaf(w0, x0.y, acc.y);
-        acc.z = fmaf(w0, x0.z, acc.z); acc.w = fmaf(w0, x0.w, acc.w);
-        acc.x = fmaf(w1, x1.x, acc.x); acc.y = fmaf(w1, x1.y, acc.y);
-        acc.z = fmaf(w1, x1.z, acc.z); acc.w = fmaf(w1, x1.w, acc.w);
-    }
+    const uint32_t d_lo = (upper_pair ? q.y : q.x) >> half_shift, d_hi = (upper_pair ? q.w : q.z) >> half_shift;
+    uint32_t a_lo, a_hi;
+    asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(a_lo) : "v"(two), "v"(d_lo));
+    asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(a_hi) : "v"(two), "v"(d_hi));
+    w_lo = *reinterpret_cast<LdsF1Ptr>((uintptr_t)a_lo);
+    w_hi = *reinterpret_cast<LdsF1Ptr>((uintptr_t)a_hi);
+}
+
+// Entry kEntry of a chunk: its 128-byte row of the strip (this lane's two pieces) times its weight.  xbase = the LDS
+// address of the lane's first piece inside row 0 of the strip; the second piece is 64 bytes above or below it.
+template <int kEntry>
+__device__ __forceinline__ void strip_entry(const uint4& q, uint32_t xbase, float w_lo, float w_hi, F4& acc0, F4& acc1) {
+    const uint32_t d = kEntry < 2 ? q.x : (kEntry < 4 ? q.y : (kEntry < 6 ? q.z : q.w));
+    uint32_t c, xa;  // written out: one bit-field extract and one shift-add
+    if (kEntry & 1) asm("v_bfe_u32 %0, %1, 16, 10" : "=v"(c) : "v"(d));
+    else asm("v_bfe_u32 %0, %1, 0, 10" : "=v"(c) : "v"(d));
+    asm("v_lshl_add_u32 %0, %1, 7, %2" : "=v"(xa) : "v"(c), "v"(xbase));
+    const F4 x0 = *reinterpret_cast<LdsF4Ptr>((uintptr_t)xa);
+    const F4 x1 = *reinterpret_cast<LdsF4Ptr>((uintptr_t)(xa ^ 64u));
+    const float w = quad_broadcast<kEntry & 3>(kEntry < 4 ? w_lo : w_hi);
+    acc0.x = fmaf(w, x0.x, acc0.x); acc0.y = fmaf(w, x0.y, acc0.y);
+    acc0.z = fmaf(w, x0.z, acc0.z); acc0.w = fmaf(w, x0.w, acc0.w);
+    acc1.x = fmaf(w, x1.x, acc1.x); acc1.y = fmaf(w, x1.y, acc1.y);
+    acc1.z = fmaf(w, x1.z, acc1.z); acc1.w = fmaf(w, x1.w, acc1.w);
+}
+
+// One chunk: eight entries.
+__device__ __forceinline__ void strip_chunk(const uint4& q, uint32_t xbase, uint32_t half_shift, bool upper_pair, F4& acc0,
+                                            F4& acc1) {
+    float w_lo, w_hi;
+    chunk_weights(q, half_shift, upper_pair, w_lo, w_hi);
+    strip_entry<0>(q, xbase, w_lo, w_hi, acc0, acc1); strip_entry<1>(q, xbase, w_lo, w_hi, acc0, acc1);
+    strip_entry<2>(q, xbase, w_lo, w_hi, acc0, acc1); strip_entry<3>(q, xbase, w_lo, w_hi, acc0, acc1);
+    strip_entry<4>(q, xbase, w_lo, w_hi, acc0, acc1); strip_entry<5>(q, xbase, w_lo, w_hi, acc0, acc1);
+    strip_entry<6>(q, xbase, w_lo, w_hi, acc0, acc1); strip_entry<7>(q, xbase, w_lo, w_hi, acc0, acc1);
 }
 
 // chunks: the strip-major index, 16 bytes per chunk, closed by one chunk of zeros (index zero_chunk);
 // sptr[s (m + 1) + r] = first chunk of (strip s, row r).
 // part: [strip][m][L] partial sums.
-template <int kP>
 __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict__ chunks, const uint32_t* __restrict__ sptr,
                                                          const float* __restrict__ X, float* __restrict__ part,
                                                          const float* __restrict__ omega, uint32_t m, uint32_t n, uint32_t L,
                                                          uint32_t K, uint32_t ntiles, uint32_t nsplit,
                                                          uint32_t rows_per_split, uint32_t zero_chunk) {
-    // LDS: [256 weights][strip: rows of 8 x 16 bytes][ends of the workgroup's rows, in chunks]; no static LDS, so the
-    // weight of an entry sits at LDS address 4 x (its top byte).
+    // LDS: [256 weights][strip: rows of 8 x 16 bytes; after the stream: one partial row sum per worker][ends of the
+    // workgroup's rows, in chunks]; no static LDS, so the weight of an entry sits at LDS address 4 x (its top byte).
     extern __shared__ __align__(16) unsigned char strip_smem[];
     float* s_w = reinterpret_cast<float*>(strip_smem);
     F4* xs4 = reinterpret_cast<F4*>(strip_smem + kStripWtsBytes);
+    F4* s_tail = xs4;
     uint32_t* s_end = reinterpret_cast<uint32_t*>(strip_smem + kStripWtsBytes + kStripBytes);
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = uniform(threadIdx.x >> 6);
@@ -90,81 +109,118 @@ __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict
     const uint32_t c0 = s * kStripRows, rows_here = min(kStripRows, n - c0);
     const uint32_t r_begin = min(m, split * rows_per_split), rows = min(m, r_begin + rows_per_split) - r_begin;
     const uint32_t* sp = sptr + (size_t)s * (m + 1) + r_begin;
-
-    // the strip of this tile of batch columns: 8 threads copy one 128-byte row, eight loads per thread in flight
     const F4* X4 = reinterpret_cast<const F4*>(X);
     const uint32_t row_f4 = L >> 2;  // 16-byte pieces per row of X
     const uint32_t tile_f4 = min(8u, row_f4 - tile * 8u);  // ... of this tile: fewer than 8 in a ragged last tile
-    {
-        const uint32_t pieces = rows_here * 8u;
-        F4 xr[8];
+    const uint32_t pieces = rows_here * 8u;
+
+    // (1) Everything is requested at once, all loads unconditional: the ends of the workgroup's rows and Omega first,
+    //     then the strip of this tile of batch columns (8 threads copy one 128-byte row, eight loads per thread).
+    static_assert(kStripMaxRows + 1 <= 4 * 1024, "four row ends per thread");
+    uint32_t er[4];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const uint32_t i = min((uint32_t)k * 1024u + threadIdx.x, pieces - 1u);
-            // the pieces of the last tile that lie behind the batch's last column re-read the tile's first piece
-            xr[k] = X4[(size_t)(c0 + (i >> 3)) * row_f4 + tile * 8u + ((i & 7u) < tile_f4 ? (i & 7u) : 0u)];
-        }
-        for (uint32_t i = threadIdx.x; i <= rows; i += 1024u) s_end[i] = sp[i];
-        if (threadIdx.x < 256u) {
-            const uint32_t rank = threadIdx.x >> 2;
-            s_w[threadIdx.x] = rank < K ? omega[rank] - omega[0] : 0.f;
-        }
+    for (int k = 0; k < 4; ++k) er[k] = sp[min((uint32_t)k * 1024u + threadIdx.x, rows)];
+    const float om_r = omega[min(threadIdx.x >> 2, K - 1u)], om_0 = omega[0];
+    __builtin_amdgcn_sched_barrier(0);
+    F4 xr[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const uint32_t i = (uint32_t)k * 1024u + threadIdx.x;
-            if (i < pieces) xs4[i] = xr[k];
-        }
+    for (int k = 0; k < 8; ++k) {
+        const uint32_t i = min((uint32_t)k * 1024u + threadIdx.x, pieces - 1u);
+        // the pieces of the last tile that lie behind the batch's last column re-read the tile's first piece
+        xr[k] = X4[(size_t)(c0 + (i >> 3)) * row_f4 + tile * 8u + ((i & 7u) < tile_f4 ? (i & 7u) : 0u)];
     }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t i = (uint32_t)k * 1024u + threadIdx.x;
+        if (i <= rows) s_end[i] = er[k];
+    }
+    if (threadIdx.x < 256u) s_w[threadIdx.x] = (threadIdx.x >> 2) < K ? om_r - om_0 : 0.f;
     __syncthreads();
 
-    // this lane's slot (kP parts = 8 kP lanes) and its contiguous run of the workgroup's rows
-    constexpr uint32_t kSlots = 128u / kP;
-    const uint32_t ch = lane & 7u, p = (lane >> 3) & (kP - 1u);
-    const uint32_t slot = wave * (8u / kP) + (lane >> 3) / kP;
-    const uint32_t ra = slot * rows / kSlots, rb = (slot + 1u) * rows / kSlots;  // rows <= kStripMaxRows: no overflow
-    const uint32_t xbase = kStripWtsBytes + ch * 16u;
-
-    // generator: the slot's next chunks; flag bit 0: the slot still has rows, bit 1: its current row ends here.  Free
-    // of branches, and every load is issued unconditionally (a part without a chunk of its own reads the chunk of
-    // zeros behind the index: entries of rank 0, weight zero), so that the waits for the three chunks in flight stay
-    // exact.  gnext = end of the row behind the current one, read from LDS an iteration before it is needed.
-    uint32_t gr = ra, gbase = s_end[ra], gce = s_end[min(ra + 1u, rows)], gnext = s_end[min(ra + 2u, rows)];
-    auto gen = [&](uint4& q, uint32_t& f) {
-        const bool active = gr < rb;
-        const bool mine = active && gbase + p < gce;
-        q = chunks[mine ? gbase + p : zero_chunk];
-        const bool ends = active && gbase + kP >= gce;
-        f = (active ? 1u : 0u) | (ends ? 2u : 0u);
-        gbase = ends ? gce : (active ? gbase + kP : gbase);
-        gce = ends ? gnext : gce;
-        gr += ends ? 1u : 0u;
-        gnext = s_end[min(gr + 2u, rows)];
-    };
-    F4 acc = F4{0.f, 0.f, 0.f, 0.f};
-    uint32_t cr = ra;  // the row the consumer is in
-    F4* out = reinterpret_cast<F4*>(part) + ((size_t)s * m + r_begin) * row_f4 + tile * 8u + ch;
-    auto consume = [&](const uint4& q, uint32_t f) {
-        strip_chunk(q, xbase, acc);
-        if (__ballot((f & 2u) != 0u) != 0ull) {  // some slot of the wave ends a row
-            F4 sum = acc;
-            if (kP > 1) {
-#pragma unroll
-                for (uint32_t o = 8u; o < 8u * kP; o <<= 1) {
-                    sum.x += __shfl_xor(sum.x, (int)o, kWave); sum.y += __shfl_xor(sum.y, (int)o, kWave);
-                    sum.z += __shfl_xor(sum.z, (int)o, kWave); sum.w += __shfl_xor(sum.w, (int)o, kWave);
-                }
-            }
-            if (f & 2u) {
-                if (p == 0u && ch < tile_f4) out[(size_t)cr * row_f4] = sum;
-                acc = F4{0.f, 0.f, 0.f, 0.f};
-                ++cr;
+    // (2) While the strip is on its way: the workgroup's chunks [C0, C1) are dealt to its 256 workers (quads) in equal
+    //     contiguous ranges [ca, cb), whatever rows they belong to.  A worker owns the rows that END inside (ca, cb]
+    //     (worker 0 also those that end at C0: empty rows in front); its first row is found by a binary search over
+    //     the row ends.
+    const uint32_t j = lane & 3u, odd = (lane >> 2) & 1u, w = wave * 16u + (lane >> 2);
+    const uint32_t p0 = j + 4u * odd, p1 = j + 4u * (1u - odd);  // the lane's pieces of a row: first and second read
+    const uint32_t xbase = kStripWtsBytes + p0 * 16u;
+    const uint32_t half_shift = 16u * (j & 1u);
+    const bool upper_pair = (j & 2u) != 0u;
+    const uint32_t C0 = s_end[0], C1 = s_end[rows];
+    F4* out0 = reinterpret_cast<F4*>(part) + ((size_t)s * m + r_begin) * row_f4 + tile * 8u;
+    if (C1 == C0) {  // uniform over the workgroup: no row has an element in this strip
+        for (uint32_t i = threadIdx.x; i < rows * 8u; i += 1024u)
+            if ((i & 7u) < tile_f4) out0[(size_t)(i >> 3) * row_f4 + (i & 7u)] = F4{0.f, 0.f, 0.f, 0.f};
+        return;
+    }
+    const uint32_t per = (C1 - C0 + 255u) >> 8;
+    const uint32_t ca = min(C1, C0 + w * per), cb = min(C1, ca + per);
+    uint32_t r0 = 0;
+    {
+        uint32_t hi = w == 0u ? 0u : rows;
+#pragma unroll 1
+        while (__ballot(r0 < hi) != 0ull) {
+            const uint32_t mid = (r0 + hi) >> 1;
+            const bool later = s_end[min(mid + 1u, rows)] > ca;
+            if (r0 < hi) {
+                if (later) hi = mid; else r0 = mid + 1u;
             }
         }
+    }
+    // generator: the worker's next iterations -- a chunk (flag bit 0: the worker is still at work), the end of one
+    // row (bit 1), or both.  Free of branches, and every load is issued unconditionally (an iteration without a chunk
+    // reads the chunk of zeros behind the index: entries of rank 0, weight zero), so that the waits for the three
+    // chunks in flight stay exact.  gnext = end of the row behind the current one, read from LDS an iteration early.
+    uint32_t gcr = r0, gbase = ca, gce = s_end[min(r0 + 1u, rows)], gnext = s_end[min(r0 + 2u, rows)];
+    auto gen = [&](uint4& q, uint32_t& f) {
+        const bool has = gbase < min(gce, cb);
+        q = chunks[has ? gbase : zero_chunk];
+        gbase += has ? 1u : 0u;
+        const bool ends = gbase == gce && gcr < rows && gce <= cb;
+        f = ((has || ends) ? 1u : 0u) | (ends ? 2u : 0u);
+        gce = ends ? gnext : gce;
+        gcr += ends ? 1u : 0u;
+        gnext = s_end[min(gcr + 2u, rows)];
     };
     uint4 qa, qb, qc;
     uint32_t fa, fb, fc;
     gen(qa, fa);
     gen(qb, fb);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // (3) the strip goes to LDS
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const uint32_t i = (uint32_t)k * 1024u + threadIdx.x;
+        if (i < pieces) xs4[i] = xr[k];
+    }
+    __syncthreads();
+
+    // (4) the stream.  A row that began in an earlier worker's range is kept back (at most one per worker: the first
+    //     it ends); what a worker has summed behind its last row end is its tail.
+    const F4 zero4 = F4{0.f, 0.f, 0.f, 0.f};
+    F4 acc0 = zero4, acc1 = zero4, head0 = zero4, head1 = zero4;
+    uint32_t cr = r0, cs = s_end[min(r0, rows)];  // the consumer's row and where it starts
+    uint32_t head_row = 0xFFFFFFFFu, head_start = 0u;
+    auto consume = [&](const uint4& q, uint32_t f) {
+        strip_chunk(q, xbase, half_shift, upper_pair, acc0, acc1);
+        if (f & 2u) {
+            if (cs >= ca) {
+                if (p0 < tile_f4) out0[(size_t)cr * row_f4 + p0] = acc0;
+                if (p1 < tile_f4) out0[(size_t)cr * row_f4 + p1] = acc1;
+            } else {
+                head0 = acc0;
+                head1 = acc1;
+                head_row = cr;
+                head_start = cs;
+            }
+            acc0 = zero4;
+            acc1 = zero4;
+            ++cr;
+            cs = s_end[min(cr, rows)];
+        }
+    };
     for (;;) {
         gen(qc, fc);
         if (__ballot(fa != 0u) == 0ull) break;
@@ -175,6 +231,27 @@ __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict
         gen(qb, fb);
         if (__ballot(fc != 0u) == 0ull) break;
         consume(qc, fc);
+    }
+
+    // (5) rows shared by several workers: the worker that ends the row adds, in worker order, the tails of the worker
+    //     the row began in and of those it runs through (they end no row: their tail is all they summed) to its own
+    //     sum.  The tails take the place of the strip, which no worker reads any more.
+    __syncthreads();
+    s_tail[w * 8u + p0] = acc0;
+    s_tail[w * 8u + p1] = acc1;
+    __syncthreads();
+    if (head_row != 0xFFFFFFFFu) {
+        uint32_t v = (head_start - C0) / per;  // the worker whose range holds the row's first chunk
+        F4 sum0 = s_tail[v * 8u + p0], sum1 = s_tail[v * 8u + p1];
+        for (++v; v < w; ++v) {
+            const F4 t0 = s_tail[v * 8u + p0], t1 = s_tail[v * 8u + p1];
+            sum0.x += t0.x; sum0.y += t0.y; sum0.z += t0.z; sum0.w += t0.w;
+            sum1.x += t1.x; sum1.y += t1.y; sum1.z += t1.z; sum1.w += t1.w;
+        }
+        sum0.x += head0.x; sum0.y += head0.y; sum0.z += head0.z; sum0.w += head0.w;
+        sum1.x += head1.x; sum1.y += head1.y; sum1.z += head1.z; sum1.w += head1.w;
+        if (p0 < tile_f4) out0[(size_t)head_row * row_f4 + p0] = sum0;
+        if (p1 < tile_f4) out0[(size_t)head_row * row_f4 + p1] = sum1;
     }
 }
 
@@ -198,7 +275,9 @@ __global__ __launch_bounds__(256) void cer_strip_sum_kernel(const float* __restr
     reinterpret_cast<F4*>(Y)[i] = a;
 }
 
-constexpr size_t strip_lds_bytes(uint32_t rows) { return (size_t)kStripWtsBytes + kStripBytes + 4u * ((size_t)rows + 1u); }
+constexpr size_t strip_lds_bytes(uint32_t rows) {
+    return (size_t)kStripWtsBytes + kStripBytes + 4u * ((size_t)rows + 1u);
+}
 
 }  // namespace
 
@@ -211,14 +290,12 @@ bool strip_applicable(const DeviceView& d, const float* X, const float* Y, uint3
 // Launch shape of the strip kernel for a batch of L columns, and a rough duration.
 //   * One workgroup per compute unit holds 128 KB of LDS, so the (strip, tile) pairs are split over the rows into
 //     about as many workgroups as there are compute units (never more than kStripMaxRows rows each).
-//   * Parts per row: enough rows for every slot (four or more each), but no more parts than a (strip, row) has
-//     chunks to keep them busy.
-//   * Duration (measured on MI355X: AlexNet-fc6 shape batch 32 / 64 / 128: 30 / 46 / 78 us, VGG-fc6 shape batch 32 /
-//     64 / 128: 38 / 52 / 92 us, 3x3 convolution shape batch 3136: 268 us): a slot's rows x its chunk rounds per row,
-//     0.62 us per round with 16 waves on a compute unit (vector ALU and LDS both close to busy: 83 vector
-//     instructions and 17 LDS reads per 64 entries), per round of workgroups; 6 us for the launch, the staging of
-//     the strip and the tail; the second kernel reads strips x m x L partial sums.
-StripPlan plan_strip(const DeviceView& d, uint32_t L, int parts) {
+//   * Duration: a worker's chunks (the workgroup's chunks / 256) x 0.85 us (one chunk per worker with 16 waves on a
+//     compute unit) + 7 us for the staging of the strip, the search and the shared rows, per round of workgroups;
+//     the launches; the second kernel reads strips x m x L partial sums.  Measured on MI355X / this estimate:
+//     AlexNet-fc6 shape batch 32 / 128: 25.3 / 61.4 us (25.9 / 62.6), VGG-fc6 shape batch 32 / 64 / 128: 33.1 / 44.8 /
+//     78.0 us (30.7 / 47.3 / 92), 3x3 convolution shape batch 3136: 209 us (215).
+StripPlan plan_strip(const DeviceView& d, uint32_t L) {
     StripPlan p;
     const uint32_t m = (uint32_t)d.m;
     p.ntiles = (L + kStripTile - 1) / kStripTile;
@@ -230,46 +307,29 @@ StripPlan plan_strip(const DeviceView& d, uint32_t L, int parts) {
     p.nsplit = (m + p.rows_per_split - 1) / std::max(p.rows_per_split, 1u);
     p.blocks = base * p.nsplit;
     const double chunks_per_row = (double)d.strip_chunks / std::max(1.0, (double)d.n_strips * (double)m);
-    p.P = 1;
-    while (p.P < 8 && p.rows_per_split * p.P < 4u * 128u && chunks_per_row >= 4.0 * p.P) p.P *= 2;
-    if (parts == 1 || parts == 2 || parts == 4 || parts == 8) p.P = (uint32_t)parts;
-    const double rows_per_slot = std::ceil((double)p.rows_per_split * p.P / 128.0);
-    const double rounds = rows_per_slot * (chunks_per_row / p.P + (p.P - 1) / (2.0 * p.P));
+    const double rounds = std::ceil((double)p.rows_per_split * chunks_per_row / 256.0);
     const double wg_rounds = std::ceil((double)p.blocks / std::max(d.cus, 1));
     const double partial_bytes = (double)d.n_strips * m * L * 4.0;
-    p.est_us = wg_rounds * (rounds * 0.62 + 3.0) + 3.0 + (3.0 + 2.0 * partial_bytes / 5e6);
+    // short rows: some quad of a wave ends a row in nearly every iteration, and the whole wave walks through that branch
+    const double per_round = kStripRoundUs * (1.0 + 1.5 / std::max(chunks_per_row, 1.0));
+    p.est_us = wg_rounds * (rounds * per_round + 7.0) + 3.0 + (3.0 + 2.0 * partial_bytes / 5e6);
     return p;
 }
 
-hipError_t launch_strip(const DeviceView& d, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream,
-                        const MatmulOptions& o) {
+hipError_t launch_strip(const DeviceView& d, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream) {
     const uint32_t m = (uint32_t)d.m, n = (uint32_t)d.n;
-    const StripPlan sp = plan_strip(d, L, o.strip_parts);
-    const uint32_t ntiles = sp.ntiles, nsplit = sp.nsplit, rows_per_split = sp.rows_per_split, P = sp.P;
-    const uint64_t blocks = sp.blocks;
-    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const StripPlan sp = plan_strip(d, L);
+    if (sp.blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     float* part = nullptr;
     const size_t part_bytes = (size_t)d.n_strips * m * L * sizeof(float);
     hipError_t e = (hipError_t)temp_alloc(reinterpret_cast<void**>(&part), part_bytes, stream);
     if (e != hipSuccess) return e;
-    const size_t lds = strip_lds_bytes(rows_per_split);
-    static LdsGrant<4> grant;
-    const void* kernels[4] = {reinterpret_cast<const void*>(cer_strip_kernel<1>), reinterpret_cast<const void*>(cer_strip_kernel<2>),
-                              reinterpret_cast<const void*>(cer_strip_kernel<4>), reinterpret_cast<const void*>(cer_strip_kernel<8>)};
-    const int slot = P == 1 ? 0 : (P == 2 ? 1 : (P == 4 ? 2 : 3));
-    e = grant.ensure(slot, kernels[slot], strip_lds_bytes(kStripMaxRows));
+    static LdsGrant<1> grant;
+    e = grant.ensure(0, reinterpret_cast<const void*>(cer_strip_kernel), strip_lds_bytes(kStripMaxRows));
     if (e == hipSuccess) {
-#define CER_STRIP_LAUNCH(PP)                                                                                           \
-    hipLaunchKernelGGL(cer_strip_kernel<PP>, dim3((uint32_t)blocks), dim3(1024), lds, stream,                          \
-                       static_cast<const uint4*>(d.strip_idx), d.strip_ptr, X, part, d.omega, m, n, L, (uint32_t)d.K,  \
-                       ntiles, nsplit, rows_per_split, (uint32_t)d.strip_chunks)
-        switch (P) {
-            case 1: CER_STRIP_LAUNCH(1); break;
-            case 2: CER_STRIP_LAUNCH(2); break;
-            case 4: CER_STRIP_LAUNCH(4); break;
-            default: CER_STRIP_LAUNCH(8); break;
-        }
-#undef CER_STRIP_LAUNCH
+        hipLaunchKernelGGL(cer_strip_kernel, dim3((uint32_t)sp.blocks), dim3(1024), strip_lds_bytes(sp.rows_per_split), stream,
+                           static_cast<const uint4*>(d.strip_idx), d.strip_ptr, X, part, d.omega, m, n, L, (uint32_t)d.K,
+                           sp.ntiles, sp.nsplit, sp.rows_per_split, (uint32_t)d.strip_chunks);
         e = hipGetLastError();
     }
     if (e == hipSuccess) {

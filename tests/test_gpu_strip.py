@@ -38,6 +38,13 @@ def strip_check(w, fmts=("cer", "cser"), expect=B.CER_PATH_STRIP, opts=STRIP):
         B.cer_free(h)
 
 
+def _with_empty_columns(w):
+    """Columns 1024 .. 2047 hold only the most frequent value: no row has an element in the second strip."""
+    vals, cnts = np.unique(w.W, return_counts=True)
+    w.W[:, 1024:2048] = vals[np.argmax(cnts)]
+    return w
+
+
 CASES = {
     "alexnet_s8_L32": lambda: wl.alexnet_fc6(L=32, scale=8),              # n = 1152 + remainder: two strips
     "vgg_s8_L64": lambda: wl.vgg_fc6(L=64, scale=8),                      # four strips, two tiles
@@ -52,6 +59,8 @@ CASES = {
     "one_row": lambda: wl.random_lowentropy(m=1, n=3000, K=16, p_dom=0.7, L=32, seed=36),
     "constant": lambda: wl.random_lowentropy(m=10, n=100, K=1, p_dom=1.0, L=32, seed=38),
     "sparse_rows": lambda: wl.random_lowentropy(m=333, n=900, K=5, p_dom=0.998, L=32, seed=45),  # most rows empty
+    "long_rows_few": lambda: wl.random_lowentropy(m=5, n=9000, K=7, p_dom=0.3, L=64, seed=46),    # every row runs through many workers
+    "empty_strip": lambda: _with_empty_columns(wl.random_lowentropy(m=300, n=3000, K=6, p_dom=0.5, L=32, seed=47)),
     "rows_1025": lambda: wl.random_lowentropy(m=1025, n=700, K=12, p_dom=0.85, L=160, seed=44),
 }
 
@@ -59,13 +68,6 @@ CASES = {
 @pytest.mark.parametrize("name", list(CASES))
 def test_strip_kernel_all_elements(name):
     strip_check(CASES[name]())
-
-
-@pytest.mark.parametrize("parts", [1, 2, 4, 8])
-@pytest.mark.parametrize("name", ["alexnet_s8_L32", "vgg_s8_L64", "sparse_rows", "one_row", "rows_1025", "conv_s4_dom_L96"])
-def test_every_number_of_parts_per_row(name, parts):
-    """1, 2, 4 or 8 parts of a wave share a row (the library picks by the launch shape): each one forced."""
-    strip_check(CASES[name](), fmts=("cer",), opts=B.MatmulOpts(path=B.CER_PATH_STRIP, strip_parts=parts))
 
 
 @pytest.mark.parametrize("L", [36, 40, 60, 100, 132, 260])
@@ -83,16 +85,10 @@ def test_full_size_alexnet_fc6_batch32_and_vgg_fc6_batch64():
 
 def test_not_applicable_cases_fall_back():
     """Batch widths that are not multiples of 4, or below 32, run the library's own choice; codebooks of more than 64
-    values cannot be prepared; an undefined number of parts is refused."""
+    values cannot be prepared."""
     for L in (42, 28):
         w = wl.random_lowentropy(m=67, n=1500, K=16, p_dom=0.8, L=L, seed=140)
         strip_check(w, expect=B.CER_PATH_GEMM if L >= 32 else None)
-    w = wl.random_lowentropy(m=20, n=300, K=4, p_dom=0.8, L=32, seed=141)
-    h = B.cer_encode(w.W, w.codebook)
-    with pytest.raises(B.CerError) as e:
-        B.cer_matmul_path_ex(h, 32, B.MatmulOpts(path=B.CER_PATH_STRIP, strip_parts=3))
-    assert e.value.code == B.CER_E_INVALID
-    B.cer_free(h)
     big = wl.random_lowentropy(m=40, n=2000, K=200, p_dom=0.3, L=32, seed=40, ratio=0.995)
     h = B.cer_encode(big.W, big.codebook)
     with pytest.raises(B.CerError) as e:
