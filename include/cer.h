@@ -286,7 +286,8 @@ int cer_get_stats(const cer_handle_t* h, double* H, double* p0, double* k_bar, d
 /*
  * cer_clone_device -- a second handle with the same host arrays and its own, freshly allocated
  * device copy on the current device.  Lets a benchmark rotate over more encoded bytes than the
- * GPU's caches hold.  Errors: CER_E_INVALID, CER_E_NOMEM, CER_E_HIP.
+ * GPU's caches hold.  The clone has no strip-major index, whether the original has one or not
+ * (cer_prepare_strips builds it per handle).  Errors: CER_E_INVALID, CER_E_NOMEM, CER_E_HIP.
  */
 int cer_clone_device(const cer_handle_t* h, cer_handle_t** out);
 

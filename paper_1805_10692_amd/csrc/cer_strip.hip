@@ -261,10 +261,19 @@ __global__ __launch_bounds__(256) void cer_strip_sum_kernel(const float* __restr
                                                             uint64_t plane_f4, uint32_t row_f4) {
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= plane_f4) return;
-    const F4* p = reinterpret_cast<const F4*>(part);
-    F4 a = p[i];
-    for (uint32_t s = 1; s < nstrips; ++s) {
-        const F4 b = p[(uint64_t)s * plane_f4 + i];
+    const F4* p = reinterpret_cast<const F4*>(part) + i;
+    F4 a = F4{0.f, 0.f, 0.f, 0.f};
+    // eight planes requested at a time, added in strip order
+    uint32_t s = 0;
+    for (; s + 8 <= nstrips; s += 8) {
+        F4 b[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) b[k] = p[(uint64_t)(s + k) * plane_f4];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) { a.x += b[k].x; a.y += b[k].y; a.z += b[k].z; a.w += b[k].w; }
+    }
+    for (; s < nstrips; ++s) {
+        const F4 b = p[(uint64_t)s * plane_f4];
         a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
     }
     if (omega0 != 0.f) {

@@ -61,6 +61,7 @@ CASES = {
     "sparse_rows": lambda: wl.random_lowentropy(m=333, n=900, K=5, p_dom=0.998, L=32, seed=45),  # most rows empty
     "long_rows_few": lambda: wl.random_lowentropy(m=5, n=9000, K=7, p_dom=0.3, L=64, seed=46),    # every row runs through many workers
     "empty_strip": lambda: _with_empty_columns(wl.random_lowentropy(m=300, n=3000, K=6, p_dom=0.5, L=32, seed=47)),
+    "unequal_rows": lambda: wl.vgg_fc6_unequal_rows(L=64, sigma=2.0, scale=8),   # log-normal row lengths, one full row
     "rows_1025": lambda: wl.random_lowentropy(m=1025, n=700, K=12, p_dom=0.85, L=160, seed=44),
 }
 
