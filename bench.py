@@ -76,10 +76,13 @@ def make_workload(name: str):
     raise SystemExit(f"unknown workload {name}")
 
 
-def kernel_name(fmt: str, L: int, path) -> str:
-    """The kernel that dominates a product (cer_matmul_path's numbering for cer / cser)."""
+def kernel_name(fmt: str, L: int, path, K: int = 0, n: int = 0) -> str:
+    """The kernel that dominates a product (cer_matmul_path's numbering for cer / cser).  Batch 1: handles of 2 - 256
+    values whose X fits in LDS (every benchmark configuration) run the rank-table kernel."""
     if fmt == "csr":
         return "csr_gemv_kernel" if L == 1 else "csr_gemm_kernel"
+    if path == 0 and 2 <= K <= 256 and 0 < n <= 36000:
+        return "cer_gemv_tab_kernel"
     return {0: "cer_gemv_kernel",
             1: "cer_gemm_expand_kernel",
             2: "cer_xtile_kernel", 3: "decode_kernel + dense_gemm_mfma_kernel", 4: "cer_gemv_expand_kernel",
@@ -524,7 +527,7 @@ def main() -> int:
                                      "k_bar", "k_tilde", "cache_state", "path")},
         "roofline": {"bound": "hbm", "achieved": r["algorithmic_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": r["algorithmic_GBps"] / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
-                     "kernel": kernel_name(args.format, r["L"], r["path"]),
+                     "kernel": kernel_name(args.format, r["L"], r["path"], r["K"], r["n"]),
                      "algorithmic_bytes_per_launch": r["algorithmic_bytes"],
                      "event_us_per_launch": r["event_ms_per_step"] * 1e3},
         "cpu_baseline": r.get("cpu_baseline"),
@@ -549,7 +552,7 @@ def main() -> int:
         st, st_src = read_traffic(sname, args.format)
         steady = {"workload": sname, "bound": "hbm", "achieved": rs["algorithmic_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                   "frac": rs["algorithmic_GBps"] / HBM_PEAK_GBS, "traffic": st, "traffic_source": st_src,
-                  "kernel": kernel_name(args.format, rs["L"], rs["path"]),
+                  "kernel": kernel_name(args.format, rs["L"], rs["path"], rs["K"], rs["n"]),
                   "algorithmic_bytes_per_launch": rs["algorithmic_bytes"], "event_us_per_launch": rs["event_ms_per_step"] * 1e3,
                   "m": rs["m"], "n": rs["n"], "nnz": rs["nnz"], "K": rs["K"], "H_bits": rs["H_bits"], "p0": rs["p0"],
                   "cache_state": rs["cache_state"]}

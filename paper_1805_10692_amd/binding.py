@@ -86,6 +86,13 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_1805_10692_amd.build` "
                               "(there is no fallback implementation)")
+        # One HIP runtime per process: PyTorch ships its own copy of it, and the tensors whose pointers this binding
+        # passes live in that one.  Loaded after torch, the library binds to the copy that is already there; loaded
+        # first, it would bring the system's copy, and products on torch's tensors then fail (no device).
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
         pvp = ctypes.POINTER(vp)
