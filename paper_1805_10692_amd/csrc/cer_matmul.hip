@@ -144,8 +144,8 @@ int choose_batched_path(const DeviceView& d, uint32_t L, const MatmulOptions& o,
     // A handle whose strip-major index was prepared takes the strip kernel where its estimate beats that of the
     // gathers from L2 (27 TB/s of whole 128-byte lines plus the start-up chain of a launch) and that of decode +
     // dense: wide batches of large matrices -- AlexNet-fc6 shape, batch 32 / 64 / 128: 25 / 38 / 61 us against
-    // 33 / 57 / 107 us; VGG-fc6 shape, batch 64 / 128: 45 / 78 against 54 / 100 us (batch 32: 33 against 31 us: the
-    // gathers are kept; 3x3 convolution shape, batch 3136: 209 us against 159 us decoded and multiplied); batch widths
+    // 33 / 57 / 107 us; VGG-fc6 shape, batch 64 / 128: 45 / 78 against 54 / 100 us (batch 32: 29 against 31 us: the
+    // estimate keeps the gathers; 3x3 convolution shape, batch 3136: 209 us against 159 us decoded and multiplied); batch widths
     // that are multiples of 4 but not of 32: AlexNet-fc6 shape batch 100: 61 against 114 us.
     if (o.path < 0 && !no_temporaries && has_elements) {
         double t_gather = 0, t_dense = 0;

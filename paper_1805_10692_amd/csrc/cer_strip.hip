@@ -203,21 +203,28 @@ __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict
     F4 acc0 = zero4, acc1 = zero4, head0 = zero4, head1 = zero4;
     uint32_t cr = r0, cs = s_end[min(r0, rows)];  // the consumer's row and where it starts
     uint32_t head_row = 0xFFFFFFFFu, head_start = 0u;
+    F4* orow = out0 + (size_t)cr * row_f4;  // where the consumer's row goes
     auto consume = [&](const uint4& q, uint32_t f) {
         strip_chunk(q, xbase, half_shift, upper_pair, acc0, acc1);
         if (f & 2u) {
-            if (cs >= ca) {
-                if (p0 < tile_f4) out0[(size_t)cr * row_f4 + p0] = acc0;
-                if (p1 < tile_f4) out0[(size_t)cr * row_f4 + p1] = acc1;
-            } else {
-                head0 = acc0;
-                head1 = acc1;
-                head_row = cr;
-                head_start = cs;
+            // the row a worker ends but did not begin (once per worker at most) is kept back: a branch the wave skips
+            const bool kept = cs < ca;
+            if (__ballot(kept) != 0ull) {
+                if (kept) {
+                    head0 = acc0;
+                    head1 = acc1;
+                    head_row = cr;
+                    head_start = cs;
+                }
+            }
+            if (!kept) {
+                if (p0 < tile_f4) orow[p0] = acc0;
+                if (p1 < tile_f4) orow[p1] = acc1;
             }
             acc0 = zero4;
             acc1 = zero4;
             ++cr;
+            orow += row_f4;
             cs = s_end[min(cr, rows)];
         }
     };
