@@ -206,9 +206,13 @@ constexpr uint32_t kExpLong = 16;  // groups longer than this are written by the
 // columns instead (all loads stay inside the row) and write only the columns no other lane owns; Y is written
 // element by element.
 template <typename IdxT, int V, int P, bool kRagged, int kExpChunk = kExpChunkLong, bool kSplit = false>
-__global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const float* __restrict__ X, float* __restrict__ Y,
-                                                              const float* __restrict__ T, uint32_t L, uint32_t ntiles,
-                                                              uint32_t rowblocks, uint32_t items_per_xcd, SplitArgs sp) {
+__global__ __launch_bounds__(256) void cer_gemm_expand_kernel(const uint2* __restrict__ rowInfo_, const void* __restrict__ colI_,
+                                                              const float* __restrict__ X, float* __restrict__ Y, uint32_t L,
+                                                              uint32_t ntiles, uint32_t rowblocks, uint32_t items_per_xcd,
+                                                              uint32_t m_, const float* __restrict__ T, KView v, SplitArgs sp) {
+    // The first 13 dwords of arguments (plain pointers and integers) arrive in scalar registers with the wave (the
+    // library is built with kernel-argument preloading): the row descriptor and the first indices are requested
+    // without waiting for a load of the argument block; what else the kernel needs of the matrix (v) comes behind.
     using G = GemmIdx<P>;
     constexpr int S = G::S, U = G::U, KQ = G::KQ, D = G::D;
     constexpr uint32_t PB = G::PB;
@@ -259,11 +263,11 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const flo
                 rank_block = i * S + j;
             }
             const uint32_t rank = rank_block * 4u + wave;
-            if (rank >= v.m) return;
+            if (rank >= m_) return;
             r = uniform(sp.order[rank]);
         } else {
             r = rb * 4u + wave;
-            if (r >= v.m) return;
+            if (r >= m_) return;
         }
     }
 
@@ -273,10 +277,10 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(KView v, const flo
     static_assert(!kRagged || V == 4, "ragged batches are gathered four columns at a time");
     const uint32_t colx = kRagged ? min(col0, L - 4u) : col0;  // ragged: L >= 4 (the launcher sees to it)
     const float* xgather = X + (active ? colx : 0u);
-    const IdxT* colI = static_cast<const IdxT*>(v.colI);
+    const IdxT* colI = static_cast<const IdxT*>(colI_);
     float* val = s_val[wave];
 
-    const uint2 d0 = v.rowInfo[r], d1 = v.rowInfo[r + 1];
+    const uint2 d0 = rowInfo_[r], d1 = rowInfo_[r + 1];
     const uint32_t g0 = d0.x, g1 = d1.x;
     uint32_t rs = d0.y, re = d1.y;
     if (kSplit) {  // a part's own positions; the first part of a split row
@@ -430,7 +434,8 @@ hipError_t launch_expand_split(Kern kern, const KView& k, const float* X, float*
     }
     sp.out = out;
     sp.part_blocks = (uint32_t)part_blocks;
-    hipLaunchKernelGGL(kern, dim3((uint32_t)blocks), dim3(256), 0, stream, k, X, Y, T, L, ntiles, rowblocks, ipx, sp);
+    hipLaunchKernelGGL(kern, dim3((uint32_t)blocks), dim3(256), 0, stream, k.rowInfo, k.colI, X, Y, L, ntiles, rowblocks, ipx,
+                       k.m, T, k, sp);
     e = hipGetLastError();
     if (sp.nparts > 0) {
         if (e == hipSuccess) {
@@ -462,10 +467,10 @@ hipError_t launch_gemm_vp(const KView& k, const float* X, float* Y, const float*
         }
         if (TW == 32 && V == 4 && short_rows)
             hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, 8, false, kExpChunkShort>), dim3(ipx * 8), dim3(256), 0, stream,
-                               k, X, Y, T, L, ntiles, rowblocks, ipx, SplitArgs{});
+                               k.rowInfo, k.colI, X, Y, L, ntiles, rowblocks, ipx, k.m, T, k, SplitArgs{});
         else
-            hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, V, P, false>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L,
-                               ntiles, rowblocks, ipx, SplitArgs{});
+            hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, V, P, false>), dim3(ipx * 8), dim3(256), 0, stream, k.rowInfo, k.colI,
+                               X, Y, L, ntiles, rowblocks, ipx, k.m, T, k, SplitArgs{});
     } else
         hipLaunchKernelGGL((cer_gemm_kernel<IdxT, V, P>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L, ntiles,
                            rowblocks, ipx);
@@ -490,11 +495,11 @@ hipError_t launch_gemm_ragged(const KView& k, const float* X, float* Y, const fl
                                    rowblocks, ipx, sp, stream);
     }
     if (P == 8 && short_rows)
-        hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, 8, true, kExpChunkShort>), dim3(ipx * 8), dim3(256), 0, stream, k, X,
-                           Y, T, L, ntiles, rowblocks, ipx, SplitArgs{});
+        hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, 8, true, kExpChunkShort>), dim3(ipx * 8), dim3(256), 0, stream,
+                           k.rowInfo, k.colI, X, Y, L, ntiles, rowblocks, ipx, k.m, T, k, SplitArgs{});
     else
-        hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, P, true>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L,
-                           ntiles, rowblocks, ipx, SplitArgs{});
+        hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, P, true>), dim3(ipx * 8), dim3(256), 0, stream, k.rowInfo, k.colI, X,
+                           Y, L, ntiles, rowblocks, ipx, k.m, T, k, SplitArgs{});
     return hipGetLastError();
 }
 
