@@ -122,3 +122,26 @@ def test_library_chooses_the_strip_kernel_only_where_it_is_expected_to_win():
             torch.cuda.synchronize()
             check(Yd.cpu().numpy(), oracle.dot(A, w.X, threads=8), oracle.abs_dot_dense(w.W, w.X, threads=8), w.name)
         B.cer_free(h)
+
+
+def test_handles_of_the_device_encoder_and_clones_can_be_prepared():
+    """The strip-major index is built from the host copy of the arrays: a handle encoded on the device fetches them
+    first; a clone starts without the index and gets its own."""
+    dev = _gpu()
+    w = wl.random_lowentropy(m=300, n=2600, K=11, p_dom=0.8, L=64, seed=310)
+    A = oracle.encode(w.W, w.codebook, "cer")
+    want, scale = oracle.dot(A, w.X, threads=8), oracle.abs_dot_dense(w.W, w.X, threads=8)
+    Wd = torch.from_numpy(w.W).to(dev)
+    Xd = torch.from_numpy(np.ascontiguousarray(w.X)).to(dev)
+    h = B.cer_encode_device(Wd, w.m, w.n, w.codebook)
+    B.cer_prepare_strips(h)
+    c = B.cer_clone_device(h)
+    assert B.cer_matmul_path_ex(h, w.L, STRIP) == B.CER_PATH_STRIP
+    assert B.cer_matmul_path_ex(c, w.L, STRIP) != B.CER_PATH_STRIP
+    B.cer_prepare_strips(c)
+    for handle in (h, c):
+        Yd = torch.full((w.m, w.L), float("nan"), dtype=torch.float32, device=dev)
+        B.cer_matmul_ex(handle, Xd, Yd, w.L, None, STRIP)
+        torch.cuda.synchronize()
+        check(Yd.cpu().numpy(), want, scale, w.name)
+        B.cer_free(handle)
