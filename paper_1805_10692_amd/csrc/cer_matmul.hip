@@ -134,7 +134,20 @@ int choose_batched_path(const DeviceView& d, uint32_t L, const MatmulOptions& o,
     const bool strips_ok = !no_temporaries && strip_applicable(d, X, Y, L);
     if (o.path == kPathStrip && strips_ok) return kPathStrip;
     if (o.path == 3 && has_elements && !no_temporaries) return 3;
-    if (o.path != 1 && o.path != 3) {
+    // the strips' estimate against the gathers' (and, below, against decode + dense)
+    bool strips_beat_gathers = false;
+    double t_strip = 0;
+    if (o.path < 0 && strips_ok && has_elements) {
+        t_strip = plan_strip(d, L).est_us * 1e-6;
+        // bytes a gather moves per index: whole 128-byte lines; a width that is not a multiple of 32 columns touches
+        // about one line more per row of X (AlexNet-fc6 shape batch 100: 114 us, VGG-fc6 shape: 158 us), unless a row
+        // of X divides a line (8 and 16 columns)
+        const double lines = L % 32u == 0 ? L / 32.0 : (L < 32u && 32u % L == 0 ? 1.0 : 0.85 * ((L + 31u) / 32u + 1.0));
+        const double t_gather_l2 = 5e-6 + (double)d.nnz * 128.0 * lines / 27e12;
+        strips_beat_gathers = t_strip < 0.95 * t_gather_l2;
+    }
+    // (from 8 columns on the strips are ahead of the LDS tile of all input rows: AlexNet-fc6 shape batch 8 23 against 28 us)
+    if (o.path != 1 && o.path != 3 && !(strips_beat_gathers && L >= 8u)) {
         const XtilePlan plan = plan_xtile(d, L);
         if (plan.valid && (o.path == 2 || xtile_pays(d, L)) && (!no_temporaries || plan.ntiles == 1)) {
             if (plan_out) *plan_out = plan;
@@ -146,19 +159,13 @@ int choose_batched_path(const DeviceView& d, uint32_t L, const MatmulOptions& o,
     // dense: wide batches of large matrices -- AlexNet-fc6 shape, batch 32 / 64 / 128: 25 / 38 / 61 us against
     // 33 / 57 / 107 us; VGG-fc6 shape, batch 64 / 128: 45 / 78 against 54 / 100 us (batch 32: 29 against 31 us: the
     // estimate keeps the gathers; 3x3 convolution shape, batch 3136: 209 us against 159 us decoded and multiplied); batch widths
-    // that are multiples of 4 but not of 32: AlexNet-fc6 shape batch 100: 61 against 114 us.
+    // that are multiples of 4 but not of 32: AlexNet-fc6 shape batch 100: 61 against 114 us; batches of 8 - 16 columns
+    // (one 16-byte piece of a row per lane): AlexNet-fc6 shape batch 16 20 against 31 us, VGG-fc6 shape 22 against 28 us.
     if (o.path < 0 && !no_temporaries && has_elements) {
         double t_gather = 0, t_dense = 0;
         const bool dense_ok = densify_estimates(d, L, &t_gather, &t_dense);
         const bool dense_pays = dense_ok && t_gather > 1.1 * t_dense;
-        if (strips_ok) {
-            const double t_strip = plan_strip(d, L).est_us * 1e-6;
-            // bytes a gather moves per index: whole 128-byte lines; a width that is not a multiple of 32 columns touches
-            // about one line more per row of X (AlexNet-fc6 shape batch 100: 114 us, VGG-fc6 shape: 158 us)
-            const double lines = L % 32u == 0 ? L / 32.0 : 0.85 * ((L + 31u) / 32u + 1.0);
-            const double t_gather_l2 = 5e-6 + (double)d.nnz * 128.0 * lines / 27e12;
-            if (t_strip < 0.95 * t_gather_l2 && (!dense_pays || t_strip < t_dense)) return kPathStrip;
-        }
+        if (strips_beat_gathers && (!dense_pays || t_strip < t_dense)) return kPathStrip;
         if (dense_pays) return 3;
     }
     return 1;

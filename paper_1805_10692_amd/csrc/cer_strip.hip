@@ -61,7 +61,7 @@ __device__ __forceinline__ void chunk_weights(const uint4& q, uint32_t half_shif
 
 // Entry kEntry of a chunk: its 128-byte row of the strip (this lane's two pieces) times its weight.  xbase = the LDS
 // address of the lane's first piece inside row 0 of the strip; the second piece is 64 bytes above or below it.
-template <int kEntry>
+template <int kEntry, bool kHalf>
 __device__ __forceinline__ void strip_entry(const uint4& q, uint32_t xbase, float w_lo, float w_hi, F4& acc0, F4& acc1) {
     const uint32_t d = kEntry < 2 ? q.x : (kEntry < 4 ? q.y : (kEntry < 6 ? q.z : q.w));
     uint32_t c, xa;  // written out: one bit-field extract and one shift-add
@@ -69,28 +69,33 @@ __device__ __forceinline__ void strip_entry(const uint4& q, uint32_t xbase, floa
     else asm("v_bfe_u32 %0, %1, 0, 10" : "=v"(c) : "v"(d));
     asm("v_lshl_add_u32 %0, %1, 7, %2" : "=v"(xa) : "v"(c), "v"(xbase));
     const F4 x0 = *reinterpret_cast<LdsF4Ptr>((uintptr_t)xa);
-    const F4 x1 = *reinterpret_cast<LdsF4Ptr>((uintptr_t)(xa ^ 64u));
     const float w = quad_broadcast<kEntry & 3>(kEntry < 4 ? w_lo : w_hi);
     acc0.x = fmaf(w, x0.x, acc0.x); acc0.y = fmaf(w, x0.y, acc0.y);
     acc0.z = fmaf(w, x0.z, acc0.z); acc0.w = fmaf(w, x0.w, acc0.w);
-    acc1.x = fmaf(w, x1.x, acc1.x); acc1.y = fmaf(w, x1.y, acc1.y);
-    acc1.z = fmaf(w, x1.z, acc1.z); acc1.w = fmaf(w, x1.w, acc1.w);
+    if (!kHalf) {
+        const F4 x1 = *reinterpret_cast<LdsF4Ptr>((uintptr_t)(xa ^ 64u));
+        acc1.x = fmaf(w, x1.x, acc1.x); acc1.y = fmaf(w, x1.y, acc1.y);
+        acc1.z = fmaf(w, x1.z, acc1.z); acc1.w = fmaf(w, x1.w, acc1.w);
+    }
 }
 
-// One chunk: eight entries.
+// One chunk: eight entries.  kHalf: a batch of at most 16 columns -- one piece per lane (the 64 bytes of a row are
+// stored twice in its 128 bytes of LDS, even quads read the lower copy, odd quads the upper one).
+template <bool kHalf>
 __device__ __forceinline__ void strip_chunk(const uint4& q, uint32_t xbase, uint32_t half_shift, bool upper_pair, F4& acc0,
                                             F4& acc1) {
     float w_lo, w_hi;
     chunk_weights(q, half_shift, upper_pair, w_lo, w_hi);
-    strip_entry<0>(q, xbase, w_lo, w_hi, acc0, acc1); strip_entry<1>(q, xbase, w_lo, w_hi, acc0, acc1);
-    strip_entry<2>(q, xbase, w_lo, w_hi, acc0, acc1); strip_entry<3>(q, xbase, w_lo, w_hi, acc0, acc1);
-    strip_entry<4>(q, xbase, w_lo, w_hi, acc0, acc1); strip_entry<5>(q, xbase, w_lo, w_hi, acc0, acc1);
-    strip_entry<6>(q, xbase, w_lo, w_hi, acc0, acc1); strip_entry<7>(q, xbase, w_lo, w_hi, acc0, acc1);
+    strip_entry<0, kHalf>(q, xbase, w_lo, w_hi, acc0, acc1); strip_entry<1, kHalf>(q, xbase, w_lo, w_hi, acc0, acc1);
+    strip_entry<2, kHalf>(q, xbase, w_lo, w_hi, acc0, acc1); strip_entry<3, kHalf>(q, xbase, w_lo, w_hi, acc0, acc1);
+    strip_entry<4, kHalf>(q, xbase, w_lo, w_hi, acc0, acc1); strip_entry<5, kHalf>(q, xbase, w_lo, w_hi, acc0, acc1);
+    strip_entry<6, kHalf>(q, xbase, w_lo, w_hi, acc0, acc1); strip_entry<7, kHalf>(q, xbase, w_lo, w_hi, acc0, acc1);
 }
 
 // chunks: the strip-major index, 16 bytes per chunk, closed by one chunk of zeros (index zero_chunk);
 // sptr[s (m + 1) + r] = first chunk of (strip s, row r).
-// part: [strip][m][L] partial sums.
+// part: [strip][m][L] partial sums.  kHalf: L <= 16 (one tile of at most four 16-byte pieces per row).
+template <bool kHalf>
 __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict__ chunks, const uint32_t* __restrict__ sptr,
                                                          const float* __restrict__ X, float* __restrict__ part,
                                                          const float* __restrict__ omega, uint32_t m, uint32_t n, uint32_t L,
@@ -126,8 +131,10 @@ __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
         const uint32_t i = min((uint32_t)k * 1024u + threadIdx.x, pieces - 1u);
-        // the pieces of the last tile that lie behind the batch's last column re-read the tile's first piece
-        xr[k] = X4[(size_t)(c0 + (i >> 3)) * row_f4 + tile * 8u + ((i & 7u) < tile_f4 ? (i & 7u) : 0u)];
+        // the pieces of the last tile that lie behind the batch's last column re-read the tile's first piece; a row of
+        // at most four pieces is stored twice
+        const uint32_t piece = kHalf ? (i & 3u) : (i & 7u);
+        xr[k] = X4[(size_t)(c0 + (i >> 3)) * row_f4 + tile * 8u + (piece < tile_f4 ? piece : 0u)];
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -143,8 +150,9 @@ __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict
     //     (worker 0 also those that end at C0: empty rows in front); its first row is found by a binary search over
     //     the row ends.
     const uint32_t j = lane & 3u, odd = (lane >> 2) & 1u, w = wave * 16u + (lane >> 2);
-    const uint32_t p0 = j + 4u * odd, p1 = j + 4u * (1u - odd);  // the lane's pieces of a row: first and second read
-    const uint32_t xbase = kStripWtsBytes + p0 * 16u;
+    // the lane's pieces of a row (first and second read), and where its first read finds them in the row's 128 bytes
+    const uint32_t p0 = kHalf ? j : j + 4u * odd, p1 = kHalf ? 8u : j + 4u * (1u - odd);
+    const uint32_t xbase = kStripWtsBytes + (j + 4u * odd) * 16u;
     const uint32_t half_shift = 16u * (j & 1u);
     const bool upper_pair = (j & 2u) != 0u;
     const uint32_t C0 = s_end[0], C1 = s_end[rows];
@@ -205,7 +213,7 @@ __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict
     uint32_t head_row = 0xFFFFFFFFu, head_start = 0u;
     F4* orow = out0 + (size_t)cr * row_f4;  // where the consumer's row goes
     auto consume = [&](const uint4& q, uint32_t f) {
-        strip_chunk(q, xbase, half_shift, upper_pair, acc0, acc1);
+        strip_chunk<kHalf>(q, xbase, half_shift, upper_pair, acc0, acc1);
         if (f & 2u) {
             // the row a worker ends but did not begin (once per worker at most) is kept back: a branch the wave skips
             const bool kept = cs < ca;
@@ -245,13 +253,14 @@ __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict
     //     sum.  The tails take the place of the strip, which no worker reads any more.
     __syncthreads();
     s_tail[w * 8u + p0] = acc0;
-    s_tail[w * 8u + p1] = acc1;
+    if (!kHalf) s_tail[w * 8u + p1] = acc1;
     __syncthreads();
     if (head_row != 0xFFFFFFFFu) {
         uint32_t v = (head_start - C0) / per;  // the worker whose range holds the row's first chunk
-        F4 sum0 = s_tail[v * 8u + p0], sum1 = s_tail[v * 8u + p1];
+        const uint32_t p1r = kHalf ? p0 : p1;  // (one piece per lane: the second sum stays unused)
+        F4 sum0 = s_tail[v * 8u + p0], sum1 = s_tail[v * 8u + p1r];
         for (++v; v < w; ++v) {
-            const F4 t0 = s_tail[v * 8u + p0], t1 = s_tail[v * 8u + p1];
+            const F4 t0 = s_tail[v * 8u + p0], t1 = s_tail[v * 8u + p1r];
             sum0.x += t0.x; sum0.y += t0.y; sum0.z += t0.z; sum0.w += t0.w;
             sum1.x += t1.x; sum1.y += t1.y; sum1.z += t1.z; sum1.w += t1.w;
         }
@@ -298,7 +307,7 @@ constexpr size_t strip_lds_bytes(uint32_t rows) {
 }  // namespace
 
 bool strip_applicable(const DeviceView& d, const float* X, const float* Y, uint32_t L) {
-    return d.strip_idx != nullptr && d.n_strips > 0 && L >= kStripTile && L % 4u == 0 && d.m > 0 &&
+    return d.strip_idx != nullptr && d.n_strips > 0 && L >= 8u && L % 4u == 0 && d.m > 0 &&
            (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15u) == 0 &&
            d.lds_per_block >= strip_lds_bytes(kStripMaxRows) + 512;
 }
@@ -327,8 +336,10 @@ StripPlan plan_strip(const DeviceView& d, uint32_t L) {
     const double wg_rounds = std::ceil((double)p.blocks / std::max(d.cus, 1));
     const double partial_bytes = (double)d.n_strips * m * L * 4.0;
     // short rows: some quad of a wave ends a row in nearly every iteration, and the whole wave walks through that branch
-    const double per_round = kStripRoundUs * (1.0 + 1.5 / std::max(chunks_per_row, 1.0));
+    const double per_round = (L <= 16u ? 0.6 : 1.0) * kStripRoundUs * (1.0 + 1.5 / std::max(chunks_per_row, 1.0));
     p.est_us = wg_rounds * (rounds * per_round + 7.0) + 3.0 + (3.0 + 2.0 * partial_bytes / 5e6);
+    // workgroups with next to nothing to stream (2048 x 2048 cells: 16 rows each) measure 17 - 21 us whatever they hold
+    if (rounds < 8.0) p.est_us += 6.0;
     return p;
 }
 
@@ -340,10 +351,12 @@ hipError_t launch_strip(const DeviceView& d, const float* X, float* Y, const flo
     const size_t part_bytes = (size_t)d.n_strips * m * L * sizeof(float);
     hipError_t e = (hipError_t)temp_alloc(reinterpret_cast<void**>(&part), part_bytes, stream);
     if (e != hipSuccess) return e;
-    static LdsGrant<1> grant;
-    e = grant.ensure(0, reinterpret_cast<const void*>(cer_strip_kernel), strip_lds_bytes(kStripMaxRows));
+    static LdsGrant<2> grant;
+    const bool half = L <= 16u;
+    auto kern = half ? cer_strip_kernel<true> : cer_strip_kernel<false>;
+    e = grant.ensure(half ? 1 : 0, reinterpret_cast<const void*>(kern), strip_lds_bytes(kStripMaxRows));
     if (e == hipSuccess) {
-        hipLaunchKernelGGL(cer_strip_kernel, dim3((uint32_t)sp.blocks), dim3(1024), strip_lds_bytes(sp.rows_per_split), stream,
+        hipLaunchKernelGGL(kern, dim3((uint32_t)sp.blocks), dim3(1024), strip_lds_bytes(sp.rows_per_split), stream,
                            static_cast<const uint4*>(d.strip_idx), d.strip_ptr, X, part, d.omega, m, n, L, (uint32_t)d.K,
                            sp.ntiles, sp.nsplit, sp.rows_per_split, (uint32_t)d.strip_chunks);
         e = hipGetLastError();

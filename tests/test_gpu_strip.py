@@ -56,6 +56,8 @@ CASES = {
     "strip_edge": lambda: wl.random_lowentropy(m=33, n=2048, K=5, p_dom=0.4, L=64, seed=61),    # exactly two full strips
     "strip_edge_plus_one": lambda: wl.random_lowentropy(m=33, n=2049, K=5, p_dom=0.4, L=32, seed=62),
     "wide_input": lambda: wl.random_lowentropy(m=9, n=70001, K=8, p_dom=0.9, L=32, seed=34),    # 69 strips, 32-bit colI
+    "alexnet_s8_L16": lambda: wl.alexnet_fc6(L=16, scale=8),            # one piece per lane
+    "vgg_s8_dom_L8": lambda: wl.random_lowentropy(m=512, n=3136, K=16, p_dom=0.9, L=8, seed=48, dominant=3),
     "one_row": lambda: wl.random_lowentropy(m=1, n=3000, K=16, p_dom=0.7, L=32, seed=36),
     "constant": lambda: wl.random_lowentropy(m=10, n=100, K=1, p_dom=1.0, L=32, seed=38),
     "sparse_rows": lambda: wl.random_lowentropy(m=333, n=900, K=5, p_dom=0.998, L=32, seed=45),  # most rows empty
@@ -71,9 +73,10 @@ def test_strip_kernel_all_elements(name):
     strip_check(CASES[name]())
 
 
-@pytest.mark.parametrize("L", [36, 40, 60, 100, 132, 260])
+@pytest.mark.parametrize("L", [8, 12, 16, 20, 28, 36, 40, 60, 100, 132, 260])
 def test_batch_widths_with_a_ragged_last_tile(L):
-    """Batch widths that are multiples of 4 but not of 32: the last tile holds fewer than 32 columns."""
+    """Batch widths that are multiples of 4 but not of 32: the last tile holds fewer than 32 columns; up to 16 columns a
+    lane holds one 16-byte piece of a row instead of two."""
     # L = 60: a non-zero most frequent value (the constant term is added with the strips' sums)
     strip_check(wl.random_lowentropy(m=150, n=2300, K=9, p_dom=0.7, L=L, seed=200 + L, dominant=1 if L == 60 else None),
                 fmts=("cer",))
@@ -85,9 +88,9 @@ def test_full_size_alexnet_fc6_batch32_and_vgg_fc6_batch64():
 
 
 def test_not_applicable_cases_fall_back():
-    """Batch widths that are not multiples of 4, or below 32, run the library's own choice; codebooks of more than 64
+    """Batch widths that are not multiples of 4, or below 8, run the library's own choice; codebooks of more than 64
     values cannot be prepared."""
-    for L in (42, 28):
+    for L in (42, 6, 4):
         w = wl.random_lowentropy(m=67, n=1500, K=16, p_dom=0.8, L=L, seed=140)
         strip_check(w, expect=B.CER_PATH_GEMM if L >= 32 else None)
     big = wl.random_lowentropy(m=40, n=2000, K=200, p_dom=0.3, L=32, seed=40, ratio=0.995)
@@ -100,13 +103,14 @@ def test_not_applicable_cases_fall_back():
 
 def test_library_chooses_the_strip_kernel_only_where_it_is_expected_to_win():
     """Once the strip-major index exists the library itself may take kernel 5: wide batches of large matrices
-    (AlexNet-fc6 shape from batch 32 on), not batches whose partial sums outweigh the gain (VGG-fc6 shape at batch 32),
+    (AlexNet-fc6 shape from batch 8 on; below that the LDS tile of all input rows), not batches whose partial sums outweigh the gain (VGG-fc6 shape at batch 32),
     small matrices, or matrices that the dense route serves better (3 x 3 convolution shape at batch 3136); without the
     index nothing changes.  The product of the library's own choice is checked like every other."""
     dev = _gpu()
     cases = [(wl.alexnet_fc6(L=32), B.CER_PATH_STRIP), (wl.alexnet_fc6(L=128), B.CER_PATH_STRIP),
+             (wl.alexnet_fc6(L=8), B.CER_PATH_STRIP), (wl.alexnet_fc6(L=4), B.CER_PATH_XTILE),
              (wl.vgg_fc6(L=32), B.CER_PATH_GEMM), (wl.sweep_cell(16, 0.9, L=32), B.CER_PATH_GEMM),
-             (wl.conv3x3(L=3136), B.CER_PATH_DENSE)]
+             (wl.sweep_cell(16, 0.5, L=16), B.CER_PATH_GEMM), (wl.conv3x3(L=3136), B.CER_PATH_DENSE)]
     for w, expect in cases:
         print(f"auto case {w.name} L={w.L}", flush=True)
         h = B.cer_encode(w.W, w.codebook)
