@@ -307,7 +307,7 @@ constexpr size_t strip_lds_bytes(uint32_t rows) {
 }  // namespace
 
 bool strip_applicable(const DeviceView& d, const float* X, const float* Y, uint32_t L) {
-    return d.strip_idx != nullptr && d.n_strips > 0 && L >= 8u && L % 4u == 0 && d.m > 0 &&
+    return d.strip_idx != nullptr && d.n_strips > 0 && L >= 4u && L % 4u == 0 && d.m > 0 &&
            (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15u) == 0 &&
            d.lds_per_block >= strip_lds_bytes(kStripMaxRows) + 512;
 }

@@ -73,7 +73,7 @@ def test_strip_kernel_all_elements(name):
     strip_check(CASES[name]())
 
 
-@pytest.mark.parametrize("L", [8, 12, 16, 20, 28, 36, 40, 60, 100, 132, 260])
+@pytest.mark.parametrize("L", [4, 8, 12, 16, 20, 28, 36, 40, 60, 100, 132, 260])
 def test_batch_widths_with_a_ragged_last_tile(L):
     """Batch widths that are multiples of 4 but not of 32: the last tile holds fewer than 32 columns; up to 16 columns a
     lane holds one 16-byte piece of a row instead of two."""
@@ -88,9 +88,9 @@ def test_full_size_alexnet_fc6_batch32_and_vgg_fc6_batch64():
 
 
 def test_not_applicable_cases_fall_back():
-    """Batch widths that are not multiples of 4, or below 8, run the library's own choice; codebooks of more than 64
+    """Batch widths that are not multiples of 4, or below 4, run the library's own choice; codebooks of more than 64
     values cannot be prepared."""
-    for L in (42, 6, 4):
+    for L in (42, 6, 2):
         w = wl.random_lowentropy(m=67, n=1500, K=16, p_dom=0.8, L=L, seed=140)
         strip_check(w, expect=B.CER_PATH_GEMM if L >= 32 else None)
     big = wl.random_lowentropy(m=40, n=2000, K=200, p_dom=0.3, L=32, seed=40, ratio=0.995)
