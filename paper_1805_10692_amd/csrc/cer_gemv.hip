@@ -1025,6 +1025,10 @@ hipError_t launch_gemv(const DeviceView& d, const KView& k, const float* X, floa
     if (x_in_lds && x_bytes > 24 * 1024) {
         const uint32_t per_unit = (k.m + (uint32_t)d.cus - 1) / (uint32_t)d.cus;
         waves = (int)std::min<uint32_t>(16u, pow2_ceil(std::max<uint32_t>(per_unit, 4u)));
+        // long rows (eight windows or more on average) and an X of at most 48 KB: two workgroups of 8 waves per
+        // compute unit instead of one of 16 -- X is staged twice, but a wave waits for 7 others instead of 15 before
+        // its first gather (the 7-bit layer of 7000 indices per row: 14.3 -> 14.1 us, alternating runs; rows of 1400: no change)
+        if (x_bytes <= 48 * 1024 && (uint64_t)d.nnz >= 8ull * GemvShape<IdxT>::WIN * (uint64_t)k.m) waves = std::min(waves, 8);
     }
     // Few rows (at most 2 per compute unit) of at least 3 windows each: a row is shared by 4 or 8 waves, and a
     // workgroup holds as many rows as spread the matrix over all compute units.  Measured against whole rows: 512 x
