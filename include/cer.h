@@ -247,9 +247,10 @@ int cer_matmul_path_ex(const cer_handle_t* h, int64_t batch, const cer_matmul_op
  * copies one strip of 32 batch columns into LDS per workgroup (128 KB), multiplies every element of the strip's share
  * of its rows by Omega[rank] - Omega[0], and leaves one partial sum per strip and row in a stream-ordered temporary
  * of strips x m x batch floats, which a second kernel adds up in strip order (the result does not depend on the
- * launch).  Applicable to codebooks of at most 64 values (CER_E_TOO_LARGE otherwise), batches of at least 4 columns
- * that are a multiple of 4 (a last tile of fewer than 32 columns costs what a full one costs; batches of up to 16
- * columns run a variant that moves half as much through LDS) and 16-byte aligned X and Y.  Once the index exists, cer_matmul / cser_matmul choose kernel 5 by
+ * launch).  Applicable to codebooks of at most 64 values (CER_E_TOO_LARGE otherwise) and batches of
+ * 2 columns or more (a last tile of fewer than 32 columns costs what a full one costs; batches of up to 16 columns
+ * run a variant that moves half as much through LDS; widths that are not multiples of 4, and X / Y that are only
+ * 4-byte aligned, are read and written in smaller pieces).  Once the index exists, cer_matmul / cser_matmul choose kernel 5 by
  * themselves where they expect it to be the fastest (cer_matmul_path tells); cer_matmul_ex can prefer or avoid it.
  * Not thread-safe against products running on the same handle: call it before the handle is shared.  A second call
  * is a no-op.  Errors: CER_E_INVALID, CER_E_TOO_LARGE, CER_E_NOMEM, CER_E_HIP (no device copy, allocation failed).

@@ -94,8 +94,10 @@ __device__ __forceinline__ void strip_chunk(const uint4& q, uint32_t xbase, uint
 
 // chunks: the strip-major index, 16 bytes per chunk, closed by one chunk of zeros (index zero_chunk);
 // sptr[s (m + 1) + r] = first chunk of (strip s, row r).
-// part: [strip][m][L] partial sums.  kHalf: L <= 16 (one tile of at most four 16-byte pieces per row).
-template <bool kHalf>
+// part: [strip][m][L rounded up to 4] partial sums.  kHalf: L <= 16 (one tile of at most four 16-byte pieces per row).
+// kAlignedX: L is a multiple of 4 and X is 16-byte aligned (otherwise the pieces of X are read from 4-byte aligned
+// addresses, the last piece of a row element by element).
+template <bool kHalf, bool kAlignedX>
 __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict__ chunks, const uint32_t* __restrict__ sptr,
                                                          const float* __restrict__ X, float* __restrict__ part,
                                                          const float* __restrict__ omega, uint32_t m, uint32_t n, uint32_t L,
@@ -115,7 +117,7 @@ __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict
     const uint32_t r_begin = min(m, split * rows_per_split), rows = min(m, r_begin + rows_per_split) - r_begin;
     const uint32_t* sp = sptr + (size_t)s * (m + 1) + r_begin;
     const F4* X4 = reinterpret_cast<const F4*>(X);
-    const uint32_t row_f4 = L >> 2;  // 16-byte pieces per row of X
+    const uint32_t row_f4 = (L + 3u) >> 2;  // 16-byte pieces per row of X and of the partial sums (the last one may be partial)
     const uint32_t tile_f4 = min(8u, row_f4 - tile * 8u);  // ... of this tile: fewer than 8 in a ragged last tile
     const uint32_t pieces = rows_here * 8u;
 
@@ -134,7 +136,19 @@ __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict
         // the pieces of the last tile that lie behind the batch's last column re-read the tile's first piece; a row of
         // at most four pieces is stored twice
         const uint32_t piece = kHalf ? (i & 3u) : (i & 7u);
-        xr[k] = X4[(size_t)(c0 + (i >> 3)) * row_f4 + tile * 8u + (piece < tile_f4 ? piece : 0u)];
+        const uint32_t col = (tile * 8u + (piece < tile_f4 ? piece : 0u)) * 4u;  // the piece's first batch column
+        if (kAlignedX) {
+            xr[k] = X4[((size_t)(c0 + (i >> 3)) * L + col) >> 2];
+        } else {
+            const float* px = X + (size_t)(c0 + (i >> 3)) * L + col;
+            if (col + 4u <= L) {
+                typedef float F4u __attribute__((ext_vector_type(4), aligned(4)));
+                const F4u t = *reinterpret_cast<const F4u*>(px);
+                xr[k] = F4{t.x, t.y, t.z, t.w};
+            } else {  // the row's last, partial piece
+                xr[k] = F4{px[0], col + 1u < L ? px[1] : 0.f, col + 2u < L ? px[2] : 0.f, 0.f};
+            }
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -271,10 +285,13 @@ __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict
     }
 }
 
-// Y[r][:] = sum over strips of part[s][r][:]  (+ Omega[0] . T[:]), in strip order
+// Y[r][:] = sum over strips of part[s][r][:]  (+ Omega[0] . T[:]), in strip order.  One thread per 16-byte piece of a row
+// of the partial sums; kAlignedY: L is a multiple of 4 and Y is 16-byte aligned (otherwise Y and T are accessed element
+// by element).
+template <bool kAlignedY>
 __global__ __launch_bounds__(256) void cer_strip_sum_kernel(const float* __restrict__ part, float* __restrict__ Y,
                                                             const float* __restrict__ T, float omega0, uint32_t nstrips,
-                                                            uint64_t plane_f4, uint32_t row_f4) {
+                                                            uint64_t plane_f4, uint32_t row_f4, uint32_t L) {
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= plane_f4) return;
     const F4* p = reinterpret_cast<const F4*>(part) + i;
@@ -292,12 +309,21 @@ __global__ __launch_bounds__(256) void cer_strip_sum_kernel(const float* __restr
         const F4 b = p[(uint64_t)s * plane_f4];
         a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
     }
-    if (omega0 != 0.f) {
-        const F4 t = reinterpret_cast<const F4*>(T)[i % row_f4];
-        a.x = fmaf(omega0, t.x, a.x); a.y = fmaf(omega0, t.y, a.y);
-        a.z = fmaf(omega0, t.z, a.z); a.w = fmaf(omega0, t.w, a.w);
+    if (kAlignedY) {
+        if (omega0 != 0.f) {
+            const F4 t = reinterpret_cast<const F4*>(T)[i % row_f4];
+            a.x = fmaf(omega0, t.x, a.x); a.y = fmaf(omega0, t.y, a.y);
+            a.z = fmaf(omega0, t.z, a.z); a.w = fmaf(omega0, t.w, a.w);
+        }
+        reinterpret_cast<F4*>(Y)[i] = a;
+    } else {
+        const uint64_t row = i / row_f4;
+        const uint32_t col = (uint32_t)(i - row * row_f4) * 4u;
+        const float o[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+        for (uint32_t e = 0; e < 4; ++e)
+            if (col + e < L) Y[row * L + col + e] = omega0 != 0.f ? fmaf(omega0, T[col + e], o[e]) : o[e];
     }
-    reinterpret_cast<F4*>(Y)[i] = a;
 }
 
 constexpr size_t strip_lds_bytes(uint32_t rows) {
@@ -306,9 +332,8 @@ constexpr size_t strip_lds_bytes(uint32_t rows) {
 
 }  // namespace
 
-bool strip_applicable(const DeviceView& d, const float* X, const float* Y, uint32_t L) {
-    return d.strip_idx != nullptr && d.n_strips > 0 && L >= 4u && L % 4u == 0 && d.m > 0 &&
-           (reinterpret_cast<uintptr_t>(X) & 15u) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15u) == 0 &&
+bool strip_applicable(const DeviceView& d, const float*, const float*, uint32_t L) {
+    return d.strip_idx != nullptr && d.n_strips > 0 && L >= 2u && d.m > 0 &&
            d.lds_per_block >= strip_lds_bytes(kStripMaxRows) + 512;
 }
 
@@ -334,7 +359,7 @@ StripPlan plan_strip(const DeviceView& d, uint32_t L) {
     const double chunks_per_row = (double)d.strip_chunks / std::max(1.0, (double)d.n_strips * (double)m);
     const double rounds = std::ceil((double)p.rows_per_split * chunks_per_row / 256.0);
     const double wg_rounds = std::ceil((double)p.blocks / std::max(d.cus, 1));
-    const double partial_bytes = (double)d.n_strips * m * L * 4.0;
+    const double partial_bytes = (double)d.n_strips * m * ((L + 3u) & ~3u) * 4.0;
     // short rows: some quad of a wave ends a row in nearly every iteration, and the whole wave walks through that branch
     const double per_round = (L <= 16u ? 0.6 : 1.0) * kStripRoundUs * (1.0 + 1.5 / std::max(chunks_per_row, 1.0));
     p.est_us = wg_rounds * (rounds * per_round + 7.0) + 3.0 + (3.0 + 2.0 * partial_bytes / 5e6);
@@ -348,13 +373,18 @@ hipError_t launch_strip(const DeviceView& d, const float* X, float* Y, const flo
     const StripPlan sp = plan_strip(d, L);
     if (sp.blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     float* part = nullptr;
-    const size_t part_bytes = (size_t)d.n_strips * m * L * sizeof(float);
+    const uint32_t row_f4 = (L + 3u) / 4u;
+    const size_t part_bytes = (size_t)d.n_strips * m * row_f4 * 16u;
     hipError_t e = (hipError_t)temp_alloc(reinterpret_cast<void**>(&part), part_bytes, stream);
     if (e != hipSuccess) return e;
-    static LdsGrant<2> grant;
+    static LdsGrant<4> grant;
     const bool half = L <= 16u;
-    auto kern = half ? cer_strip_kernel<true> : cer_strip_kernel<false>;
-    e = grant.ensure(half ? 1 : 0, reinterpret_cast<const void*>(kern), strip_lds_bytes(kStripMaxRows));
+    const bool aligned_x = L % 4u == 0 && (reinterpret_cast<uintptr_t>(X) & 15u) == 0;
+    const bool aligned_y = L % 4u == 0 && (reinterpret_cast<uintptr_t>(Y) & 15u) == 0 &&
+                           (T == nullptr || (reinterpret_cast<uintptr_t>(T) & 15u) == 0);
+    auto kern = half ? (aligned_x ? cer_strip_kernel<true, true> : cer_strip_kernel<true, false>)
+                     : (aligned_x ? cer_strip_kernel<false, true> : cer_strip_kernel<false, false>);
+    e = grant.ensure((half ? 2 : 0) + (aligned_x ? 1 : 0), reinterpret_cast<const void*>(kern), strip_lds_bytes(kStripMaxRows));
     if (e == hipSuccess) {
         hipLaunchKernelGGL(kern, dim3((uint32_t)sp.blocks), dim3(1024), strip_lds_bytes(sp.rows_per_split), stream,
                            static_cast<const uint4*>(d.strip_idx), d.strip_ptr, X, part, d.omega, m, n, L, (uint32_t)d.K,
@@ -362,9 +392,14 @@ hipError_t launch_strip(const DeviceView& d, const float* X, float* Y, const flo
         e = hipGetLastError();
     }
     if (e == hipSuccess) {
-        const uint64_t plane_f4 = (uint64_t)m * (L / 4);
-        hipLaunchKernelGGL(cer_strip_sum_kernel, dim3((uint32_t)((plane_f4 + 255) / 256)), dim3(256), 0, stream, part, Y, T,
-                           d.omega0, d.n_strips, plane_f4, L / 4);
+        const uint64_t plane_f4 = (uint64_t)m * row_f4;
+        const dim3 grid((uint32_t)((plane_f4 + 255) / 256));
+        if (aligned_y)
+            hipLaunchKernelGGL(cer_strip_sum_kernel<true>, grid, dim3(256), 0, stream, part, Y, T, d.omega0, d.n_strips, plane_f4,
+                               row_f4, L);
+        else
+            hipLaunchKernelGGL(cer_strip_sum_kernel<false>, grid, dim3(256), 0, stream, part, Y, T, d.omega0, d.n_strips, plane_f4,
+                               row_f4, L);
         e = hipGetLastError();
     }
     const hipError_t f = (hipError_t)temp_free(part, stream);

@@ -73,10 +73,11 @@ def test_strip_kernel_all_elements(name):
     strip_check(CASES[name]())
 
 
-@pytest.mark.parametrize("L", [4, 8, 12, 16, 20, 28, 36, 40, 60, 100, 132, 260])
+@pytest.mark.parametrize("L", [2, 3, 4, 5, 8, 9, 12, 16, 17, 20, 28, 33, 36, 40, 50, 60, 99, 100, 130, 132, 260])
 def test_batch_widths_with_a_ragged_last_tile(L):
-    """Batch widths that are multiples of 4 but not of 32: the last tile holds fewer than 32 columns; up to 16 columns a
-    lane holds one 16-byte piece of a row instead of two."""
+    """Batch widths that are not multiples of 32: the last tile holds fewer than 32 columns; up to 16 columns a lane holds
+    one 16-byte piece of a row instead of two; widths that are not multiples of 4 read X from 4-byte aligned addresses
+    and write Y element by element."""
     # L = 60: a non-zero most frequent value (the constant term is added with the strips' sums)
     strip_check(wl.random_lowentropy(m=150, n=2300, K=9, p_dom=0.7, L=L, seed=200 + L, dominant=1 if L == 60 else None),
                 fmts=("cer",))
@@ -87,12 +88,32 @@ def test_full_size_alexnet_fc6_batch32_and_vgg_fc6_batch64():
     strip_check(wl.vgg_fc6(L=64), fmts=("cser",))
 
 
+def test_unaligned_device_pointers():
+    """X and Y that are only 4-byte aligned."""
+    dev = _gpu()
+    for L in (32, 9, 16):
+        w = wl.random_lowentropy(m=130, n=1500, K=7, p_dom=0.6, L=L, seed=400 + L, dominant=2)
+        A = oracle.encode(w.W, w.codebook, "cer")
+        want, scale = oracle.dot(A, w.X, threads=8), oracle.abs_dot_dense(w.W, w.X, threads=8)
+        h = B.cer_encode(w.W, w.codebook)
+        B.cer_prepare_strips(h)
+        xbuf = torch.zeros(w.n * L + 3, dtype=torch.float32, device=dev)
+        ybuf = torch.full((w.m * L + 3,), float("nan"), dtype=torch.float32, device=dev)
+        for shift in (1, 3):
+            Xd = xbuf[shift:shift + w.n * L]
+            Xd.copy_(torch.from_numpy(np.ascontiguousarray(w.X)).reshape(-1))
+            ybuf.fill_(float("nan"))
+            Yd = ybuf[shift:shift + w.m * L]
+            assert B.cer_matmul_path_ex(h, L, STRIP) == B.CER_PATH_STRIP
+            B.cer_matmul_ex(h, Xd, Yd, L, None, STRIP)
+            torch.cuda.synchronize()
+            check(Yd.cpu().numpy().reshape(w.m, L), want, scale, f"{w.name}/shift{shift}")
+            assert torch.isnan(ybuf[:shift]).all() and torch.isnan(ybuf[shift + w.m * L:]).all()   # nothing written outside Y
+        B.cer_free(h)
+
+
 def test_not_applicable_cases_fall_back():
-    """Batch widths that are not multiples of 4, or below 4, run the library's own choice; codebooks of more than 64
-    values cannot be prepared."""
-    for L in (42, 6, 2):
-        w = wl.random_lowentropy(m=67, n=1500, K=16, p_dom=0.8, L=L, seed=140)
-        strip_check(w, expect=B.CER_PATH_GEMM if L >= 32 else None)
+    """Codebooks of more than 64 values cannot be prepared."""
     big = wl.random_lowentropy(m=40, n=2000, K=200, p_dom=0.3, L=32, seed=40, ratio=0.995)
     h = B.cer_encode(big.W, big.codebook)
     with pytest.raises(B.CerError) as e:
