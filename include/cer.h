@@ -111,8 +111,9 @@ int cser_encode(const float* W_host, int64_t m, int64_t n, const float* codebook
  * ownership of X and Y and must keep them alive until the stream has run the work.  When
  * Omega[0] != 0 and batch > 1 (or X does not fit in LDS) a stream-ordered temporary of batch floats
  * (plus partial sums) is allocated and released on `stream`, and so is one for a batched product
- * of a matrix with split rows (cer_long_row_parts > 0); otherwise (and when cer_matmul_path
- * reports kernel 0 or 1) the call only launches kernels and may be recorded into a HIP graph
+ * of a matrix with split rows (cer_long_row_parts > 0); kernels 2, 3 and 5 have temporaries of
+ * their own (a tile-major copy of X; the decoded matrix; strips x m x batch partial sums).
+ * Otherwise (and when cer_matmul_path reports kernel 0 or 1) the call only launches kernels and may be recorded into a HIP graph
  * after one eager call on the device.
  * fp32 arithmetic; the summation order differs from a sequential loop.  With Omega[0] != 0 the
  * rounding error is relative to sum|w||x| + |Omega[0]|.sum|x|: Appendix A-A1 adds that term and
