@@ -112,6 +112,12 @@ def test_unaligned_device_pointers():
         B.cer_free(h)
 
 
+@pytest.mark.parametrize("variant", [False, True], ids=["zero_dominant", "nonzero_dominant"])
+def test_full_size_conv3x3_batch3136(variant):
+    """The convolution shape at its full batch: 98 tiles x 5 strips (the last one half empty), two rounds of workgroups."""
+    strip_check(wl.conv3x3(nonzero_dominant=variant), fmts=("cer",))
+
+
 def test_not_applicable_cases_fall_back():
     """Codebooks of more than 64 values cannot be prepared."""
     big = wl.random_lowentropy(m=40, n=2000, K=200, p_dom=0.3, L=32, seed=40, ratio=0.995)
