@@ -43,7 +43,8 @@ typedef const float __attribute__((address_space(3))) * LdsF1Ptr;
 // The value of lane kLane of the lane's quad.
 template <int kLane>
 __device__ __forceinline__ float quad_broadcast(float w) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(w), kLane * 0x55 /* quad_perm:[k,k,k,k] */, 0xF, 0xF, false));
+    // (every lane of a quad is a valid source: with bound_ctrl set the destination needs no previous value)
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(w), kLane * 0x55 /* quad_perm:[k,k,k,k] */, 0xF, 0xF, true));
 }
 
 // The weights of the two entries of a chunk that lane j of a quad looks up (entries j and j + 4): the entry's top byte
