@@ -45,6 +45,8 @@ struct KView {
     uint32_t m;
     uint32_t n;
     float omega0;
+    const uint32_t* rank_tab;  // derived: the rank table (null: none), 1 << rank_tab_shift words per row
+    int32_t rank_tab_shift;
 };
 
 // Matrices with rows of unequal length, default batched kernel (kSplit instantiation).  The rows are taken in
@@ -327,6 +329,8 @@ inline KView make_kview(const DeviceView& d) {
     k.m = (uint32_t)d.m;
     k.n = (uint32_t)d.n;
     k.omega0 = d.omega0;
+    k.rank_tab = d.rank_tab;
+    k.rank_tab_shift = d.rank_tab_shift;
     return k;
 }
 

@@ -205,10 +205,14 @@ constexpr uint32_t kExpLong = 16;  // groups longer than this are written by the
 // 16-byte loads from 4-byte aligned addresses; the lanes of the last, partial column group take the row's last four
 // columns instead (all loads stay inside the row) and write only the columns no other lane owns; Y is written
 // element by element.
-template <typename IdxT, int V, int P, bool kRagged, int kExpChunk = kExpChunkLong, bool kSplit = false>
-__global__ __launch_bounds__(256) void cer_gemm_expand_kernel(const uint2* __restrict__ rowInfo_, const void* __restrict__ colI_,
+// kTab (handles of 2 - 64 values, rows whole and in place): the wave finds its row in the rank table -- one record per
+// row at a fixed stride, word 0 = the row's first colI position, word k = the end of its group of rank k -- so its first
+// memory request brings the row's extent and every group boundary; row_src_ is then the table (otherwise the row
+// descriptors), its log2(words per record) sits in the top four bits of ntiles_.
+template <typename IdxT, int V, int P, bool kRagged, int kExpChunk = kExpChunkLong, bool kSplit = false, bool kTab = false>
+__global__ __launch_bounds__(256) void cer_gemm_expand_kernel(const void* __restrict__ row_src_, const void* __restrict__ colI_,
                                                               const float* __restrict__ X, float* __restrict__ Y, uint32_t L,
-                                                              uint32_t ntiles, uint32_t rowblocks, uint32_t items_per_xcd,
+                                                              uint32_t ntiles_, uint32_t rowblocks, uint32_t items_per_xcd,
                                                               uint32_t m_, const float* __restrict__ T, KView v, SplitArgs sp) {
     // The first 13 dwords of arguments (plain pointers and integers) arrive in scalar registers with the wave (the
     // library is built with kernel-argument preloading): the row descriptor and the first indices are requested
@@ -218,7 +222,10 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(const uint2* __res
     constexpr uint32_t PB = G::PB;
     constexpr uint32_t PAD = D * PB;  // the last loop body of a chunk reads (zero) values this far past its end
     constexpr int TW = V * P;
+    static_assert(!(kTab && kSplit), "the rank table serves rows that are whole and in place");
     __shared__ float s_val[4][kExpChunk + PAD];
+    const uint32_t ntiles = ntiles_ & 0x0FFFFFFFu, tab_shift = ntiles_ >> 28;
+    const uint2* rowInfo_ = static_cast<const uint2*>(row_src_);
 
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = uniform(threadIdx.x >> 6);
@@ -280,9 +287,25 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(const uint2* __res
     const IdxT* colI = static_cast<const IdxT*>(colI_);
     float* val = s_val[wave];
 
-    const uint2 d0 = rowInfo_[r], d1 = rowInfo_[r + 1];
-    const uint32_t g0 = d0.x, g1 = d1.x;
-    uint32_t rs = d0.y, re = d1.y;
+    uint32_t g0 = 0, g1 = 0, rs, re;
+    PtrTile tab_tile{0u, 0u, 0u};
+    if (kTab) {
+        const uint32_t last_word = (1u << tab_shift) - 1u;  // at most 63
+        const uint32_t rec = static_cast<const uint32_t*>(row_src_)[((size_t)r << tab_shift) + min(lane, last_word)];
+        rs = (uint32_t)__builtin_amdgcn_readlane((int)rec, 0);
+        re = (uint32_t)__builtin_amdgcn_readlane((int)rec, (int)last_word);
+        // lane l holds the group of rank l + 1, which ends where the next lane's begins
+        tab_tile.s = rec;
+        tab_tile.e = (uint32_t)__builtin_amdgcn_update_dpp((int)rec, (int)rec, 0x130 /* wave_shl:1 */, 0xF, 0xF, false);
+        if (lane >= last_word) tab_tile.e = tab_tile.s;
+        tab_tile.rank = lane + 1u;
+    } else {
+        const uint2 d0 = rowInfo_[r], d1 = rowInfo_[r + 1];
+        g0 = d0.x;
+        g1 = d1.x;
+        rs = d0.y;
+        re = d1.y;
+    }
     if (kSplit) {  // a part's own positions; the first part of a split row
         if (is_part) {
             rs = part_begin;
@@ -303,7 +326,8 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(const uint2* __res
         const uint32_t c1 = min(re, c0 + (uint32_t)kExpChunk);
         // request order = arrival order: the chunk's first 64 group pointers, then its indices, then (below) the
         // first gathers; the expansion then waits for the pointers only and runs under the gathers' L2 latency
-        const PtrTile p_first = load_ptr_tile_first(v, cser, g0, gcur, g1, lane);
+        PtrTile p_first = tab_tile;
+        if (!kTab) p_first = load_ptr_tile_first(v, cser, g0, gcur, g1, lane);
         const uint32_t g_first = gcur;
         uint32_t iq[D][KQ];
 #pragma unroll
@@ -330,8 +354,7 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(const uint2* __res
 
         // ---- expansion: value of every position of [c0, c1); zeros behind it
         for (uint32_t i = c1 - c0 + lane; i < min(c1 - c0 + PAD, (uint32_t)kExpChunk + PAD); i += kWave) val[i] = 0.f;
-        for (uint32_t gt = gcur; gt < g1; gt += kWave) {
-            const PtrTile p = gt == g_first ? p_first : load_ptr_tile(v, cser, g0, gt, g1, lane);
+        auto expand_tile = [&](const PtrTile& p) {
             const float w = (omega_by_lane ? __shfl(om_l, (int)(p.rank & 63u), kWave) : v.omega[p.rank < v.K ? p.rank : 0u]) - v.omega0;
             const uint32_t s = max(p.s, c0), e = min(p.e, c1);
             const uint32_t len = e > s ? e - s : 0u;
@@ -348,10 +371,18 @@ __global__ __launch_bounds__(256) void cer_gemm_expand_kernel(const uint2* __res
                 for (uint32_t k = 0; k < kExpLong; ++k)
                     if (k < len) val[s - c0 + k] = w;
             }
-            // groups of this tile that end inside the chunk are done with
-            const uint32_t done = (uint32_t)__popcll(__ballot(gt + lane < g1 && p.e <= c1));
-            gcur = gt + done;
-            if (done < (uint32_t)kWave) break;  // the next group reaches beyond the chunk (or the row is finished)
+        };
+        if (kTab) {
+            expand_tile(p_first);  // the record holds every group of the row
+        } else {
+            for (uint32_t gt = gcur; gt < g1; gt += kWave) {
+                const PtrTile p = gt == g_first ? p_first : load_ptr_tile(v, cser, g0, gt, g1, lane);
+                expand_tile(p);
+                // groups of this tile that end inside the chunk are done with
+                const uint32_t done = (uint32_t)__popcll(__ballot(gt + lane < g1 && p.e <= c1));
+                gcur = gt + done;
+                if (done < (uint32_t)kWave) break;  // the next group reaches beyond the chunk (or the row is finished)
+            }
         }
         wave_lds_sync();
 
@@ -450,7 +481,7 @@ hipError_t launch_expand_split(Kern kern, const KView& k, const float* X, float*
 
 template <typename IdxT, int V, int P>
 hipError_t launch_gemm_vp(const KView& k, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream,
-                          const SplitArgs& sp, bool expand, bool short_rows = false) {
+                          const SplitArgs& sp, bool expand, bool short_rows = false, bool no_tab = false) {
     constexpr uint32_t TW = V * P;
     const uint32_t ntiles = (L + TW - 1) / TW;
     const uint32_t rowblocks = (k.m + 3) / 4;
@@ -465,12 +496,25 @@ hipError_t launch_gemm_vp(const KView& k, const float* X, float* Y, const float*
             return launch_expand_split(cer_gemm_expand_kernel<IdxT, V, P, false, kExpChunkLong, true>, k, X, Y, T, L, ntiles,
                                        rowblocks, ipx, sp, stream);
         }
-        if (TW == 32 && V == 4 && short_rows)
-            hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, 8, false, kExpChunkShort>), dim3(ipx * 8), dim3(256), 0, stream,
-                               k.rowInfo, k.colI, X, Y, L, ntiles, rowblocks, ipx, k.m, T, k, SplitArgs{});
-        else
+        // handles of 2 - 64 values, batches of whole 16-byte pieces: the row's extent and group boundaries from the rank
+        // table (records of at most 64 words), one trip to memory instead of two before the expansion can start
+        const bool tab = V == 4 && k.rank_tab != nullptr && k.K >= 2 && k.rank_tab_shift >= 1 && k.rank_tab_shift <= 6 &&
+                         ntiles < (1u << 28) && !no_tab;
+        const uint32_t ntiles_tab = ntiles | ((uint32_t)k.rank_tab_shift << 28);
+        if (TW == 32 && V == 4 && short_rows) {
+            if (tab)
+                hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, 8, false, kExpChunkShort, false, true>), dim3(ipx * 8), dim3(256),
+                                   0, stream, k.rank_tab, k.colI, X, Y, L, ntiles_tab, rowblocks, ipx, k.m, T, k, SplitArgs{});
+            else
+                hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, 8, false, kExpChunkShort>), dim3(ipx * 8), dim3(256), 0, stream,
+                                   k.rowInfo, k.colI, X, Y, L, ntiles, rowblocks, ipx, k.m, T, k, SplitArgs{});
+        } else if (tab && V == 4) {
+            hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, 4, (V == 4 ? P : 8), false, kExpChunkLong, false, true>), dim3(ipx * 8),
+                               dim3(256), 0, stream, k.rank_tab, k.colI, X, Y, L, ntiles_tab, rowblocks, ipx, k.m, T, k, SplitArgs{});
+        } else {
             hipLaunchKernelGGL((cer_gemm_expand_kernel<IdxT, V, P, false>), dim3(ipx * 8), dim3(256), 0, stream, k.rowInfo, k.colI,
                                X, Y, L, ntiles, rowblocks, ipx, k.m, T, k, SplitArgs{});
+        }
     } else
         hipLaunchKernelGGL((cer_gemm_kernel<IdxT, V, P>), dim3(ipx * 8), dim3(256), 0, stream, k, X, Y, T, L, ntiles,
                            rowblocks, ipx);
@@ -539,6 +583,7 @@ template <typename IdxT>
 hipError_t launch_gemm(const KView& k, const float* X, float* Y, const float* T, uint32_t L, hipStream_t stream,
                        const SplitArgs& sp, bool short_rows, const MatmulOptions& o) {
     const bool expand = (o.flags & kOptSumThenMultiply) == 0;
+    const bool no_tab = (o.flags & kOptNoRankTable) != 0;
     const bool vec4 = (L % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15u) == 0) &&
                       ((reinterpret_cast<uintptr_t>(Y) & 15u) == 0) && ((reinterpret_cast<uintptr_t>(T) & 15u) == 0);
     if (vec4) {
@@ -549,13 +594,13 @@ hipError_t launch_gemm(const KView& k, const float* X, float* Y, const float* T,
         if (L > 32) tw = pick_wide_tile(L, k.m, X, 128u);
         if (o.tile_cols > 0) tw = (uint32_t)o.tile_cols;
         switch (tw) {
-            case 4: return launch_gemm_vp<IdxT, 4, 1>(k, X, Y, T, L, stream, sp, expand);
-            case 8: return launch_gemm_vp<IdxT, 4, 2>(k, X, Y, T, L, stream, sp, expand);
-            case 16: return launch_gemm_vp<IdxT, 4, 4>(k, X, Y, T, L, stream, sp, expand);
-            case 32: return launch_gemm_vp<IdxT, 4, 8>(k, X, Y, T, L, stream, sp, expand, short_rows);
-            case 64: return launch_gemm_vp<IdxT, 4, 16>(k, X, Y, T, L, stream, sp, expand);
-            case 128: return launch_gemm_vp<IdxT, 4, 32>(k, X, Y, T, L, stream, sp, expand);
-            case 256: return launch_gemm_vp<IdxT, 4, 64>(k, X, Y, T, L, stream, sp, expand);
+            case 4: return launch_gemm_vp<IdxT, 4, 1>(k, X, Y, T, L, stream, sp, expand, false, no_tab);
+            case 8: return launch_gemm_vp<IdxT, 4, 2>(k, X, Y, T, L, stream, sp, expand, false, no_tab);
+            case 16: return launch_gemm_vp<IdxT, 4, 4>(k, X, Y, T, L, stream, sp, expand, false, no_tab);
+            case 32: return launch_gemm_vp<IdxT, 4, 8>(k, X, Y, T, L, stream, sp, expand, short_rows, no_tab);
+            case 64: return launch_gemm_vp<IdxT, 4, 16>(k, X, Y, T, L, stream, sp, expand, false, no_tab);
+            case 128: return launch_gemm_vp<IdxT, 4, 32>(k, X, Y, T, L, stream, sp, expand, false, no_tab);
+            case 256: return launch_gemm_vp<IdxT, 4, 64>(k, X, Y, T, L, stream, sp, expand, false, no_tab);
             default: return hipErrorInvalidValue;
         }
     }
