@@ -366,6 +366,8 @@ StripPlan plan_strip(const DeviceView& d, uint32_t L) {
     p.est_us = wg_rounds * (rounds * per_round + 7.0) + 3.0 + (3.0 + 2.0 * partial_bytes / 5e6);
     // workgroups with next to nothing to stream (2048 x 2048 cells: 16 rows each) measure 17 - 21 us whatever they hold
     if (rounds < 8.0) p.est_us += 6.0;
+    // the library itself never asks for more than 1 GiB of partial sums (as for the decoded matrix of the dense route)
+    if (partial_bytes > (double)(1ull << 30)) p.est_us = 1e12;
     return p;
 }
 
