@@ -212,13 +212,14 @@ int cer_matmul_path(const cer_handle_t* h, int64_t batch);
  *                                                 lane instead of 16-byte gathers
  *                    CER_OPT_SHORT_CHUNKS / CER_OPT_LONG_CHUNKS  kernel 1: group values expanded 512 /
  *                                                 2048 positions at a time (default: by the average row)
- *                    CER_OPT_NO_RANK_TABLE        kernel 0: find the group boundaries through rowPtr and
+ *                    CER_OPT_NO_RANK_TABLE        kernels 0 and 1: find the group boundaries through rowPtr and
  *                                                 OmegaPtr even when the handle has a rank table
  *                                                 (a derived array of handles with 2 - 256 values:
  *                                                 per row its first colI position and the end of the
  *                                                 group of every rank, at a fixed stride, 4 bytes per
  *                                                 row and rank; it lets a wave fetch all boundaries
- *                                                 of its row with its first memory request)
+ *                                                 of its row with its first memory request; kernel 1
+ *                                                 uses it for handles of 2 - 64 values)
  * opts == NULL is cer_matmul's behaviour.  Errors: those of cer_matmul; CER_E_INVALID also for an
  * undefined path, tile width or flag.
  */

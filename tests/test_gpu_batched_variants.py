@@ -3,7 +3,8 @@ position in LDS, then a plain multiply-add stream), the cursor variant that sums
 multiplication (CER_OPT_SUM_THEN_MULTIPLY), and the default one with ragged batch widths served one column per
 lane instead of by 16-byte gathers (CER_OPT_ONE_COLUMN_PER_LANE) -- on every kind of matrix, against the oracle
 under the usual bound.  A fourth run forces the 512-position value chunks meant for matrices of short rows
-(CER_OPT_SHORT_CHUNKS) onto every matrix, so that long rows walk many chunks.  The variants are selected per call
+(CER_OPT_SHORT_CHUNKS) onto every matrix, so that long rows walk many chunks; a fifth keeps the default kernel away
+from the rank table (CER_OPT_NO_RANK_TABLE).  The variants are selected per call
 through cer_matmul_ex."""
 import numpy as np
 import pytest
@@ -20,6 +21,8 @@ VARIANTS = {
     "cursor": B.CER_OPT_SUM_THEN_MULTIPLY,
     "expand_one_column_per_lane": B.CER_OPT_ONE_COLUMN_PER_LANE,    # ragged widths without 16-byte gathers
     "expand_short_chunks": B.CER_OPT_SHORT_CHUNKS,                  # 512-position chunks on every matrix
+    "expand_no_rank_table": B.CER_OPT_NO_RANK_TABLE,                # rows found through rowPtr -> OmegaPtr (the default kernel
+                                                                    # takes handles of 2 - 64 values through their rank table)
 }
 
 
