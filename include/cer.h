@@ -240,7 +240,7 @@ int cer_matmul_path_ex(const cer_handle_t* h, int64_t batch, const cer_matmul_op
 
 /*
  * cer_prepare_strips -- builds, once per handle, the strip-major index that kernel 5 (CER_PATH_STRIP) needs: the
- * column-blocked reuse of input elements (Section V-C).  X is cut into strips of 1024 consecutive rows; for
+ * column-blocked reuse of input elements (Section V-C).  X is cut into equally long strips of at most 1024 consecutive rows; for
  * every strip and every row of W the index lists the row's indexed elements whose column falls into the strip, each
  * as 16 bits: the rank of the element's value in Omega (6 bits) and the column inside the strip (10 bits), in chunks
  * of eight entries (the last chunk of a strip's share of a row is filled up with entries of rank 0, whose weight

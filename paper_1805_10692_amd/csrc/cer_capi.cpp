@@ -632,7 +632,10 @@ int cer_prepare_strips(cer_handle_t* h) {
     try {
         const int rc = cer::ensure_host_arrays(h);
         if (rc != CER_OK) return rc;
-        const uint64_t S = cer::kStripRows, ns = ((uint64_t)A.n + S - 1) / S, m = (uint64_t)A.m;
+        // as few strips as 1024 rows each allow, all equally long (4608 columns: five strips of 922, not four of 1024
+        // and a half-empty fifth)
+        const uint64_t ns = ((uint64_t)A.n + cer::kStripRows - 1) / cer::kStripRows, m = (uint64_t)A.m;
+        const uint64_t S = ((uint64_t)A.n + ns - 1) / ns;
         if (ns * (m + 1) > 0x7FFFFFFFull) return CER_E_TOO_LARGE;
         // rank of every raw group (Algorithm 3: position in the row + 1; Algorithm 4: OmegaI)
         std::vector<uint32_t> ptr((size_t)(ns * (m + 1)) + 1, 0u);
@@ -678,6 +681,7 @@ int cer_prepare_strips(cer_handle_t* h) {
         h->view.strip_idx = base;
         h->view.strip_ptr = reinterpret_cast<const uint32_t*>(b8 + idx_bytes);
         h->view.n_strips = (uint32_t)ns;
+        h->view.strip_rows = (uint32_t)S;
         h->view.strip_chunks = nchunks;
         return CER_OK;
     } catch (const std::bad_alloc&) {

@@ -72,12 +72,13 @@ struct DeviceView {
     uint32_t n_split_parts = 0, n_split_rows = 0;
     uint32_t split_len = 0;  // positions per part
     uint32_t split_min = 0;  // rows with more positions than this are split
-    // Strip-major index (derived by cer_prepare_strips; null otherwise): for strip s (kStripRows consecutive columns of
+    // Strip-major index (derived by cer_prepare_strips; null otherwise): for strip s (strip_rows <= kStripRows consecutive columns of
     // W) and row r, chunks strip_ptr[s * (m + 1) + r] .. strip_ptr[s * (m + 1) + r + 1] of strip_idx; a chunk is eight
-    // uint16 entries (rank << 10) | (column - s * kStripRows), the last chunk of a (strip, row) padded with zeros.
+    // uint16 entries (rank << 10) | (column - s * strip_rows), the last chunk of a (strip, row) padded with zeros.
     const void* strip_idx = nullptr;
     const uint32_t* strip_ptr = nullptr;
     uint64_t strip_chunks = 0;
+    uint32_t strip_rows = 0;
     uint32_t n_strips = 0;
     // Rank table (derived; null unless the codebook has 2 .. 256 values): per row 1 << rank_tab_shift words at a fixed
     // stride, word 0 = the row's first colI position, word k = end of its group of rank k (the previous word when the

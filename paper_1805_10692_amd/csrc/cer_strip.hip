@@ -3,7 +3,7 @@
 //
 // The kernels that gather rows of X from L2 are bound by the compute unit's vector-memory pipeline (about 26 clocks
 // per wave instruction of 1 KB, i.e. 40 bytes per clock); LDS delivers 128 bytes per clock.  Here the input is cut
-// into strips of 1024 consecutive rows; a workgroup copies one strip of one tile of 32 batch columns into LDS
+// into equally long strips of at most 1024 consecutive rows; a workgroup copies one strip of one tile of 32 batch columns into LDS
 // (128 KB, rows of 128 bytes) and serves from it every indexed element of its rows of W whose column falls into the
 // strip.  The format orders a row's indices by value, then column, so a strip's share of a row is scattered over
 // the row's groups: the handle carries a DERIVED strip-major index (built once by cer_prepare_strips from the format
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict
                                                          const float* __restrict__ X, float* __restrict__ part,
                                                          const float* __restrict__ omega, uint32_t m, uint32_t n, uint32_t L,
                                                          uint32_t K, uint32_t ntiles, uint32_t nsplit,
-                                                         uint32_t rows_per_split, uint32_t zero_chunk) {
+                                                         uint32_t rows_per_split, uint32_t zero_chunk, uint32_t strip_rows) {
     // LDS: [256 weights][strip: rows of 8 x 16 bytes; after the stream: one partial row sum per worker][ends of the
     // workgroup's rows, in chunks]; no static LDS, so the weight of an entry sits at LDS address 4 x (its top byte).
     extern __shared__ __align__(16) unsigned char strip_smem[];
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(1024) void cer_strip_kernel(const uint4* __restrict
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = uniform(threadIdx.x >> 6);
     const uint32_t split = blockIdx.x % nsplit, tile = (blockIdx.x / nsplit) % ntiles, s = blockIdx.x / (nsplit * ntiles);
-    const uint32_t c0 = s * kStripRows, rows_here = min(kStripRows, n - c0);
+    const uint32_t c0 = s * strip_rows, rows_here = min(strip_rows, n - c0);
     const uint32_t r_begin = min(m, split * rows_per_split), rows = min(m, r_begin + rows_per_split) - r_begin;
     const uint32_t* sp = sptr + (size_t)s * (m + 1) + r_begin;
     const F4* X4 = reinterpret_cast<const F4*>(X);
@@ -391,7 +391,7 @@ hipError_t launch_strip(const DeviceView& d, const float* X, float* Y, const flo
     if (e == hipSuccess) {
         hipLaunchKernelGGL(kern, dim3((uint32_t)sp.blocks), dim3(1024), strip_lds_bytes(sp.rows_per_split), stream,
                            static_cast<const uint4*>(d.strip_idx), d.strip_ptr, X, part, d.omega, m, n, L, (uint32_t)d.K,
-                           sp.ntiles, sp.nsplit, sp.rows_per_split, (uint32_t)d.strip_chunks);
+                           sp.ntiles, sp.nsplit, sp.rows_per_split, (uint32_t)d.strip_chunks, d.strip_rows);
         e = hipGetLastError();
     }
     if (e == hipSuccess) {
